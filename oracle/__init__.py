@@ -1,0 +1,200 @@
+"""ctypes loader for the CPU float64 oracle (oracle/specgbv_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()`` and
+by the ``cpu_baseline`` leg of ``bench.py``.  The product package never imports
+this module, and this module never imports the product package.
+
+Every wrapper only marshals numpy arrays to the C functions; the arithmetic
+(paper Section 4.2: Algorithm 1, Eq. (hik), Eq. (hLk), Eq. (pres)) lives in the
+C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from ctypes import POINTER, c_double, c_float, c_int, c_int32, c_uint32, c_uint64, c_void_p
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "specgbv_oracle.c")
+_LIB = os.path.join(_HERE, "libspecgbv_oracle.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP only for the prefix loop)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Debug(ctypes.Structure):
+    _fields_ = [
+        ("lse_q", POINTER(c_double)), ("lse_p", POINTER(c_double)),
+        ("log_nu", POINTER(c_double)), ("log_P", POINTER(c_double)),
+        ("s", POINTER(c_double)), ("h", POINTER(c_double)), ("eta", POINTER(c_double)),
+        ("state", POINTER(c_int32)), ("res_norm", POINTER(c_double)),
+        ("u_final", POINTER(c_double)), ("margin", POINTER(c_double)),
+        ("fallback", POINTER(c_int32)),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.specgbv_oracle_philox4x32_10.argtypes = [POINTER(c_uint32)] * 3
+        L.specgbv_oracle_philox4x32_10.restype = None
+        L.specgbv_oracle_uniform.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32]
+        L.specgbv_oracle_uniform.restype = c_double
+        L.specgbv_oracle_log_softmax.argtypes = [POINTER(c_double), c_int, c_double, POINTER(c_double)]
+        L.specgbv_oracle_log_softmax.restype = c_double
+        L.specgbv_oracle_ot_sum.argtypes = [POINTER(c_double), POINTER(c_double), c_int, c_double, c_int]
+        L.specgbv_oracle_ot_sum.restype = c_double
+        L.specgbv_oracle_h_sub.argtypes = [c_double, c_double, c_double, c_int]
+        L.specgbv_oracle_h_sub.restype = c_double
+        L.specgbv_oracle_h_full.argtypes = [c_double, c_double, c_int]
+        L.specgbv_oracle_h_full.restype = c_double
+        L.specgbv_oracle_decision_scan.argtypes = [POINTER(c_double), POINTER(c_double), POINTER(c_int32),
+                                                   c_int, c_int, POINTER(c_int32), POINTER(c_int32),
+                                                   POINTER(c_int32)]
+        L.specgbv_oracle_decision_scan.restype = None
+        L.specgbv_oracle_sample_cdf.argtypes = [POINTER(c_double), c_int, c_double, POINTER(c_double),
+                                                POINTER(c_double)]
+        L.specgbv_oracle_sample_cdf.restype = c_int32
+        L.specgbv_oracle_verify.argtypes = [c_void_p, c_void_p, POINTER(c_int32), c_int, c_int, c_int, c_int,
+                                            c_int, c_float, c_uint64, c_uint64, POINTER(c_int32),
+                                            POINTER(c_int32), POINTER(c_int32), POINTER(_Debug), c_int]
+        L.specgbv_oracle_verify.restype = c_int
+        L.specgbv_oracle_num_procs.argtypes = []
+        L.specgbv_oracle_num_procs.restype = c_int
+        _lib = L
+    return _lib
+
+
+def _dp(a: np.ndarray):
+    return a.ctypes.data_as(POINTER(c_double))
+
+
+def _ip(a: np.ndarray):
+    return a.ctypes.data_as(POINTER(c_int32))
+
+
+def philox4x32_10(counter, key) -> tuple:
+    c = (c_uint32 * 4)(*[int(v) & 0xFFFFFFFF for v in counter])
+    k = (c_uint32 * 2)(*[int(v) & 0xFFFFFFFF for v in key])
+    out = (c_uint32 * 4)()
+    lib().specgbv_oracle_philox4x32_10(c, k, out)
+    return tuple(int(v) for v in out)
+
+
+def uniform(seed: int, offset: int, prefix: int, slot: int) -> float:
+    return float(lib().specgbv_oracle_uniform(seed, offset, prefix, slot))
+
+
+def log_softmax(z, T: float = 1.0):
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    out = np.empty_like(z)
+    lse = lib().specgbv_oracle_log_softmax(_dp(z), z.size, float(T), _dp(out))
+    return out, float(lse)
+
+
+def ot_sum(lq, lp, log_nu: float, K: int) -> float:
+    lq = np.ascontiguousarray(lq, dtype=np.float64)
+    lp = np.ascontiguousarray(lp, dtype=np.float64)
+    assert lq.shape == lp.shape
+    return float(lib().specgbv_oracle_ot_sum(_dp(lq), _dp(lp), lq.size, float(log_nu), int(K)))
+
+
+def h_sub(log_nu: float, log_P: float, s: float, K: int) -> float:
+    return float(lib().specgbv_oracle_h_sub(float(log_nu), float(log_P), float(s), int(K)))
+
+
+def h_full(log_nu: float, log_P: float, K: int) -> float:
+    return float(lib().specgbv_oracle_h_full(float(log_nu), float(log_P), int(K)))
+
+
+def decision_scan(h, eta, tokens):
+    """Algorithm 1's loop for one prefix.  h, eta: [K, L]; tokens: [K, L]."""
+    h = np.ascontiguousarray(h, dtype=np.float64)
+    eta = np.ascontiguousarray(eta, dtype=np.float64)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    K, L = tokens.shape
+    assert h.shape == (K, L) and eta.shape == (K, L)
+    tau, f = c_int32(), c_int32()
+    state = np.zeros((K, L), dtype=np.int32)
+    lib().specgbv_oracle_decision_scan(_dp(h), _dp(eta), _ip(tokens), K, L, ctypes.byref(tau),
+                                       ctypes.byref(f), _ip(state))
+    return int(tau.value), int(f.value), state
+
+
+def sample_cdf(w, u: float):
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    W, margin = c_double(), c_double()
+    y = lib().specgbv_oracle_sample_cdf(_dp(w), w.size, float(u), ctypes.byref(W), ctypes.byref(margin))
+    return int(y), float(W.value), float(margin.value)
+
+
+def to_raw(logits: np.ndarray):
+    """(contiguous array, dtype code) for float32 arrays or uint16 bfloat16 bit patterns."""
+    if logits.dtype == np.float32:
+        return np.ascontiguousarray(logits), F32
+    if logits.dtype == np.uint16:
+        return np.ascontiguousarray(logits), BF16
+    raise TypeError("logits must be float32 or uint16 (bfloat16 bits), got %s" % logits.dtype)
+
+
+def verify(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np.ndarray,
+           temperature: float, rng_seed: int, rng_offset: int, debug: bool = False, nthreads: int = 1):
+    """Run the oracle on host arrays.
+
+    target_logits [B, K, L+1, V], draft_logits [B, K, L, V] (float32, or uint16 holding
+    bfloat16 bits), draft_tokens [B, K, L] int32.  Returns a dict with accepted_len [B],
+    accepted_draft_idx [B], out_tokens [B, L+1] and, with debug=True, the intermediates.
+    """
+    tl, dt = to_raw(target_logits)
+    dl, dt2 = to_raw(draft_logits)
+    assert dt == dt2
+    B, K, L1, V = tl.shape
+    L = L1 - 1
+    assert dl.shape == (B, K, L, V), (dl.shape, (B, K, L, V))
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    assert tok.shape == (B, K, L)
+    res = {
+        "accepted_len": np.full(B, -9, np.int32),
+        "accepted_draft_idx": np.full(B, -9, np.int32),
+        "out_tokens": np.full((B, L + 1), -9, np.int32),
+    }
+    dbg = None
+    if debug:
+        nan = np.nan
+        res.update(
+            lse_q=np.full((B, K, L + 1), nan), lse_p=np.full((B, K, L), nan),
+            log_nu=np.full((B, K, L), nan), log_P=np.full((B, K, L), nan),
+            s=np.full((B, K, L), nan), h=np.full((B, K, L), nan), eta=np.full((B, K, L), nan),
+            state=np.zeros((B, K, L), np.int32), res_norm=np.full(B, nan), u_final=np.full(B, nan),
+            margin=np.full(B, nan), fallback=np.zeros(B, np.int32))
+        dbg = _Debug(_dp(res["lse_q"]), _dp(res["lse_p"]), _dp(res["log_nu"]), _dp(res["log_P"]),
+                     _dp(res["s"]), _dp(res["h"]), _dp(res["eta"]), _ip(res["state"]),
+                     _dp(res["res_norm"]), _dp(res["u_final"]), _dp(res["margin"]), _ip(res["fallback"]))
+    rc = lib().specgbv_oracle_verify(
+        tl.ctypes.data_as(c_void_p), dl.ctypes.data_as(c_void_p), _ip(tok), K, L, V, B, dt,
+        c_float(temperature), rng_seed, rng_offset, _ip(res["accepted_len"]),
+        _ip(res["accepted_draft_idx"]), _ip(res["out_tokens"]),
+        ctypes.byref(dbg) if dbg is not None else None, int(nthreads))
+    if rc != 0:
+        raise ValueError("specgbv_oracle_verify rejected its arguments (code %d)" % rc)
+    return res
+
+
+def num_procs() -> int:
+    return int(lib().specgbv_oracle_num_procs())

@@ -1,0 +1,185 @@
+"""Exact-rational brute force of SpecTr-GBV on tiny vocabularies.
+
+TEST INFRASTRUCTURE ONLY (like the rest of oracle/).  Independent of
+specgbv_oracle.c: it evaluates the paper's equations *literally* (with the
+joint block probabilities p(x^i), q(x^i) of Eq. (hik), Eq. (hLk), Eq. (pres)) in
+``fractions.Fraction`` and enumerates every K-tuple of drafts and every
+accept/reject branch of Algorithm 1.  The C oracle's rescaled formulas, its scan
+and its Monte-Carlo behaviour are pinned against these exact values.
+"""
+from __future__ import annotations
+
+import itertools
+from fractions import Fraction
+from typing import Callable, Dict, Tuple
+
+Block = Tuple[int, ...]
+Table = Callable[[Block], list]
+
+
+def joint(table: Table, block: Block) -> Fraction:
+    """Probability of a token block under an autoregressive table."""
+    pr = Fraction(1)
+    for j, t in enumerate(block):
+        pr *= table(block[:j])[t]
+    return pr
+
+
+def _one_minus_min_pow(pb: Fraction, qb: Fraction, K: int) -> Fraction:
+    """(1 - min{p/q, 1})^K."""
+    ratio = pb / qb
+    return (1 - min(ratio, Fraction(1))) ** K
+
+
+def ot_sum_joint(p_of: Table, q_of: Table, block: Block, V: int, K: int) -> Fraction:
+    """sum_x q(x^i, x) (1 - min{p(x^i,x)/q(x^i,x), 1})^K  -- the vocabulary sum of Eq. (hik)."""
+    tot = Fraction(0)
+    for x in range(V):
+        ext = block + (x,)
+        tot += joint(q_of, ext) * _one_minus_min_pow(joint(p_of, ext), joint(q_of, ext), K)
+    return tot
+
+
+def h_literal(p_of: Table, q_of: Table, block: Block, V: int, L: int, K: int) -> Fraction:
+    """Acceptance probability of a block: Eq. (hik) for len < L, Eq. (hLk) for len = L."""
+    P, Q = joint(p_of, block), joint(q_of, block)
+    if len(block) == L:
+        return Q * (1 - _one_minus_min_pow(P, Q, K)) / (1 - (1 - P) ** K)
+    S = ot_sum_joint(p_of, q_of, block, V, K)
+    num = S - Q * _one_minus_min_pow(P, Q, K)
+    den = 1 - (1 - P) ** K - Q + S
+    if den == 0:
+        return Fraction(1)          # 0/0 read as its limit
+    h = num / den
+    assert 0 <= h <= 1, (block, h)
+    return h
+
+
+def residual_literal(p_of: Table, q_of: Table, block: Block, V: int, K: int):
+    """Eq. (pres): distribution of the token after the accepted block (length < L).
+
+    Returns (distribution, degenerate) where degenerate marks the all-zero case, read as
+    a draw from q(.|block)."""
+    w = []
+    for x in range(V):
+        ext = block + (x,)
+        w.append(joint(q_of, ext) * _one_minus_min_pow(joint(p_of, ext), joint(q_of, ext), K))
+    tot = sum(w)
+    if tot == 0:
+        return list(q_of(block)), True
+    return [v / tot for v in w], False
+
+
+def closed_form_E_tau(p_of: Table, q_of: Table, V: int, L: int, K: int) -> Fraction:
+    """Right-hand side of Lemma 5.1 / Theorem 5.3."""
+    tot = Fraction(0)
+    for t in range(1, L + 1):
+        for block in itertools.product(range(V), repeat=t):
+            P, Q = joint(p_of, block), joint(q_of, block)
+            tot += Q * (1 - _one_minus_min_pow(P, Q, K))
+    return tot
+
+
+def _scan_branches(drafts, hval, K: int, L: int):
+    """All (probability, tau, f) leaves of Algorithm 1's loop for fixed drafts."""
+    leaves = []
+
+    def rec(k, i, start_done, tau, f, H, pr):
+        # (k, i): next test is sub-block length i of draft k; i runs tau_at_entry+1 .. L
+        if pr == 0:
+            return
+        if k == K:
+            leaves.append((pr, tau, f))
+            return
+        if i > L:
+            rec(k + 1, tau + 1, False, tau, f, H, pr)
+            return
+        block = drafts[k][:i]
+        if block in H:
+            rec(k, i + 1, True, tau, f, H, pr)
+            return
+        h = hval(block)
+        # accept
+        if i == L:
+            leaves.append((pr * h, L, k))            # break
+        else:
+            rec(k, i + 1, True, i, k, H, pr * h)
+        # reject
+        rec(k, i + 1, True, tau, f, H | {block}, pr * (1 - h))
+
+    rec(0, 1, False, 0, -1, frozenset(), Fraction(1))
+    return leaves
+
+
+def enumerate_alg1(p_of: Table, q_of: Table, V: int, L: int, K: int):
+    """Exact law of Algorithm 1's output.
+
+    Returns (dist, E_tau, degenerate_mass): dist maps the output token tuple
+    (t^tau followed by y) to its probability.
+    """
+    hcache: Dict[Block, Fraction] = {}
+
+    def hval(block):
+        if block not in hcache:
+            hcache[block] = h_literal(p_of, q_of, block, V, L, K)
+        return hcache[block]
+
+    rcache = {}
+    dist: Dict[Block, Fraction] = {}
+    E_tau = Fraction(0)
+    degenerate_mass = Fraction(0)
+    blocks = list(itertools.product(range(V), repeat=L))
+    for drafts in itertools.product(blocks, repeat=K):
+        pd = Fraction(1)
+        for d in drafts:
+            pd *= joint(p_of, d)
+        if pd == 0:
+            continue
+        for pr, tau, f in _scan_branches(drafts, hval, K, L):
+            w = pd * pr
+            if w == 0:
+                continue
+            E_tau += w * tau
+            t = drafts[f][:tau] if tau > 0 else ()
+            if tau == L:
+                ydist, deg = list(q_of(t)), False
+            else:
+                if t not in rcache:
+                    rcache[t] = residual_literal(p_of, q_of, t, V, K)
+                ydist, deg = rcache[t]
+            if deg:
+                degenerate_mass += w
+            for y in range(V):
+                if ydist[y] != 0:
+                    key = t + (y,)
+                    dist[key] = dist.get(key, Fraction(0)) + w * ydist[y]
+    assert sum(dist.values()) == 1
+    return dist, E_tau, degenerate_mass
+
+
+def first_token_marginal(dist, V: int):
+    m = [Fraction(0)] * V
+    for key, pr in dist.items():
+        m[key[0]] += pr
+    return m
+
+
+def table_from_dict(d):
+    """Table callable from {block tuple: [Fraction,...]}."""
+    return lambda block: d[tuple(block)]
+
+
+def random_tables(rng, V: int, L: int, denom: int = 12):
+    """Strictly positive random rational conditional tables for all blocks of length <= L."""
+    def rand_dist():
+        while True:
+            cuts = sorted(rng.integers(1, denom, size=V - 1).tolist())
+            parts = [a - b for a, b in zip(cuts + [denom], [0] + cuts)]
+            if all(v > 0 for v in parts):
+                return [Fraction(v, denom) for v in parts]
+    p, q = {}, {}
+    for r in range(L + 1):
+        for block in itertools.product(range(V), repeat=r):
+            p[block] = rand_dist()
+            q[block] = rand_dist()
+    return table_from_dict(p), table_from_dict(q)

@@ -1,0 +1,476 @@
+/*
+ * specgbv_oracle.c -- plain CPU float64 oracle for SpecTr-GBV verification.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct reference
+ * that the GPU library is compared against.  It shares no code with the HIP
+ * path; only tests, the smoke check and the benchmark's cpu_baseline leg may
+ * link or load it.
+ *
+ * What it computes (paper, Section 4.2): Algorithm 1 "SpecTr-GBV" with the
+ * acceptance probabilities of Eq. (hik) [sub-block] and Eq. (hLk) [whole
+ * block] and the residual distribution of Eq. (pres), for a batch of
+ * independent prefixes.  Everything is written in the order and notation of
+ * the paper; there is no blocking, fusion or reordering.
+ *
+ * Notation.  For one prefix and one draft k: row r (0-based) of the target
+ * (draft) logits is the conditional distribution q(.|x^r) (p(.|x^r)), i.e. the
+ * one that draft token x^(r+1) = tokens[r] was drawn from; the target has one
+ * more row (r = L) used for the bonus token.  With q_r = softmax(z_q/T) and
+ * p_r = softmax(z_p/T),
+ *     P_i = prod_{j<=i} p_{j-1}[x^(j)],   Q_i likewise,   nu_i = Q_i / P_i
+ * (nu_i is the block likelihood ratio of greedy block verification,
+ * Section 3.3).  Arrays of shape [.., L] that are indexed by the sub-block
+ * length i = 1..L store entry i at position i-1.
+ *
+ * Rescaled form of the acceptance probabilities.  Eq. (hik) and Eq. (hLk) are
+ * written in the paper with joint block probabilities p(x^i), q(x^i), which
+ * underflow for realistic L and V.  Dividing numerator and denominator by
+ * P_i gives the algebraically identical
+ *     s_i  = sum_x q_i[x] * max(1 - p_i[x] / (nu_i q_i[x]), 0)^K
+ *     g_i  = max(1 - 1/nu_i, 0)^K
+ *     c_K(P) = (1 - (1-P)^K) / P
+ *     h_ik = nu_i (s_i - g_i) / (c_K(P_i) - nu_i (1 - s_i)),   i < L
+ *     h_Lk = nu_L (1 - g_L) / c_K(P_L)
+ * which is what this file evaluates (tests check it against the literal
+ * equations in exact rational arithmetic).
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   - uniforms come from Philox4x32-10 (Salmon et al., SC'11) with
+ *     key = seed, counter = (offset_lo, offset_hi, prefix index, slot),
+ *     slot = k*L + (i-1) for the test of sub-block i of draft k and K*L for the
+ *     final token; u = (word0 >> 8) * 2^-24;
+ *   - the final token is drawn by inverse CDF in token-id order,
+ *     y = min{ j : sum_{x<=j} w_x > u * sum_x w_x };
+ *   - 0/0 in Eq. (hik) is read as its limit 1; h is clamped to [0,1];
+ *   - if every residual weight is zero the token is drawn from q_tau itself;
+ *   - tau = 0 uses row 0 of draft 0 and reports draft index -1.
+ *
+ * Parity status: every function is pinned by tests/test_oracle_*.py
+ * (closed forms, exact-rational enumeration of Algorithm 1, K=1 reduction to
+ * greedy block verification, library log-softmax, published Philox
+ * known-answer vectors).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_F32 0
+#define ORACLE_BF16 1
+
+/* ------------------------------------------------------------------ Philox */
+
+/* One Philox4x32 round: two 32x32->64 multiplies, then the permutation and
+ * key injection of the published S-P network. */
+static void philox_round(uint32_t c[4], const uint32_t k[2])
+{
+    const uint64_t m0 = (uint64_t)0xD2511F53u * c[0];
+    const uint64_t m1 = (uint64_t)0xCD9E8D57u * c[2];
+    const uint32_t hi0 = (uint32_t)(m0 >> 32), lo0 = (uint32_t)m0;
+    const uint32_t hi1 = (uint32_t)(m1 >> 32), lo1 = (uint32_t)m1;
+    const uint32_t n0 = hi1 ^ c[1] ^ k[0];
+    const uint32_t n1 = lo1;
+    const uint32_t n2 = hi0 ^ c[3] ^ k[1];
+    const uint32_t n3 = lo0;
+    c[0] = n0; c[1] = n1; c[2] = n2; c[3] = n3;
+}
+
+/* Philox4x32-10: ten rounds, the key advanced by the Weyl constants between
+ * rounds. */
+void specgbv_oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2],
+                                  uint32_t out[4])
+{
+    uint32_t c[4] = { ctr[0], ctr[1], ctr[2], ctr[3] };
+    uint32_t k[2] = { key[0], key[1] };
+    for (int r = 0; r < 10; ++r) {
+        if (r > 0) { k[0] += 0x9E3779B9u; k[1] += 0xBB67AE85u; }
+        philox_round(c, k);
+    }
+    memcpy(out, c, sizeof c);
+}
+
+/* The uniform of one test: 24 random bits, exactly representable in float32
+ * and float64, in [0,1). */
+double specgbv_oracle_uniform(uint64_t seed, uint64_t offset, uint32_t prefix,
+                              uint32_t slot)
+{
+    const uint32_t ctr[4] = { (uint32_t)offset, (uint32_t)(offset >> 32), prefix, slot };
+    const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    specgbv_oracle_philox4x32_10(ctr, key, out);
+    return (double)(out[0] >> 8) * (1.0 / 16777216.0);
+}
+
+/* ------------------------------------------------------- input conversions */
+
+static double bf16_to_double(uint16_t h)
+{
+    const uint32_t bits = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static void load_row(const void *base, int dtype, size_t row, int V, double *z)
+{
+    if (dtype == ORACLE_BF16) {
+        const uint16_t *p = (const uint16_t *)base + row * (size_t)V;
+        for (int x = 0; x < V; ++x) z[x] = bf16_to_double(p[x]);
+    } else {
+        const float *p = (const float *)base + row * (size_t)V;
+        for (int x = 0; x < V; ++x) z[x] = (double)p[x];
+    }
+}
+
+/* ----------------------------------------------------------------- softmax */
+
+/* log softmax(z / T): out[x] = z[x]/T - lse, lse = log sum_x exp(z[x]/T).
+ * Returns lse. */
+double specgbv_oracle_log_softmax(const double *z, int V, double T, double *out)
+{
+    double m = -INFINITY;
+    for (int x = 0; x < V; ++x) {
+        out[x] = z[x] / T;
+        if (out[x] > m) m = out[x];
+    }
+    double sum = 0.0;
+    for (int x = 0; x < V; ++x) sum += exp(out[x] - m);
+    const double lse = m + log(sum);
+    for (int x = 0; x < V; ++x) out[x] -= lse;
+    return lse;
+}
+
+/* ----------------------------------------------------- Eq. (hik) / (hLk) */
+
+static double ipow(double t, int K)
+{
+    double r = 1.0;
+    for (int j = 0; j < K; ++j) r *= t;
+    return r;
+}
+
+/* One term of the vocabulary sums of Eq. (hik) and Eq. (pres) after dividing
+ * by q(x^i):  q[x] * (1 - min{ p[x] / (nu q[x]), 1 })^K. */
+static double ot_term(double lq, double lp, double log_nu, int K)
+{
+    const double ratio = exp(lp - lq - log_nu);
+    const double t = 1.0 - (ratio < 1.0 ? ratio : 1.0);
+    return exp(lq) * ipow(t, K);
+}
+
+/* s = sum_x q[x] * max(1 - p[x]/(nu q[x]), 0)^K, plain left-to-right. */
+double specgbv_oracle_ot_sum(const double *lq, const double *lp, int V,
+                             double log_nu, int K)
+{
+    double s = 0.0;
+    for (int x = 0; x < V; ++x) s += ot_term(lq[x], lp[x], log_nu, K);
+    return s;
+}
+
+/* c_K(P) = (1 - (1-P)^K) / P, the probability that at least one of K i.i.d.
+ * drafts equals a block of draft probability P, divided by P. */
+static double c_K(double logP, int K)
+{
+    const double P = exp(logP);
+    if (P <= 0.0) return (double)K;           /* limit P -> 0 */
+    if (P >= 1.0) return 1.0;
+    return -expm1((double)K * log1p(-P)) / P;
+}
+
+static double g_K(double log_nu, int K)
+{
+    const double t = 1.0 - exp(-log_nu);      /* 1 - min{P/Q, 1} */
+    return t > 0.0 ? ipow(t, K) : 0.0;
+}
+
+static double clamp01(double h)
+{
+    if (!(h > 0.0)) return 0.0;
+    return h < 1.0 ? h : 1.0;
+}
+
+/* Eq. (hik), sub-block of length i < L, rescaled by P_i. */
+double specgbv_oracle_h_sub(double log_nu, double logP, double s, int K)
+{
+    const double nu = exp(log_nu);
+    const double num = nu * (s - g_K(log_nu, K));
+    const double den = c_K(logP, K) - nu * (1.0 - s);
+    if (!(den > 0.0)) return 1.0;             /* 0/0: limit is 1 */
+    return clamp01(num / den);
+}
+
+/* Eq. (hLk), whole block, rescaled by P_L. */
+double specgbv_oracle_h_full(double log_nu, double logP, int K)
+{
+    const double nu = exp(log_nu);
+    return clamp01(nu * (1.0 - g_K(log_nu, K)) / c_K(logP, K));
+}
+
+/* ------------------------------------------------- Algorithm 1, the scan */
+
+static int same_block(const int32_t *a, const int32_t *b, int len)
+{
+    for (int j = 0; j < len; ++j)
+        if (a[j] != b[j]) return 0;
+    return 1;
+}
+
+/* Is the length-len block of draft k in H?  H holds (draft, length) pairs of
+ * blocks that were tested and not accepted; membership is equality of the
+ * token blocks. */
+static int in_H(const int32_t *tokens, int L, const int *Hk, const int *Hlen,
+                int nH, int k, int len)
+{
+    for (int e = 0; e < nH; ++e)
+        if (Hlen[e] == len && same_block(tokens + (size_t)Hk[e] * L, tokens + (size_t)k * L, len))
+            return 1;
+    return 0;
+}
+
+/*
+ * The sequential loop of Algorithm 1 for one prefix.
+ *   h, eta : [K, L], entry (k, i-1) for sub-block length i
+ *   tokens : [K, L]
+ *   state  : [K, L] out (may be NULL): 0 = never reached, 1 = tested with
+ *            its uniform, 2 = reached but skipped because the block is in H
+ * Outputs tau in [0, L] and f (0-based draft index, -1 if tau = 0).
+ */
+void specgbv_oracle_decision_scan(const double *h, const double *eta,
+                                  const int32_t *tokens, int K, int L,
+                                  int32_t *tau_out, int32_t *f_out, int32_t *state)
+{
+    int tau = 0, f = -1, nH = 0;
+    int *Hk = (int *)malloc(sizeof(int) * (size_t)K * L);
+    int *Hlen = (int *)malloc(sizeof(int) * (size_t)K * L);
+    if (state) memset(state, 0, sizeof(int32_t) * (size_t)K * L);
+
+    for (int k = 0; k < K; ++k) {
+        const int start = tau + 1;            /* range fixed at loop entry */
+        for (int i = start; i <= L - 1; ++i) {
+            if (in_H(tokens, L, Hk, Hlen, nH, k, i)) {
+                if (state) state[k * L + i - 1] = 2;
+                continue;                     /* no sampling for a known reject */
+            }
+            if (state) state[k * L + i - 1] = 1;
+            if (eta[k * L + i - 1] < h[k * L + i - 1]) {
+                tau = i; f = k;               /* longest accepted so far */
+            } else {
+                Hk[nH] = k; Hlen[nH] = i; ++nH;
+            }
+        }
+        /* whole block */
+        if (in_H(tokens, L, Hk, Hlen, nH, k, L)) {
+            if (state) state[k * L + L - 1] = 2;
+            continue;
+        }
+        if (state) state[k * L + L - 1] = 1;
+        if (eta[k * L + L - 1] < h[k * L + L - 1]) {
+            tau = L; f = k;
+            break;
+        }
+        Hk[nH] = k; Hlen[nH] = L; ++nH;
+    }
+    free(Hk); free(Hlen);
+    *tau_out = tau; *f_out = f;
+}
+
+/* ---------------------------------------------------------- final sample */
+
+/* Inverse CDF in token-id order: the first j whose running sum exceeds u*W.
+ * margin (may be NULL) = distance of u*W to the nearer end of token j's
+ * interval, divided by W.  Returns -1 when W = 0. */
+int32_t specgbv_oracle_sample_cdf(const double *w, int V, double u,
+                                  double *W_out, double *margin)
+{
+    double W = 0.0;
+    for (int x = 0; x < V; ++x) W += w[x];
+    if (W_out) *W_out = W;
+    if (!(W > 0.0)) return -1;
+    const double target = u * W;
+    double c = 0.0;
+    int32_t last_pos = -1;
+    for (int x = 0; x < V; ++x) {
+        const double c_prev = c;
+        c += w[x];
+        if (w[x] > 0.0) last_pos = x;
+        if (c > target) {
+            if (margin) {
+                const double lo = target - c_prev, hi = c - target;
+                *margin = (lo < hi ? lo : hi) / W;
+            }
+            return x;
+        }
+    }
+    if (margin) *margin = 0.0;                /* only reachable through rounding */
+    return last_pos;
+}
+
+/* ------------------------------------------------------------ whole call */
+
+/* Optional per-call intermediates (any pointer may be NULL). */
+typedef struct {
+    double *lse_q;      /* [B, K, L+1] log-sum-exp of target rows (z/T)      */
+    double *lse_p;      /* [B, K, L]                                         */
+    double *log_nu;     /* [B, K, L]   log nu_i at i-1                        */
+    double *log_P;      /* [B, K, L]   log P_i at i-1                         */
+    double *s;          /* [B, K, L]   OT sum of row r at r (row 0: nu = 1)   */
+    double *h;          /* [B, K, L]   acceptance probability of length i    */
+    double *eta;        /* [B, K, L]   uniform of that test                   */
+    int32_t *state;     /* [B, K, L]   0 unreached, 1 tested, 2 skipped (H)   */
+    double *res_norm;   /* [B] sum of the weights the final token is drawn from */
+    double *u_final;    /* [B] uniform of the final token                     */
+    double *margin;     /* [B] inverse-CDF margin of the final token          */
+    int32_t *fallback;  /* [B] 1 if all residual weights were zero            */
+} specgbv_oracle_debug;
+
+static void verify_one(const void *target_logits, const void *draft_logits,
+                       const int32_t *draft_tokens, int K, int L, int V, int b,
+                       int dtype, double T, uint64_t seed, uint64_t offset,
+                       int32_t *accepted_len, int32_t *accepted_draft_idx,
+                       int32_t *out_tokens, const specgbv_oracle_debug *dbg)
+{
+    const size_t KL = (size_t)K * L;
+    double *z = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lq = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)V);
+    double *w = (double *)malloc(sizeof(double) * (size_t)V);
+    double *h = (double *)malloc(sizeof(double) * KL);
+    double *eta = (double *)malloc(sizeof(double) * KL);
+    double *log_nu = (double *)malloc(sizeof(double) * KL);
+    double *log_P = (double *)malloc(sizeof(double) * KL);
+    const int32_t *tokens = draft_tokens + (size_t)b * KL;
+
+    for (int k = 0; k < K; ++k) {
+        const size_t trow0 = ((size_t)b * K + k) * (size_t)(L + 1);
+        const size_t drow0 = ((size_t)b * K + k) * (size_t)L;
+        double lognu = 0.0, logP = 0.0;       /* nu_0 = P_0 = 1 */
+        for (int r = 0; r < L; ++r) {
+            load_row(target_logits, dtype, trow0 + r, V, z);
+            const double lse_q = specgbv_oracle_log_softmax(z, V, T, lq);
+            load_row(draft_logits, dtype, drow0 + r, V, z);
+            const double lse_p = specgbv_oracle_log_softmax(z, V, T, lp);
+            /* OT sum of row r with the ratio of the length-r block (r = 0: nu = 1). */
+            const double s = specgbv_oracle_ot_sum(lq, lp, V, lognu, K);
+            if (r >= 1) {
+                /* Eq. (hik) for sub-block length i = r */
+                h[k * L + r - 1] = specgbv_oracle_h_sub(lognu, logP, s, K);
+            }
+            if (dbg) {
+                if (dbg->lse_q) dbg->lse_q[trow0 + r] = lse_q;
+                if (dbg->lse_p) dbg->lse_p[drow0 + r] = lse_p;
+                if (dbg->s) dbg->s[drow0 + r] = s;
+            }
+            /* extend the block by token x^(r+1) */
+            const int32_t tok = tokens[k * L + r];
+            lognu += lq[tok] - lp[tok];
+            logP += lp[tok];
+            log_nu[k * L + r] = lognu;
+            log_P[k * L + r] = logP;
+        }
+        /* Eq. (hLk) for the whole block */
+        h[k * L + L - 1] = specgbv_oracle_h_full(lognu, logP, K);
+        for (int i = 1; i <= L; ++i)
+            eta[k * L + i - 1] = specgbv_oracle_uniform(seed, offset, (uint32_t)b,
+                                                        (uint32_t)(k * L + i - 1));
+    }
+
+    int32_t tau, f;
+    int32_t *state = dbg && dbg->state ? dbg->state + (size_t)b * KL : NULL;
+    specgbv_oracle_decision_scan(h, eta, tokens, K, L, &tau, &f, state);
+
+    /* final token */
+    const int kf = f < 0 ? 0 : f;             /* tau = 0: row 0 of draft 0 */
+    const size_t trow = ((size_t)b * K + kf) * (size_t)(L + 1) + (size_t)tau;
+    load_row(target_logits, dtype, trow, V, z);
+    const double lse_q = specgbv_oracle_log_softmax(z, V, T, lq);
+    int fallback = 0;
+    if (tau == L) {
+        for (int x = 0; x < V; ++x) w[x] = exp(lq[x]);        /* bonus: y ~ q_L */
+        if (dbg && dbg->lse_q) dbg->lse_q[trow] = lse_q;
+    } else {
+        const size_t drow = ((size_t)b * K + kf) * (size_t)L + (size_t)tau;
+        load_row(draft_logits, dtype, drow, V, z);
+        specgbv_oracle_log_softmax(z, V, T, lp);
+        const double lognu_tau = tau == 0 ? 0.0 : log_nu[kf * L + tau - 1];
+        /* Eq. (pres) with q(x^tau) cancelled */
+        for (int x = 0; x < V; ++x) w[x] = ot_term(lq[x], lp[x], lognu_tau, K);
+    }
+    const double u = specgbv_oracle_uniform(seed, offset, (uint32_t)b, (uint32_t)KL);
+    double W = 0.0, margin = 0.0;
+    int32_t y = specgbv_oracle_sample_cdf(w, V, u, &W, &margin);
+    if (y < 0) {                               /* all-zero residual: y ~ q_tau */
+        fallback = 1;
+        for (int x = 0; x < V; ++x) w[x] = exp(lq[x]);
+        y = specgbv_oracle_sample_cdf(w, V, u, &W, &margin);
+    }
+
+    accepted_len[b] = tau;
+    accepted_draft_idx[b] = f;
+    for (int j = 0; j <= L; ++j) {
+        int32_t v = -1;
+        if (j < tau) v = tokens[kf * L + j];
+        else if (j == tau) v = y;
+        out_tokens[(size_t)b * (L + 1) + j] = v;
+    }
+    if (dbg) {
+        const size_t o = (size_t)b * KL;
+        if (dbg->log_nu) memcpy(dbg->log_nu + o, log_nu, sizeof(double) * KL);
+        if (dbg->log_P) memcpy(dbg->log_P + o, log_P, sizeof(double) * KL);
+        if (dbg->h) memcpy(dbg->h + o, h, sizeof(double) * KL);
+        if (dbg->eta) memcpy(dbg->eta + o, eta, sizeof(double) * KL);
+        if (dbg->res_norm) dbg->res_norm[b] = W;
+        if (dbg->u_final) dbg->u_final[b] = u;
+        if (dbg->margin) dbg->margin[b] = margin;
+        if (dbg->fallback) dbg->fallback[b] = fallback;
+    }
+    free(z); free(lq); free(lp); free(w); free(h); free(eta); free(log_nu); free(log_P);
+}
+
+/*
+ * Host-pointer twin of the GPU entry point.
+ *   target_logits [batch, K, L+1, V], draft_logits [batch, K, L, V] (dtype:
+ *   0 = float32, 1 = bfloat16 bit patterns), draft_tokens [batch, K, L].
+ *   Outputs accepted_len [batch], accepted_draft_idx [batch] (-1 when 0
+ *   tokens are accepted), out_tokens [batch, L+1] (accepted tokens, the final
+ *   token, then -1).  nthreads > 1 only distributes prefixes over threads.
+ * Returns 0, or 1 for invalid arguments.
+ */
+int specgbv_oracle_verify(const void *target_logits, const void *draft_logits,
+                          const int32_t *draft_tokens, int K, int L, int V,
+                          int batch, int dtype, float temperature,
+                          uint64_t rng_seed, uint64_t rng_offset,
+                          int32_t *accepted_len, int32_t *accepted_draft_idx,
+                          int32_t *out_tokens, const specgbv_oracle_debug *dbg,
+                          int nthreads)
+{
+    if (!target_logits || !draft_logits || !draft_tokens || !accepted_len ||
+        !accepted_draft_idx || !out_tokens)
+        return 1;
+    if (K < 1 || L < 1 || V < 1 || batch < 0) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (!(temperature > 0.0f) || !isfinite(temperature)) return 1;
+    for (size_t j = 0; j < (size_t)batch * K * L; ++j)
+        if (draft_tokens[j] < 0 || draft_tokens[j] >= V) return 1;
+    const double T = (double)temperature;
+    (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 1 ? nthreads : 1)
+#endif
+    for (int b = 0; b < batch; ++b)
+        verify_one(target_logits, draft_logits, draft_tokens, K, L, V, b, dtype, T,
+                   rng_seed, rng_offset, accepted_len, accepted_draft_idx,
+                   out_tokens, dbg);
+    return 0;
+}
+
+int specgbv_oracle_num_procs(void)
+{
+#ifdef _OPENMP
+    return omp_get_num_procs();
+#else
+    return 1;
+#endif
+}
