@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpecTr-GBV verification hot path on one MI355X.
+
+A step is one specgbv_verify call (statistics + sums of Eq. (hik), Algorithm 1's decision
+scan, residual / bonus draw) over one synthetic batch already resident in HBM.  Prints ONE
+JSON line with whole-call throughput (verifications/s), the HBM roofline figures of the
+dominant (vocabulary-streaming) kernel measured with HIP events, and the CPU oracle timed
+on the host cores of the same machine as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ProcessPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from specgbv_synth import WORKLOADS, make_prefix  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def _gen(args):
+    name, seed, b = args
+    return make_prefix(WORKLOADS[name], seed, b)
+
+
+def generate(name: str, seed: int, workers: int):
+    w = WORKLOADS[name]
+    store = np.uint16 if w.dtype == "bf16" else np.float32
+    target = np.empty((w.batch, w.K, w.L + 1, w.V), dtype=store)
+    draft = np.empty((w.batch, w.K, w.L, w.V), dtype=store)
+    tokens = np.empty((w.batch, w.K, w.L), dtype=np.int32)
+    jobs = [(name, seed, b) for b in range(w.batch)]
+    if workers > 1:
+        with ProcessPoolExecutor(max_workers=workers) as ex:
+            for b, (t, d, k) in enumerate(ex.map(_gen, jobs)):
+                target[b], draft[b], tokens[b] = t, d, k
+    else:
+        for b, j in enumerate(jobs):
+            target[b], draft[b], tokens[b] = _gen(j)
+    return target, draft, tokens
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
+    ap.add_argument("--algo", default="auto", choices=["auto", "split", "chain"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path is embarrassingly parallel over prefixes; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    w = WORKLOADS[a.workload]
+    # inputs are generated on the host before the GPU is touched (worker processes fork here)
+    t0 = time.time()
+    target, draft, tokens = generate(a.workload, a.seed, workers=min(16, os.cpu_count() or 1))
+    gen_s = time.time() - t0
+
+    import torch
+    import paper_2604_25925_amd as sg
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+
+    def up(x):
+        if x.dtype == np.uint16:
+            return torch.from_numpy(x.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(x).to(dev)
+
+    tl, dl, tk = up(target), up(draft), up(tokens)
+    dt = 1 if w.dtype == "bf16" else 0
+    ws = torch.empty(sg.specgbv_workspace_bytes(w.batch, w.K, w.L, w.V, dt), dtype=torch.uint8, device=dev)
+    out = (torch.empty(w.batch, dtype=torch.int32, device=dev), torch.empty(w.batch, dtype=torch.int32, device=dev),
+           torch.empty((w.batch, w.L + 1), dtype=torch.int32, device=dev))
+
+    def step(offset, events=None):
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, offset, workspace=ws, out=out, algo=a.algo,
+                             events=events)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(a.warmup + i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+    tau_mean = float(out[0].float().mean().item())
+
+    # dominant kernel(s): HIP events recorded by the library on the launch stream, around the
+    # vocabulary-streaming kernels only
+    evs = []
+    for i in range(a.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); e1.record()                    # materialise the hipEvent_t handles
+        evs.append((e0, e1))
+    torch.cuda.synchronize()
+    for i, (e0, e1) in enumerate(evs):
+        step(a.warmup + a.steps + i, events=(e0.cuda_event, e1.cuda_event))
+    torch.cuda.synchronize()
+    main_ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    main_avg = sum(main_ms) / len(main_ms)
+    main_bytes = w.row_pairs * w.V * 2 * w.elem_bytes       # every (target, draft) row pair once
+    achieved = main_bytes / (main_avg * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % a.workload)
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+
+    res = {
+        "metric": "verifications/sec and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",
+        "value": w.batch / (ms_per_step * 1e-3),
+        "unit": "verifications/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: batch %d, K=%d, L=%d, V=%d, %s logits, T=%g" % (
+                       w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
+                   "algo": a.algo, "row_pairs_per_s": w.row_pairs / (ms_per_step * 1e-3),
+                   "whole_call_algorithmic_GBps": w.algorithmic_bytes / (ms_per_step * 1e-3) / 1e9,
+                   "mean_accepted_len": tau_mean, "input_generation_s": round(gen_s, 1)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "vocabulary-streaming kernels (statistics + sums of Eq. (hik))",
+                     "kernel_ms_avg": main_avg, "kernel_ms_min": main_ms[0],
+                     "algorithmic_bytes_per_launch": main_bytes},
+    }
+
+    if not a.no_cpu_baseline:
+        import oracle
+        # bounded sample: time two prefixes, then as many as fit the CPU-time target
+        t0 = time.perf_counter()
+        oracle.verify(target[:2], draft[:2], tokens[:2], w.temperature, a.seed, 0, nthreads=1)
+        per = (time.perf_counter() - t0) / 2
+        n = int(max(2, min(w.batch, a.cpu_seconds / max(per, 1e-9))))
+        t0 = time.perf_counter()
+        ref = oracle.verify(target[:n], draft[:n], tokens[:n], w.temperature, a.seed, a.warmup + a.steps - 1,
+                            nthreads=1)
+        cpu_s = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": n / cpu_s, "unit": "verifications/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d of %d prefixes of the same batch, float64, 1 thread, %.1f s" % (
+                                   n, w.batch, cpu_s),
+                               "host_cpus": os.cpu_count()}
+        # the last timed step used the same counters: report agreement on the sample
+        step(a.warmup + a.steps - 1)
+        torch.cuda.synchronize()
+        got = out[0][:n].cpu().numpy()
+        res["config"]["sample_accepted_len_agree"] = int((got == ref["accepted_len"]).sum())
+        res["config"]["sample_size"] = n
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,165 @@
+/*
+ * specgbv.h -- C ABI of the MI355X SpecTr-GBV verification library (libspecgbv.so).
+ *
+ * One call verifies, for a batch of independent prefixes, K i.i.d. draft blocks
+ * of length L against the target model: paper Section 4.2, Algorithm 1
+ * ("SpecTr-GBV"), with the sub-block and whole-block acceptance probabilities
+ * of Eq. (hik) and Eq. (hLk) and the residual distribution of Eq. (pres).
+ *
+ * All logits/tokens/outputs/workspace pointers are DEVICE pointers; the library
+ * allocates no device memory, never synchronises the stream (except
+ * specgbv_read_intermediates) and keeps no state between calls: the same inputs
+ * with the same (rng_seed, rng_offset) give the same outputs.
+ *
+ * Row convention.  For prefix b and draft k, target row r is q(.|x_k^r), the
+ * target distribution after the first r draft tokens (r = 0..L; row L serves
+ * the bonus token), draft row r is p(.|x_k^r) (r = 0..L-1) and
+ * draft_tokens[b,k,r] = x_k^(r+1) is the token drawn from draft row r.
+ * Distributions are softmax(logits / temperature) for both models.
+ *
+ * Randomness.  Uniforms are Philox4x32-10 outputs with key = rng_seed and
+ * counter = (rng_offset low, rng_offset high, b, slot); slot = k*L + (i-1) for
+ * the acceptance test of sub-block length i of draft k, slot = K*L for the
+ * final token; u = (word0 >> 8) * 2^-24.  A call consumes exactly these
+ * counters; advance rng_offset by one per call.
+ */
+#ifndef SPECGBV_H
+#define SPECGBV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SPECGBV_OK = 0,
+    SPECGBV_EINVAL = 1,        /* null pointer, non-positive size, bad temperature, ...   */
+    SPECGBV_EUNSUPPORTED = 2,  /* valid request outside the implemented limits            */
+    SPECGBV_EWORKSPACE = 3,    /* workspace null, misaligned or smaller than required     */
+    SPECGBV_EHIP = 4           /* a HIP runtime call failed (launch, event record, copy)  */
+} specgbv_status;
+
+typedef enum {
+    SPECGBV_F32 = 0,           /* IEEE float32 logits                                      */
+    SPECGBV_BF16 = 1           /* bfloat16 logits, widened to float32 in the kernels       */
+} specgbv_dtype;
+
+/* Kernel schedule.  AUTO picks by shape; the other values force one schedule (for tests
+ * and measurements) and fail with SPECGBV_EUNSUPPORTED if the shape does not allow it. */
+typedef enum {
+    SPECGBV_ALGO_AUTO = 0,
+    SPECGBV_ALGO_SPLIT = 1,    /* statistics pass, then a second pass for the sums of Eq. (hik) */
+    SPECGBV_ALGO_CHAIN = 2     /* one workgroup per (prefix, draft) keeps each row pair on chip  */
+} specgbv_algo;
+
+/* Limits (checked; violations return SPECGBV_EUNSUPPORTED). */
+#define SPECGBV_MAX_K 64
+#define SPECGBV_MAX_L 62
+
+/*
+ * Bytes of device workspace specgbv_verify needs for this shape (0 if the shape is
+ * invalid).  The workspace must be 256-byte aligned; its contents need not be
+ * initialised and are overwritten by every call.
+ */
+size_t specgbv_workspace_bytes(int batch, int K, int L, int V, specgbv_dtype dtype);
+
+/*
+ * Multi-draft greedy block verification (Algorithm 1; Eq. (hik), Eq. (hLk), Eq. (pres)).
+ *
+ *   target_logits      device, [batch, K, L+1, V], dense, V fastest
+ *   draft_logits       device, [batch, K, L,   V], dense, V fastest
+ *   draft_tokens       device, [batch, K, L] int32, each in [0, V) (not checked on device
+ *                      beyond clamping the gather index; out-of-range tokens give
+ *                      meaningless but memory-safe results)
+ *   K, L, V, batch     >= 1 (batch may be 0: nothing is launched); K <= SPECGBV_MAX_K,
+ *                      L <= SPECGBV_MAX_L
+ *   dtype              element type of both logits tensors
+ *   temperature        > 0 and finite; applied to both models
+ *   rng_seed/offset    Philox key and call counter (see above)
+ *   accepted_len       device out, [batch] int32: tau in [0, L]
+ *   accepted_draft_idx device out, [batch] int32: index f of the draft whose first tau
+ *                      tokens were accepted, -1 when tau = 0
+ *   out_tokens         device out, [batch, L+1] int32: the tau accepted tokens, then the
+ *                      final token y (residual draw of Eq. (pres) when tau < L, a draw from
+ *                      target row L of draft f when tau = L), then -1 padding
+ *   workspace          device, >= specgbv_workspace_bytes(...) bytes, 256-byte aligned
+ *   hip_stream         hipStream_t (NULL = default stream); all work is enqueued on it and
+ *                      the call returns without waiting
+ *
+ * Readings where the paper is silent: 0/0 in Eq. (hik) is 1; acceptance probabilities are
+ * clamped to [0,1]; the final token is the first id whose running weight sum exceeds
+ * u * total; if every residual weight is zero the token is drawn from target row tau; the
+ * tau = 0 residual uses rows 0 of draft 0.
+ *
+ * Errors are detected on the host before anything is launched; on error nothing is
+ * written and specgbv_last_error() describes the cause.
+ */
+specgbv_status specgbv_verify(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int L, int V, int batch, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset,
+    int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Extra controls for specgbv_verify_ex; zero-initialise for the defaults. */
+typedef struct specgbv_options {
+    int32_t algo;              /* specgbv_algo                                              */
+    int32_t reserved;
+    void *ev_main_start;       /* hipEvent_t or NULL: recorded on the stream immediately    */
+    void *ev_main_stop;        /*   before / after the vocabulary-streaming kernels that    */
+                               /*   compute the statistics and the sums of Eq. (hik)        */
+} specgbv_options;
+
+/* specgbv_verify with explicit options (options == NULL means defaults). */
+specgbv_status specgbv_verify_ex(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int L, int V, int batch, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset,
+    int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
+    void *workspace, size_t workspace_bytes, void *hip_stream,
+    const specgbv_options *options);
+
+/*
+ * HOST buffers receiving the intermediates of the most recent call that used a
+ * workspace (any pointer may be NULL).  Arrays indexed by the sub-block length
+ * i = 1..L store entry i at position i-1.
+ */
+typedef struct specgbv_intermediates {
+    double *lse_q;       /* [batch, K, L]  ln sum_x exp(z_q/T) of target rows 0..L-1        */
+    double *lse_p;       /* [batch, K, L]  same for the draft rows                          */
+    double *log_nu;      /* [batch, K, L]  ln nu_i, the block likelihood ratio Q_i / P_i    */
+    double *log_P;       /* [batch, K, L]  ln P_i, the draft probability of the block       */
+    double *s;           /* [batch, K, L]  vocabulary sum of Eq. (hik) divided by q(x^i),   */
+                         /*                at position i (i = 1..L-1; position 0 is NaN)    */
+    double *h;           /* [batch, K, L]  acceptance probability of sub-block length i     */
+    double *eta;         /* [batch, K, L]  uniform of that test                             */
+    int32_t *state;      /* [batch, K, L]  0 never reached, 1 tested, 2 skipped (block in H) */
+    double *res_norm;    /* [batch] total weight the final token was drawn from (weights    */
+                         /*         are q[x] * max(1 - p[x]/(nu q[x]), 0)^K, or q[x])        */
+    double *u_final;     /* [batch] uniform of the final token                              */
+    double *margin;      /* [batch] distance of u*total to the nearer end of the drawn      */
+                         /*         token's CDF interval, divided by total                  */
+    int32_t *fallback;   /* [batch] 1 if all residual weights were zero                     */
+} specgbv_intermediates;
+
+/*
+ * Copies the intermediates left in `workspace` by the last specgbv_verify[_ex] call with
+ * the same (batch, K, L) to host memory and waits for the copies (this is the only
+ * function that synchronises the stream).  Debug/parity aid, not part of the hot path.
+ */
+specgbv_status specgbv_read_intermediates(
+    const void *workspace, size_t workspace_bytes, int batch, int K, int L, int V,
+    specgbv_dtype dtype, const specgbv_intermediates *host_out, void *hip_stream);
+
+/* Message of the last failing call made by this thread ("" if none); static storage. */
+const char *specgbv_last_error(void);
+
+/* Library version string, static storage. */
+const char *specgbv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECGBV_H */

@@ -73,7 +73,7 @@ def lib() -> ctypes.CDLL:
         L.specgbv_oracle_sample_cdf.restype = c_int32
         L.specgbv_oracle_verify.argtypes = [c_void_p, c_void_p, POINTER(c_int32), c_int, c_int, c_int, c_int,
                                             c_int, c_float, c_uint64, c_uint64, POINTER(c_int32),
-                                            POINTER(c_int32), POINTER(c_int32), POINTER(_Debug), c_int]
+                                            POINTER(c_int32), POINTER(c_int32), POINTER(_Debug), POINTER(c_int32), c_int]
         L.specgbv_oracle_verify.restype = c_int
         L.specgbv_oracle_num_procs.argtypes = []
         L.specgbv_oracle_num_procs.restype = c_int
@@ -154,12 +154,14 @@ def to_raw(logits: np.ndarray):
 
 
 def verify(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np.ndarray,
-           temperature: float, rng_seed: int, rng_offset: int, debug: bool = False, nthreads: int = 1):
+           temperature: float, rng_seed: int, rng_offset: int, debug: bool = False, nthreads: int = 1,
+           prefix_ids=None):
     """Run the oracle on host arrays.
 
     target_logits [B, K, L+1, V], draft_logits [B, K, L, V] (float32, or uint16 holding
     bfloat16 bits), draft_tokens [B, K, L] int32.  Returns a dict with accepted_len [B],
     accepted_draft_idx [B], out_tokens [B, L+1] and, with debug=True, the intermediates.
+    prefix_ids [B] (optional) are the Philox prefix counters of the batch entries.
     """
     tl, dt = to_raw(target_logits)
     dl, dt2 = to_raw(draft_logits)
@@ -174,6 +176,10 @@ def verify(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np
         "accepted_draft_idx": np.full(B, -9, np.int32),
         "out_tokens": np.full((B, L + 1), -9, np.int32),
     }
+    pids = None
+    if prefix_ids is not None:
+        pids = np.ascontiguousarray(prefix_ids, dtype=np.int32)
+        assert pids.shape == (B,)
     dbg = None
     if debug:
         nan = np.nan
@@ -190,7 +196,8 @@ def verify(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np
         tl.ctypes.data_as(c_void_p), dl.ctypes.data_as(c_void_p), _ip(tok), K, L, V, B, dt,
         c_float(temperature), rng_seed, rng_offset, _ip(res["accepted_len"]),
         _ip(res["accepted_draft_idx"]), _ip(res["out_tokens"]),
-        ctypes.byref(dbg) if dbg is not None else None, int(nthreads))
+        ctypes.byref(dbg) if dbg is not None else None,
+        _ip(pids) if pids is not None else None, int(nthreads))
     if rc != 0:
         raise ValueError("specgbv_oracle_verify rejected its arguments (code %d)" % rc)
     return res

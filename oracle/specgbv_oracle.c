@@ -327,7 +327,7 @@ typedef struct {
 } specgbv_oracle_debug;
 
 static void verify_one(const void *target_logits, const void *draft_logits,
-                       const int32_t *draft_tokens, int K, int L, int V, int b,
+                       const int32_t *draft_tokens, int K, int L, int V, int b, uint32_t pid,
                        int dtype, double T, uint64_t seed, uint64_t offset,
                        int32_t *accepted_len, int32_t *accepted_draft_idx,
                        int32_t *out_tokens, const specgbv_oracle_debug *dbg)
@@ -373,7 +373,7 @@ static void verify_one(const void *target_logits, const void *draft_logits,
         /* Eq. (hLk) for the whole block */
         h[k * L + L - 1] = specgbv_oracle_h_full(lognu, logP, K);
         for (int i = 1; i <= L; ++i)
-            eta[k * L + i - 1] = specgbv_oracle_uniform(seed, offset, (uint32_t)b,
+            eta[k * L + i - 1] = specgbv_oracle_uniform(seed, offset, pid,
                                                         (uint32_t)(k * L + i - 1));
     }
 
@@ -398,7 +398,7 @@ static void verify_one(const void *target_logits, const void *draft_logits,
         /* Eq. (pres) with q(x^tau) cancelled */
         for (int x = 0; x < V; ++x) w[x] = ot_term(lq[x], lp[x], lognu_tau, K);
     }
-    const double u = specgbv_oracle_uniform(seed, offset, (uint32_t)b, (uint32_t)KL);
+    const double u = specgbv_oracle_uniform(seed, offset, pid, (uint32_t)KL);
     double W = 0.0, margin = 0.0;
     int32_t y = specgbv_oracle_sample_cdf(w, V, u, &W, &margin);
     if (y < 0) {                               /* all-zero residual: y ~ q_tau */
@@ -435,7 +435,9 @@ static void verify_one(const void *target_logits, const void *draft_logits,
  *   0 = float32, 1 = bfloat16 bit patterns), draft_tokens [batch, K, L].
  *   Outputs accepted_len [batch], accepted_draft_idx [batch] (-1 when 0
  *   tokens are accepted), out_tokens [batch, L+1] (accepted tokens, the final
- *   token, then -1).  nthreads > 1 only distributes prefixes over threads.
+ *   token, then -1).  prefix_ids (may be NULL) gives the Philox prefix counter of each
+ *   batch entry, so that a subset of a larger batch can be re-run; NULL means 0..batch-1.
+ *   nthreads > 1 only distributes prefixes over threads.
  * Returns 0, or 1 for invalid arguments.
  */
 int specgbv_oracle_verify(const void *target_logits, const void *draft_logits,
@@ -444,7 +446,7 @@ int specgbv_oracle_verify(const void *target_logits, const void *draft_logits,
                           uint64_t rng_seed, uint64_t rng_offset,
                           int32_t *accepted_len, int32_t *accepted_draft_idx,
                           int32_t *out_tokens, const specgbv_oracle_debug *dbg,
-                          int nthreads)
+                          const int32_t *prefix_ids, int nthreads)
 {
     if (!target_logits || !draft_logits || !draft_tokens || !accepted_len ||
         !accepted_draft_idx || !out_tokens)
@@ -460,7 +462,8 @@ int specgbv_oracle_verify(const void *target_logits, const void *draft_logits,
 #pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 1 ? nthreads : 1)
 #endif
     for (int b = 0; b < batch; ++b)
-        verify_one(target_logits, draft_logits, draft_tokens, K, L, V, b, dtype, T,
+        verify_one(target_logits, draft_logits, draft_tokens, K, L, V, b,
+                   prefix_ids ? (uint32_t)prefix_ids[b] : (uint32_t)b, dtype, T,
                    rng_seed, rng_offset, accepted_len, accepted_draft_idx,
                    out_tokens, dbg);
     return 0;

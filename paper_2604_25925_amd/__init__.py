@@ -1,0 +1,12 @@
+"""MI355X-native SpecTr-GBV verification (multi-draft greedy block verification).
+
+The work is done by hand-written HIP kernels in ``libspecgbv.so`` behind the C ABI of
+``include/specgbv.h``; this package is only the argument-marshalling binding.
+"""
+from .binding import (ALGO_AUTO, ALGO_CHAIN, ALGO_SPLIT, SpecGBVError, load_library, specgbv_last_error,
+                      specgbv_read_intermediates, specgbv_verify, specgbv_verify_ex, specgbv_version,
+                      specgbv_workspace_bytes)
+
+__all__ = ["ALGO_AUTO", "ALGO_CHAIN", "ALGO_SPLIT", "SpecGBVError", "load_library", "specgbv_last_error",
+           "specgbv_read_intermediates", "specgbv_verify", "specgbv_verify_ex", "specgbv_version",
+           "specgbv_workspace_bytes"]

@@ -1,0 +1,199 @@
+"""ctypes binding of libspecgbv.so: same names as the C ABI, argument marshalling only.
+
+PyTorch appears here for device memory and the current HIP stream; every step of the
+verification runs inside the library's kernels.  There is no fallback: if the library
+cannot be loaded the import of a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_double, c_float, c_int, c_int32, c_size_t, c_uint64, c_void_p
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libspecgbv.so")
+
+F32, BF16 = 0, 1
+ALGO_AUTO, ALGO_SPLIT, ALGO_CHAIN = 0, 1, 2
+_ALGO = {"auto": ALGO_AUTO, "split": ALGO_SPLIT, "chain": ALGO_CHAIN}
+
+EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_ex", "specgbv_read_intermediates",
+           "specgbv_last_error", "specgbv_version")
+
+
+class SpecGBVError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("specgbv status %d: %s" % (status, message))
+        self.status = status
+
+
+class _Options(ctypes.Structure):
+    _fields_ = [("algo", c_int32), ("reserved", c_int32), ("ev_main_start", c_void_p), ("ev_main_stop", c_void_p)]
+
+
+class _Intermediates(ctypes.Structure):
+    _fields_ = [("lse_q", POINTER(c_double)), ("lse_p", POINTER(c_double)), ("log_nu", POINTER(c_double)),
+                ("log_P", POINTER(c_double)), ("s", POINTER(c_double)), ("h", POINTER(c_double)),
+                ("eta", POINTER(c_double)), ("state", POINTER(c_int32)), ("res_norm", POINTER(c_double)),
+                ("u_final", POINTER(c_double)), ("margin", POINTER(c_double)), ("fallback", POINTER(c_int32))]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libspecgbv.so (building it with hipcc only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build
+        build()
+    L = ctypes.CDLL(_LIB_PATH)
+    L.specgbv_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int]
+    L.specgbv_workspace_bytes.restype = c_size_t
+    verify_args = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, c_uint64, c_uint64,
+                   c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    L.specgbv_verify.argtypes = verify_args
+    L.specgbv_verify.restype = c_int
+    L.specgbv_verify_ex.argtypes = verify_args + [POINTER(_Options)]
+    L.specgbv_verify_ex.restype = c_int
+    L.specgbv_read_intermediates.argtypes = [c_void_p, c_size_t, c_int, c_int, c_int, c_int, c_int,
+                                             POINTER(_Intermediates), c_void_p]
+    L.specgbv_read_intermediates.restype = c_int
+    L.specgbv_last_error.argtypes = []
+    L.specgbv_last_error.restype = c_char_p
+    L.specgbv_version.argtypes = []
+    L.specgbv_version.restype = c_char_p
+    _lib = L
+    return L
+
+
+def specgbv_last_error() -> str:
+    return load_library().specgbv_last_error().decode()
+
+
+def specgbv_version() -> str:
+    return load_library().specgbv_version().decode()
+
+
+def _check(status: int):
+    if status != 0:
+        raise SpecGBVError(status, specgbv_last_error())
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("logits must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def specgbv_workspace_bytes(batch: int, K: int, L: int, V: int, dtype: int) -> int:
+    return int(load_library().specgbv_workspace_bytes(batch, K, L, V, dtype))
+
+
+def _shapes(target_logits, draft_logits, draft_tokens):
+    import torch
+    if target_logits.dim() != 4 or draft_logits.dim() != 4 or draft_tokens.dim() != 3:
+        raise ValueError("expected target [B,K,L+1,V], draft [B,K,L,V], tokens [B,K,L]")
+    B, K, L1, V = target_logits.shape
+    L = L1 - 1
+    if tuple(draft_logits.shape) != (B, K, L, V) or tuple(draft_tokens.shape) != (B, K, L):
+        raise ValueError("inconsistent shapes: target %s draft %s tokens %s" %
+                         (tuple(target_logits.shape), tuple(draft_logits.shape), tuple(draft_tokens.shape)))
+    if target_logits.dtype != draft_logits.dtype:
+        raise TypeError("target and draft logits must share a dtype")
+    if draft_tokens.dtype != torch.int32:
+        raise TypeError("draft_tokens must be int32")
+    for t in (target_logits, draft_logits, draft_tokens):
+        if not t.is_cuda:
+            raise ValueError("all tensors must live on the GPU")
+        if not t.is_contiguous():
+            raise ValueError("all tensors must be contiguous")
+    return B, K, L, V
+
+
+def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int,
+                      rng_offset: int, *, workspace=None, out: Optional[Tuple] = None, algo="auto",
+                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None):
+    """Enqueue one verification on the current (or given) HIP stream.
+
+    Returns (accepted_len [B], accepted_draft_idx [B], out_tokens [B, L+1], workspace), all
+    device tensors; nothing is synchronised.  `events` is a pair of raw hipEvent_t handles
+    recorded around the vocabulary-streaming kernels.
+    """
+    import torch
+    lib = load_library()
+    B, K, L, V = _shapes(target_logits, draft_logits, draft_tokens)
+    dt = _dtype_code(target_logits)
+    dev = target_logits.device
+    need = specgbv_workspace_bytes(B, K, L, V, dt)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, L + 1), dtype=torch.int32, device=dev))
+    acc_len, acc_idx, out_tokens = out
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    opt = _Options(_ALGO[algo] if isinstance(algo, str) else int(algo), 0,
+                   events[0] if events else None, events[1] if events else None)
+    st = lib.specgbv_verify_ex(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V,
+                               B, dt, c_float(temperature), rng_seed, rng_offset, acc_len.data_ptr(),
+                               acc_idx.data_ptr(), out_tokens.data_ptr(), workspace.data_ptr(),
+                               workspace.numel() * workspace.element_size(), stream, ctypes.byref(opt))
+    _check(st)
+    return acc_len, acc_idx, out_tokens, workspace
+
+
+def specgbv_verify(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int, rng_offset: int,
+                   *, workspace=None, out: Optional[Tuple] = None, stream: Optional[int] = None):
+    """specgbv_verify of the C ABI: default schedule, no instrumentation."""
+    import torch
+    lib = load_library()
+    B, K, L, V = _shapes(target_logits, draft_logits, draft_tokens)
+    dt = _dtype_code(target_logits)
+    dev = target_logits.device
+    if workspace is None:
+        workspace = torch.empty(max(specgbv_workspace_bytes(B, K, L, V, dt), 256), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, L + 1), dtype=torch.int32, device=dev))
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    st = lib.specgbv_verify(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V, B,
+                            dt, c_float(temperature), rng_seed, rng_offset, out[0].data_ptr(), out[1].data_ptr(),
+                            out[2].data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                            stream)
+    _check(st)
+    return out[0], out[1], out[2], workspace
+
+
+def specgbv_read_intermediates(workspace, batch: int, K: int, L: int, V: int, dtype: int,
+                               stream: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """Copy the intermediates of the last call out of `workspace` (synchronises the stream)."""
+    import torch
+    lib = load_library()
+    if stream is None:
+        stream = torch.cuda.current_stream(workspace.device).cuda_stream
+    n = (batch, K, L)
+    res = {k: np.empty(n, np.float64) for k in ("lse_q", "lse_p", "log_nu", "log_P", "s", "h", "eta")}
+    res["state"] = np.empty(n, np.int32)
+    for k in ("res_norm", "u_final", "margin"):
+        res[k] = np.empty(batch, np.float64)
+    res["fallback"] = np.empty(batch, np.int32)
+    dp = lambda a: a.ctypes.data_as(POINTER(c_double))
+    ip = lambda a: a.ctypes.data_as(POINTER(c_int32))
+    im = _Intermediates(dp(res["lse_q"]), dp(res["lse_p"]), dp(res["log_nu"]), dp(res["log_P"]), dp(res["s"]),
+                        dp(res["h"]), dp(res["eta"]), ip(res["state"]), dp(res["res_norm"]), dp(res["u_final"]),
+                        dp(res["margin"]), ip(res["fallback"]))
+    st = lib.specgbv_read_intermediates(workspace.data_ptr(), workspace.numel() * workspace.element_size(), batch,
+                                        K, L, V, dtype, ctypes.byref(im), stream)
+    _check(st)
+    return res

@@ -1,0 +1,213 @@
+// C ABI of libspecgbv.so: argument checks, workspace layout, kernel sequencing.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/specgbv.h"
+#include "specgbv_internal.hpp"
+
+namespace specgbv {
+
+static thread_local char g_err[512] = "";
+
+static specgbv_status fail(specgbv_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+Workspace make_workspace(int batch, int K, int L, int V)
+{
+    Workspace w{};
+    const size_t n = static_cast<size_t>(batch) * K * L;
+    size_t off = 0;
+    auto take = [&off](size_t bytes) { const size_t o = off; off = align256(off + bytes); return o; };
+    w.nseg = (V + kSegElems - 1) / kSegElems;
+    w.stats = take(n * sizeof(RowStat));
+    w.s = take(n * sizeof(double));
+    w.log_nu = take(n * sizeof(double));
+    w.log_P = take(n * sizeof(double));
+    w.h = take(n * sizeof(double));
+    w.eta = take(n * sizeof(double));
+    w.state = take(n * sizeof(int32_t));
+    w.sel = take(static_cast<size_t>(batch) * sizeof(Selection));
+    w.partial = take(static_cast<size_t>(batch) * w.nseg * sizeof(SegPartial));
+    w.res_norm = take(static_cast<size_t>(batch) * sizeof(double));
+    w.u_final = take(static_cast<size_t>(batch) * sizeof(double));
+    w.margin = take(static_cast<size_t>(batch) * sizeof(double));
+    w.fallback = take(static_cast<size_t>(batch) * sizeof(int32_t));
+    w.total = off;
+    return w;
+}
+
+static bool shape_ok(int batch, int K, int L, int V)
+{
+    return batch >= 0 && K >= 1 && L >= 1 && V >= 1;
+}
+
+static specgbv_status check_limits(int batch, int K, int L, int V)
+{
+    if (K > SPECGBV_MAX_K) return fail(SPECGBV_EUNSUPPORTED, "K=%d exceeds SPECGBV_MAX_K=%d", K, SPECGBV_MAX_K);
+    if (L > SPECGBV_MAX_L) return fail(SPECGBV_EUNSUPPORTED, "L=%d exceeds SPECGBV_MAX_L=%d", L, SPECGBV_MAX_L);
+    if (K * L > 1024) return fail(SPECGBV_EUNSUPPORTED, "K*L=%d exceeds 1024", K * L);
+    const double rows = static_cast<double>(batch) * K * (L + 1);
+    if (rows > 2.0e9 || static_cast<double>(batch) > 65535.0)
+        return fail(SPECGBV_EUNSUPPORTED, "batch=%d is too large for one launch", batch);
+    if (rows * V > 9.0e18) return fail(SPECGBV_EUNSUPPORTED, "tensor too large");
+    return SPECGBV_OK;
+}
+
+}  // namespace specgbv
+
+using namespace specgbv;
+
+extern "C" {
+
+size_t specgbv_workspace_bytes(int batch, int K, int L, int V, specgbv_dtype dtype)
+{
+    if (!shape_ok(batch, K, L, V) || (dtype != SPECGBV_F32 && dtype != SPECGBV_BF16)) return 0;
+    if (check_limits(batch, K, L, V) != SPECGBV_OK) return 0;
+    return make_workspace(batch < 1 ? 1 : batch, K, L, V).total;
+}
+
+specgbv_status specgbv_verify_ex(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int L, int V, int batch, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset,
+    int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
+    void *workspace, size_t workspace_bytes, void *hip_stream,
+    const specgbv_options *options)
+{
+    if (!shape_ok(batch, K, L, V))
+        return fail(SPECGBV_EINVAL, "sizes must satisfy batch >= 0, K, L, V >= 1 (got batch=%d K=%d L=%d V=%d)",
+                    batch, K, L, V);
+    if (dtype != SPECGBV_F32 && dtype != SPECGBV_BF16) return fail(SPECGBV_EINVAL, "unknown dtype %d", (int)dtype);
+    if (!(temperature > 0.0f) || !std::isfinite(temperature))
+        return fail(SPECGBV_EINVAL, "temperature must be finite and > 0 (got %g)", (double)temperature);
+    const int algo = options ? options->algo : SPECGBV_ALGO_AUTO;
+    if (algo < SPECGBV_ALGO_AUTO || algo > SPECGBV_ALGO_CHAIN) return fail(SPECGBV_EINVAL, "unknown algo %d", algo);
+    specgbv_status st = check_limits(batch, K, L, V);
+    if (st != SPECGBV_OK) return st;
+    if (batch == 0) return SPECGBV_OK;
+    if (!target_logits || !draft_logits || !draft_tokens || !accepted_len || !accepted_draft_idx || !out_tokens)
+        return fail(SPECGBV_EINVAL, "null input or output pointer");
+    const size_t esz = dtype == SPECGBV_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(target_logits) % esz || reinterpret_cast<uintptr_t>(draft_logits) % esz ||
+        reinterpret_cast<uintptr_t>(draft_tokens) % 4 || reinterpret_cast<uintptr_t>(accepted_len) % 4 ||
+        reinterpret_cast<uintptr_t>(accepted_draft_idx) % 4 || reinterpret_cast<uintptr_t>(out_tokens) % 4)
+        return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
+
+    Problem p{};
+    p.lay = make_workspace(batch, K, L, V);
+    if (!workspace) return fail(SPECGBV_EWORKSPACE, "workspace is null (need %zu bytes)", p.lay.total);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(SPECGBV_EWORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < p.lay.total)
+        return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, p.lay.total);
+    p.target = target_logits; p.draft = draft_logits; p.tokens = draft_tokens;
+    p.K = K; p.L = L; p.V = V; p.batch = batch; p.dtype = dtype == SPECGBV_BF16 ? 1 : 0;
+    p.c = static_cast<float>(1.4426950408889634074 / static_cast<double>(temperature));
+    p.seed = rng_seed; p.offset = rng_offset;
+    p.accepted_len = accepted_len; p.accepted_draft_idx = accepted_draft_idx; p.out_tokens = out_tokens;
+    p.ws = static_cast<char *>(workspace);
+    p.stream = static_cast<hipStream_t>(hip_stream);
+
+    bool use_chain = false;
+    if (algo == SPECGBV_ALGO_CHAIN) {
+        if (!chain_supported(p)) return fail(SPECGBV_EUNSUPPORTED, "the chain schedule does not support this shape");
+        use_chain = true;
+    } else if (algo == SPECGBV_ALGO_AUTO) {
+        use_chain = chain_supported(p) && static_cast<long long>(batch) * K >= 128;
+    }
+
+    hipError_t e;
+    if (options && options->ev_main_start) {
+        e = hipEventRecord(static_cast<hipEvent_t>(options->ev_main_start), p.stream);
+        if (e != hipSuccess) return fail(SPECGBV_EHIP, "hipEventRecord: %s", hipGetErrorString(e));
+    }
+    e = use_chain ? launch_chain_main(p) : launch_split_main(p);
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "main kernel launch: %s", hipGetErrorString(e));
+    if (options && options->ev_main_stop) {
+        e = hipEventRecord(static_cast<hipEvent_t>(options->ev_main_stop), p.stream);
+        if (e != hipSuccess) return fail(SPECGBV_EHIP, "hipEventRecord: %s", hipGetErrorString(e));
+    }
+    e = launch_decide_and_sample(p);
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "decision/sampling kernel launch: %s", hipGetErrorString(e));
+    return SPECGBV_OK;
+}
+
+specgbv_status specgbv_verify(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int L, int V, int batch, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset,
+    int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
+    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return specgbv_verify_ex(target_logits, draft_logits, draft_tokens, K, L, V, batch, dtype, temperature,
+                             rng_seed, rng_offset, accepted_len, accepted_draft_idx, out_tokens, workspace,
+                             workspace_bytes, hip_stream, nullptr);
+}
+
+specgbv_status specgbv_read_intermediates(
+    const void *workspace, size_t workspace_bytes, int batch, int K, int L, int V,
+    specgbv_dtype dtype, const specgbv_intermediates *out, void *hip_stream)
+{
+    (void)dtype;
+    if (!shape_ok(batch, K, L, V) || batch < 1) return fail(SPECGBV_EINVAL, "bad shape");
+    if (!workspace || !out) return fail(SPECGBV_EINVAL, "null pointer");
+    const Workspace lay = make_workspace(batch, K, L, V);
+    if (workspace_bytes < lay.total) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, lay.total);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const char *ws = static_cast<const char *>(workspace);
+    const size_t n = static_cast<size_t>(batch) * K * L;
+    hipError_t e = hipSuccess;
+    auto copy = [&](void *dst, size_t off, size_t bytes) {
+        if (dst && e == hipSuccess) e = hipMemcpyAsync(dst, ws + off, bytes, hipMemcpyDeviceToHost, stream);
+    };
+    // statistics are stored interleaved in base 2; unpack on the host
+    RowStat *tmp = nullptr;
+    if (out->lse_q || out->lse_p) {
+        tmp = static_cast<RowStat *>(malloc(n * sizeof(RowStat)));
+        if (!tmp) return fail(SPECGBV_EINVAL, "host allocation failed");
+        copy(tmp, lay.stats, n * sizeof(RowStat));
+    }
+    copy(out->log_nu, lay.log_nu, n * sizeof(double));
+    copy(out->log_P, lay.log_P, n * sizeof(double));
+    copy(out->s, lay.s, n * sizeof(double));
+    copy(out->h, lay.h, n * sizeof(double));
+    copy(out->eta, lay.eta, n * sizeof(double));
+    copy(out->state, lay.state, n * sizeof(int32_t));
+    copy(out->res_norm, lay.res_norm, batch * sizeof(double));
+    copy(out->u_final, lay.u_final, batch * sizeof(double));
+    copy(out->margin, lay.margin, batch * sizeof(double));
+    copy(out->fallback, lay.fallback, batch * sizeof(int32_t));
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) {
+        free(tmp);
+        return fail(SPECGBV_EHIP, "reading intermediates: %s", hipGetErrorString(e));
+    }
+    if (tmp) {
+        const double ln2 = 0.693147180559945309417;
+        for (size_t j = 0; j < n; ++j) {
+            if (out->lse_q) out->lse_q[j] = tmp[j].lse2_q * ln2;
+            if (out->lse_p) out->lse_p[j] = tmp[j].lse2_p * ln2;
+        }
+        free(tmp);
+    }
+    if (out->s) {
+        const double nan = std::nan("");
+        for (size_t j = 0; j < n; j += L) out->s[j] = nan;      // row 0 carries no Eq. (hik) sum
+    }
+    return SPECGBV_OK;
+}
+
+const char *specgbv_last_error(void) { return g_err; }
+
+const char *specgbv_version(void) { return "specgbv 0.1 (gfx950)"; }
+
+}  // extern "C"

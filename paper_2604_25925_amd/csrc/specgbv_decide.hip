@@ -1,0 +1,422 @@
+// Decision scan of Algorithm 1 and the final-token draw.
+//
+//   k_decide      : one wave per prefix.  Builds nu_i, P_i, the acceptance table
+//                   (Eq. (hik) for i < L, Eq. (hLk) for i = L, both divided through by
+//                   P_i so that no joint block probability is ever formed), draws the
+//                   Philox uniforms and runs the sequential loop with the set H of
+//                   rejected blocks.
+//   k_res_partial : per (prefix, vocabulary segment) partial sums of the weights the
+//                   final token is drawn from -- Eq. (pres) with q(x^tau) cancelled,
+//                   w[x] = q[x] max(1 - p[x]/(nu q[x]), 0)^K, or q[x] for the bonus token.
+//   k_res_locate  : per prefix inverse-CDF search: the first token id whose running
+//                   weight exceeds u * total.
+#include "specgbv_internal.hpp"
+
+namespace specgbv {
+namespace {
+
+// ---------------------------------------------------------------- k_decide
+
+__device__ double c_K(double log_P, int K)
+{
+    // (1 - (1-P)^K) / P: chance that one of K i.i.d. drafts equals a block of draft
+    // probability P, over P.
+    const double P = exp(log_P);
+    if (!(P > 0.0)) return static_cast<double>(K);
+    if (P >= 1.0) return 1.0;
+    return -expm1(static_cast<double>(K) * log1p(-P)) / P;
+}
+
+__device__ double g_K(double log_nu, int K)
+{
+    const double t = 1.0 - exp(-log_nu);
+    return t > 0.0 ? powi_uniform(t, K) : 0.0;
+}
+
+__device__ double clamp01(double h)
+{
+    if (!(h > 0.0)) return 0.0;
+    return h < 1.0 ? h : 1.0;
+}
+
+__global__ void __launch_bounds__(kWave)
+k_decide(const int32_t *__restrict__ tokens, int K, int L, int V, uint64_t seed, uint64_t offset,
+         const RowStat *__restrict__ stats, const double *__restrict__ s_arr,
+         double *__restrict__ log_nu_out, double *__restrict__ log_P_out, double *__restrict__ h_out,
+         double *__restrict__ eta_out, int32_t *__restrict__ state_out, Selection *__restrict__ sel,
+         int32_t *__restrict__ accepted_len, int32_t *__restrict__ accepted_draft_idx,
+         int32_t *__restrict__ out_tokens)
+{
+    extern __shared__ double lds[];
+    const int KL = K * L;
+    double *h = lds;                                        // [K*L]
+    double *eta = lds + KL;                                 // [K*L]
+    double *l2nu = lds + 2 * KL;                            // [K*L] log2 nu_i
+    int *tok = reinterpret_cast<int *>(lds + 3 * KL);       // [K*L]
+    int *cpl = tok + KL;                                    // [K*K] common prefix lengths
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const long long base = static_cast<long long>(b) * KL;
+    constexpr double kLn2 = 0.693147180559945309417;
+
+    for (int idx = lane; idx < KL; idx += kWave) {
+        const int k = idx / L, i = idx % L + 1;
+        double log2nu = 0.0, log2P = 0.0;
+        for (int j = 0; j < i; ++j) {
+            const RowStat st = stats[base + k * L + j];
+            const double lq = st.tok2_q - st.lse2_q, lp = st.tok2_p - st.lse2_p;
+            log2nu += lq - lp;
+            log2P += lp;
+        }
+        const double log_nu = log2nu * kLn2, log_P = log2P * kLn2;
+        double hv;
+        if (i < L) {
+            const double s = s_arr[base + k * L + i];
+            const double nu = exp(log_nu);
+            const double num = nu * (s - g_K(log_nu, K));
+            const double den = c_K(log_P, K) - nu * (1.0 - s);
+            hv = den > 0.0 ? clamp01(num / den) : 1.0;
+        } else {
+            hv = clamp01(exp(log_nu) * (1.0 - g_K(log_nu, K)) / c_K(log_P, K));
+        }
+        const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
+        h[idx] = hv; eta[idx] = e; l2nu[idx] = log2nu;
+        tok[idx] = tokens[base + idx];
+        log_nu_out[base + idx] = log_nu; log_P_out[base + idx] = log_P;
+        h_out[base + idx] = hv; eta_out[base + idx] = e;
+        state_out[base + idx] = 0;
+    }
+    __syncthreads();
+    for (int idx = lane; idx < K * K; idx += kWave) {
+        const int k1 = idx / K, k2 = idx % K;
+        int n = 0;
+        while (n < L && tok[k1 * L + n] == tok[k2 * L + n]) ++n;
+        cpl[idx] = n;
+    }
+    __syncthreads();
+
+    // Sequential loop of Algorithm 1, executed by the whole wave in lock step; lane j
+    // keeps the lengths at which draft j was tested and rejected (its entries of H).
+    int tau = 0, f = -1;
+    unsigned long long rejected = 0ull;
+    bool done = false;
+    for (int k = 0; k < K && !done; ++k) {
+        const int my_cpl = (lane < k) ? cpl[k * K + lane] : 0;
+        for (int i = tau + 1; i <= L; ++i) {
+            const bool hit = (lane < k) && ((rejected >> i) & 1ull) && (my_cpl >= i);
+            const int idx = k * L + i - 1;
+            if (__any(hit)) {                 // block already in H: no sampling
+                if (lane == 0) state_out[base + idx] = 2;
+                continue;
+            }
+            if (lane == 0) state_out[base + idx] = 1;
+            if (eta[idx] < h[idx]) {
+                tau = i; f = k;
+                if (i == L) { done = true; break; }
+            } else if (lane == k) {
+                rejected |= 1ull << i;
+            }
+        }
+    }
+
+    const int kf = f < 0 ? 0 : f;
+    if (lane == 0) {
+        accepted_len[b] = tau;
+        accepted_draft_idx[b] = f;
+        Selection sl;
+        sl.tau = tau;
+        sl.target_row = (static_cast<long long>(b) * K + kf) * (L + 1) + tau;
+        if (tau == L) {
+            sl.draft_row = -1; sl.C2 = 0.0; sl.shift_q = 0.0f; sl.lse2_q = 0.0;
+        } else {
+            sl.draft_row = (static_cast<long long>(b) * K + kf) * L + tau;
+            const RowStat st = stats[sl.draft_row];
+            sl.C2 = st.lse2_p - st.lse2_q + (tau == 0 ? 0.0 : l2nu[kf * L + tau - 1]);
+            sl.shift_q = static_cast<float>(st.lse2_q);
+            sl.lse2_q = st.lse2_q;
+        }
+        sel[b] = sl;
+    }
+    for (int j = lane; j <= L; j += kWave)
+        out_tokens[static_cast<long long>(b) * (L + 1) + j] = j < tau ? tok[kf * L + j] : -1;
+    (void)V;
+}
+
+// ------------------------------------------------------------ final token
+
+// Weights of the 8 vocabulary entries [e0, e0+8) of the selected row(s); entries at or
+// beyond V get weight 0.  Returns the weights relative to 2^m2.
+template <typename T, bool VEC>
+__device__ __forceinline__ void load8(const T *row, long long e0, int V, float (&z)[8])
+{
+    constexpr int PV = Elem<T>::kPerVec;
+    if (VEC && e0 + 8 <= V) {
+#pragma unroll
+        for (int v = 0; v < 8 / PV; ++v) {
+            float t[PV];
+            Elem<T>::unpack(load16(row + e0 + v * PV), t);
+#pragma unroll
+            for (int j = 0; j < PV; ++j) z[v * PV + j] = t[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) z[j] = (e0 + j < V) ? Elem<T>::scalar(row + e0 + j) : -INFINITY;
+    }
+}
+
+template <typename T, bool VEC>
+__device__ __forceinline__ void segment_weights(const T *target, const T *draft, const Selection &sl, int V,
+                                                int K, float c, int seg, float m2, float (&w)[8], float (&wq)[8])
+{
+    const long long e0 = static_cast<long long>(seg) * kSegElems + threadIdx.x * 8;
+    float zq[8];
+    if (e0 < V) load8<T, VEC>(target + sl.target_row * V, e0, V, zq);
+    else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) zq[j] = -INFINITY;
+    }
+    if (sl.draft_row < 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -m2)); w[j] = wq[j]; }
+        return;
+    }
+    float zp[8];
+    if (e0 < V) load8<T, VEC>(draft + sl.draft_row * V, e0, V, zp);
+    else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) zp[j] = 0.0f;
+    }
+    const RatioConst rc(sl.C2);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const bool live = e0 + j < V;
+        const float eq = live ? exp2_fast(fmaf(zq[j], c, -m2)) : 0.0f;
+        const float t = live ? rc.one_minus_ratio(zp[j] - zq[j], c) : 0.0f;
+        wq[j] = eq;
+        w[j] = eq * powi_uniform(t, K);
+    }
+}
+
+// Reference exponent of a segment: the fixed shift of the selected target row for a
+// residual draw, the segment's own maximum for the bonus row (whose statistics were
+// never computed).
+template <typename T, bool VEC>
+__device__ __forceinline__ float segment_reference(const T *target, const Selection &sl, int V, float c,
+                                                   int seg, float *sh_f)
+{
+    if (sl.draft_row >= 0) return sl.shift_q;
+    const long long e0 = static_cast<long long>(seg) * kSegElems + threadIdx.x * 8;
+    float zq[8];
+    float m = -INFINITY;
+    if (e0 < V) {
+        load8<T, VEC>(target + sl.target_row * V, e0, V, zq);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m = fmaxf(m, zq[j]);
+    }
+    return block_max(m, sh_f) * c;
+}
+
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kSegThreads)
+k_res_partial(const T *__restrict__ target, const T *__restrict__ draft, const Selection *__restrict__ sel,
+              int V, int K, float c, int nseg, SegPartial *__restrict__ partial)
+{
+    __shared__ double sh_d[kSegThreads / kWave];
+    __shared__ float sh_f[kSegThreads / kWave];
+    const int seg = blockIdx.x, b = blockIdx.y;
+    const Selection sl = sel[b];
+    const float m2 = segment_reference<T, VEC>(target, sl, V, c, seg, sh_f);
+    float w[8], wq[8];
+    segment_weights<T, VEC>(target, draft, sl, V, K, c, seg, m2, w, wq);
+    double sw = 0.0, sq = 0.0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { sw += static_cast<double>(w[j]); sq += static_cast<double>(wq[j]); }
+    sw = block_sum(sw, sh_d);
+    sq = block_sum(sq, sh_d);
+    if (threadIdx.x == 0) {
+        SegPartial pt;
+        pt.sum_w = sw; pt.sum_q = sq; pt.m2 = m2; pt.pad = 0.0f;
+        partial[static_cast<long long>(b) * nseg + seg] = pt;
+    }
+}
+
+__device__ __forceinline__ double wave_inclusive_scan(double v)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const double o = __shfl_up(v, off, kWave);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kSegThreads)
+k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Selection *__restrict__ sel,
+             int V, int K, int L, float c, int nseg, const SegPartial *__restrict__ partial,
+             uint64_t seed, uint64_t offset, int32_t *__restrict__ out_tokens,
+             double *__restrict__ res_norm, double *__restrict__ u_final, double *__restrict__ margin_out,
+             int32_t *__restrict__ fallback_out)
+{
+    __shared__ double sh_d[kSegThreads / kWave];
+    __shared__ double sh_scan[kSegThreads / kWave];
+    __shared__ float sh_f[kSegThreads / kWave];
+    __shared__ int sh_seg;
+    __shared__ double sh_local_target, sh_total;
+    __shared__ int sh_use_q;
+    __shared__ int sh_winner;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const Selection sl = sel[b];
+    const SegPartial *pp = partial + static_cast<long long>(b) * nseg;
+
+    // common reference exponent and totals
+    float mloc = -INFINITY;
+    for (int s = tid; s < nseg; s += kSegThreads) mloc = fmaxf(mloc, pp[s].m2);
+    const float M = block_max(mloc, sh_f);
+    double tw = 0.0, tq = 0.0;
+    for (int s = tid; s < nseg; s += kSegThreads) {
+        const double sc = exp2(static_cast<double>(pp[s].m2) - static_cast<double>(M));
+        tw += pp[s].sum_w * sc; tq += pp[s].sum_q * sc;
+    }
+    tw = block_sum(tw, sh_d);
+    tq = block_sum(tq, sh_d);
+    const bool use_q = !(tw > 0.0);           // every residual weight is zero: draw from q
+    const double W = use_q ? tq : tw;
+    const double u = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(K * L));
+    const double goal = u * W;
+
+    // first segment whose running total exceeds the goal (thread 0; nseg is small)
+    if (tid == 0) {
+        double cum = 0.0;
+        int found = -1, last_pos = 0;
+        double cum_before = 0.0, cum_before_last = 0.0;
+        for (int s = 0; s < nseg; ++s) {
+            const double sc = exp2(static_cast<double>(pp[s].m2) - static_cast<double>(M));
+            const double v = (use_q ? pp[s].sum_q : pp[s].sum_w) * sc;
+            if (v > 0.0) { last_pos = s; cum_before_last = cum; }
+            if (cum + v > goal) { found = s; cum_before = cum; break; }
+            cum += v;
+        }
+        if (found < 0) { found = last_pos; cum_before = cum_before_last; }
+        sh_seg = found;
+        // goal expressed in the segment's own scale
+        sh_local_target = (goal - cum_before) * exp2(static_cast<double>(M) - static_cast<double>(pp[found].m2));
+        sh_total = W * exp2(static_cast<double>(M) - static_cast<double>(pp[found].m2));
+        sh_use_q = use_q ? 1 : 0;
+        sh_winner = kSegThreads;
+    }
+    __syncthreads();
+    const int seg = sh_seg;
+    const double local_target = sh_local_target;
+    const float m2 = pp[seg].m2;
+    float w[8], wq[8];
+    segment_weights<T, VEC>(target, draft, sl, V, K, c, seg, m2, w, wq);
+    double ws[8];
+    double mine = 0.0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        ws[j] = static_cast<double>(use_q ? wq[j] : w[j]);
+        mine += ws[j];
+    }
+    // exclusive scan of the per-thread sums in thread (= token id) order
+    const int lane = tid & (kWave - 1), wid = tid / kWave;
+    const double incl = wave_inclusive_scan(mine);
+    if (lane == kWave - 1) sh_scan[wid] = incl;
+    __syncthreads();
+    double wave_off = 0.0;
+    for (int wv = 0; wv < wid; ++wv) wave_off += sh_scan[wv];
+    const double excl = wave_off + incl - mine;
+    const bool crosses = mine > 0.0 && excl + mine > local_target;
+    if (crosses) atomicMin(&sh_winner, tid);
+    // fallback for a goal that rounding pushed past the segment: last positive thread
+    __shared__ int sh_last_pos;
+    if (tid == 0) sh_last_pos = -1;
+    __syncthreads();
+    if (mine > 0.0) atomicMax(&sh_last_pos, tid);
+    __syncthreads();
+    int winner = sh_winner;
+    const bool past_end = winner == kSegThreads;
+    if (past_end) winner = sh_last_pos < 0 ? 0 : sh_last_pos;
+    if (tid == winner) {
+        const long long e0 = static_cast<long long>(seg) * kSegElems + tid * 8;
+        double run = excl;
+        int y = -1;
+        double mg = 0.0;
+        int last = -1;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const double prev = run;
+            run += ws[j];
+            if (ws[j] > 0.0) last = j;
+            if (y < 0 && run > local_target) {
+                y = j;
+                const double lo = local_target - prev, hi = run - local_target;
+                mg = (lo < hi ? lo : hi) / sh_total;
+            }
+        }
+        if (y < 0) { y = last < 0 ? 0 : last; mg = 0.0; }
+        long long tokid = e0 + y;
+        if (tokid >= V) tokid = V - 1;
+        out_tokens[static_cast<long long>(b) * (L + 1) + sl.tau] = static_cast<int32_t>(tokid);
+        margin_out[b] = mg;
+        u_final[b] = u;
+        fallback_out[b] = sh_use_q;
+        // total weight in probability units: weights are relative to 2^M, the target row's
+        // normaliser is 2^lse2_q (bonus row: the total is the normaliser itself)
+        res_norm[b] = sl.draft_row < 0 ? 1.0 : W * exp2(static_cast<double>(M) - sl.lse2_q);
+    }
+}
+
+template <typename T>
+hipError_t launch_sample_typed(const Problem &p)
+{
+    const T *target = static_cast<const T *>(p.target);
+    const T *draft = static_cast<const T *>(p.draft);
+    const Selection *sel = reinterpret_cast<const Selection *>(p.ws + p.lay.sel);
+    SegPartial *partial = reinterpret_cast<SegPartial *>(p.ws + p.lay.partial);
+    const bool vec = (p.V % Elem<T>::kPerVec) == 0 &&
+                     (reinterpret_cast<uintptr_t>(p.target) % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(p.draft) % 16 == 0);
+    const dim3 g(static_cast<unsigned>(p.lay.nseg), static_cast<unsigned>(p.batch));
+    double *res_norm = reinterpret_cast<double *>(p.ws + p.lay.res_norm);
+    double *u_final = reinterpret_cast<double *>(p.ws + p.lay.u_final);
+    double *margin = reinterpret_cast<double *>(p.ws + p.lay.margin);
+    int32_t *fallback = reinterpret_cast<int32_t *>(p.ws + p.lay.fallback);
+    if (vec) {
+        hipLaunchKernelGGL((k_res_partial<T, true>), g, dim3(kSegThreads), 0, p.stream, target, draft, sel,
+                           p.V, p.K, p.c, p.lay.nseg, partial);
+        hipLaunchKernelGGL((k_res_locate<T, true>), dim3(p.batch), dim3(kSegThreads), 0, p.stream, target,
+                           draft, sel, p.V, p.K, p.L, p.c, p.lay.nseg, partial, p.seed, p.offset,
+                           p.out_tokens, res_norm, u_final, margin, fallback);
+    } else {
+        hipLaunchKernelGGL((k_res_partial<T, false>), g, dim3(kSegThreads), 0, p.stream, target, draft, sel,
+                           p.V, p.K, p.c, p.lay.nseg, partial);
+        hipLaunchKernelGGL((k_res_locate<T, false>), dim3(p.batch), dim3(kSegThreads), 0, p.stream, target,
+                           draft, sel, p.V, p.K, p.L, p.c, p.lay.nseg, partial, p.seed, p.offset,
+                           p.out_tokens, res_norm, u_final, margin, fallback);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_decide_and_sample(const Problem &p)
+{
+    const int KL = p.K * p.L;
+    const size_t lds = sizeof(double) * 3 * KL + sizeof(int) * (KL + p.K * p.K);
+    hipLaunchKernelGGL(k_decide, dim3(p.batch), dim3(kWave), lds, p.stream, p.tokens, p.K, p.L, p.V, p.seed,
+                       p.offset, reinterpret_cast<const RowStat *>(p.ws + p.lay.stats),
+                       reinterpret_cast<const double *>(p.ws + p.lay.s),
+                       reinterpret_cast<double *>(p.ws + p.lay.log_nu),
+                       reinterpret_cast<double *>(p.ws + p.lay.log_P),
+                       reinterpret_cast<double *>(p.ws + p.lay.h),
+                       reinterpret_cast<double *>(p.ws + p.lay.eta),
+                       reinterpret_cast<int32_t *>(p.ws + p.lay.state),
+                       reinterpret_cast<Selection *>(p.ws + p.lay.sel), p.accepted_len,
+                       p.accepted_draft_idx, p.out_tokens);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return p.dtype == 1 ? launch_sample_typed<uint16_t>(p) : launch_sample_typed<float>(p);
+}
+
+}  // namespace specgbv

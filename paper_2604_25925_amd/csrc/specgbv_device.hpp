@@ -1,0 +1,195 @@
+// Device-side helpers shared by the SpecTr-GBV kernels (gfx950, wave64).
+//
+// Arithmetic conventions used by every kernel:
+//   * logits are scaled to base-2 exponents with one float constant
+//       c = float(log2(e) / temperature)
+//     and the same float is used (widened) on the float64 scalar side, so all
+//     GPU-side quantities are mutually consistent;
+//   * vocabulary-wide sums are accumulated per thread in float32 and combined
+//     across threads in float64;
+//   * O(batch*K*L) scalars (block ratios, acceptance probabilities) are float64.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace specgbv {
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------- workspace
+
+// Per (prefix, draft, row) statistics, all in base-2 logarithms.
+struct RowStat {
+    double lse2_q;   // log2 sum_x 2^(c z_q[x])
+    double lse2_p;   // log2 sum_x 2^(c z_p[x])
+    double tok2_q;   // c * z_q[token of this row]
+    double tok2_p;   // c * z_p[token of this row]
+};
+
+// What the final-token kernels need to know about one prefix.
+struct Selection {
+    long long target_row;   // row index into target_logits (in rows of V elements)
+    long long draft_row;    // row index into draft_logits, or -1 for the bonus row
+    double C2;              // log2 of nu * Z_p / Z_q: the ratio p/(nu q) is 2^(c (z_p - z_q) - C2)
+    double lse2_q;          // log2 normaliser of the target row (0 for the bonus row)
+    float shift_q;          // reference exponent for target-row weights (unused for the bonus row)
+    int tau;
+};
+
+// Partial sums of one residual segment, relative to 2^m2.
+struct SegPartial {
+    double sum_w;    // sum of residual weights
+    double sum_q;    // sum of plain target weights (used if every residual weight is zero)
+    float m2;        // reference exponent of both sums
+    float pad;
+};
+
+// ------------------------------------------------------------------- loads
+
+struct alignas(16) U4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kPerVec = 4;       // elements per 16-byte load
+    __device__ static __forceinline__ void unpack(const U4 &v, float (&o)[4]) {
+        o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y);
+        o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
+    }
+    __device__ static __forceinline__ float scalar(const float *p) { return *p; }
+};
+template <> struct Elem<uint16_t> {
+    static constexpr int kPerVec = 8;
+    __device__ static __forceinline__ void unpack(const U4 &v, float (&o)[8]) {
+        o[0] = bf16_lo(v.x); o[1] = bf16_hi(v.x); o[2] = bf16_lo(v.y); o[3] = bf16_hi(v.y);
+        o[4] = bf16_lo(v.z); o[5] = bf16_hi(v.z); o[6] = bf16_lo(v.w); o[7] = bf16_hi(v.w);
+    }
+    __device__ static __forceinline__ float scalar(const uint16_t *p) {
+        return __uint_as_float(static_cast<uint32_t>(*p) << 16);
+    }
+};
+
+__device__ __forceinline__ U4 load16(const void *p) {
+    return *reinterpret_cast<const U4 *>(p);
+}
+
+// ------------------------------------------------------------------- math
+
+// v_exp_f32: 2^x, about 1 ulp, flushes results below 2^-126.
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// max(1 - r, 0) for r >= 0, as one clamped subtract.
+__device__ __forceinline__ float one_minus_clamped(float r) {
+    return __builtin_amdgcn_fmed3f(1.0f - r, 0.0f, 1.0f);
+}
+
+// The ratio p[x] / (nu q[x]) = 2^(c (z_p - z_q) - C2) with a float64 constant C2 that can be
+// large while the exponent itself is small for the entries that matter.  C2 is split into
+// a float part used inside the exponent and a factor kappa = 2^-(C2 - float(C2)) applied in
+// the following "1 - ratio" (as one fused multiply-add), so the rounding of C2 to float
+// costs neither accuracy nor an instruction.
+struct RatioConst {
+    float C2_hi;
+    float neg_kappa;
+    __device__ __forceinline__ explicit RatioConst(double C2) {
+        C2_hi = static_cast<float>(C2);
+        const double kappa = exp2(static_cast<double>(C2_hi) - C2);
+        neg_kappa = (kappa > 0.5 && kappa < 2.0) ? -static_cast<float>(kappa) : -1.0f;   // non-finite C2
+    }
+    // max(1 - p/(nu q), 0) for logit difference d = z_p - z_q
+    __device__ __forceinline__ float one_minus_ratio(float d, float c) const {
+        const float r = __builtin_amdgcn_exp2f(fmaf(d, c, -C2_hi));
+        return __builtin_amdgcn_fmed3f(fmaf(r, neg_kappa, 1.0f), 0.0f, 1.0f);
+    }
+};
+
+// t^K for a wave-uniform integer K >= 1 (square and multiply).
+__device__ __forceinline__ float powi_uniform(float t, int K) {
+    float acc = (K & 1) ? t : 1.0f;
+    float base = t;
+    for (int k = K >> 1; k; k >>= 1) {
+        base *= base;
+        if (k & 1) acc *= base;
+    }
+    return acc;
+}
+
+__device__ __forceinline__ double powi_uniform(double t, int K) {
+    double acc = (K & 1) ? t : 1.0;
+    double base = t;
+    for (int k = K >> 1; k; k >>= 1) {
+        base *= base;
+        if (k & 1) acc *= base;
+    }
+    return acc;
+}
+
+// ------------------------------------------------------------- reductions
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int off = kWave / 2; off; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = kWave / 2; off; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// Sum over the workgroup; every thread gets the result.  `scratch` holds at least
+// (blockDim.x / 64) doubles of LDS; safe to call repeatedly with the same scratch.
+__device__ __forceinline__ double block_sum(double v, double *scratch) {
+    const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+    const int nw = (blockDim.x + kWave - 1) / kWave;
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) scratch[wid] = v;
+    __syncthreads();
+    double r = 0.0;
+    for (int w = 0; w < nw; ++w) r += scratch[w];
+    return r;
+}
+
+__device__ __forceinline__ float block_max(float v, float *scratch) {
+    const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+    const int nw = (blockDim.x + kWave - 1) / kWave;
+    v = wave_max(v);
+    __syncthreads();
+    if (lane == 0) scratch[wid] = v;
+    __syncthreads();
+    float r = scratch[0];
+    for (int w = 1; w < nw; ++w) r = fmaxf(r, scratch[w]);
+    return r;
+}
+
+// ------------------------------------------------------------------ Philox
+
+// Philox4x32-10 (Salmon et al., SC'11); returns output word 0.
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2,
+                                                        uint32_t c3, uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
+
+// Uniform in [0,1) with 24 random bits for (seed, offset, prefix, slot).
+__device__ __forceinline__ double philox_uniform(uint64_t seed, uint64_t offset, uint32_t prefix,
+                                                 uint32_t slot) {
+    const uint32_t w = philox4x32_10_word0(static_cast<uint32_t>(offset), static_cast<uint32_t>(offset >> 32),
+                                           prefix, slot, static_cast<uint32_t>(seed),
+                                           static_cast<uint32_t>(seed >> 32));
+    return static_cast<double>(w >> 8) * (1.0 / 16777216.0);
+}
+
+}  // namespace specgbv

@@ -1,0 +1,64 @@
+// Host-side declarations shared by the translation units of libspecgbv.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "specgbv_device.hpp"
+
+namespace specgbv {
+
+// Device workspace carved into arrays; offsets in bytes, all 256-byte aligned.
+struct Workspace {
+    size_t stats;      // RowStat [B*K*L]
+    size_t s;          // double  [B*K*L]   (position i = row i; position 0 unused)
+    size_t log_nu;     // double  [B*K*L]
+    size_t log_P;      // double  [B*K*L]
+    size_t h;          // double  [B*K*L]
+    size_t eta;        // double  [B*K*L]
+    size_t state;      // int32   [B*K*L]
+    size_t sel;        // Selection [B]
+    size_t partial;    // SegPartial [B*nseg]
+    size_t res_norm;   // double [B]
+    size_t u_final;    // double [B]
+    size_t margin;     // double [B]
+    size_t fallback;   // int32  [B]
+    size_t total;
+    int nseg;
+};
+
+constexpr int kSegThreads = 256;
+constexpr int kSegElems = kSegThreads * 8;     // vocabulary entries per residual segment
+
+Workspace make_workspace(int batch, int K, int L, int V);
+
+struct Problem {
+    const void *target;
+    const void *draft;
+    const int32_t *tokens;
+    int K, L, V, batch;
+    int dtype;          // 0 = float32, 1 = bfloat16
+    float c;            // log2(e) / temperature
+    uint64_t seed, offset;
+    int32_t *accepted_len;
+    int32_t *accepted_draft_idx;
+    int32_t *out_tokens;
+    char *ws;
+    Workspace lay;
+    hipStream_t stream;
+};
+
+// Schedule "split": statistics kernel, then a second pass for the sums of Eq. (hik).
+hipError_t launch_split_main(const Problem &p);
+
+// Schedule "chain": one workgroup per (prefix, draft) keeps each row pair on chip between
+// the statistics sweep and the Eq. (hik) sweep.  chain_supported() says whether the shape
+// fits the kernel's static limits.
+bool chain_supported(const Problem &p);
+hipError_t launch_chain_main(const Problem &p);
+
+// Decision scan (Algorithm 1) and final-token kernels (Eq. (pres) / bonus token).
+hipError_t launch_decide_and_sample(const Problem &p);
+
+}  // namespace specgbv

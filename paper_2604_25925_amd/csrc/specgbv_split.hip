@@ -1,0 +1,168 @@
+// Schedule "split": two streaming passes over the logits.
+//
+//   k_row_stats : per row, log2 sum_x 2^(c z[x]) and the token's scaled logit
+//                 (soft-max statistics of the distributions Algorithm 1 takes as input)
+//   k_ot_sum    : per row pair i = 1..L-1, the vocabulary sum of Eq. (hik) divided by
+//                 q(x^i):  s_i = sum_x q_i[x] max(1 - p_i[x] / (nu_i q_i[x]), 0)^K
+//
+// Any V and any alignment is accepted (rows whose byte length is not a multiple of 16
+// take the scalar-load path).  This schedule reads every row pair twice; it is the
+// general fallback and the reference schedule for the on-chip "chain" kernel.
+#include "specgbv_internal.hpp"
+
+namespace specgbv {
+namespace {
+
+constexpr int kStatThreads = 512;
+
+// Per-thread running sum of 2^(c z - m2) with a running reference exponent m2.
+struct OnlineSum {
+    float m2 = -3.0e38f;          // finite, so that -inf logits give 2^(-inf) = 0, not NaN
+    float Z = 0.0f;
+    template <int N>
+    __device__ __forceinline__ void add(const float (&z)[N], float c) {
+        float vm = z[0];
+#pragma unroll
+        for (int j = 1; j < N; ++j) vm = fmaxf(vm, z[j]);
+        const float vm2 = vm * c;
+        if (vm2 > m2) {
+            Z *= exp2_fast(m2 - vm2);     // first use: Z is 0 and stays 0
+            m2 = vm2;
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) Z += exp2_fast(fmaf(z[j], c, -m2));
+    }
+    __device__ __forceinline__ void add1(float z, float c) {
+        const float z2 = z * c;
+        if (z2 > m2) {
+            Z *= exp2_fast(m2 - z2);
+            m2 = z2;
+        }
+        Z += exp2_fast(fmaf(z, c, -m2));
+    }
+};
+
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kStatThreads)
+k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
+            const int32_t *__restrict__ tokens, int L, int V, float c,
+            RowStat *__restrict__ stats)
+{
+    __shared__ double sh_d[kStatThreads / kWave];
+    __shared__ float sh_f[kStatThreads / kWave];
+    const long long pair = blockIdx.x;            // (b*K + k)*L + r
+    const int r = static_cast<int>(pair % L);
+    const long long bk = pair / L;
+    const bool is_draft = blockIdx.y == 1;
+    const T *row = is_draft ? draft + (bk * L + r) * static_cast<long long>(V)
+                            : target + (bk * (L + 1) + r) * static_cast<long long>(V);
+    constexpr int PV = Elem<T>::kPerVec;
+    OnlineSum acc;
+    if (VEC) {
+        const int nvec = V / PV;
+        for (int i = threadIdx.x; i < nvec; i += kStatThreads) {
+            float z[PV];
+            Elem<T>::unpack(load16(row + static_cast<long long>(i) * PV), z);
+            acc.add(z, c);
+        }
+    } else {
+        for (int x = threadIdx.x; x < V; x += kStatThreads) acc.add1(Elem<T>::scalar(row + x), c);
+    }
+    const float M = block_max(acc.m2, sh_f);
+    const double part = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));
+    const double total = block_sum(acc.Z > 0.0f ? part : 0.0, sh_d);
+    if (threadIdx.x == 0) {
+        const double lse2 = static_cast<double>(M) + log2(total);
+        int tok = tokens[pair];
+        tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+        const double tok2 = static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c);
+        if (is_draft) { stats[pair].lse2_p = lse2; stats[pair].tok2_p = tok2; }
+        else { stats[pair].lse2_q = lse2; stats[pair].tok2_q = tok2; }
+    }
+}
+
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kStatThreads)
+k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
+         const RowStat *__restrict__ stats, double *__restrict__ s_out)
+{
+    __shared__ double sh_d[kStatThreads / kWave];
+    const long long idx = blockIdx.x;             // bk*(L-1) + (i-1)
+    const int i = static_cast<int>(idx % (L - 1)) + 1;
+    const long long bk = idx / (L - 1);
+    // block likelihood ratio of the length-i block, from the rows before row i
+    double log2nu = 0.0;
+    for (int j = 0; j < i; ++j) {
+        const RowStat st = stats[bk * L + j];
+        log2nu += (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);
+    }
+    const RowStat st = stats[bk * L + i];
+    const float shift_q = static_cast<float>(st.lse2_q);
+    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu);
+    const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
+    const T *rp = draft + (bk * L + i) * static_cast<long long>(V);
+    constexpr int PV = Elem<T>::kPerVec;
+    float acc = 0.0f;
+    if (VEC) {
+        const int nvec = V / PV;
+        for (int v = threadIdx.x; v < nvec; v += kStatThreads) {
+            float zq[PV], zp[PV];
+            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
+            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
+#pragma unroll
+            for (int j = 0; j < PV; ++j) {
+                const float eq = exp2_fast(fmaf(zq[j], c, -shift_q));
+                acc = fmaf(eq, powi_uniform(rc.one_minus_ratio(zp[j] - zq[j], c), K), acc);
+            }
+        }
+    } else {
+        for (int x = threadIdx.x; x < V; x += kStatThreads) {
+            const float zq = Elem<T>::scalar(rq + x), zp = Elem<T>::scalar(rp + x);
+            const float eq = exp2_fast(fmaf(zq, c, -shift_q));
+            acc = fmaf(eq, powi_uniform(rc.one_minus_ratio(zp - zq, c), K), acc);
+        }
+    }
+    const double total = block_sum(static_cast<double>(acc), sh_d);
+    if (threadIdx.x == 0)
+        s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q);
+}
+
+template <typename T>
+hipError_t launch_typed(const Problem &p)
+{
+    const T *target = static_cast<const T *>(p.target);
+    const T *draft = static_cast<const T *>(p.draft);
+    RowStat *stats = reinterpret_cast<RowStat *>(p.ws + p.lay.stats);
+    double *s = reinterpret_cast<double *>(p.ws + p.lay.s);
+    const long long pairs = static_cast<long long>(p.batch) * p.K * p.L;
+    const bool vec = (p.V % Elem<T>::kPerVec) == 0 &&
+                     (reinterpret_cast<uintptr_t>(p.target) % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(p.draft) % 16 == 0);
+    const dim3 g1(static_cast<unsigned>(pairs), 2);
+    if (vec)
+        hipLaunchKernelGGL((k_row_stats<T, true>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
+                           p.tokens, p.L, p.V, p.c, stats);
+    else
+        hipLaunchKernelGGL((k_row_stats<T, false>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
+                           p.tokens, p.L, p.V, p.c, stats);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.L < 2) return e;
+    const long long rows = static_cast<long long>(p.batch) * p.K * (p.L - 1);
+    const dim3 g2(static_cast<unsigned>(rows));
+    if (vec)
+        hipLaunchKernelGGL((k_ot_sum<T, true>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K,
+                           p.L, p.V, p.c, stats, s);
+    else
+        hipLaunchKernelGGL((k_ot_sum<T, false>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K,
+                           p.L, p.V, p.c, stats, s);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_split_main(const Problem &p)
+{
+    return p.dtype == 1 ? launch_typed<uint16_t>(p) : launch_typed<float>(p);
+}
+
+}  // namespace specgbv

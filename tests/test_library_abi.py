@@ -1,0 +1,84 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/specgbv.h
+declares, sizes its workspace sanely and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2604_25925_amd as sg
+from paper_2604_25925_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "specgbv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(specgbv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sg.load_library()
+    names = _declared_functions()
+    assert "specgbv_verify" in names and "specgbv_workspace_bytes" in names and len(names) >= 6
+    for n in names:
+        assert hasattr(lib, n), "libspecgbv.so does not export %s" % n
+    assert sorted(binding.EXPORTS) == names
+    assert "gfx950" in sg.specgbv_version()
+
+
+def test_binding_has_same_names_as_the_abi():
+    for n in _declared_functions():
+        assert hasattr(sg, n), "python binding lacks %s" % n
+
+
+def test_workspace_bytes():
+    small = sg.specgbv_workspace_bytes(1, 2, 4, 1000, 0)
+    big = sg.specgbv_workspace_bytes(128, 16, 8, 152064, 1)
+    assert 0 < small < big < 64 << 20
+    assert small % 256 == 0
+    assert sg.specgbv_workspace_bytes(1, 0, 4, 1000, 0) == 0
+    assert sg.specgbv_workspace_bytes(1, 2, 4, 1000, 7) == 0
+    assert sg.specgbv_workspace_bytes(1, 65, 4, 1000, 0) == 0       # beyond SPECGBV_MAX_K
+    assert sg.specgbv_workspace_bytes(0, 2, 4, 1000, 0) > 0
+
+
+def _call(lib, **kw):
+    a = dict(t=1 << 20, d=1 << 20, tok=1 << 20, K=2, L=3, V=64, B=1, dt=0, T=1.0, out=1 << 20, ws=1 << 20,
+             wsb=1 << 30)
+    a.update(kw)
+    return lib.specgbv_verify(a["t"], a["d"], a["tok"], a["K"], a["L"], a["V"], a["B"], a["dt"],
+                              ctypes.c_float(a["T"]), 0, 0, a["out"], a["out"], a["out"], a["ws"], a["wsb"], None)
+
+
+def test_argument_errors_are_caught_before_any_launch():
+    # the pointers below are never dereferenced: every call must fail in the host checks
+    lib = sg.load_library()
+    assert _call(lib, K=0) == 1 and "K" in sg.specgbv_last_error()
+    assert _call(lib, V=-5) == 1
+    assert _call(lib, B=-1) == 1
+    assert _call(lib, dt=3) == 1
+    assert _call(lib, T=0.0) == 1 and "temperature" in sg.specgbv_last_error()
+    assert _call(lib, T=float("inf")) == 1
+    assert _call(lib, t=None) == 1
+    assert _call(lib, out=None) == 1
+    assert _call(lib, t=(1 << 20) + 2) == 1                 # misaligned float pointer
+    assert _call(lib, K=65) == 2                            # over the limit: unsupported
+    assert _call(lib, L=63) == 2
+    assert _call(lib, K=64, L=32) == 2                      # K*L over 1024
+    assert _call(lib, ws=None) == 3
+    assert _call(lib, ws=(1 << 20) + 8) == 3                # misaligned workspace
+    assert _call(lib, wsb=128) == 3 and "need" in sg.specgbv_last_error()
+    assert _call(lib, B=0) == 0                             # empty batch: nothing to do
+
+
+def test_python_binding_validates_tensors():
+    import torch
+    t = torch.zeros((1, 2, 4, 64))
+    d = torch.zeros((1, 2, 3, 64))
+    tok = torch.zeros((1, 2, 3), dtype=torch.int32)
+    with pytest.raises(ValueError):
+        sg.specgbv_verify(t, d, tok, 1.0, 0, 0)             # CPU tensors: no silent fallback
+    with pytest.raises(ValueError):
+        sg.specgbv_verify(t, d[:, :, :2], tok, 1.0, 0, 0)
