@@ -56,6 +56,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--algo", default="auto", choices=["auto", "split", "chain"])
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     a = ap.parse_args()
@@ -67,7 +68,7 @@ def main() -> int:
     w = WORKLOADS[a.workload]
     # inputs are generated on the host before the GPU is touched (worker processes fork here)
     t0 = time.time()
-    target, draft, tokens = generate(a.workload, a.seed, workers=min(16, os.cpu_count() or 1))
+    target, draft, tokens = generate(a.workload, a.seed, workers=a.workers or min(16, os.cpu_count() or 1))
     gen_s = time.time() - t0
 
     import torch
