@@ -121,7 +121,7 @@ def _shapes(target_logits, draft_logits, draft_tokens):
 
 def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int,
                       rng_offset: int, *, workspace=None, out: Optional[Tuple] = None, algo="auto",
-                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None):
+                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None, _debug: int = 0):
     """Enqueue one verification on the current (or given) HIP stream.
 
     Returns (accepted_len [B], accepted_draft_idx [B], out_tokens [B, L+1], workspace), all
@@ -142,7 +142,7 @@ def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: fl
     acc_len, acc_idx, out_tokens = out
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
-    opt = _Options(_ALGO[algo] if isinstance(algo, str) else int(algo), 0,
+    opt = _Options(_ALGO[algo] if isinstance(algo, str) else int(algo), _debug,
                    events[0] if events else None, events[1] if events else None)
     st = lib.specgbv_verify_ex(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V,
                                B, dt, c_float(temperature), rng_seed, rng_offset, acc_len.data_ptr(),

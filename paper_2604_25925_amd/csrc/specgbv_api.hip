@@ -113,6 +113,7 @@ specgbv_status specgbv_verify_ex(
     p.K = K; p.L = L; p.V = V; p.batch = batch; p.dtype = dtype == SPECGBV_BF16 ? 1 : 0;
     p.c = static_cast<float>(1.4426950408889634074 / static_cast<double>(temperature));
     p.seed = rng_seed; p.offset = rng_offset;
+    p.debug = options ? options->reserved : 0;
     p.accepted_len = accepted_len; p.accepted_draft_idx = accepted_draft_idx; p.out_tokens = out_tokens;
     p.ws = static_cast<char *>(workspace);
     p.stream = static_cast<hipStream_t>(hip_stream);

@@ -195,7 +195,7 @@ __device__ __noinline__ void exact_row_stats(const T *row, int nvec, float c, fl
 template <typename T, int KP, int RS>
 __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
-        int K, int L, int V, float c, RowStat *__restrict__ stats, double *__restrict__ s_out)
+        int K, int L, int V, float c, RowStat *__restrict__ stats, double *__restrict__ s_out, int dbg)
 {
     __shared__ U4 lds_q[kLdsSlots][kChainThreads];
     __shared__ U4 lds_p[kLdsSlots][kChainThreads];
@@ -207,7 +207,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     const long long bk = blockIdx.x;                       // b*K + k
     const int nvec = V / PV;                               // host guarantees nvec >= RS * 512
     const int rem = nvec - static_cast<int>(tid);          // slot j holds a vector of this thread iff j*512 < rem
-    const int nslots = (nvec + kChainThreads - 1) / kChainThreads;
+    const int nslots = (dbg & 2) ? RS : (nvec + kChainThreads - 1) / kChainThreads;
     const T *trow0 = target + bk * (L + 1) * static_cast<long long>(V);
     const T *drow0 = draft + bk * L * static_cast<long long>(V);
 
@@ -265,7 +265,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         // ---- sweep 2 (rows 1..L-1; row 0 carries no Eq. (hik) sum) and loads of the next row.
         // After the last row the "next row" loads all read one 16-byte line of the current
         // row (lane offset 0) so that the register slots are written on every path.
-        const bool more = r + 1 < L;
+        const bool more = r + 1 < L && !(dbg & 1);
         const bool sum_row = r >= 1;
         const T *qnext = more ? qrow + V : qrow, *pnext = more ? prow + V : prow;
         const unsigned lane_next = more ? tid : 0u;
@@ -310,7 +310,7 @@ hipError_t launch_kp(const Problem &p)
     const int full_slots = (p.V / Elem<T>::kPerVec) / kChainThreads;
 #define SPECGBV_LAUNCH(RS)                                                                              \
     hipLaunchKernelGGL((k_chain<T, KP, RS>), grid, dim3(kChainThreads), 0, p.stream, target, draft,    \
-                       p.tokens, p.K, p.L, p.V, p.c, stats, s)
+                       p.tokens, p.K, p.L, p.V, p.c, stats, s, p.debug)
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);

@@ -41,6 +41,7 @@ struct Problem {
     int dtype;          // 0 = float32, 1 = bfloat16
     float c;            // log2(e) / temperature
     uint64_t seed, offset;
+    int debug;          // experiment switches (0 in production)
     int32_t *accepted_len;
     int32_t *accepted_draft_idx;
     int32_t *out_tokens;
