@@ -1,19 +1,23 @@
 // Decision scan of Algorithm 1 and the final-token draw.
 //
-//   k_decide      : one wave per prefix.  Builds nu_i, P_i, the acceptance table
+//   k_decide      : one workgroup per prefix.  Builds nu_i, P_i, the acceptance table
 //                   (Eq. (hik) for i < L, Eq. (hLk) for i = L, both divided through by
 //                   P_i so that no joint block probability is ever formed), draws the
-//                   Philox uniforms and runs the sequential loop with the set H of
-//                   rejected blocks.
-//   k_res_partial : per (prefix, vocabulary segment) partial sums of the weights the
-//                   final token is drawn from -- Eq. (pres) with q(x^tau) cancelled,
-//                   w[x] = q[x] max(1 - p[x]/(nu q[x]), 0)^K, or q[x] for the bonus token.
+//                   Philox uniforms, then its first wave runs the sequential loop with the
+//                   set H of rejected blocks.
+//   k_res_partial : one wave per (prefix, 512-entry vocabulary segment): partial sums of
+//                   the weights the final token is drawn from -- Eq. (pres) with q(x^tau)
+//                   cancelled, w[x] = q[x] max(1 - p[x]/(nu q[x]), 0)^K, or q[x] for the
+//                   bonus token.
 //   k_res_locate  : per prefix inverse-CDF search: the first token id whose running
-//                   weight exceeds u * total.
+//                   weight exceeds u * total (segment by a workgroup-wide scan of the
+//                   partial sums, entry by a wave scan inside that segment).
 #include "specgbv_internal.hpp"
 
 namespace specgbv {
 namespace {
+
+constexpr int kDecideThreads = 256;
 
 // ---------------------------------------------------------------- k_decide
 
@@ -39,8 +43,8 @@ __device__ double clamp01(double h)
     return h < 1.0 ? h : 1.0;
 }
 
-__global__ void __launch_bounds__(kWave)
-k_decide(const int32_t *__restrict__ tokens, int K, int L, int V, uint64_t seed, uint64_t offset,
+__global__ void __launch_bounds__(kDecideThreads)
+k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64_t offset,
          const RowStat *__restrict__ stats, const double *__restrict__ s_arr,
          double *__restrict__ log_nu_out, double *__restrict__ log_P_out, double *__restrict__ h_out,
          double *__restrict__ eta_out, int32_t *__restrict__ state_out, Selection *__restrict__ sel,
@@ -49,28 +53,35 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, int V, uint64_t seed,
 {
     extern __shared__ double lds[];
     const int KL = K * L;
-    double *h = lds;                                        // [K*L]
-    double *eta = lds + KL;                                 // [K*L]
+    double *h = lds;                                        // [K*L] acceptance probabilities
+    double *eta = lds + KL;                                 // [K*L] uniforms
     double *l2nu = lds + 2 * KL;                            // [K*L] log2 nu_i
-    int *tok = reinterpret_cast<int *>(lds + 3 * KL);       // [K*L]
+    double *tq = lds + 3 * KL;                              // [K*L] log2 q_r[token of row r]
+    double *tp = lds + 4 * KL;                              // [K*L] log2 p_r[token of row r]
+    int *tok = reinterpret_cast<int *>(lds + 5 * KL);       // [K*L]
     int *cpl = tok + KL;                                    // [K*K] common prefix lengths
-    const int b = blockIdx.x, lane = threadIdx.x;
+    const int b = blockIdx.x, tid = threadIdx.x;
     const long long base = static_cast<long long>(b) * KL;
     constexpr double kLn2 = 0.693147180559945309417;
 
-    for (int idx = lane; idx < KL; idx += kWave) {
+    for (int idx = tid; idx < KL; idx += kDecideThreads) {
+        const RowStat st = stats[base + idx];
+        tq[idx] = st.tok2_q - st.lse2_q;
+        tp[idx] = st.tok2_p - st.lse2_p;
+        tok[idx] = tokens[base + idx];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < KL; idx += kDecideThreads) {
         const int k = idx / L, i = idx % L + 1;
+        const double s = i < L ? s_arr[base + k * L + i] : 0.0;
         double log2nu = 0.0, log2P = 0.0;
         for (int j = 0; j < i; ++j) {
-            const RowStat st = stats[base + k * L + j];
-            const double lq = st.tok2_q - st.lse2_q, lp = st.tok2_p - st.lse2_p;
-            log2nu += lq - lp;
-            log2P += lp;
+            log2nu += tq[k * L + j] - tp[k * L + j];
+            log2P += tp[k * L + j];
         }
         const double log_nu = log2nu * kLn2, log_P = log2P * kLn2;
         double hv;
         if (i < L) {
-            const double s = s_arr[base + k * L + i];
             const double nu = exp(log_nu);
             const double num = nu * (s - g_K(log_nu, K));
             const double den = c_K(log_P, K) - nu * (1.0 - s);
@@ -80,24 +91,25 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, int V, uint64_t seed,
         }
         const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
         h[idx] = hv; eta[idx] = e; l2nu[idx] = log2nu;
-        tok[idx] = tokens[base + idx];
         log_nu_out[base + idx] = log_nu; log_P_out[base + idx] = log_P;
         h_out[base + idx] = hv; eta_out[base + idx] = e;
-        state_out[base + idx] = 0;
     }
-    __syncthreads();
-    for (int idx = lane; idx < K * K; idx += kWave) {
+    for (int idx = tid; idx < K * K; idx += kDecideThreads) {
         const int k1 = idx / K, k2 = idx % K;
         int n = 0;
         while (n < L && tok[k1 * L + n] == tok[k2 * L + n]) ++n;
         cpl[idx] = n;
     }
     __syncthreads();
+    if (tid >= kWave) return;
 
-    // Sequential loop of Algorithm 1, executed by the whole wave in lock step; lane j
-    // keeps the lengths at which draft j was tested and rejected (its entries of H).
+    // Sequential loop of Algorithm 1, executed by the first wave in lock step; lane j keeps
+    // the lengths at which draft j was tested and rejected (its entries of H), and the test
+    // states of draft j (2 bits per length: 1 tested, 2 skipped because the block is in H).
+    const int lane = tid;
     int tau = 0, f = -1;
     unsigned long long rejected = 0ull;
+    unsigned long long st_lo = 0ull, st_hi = 0ull;        // state bits of draft `lane`
     bool done = false;
     for (int k = 0; k < K && !done; ++k) {
         const int my_cpl = (lane < k) ? cpl[k * K + lane] : 0;
@@ -105,10 +117,10 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, int V, uint64_t seed,
             const bool hit = (lane < k) && ((rejected >> i) & 1ull) && (my_cpl >= i);
             const int idx = k * L + i - 1;
             if (__any(hit)) {                 // block already in H: no sampling
-                if (lane == 0) state_out[base + idx] = 2;
+                if (lane == k) st_hi |= 1ull << i;
                 continue;
             }
-            if (lane == 0) state_out[base + idx] = 1;
+            if (lane == k) st_lo |= 1ull << i;
             if (eta[idx] < h[idx]) {
                 tau = i; f = k;
                 if (i == L) { done = true; break; }
@@ -117,6 +129,10 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, int V, uint64_t seed,
             }
         }
     }
+    if (lane < K)
+        for (int i = 1; i <= L; ++i)
+            state_out[base + lane * L + i - 1] =
+                static_cast<int32_t>(((st_lo >> i) & 1ull) | (((st_hi >> i) & 1ull) << 1));
 
     const int kf = f < 0 ? 0 : f;
     if (lane == 0) {
@@ -138,13 +154,11 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, int V, uint64_t seed,
     }
     for (int j = lane; j <= L; j += kWave)
         out_tokens[static_cast<long long>(b) * (L + 1) + j] = j < tau ? tok[kf * L + j] : -1;
-    (void)V;
 }
 
 // ------------------------------------------------------------ final token
 
-// Weights of the 8 vocabulary entries [e0, e0+8) of the selected row(s); entries at or
-// beyond V get weight 0.  Returns the weights relative to 2^m2.
+// The 8 logits [e0, e0+8) of a row; entries at or beyond V read as -inf.
 template <typename T, bool VEC>
 __device__ __forceinline__ void load8(const T *row, long long e0, int V, float (&z)[8])
 {
@@ -163,11 +177,15 @@ __device__ __forceinline__ void load8(const T *row, long long e0, int V, float (
     }
 }
 
+// Weights of this lane's 8 entries of segment `seg` relative to 2^m2 (w: the weights the
+// token is drawn from; wq: plain target weights).  With m2 = NaN on entry for the bonus row
+// the segment's own maximum is used as reference and returned.
 template <typename T, bool VEC>
-__device__ __forceinline__ void segment_weights(const T *target, const T *draft, const Selection &sl, int V,
-                                                int K, float c, int seg, float m2, float (&w)[8], float (&wq)[8])
+__device__ __forceinline__ float segment_weights(const T *target, const T *draft, const Selection &sl, int V,
+                                                 int K, float c, int seg, int lane, float m2_in,
+                                                 float (&w)[8], float (&wq)[8])
 {
-    const long long e0 = static_cast<long long>(seg) * kSegElems + threadIdx.x * 8;
+    const long long e0 = static_cast<long long>(seg) * kSegElems + lane * 8;
     float zq[8];
     if (e0 < V) load8<T, VEC>(target + sl.target_row * V, e0, V, zq);
     else {
@@ -175,9 +193,16 @@ __device__ __forceinline__ void segment_weights(const T *target, const T *draft,
         for (int j = 0; j < 8; ++j) zq[j] = -INFINITY;
     }
     if (sl.draft_row < 0) {
+        float m2 = m2_in;
+        if (!(m2 == m2)) {                      // reference not fixed yet: this segment's maximum
+            float m = -3.0e38f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) m = fmaxf(m, zq[j]);
+            m2 = wave_max(m) * c;
+        }
 #pragma unroll
         for (int j = 0; j < 8; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -m2)); w[j] = wq[j]; }
-        return;
+        return m2;
     }
     float zp[8];
     if (e0 < V) load8<T, VEC>(draft + sl.draft_row * V, e0, V, zp);
@@ -185,6 +210,7 @@ __device__ __forceinline__ void segment_weights(const T *target, const T *draft,
 #pragma unroll
         for (int j = 0; j < 8; ++j) zp[j] = 0.0f;
     }
+    const float m2 = sl.shift_q;
     const RatioConst rc(sl.C2);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -194,25 +220,7 @@ __device__ __forceinline__ void segment_weights(const T *target, const T *draft,
         wq[j] = eq;
         w[j] = eq * powi_uniform(t, K);
     }
-}
-
-// Reference exponent of a segment: the fixed shift of the selected target row for a
-// residual draw, the segment's own maximum for the bonus row (whose statistics were
-// never computed).
-template <typename T, bool VEC>
-__device__ __forceinline__ float segment_reference(const T *target, const Selection &sl, int V, float c,
-                                                   int seg, float *sh_f)
-{
-    if (sl.draft_row >= 0) return sl.shift_q;
-    const long long e0 = static_cast<long long>(seg) * kSegElems + threadIdx.x * 8;
-    float zq[8];
-    float m = -INFINITY;
-    if (e0 < V) {
-        load8<T, VEC>(target + sl.target_row * V, e0, V, zq);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) m = fmaxf(m, zq[j]);
-    }
-    return block_max(m, sh_f) * c;
+    return m2;
 }
 
 template <typename T, bool VEC>
@@ -220,19 +228,18 @@ __global__ void __launch_bounds__(kSegThreads)
 k_res_partial(const T *__restrict__ target, const T *__restrict__ draft, const Selection *__restrict__ sel,
               int V, int K, float c, int nseg, SegPartial *__restrict__ partial)
 {
-    __shared__ double sh_d[kSegThreads / kWave];
-    __shared__ float sh_f[kSegThreads / kWave];
-    const int seg = blockIdx.x, b = blockIdx.y;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int seg = blockIdx.x * (kSegThreads / kWave) + threadIdx.x / kWave, b = blockIdx.y;
+    if (seg >= nseg) return;                    // whole wave; the kernel has no barrier
     const Selection sl = sel[b];
-    const float m2 = segment_reference<T, VEC>(target, sl, V, c, seg, sh_f);
     float w[8], wq[8];
-    segment_weights<T, VEC>(target, draft, sl, V, K, c, seg, m2, w, wq);
+    const float m2 = segment_weights<T, VEC>(target, draft, sl, V, K, c, seg, lane, __builtin_nanf(""), w, wq);
     double sw = 0.0, sq = 0.0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) { sw += static_cast<double>(w[j]); sq += static_cast<double>(wq[j]); }
-    sw = block_sum(sw, sh_d);
-    sq = block_sum(sq, sh_d);
-    if (threadIdx.x == 0) {
+    sw = wave_sum(sw);
+    sq = wave_sum(sq);
+    if (lane == 0) {
         SegPartial pt;
         pt.sum_w = sw; pt.sum_q = sq; pt.m2 = m2; pt.pad = 0.0f;
         partial[static_cast<long long>(b) * nseg + seg] = pt;
@@ -261,36 +268,53 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
     __shared__ double sh_d[kSegThreads / kWave];
     __shared__ double sh_scan[kSegThreads / kWave];
     __shared__ float sh_f[kSegThreads / kWave];
-    __shared__ int sh_seg;
+    __shared__ int sh_seg, sh_winner, sh_last_pos;
     __shared__ double sh_local_target, sh_total;
-    __shared__ int sh_use_q;
-    __shared__ int sh_winner;
     const int b = blockIdx.x, tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wid = tid / kWave;
     const Selection sl = sel[b];
     const SegPartial *pp = partial + static_cast<long long>(b) * nseg;
 
-    // common reference exponent and totals
-    float mloc = -INFINITY;
-    for (int s = tid; s < nseg; s += kSegThreads) mloc = fmaxf(mloc, pp[s].m2);
+    // thread t owns the contiguous segments [t*chunk, (t+1)*chunk)
+    const int chunk = (nseg + kSegThreads - 1) / kSegThreads;
+    const int s0 = tid * chunk, s1 = min(nseg, s0 + chunk);
+    float mloc = -3.0e38f;
+    for (int s = s0; s < s1; ++s) mloc = fmaxf(mloc, pp[s].m2);
     const float M = block_max(mloc, sh_f);
-    double tw = 0.0, tq = 0.0;
-    for (int s = tid; s < nseg; s += kSegThreads) {
+    double tw = 0.0, tqs = 0.0;
+    for (int s = s0; s < s1; ++s) {
         const double sc = exp2(static_cast<double>(pp[s].m2) - static_cast<double>(M));
-        tw += pp[s].sum_w * sc; tq += pp[s].sum_q * sc;
+        tw += pp[s].sum_w * sc; tqs += pp[s].sum_q * sc;
     }
-    tw = block_sum(tw, sh_d);
-    tq = block_sum(tq, sh_d);
-    const bool use_q = !(tw > 0.0);           // every residual weight is zero: draw from q
-    const double W = use_q ? tq : tw;
+    const double Ww = block_sum(tw, sh_d);
+    const double Wq = block_sum(tqs, sh_d);
+    const bool use_q = !(Ww > 0.0);           // every residual weight is zero: draw from q
+    const double W = use_q ? Wq : Ww;
     const double u = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(K * L));
     const double goal = u * W;
 
-    // first segment whose running total exceeds the goal (thread 0; nseg is small)
-    if (tid == 0) {
-        double cum = 0.0;
-        int found = -1, last_pos = 0;
-        double cum_before = 0.0, cum_before_last = 0.0;
-        for (int s = 0; s < nseg; ++s) {
+    // first thread, then first segment, whose running total exceeds the goal
+    const double mine_seg = use_q ? tqs : tw;
+    if (tid == 0) { sh_winner = kSegThreads; sh_last_pos = -1; }
+    const double incl_t = wave_inclusive_scan(mine_seg);
+    if (lane == kWave - 1) sh_scan[wid] = incl_t;
+    __syncthreads();
+    double wave_off = 0.0;
+    for (int wv = 0; wv < wid; ++wv) wave_off += sh_scan[wv];
+    const double excl_t = wave_off + incl_t - mine_seg;
+    if (mine_seg > 0.0) {
+        atomicMax(&sh_last_pos, tid);
+        if (excl_t + mine_seg > goal) atomicMin(&sh_winner, tid);
+    }
+    __syncthreads();
+    int win_t = sh_winner;
+    if (win_t == kSegThreads) win_t = sh_last_pos < 0 ? 0 : sh_last_pos;   // rounding pushed the goal past the end
+    __syncthreads();
+    if (tid == win_t) {
+        double cum = excl_t, cum_before = excl_t;
+        int found = -1, last_pos = s0 < nseg ? s0 : 0;
+        double cum_before_last = excl_t;
+        for (int s = s0; s < s1; ++s) {
             const double sc = exp2(static_cast<double>(pp[s].m2) - static_cast<double>(M));
             const double v = (use_q ? pp[s].sum_q : pp[s].sum_w) * sc;
             if (v > 0.0) { last_pos = s; cum_before_last = cum; }
@@ -298,19 +322,19 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
             cum += v;
         }
         if (found < 0) { found = last_pos; cum_before = cum_before_last; }
+        const double rescale = exp2(static_cast<double>(M) - static_cast<double>(pp[found].m2));
         sh_seg = found;
-        // goal expressed in the segment's own scale
-        sh_local_target = (goal - cum_before) * exp2(static_cast<double>(M) - static_cast<double>(pp[found].m2));
-        sh_total = W * exp2(static_cast<double>(M) - static_cast<double>(pp[found].m2));
-        sh_use_q = use_q ? 1 : 0;
-        sh_winner = kSegThreads;
+        sh_local_target = (goal - cum_before) * rescale;   // goal in the segment's own scale
+        sh_total = W * rescale;
     }
     __syncthreads();
+    if (wid != 0) return;
+
+    // inside the segment: one wave, lane order = token-id order
     const int seg = sh_seg;
     const double local_target = sh_local_target;
-    const float m2 = pp[seg].m2;
     float w[8], wq[8];
-    segment_weights<T, VEC>(target, draft, sl, V, K, c, seg, m2, w, wq);
+    segment_weights<T, VEC>(target, draft, sl, V, K, c, seg, lane, pp[seg].m2, w, wq);
     double ws[8];
     double mine = 0.0;
 #pragma unroll
@@ -318,27 +342,16 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
         ws[j] = static_cast<double>(use_q ? wq[j] : w[j]);
         mine += ws[j];
     }
-    // exclusive scan of the per-thread sums in thread (= token id) order
-    const int lane = tid & (kWave - 1), wid = tid / kWave;
     const double incl = wave_inclusive_scan(mine);
-    if (lane == kWave - 1) sh_scan[wid] = incl;
-    __syncthreads();
-    double wave_off = 0.0;
-    for (int wv = 0; wv < wid; ++wv) wave_off += sh_scan[wv];
-    const double excl = wave_off + incl - mine;
-    const bool crosses = mine > 0.0 && excl + mine > local_target;
-    if (crosses) atomicMin(&sh_winner, tid);
-    // fallback for a goal that rounding pushed past the segment: last positive thread
-    __shared__ int sh_last_pos;
-    if (tid == 0) sh_last_pos = -1;
-    __syncthreads();
-    if (mine > 0.0) atomicMax(&sh_last_pos, tid);
-    __syncthreads();
-    int winner = sh_winner;
-    const bool past_end = winner == kSegThreads;
-    if (past_end) winner = sh_last_pos < 0 ? 0 : sh_last_pos;
-    if (tid == winner) {
-        const long long e0 = static_cast<long long>(seg) * kSegElems + tid * 8;
+    const double excl = incl - mine;
+    const unsigned long long cross = __ballot(mine > 0.0 && incl > local_target);
+    const unsigned long long pos = __ballot(mine > 0.0);
+    int winner;
+    if (cross) winner = __ffsll(static_cast<long long>(cross)) - 1;
+    else if (pos) winner = 63 - __clzll(static_cast<long long>(pos));
+    else winner = 0;
+    if (lane == winner) {
+        const long long e0 = static_cast<long long>(seg) * kSegElems + lane * 8;
         double run = excl;
         int y = -1;
         double mg = 0.0;
@@ -360,7 +373,7 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
         out_tokens[static_cast<long long>(b) * (L + 1) + sl.tau] = static_cast<int32_t>(tokid);
         margin_out[b] = mg;
         u_final[b] = u;
-        fallback_out[b] = sh_use_q;
+        fallback_out[b] = use_q ? 1 : 0;
         // total weight in probability units: weights are relative to 2^M, the target row's
         // normaliser is 2^lse2_q (bonus row: the total is the normaliser itself)
         res_norm[b] = sl.draft_row < 0 ? 1.0 : W * exp2(static_cast<double>(M) - sl.lse2_q);
@@ -377,7 +390,8 @@ hipError_t launch_sample_typed(const Problem &p)
     const bool vec = (p.V % Elem<T>::kPerVec) == 0 &&
                      (reinterpret_cast<uintptr_t>(p.target) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(p.draft) % 16 == 0);
-    const dim3 g(static_cast<unsigned>(p.lay.nseg), static_cast<unsigned>(p.batch));
+    constexpr int kSegPerBlock = kSegThreads / kWave;
+    const dim3 g(static_cast<unsigned>((p.lay.nseg + kSegPerBlock - 1) / kSegPerBlock), static_cast<unsigned>(p.batch));
     double *res_norm = reinterpret_cast<double *>(p.ws + p.lay.res_norm);
     double *u_final = reinterpret_cast<double *>(p.ws + p.lay.u_final);
     double *margin = reinterpret_cast<double *>(p.ws + p.lay.margin);
@@ -403,8 +417,8 @@ hipError_t launch_sample_typed(const Problem &p)
 hipError_t launch_decide_and_sample(const Problem &p)
 {
     const int KL = p.K * p.L;
-    const size_t lds = sizeof(double) * 3 * KL + sizeof(int) * (KL + p.K * p.K);
-    hipLaunchKernelGGL(k_decide, dim3(p.batch), dim3(kWave), lds, p.stream, p.tokens, p.K, p.L, p.V, p.seed,
+    const size_t lds = sizeof(double) * 5 * KL + sizeof(int) * (KL + p.K * p.K);
+    hipLaunchKernelGGL(k_decide, dim3(p.batch), dim3(kDecideThreads), lds, p.stream, p.tokens, p.K, p.L, p.seed,
                        p.offset, reinterpret_cast<const RowStat *>(p.ws + p.lay.stats),
                        reinterpret_cast<const double *>(p.ws + p.lay.s),
                        reinterpret_cast<double *>(p.ws + p.lay.log_nu),

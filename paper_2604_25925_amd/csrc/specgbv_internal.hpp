@@ -28,8 +28,8 @@ struct Workspace {
     int nseg;
 };
 
-constexpr int kSegThreads = 256;
-constexpr int kSegElems = kSegThreads * 8;     // vocabulary entries per residual segment
+constexpr int kSegThreads = 256;               // final-token kernels: 4 waves per workgroup
+constexpr int kSegElems = kWave * 8;           // vocabulary entries per residual segment (one wave)
 
 Workspace make_workspace(int batch, int K, int L, int V);
 
