@@ -65,6 +65,9 @@ __device__ __forceinline__ void pow_inplace(float (&t)[N], int K)
     }
 }
 
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void glb_cvoid;
+
 struct RowConsts {
     float c;
     float nref_q, nref_p;    // minus the reference exponents
@@ -211,6 +214,10 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     const T *trow0 = target + bk * (L + 1) * static_cast<long long>(V);
     const T *drow0 = draft + bk * L * static_cast<long long>(V);
 
+    if (dbg & 4) {                                         // experiment: de-phase neighbouring workgroups
+        const int naps = (blockIdx.x & 3) * ((dbg >> 4) & 15);
+        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
+    }
     U4 rq[RS], rp[RS];
 #pragma unroll
     for (int j = 0; j < RS; ++j) {
@@ -231,14 +238,39 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         rc.nref_q = -(mq * c); rc.nref_p = -(mp * c);
 
         // ---- sweep 1
+        // The LDS slots of this row are filled by asynchronous global->LDS loads (no VGPRs,
+        // one 16-byte element per lane, written to consecutive LDS addresses of the wave)
+        // while the register slots are being processed.
+        const int lds_end = nslots < RS + kLdsSlots ? nslots : RS + kLdsSlots;
+        if (!(dbg & 32)) {
+            for (int j = RS; j < lds_end; ++j) {
+                if (j * kChainThreads < rem) {
+                    const unsigned wbase = tid & ~(kWave - 1u);
+                    __builtin_amdgcn_global_load_lds(
+                        (glb_cvoid *)(reinterpret_cast<const U4 *>(qrow) + static_cast<size_t>(j) * kChainThreads + tid),
+                        (lds_void *)&lds_q[j - RS][wbase], 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds(
+                        (glb_cvoid *)(reinterpret_cast<const U4 *>(prow) + static_cast<size_t>(j) * kChainThreads + tid),
+                        (lds_void *)&lds_p[j - RS][wbase], 16, 0, 0);
+                }
+            }
+        }
         float Zq = 0.0f, Zp = 0.0f;
 #pragma unroll
-        for (int j = 0; j < RS; ++j) sweep1_vec<T>(rq[j], rp[j], rc, Zq, Zp);
+        for (int j = 0; j < RS; ++j) {
+            if (dbg & 8) { Zq += __uint_as_float((rq[j].x ^ rq[j].y ^ rq[j].z ^ rq[j].w) & 0x3fffffffu); Zp += __uint_as_float((rp[j].x ^ rp[j].w) & 0x3fffffffu); }
+            else sweep1_vec<T>(rq[j], rp[j], rc, Zq, Zp);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the LDS fills have landed
         for (int j = RS; j < nslots; ++j) {
             if (j * kChainThreads < rem) {
-                const U4 q = load_slot(qrow, j, tid), p = load_slot(prow, j, tid);
+                U4 q, p;
+                if (j < lds_end && !(dbg & 32)) { q = lds_q[j - RS][tid]; p = lds_p[j - RS][tid]; }
+                else {
+                    q = load_slot(qrow, j, tid); p = load_slot(prow, j, tid);
+                    if (j < lds_end) { lds_q[j - RS][tid] = q; lds_p[j - RS][tid] = p; }
+                }
                 sweep1_vec<T>(q, p, rc, Zq, Zp);
-                if (j < RS + kLdsSlots) { lds_q[j - RS][tid] = q; lds_p[j - RS][tid] = p; }
             }
         }
         double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp);
@@ -276,7 +308,8 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         float acc = 0.0f;
 #pragma unroll
         for (int j = 0; j < RS; ++j) {
-            if (sum_row) sweep2_vec<T, KP>(rq[j], rp[j], rc, acc);
+            if (dbg & 8) acc += __uint_as_float((rq[j].y ^ rp[j].z) & 0x3fffffffu);
+            else if (sum_row) sweep2_vec<T, KP>(rq[j], rp[j], rc, acc);
             unsigned lane = lane_next;
             asm volatile("" : "+v"(lane) : "v"(acc));       // keep the loads behind this slot's arithmetic
             rq[j] = load_slot(qnext, j, lane);
