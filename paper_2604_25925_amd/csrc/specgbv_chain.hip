@@ -22,6 +22,8 @@
 // first vector (a 4096-entry sample) instead of the exact row maxima; should a row
 // overflow float32 with that reference (possible only for extremely peaked rows), its
 // statistics are recomputed from memory with the exact maximum.
+#include <utility>
+
 #include "specgbv_internal.hpp"
 
 namespace specgbv {
@@ -65,8 +67,21 @@ __device__ __forceinline__ void pow_inplace(float (&t)[N], int K)
     }
 }
 
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void glb_cvoid;
+// Asynchronous 16-byte-per-lane load from global memory straight into LDS: lane l of the
+// wave writes LDS bytes [dst + 16 l, dst + 16 l + 16), dst wave-uniform.  Completion is
+// tracked by vmcnt only.  Issued as inline assembly: the compiler otherwise treats the
+// instruction as a flat access that may touch LDS and from then on turns every vector-memory
+// wait into vmcnt(0), which would drain the load pipeline at each use of a loaded register.
+// (Its own vmcnt arithmetic does not see these loads, so its waits are conservative.)
+__device__ __forceinline__ void lds_fill16(const void *src, const void *lds_dst_wave_uniform)
+{
+    const unsigned m0 = __builtin_amdgcn_readfirstlane(
+        static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds_dst_wave_uniform)));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(m0)
+                 : "memory", "m0");
+}
 
 struct RowConsts {
     float c;
@@ -96,13 +111,8 @@ __device__ __forceinline__ void sweep2_vec(const U4 &q, const U4 &p, const RowCo
 {
     constexpr int PV = Elem<T>::kPerVec;
     float zq[PV], zp[PV], t[PV];
-    // Opaque copies: without them the compiler keeps the floats that sweep 1 unpacked from
-    // these registers alive until here, which doubles the footprint of bf16 rows.
-    U4 qq = q, pp = p;
-    asm volatile("" : "+v"(qq.x), "+v"(qq.y), "+v"(qq.z), "+v"(qq.w));
-    asm volatile("" : "+v"(pp.x), "+v"(pp.y), "+v"(pp.z), "+v"(pp.w));
-    Elem<T>::unpack(qq, zq);
-    Elem<T>::unpack(pp, zp);
+    Elem<T>::unpack(q, zq);
+    Elem<T>::unpack(p, zp);
 #pragma unroll
     for (int j = 0; j < PV; ++j) {
         const float r = exp2_fast(fmaf(zp[j] - zq[j], rc.c, -rc.C2_hi));
@@ -149,6 +159,20 @@ __device__ __forceinline__ void block_sum2(double &a, double &b, double *scratch
     a = ra; b = rb;
 }
 
+// Three workgroup-wide double sums with one pair of barriers.
+__device__ __forceinline__ void block_sum3(double &a, double &b, double &d, double *scratch)
+{
+    const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+    a = wave_sum(a); b = wave_sum(b); d = wave_sum(d);
+    __syncthreads();
+    if (lane == 0) { scratch[3 * wid] = a; scratch[3 * wid + 1] = b; scratch[3 * wid + 2] = d; }
+    __syncthreads();
+    double ra = 0.0, rb = 0.0, rd = 0.0;
+#pragma unroll
+    for (int w = 0; w < kChainWaves; ++w) { ra += scratch[3 * w]; rb += scratch[3 * w + 1]; rd += scratch[3 * w + 2]; }
+    a = ra; b = rb; d = rd;
+}
+
 __device__ __forceinline__ void block_max2(float &a, float &b, float *scratch)
 {
     const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
@@ -174,8 +198,9 @@ __device__ __forceinline__ double log2_cheap(double z)
 // Exact-maximum statistics of one row straight from memory (overflow fallback).
 template <typename T>
 __device__ __noinline__ void exact_row_stats(const T *row, int nvec, float c, float &ref_out, double &Z_out,
-                                             float *sh_f, double *sh_d)
+                                             double *sh_d)
 {
+    float *sh_f = reinterpret_cast<float *>(sh_d);
     constexpr int PV = Elem<T>::kPerVec;
     float m = -3.0e38f;
     for (int v = threadIdx.x; v < nvec; v += kChainThreads)
@@ -195,141 +220,176 @@ __device__ __noinline__ void exact_row_stats(const T *row, int nvec, float c, fl
     ref_out = ref; Z_out = a;
 }
 
+constexpr int kLag = 6;    // slots between the load of a vector and its first use
+
+static_assert(kLdsSlots == 9, "one named LDS object per slot");
+struct LdsSlots {
+    U4 (*slot[kLdsSlots])[kChainThreads];                   // slot[s][0] = target vectors, slot[s][1] = draft vectors
+};
+
+template <typename T>
+struct StepCtx {
+    const T *qnew, *pnew;
+    const RowConsts &rc_sum, &rc_new;
+    unsigned tid, lane_new, wbase;
+    int nvec, rem, n_on;
+    bool do_new, do_sum;
+};
+
+// Step J of the slot pipeline (all indices are compile-time constants so that the slot
+// arrays stay in registers): sweep 2 of the old row on slot J, the load of the new row into
+// slot J, and sweep 1 of the new row on slot J - kLag.  Register slots are waited for by the
+// compiler; LDS slots were filled by asynchronous global->LDS loads, so a manual wait
+// precedes their first read: inside the pipeline exactly 2 * kLag vector-memory operations
+// were issued after the fill of slot J - kLag, and none may be pending once it drains.
+template <typename T, int KP, int RS, int J>
+__device__ __forceinline__ void pipeline_step(const StepCtx<T> &cx, U4 (&rq)[RS], U4 (&rp)[RS],
+                                              const LdsSlots &lds, float &Zq, float &Zp, float &acc)
+{
+    constexpr int NS = RS + kLdsSlots;
+    if constexpr (J < RS) {
+        // Opaque touch of the slot: without it the compiler keeps the floats that sweep 1
+        // unpacked from these registers alive until sweep 2, which doubles the footprint of
+        // bf16 rows.
+        asm volatile("" : "+v"(rq[J].x), "+v"(rq[J].y), "+v"(rq[J].z), "+v"(rq[J].w));
+        asm volatile("" : "+v"(rp[J].x), "+v"(rp[J].y), "+v"(rp[J].z), "+v"(rp[J].w));
+        if (cx.do_sum) sweep2_vec<T, KP>(rq[J], rp[J], cx.rc_sum, acc);
+        unsigned lane = cx.lane_new;
+        asm volatile("" : "+v"(lane) : "v"(acc));           // keep the loads behind this slot's arithmetic
+        rq[J] = load_slot(cx.qnew, J, lane);
+        rp[J] = load_slot(cx.pnew, J, lane);
+    } else if constexpr (J < NS) {
+        if (J < cx.n_on) {
+            if (cx.do_sum && J * kChainThreads < cx.rem)
+                sweep2_vec<T, KP>(lds.slot[J - RS][0][cx.tid], lds.slot[J - RS][1][cx.tid], cx.rc_sum, acc);
+            if (cx.do_new) {
+                // every lane loads (lanes past the row end re-read its last vector) so that
+                // all waves issue the same number of vector-memory operations
+                int v = J * kChainThreads + static_cast<int>(cx.tid);
+                v = v < cx.nvec ? v : cx.nvec - 1;
+                asm volatile("" : "+v"(v) : "v"(acc));
+                lds_fill16(reinterpret_cast<const U4 *>(cx.qnew) + v, &lds.slot[J - RS][0][cx.wbase]);
+                lds_fill16(reinterpret_cast<const U4 *>(cx.pnew) + v, &lds.slot[J - RS][1][cx.wbase]);
+            }
+        }
+    }
+    constexpr int JJ = J - kLag;                            // lagged sweep 1 of the new row
+    if constexpr (JJ >= 0 && JJ < RS) {
+        if (cx.do_new) sweep1_vec<T>(rq[JJ], rp[JJ], cx.rc_new, Zq, Zp);
+    } else if constexpr (JJ >= RS && JJ < NS) {
+        if (cx.do_new && JJ < cx.n_on) {
+            if (J < cx.n_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLag) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (JJ * kChainThreads < cx.rem)
+                sweep1_vec<T>(lds.slot[JJ - RS][0][cx.tid], lds.slot[JJ - RS][1][cx.tid], cx.rc_new, Zq, Zp);
+        }
+    }
+}
+
+template <typename T, int KP, int RS, int... Js>
+__device__ __forceinline__ void run_steps(std::integer_sequence<int, Js...>, const StepCtx<T> &cx, U4 (&rq)[RS],
+                                          U4 (&rp)[RS], const LdsSlots &lds, float &Zq, float &Zp, float &acc)
+{
+    (pipeline_step<T, KP, RS, Js>(cx, rq, rp, lds, Zq, Zp, acc), ...);
+}
+
 template <typename T, int KP, int RS>
 __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
         int K, int L, int V, float c, RowStat *__restrict__ stats, double *__restrict__ s_out, int dbg)
 {
-    __shared__ U4 lds_q[kLdsSlots][kChainThreads];
-    __shared__ U4 lds_p[kLdsSlots][kChainThreads];
-    __shared__ double sh_d[2 * kChainWaves];
-    __shared__ float sh_f[2 * kChainWaves];
+    // One LDS object per slot: the compiler tracks asynchronous LDS fills per object, so reads
+    // of one slot do not wait for the fills of the others.
+    __shared__ U4 lds0[2][kChainThreads], lds1[2][kChainThreads], lds2[2][kChainThreads], lds3[2][kChainThreads],
+        lds4[2][kChainThreads], lds5[2][kChainThreads], lds6[2][kChainThreads], lds7[2][kChainThreads],
+        lds8[2][kChainThreads];
+    __shared__ double sh_d[3 * kChainWaves];
+    const LdsSlots lds{{lds0, lds1, lds2, lds3, lds4, lds5, lds6, lds7, lds8}};
 
     constexpr int PV = Elem<T>::kPerVec;
+    constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
     const unsigned tid = threadIdx.x;
+    const unsigned wbase = tid & ~(kWave - 1u);
     const long long bk = blockIdx.x;                       // b*K + k
     const int nvec = V / PV;                               // host guarantees nvec >= RS * 512
     const int rem = nvec - static_cast<int>(tid);          // slot j holds a vector of this thread iff j*512 < rem
-    const int nslots = (dbg & 2) ? RS : (nvec + kChainThreads - 1) / kChainThreads;
+    const int nslots = (nvec + kChainThreads - 1) / kChainThreads;
+    const int n_on = nslots < NS ? nslots : NS;            // on-chip slots in use
     const T *trow0 = target + bk * (L + 1) * static_cast<long long>(V);
     const T *drow0 = draft + bk * L * static_cast<long long>(V);
 
-    if (dbg & 4) {                                         // experiment: de-phase neighbouring workgroups
-        const int naps = (blockIdx.x & 3) * ((dbg >> 4) & 15);
-        for (int i = 0; i < naps; ++i) __builtin_amdgcn_s_sleep(127);
-    }
     U4 rq[RS], rp[RS];
 #pragma unroll
-    for (int j = 0; j < RS; ++j) {
-        rq[j] = load_slot(trow0, j, tid);
-        rp[j] = load_slot(drow0, j, tid);
-    }
+    for (int j = 0; j < RS; ++j) { rq[j] = U4{0, 0, 0, 0}; rp[j] = U4{0, 0, 0, 0}; }
 
-    double log2nu = 0.0;                                   // block ratio of the rows before row r
-    for (int r = 0; r < L; ++r) {
-        const T *qrow = trow0 + static_cast<long long>(r) * V;
-        const T *prow = drow0 + static_cast<long long>(r) * V;
+    RowConsts rc_sum;                                      // constants of the row in sweep 2
+    rc_sum.c = c; rc_sum.K = K; rc_sum.nref_q = rc_sum.nref_p = 0.0f; rc_sum.C2_hi = 0.0f; rc_sum.neg_kappa = -1.0f;
+    double Zq_prev = 1.0;                                  // target normaliser of the row in sweep 2
+    double log2nu = 0.0;                                   // block ratio of the rows before the row being loaded
 
-        // reference exponents from the first vector of every thread
-        float mq = vec_max<T>(rq[0]), mp = vec_max<T>(rp[0]);
-        block_max2(mq, mp, sh_f);
-        RowConsts rc;
-        rc.c = c; rc.K = K;
-        rc.nref_q = -(mq * c); rc.nref_p = -(mp * c);
+    // Iteration `it` overlaps three things slot by slot: sweep 2 of row it-1 (its Eq. (hik)
+    // sum, rows >= 1), the load of row it into the slot that sweep 2 just released, and
+    // sweep 1 of row it on the slot loaded kLag steps earlier.  Loads are therefore issued
+    // evenly over the whole row period and the memory pipeline never drains between rows.
+    for (int it = 0; it <= L; ++it) {
+        const bool do_new = it < L;                        // a row is being loaded and gets its statistics
+        const bool do_sum = it >= 2;                       // row it-1 >= 1 gets its Eq. (hik) sum
+        const int r_new = do_new ? it : L - 1;             // keeps every address in bounds
+        const T *qnew = trow0 + static_cast<long long>(r_new) * V;
+        const T *pnew = drow0 + static_cast<long long>(r_new) * V;
+        const T *qold = trow0 + static_cast<long long>(it >= 1 ? it - 1 : 0) * V;
+        const T *pold = drow0 + static_cast<long long>(it >= 1 ? it - 1 : 0) * V;
+        const unsigned lane_new = do_new ? tid : 0u;       // after the last row: one harmless line
 
-        // ---- sweep 1
-        // The LDS slots of this row are filled by asynchronous global->LDS loads (no VGPRs,
-        // one 16-byte element per lane, written to consecutive LDS addresses of the wave)
-        // while the register slots are being processed.
-        const int lds_end = nslots < RS + kLdsSlots ? nslots : RS + kLdsSlots;
-        if (!(dbg & 32)) {
-            for (int j = RS; j < lds_end; ++j) {
-                if (j * kChainThreads < rem) {
-                    const unsigned wbase = tid & ~(kWave - 1u);
-                    __builtin_amdgcn_global_load_lds(
-                        (glb_cvoid *)(reinterpret_cast<const U4 *>(qrow) + static_cast<size_t>(j) * kChainThreads + tid),
-                        (lds_void *)&lds_q[j - RS][wbase], 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds(
-                        (glb_cvoid *)(reinterpret_cast<const U4 *>(prow) + static_cast<size_t>(j) * kChainThreads + tid),
-                        (lds_void *)&lds_p[j - RS][wbase], 16, 0, 0);
-                }
-            }
-        }
-        float Zq = 0.0f, Zp = 0.0f;
-#pragma unroll
-        for (int j = 0; j < RS; ++j) {
-            if (dbg & 8) { Zq += __uint_as_float((rq[j].x ^ rq[j].y ^ rq[j].z ^ rq[j].w) & 0x3fffffffu); Zp += __uint_as_float((rp[j].x ^ rp[j].w) & 0x3fffffffu); }
-            else sweep1_vec<T>(rq[j], rp[j], rc, Zq, Zp);
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the LDS fills have landed
-        for (int j = RS; j < nslots; ++j) {
-            if (j * kChainThreads < rem) {
-                U4 q, p;
-                if (j < lds_end && !(dbg & 32)) { q = lds_q[j - RS][tid]; p = lds_p[j - RS][tid]; }
-                else {
-                    q = load_slot(qrow, j, tid); p = load_slot(prow, j, tid);
-                    if (j < lds_end) { lds_q[j - RS][tid] = q; lds_p[j - RS][tid] = p; }
-                }
-                sweep1_vec<T>(q, p, rc, Zq, Zp);
-            }
-        }
-        double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp);
-        block_sum2(Zq_tot, Zp_tot, sh_d);
-        float ref_q = -rc.nref_q, ref_p = -rc.nref_p;
-        if (!(Zq_tot < 1.0e37) || !(Zq_tot > 0.0)) {       // float32 overflow with the sample reference
-            exact_row_stats<T>(qrow, nvec, c, ref_q, Zq_tot, sh_f, sh_d);
-            rc.nref_q = -ref_q;                            // sweep 2 reuses the target reference
-        }
-        if (!(Zp_tot < 1.0e37) || !(Zp_tot > 0.0)) exact_row_stats<T>(prow, nvec, c, ref_p, Zp_tot, sh_f, sh_d);
-
-        const double lse2_q = static_cast<double>(ref_q) + log2_cheap(Zq_tot);
-        const double lse2_p = static_cast<double>(ref_p) + log2_cheap(Zp_tot);
-        int tok = tokens[bk * L + r];
+        // Reference exponents of the new row: its token's logits (the drafted token was
+        // sampled from this draft row, so no entry can exceed it by a factor near 2^127
+        // unless the row is extremely peaked; that case is caught below).
+        int tok = tokens[bk * L + r_new];
         tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-        const double tok2_q = static_cast<double>(Elem<T>::scalar(qrow + tok)) * static_cast<double>(c);
-        const double tok2_p = static_cast<double>(Elem<T>::scalar(prow + tok)) * static_cast<double>(c);
-        if (tid == 0) {
-            RowStat st;
-            st.lse2_q = lse2_q; st.lse2_p = lse2_p; st.tok2_q = tok2_q; st.tok2_p = tok2_p;
-            stats[bk * L + r] = st;
+        const float zq_tok = Elem<T>::scalar(qnew + tok), zp_tok = Elem<T>::scalar(pnew + tok);
+        RowConsts rc_new;
+        rc_new.c = c; rc_new.K = K; rc_new.C2_hi = 0.0f; rc_new.neg_kappa = -1.0f;
+        rc_new.nref_q = -(zq_tok * c); rc_new.nref_p = -(zp_tok * c);
+
+        float Zq = 0.0f, Zp = 0.0f, acc = 0.0f;
+        StepCtx<T> cx{qnew, pnew, rc_sum, rc_new, tid, lane_new, wbase, nvec, rem, n_on, do_new, do_sum};
+        run_steps<T, KP, RS>(std::make_integer_sequence<int, NS + kLag>{}, cx, rq, rp, lds, Zq, Zp, acc);
+        // vectors that do not fit on chip: read for the statistics now, once more for the sum
+        for (int j = NS; j < nslots; ++j) {
+            if (j * kChainThreads < rem) {
+                if (do_new) sweep1_vec<T>(load_slot(qnew, j, tid), load_slot(pnew, j, tid), rc_new, Zq, Zp);
+                if (do_sum) sweep2_vec<T, KP>(load_slot(qold, j, tid), load_slot(pold, j, tid), rc_sum, acc);
+            }
         }
 
-        // ---- sweep 2 (rows 1..L-1; row 0 carries no Eq. (hik) sum) and loads of the next row.
-        // After the last row the "next row" loads all read one 16-byte line of the current
-        // row (lane offset 0) so that the register slots are written on every path.
-        const bool more = r + 1 < L && !(dbg & 1);
-        const bool sum_row = r >= 1;
-        const T *qnext = more ? qrow + V : qrow, *pnext = more ? prow + V : prow;
-        const unsigned lane_next = more ? tid : 0u;
-        const double C2 = lse2_p - lse2_q + log2nu;
-        rc.C2_hi = static_cast<float>(C2);
-        const double dk = (static_cast<double>(rc.C2_hi) - C2) * 0.693147180559945309417;
-        rc.neg_kappa = (dk > -0.25 && dk < 0.25) ? -static_cast<float>(1.0 + dk + 0.5 * dk * dk) : -1.0f;
-        float acc = 0.0f;
-#pragma unroll
-        for (int j = 0; j < RS; ++j) {
-            if (dbg & 8) acc += __uint_as_float((rq[j].y ^ rp[j].z) & 0x3fffffffu);
-            else if (sum_row) sweep2_vec<T, KP>(rq[j], rp[j], rc, acc);
-            unsigned lane = lane_next;
-            asm volatile("" : "+v"(lane) : "v"(acc));       // keep the loads behind this slot's arithmetic
-            rq[j] = load_slot(qnext, j, lane);
-            rp[j] = load_slot(pnext, j, lane);
-        }
-        if (sum_row) {
-            for (int j = RS; j < nslots; ++j) {
-                if (j * kChainThreads < rem) {
-                    U4 q, p;
-                    if (j < RS + kLdsSlots) { q = lds_q[j - RS][tid]; p = lds_p[j - RS][tid]; }
-                    else { q = load_slot(qrow, j, tid); p = load_slot(prow, j, tid); }
-                    sweep2_vec<T, KP>(q, p, rc, acc);
-                }
+        double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp), s_tot = static_cast<double>(acc);
+        block_sum3(Zq_tot, Zp_tot, s_tot, sh_d);
+        if (do_sum && tid == 0) s_out[bk * L + it - 1] = s_tot / Zq_prev;
+        if (do_new) {
+            float ref_q = -rc_new.nref_q, ref_p = -rc_new.nref_p;
+            if (!(Zq_tot < 1.0e37) || !(Zq_tot > 0.0))     // float32 overflow with the token reference
+                exact_row_stats<T>(qnew, nvec, c, ref_q, Zq_tot, sh_d);
+            if (!(Zp_tot < 1.0e37) || !(Zp_tot > 0.0)) exact_row_stats<T>(pnew, nvec, c, ref_p, Zp_tot, sh_d);
+            const double lse2_q = static_cast<double>(ref_q) + log2_cheap(Zq_tot);
+            const double lse2_p = static_cast<double>(ref_p) + log2_cheap(Zp_tot);
+            const double tok2_q = static_cast<double>(zq_tok) * static_cast<double>(c);
+            const double tok2_p = static_cast<double>(zp_tok) * static_cast<double>(c);
+            if (tid == 0) {
+                RowStat st;
+                st.lse2_q = lse2_q; st.lse2_p = lse2_p; st.tok2_q = tok2_q; st.tok2_p = tok2_p;
+                stats[bk * L + it] = st;
             }
-            double s_tot = static_cast<double>(acc), unused = 0.0;
-            block_sum2(s_tot, unused, sh_d);
-            if (tid == 0) s_out[bk * L + r] = s_tot / Zq_tot;
+            // constants of this row's sweep 2 (next iteration)
+            const double C2 = lse2_p - lse2_q + log2nu;
+            rc_sum.nref_q = -ref_q;
+            rc_sum.C2_hi = static_cast<float>(C2);
+            const double dk = (static_cast<double>(rc_sum.C2_hi) - C2) * 0.693147180559945309417;
+            rc_sum.neg_kappa = (dk > -0.25 && dk < 0.25) ? -static_cast<float>(1.0 + dk + 0.5 * dk * dk) : -1.0f;
+            Zq_prev = Zq_tot;
+            log2nu += (tok2_q - lse2_q) - (tok2_p - lse2_p);
         }
-        log2nu += (tok2_q - lse2_q) - (tok2_p - lse2_p);
     }
+    (void)dbg;
 }
 
 template <typename T, int KP>
