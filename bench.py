@@ -59,6 +59,9 @@ def main() -> int:
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also run a plain device-to-device copy of this many MiB (three times) before the timed "
+                         "region: under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the counters")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build measures one GPU only (the path is embarrassingly parallel over prefixes; "
@@ -91,6 +94,14 @@ def main() -> int:
         sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, offset, workspace=ws, out=out, algo=a.algo,
                              events=events)
 
+    if a.calibrate_copy_mib > 0:
+        src = torch.empty(a.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -117,10 +128,14 @@ def main() -> int:
     main_bytes = w.row_pairs * w.V * 2 * w.elem_bytes       # every (target, draft) row pair once
     achieved = main_bytes / (main_avg * 1e-3) / 1e9
 
+    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE +
+    # WRITE_SIZE, calibrated against a plain copy), if one exists for this workload and schedule
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % a.workload)
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % a.workload)
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("traffic_bytes_per_launch")
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":", 1)[1])
 
     res = {
         "metric": "verifications/sec and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",

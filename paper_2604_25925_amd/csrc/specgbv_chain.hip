@@ -73,13 +73,11 @@ __device__ __forceinline__ void pow_inplace(float (&t)[N], int K)
 // instruction as a flat access that may touch LDS and from then on turns every vector-memory
 // wait into vmcnt(0), which would drain the load pipeline at each use of a loaded register.
 // (Its own vmcnt arithmetic does not see these loads, so its waits are conservative.)
-__device__ __forceinline__ void lds_fill16(const void *src, const void *lds_dst_wave_uniform)
+__device__ __forceinline__ void lds_fill16(const void *src_base_uniform, unsigned lane_byte_off, unsigned lds_dst_wave_uniform)
 {
-    const unsigned m0 = __builtin_amdgcn_readfirstlane(
-        static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds_dst_wave_uniform)));
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(src), "s"(m0)
+                 : "v"(lane_byte_off), "s"(src_base_uniform), "s"(lds_dst_wave_uniform)
                  : "memory", "m0");
 }
 
@@ -125,12 +123,16 @@ __device__ __forceinline__ void sweep2_vec(const U4 &q, const U4 &p, const RowCo
     acc += a;
 }
 
-// 16-byte vector number slot*512 + lane of a row: wave-uniform base plus a 32-bit lane offset.
+// 16-byte vector at a wave-uniform base plus a 32-bit per-lane byte offset (scalar-base addressing:
+// no per-load vector address arithmetic, no 64-bit address registers).
+__device__ __forceinline__ U4 load_vec(const void *base_uniform, unsigned lane_byte_off)
+{
+    return *reinterpret_cast<const U4 *>(static_cast<const char *>(base_uniform) + lane_byte_off);
+}
 template <typename T>
 __device__ __forceinline__ U4 load_slot(const T *row, int slot, unsigned lane)
 {
-    const U4 *base = reinterpret_cast<const U4 *>(row) + static_cast<size_t>(slot) * kChainThreads;
-    return base[lane];
+    return load_vec(reinterpret_cast<const char *>(row) + static_cast<size_t>(slot) * (kChainThreads * 16), lane * 16u);
 }
 
 template <typename T>
@@ -186,6 +188,16 @@ __device__ __forceinline__ void block_max2(float &a, float &b, float *scratch)
     a = ra; b = rb;
 }
 
+// A workgroup-uniform double moved to scalar registers, so that values carried across the row
+// loop do not occupy (or spill) vector registers.
+__device__ __forceinline__ double uniform_d(double v)
+{
+    const long long b = __double_as_longlong(v);
+    const unsigned lo = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(b));
+    const unsigned hi = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(static_cast<unsigned long long>(b) >> 32));
+    return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
+}
+
 // log2 of a positive finite double from its exponent and a float log of the mantissa
 // (absolute error about 1e-7).
 __device__ __forceinline__ double log2_cheap(double z)
@@ -195,10 +207,12 @@ __device__ __forceinline__ double log2_cheap(double z)
     return static_cast<double>(e) + static_cast<double>(__log2f(static_cast<float>(m)));
 }
 
-// Exact-maximum statistics of one row straight from memory (overflow fallback).
+// Exact-maximum statistics of one row straight from memory (overflow fallback).  Results are
+// returned by value: reference parameters of a function that is not inlined would pin the
+// caller's variables to scratch memory for the whole kernel.
+struct ExactStats { float ref; double Z; };
 template <typename T>
-__device__ __noinline__ void exact_row_stats(const T *row, int nvec, float c, float &ref_out, double &Z_out,
-                                             double *sh_d)
+__device__ __noinline__ ExactStats exact_row_stats(const T *row, int nvec, float c, double *sh_d)
 {
     float *sh_f = reinterpret_cast<float *>(sh_d);
     constexpr int PV = Elem<T>::kPerVec;
@@ -217,21 +231,25 @@ __device__ __noinline__ void exact_row_stats(const T *row, int nvec, float c, fl
     }
     double a = static_cast<double>(Z), b = 0.0;
     block_sum2(a, b, sh_d);
-    ref_out = ref; Z_out = a;
+    return ExactStats{ref, a};
 }
 
 constexpr int kLag = 6;    // slots between the load of a vector and its first use
 
-static_assert(kLdsSlots == 9, "one named LDS object per slot");
 struct LdsSlots {
-    U4 (*slot[kLdsSlots])[kChainThreads];                   // slot[s][0] = target vectors, slot[s][1] = draft vectors
+    U4 *all;                 // [kLdsSlots][2][kChainThreads]: slot s, half 0 = target vectors, half 1 = draft vectors
+    unsigned wave_base;      // LDS byte address of this wave's 1 KiB window in slot 0, half 0
 };
+__device__ __forceinline__ const U4 &lds_vec(const LdsSlots &lds, int s, int half, unsigned t)
+{
+    return lds.all[(s * 2 + half) * kChainThreads + t];
+}
 
 template <typename T>
 struct StepCtx {
     const T *qnew, *pnew;
     const RowConsts &rc_sum, &rc_new;
-    unsigned tid, lane_new, wbase;
+    unsigned tid, off_new;   // thread index; byte offset of this lane's vector within a slot of the new row (0 after the last row)
     int nvec, rem, n_on;
     bool do_new, do_sum;
 };
@@ -247,6 +265,11 @@ __device__ __forceinline__ void pipeline_step(const StepCtx<T> &cx, U4 (&rq)[RS]
                                               const LdsSlots &lds, float &Zq, float &Zp, float &acc)
 {
     constexpr int NS = RS + kLdsSlots;
+    constexpr size_t kSlotBytes = static_cast<size_t>(kChainThreads) * 16;
+    // Opaque copies: everything derived from them is recomputed per step instead of being
+    // hoisted out of the row loop and kept (or spilled) across it.
+    unsigned t = cx.tid, off = cx.off_new;
+    asm volatile("" : "+v"(t), "+v"(off));
     if constexpr (J < RS) {
         // Opaque touch of the slot: without it the compiler keeps the floats that sweep 1
         // unpacked from these registers alive until sweep 2, which doubles the footprint of
@@ -254,22 +277,23 @@ __device__ __forceinline__ void pipeline_step(const StepCtx<T> &cx, U4 (&rq)[RS]
         asm volatile("" : "+v"(rq[J].x), "+v"(rq[J].y), "+v"(rq[J].z), "+v"(rq[J].w));
         asm volatile("" : "+v"(rp[J].x), "+v"(rp[J].y), "+v"(rp[J].z), "+v"(rp[J].w));
         if (cx.do_sum) sweep2_vec<T, KP>(rq[J], rp[J], cx.rc_sum, acc);
-        unsigned lane = cx.lane_new;
-        asm volatile("" : "+v"(lane) : "v"(acc));           // keep the loads behind this slot's arithmetic
-        rq[J] = load_slot(cx.qnew, J, lane);
-        rp[J] = load_slot(cx.pnew, J, lane);
+        asm volatile("" : "+v"(off) : "v"(acc));            // keep the loads behind this slot's arithmetic
+        rq[J] = load_vec(reinterpret_cast<const char *>(cx.qnew) + J * kSlotBytes, off);
+        rp[J] = load_vec(reinterpret_cast<const char *>(cx.pnew) + J * kSlotBytes, off);
     } else if constexpr (J < NS) {
         if (J < cx.n_on) {
             if (cx.do_sum && J * kChainThreads < cx.rem)
-                sweep2_vec<T, KP>(lds.slot[J - RS][0][cx.tid], lds.slot[J - RS][1][cx.tid], cx.rc_sum, acc);
+                sweep2_vec<T, KP>(lds_vec(lds, J - RS, 0, t), lds_vec(lds, J - RS, 1, t), cx.rc_sum, acc);
             if (cx.do_new) {
                 // every lane loads (lanes past the row end re-read its last vector) so that
                 // all waves issue the same number of vector-memory operations
-                int v = J * kChainThreads + static_cast<int>(cx.tid);
-                v = v < cx.nvec ? v : cx.nvec - 1;
-                asm volatile("" : "+v"(v) : "v"(acc));
-                lds_fill16(reinterpret_cast<const U4 *>(cx.qnew) + v, &lds.slot[J - RS][0][cx.wbase]);
-                lds_fill16(reinterpret_cast<const U4 *>(cx.pnew) + v, &lds.slot[J - RS][1][cx.wbase]);
+                const unsigned last = static_cast<unsigned>(cx.nvec - 1 - J * kChainThreads) * 16u;   // uniform
+                unsigned o = off < last ? off : last;
+                asm volatile("" : "+v"(o) : "v"(acc));
+                lds_fill16(reinterpret_cast<const char *>(cx.qnew) + J * kSlotBytes, o,
+                           lds.wave_base + (J - RS) * 2 * kChainThreads * 16);
+                lds_fill16(reinterpret_cast<const char *>(cx.pnew) + J * kSlotBytes, o,
+                           lds.wave_base + ((J - RS) * 2 + 1) * kChainThreads * 16);
             }
         }
     }
@@ -281,7 +305,7 @@ __device__ __forceinline__ void pipeline_step(const StepCtx<T> &cx, U4 (&rq)[RS]
             if (J < cx.n_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLag) : "memory");
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             if (JJ * kChainThreads < cx.rem)
-                sweep1_vec<T>(lds.slot[JJ - RS][0][cx.tid], lds.slot[JJ - RS][1][cx.tid], cx.rc_new, Zq, Zp);
+                sweep1_vec<T>(lds_vec(lds, JJ - RS, 0, t), lds_vec(lds, JJ - RS, 1, t), cx.rc_new, Zq, Zp);
         }
     }
 }
@@ -298,18 +322,15 @@ __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
         int K, int L, int V, float c, RowStat *__restrict__ stats, double *__restrict__ s_out, int dbg)
 {
-    // One LDS object per slot: the compiler tracks asynchronous LDS fills per object, so reads
-    // of one slot do not wait for the fills of the others.
-    __shared__ U4 lds0[2][kChainThreads], lds1[2][kChainThreads], lds2[2][kChainThreads], lds3[2][kChainThreads],
-        lds4[2][kChainThreads], lds5[2][kChainThreads], lds6[2][kChainThreads], lds7[2][kChainThreads],
-        lds8[2][kChainThreads];
+    __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
-    const LdsSlots lds{{lds0, lds1, lds2, lds3, lds4, lds5, lds6, lds7, lds8}};
 
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
     const unsigned tid = threadIdx.x;
-    const unsigned wbase = tid & ~(kWave - 1u);
+    const unsigned lds_wave_addr = static_cast<unsigned>(
+        reinterpret_cast<uintptr_t>(static_cast<void *>(&lds_all[tid & ~(kWave - 1u)])));
+    const LdsSlots lds{lds_all, static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(lds_wave_addr)))};
     const long long bk = blockIdx.x;                       // b*K + k
     const int nvec = V / PV;                               // host guarantees nvec >= RS * 512
     const int rem = nvec - static_cast<int>(tid);          // slot j holds a vector of this thread iff j*512 < rem
@@ -339,7 +360,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         const T *pnew = drow0 + static_cast<long long>(r_new) * V;
         const T *qold = trow0 + static_cast<long long>(it >= 1 ? it - 1 : 0) * V;
         const T *pold = drow0 + static_cast<long long>(it >= 1 ? it - 1 : 0) * V;
-        const unsigned lane_new = do_new ? tid : 0u;       // after the last row: one harmless line
+        const unsigned off_new = do_new ? tid * 16u : 0u;  // after the last row: one harmless line
 
         // Reference exponents of the new row: its token's logits (the drafted token was
         // sampled from this draft row, so no entry can exceed it by a factor near 2^127
@@ -352,7 +373,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         rc_new.nref_q = -(zq_tok * c); rc_new.nref_p = -(zp_tok * c);
 
         float Zq = 0.0f, Zp = 0.0f, acc = 0.0f;
-        StepCtx<T> cx{qnew, pnew, rc_sum, rc_new, tid, lane_new, wbase, nvec, rem, n_on, do_new, do_sum};
+        StepCtx<T> cx{qnew, pnew, rc_sum, rc_new, tid, off_new, nvec, rem, n_on, do_new, do_sum};
         run_steps<T, KP, RS>(std::make_integer_sequence<int, NS + kLag>{}, cx, rq, rp, lds, Zq, Zp, acc);
         // vectors that do not fit on chip: read for the statistics now, once more for the sum
         for (int j = NS; j < nslots; ++j) {
@@ -364,12 +385,18 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
 
         double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp), s_tot = static_cast<double>(acc);
         block_sum3(Zq_tot, Zp_tot, s_tot, sh_d);
+        Zq_tot = uniform_d(Zq_tot); Zp_tot = uniform_d(Zp_tot); s_tot = uniform_d(s_tot);
         if (do_sum && tid == 0) s_out[bk * L + it - 1] = s_tot / Zq_prev;
         if (do_new) {
             float ref_q = -rc_new.nref_q, ref_p = -rc_new.nref_p;
-            if (!(Zq_tot < 1.0e37) || !(Zq_tot > 0.0))     // float32 overflow with the token reference
-                exact_row_stats<T>(qnew, nvec, c, ref_q, Zq_tot, sh_d);
-            if (!(Zp_tot < 1.0e37) || !(Zp_tot > 0.0)) exact_row_stats<T>(pnew, nvec, c, ref_p, Zp_tot, sh_d);
+            if (!(Zq_tot < 1.0e37) || !(Zq_tot > 0.0)) {   // float32 overflow with the token reference
+                const ExactStats e = exact_row_stats<T>(qnew, nvec, c, sh_d);
+                ref_q = e.ref; Zq_tot = e.Z;
+            }
+            if (!(Zp_tot < 1.0e37) || !(Zp_tot > 0.0)) {
+                const ExactStats e = exact_row_stats<T>(pnew, nvec, c, sh_d);
+                ref_p = e.ref; Zp_tot = e.Z;
+            }
             const double lse2_q = static_cast<double>(ref_q) + log2_cheap(Zq_tot);
             const double lse2_p = static_cast<double>(ref_p) + log2_cheap(Zp_tot);
             const double tok2_q = static_cast<double>(zq_tok) * static_cast<double>(c);
@@ -385,8 +412,8 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             rc_sum.C2_hi = static_cast<float>(C2);
             const double dk = (static_cast<double>(rc_sum.C2_hi) - C2) * 0.693147180559945309417;
             rc_sum.neg_kappa = (dk > -0.25 && dk < 0.25) ? -static_cast<float>(1.0 + dk + 0.5 * dk * dk) : -1.0f;
-            Zq_prev = Zq_tot;
-            log2nu += (tok2_q - lse2_q) - (tok2_p - lse2_p);
+            Zq_prev = uniform_d(Zq_tot);
+            log2nu = uniform_d(log2nu + ((tok2_q - lse2_q) - (tok2_p - lse2_p)));
         }
     }
     (void)dbg;
