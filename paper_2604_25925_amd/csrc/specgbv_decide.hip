@@ -21,20 +21,49 @@ constexpr int kDecideThreads = 256;
 
 // ---------------------------------------------------------------- k_decide
 
-__device__ double c_K(double log_P, int K)
+// (1 - (1-P)^K) / P = sum_{j<K} (1-P)^j: chance that one of K i.i.d. drafts equals a block of
+// draft probability P, over P.  The geometric sum has no cancellation for tiny P (it tends to K)
+// and costs K - 1 fused multiply-adds instead of a log1p and an expm1.
+__device__ double c_K(double P, int K)
 {
-    // (1 - (1-P)^K) / P: chance that one of K i.i.d. drafts equals a block of draft
-    // probability P, over P.
-    const double P = exp(log_P);
     if (!(P > 0.0)) return static_cast<double>(K);
     if (P >= 1.0) return 1.0;
-    return -expm1(static_cast<double>(K) * log1p(-P)) / P;
+    const double a = 1.0 - P;
+    double c = 1.0;
+    for (int j = 1; j < K; ++j) c = fma(c, a, 1.0);
+    return c;
 }
 
-__device__ double g_K(double log_nu, int K)
+// max(1 - 1/nu, 0)^K from 1/nu.
+__device__ double g_K(double inv_nu, int K)
 {
-    const double t = 1.0 - exp(-log_nu);
+    const double t = 1.0 - inv_nu;
     return t > 0.0 ? powi_uniform(t, K) : 0.0;
+}
+
+// Bitwise OR over the 64 lanes of the wave with data-parallel-primitive moves (row shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then the two row broadcasts), result read from lane 63.
+__device__ __forceinline__ unsigned wave_or32(unsigned v)
+{
+    v |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x111, 0xf, 0xf, false));   // row_shr:1
+    v |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x112, 0xf, 0xf, false));   // row_shr:2
+    v |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x114, 0xf, 0xf, false));   // row_shr:4
+    v |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x118, 0xf, 0xf, false));   // row_shr:8
+    v |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x142, 0xa, 0xf, false));   // row_bcast:15
+    v |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x143, 0xc, 0xf, false));   // row_bcast:31
+    return static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(v), 63));
+}
+
+__device__ __forceinline__ unsigned long long wave_or64(unsigned long long v)
+{
+    return (static_cast<unsigned long long>(wave_or32(static_cast<unsigned>(v >> 32))) << 32) |
+           wave_or32(static_cast<unsigned>(v));
+}
+
+__device__ __forceinline__ unsigned long long uniform_u64(unsigned long long v)
+{
+    return (static_cast<unsigned long long>(__builtin_amdgcn_readfirstlane(static_cast<unsigned>(v >> 32))) << 32) |
+           static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<unsigned>(v)));
 }
 
 __device__ double clamp01(double h)
@@ -53,21 +82,24 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
 {
     extern __shared__ double lds[];
     const int KL = K * L;
-    double *h = lds;                                        // [K*L] acceptance probabilities
-    double *eta = lds + KL;                                 // [K*L] uniforms
-    double *l2nu = lds + 2 * KL;                            // [K*L] log2 nu_i
-    double *tq = lds + 3 * KL;                              // [K*L] log2 q_r[token of row r]
-    double *tp = lds + 4 * KL;                              // [K*L] log2 p_r[token of row r]
-    int *tok = reinterpret_cast<int *>(lds + 5 * KL);       // [K*L]
+    double *l2nu = lds;                                     // [K*L] log2 nu_i
+    double *tq = lds + KL;                                  // [K*L] log2 q_r[token of row r]
+    double *tp = lds + 2 * KL;                              // [K*L] log2 p_r[token of row r]
+    double *lq = lds + 3 * KL;                              // [K*L] log2 normaliser of target row r
+    double *lp = lds + 4 * KL;                              // [K*L] log2 normaliser of draft row r
+    unsigned long long *acc_bits = reinterpret_cast<unsigned long long *>(lds + 5 * KL);   // [K] bit i: eta_{k,i} < h_{k,i}
+    int *tok = reinterpret_cast<int *>(acc_bits + K);       // [K*L]
     int *cpl = tok + KL;                                    // [K*K] common prefix lengths
     const int b = blockIdx.x, tid = threadIdx.x;
     const long long base = static_cast<long long>(b) * KL;
     constexpr double kLn2 = 0.693147180559945309417;
 
+    for (int idx = tid; idx < K; idx += kDecideThreads) acc_bits[idx] = 0ull;
     for (int idx = tid; idx < KL; idx += kDecideThreads) {
         const RowStat st = stats[base + idx];
         tq[idx] = st.tok2_q - st.lse2_q;
         tp[idx] = st.tok2_p - st.lse2_p;
+        lq[idx] = st.lse2_q; lp[idx] = st.lse2_p;
         tok[idx] = tokens[base + idx];
     }
     __syncthreads();
@@ -80,17 +112,21 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
             log2P += tp[k * L + j];
         }
         const double log_nu = log2nu * kLn2, log_P = log2P * kLn2;
+        // two exponentials per entry: 1/nu (nu by one division) and P
+        const double inv_nu = exp2(-log2nu), P = exp2(log2P);
+        const double nu = 1.0 / inv_nu;
+        const double g = g_K(inv_nu, K), cK = c_K(P, K);
         double hv;
         if (i < L) {
-            const double nu = exp(log_nu);
-            const double num = nu * (s - g_K(log_nu, K));
-            const double den = c_K(log_P, K) - nu * (1.0 - s);
+            const double num = nu * (s - g);
+            const double den = cK - nu * (1.0 - s);
             hv = den > 0.0 ? clamp01(num / den) : 1.0;
         } else {
-            hv = clamp01(exp(log_nu) * (1.0 - g_K(log_nu, K)) / c_K(log_P, K));
+            hv = clamp01(nu * (1.0 - g) / cK);
         }
         const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
-        h[idx] = hv; eta[idx] = e; l2nu[idx] = log2nu;
+        l2nu[idx] = log2nu;
+        if (e < hv) atomicOr(&acc_bits[k], 1ull << i);
         log_nu_out[base + idx] = log_nu; log_P_out[base + idx] = log_P;
         h_out[base + idx] = hv; eta_out[base + idx] = e;
     }
@@ -103,31 +139,36 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
     __syncthreads();
     if (tid >= kWave) return;
 
-    // Sequential loop of Algorithm 1, executed by the first wave in lock step; lane j keeps
-    // the lengths at which draft j was tested and rejected (its entries of H), and the test
-    // states of draft j (2 bits per length: 1 tested, 2 skipped because the block is in H).
+    // Sequential loop of Algorithm 1, executed by the first wave.  acc_bits[j] holds the outcomes
+    // of draft j's L tests as a bit mask (bit i: eta_{j,i} < h_{j,i}); lane j holds the lengths at
+    // which draft j was tested and rejected (its entries of H) and its test states (2 bits per length: 1 tested,
+    // 2 skipped because the block is in H).  For draft k the lengths already in H are the union
+    // over earlier drafts j of (rejected_j restricted to lengths <= common prefix of j and k), a
+    // wave-wide OR; the loop over lengths then runs on wave-uniform bit masks only.
     const int lane = tid;
     int tau = 0, f = -1;
     unsigned long long rejected = 0ull;
     unsigned long long st_lo = 0ull, st_hi = 0ull;        // state bits of draft `lane`
     bool done = false;
+    // Per draft the loop over lengths has a closed form on bit masks, because the index keeps
+    // running after an acceptance: every length in (tau, L] that is not in H is tested; the
+    // longest accepted one becomes tau; the failed ones join H; a full-length acceptance ends
+    // the scan.
+    const unsigned long long upto_L = (2ull << L) - 1ull;                      // bits 0..L
     for (int k = 0; k < K && !done; ++k) {
         const int my_cpl = (lane < k) ? cpl[k * K + lane] : 0;
-        for (int i = tau + 1; i <= L; ++i) {
-            const bool hit = (lane < k) && ((rejected >> i) & 1ull) && (my_cpl >= i);
-            const int idx = k * L + i - 1;
-            if (__any(hit)) {                 // block already in H: no sampling
-                if (lane == k) st_hi |= 1ull << i;
-                continue;
-            }
-            if (lane == k) st_lo |= 1ull << i;
-            if (eta[idx] < h[idx]) {
-                tau = i; f = k;
-                if (i == L) { done = true; break; }
-            } else if (lane == k) {
-                rejected |= 1ull << i;
-            }
+        const unsigned long long in_H =
+            wave_or64((lane < k) ? (rejected & ((2ull << my_cpl) - 1ull)) : 0ull);   // lengths <= common prefix
+        const unsigned long long acc_k = uniform_u64(acc_bits[k]);
+        const unsigned long long range = upto_L & ~((2ull << tau) - 1ull);      // lengths tau+1 .. L
+        const unsigned long long tested = range & ~in_H, skipped = range & in_H;
+        const unsigned long long won = tested & acc_k;
+        if (won) {
+            tau = 63 - __clzll(static_cast<long long>(won));
+            f = k;
+            done = (won >> L) & 1ull;
         }
+        if (lane == k) { st_lo = tested; st_hi = skipped; rejected = tested & ~acc_k; }
     }
     if (lane < K)
         for (int i = 1; i <= L; ++i)
@@ -145,10 +186,10 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
             sl.draft_row = -1; sl.C2 = 0.0; sl.shift_q = 0.0f; sl.lse2_q = 0.0;
         } else {
             sl.draft_row = (static_cast<long long>(b) * K + kf) * L + tau;
-            const RowStat st = stats[sl.draft_row];
-            sl.C2 = st.lse2_p - st.lse2_q + (tau == 0 ? 0.0 : l2nu[kf * L + tau - 1]);
-            sl.shift_q = static_cast<float>(st.lse2_q);
-            sl.lse2_q = st.lse2_q;
+            const double lse2_q = lq[kf * L + tau], lse2_p = lp[kf * L + tau];
+            sl.C2 = lse2_p - lse2_q + (tau == 0 ? 0.0 : l2nu[kf * L + tau - 1]);
+            sl.shift_q = rintf(static_cast<float>(lse2_q));         // integral: partial sums rescale exactly
+            sl.lse2_q = lse2_q;
         }
         sel[b] = sl;
     }
@@ -198,7 +239,7 @@ __device__ __forceinline__ float segment_weights(const T *target, const T *draft
             float m = -3.0e38f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) m = fmaxf(m, zq[j]);
-            m2 = wave_max(m) * c;
+            m2 = ceilf(wave_max(m) * c);          // integral: partial sums rescale exactly
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -m2)); w[j] = wq[j]; }
@@ -246,17 +287,6 @@ k_res_partial(const T *__restrict__ target, const T *__restrict__ draft, const S
     }
 }
 
-__device__ __forceinline__ double wave_inclusive_scan(double v)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const double o = __shfl_up(v, off, kWave);
-        if (lane >= off) v += o;
-    }
-    return v;
-}
-
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kSegThreads)
 k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Selection *__restrict__ sel,
@@ -283,8 +313,8 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
     const float M = block_max(mloc, sh_f);
     double tw = 0.0, tqs = 0.0;
     for (int s = s0; s < s1; ++s) {
-        const double sc = exp2(static_cast<double>(pp[s].m2) - static_cast<double>(M));
-        tw += pp[s].sum_w * sc; tqs += pp[s].sum_q * sc;
+        const int sh = static_cast<int>(pp[s].m2 - M);      // both integral, difference <= 0
+        tw += ldexp(pp[s].sum_w, sh); tqs += ldexp(pp[s].sum_q, sh);
     }
     const double Ww = block_sum(tw, sh_d);
     const double Wq = block_sum(tqs, sh_d);
@@ -296,7 +326,7 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
     // first thread, then first segment, whose running total exceeds the goal
     const double mine_seg = use_q ? tqs : tw;
     if (tid == 0) { sh_winner = kSegThreads; sh_last_pos = -1; }
-    const double incl_t = wave_inclusive_scan(mine_seg);
+    const double incl_t = wave_inclusive_sum(mine_seg);
     if (lane == kWave - 1) sh_scan[wid] = incl_t;
     __syncthreads();
     double wave_off = 0.0;
@@ -315,17 +345,16 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
         int found = -1, last_pos = s0 < nseg ? s0 : 0;
         double cum_before_last = excl_t;
         for (int s = s0; s < s1; ++s) {
-            const double sc = exp2(static_cast<double>(pp[s].m2) - static_cast<double>(M));
-            const double v = (use_q ? pp[s].sum_q : pp[s].sum_w) * sc;
+            const double v = ldexp(use_q ? pp[s].sum_q : pp[s].sum_w, static_cast<int>(pp[s].m2 - M));
             if (v > 0.0) { last_pos = s; cum_before_last = cum; }
             if (cum + v > goal) { found = s; cum_before = cum; break; }
             cum += v;
         }
         if (found < 0) { found = last_pos; cum_before = cum_before_last; }
-        const double rescale = exp2(static_cast<double>(M) - static_cast<double>(pp[found].m2));
+        const int up = static_cast<int>(M - pp[found].m2);
         sh_seg = found;
-        sh_local_target = (goal - cum_before) * rescale;   // goal in the segment's own scale
-        sh_total = W * rescale;
+        sh_local_target = ldexp(goal - cum_before, up);    // goal in the segment's own scale
+        sh_total = ldexp(W, up);
     }
     __syncthreads();
     if (wid != 0) return;
@@ -342,7 +371,7 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
         ws[j] = static_cast<double>(use_q ? wq[j] : w[j]);
         mine += ws[j];
     }
-    const double incl = wave_inclusive_scan(mine);
+    const double incl = wave_inclusive_sum(mine);
     const double excl = incl - mine;
     const unsigned long long cross = __ballot(mine > 0.0 && incl > local_target);
     const unsigned long long pos = __ballot(mine > 0.0);
@@ -417,7 +446,7 @@ hipError_t launch_sample_typed(const Problem &p)
 hipError_t launch_decide_and_sample(const Problem &p)
 {
     const int KL = p.K * p.L;
-    const size_t lds = sizeof(double) * 5 * KL + sizeof(int) * (KL + p.K * p.K);
+    const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
     hipLaunchKernelGGL(k_decide, dim3(p.batch), dim3(kDecideThreads), lds, p.stream, p.tokens, p.K, p.L, p.seed,
                        p.offset, reinterpret_cast<const RowStat *>(p.ws + p.lay.stats),
                        reinterpret_cast<const double *>(p.ws + p.lay.s),

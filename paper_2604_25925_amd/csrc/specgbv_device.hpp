@@ -129,16 +129,50 @@ __device__ __forceinline__ double powi_uniform(double t, int K) {
 
 // ------------------------------------------------------------- reductions
 
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int off = kWave / 2; off; off >>= 1) v += __shfl_xor(v, off, kWave);
+// Wave-wide reductions with data-parallel-primitive moves instead of LDS permutes: shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes, then the two row broadcasts (lane 15 -> next row of
+// each half, lane 31 -> upper half).  The sequence is an inclusive scan in lane order; lane 63
+// ends up with the reduction over all 64 lanes.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_move(double v) {
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_update_dpp(0, static_cast<int>(b), CTRL, ROW_MASK, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, static_cast<int>(b >> 32), CTRL, ROW_MASK, 0xf, false);
+    return __longlong_as_double((static_cast<long long>(hi) << 32) | static_cast<unsigned>(lo));
+}
+
+// Inclusive prefix sum over the wave in lane order (lanes without a source add +0.0).
+__device__ __forceinline__ double wave_inclusive_sum(double v) {
+    v += dpp_move<0x111, 0xf>(v);       // row_shr:1
+    v += dpp_move<0x112, 0xf>(v);       // row_shr:2
+    v += dpp_move<0x114, 0xf>(v);       // row_shr:4
+    v += dpp_move<0x118, 0xf>(v);       // row_shr:8
+    v += dpp_move<0x142, 0xa>(v);       // row_bcast:15 into rows 1 and 3
+    v += dpp_move<0x143, 0xc>(v);       // row_bcast:31 into rows 2 and 3
     return v;
 }
 
+// Sum over the wave; every lane gets the result.
+__device__ __forceinline__ double wave_sum(double v) {
+    const long long b = __double_as_longlong(wave_inclusive_sum(v));
+    const unsigned lo = __builtin_amdgcn_readlane(static_cast<int>(b), 63);
+    const unsigned hi = __builtin_amdgcn_readlane(static_cast<int>(b >> 32), 63);
+    return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
+}
+
+// Maximum over the wave; every lane gets the result.  Lanes without a source keep their own value.
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int off = kWave / 2; off; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
+#define SPECGBV_MAX_STEP(CTRL, ROW_MASK)                                                                   \
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, \
+                                                            ROW_MASK, 0xf, false)))
+    SPECGBV_MAX_STEP(0x111, 0xf);
+    SPECGBV_MAX_STEP(0x112, 0xf);
+    SPECGBV_MAX_STEP(0x114, 0xf);
+    SPECGBV_MAX_STEP(0x118, 0xf);
+    SPECGBV_MAX_STEP(0x142, 0xa);
+    SPECGBV_MAX_STEP(0x143, 0xc);
+#undef SPECGBV_MAX_STEP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // Sum over the workgroup; every thread gets the result.  `scratch` holds at least
