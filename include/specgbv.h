@@ -69,7 +69,11 @@ size_t specgbv_workspace_bytes(int batch, int K, int L, int V, specgbv_dtype dty
  * Multi-draft greedy block verification (Algorithm 1; Eq. (hik), Eq. (hLk), Eq. (pres)).
  *
  *   target_logits      device, [batch, K, L+1, V], dense, V fastest
- *   draft_logits       device, [batch, K, L,   V], dense, V fastest
+ *   draft_logits       device, [batch, K, L,   V], dense, V fastest.  Logits may be -inf
+ *                      (masked vocabulary entries: probability 0, residual weight 0) but
+ *                      not +inf or NaN, and every row needs at least one finite entry; a
+ *                      drafted token whose target logit is -inf makes its block and every
+ *                      longer one unacceptable (h = 0)
  *   draft_tokens       device, [batch, K, L] int32, each in [0, V) (not checked on device
  *                      beyond clamping the gather index; out-of-range tokens give
  *                      meaningless but memory-safe results)

@@ -158,6 +158,35 @@ def test_extreme_logits(algo):
     _algo_or_skip(algo, lambda: check_case(tb, db, tok, 0.7, 0, 0, algo, "extreme bf16"))
 
 
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("dtype,V", [("f32", 3000), ("bf16", 32768)])
+def test_masked_logits_minus_infinity(algo, dtype, V):
+    # vocabulary masks: -inf in both models (padded tail), in the target only and in the draft only
+    # (never at a drafted token's draft logit); a masked entry has probability 0 and weight 0
+    t, d, tok, T = _gauss_case(3, 4, 4, V, "f32", seed=11)
+    rng = np.random.default_rng(12)
+    t[..., V - 200:] = -np.inf
+    d[..., V - 200:] = -np.inf
+    only_t = rng.integers(0, V - 200, 300)
+    only_d = rng.integers(0, V - 200, 300)
+    t[..., only_t] = -np.inf
+    d[..., only_d] = -np.inf
+    B, K, L = tok.shape
+    for b in range(B):
+        for k in range(K):
+            for r in range(L):
+                # the drafted token must have positive draft probability: redraw onto an unmasked entry
+                while not np.isfinite(d[b, k, r, tok[b, k, r]]) or not np.isfinite(t[b, k, r, tok[b, k, r]]):
+                    tok[b, k, r] = rng.integers(0, V - 200)
+    # one drafted token that the target forbids outright: its block and every longer one have nu = 0
+    t[1, 2, 1, tok[1, 2, 1]] = -np.inf
+    if dtype == "bf16":
+        t, d = f32_to_bf16_bits(t), f32_to_bf16_bits(d)
+    for off in (0, 1):
+        rep, gpu, ora = _algo_or_skip(algo, lambda: check_case(t, d, tok, T, 2, off, algo, "masked %s" % dtype))
+        assert np.all(ora["h"][1, 2, 1:] == 0.0) and np.all(gpu["h"][1, 2, 1:] == 0.0)
+
+
 def test_plain_entry_point_matches_ex_and_offsets_differ():
     w = with_batch(WORKLOADS["cfg2"], 4)
     t, d, tok = make_inputs(w, seed=2)
