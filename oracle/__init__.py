@@ -41,6 +41,7 @@ class _Debug(ctypes.Structure):
         ("state", POINTER(c_int32)), ("res_norm", POINTER(c_double)),
         ("u_final", POINTER(c_double)), ("margin", POINTER(c_double)),
         ("fallback", POINTER(c_int32)),
+        ("carry_log_nu", POINTER(c_double)), ("modify_count", POINTER(c_int32)),
     ]
 
 
@@ -75,6 +76,10 @@ def lib() -> ctypes.CDLL:
                                             c_int, c_float, c_uint64, c_uint64, POINTER(c_int32),
                                             POINTER(c_int32), POINTER(c_int32), POINTER(_Debug), POINTER(c_int32), c_int]
         L.specgbv_oracle_verify.restype = c_int
+        L.specgbv_oracle_modify.argtypes = [c_void_p, c_void_p, POINTER(c_int32), c_int, c_int, c_int, c_int, c_int,
+                                            c_float, POINTER(c_double), POINTER(c_int32), POINTER(c_double),
+                                            POINTER(c_double), POINTER(c_int32)]
+        L.specgbv_oracle_modify.restype = c_int
         L.specgbv_oracle_num_procs.argtypes = []
         L.specgbv_oracle_num_procs.restype = c_int
         _lib = L
@@ -188,10 +193,12 @@ def verify(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np
             log_nu=np.full((B, K, L), nan), log_P=np.full((B, K, L), nan),
             s=np.full((B, K, L), nan), h=np.full((B, K, L), nan), eta=np.full((B, K, L), nan),
             state=np.zeros((B, K, L), np.int32), res_norm=np.full(B, nan), u_final=np.full(B, nan),
-            margin=np.full(B, nan), fallback=np.zeros(B, np.int32))
+            margin=np.full(B, nan), fallback=np.zeros(B, np.int32),
+            carry_log_nu=np.full(B, nan), modify_count=np.zeros(B, np.int32))
         dbg = _Debug(_dp(res["lse_q"]), _dp(res["lse_p"]), _dp(res["log_nu"]), _dp(res["log_P"]),
                      _dp(res["s"]), _dp(res["h"]), _dp(res["eta"]), _ip(res["state"]),
-                     _dp(res["res_norm"]), _dp(res["u_final"]), _dp(res["margin"]), _ip(res["fallback"]))
+                     _dp(res["res_norm"]), _dp(res["u_final"]), _dp(res["margin"]), _ip(res["fallback"]),
+                     _dp(res["carry_log_nu"]), _ip(res["modify_count"]))
     rc = lib().specgbv_oracle_verify(
         tl.ctypes.data_as(c_void_p), dl.ctypes.data_as(c_void_p), _ip(tok), K, L, V, B, dt,
         c_float(temperature), rng_seed, rng_offset, _ip(res["accepted_len"]),
@@ -200,6 +207,33 @@ def verify(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np
         _ip(pids) if pids is not None else None, int(nthreads))
     if rc != 0:
         raise ValueError("specgbv_oracle_verify rejected its arguments (code %d)" % rc)
+    return res
+
+
+def modify(target_logits: np.ndarray, draft_logits: np.ndarray, tokens: np.ndarray, temperature: float,
+           carry_log_nu, count):
+    """Algorithm 2 on host arrays: the distribution to use for the first rows of the next iteration.
+
+    target_logits, draft_logits [B, K, M, V]; tokens [B, K, M]; carry_log_nu [B] and count [B] come
+    from the previous iteration (verify(..., debug=True)).  Returns a dict with logq [B, K, M, V]
+    (natural log of q_new for rows < count, of q otherwise), norm [B, K, M], fallback [B, K, M].
+    """
+    tl, dt = to_raw(target_logits)
+    dl, dt2 = to_raw(draft_logits)
+    assert dt == dt2 and tl.shape == dl.shape
+    B, K, M, V = tl.shape
+    tok = np.ascontiguousarray(tokens, dtype=np.int32)
+    assert tok.shape == (B, K, M)
+    carry = np.ascontiguousarray(carry_log_nu, dtype=np.float64)
+    cnt = np.ascontiguousarray(count, dtype=np.int32)
+    assert carry.shape == (B,) and cnt.shape == (B,)
+    res = {"logq": np.full((B, K, M, V), np.nan), "norm": np.full((B, K, M), np.nan),
+           "fallback": np.zeros((B, K, M), np.int32)}
+    rc = lib().specgbv_oracle_modify(tl.ctypes.data_as(c_void_p), dl.ctypes.data_as(c_void_p), _ip(tok), K, M, V, B,
+                                     dt, c_float(temperature), _dp(carry), _ip(cnt), _dp(res["logq"]),
+                                     _dp(res["norm"]), _ip(res["fallback"]))
+    if rc != 0:
+        raise ValueError("specgbv_oracle_modify rejected its arguments (code %d)" % rc)
     return res
 
 

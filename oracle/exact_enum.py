@@ -157,6 +157,36 @@ def enumerate_alg1(p_of: Table, q_of: Table, V: int, L: int, K: int):
     return dist, E_tau, degenerate_mass
 
 
+def modified_literal(p_of: Table, q_of: Table, prefix: Block, V: int, K: int):
+    """Algorithm 2: q_new(. | prefix) for prefix = (t^tau, y, x^(i-1)), written with the joint
+    probabilities of the whole sequence exactly as printed.  It is the expression of Eq. (pres)
+    evaluated at that longer block; all-zero weights are read as q(. | prefix)."""
+    return residual_literal(p_of, q_of, prefix, V, K)
+
+
+def enumerate_full_output(p_of: Table, q_of: Table, V: int, L: int, K: int):
+    """Exact law of the first L tokens of O = (t^tau, y, x^(L-tau-1)) of Theorem 4.2: Algorithm 1's
+    output completed with tokens drawn one by one from Algorithm 2's modified distributions."""
+    dist, _, _ = enumerate_alg1(p_of, q_of, V, L, K)
+    out: Dict[Block, Fraction] = {}
+
+    def extend(prefix, pr):
+        if pr == 0:
+            return
+        if len(prefix) >= L:
+            key = prefix[:L]
+            out[key] = out.get(key, Fraction(0)) + pr
+            return
+        qn, _ = modified_literal(p_of, q_of, prefix, V, K)
+        for x in range(V):
+            extend(prefix + (x,), pr * qn[x])
+
+    for key, pr in dist.items():
+        extend(key, pr)
+    assert sum(out.values()) == 1
+    return out
+
+
 def first_token_marginal(dist, V: int):
     m = [Fraction(0)] * V
     for key, pr in dist.items():

@@ -9,8 +9,10 @@
  * What it computes (paper, Section 4.2): Algorithm 1 "SpecTr-GBV" with the
  * acceptance probabilities of Eq. (hik) [sub-block] and Eq. (hLk) [whole
  * block] and the residual distribution of Eq. (pres), for a batch of
- * independent prefixes.  Everything is written in the order and notation of
- * the paper; there is no blocking, fusion or reordering.
+ * independent prefixes, and Algorithm 2 "Distribution Modification" (the
+ * target distribution of the first L - tau - 1 positions of the next
+ * iteration).  Everything is written in the order and notation of the paper;
+ * there is no blocking, fusion or reordering.
  *
  * Notation.  For one prefix and one draft k: row r (0-based) of the target
  * (draft) logits is the conditional distribution q(.|x^r) (p(.|x^r)), i.e. the
@@ -324,6 +326,9 @@ typedef struct {
     double *u_final;    /* [B] uniform of the final token                     */
     double *margin;     /* [B] inverse-CDF margin of the final token          */
     int32_t *fallback;  /* [B] 1 if all residual weights were zero            */
+    double *carry_log_nu;   /* [B] log of q(t^tau, y) / p(t^tau, y): the block ratio that
+                             *     Algorithm 2 continues in the next iteration (0 if tau = L) */
+    int32_t *modify_count;  /* [B] L - tau - 1 positions to modify next (0 if tau >= L - 1) */
 } specgbv_oracle_debug;
 
 static void verify_one(const void *target_logits, const void *draft_logits,
@@ -406,6 +411,9 @@ static void verify_one(const void *target_logits, const void *draft_logits,
         for (int x = 0; x < V; ++x) w[x] = exp(lq[x]);
         y = specgbv_oracle_sample_cdf(w, V, u, &W, &margin);
     }
+    /* Algorithm 2 conditions on (t^tau, y): the block ratio extended by the final token */
+    double carry = 0.0;
+    if (tau < L) carry = (tau == 0 ? 0.0 : log_nu[kf * L + tau - 1]) + lq[y] - lp[y];
 
     accepted_len[b] = tau;
     accepted_draft_idx[b] = f;
@@ -425,6 +433,8 @@ static void verify_one(const void *target_logits, const void *draft_logits,
         if (dbg->u_final) dbg->u_final[b] = u;
         if (dbg->margin) dbg->margin[b] = margin;
         if (dbg->fallback) dbg->fallback[b] = fallback;
+        if (dbg->carry_log_nu) dbg->carry_log_nu[b] = carry;
+        if (dbg->modify_count) dbg->modify_count[b] = tau < L ? L - tau - 1 : 0;
     }
     free(z); free(lq); free(lp); free(w); free(h); free(eta); free(log_nu); free(log_P);
 }
@@ -476,4 +486,79 @@ int specgbv_oracle_num_procs(void)
 #else
     return 1;
 #endif
+}
+
+/* ------------------------------------------------ Algorithm 2 (next iteration) */
+
+/*
+ * Distribution modification (Algorithm 2).  After an iteration that accepted t^tau and drew
+ * the final token y, the first count = L - tau - 1 positions of the next iteration use
+ *     q_new(x | x^(i-1)) ~ q(t^tau, y, x^(i-1), x) (1 - min{ p(t^tau, y, x^(i-1), x) /
+ *                                                        q(t^tau, y, x^(i-1), x), 1 })^K
+ * instead of q.  Dividing by the joint probability of (t^tau, y, x^(i-1)) this is the same
+ * per-token form as Eq. (pres),
+ *     w[x] = q_r[x] max(1 - p_r[x] / (nu q_r[x]), 0)^K,   q_new = w / sum_x w,
+ * with nu = [q(t^tau, y) / p(t^tau, y)] * prod_{j<r} q_j[x^(j+1)] / p_j[x^(j+1)]: the ratio
+ * carried over from the previous iteration, continued along the new draft with the ORIGINAL
+ * target probabilities.  If every weight is zero the row is left as q (same reading as for
+ * the residual).
+ *
+ *   target_logits, draft_logits [batch, K, M, V]: rows r = 0..M-1 of the new drafts
+ *   tokens [batch, K, M]: the new drafts' tokens (row r was sampled into tokens[r])
+ *   carry_log_nu [batch], count [batch] (0..M): from the previous iteration
+ *   out_logq [batch, K, M, V]: natural log of the distribution to use for row r
+ *            (q_new for r < count, q otherwise; -inf where the probability is 0)
+ *   norm_out [batch, K, M] (may be NULL): sum_x w of modified rows, 1 otherwise
+ *   fallback_out [batch, K, M] (may be NULL): 1 where all weights were zero
+ */
+int specgbv_oracle_modify(const void *target_logits, const void *draft_logits,
+                          const int32_t *tokens, int K, int M, int V, int batch,
+                          int dtype, float temperature, const double *carry_log_nu,
+                          const int32_t *count, double *out_logq, double *norm_out,
+                          int32_t *fallback_out)
+{
+    if (!target_logits || !draft_logits || !tokens || !carry_log_nu || !count || !out_logq) return 1;
+    if (K < 1 || M < 1 || V < 1 || batch < 0) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (!(temperature > 0.0f) || !isfinite(temperature)) return 1;
+    const double T = (double)temperature;
+    double *z = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lq = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)V);
+    double *w = (double *)malloc(sizeof(double) * (size_t)V);
+    for (int b = 0; b < batch; ++b) {
+        if (count[b] < 0 || count[b] > M) { free(z); free(lq); free(lp); free(w); return 1; }
+        for (int k = 0; k < K; ++k) {
+            double lognu = carry_log_nu[b];
+            for (int r = 0; r < M; ++r) {
+                const size_t row = ((size_t)b * K + k) * (size_t)M + (size_t)r;
+                load_row(target_logits, dtype, row, V, z);
+                specgbv_oracle_log_softmax(z, V, T, lq);
+                load_row(draft_logits, dtype, row, V, z);
+                specgbv_oracle_log_softmax(z, V, T, lp);
+                double *out = out_logq + row * (size_t)V;
+                double W = 1.0;
+                int fb = 0;
+                if (r < count[b]) {
+                    W = 0.0;
+                    for (int x = 0; x < V; ++x) { w[x] = ot_term(lq[x], lp[x], lognu, K); W += w[x]; }
+                    if (W > 0.0) {
+                        for (int x = 0; x < V; ++x) out[x] = log(w[x]) - log(W);
+                    } else {
+                        fb = 1; W = 1.0;
+                        for (int x = 0; x < V; ++x) out[x] = lq[x];
+                    }
+                } else {
+                    for (int x = 0; x < V; ++x) out[x] = lq[x];
+                }
+                if (norm_out) norm_out[row] = W;
+                if (fallback_out) fallback_out[row] = fb;
+                const int32_t tok = tokens[row];
+                if (tok < 0 || tok >= V) { free(z); free(lq); free(lp); free(w); return 1; }
+                lognu += lq[tok] - lp[tok];
+            }
+        }
+    }
+    free(z); free(lq); free(lp); free(w);
+    return 0;
 }
