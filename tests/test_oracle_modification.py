@@ -83,12 +83,13 @@ def test_k1_modification_is_greedy_block_verification():
     d = (t + rng.normal(0, 1, (2, 1, M, V))).astype(np.float32)
     tok = rng.integers(0, V, (2, 1, M)).astype(np.int32)
     carry = np.array([0.3, -0.8])
-    res = oracle.modify(t, d, tok, 0.9, carry, [M, 1])
+    T = float(np.float32(0.9))                           # the entry point takes a float32 temperature
+    res = oracle.modify(t, d, tok, T, carry, [M, 1])
     for b in range(2):
         lognu = carry[b]
         for r in range(M):
-            lq, _ = oracle.log_softmax(t[b, 0, r], 0.9)
-            lp, _ = oracle.log_softmax(d[b, 0, r], 0.9)
+            lq, _ = oracle.log_softmax(t[b, 0, r], T)
+            lp, _ = oracle.log_softmax(d[b, 0, r], T)
             if r < (M, 1)[b]:
                 w = np.maximum(np.exp(lognu) * np.exp(lq) - np.exp(lp), 0.0)
                 want = w / w.sum()
