@@ -146,6 +146,9 @@ typedef struct specgbv_intermediates {
     double *margin;      /* [batch] distance of u*total to the nearer end of the drawn      */
                          /*         token's CDF interval, divided by total                  */
     int32_t *fallback;   /* [batch] 1 if all residual weights were zero                     */
+    double *carry_log_nu;   /* [batch] ln [q(t^tau, y) / p(t^tau, y)] relative to the prefix: the */
+                            /*         block ratio Algorithm 2 starts from (0 when tau = L)    */
+    int32_t *modify_count;  /* [batch] L - tau - 1 rows Algorithm 2 modifies next (0 if tau = L) */
 } specgbv_intermediates;
 
 /*
@@ -156,6 +159,58 @@ typedef struct specgbv_intermediates {
 specgbv_status specgbv_read_intermediates(
     const void *workspace, size_t workspace_bytes, int batch, int K, int L, int V,
     specgbv_dtype dtype, const specgbv_intermediates *host_out, void *hip_stream);
+
+/*
+ * Device pointers, inside `workspace`, of the two per-prefix values every specgbv_verify[_ex]
+ * call leaves for the distribution modification of the next decoding iteration
+ * (Algorithm 2; Section 4.2): carry_log_nu [batch] float64 and modify_count [batch] int32, as
+ * described in specgbv_intermediates.  They stay valid until the next call that uses the
+ * workspace; pass them to specgbv_modify_target on the same stream, or copy them out.
+ * (batch, K, L, V) must be those of the verification call.  Host-side arithmetic only.
+ */
+specgbv_status specgbv_workspace_carry(
+    void *workspace, size_t workspace_bytes, int batch, int K, int L, int V,
+    double **carry_log_nu, int32_t **modify_count);
+
+/*
+ * Distribution modification (Algorithm 2, Section 4.2) for the drafts of the NEXT iteration.
+ *
+ * After an iteration accepted t^tau and drew y, the first count = L - tau - 1 target rows of
+ * every new draft are replaced by
+ *     q_new[x] = w[x] / sum_x w[x],   w[x] = q_r[x] * max(1 - p_r[x] / (nu_r q_r[x]), 0)^K
+ * (Algorithm 2 with numerator and normaliser divided by the joint probability of the
+ * conditioning block, the per-token form of Eq. (pres)), where
+ * nu_r = exp(carry_log_nu) * prod_{j<r} q_j[x^(j+1)] / p_j[x^(j+1)] continues the previous
+ * iteration's block ratio along the new draft's own tokens with the ORIGINAL target
+ * probabilities.  Rows r >= count are left as q_r.  If every weight of a row is zero the row
+ * is left as q_r (same reading as for the residual of Eq. (pres)).
+ *
+ *   target_logits   device, [batch, K, M, V]: target rows r = 0..M-1 of the new drafts
+ *                   (row r is conditioned on the new prefix and the draft's first r tokens)
+ *   draft_logits    device, [batch, K, M, V]: the draft rows the tokens were drawn from
+ *   draft_tokens    device, [batch, K, M] int32, each in [0, V)
+ *   K, M, V, batch  K, M, V >= 1, batch >= 0; K <= SPECGBV_MAX_K
+ *   dtype, temperature   as in specgbv_verify
+ *   carry_log_nu    device, [batch] float64; modify_count device, [batch] int32, clamped to
+ *                   [0, M] (both as left by the previous specgbv_verify call)
+ *   out_logq        device out, [batch, K, M, V] float32: natural logarithm of the
+ *                   distribution to verify row r against (q_new for r < count, q otherwise;
+ *                   -inf where the probability is 0).  Being normalised log-probabilities the
+ *                   rows can be handed to specgbv_verify as float32 logits at temperature 1.
+ *   out_logp        device out or NULL, [batch, K, M, V] float32: ln p_r, so that both models
+ *                   can be passed on at temperature 1
+ *   norm_out        device out or NULL, [batch, K, M] float64: sum_x w[x] of modified rows
+ *                   (1 for unmodified rows and for rows whose weights were all zero)
+ *   fallback_out    device out or NULL, [batch, K, M] int32: 1 where all weights were zero
+ *   hip_stream      all work is enqueued on it; the call does not wait
+ *
+ * No workspace is needed.  Errors are detected on the host before anything is launched.
+ */
+specgbv_status specgbv_modify_target(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int M, int V, int batch, specgbv_dtype dtype, float temperature,
+    const double *carry_log_nu, const int32_t *modify_count,
+    float *out_logq, float *out_logp, double *norm_out, int32_t *fallback_out, void *hip_stream);
 
 /* Message of the last failing call made by this thread ("" if none); static storage. */
 const char *specgbv_last_error(void);

@@ -21,7 +21,7 @@ ALGO_AUTO, ALGO_SPLIT, ALGO_CHAIN = 0, 1, 2
 _ALGO = {"auto": ALGO_AUTO, "split": ALGO_SPLIT, "chain": ALGO_CHAIN}
 
 EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_ex", "specgbv_read_intermediates",
-           "specgbv_last_error", "specgbv_version")
+           "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_last_error", "specgbv_version")
 
 
 class SpecGBVError(RuntimeError):
@@ -38,7 +38,8 @@ class _Intermediates(ctypes.Structure):
     _fields_ = [("lse_q", POINTER(c_double)), ("lse_p", POINTER(c_double)), ("log_nu", POINTER(c_double)),
                 ("log_P", POINTER(c_double)), ("s", POINTER(c_double)), ("h", POINTER(c_double)),
                 ("eta", POINTER(c_double)), ("state", POINTER(c_int32)), ("res_norm", POINTER(c_double)),
-                ("u_final", POINTER(c_double)), ("margin", POINTER(c_double)), ("fallback", POINTER(c_int32))]
+                ("u_final", POINTER(c_double)), ("margin", POINTER(c_double)), ("fallback", POINTER(c_int32)),
+                ("carry_log_nu", POINTER(c_double)), ("modify_count", POINTER(c_int32))]
 
 
 _lib = None
@@ -64,6 +65,12 @@ def load_library() -> ctypes.CDLL:
     L.specgbv_read_intermediates.argtypes = [c_void_p, c_size_t, c_int, c_int, c_int, c_int, c_int,
                                              POINTER(_Intermediates), c_void_p]
     L.specgbv_read_intermediates.restype = c_int
+    L.specgbv_workspace_carry.argtypes = [c_void_p, c_size_t, c_int, c_int, c_int, c_int, POINTER(c_void_p),
+                                          POINTER(c_void_p)]
+    L.specgbv_workspace_carry.restype = c_int
+    L.specgbv_modify_target.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float,
+                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.specgbv_modify_target.restype = c_int
     L.specgbv_last_error.argtypes = []
     L.specgbv_last_error.restype = c_char_p
     L.specgbv_version.argtypes = []
@@ -188,12 +195,74 @@ def specgbv_read_intermediates(workspace, batch: int, K: int, L: int, V: int, dt
     for k in ("res_norm", "u_final", "margin"):
         res[k] = np.empty(batch, np.float64)
     res["fallback"] = np.empty(batch, np.int32)
+    res["carry_log_nu"] = np.empty(batch, np.float64)
+    res["modify_count"] = np.empty(batch, np.int32)
     dp = lambda a: a.ctypes.data_as(POINTER(c_double))
     ip = lambda a: a.ctypes.data_as(POINTER(c_int32))
     im = _Intermediates(dp(res["lse_q"]), dp(res["lse_p"]), dp(res["log_nu"]), dp(res["log_P"]), dp(res["s"]),
                         dp(res["h"]), dp(res["eta"]), ip(res["state"]), dp(res["res_norm"]), dp(res["u_final"]),
-                        dp(res["margin"]), ip(res["fallback"]))
+                        dp(res["margin"]), ip(res["fallback"]), dp(res["carry_log_nu"]), ip(res["modify_count"]))
     st = lib.specgbv_read_intermediates(workspace.data_ptr(), workspace.numel() * workspace.element_size(), batch,
                                         K, L, V, dtype, ctypes.byref(im), stream)
+    _check(st)
+    return res
+
+
+def specgbv_workspace_carry(workspace, batch: int, K: int, L: int, V: int) -> Tuple[int, int]:
+    """Raw device addresses (carry_log_nu [batch] float64, modify_count [batch] int32) inside
+    `workspace`, as left by the last verification of this shape."""
+    lib = load_library()
+    a, b = c_void_p(), c_void_p()
+    st = lib.specgbv_workspace_carry(workspace.data_ptr(), workspace.numel() * workspace.element_size(), batch, K, L,
+                                     V, ctypes.byref(a), ctypes.byref(b))
+    _check(st)
+    return int(a.value), int(b.value)
+
+
+def _dev_ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    return x if isinstance(x, int) else x.data_ptr()
+
+
+def specgbv_modify_target(target_logits, draft_logits, draft_tokens, temperature: float, carry_log_nu, modify_count,
+                          *, want_logp: bool = False, want_norm: bool = False, out=None,
+                          stream: Optional[int] = None):
+    """Enqueue Algorithm 2 for the drafts of the next iteration.
+
+    target_logits, draft_logits [B, K, M, V]; draft_tokens [B, K, M]; carry_log_nu / modify_count are
+    device tensors ([B] float64 / int32) or the raw addresses returned by specgbv_workspace_carry.
+    Returns a dict of device tensors: logq [B, K, M, V] float32 and, on request, logp, norm, fallback.
+    """
+    import torch
+    lib = load_library()
+    if target_logits.dim() != 4 or tuple(target_logits.shape) != tuple(draft_logits.shape):
+        raise ValueError("expected target and draft logits of one shape [B, K, M, V]")
+    B, K, M, V = target_logits.shape
+    if tuple(draft_tokens.shape) != (B, K, M) or draft_tokens.dtype != torch.int32:
+        raise ValueError("draft_tokens must be int32 [B, K, M]")
+    if target_logits.dtype != draft_logits.dtype:
+        raise TypeError("target and draft logits must share a dtype")
+    for t in (target_logits, draft_logits, draft_tokens):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("all tensors must be contiguous GPU tensors")
+    for t, dt in ((carry_log_nu, torch.float64), (modify_count, torch.int32)):
+        if not isinstance(t, int) and (t.dtype != dt or tuple(t.shape) != (B,) or not t.is_cuda):
+            raise ValueError("carry_log_nu / modify_count must be [B] float64 / int32 GPU tensors")
+    dev = target_logits.device
+    res = dict(out) if out else {}
+    if "logq" not in res:
+        res["logq"] = torch.empty((B, K, M, V), dtype=torch.float32, device=dev)
+    if want_logp and "logp" not in res:
+        res["logp"] = torch.empty((B, K, M, V), dtype=torch.float32, device=dev)
+    if want_norm:
+        res.setdefault("norm", torch.empty((B, K, M), dtype=torch.float64, device=dev))
+        res.setdefault("fallback", torch.empty((B, K, M), dtype=torch.int32, device=dev))
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    st = lib.specgbv_modify_target(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, M, V,
+                                   B, _dtype_code(target_logits), c_float(temperature), _dev_ptr(carry_log_nu),
+                                   _dev_ptr(modify_count), res["logq"].data_ptr(), _dev_ptr(res.get("logp")),
+                                   _dev_ptr(res.get("norm")), _dev_ptr(res.get("fallback")), stream)
     _check(st)
     return res

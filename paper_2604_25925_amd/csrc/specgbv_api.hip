@@ -42,6 +42,8 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.u_final = take(static_cast<size_t>(batch) * sizeof(double));
     w.margin = take(static_cast<size_t>(batch) * sizeof(double));
     w.fallback = take(static_cast<size_t>(batch) * sizeof(int32_t));
+    w.carry = take(static_cast<size_t>(batch) * sizeof(double));
+    w.mcount = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.total = off;
     return w;
 }
@@ -187,6 +189,8 @@ specgbv_status specgbv_read_intermediates(
     copy(out->u_final, lay.u_final, batch * sizeof(double));
     copy(out->margin, lay.margin, batch * sizeof(double));
     copy(out->fallback, lay.fallback, batch * sizeof(int32_t));
+    copy(out->carry_log_nu, lay.carry, batch * sizeof(double));
+    copy(out->modify_count, lay.mcount, batch * sizeof(int32_t));
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) {
         free(tmp);
@@ -207,8 +211,47 @@ specgbv_status specgbv_read_intermediates(
     return SPECGBV_OK;
 }
 
+specgbv_status specgbv_workspace_carry(void *workspace, size_t workspace_bytes, int batch, int K, int L, int V,
+                                       double **carry_log_nu, int32_t **modify_count)
+{
+    if (!shape_ok(batch, K, L, V) || batch < 1) return fail(SPECGBV_EINVAL, "bad shape");
+    if (!workspace || !carry_log_nu || !modify_count) return fail(SPECGBV_EINVAL, "null pointer");
+    const Workspace lay = make_workspace(batch, K, L, V);
+    if (workspace_bytes < lay.total) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, lay.total);
+    *carry_log_nu = reinterpret_cast<double *>(static_cast<char *>(workspace) + lay.carry);
+    *modify_count = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + lay.mcount);
+    return SPECGBV_OK;
+}
+
+specgbv_status specgbv_modify_target(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int M, int V, int batch, specgbv_dtype dtype, float temperature,
+    const double *carry_log_nu, const int32_t *modify_count,
+    float *out_logq, float *out_logp, double *norm_out, int32_t *fallback_out, void *hip_stream)
+{
+    if (batch < 0 || K < 1 || M < 1 || V < 1) return fail(SPECGBV_EINVAL, "bad shape batch=%d K=%d M=%d V=%d", batch, K, M, V);
+    if (dtype != SPECGBV_F32 && dtype != SPECGBV_BF16) return fail(SPECGBV_EINVAL, "unknown dtype %d", static_cast<int>(dtype));
+    if (!(temperature > 0.0f) || !std::isfinite(temperature)) return fail(SPECGBV_EINVAL, "temperature must be positive and finite");
+    if (K > SPECGBV_MAX_K) return fail(SPECGBV_EUNSUPPORTED, "K=%d exceeds SPECGBV_MAX_K=%d", K, SPECGBV_MAX_K);
+    const double rows = static_cast<double>(batch) * K * M;
+    if (rows > 2.0e9 || rows * V > 9.0e18 || static_cast<double>(batch) * K > 2.0e9)
+        return fail(SPECGBV_EUNSUPPORTED, "tensor too large");
+    if (batch == 0) return SPECGBV_OK;
+    if (!target_logits || !draft_logits || !draft_tokens || !carry_log_nu || !modify_count || !out_logq)
+        return fail(SPECGBV_EINVAL, "null pointer");
+    const size_t esz = dtype == SPECGBV_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(target_logits) % esz || reinterpret_cast<uintptr_t>(draft_logits) % esz)
+        return fail(SPECGBV_EINVAL, "logits are not aligned to their element size");
+    const float c = static_cast<float>(1.44269504088896340736 / static_cast<double>(temperature));
+    const hipError_t e = launch_modify(target_logits, draft_logits, draft_tokens, K, M, V, batch, dtype == SPECGBV_BF16 ? 1 : 0,
+                                       c, carry_log_nu, modify_count, out_logq, out_logp, norm_out, fallback_out,
+                                       static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "modification kernel launch: %s", hipGetErrorString(e));
+    return SPECGBV_OK;
+}
+
 const char *specgbv_last_error(void) { return g_err; }
 
-const char *specgbv_version(void) { return "specgbv 0.1 (gfx950)"; }
+const char *specgbv_version(void) { return "specgbv 0.2 (gfx950)"; }
 
 }  // extern "C"

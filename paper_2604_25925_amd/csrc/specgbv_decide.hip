@@ -293,7 +293,7 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
              int V, int K, int L, float c, int nseg, const SegPartial *__restrict__ partial,
              uint64_t seed, uint64_t offset, int32_t *__restrict__ out_tokens,
              double *__restrict__ res_norm, double *__restrict__ u_final, double *__restrict__ margin_out,
-             int32_t *__restrict__ fallback_out)
+             int32_t *__restrict__ fallback_out, double *__restrict__ carry_out, int32_t *__restrict__ mcount_out)
 {
     __shared__ double sh_d[kSegThreads / kWave];
     __shared__ double sh_scan[kSegThreads / kWave];
@@ -406,6 +406,16 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
         // total weight in probability units: weights are relative to 2^M, the target row's
         // normaliser is 2^lse2_q (bonus row: the total is the normaliser itself)
         res_norm[b] = sl.draft_row < 0 ? 1.0 : W * exp2(static_cast<double>(M) - sl.lse2_q);
+        // Algorithm 2 conditions the next iteration on (t^tau, y): the block ratio extended by
+        // the final token, ln [nu_tau q_tau[y] / p_tau[y]], and the number of rows it modifies
+        double carry = 0.0;
+        if (sl.draft_row >= 0) {
+            const double zq = static_cast<double>(Elem<T>::scalar(target + sl.target_row * V + tokid));
+            const double zp = static_cast<double>(Elem<T>::scalar(draft + sl.draft_row * V + tokid));
+            carry = (sl.C2 + static_cast<double>(c) * (zq - zp)) * 0.693147180559945309417;
+        }
+        carry_out[b] = carry;
+        mcount_out[b] = sl.draft_row < 0 ? 0 : L - sl.tau - 1;
     }
 }
 
@@ -425,18 +435,20 @@ hipError_t launch_sample_typed(const Problem &p)
     double *u_final = reinterpret_cast<double *>(p.ws + p.lay.u_final);
     double *margin = reinterpret_cast<double *>(p.ws + p.lay.margin);
     int32_t *fallback = reinterpret_cast<int32_t *>(p.ws + p.lay.fallback);
+    double *carry = reinterpret_cast<double *>(p.ws + p.lay.carry);
+    int32_t *mcount = reinterpret_cast<int32_t *>(p.ws + p.lay.mcount);
     if (vec) {
         hipLaunchKernelGGL((k_res_partial<T, true>), g, dim3(kSegThreads), 0, p.stream, target, draft, sel,
                            p.V, p.K, p.c, p.lay.nseg, partial);
         hipLaunchKernelGGL((k_res_locate<T, true>), dim3(p.batch), dim3(kSegThreads), 0, p.stream, target,
                            draft, sel, p.V, p.K, p.L, p.c, p.lay.nseg, partial, p.seed, p.offset,
-                           p.out_tokens, res_norm, u_final, margin, fallback);
+                           p.out_tokens, res_norm, u_final, margin, fallback, carry, mcount);
     } else {
         hipLaunchKernelGGL((k_res_partial<T, false>), g, dim3(kSegThreads), 0, p.stream, target, draft, sel,
                            p.V, p.K, p.c, p.lay.nseg, partial);
         hipLaunchKernelGGL((k_res_locate<T, false>), dim3(p.batch), dim3(kSegThreads), 0, p.stream, target,
                            draft, sel, p.V, p.K, p.L, p.c, p.lay.nseg, partial, p.seed, p.offset,
-                           p.out_tokens, res_norm, u_final, margin, fallback);
+                           p.out_tokens, res_norm, u_final, margin, fallback, carry, mcount);
     }
     return hipGetLastError();
 }

@@ -4,7 +4,8 @@ Bar (from the benchmark definition): accepted length, draft index and tokens are
 bit-exact except where a decision's margin is below 1e-6 (|eta - h| of a performed
 test, or the inverse-CDF margin of the final token); such events are counted and
 reported.  Probabilities agree to 1e-5 relative: log-normalisers to 1e-5 (1 + |value|),
-ln nu and ln P to 1e-5 absolute in the logarithm (= 1e-5 relative on nu and P); the sums s of Eq. (hik)
+ln nu and ln P to 1e-5 absolute in the logarithm (= 1e-5 relative on nu and P), the ratio carried
+into Algorithm 2 (ln nu_tau plus the final token's two log-probabilities) to 2e-5; the sums s of Eq. (hik)
 and the acceptance probabilities h to 1e-5 relative with an absolute floor of 1e-9
 (h's numerator nu (s - g) cancels when nu > 1); the residual normaliser to 1e-5.
 """
@@ -157,10 +158,14 @@ def compare(gpu, ora, tokens, label=""):
             rep["token_mismatches"] += 1
         else:
             assert 0 <= go[tau] < 2 ** 31
-    worst = {k: v for k, v in rep["max_err"].items() if not k.startswith("res_norm[")}
-    rn = [v for k, v in rep["max_err"].items() if k.startswith("res_norm[")]
-    if rn:
-        worst["res_norm"] = max(rn)
+            # what Algorithm 2 starts from in the next iteration: ln [nu_tau q_tau[y] / p_tau[y]]
+            assert gpu["modify_count"][b] == ora["modify_count"][b], "%s prefix %d: modify_count" % (label, b)
+            abserr("carry_log_nu[%d]" % b, gpu["carry_log_nu"][b:b + 1], ora["carry_log_nu"][b:b + 1], 2 * RTOL)
+    worst = {k: v for k, v in rep["max_err"].items() if "[" not in k}
+    for name in ("res_norm", "carry_log_nu"):
+        vals = [v for k, v in rep["max_err"].items() if k.startswith(name + "[")]
+        if vals:
+            worst[name] = max(vals)
     rep["max_err"] = worst
     return rep
 

@@ -73,6 +73,28 @@ def test_argument_errors_are_caught_before_any_launch():
     assert _call(lib, B=0) == 0                             # empty batch: nothing to do
 
 
+def test_modify_target_argument_errors():
+    lib = sg.load_library()
+    P = 1 << 20
+
+    def call(**kw):
+        a = dict(t=P, d=P, tok=P, K=2, M=3, V=64, B=1, dt=0, T=1.0, carry=P, count=P, out=P)
+        a.update(kw)
+        return lib.specgbv_modify_target(a["t"], a["d"], a["tok"], a["K"], a["M"], a["V"], a["B"], a["dt"],
+                                         ctypes.c_float(a["T"]), a["carry"], a["count"], a["out"], None, None, None, None)
+    assert call(K=0) == 1 and call(M=0) == 1 and call(V=0) == 1 and call(B=-1) == 1
+    assert call(dt=2) == 1 and call(T=-1.0) == 1
+    assert call(carry=None) == 1 and call(out=None) == 1 and call(t=None) == 1
+    assert call(K=65) == 2
+    assert call(B=0) == 0
+    a, b = ctypes.c_void_p(), ctypes.c_void_p()
+    need = sg.specgbv_workspace_bytes(4, 2, 3, 64, 0)
+    assert lib.specgbv_workspace_carry(P, need, 4, 2, 3, 64, ctypes.byref(a), ctypes.byref(b)) == 0
+    assert P < a.value < b.value < P + need and a.value % 8 == 0 and b.value % 4 == 0
+    assert lib.specgbv_workspace_carry(P, need - 1, 4, 2, 3, 64, ctypes.byref(a), ctypes.byref(b)) == 3
+    assert lib.specgbv_workspace_carry(None, need, 4, 2, 3, 64, ctypes.byref(a), ctypes.byref(b)) == 1
+
+
 def test_python_binding_validates_tensors():
     import torch
     t = torch.zeros((1, 2, 4, 64))
