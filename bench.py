@@ -48,6 +48,49 @@ def generate(name: str, seed: int, workers: int):
     return target, draft, tokens
 
 
+def bench_modify(a, w, sg, torch, tl, dl, tk, ws, out):
+    """One step = one specgbv_modify_target call over the whole batch: M = L draft rows plus the bonus row per
+    draft, float32 log-probabilities of both models written.  The carried ratios and row counts are those a
+    verification of the same batch leaves in its workspace (the tensors stand in for the next iteration's)."""
+    sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 0, workspace=ws, out=out, algo=a.algo)
+    carry_ptr, count_ptr = sg.specgbv_workspace_carry(ws, w.batch, w.K, w.L, w.V)
+    torch.cuda.synchronize()
+    dt = 1 if w.dtype == "bf16" else 0
+    counts = sg.specgbv_read_intermediates(ws, w.batch, w.K, w.L, w.V, dt)["modify_count"]
+    res = sg.specgbv_modify_target(tl, dl, tk, w.temperature, carry_ptr, count_ptr, want_logp=True)
+    for _ in range(a.warmup):
+        sg.specgbv_modify_target(tl, dl, tk, w.temperature, carry_ptr, count_ptr, want_logp=True, out=res)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record()
+        sg.specgbv_modify_target(tl, dl, tk, w.temperature, carry_ptr, count_ptr, want_logp=True, out=res)
+        e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+    ker = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    avg = sum(ker) / len(ker)
+    rows_d, rows_t = w.batch * w.K * w.L, w.batch * w.K * (w.L + 1)
+    read_b = (rows_d + rows_t) * w.V * w.elem_bytes          # every input row once
+    write_b = (rows_d + rows_t) * w.V * 4                    # float32 log-probabilities of both models
+    achieved = (read_b + write_b) / (avg * 1e-3) / 1e9
+    return {
+        "metric": "distribution modifications/sec (Algorithm 2) and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",
+        "value": w.batch / (ms_per_step * 1e-3), "unit": "prefixes/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: batch %d, K=%d, M=L=%d plus bonus row, V=%d, %s logits, T=%g" % (
+                       w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
+                   "mean_rows_modified": float(np.mean(counts)), "outputs": "logq [B,K,L+1,V] and logp [B,K,L,V], float32"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "k_modify",
+                     "kernel_ms_avg": avg, "kernel_ms_min": ker[0],
+                     "algorithmic_bytes_per_launch": read_b + write_b,
+                     "algorithmic_read_bytes": read_b, "algorithmic_write_bytes": write_b},
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,6 +98,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--algo", default="auto", choices=["auto", "split", "chain"])
+    ap.add_argument("--op", default="verify", choices=["verify", "modify"],
+                    help="verify: the verification call (the benchmark); modify: the distribution modification "
+                         "(Algorithm 2) for the drafts of the next iteration, on the same tensors")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -93,6 +139,10 @@ def main() -> int:
     def step(offset, events=None):
         sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, offset, workspace=ws, out=out, algo=a.algo,
                              events=events)
+
+    if a.op == "modify":
+        print(json.dumps(bench_modify(a, w, sg, torch, tl, dl, tk, ws, out)))
+        return 0
 
     if a.calibrate_copy_mib > 0:
         src = torch.empty(a.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)

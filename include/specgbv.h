@@ -185,32 +185,44 @@ specgbv_status specgbv_workspace_carry(
  * probabilities.  Rows r >= count are left as q_r.  If every weight of a row is zero the row
  * is left as q_r (same reading as for the residual of Eq. (pres)).
  *
- *   target_logits   device, [batch, K, M, V]: target rows r = 0..M-1 of the new drafts
- *                   (row r is conditioned on the new prefix and the draft's first r tokens)
+ *   target_logits   device, [batch, K, M + bonus_row, V]: target rows r = 0..M-1 of the new
+ *                   drafts (row r is conditioned on the new prefix and the draft's first r
+ *                   tokens) and, with bonus_row = 1, row M, which Algorithm 2 never modifies
+ *                   (the bonus-token row of the next verification)
  *   draft_logits    device, [batch, K, M, V]: the draft rows the tokens were drawn from
  *   draft_tokens    device, [batch, K, M] int32, each in [0, V)
- *   K, M, V, batch  K, M, V >= 1, batch >= 0; K <= SPECGBV_MAX_K
+ *   K, M, V, batch  K, M, V >= 1, batch >= 0; K <= SPECGBV_MAX_K, M <= SPECGBV_MAX_L; bonus_row is
+ *                   0 or 1
  *   dtype, temperature   as in specgbv_verify
  *   carry_log_nu    device, [batch] float64; modify_count device, [batch] int32, clamped to
  *                   [0, M] (both as left by the previous specgbv_verify call)
- *   out_logq        device out, [batch, K, M, V] float32: natural logarithm of the
+ *   out_logq        device out, [batch, K, M + bonus_row, V] float32: natural logarithm of the
  *                   distribution to verify row r against (q_new for r < count, q otherwise;
  *                   -inf where the probability is 0).  Being normalised log-probabilities the
- *                   rows can be handed to specgbv_verify as float32 logits at temperature 1.
+ *                   rows can be handed to specgbv_verify as float32 logits at temperature 1
+ *                   (with M = L and bonus_row = 1 the tensor has the shape it expects).
  *   out_logp        device out or NULL, [batch, K, M, V] float32: ln p_r, so that both models
  *                   can be passed on at temperature 1
  *   norm_out        device out or NULL, [batch, K, M] float64: sum_x w[x] of modified rows
  *                   (1 for unmodified rows and for rows whose weights were all zero)
  *   fallback_out    device out or NULL, [batch, K, M] int32: 1 where all weights were zero
+ *   workspace       device, >= specgbv_modify_workspace_bytes(batch, K, M, bonus_row) bytes,
+ *                   256-byte aligned, contents need not be initialised (per-row statistics);
+ *                   it must not be the verification workspace that carry_log_nu and
+ *                   modify_count point into
  *   hip_stream      all work is enqueued on it; the call does not wait
  *
- * No workspace is needed.  Errors are detected on the host before anything is launched.
+ * Errors are detected on the host before anything is launched.
  */
 specgbv_status specgbv_modify_target(
     const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
-    int K, int M, int V, int batch, specgbv_dtype dtype, float temperature,
+    int K, int M, int bonus_row, int V, int batch, specgbv_dtype dtype, float temperature,
     const double *carry_log_nu, const int32_t *modify_count,
-    float *out_logq, float *out_logp, double *norm_out, int32_t *fallback_out, void *hip_stream);
+    float *out_logq, float *out_logp, double *norm_out, int32_t *fallback_out,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device workspace specgbv_modify_target needs (0 if the shape is invalid). */
+size_t specgbv_modify_workspace_bytes(int batch, int K, int M, int bonus_row);
 
 /* Message of the last failing call made by this thread ("" if none); static storage. */
 const char *specgbv_last_error(void);

@@ -21,7 +21,7 @@ ALGO_AUTO, ALGO_SPLIT, ALGO_CHAIN = 0, 1, 2
 _ALGO = {"auto": ALGO_AUTO, "split": ALGO_SPLIT, "chain": ALGO_CHAIN}
 
 EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_ex", "specgbv_read_intermediates",
-           "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_last_error", "specgbv_version")
+           "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_modify_workspace_bytes", "specgbv_last_error", "specgbv_version")
 
 
 class SpecGBVError(RuntimeError):
@@ -68,9 +68,12 @@ def load_library() -> ctypes.CDLL:
     L.specgbv_workspace_carry.argtypes = [c_void_p, c_size_t, c_int, c_int, c_int, c_int, POINTER(c_void_p),
                                           POINTER(c_void_p)]
     L.specgbv_workspace_carry.restype = c_int
-    L.specgbv_modify_target.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float,
-                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.specgbv_modify_target.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_float,
+                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                        c_void_p]
     L.specgbv_modify_target.restype = c_int
+    L.specgbv_modify_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int]
+    L.specgbv_modify_workspace_bytes.restype = c_size_t
     L.specgbv_last_error.argtypes = []
     L.specgbv_last_error.restype = c_char_p
     L.specgbv_version.argtypes = []
@@ -219,6 +222,10 @@ def specgbv_workspace_carry(workspace, batch: int, K: int, L: int, V: int) -> Tu
     return int(a.value), int(b.value)
 
 
+def specgbv_modify_workspace_bytes(batch: int, K: int, M: int, bonus_row: int) -> int:
+    return int(load_library().specgbv_modify_workspace_bytes(batch, K, M, bonus_row))
+
+
 def _dev_ptr(x) -> Optional[int]:
     if x is None:
         return None
@@ -226,19 +233,24 @@ def _dev_ptr(x) -> Optional[int]:
 
 
 def specgbv_modify_target(target_logits, draft_logits, draft_tokens, temperature: float, carry_log_nu, modify_count,
-                          *, want_logp: bool = False, want_norm: bool = False, out=None,
+                          *, want_logp: bool = False, want_norm: bool = False, out=None, workspace=None,
                           stream: Optional[int] = None):
     """Enqueue Algorithm 2 for the drafts of the next iteration.
 
-    target_logits, draft_logits [B, K, M, V]; draft_tokens [B, K, M]; carry_log_nu / modify_count are
-    device tensors ([B] float64 / int32) or the raw addresses returned by specgbv_workspace_carry.
-    Returns a dict of device tensors: logq [B, K, M, V] float32 and, on request, logp, norm, fallback.
+    draft_logits [B, K, M, V]; target_logits [B, K, M, V] or [B, K, M+1, V] (with the bonus row);
+    draft_tokens [B, K, M]; carry_log_nu / modify_count are device tensors ([B] float64 / int32) or
+    the raw addresses returned by specgbv_workspace_carry.  Returns a dict of device tensors: logq
+    (float32, shape of target_logits) and, on request, logp [B, K, M, V], norm, fallback [B, K, M],
+    plus the workspace used (pass the dict back as `out` to reuse every buffer).
     """
     import torch
     lib = load_library()
-    if target_logits.dim() != 4 or tuple(target_logits.shape) != tuple(draft_logits.shape):
-        raise ValueError("expected target and draft logits of one shape [B, K, M, V]")
-    B, K, M, V = target_logits.shape
+    if target_logits.dim() != 4 or draft_logits.dim() != 4:
+        raise ValueError("expected draft logits [B, K, M, V] and target logits [B, K, M or M+1, V]")
+    B, K, M, V = draft_logits.shape
+    bonus = target_logits.shape[2] - M
+    if bonus not in (0, 1) or tuple(target_logits.shape) != (B, K, M + bonus, V):
+        raise ValueError("expected draft logits [B, K, M, V] and target logits [B, K, M or M+1, V]")
     if tuple(draft_tokens.shape) != (B, K, M) or draft_tokens.dtype != torch.int32:
         raise ValueError("draft_tokens must be int32 [B, K, M]")
     if target_logits.dtype != draft_logits.dtype:
@@ -252,17 +264,23 @@ def specgbv_modify_target(target_logits, draft_logits, draft_tokens, temperature
     dev = target_logits.device
     res = dict(out) if out else {}
     if "logq" not in res:
-        res["logq"] = torch.empty((B, K, M, V), dtype=torch.float32, device=dev)
+        res["logq"] = torch.empty((B, K, M + bonus, V), dtype=torch.float32, device=dev)
     if want_logp and "logp" not in res:
         res["logp"] = torch.empty((B, K, M, V), dtype=torch.float32, device=dev)
     if want_norm:
         res.setdefault("norm", torch.empty((B, K, M), dtype=torch.float64, device=dev))
         res.setdefault("fallback", torch.empty((B, K, M), dtype=torch.int32, device=dev))
+    if workspace is None:
+        workspace = res.get("workspace")
+    if workspace is None:
+        workspace = torch.empty(max(specgbv_modify_workspace_bytes(B, K, M, bonus), 256), dtype=torch.uint8, device=dev)
+    res["workspace"] = workspace
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
-    st = lib.specgbv_modify_target(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, M, V,
-                                   B, _dtype_code(target_logits), c_float(temperature), _dev_ptr(carry_log_nu),
+    st = lib.specgbv_modify_target(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, M, bonus,
+                                   V, B, _dtype_code(target_logits), c_float(temperature), _dev_ptr(carry_log_nu),
                                    _dev_ptr(modify_count), res["logq"].data_ptr(), _dev_ptr(res.get("logp")),
-                                   _dev_ptr(res.get("norm")), _dev_ptr(res.get("fallback")), stream)
+                                   _dev_ptr(res.get("norm")), _dev_ptr(res.get("fallback")), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), stream)
     _check(st)
     return res

@@ -44,6 +44,7 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.fallback = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.carry = take(static_cast<size_t>(batch) * sizeof(double));
     w.mcount = take(static_cast<size_t>(batch) * sizeof(int32_t));
+    w.counter = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.total = off;
     return w;
 }
@@ -223,28 +224,51 @@ specgbv_status specgbv_workspace_carry(void *workspace, size_t workspace_bytes, 
     return SPECGBV_OK;
 }
 
-specgbv_status specgbv_modify_target(
-    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
-    int K, int M, int V, int batch, specgbv_dtype dtype, float temperature,
-    const double *carry_log_nu, const int32_t *modify_count,
-    float *out_logq, float *out_logp, double *norm_out, int32_t *fallback_out, void *hip_stream)
+static specgbv_status check_modify_shape(int batch, int K, int M, int bonus_row, int V)
 {
     if (batch < 0 || K < 1 || M < 1 || V < 1) return fail(SPECGBV_EINVAL, "bad shape batch=%d K=%d M=%d V=%d", batch, K, M, V);
+    if (bonus_row != 0 && bonus_row != 1) return fail(SPECGBV_EINVAL, "bonus_row must be 0 or 1 (got %d)", bonus_row);
+    if (K > SPECGBV_MAX_K) return fail(SPECGBV_EUNSUPPORTED, "K=%d exceeds SPECGBV_MAX_K=%d", K, SPECGBV_MAX_K);
+    if (M > SPECGBV_MAX_L) return fail(SPECGBV_EUNSUPPORTED, "M=%d exceeds SPECGBV_MAX_L=%d", M, SPECGBV_MAX_L);
+    const double rows = static_cast<double>(batch) * K * (2 * M + 1);
+    if (rows > 2.0e9 || rows * V > 9.0e18) return fail(SPECGBV_EUNSUPPORTED, "tensor too large");
+    return SPECGBV_OK;
+}
+
+size_t specgbv_modify_workspace_bytes(int batch, int K, int M, int bonus_row)
+{
+    if (check_modify_shape(batch, K, M, bonus_row, 1) != SPECGBV_OK) return 0;
+    return modify_workspace_bytes(batch < 1 ? 1 : batch, K, M, bonus_row);
+}
+
+specgbv_status specgbv_modify_target(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int M, int bonus_row, int V, int batch, specgbv_dtype dtype, float temperature,
+    const double *carry_log_nu, const int32_t *modify_count,
+    float *out_logq, float *out_logp, double *norm_out, int32_t *fallback_out,
+    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const specgbv_status st = check_modify_shape(batch, K, M, bonus_row, V);
+    if (st != SPECGBV_OK) return st;
     if (dtype != SPECGBV_F32 && dtype != SPECGBV_BF16) return fail(SPECGBV_EINVAL, "unknown dtype %d", static_cast<int>(dtype));
     if (!(temperature > 0.0f) || !std::isfinite(temperature)) return fail(SPECGBV_EINVAL, "temperature must be positive and finite");
-    if (K > SPECGBV_MAX_K) return fail(SPECGBV_EUNSUPPORTED, "K=%d exceeds SPECGBV_MAX_K=%d", K, SPECGBV_MAX_K);
-    const double rows = static_cast<double>(batch) * K * M;
-    if (rows > 2.0e9 || rows * V > 9.0e18 || static_cast<double>(batch) * K > 2.0e9)
-        return fail(SPECGBV_EUNSUPPORTED, "tensor too large");
     if (batch == 0) return SPECGBV_OK;
     if (!target_logits || !draft_logits || !draft_tokens || !carry_log_nu || !modify_count || !out_logq)
         return fail(SPECGBV_EINVAL, "null pointer");
     const size_t esz = dtype == SPECGBV_BF16 ? 2 : 4;
-    if (reinterpret_cast<uintptr_t>(target_logits) % esz || reinterpret_cast<uintptr_t>(draft_logits) % esz)
-        return fail(SPECGBV_EINVAL, "logits are not aligned to their element size");
+    if (reinterpret_cast<uintptr_t>(target_logits) % esz || reinterpret_cast<uintptr_t>(draft_logits) % esz ||
+        reinterpret_cast<uintptr_t>(out_logq) % 4 || reinterpret_cast<uintptr_t>(out_logp) % 4 ||
+        reinterpret_cast<uintptr_t>(carry_log_nu) % 8 || reinterpret_cast<uintptr_t>(modify_count) % 4 ||
+        reinterpret_cast<uintptr_t>(norm_out) % 8 || reinterpret_cast<uintptr_t>(fallback_out) % 4)
+        return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
+    const size_t need = modify_workspace_bytes(batch, K, M, bonus_row);
+    if (!workspace) return fail(SPECGBV_EWORKSPACE, "workspace is null (need %zu bytes)", need);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(SPECGBV_EWORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < need) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, need);
     const float c = static_cast<float>(1.44269504088896340736 / static_cast<double>(temperature));
-    const hipError_t e = launch_modify(target_logits, draft_logits, draft_tokens, K, M, V, batch, dtype == SPECGBV_BF16 ? 1 : 0,
-                                       c, carry_log_nu, modify_count, out_logq, out_logp, norm_out, fallback_out,
+    const hipError_t e = launch_modify(target_logits, draft_logits, draft_tokens, K, M, bonus_row, V, batch,
+                                       dtype == SPECGBV_BF16 ? 1 : 0, c, carry_log_nu, modify_count, out_logq, out_logp,
+                                       norm_out, fallback_out, static_cast<char *>(workspace),
                                        static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(SPECGBV_EHIP, "modification kernel launch: %s", hipGetErrorString(e));
     return SPECGBV_OK;

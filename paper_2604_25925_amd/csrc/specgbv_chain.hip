@@ -320,7 +320,8 @@ __device__ __forceinline__ void run_steps(std::integer_sequence<int, Js...>, con
 template <typename T, int KP, int RS>
 __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
-        int K, int L, int V, float c, RowStat *__restrict__ stats, double *__restrict__ s_out, int dbg)
+        int K, int L, int V, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
+        int32_t *__restrict__ final_counter, int dbg)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
@@ -332,6 +333,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         reinterpret_cast<uintptr_t>(static_cast<void *>(&lds_all[tid & ~(kWave - 1u)])));
     const LdsSlots lds{lds_all, static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(lds_wave_addr)))};
     const long long bk = blockIdx.x;                       // b*K + k
+    if (tid == 0 && bk % K == 0) final_counter[bk / K] = 0;   // arrival counter of the final-token kernel
     const int nvec = V / PV;                               // host guarantees nvec >= RS * 512
     const int rem = nvec - static_cast<int>(tid);          // slot j holds a vector of this thread iff j*512 < rem
     const int nslots = (nvec + kChainThreads - 1) / kChainThreads;
@@ -430,7 +432,7 @@ hipError_t launch_kp(const Problem &p)
     const int full_slots = (p.V / Elem<T>::kPerVec) / kChainThreads;
 #define SPECGBV_LAUNCH(RS)                                                                              \
     hipLaunchKernelGGL((k_chain<T, KP, RS>), grid, dim3(kChainThreads), 0, p.stream, target, draft,    \
-                       p.tokens, p.K, p.L, p.V, p.c, stats, s, p.debug)
+                       p.tokens, p.K, p.L, p.V, p.c, stats, s, reinterpret_cast<int32_t *>(p.ws + p.lay.counter), p.debug)
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);
@@ -441,8 +443,13 @@ hipError_t launch_kp(const Problem &p)
 template <typename T>
 hipError_t launch_typed(const Problem &p)
 {
-    switch (p.K) {
+    switch (p.K) {                      // the power t^K unrolled for the common draft counts
+    case 1: return launch_kp<T, 1>(p);
+    case 2: return launch_kp<T, 2>(p);
+    case 3: return launch_kp<T, 3>(p);
+    case 4: return launch_kp<T, 4>(p);
     case 8: return launch_kp<T, 8>(p);
+    case 16: return launch_kp<T, 16>(p);
     default: return launch_kp<T, 0>(p);
     }
 }

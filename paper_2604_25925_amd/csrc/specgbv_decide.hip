@@ -1,23 +1,29 @@
-// Decision scan of Algorithm 1 and the final-token draw.
+// Decision scan of Algorithm 1 and the final-token draw, in one kernel.
 //
-//   k_decide      : one workgroup per prefix.  Builds nu_i, P_i, the acceptance table
-//                   (Eq. (hik) for i < L, Eq. (hLk) for i = L, both divided through by
-//                   P_i so that no joint block probability is ever formed), draws the
-//                   Philox uniforms, then its first wave runs the sequential loop with the
-//                   set H of rejected blocks.
-//   k_res_partial : one wave per (prefix, 512-entry vocabulary segment): partial sums of
-//                   the weights the final token is drawn from -- Eq. (pres) with q(x^tau)
-//                   cancelled, w[x] = q[x] max(1 - p[x]/(nu q[x]), 0)^K, or q[x] for the
-//                   bonus token.
-//   k_res_locate  : per prefix inverse-CDF search: the first token id whose running
-//                   weight exceeds u * total (segment by a workgroup-wide scan of the
-//                   partial sums, entry by a wave scan inside that segment).
+// k_final runs on a grid of (segment groups, prefixes); a workgroup has four waves and each
+// wave owns four consecutive 512-entry vocabulary segments of the row the final token is drawn from.
+//   1. decision  : every workgroup of a prefix rebuilds the prefix's decision (it is a few
+//                  microseconds of scalar work and saves a kernel boundary): nu_i, P_i, the
+//                  acceptance table (Eq. (hik) for i < L, Eq. (hLk) for i = L, both divided
+//                  through by P_i so that no joint block probability is ever formed), the
+//                  Philox uniforms, then the sequential loop with the set H of rejected
+//                  blocks on the first wave.  The first workgroup of the prefix writes the
+//                  outputs and intermediates.
+//   2. partials  : per segment, the sum of the weights the final token is drawn from --
+//                  Eq. (pres) with q(x^tau) cancelled, w[x] = q[x] max(1 - p[x]/(nu q[x]), 0)^K,
+//                  or q[x] for the bonus token.
+//   3. locate    : the workgroup that finishes last for its prefix (a counter in the
+//                  workspace, zeroed by the streaming kernel that runs before) does the
+//                  inverse-CDF search: the first token id whose running weight exceeds
+//                  u * total (segment by a workgroup-wide scan of the partial sums, entry by
+//                  a wave scan inside that segment).
 #include "specgbv_internal.hpp"
 
 namespace specgbv {
 namespace {
 
 constexpr int kDecideThreads = 256;
+constexpr int kSegPerWave = 4;               // residual segments per wave of the final-token kernel
 
 // ---------------------------------------------------------------- k_decide
 
@@ -66,21 +72,56 @@ __device__ __forceinline__ unsigned long long uniform_u64(unsigned long long v)
            static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<unsigned>(v)));
 }
 
+// 2^x in float64 (0 below x = -1000, infinity above x = 1000) by a degree-12 polynomial on [-1/2, 1/2] and an exponent shift
+// (relative error about 1e-15; far less code than the general library routine, which matters
+// in a kernel whose run time is mostly instruction fetch).
+__device__ __forceinline__ double exp2_small(double x)
+{
+    if (!(x > -1000.0)) return 0.0;
+    if (x > 1000.0) return INFINITY;
+    const double n = rint(x);
+    const double f = (x - n) * 0.693147180559945309417;      // |f| <= 0.3466
+    double p = 1.0 / 479001600.0;
+    p = fma(p, f, 1.0 / 39916800.0);
+    p = fma(p, f, 1.0 / 3628800.0);
+    p = fma(p, f, 1.0 / 362880.0);
+    p = fma(p, f, 1.0 / 40320.0);
+    p = fma(p, f, 1.0 / 5040.0);
+    p = fma(p, f, 1.0 / 720.0);
+    p = fma(p, f, 1.0 / 120.0);
+    p = fma(p, f, 1.0 / 24.0);
+    p = fma(p, f, 1.0 / 6.0);
+    p = fma(p, f, 0.5);
+    p = fma(p, f, 1.0);
+    p = fma(p, f, 1.0);
+    return ldexp(p, static_cast<int>(n));
+}
+
 __device__ double clamp01(double h)
 {
     if (!(h > 0.0)) return 0.0;
     return h < 1.0 ? h : 1.0;
 }
 
-__global__ void __launch_bounds__(kDecideThreads)
-k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64_t offset,
-         const RowStat *__restrict__ stats, const double *__restrict__ s_arr,
-         double *__restrict__ log_nu_out, double *__restrict__ log_P_out, double *__restrict__ h_out,
-         double *__restrict__ eta_out, int32_t *__restrict__ state_out, Selection *__restrict__ sel,
-         int32_t *__restrict__ accepted_len, int32_t *__restrict__ accepted_draft_idx,
-         int32_t *__restrict__ out_tokens)
+struct DecideIO {
+    const int32_t *tokens;
+    const RowStat *stats;
+    const double *s_arr;
+    double *log_nu_out, *log_P_out, *h_out, *eta_out;
+    int32_t *state_out;
+    int32_t *accepted_len, *accepted_draft_idx, *out_tokens;
+};
+
+// Decision of prefix b by the whole workgroup (kDecideThreads threads); the result is left in
+// *sel_out (shared memory) and is visible to every thread on return.  Only a workgroup with
+// write = true stores outputs and intermediates.  *u_final_out (shared memory) receives the uniform
+// of the final token (Philox slot K*L), drawn here so that the generator is instantiated once.
+__device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, int L, uint64_t seed, uint64_t offset,
+                                              bool write, double *lds, Selection *sel_out, double *u_final_out)
 {
-    extern __shared__ double lds[];
+    const int32_t *__restrict__ tokens = io.tokens;
+    const RowStat *__restrict__ stats = io.stats;
+    const double *__restrict__ s_arr = io.s_arr;
     const int KL = K * L;
     double *l2nu = lds;                                     // [K*L] log2 nu_i
     double *tq = lds + KL;                                  // [K*L] log2 q_r[token of row r]
@@ -90,7 +131,7 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
     unsigned long long *acc_bits = reinterpret_cast<unsigned long long *>(lds + 5 * KL);   // [K] bit i: eta_{k,i} < h_{k,i}
     int *tok = reinterpret_cast<int *>(acc_bits + K);       // [K*L]
     int *cpl = tok + KL;                                    // [K*K] common prefix lengths
-    const int b = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const long long base = static_cast<long long>(b) * KL;
     constexpr double kLn2 = 0.693147180559945309417;
 
@@ -103,7 +144,9 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
         tok[idx] = tokens[base + idx];
     }
     __syncthreads();
-    for (int idx = tid; idx < KL; idx += kDecideThreads) {
+    for (int idx = tid; idx <= KL; idx += kDecideThreads) {
+        const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
+        if (idx == KL) { *u_final_out = e; continue; }
         const int k = idx / L, i = idx % L + 1;
         const double s = i < L ? s_arr[base + k * L + i] : 0.0;
         double log2nu = 0.0, log2P = 0.0;
@@ -113,7 +156,7 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
         }
         const double log_nu = log2nu * kLn2, log_P = log2P * kLn2;
         // two exponentials per entry: 1/nu (nu by one division) and P
-        const double inv_nu = exp2(-log2nu), P = exp2(log2P);
+        const double inv_nu = exp2_small(-log2nu), P = exp2_small(log2P);
         const double nu = 1.0 / inv_nu;
         const double g = g_K(inv_nu, K), cK = c_K(P, K);
         double hv;
@@ -124,11 +167,12 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
         } else {
             hv = clamp01(nu * (1.0 - g) / cK);
         }
-        const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
         l2nu[idx] = log2nu;
         if (e < hv) atomicOr(&acc_bits[k], 1ull << i);
-        log_nu_out[base + idx] = log_nu; log_P_out[base + idx] = log_P;
-        h_out[base + idx] = hv; eta_out[base + idx] = e;
+        if (write) {
+            io.log_nu_out[base + idx] = log_nu; io.log_P_out[base + idx] = log_P;
+            io.h_out[base + idx] = hv; io.eta_out[base + idx] = e;
+        }
     }
     for (int idx = tid; idx < K * K; idx += kDecideThreads) {
         const int k1 = idx / K, k2 = idx % K;
@@ -137,8 +181,7 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
         cpl[idx] = n;
     }
     __syncthreads();
-    if (tid >= kWave) return;
-
+    if (tid < kWave) {
     // Sequential loop of Algorithm 1, executed by the first wave.  acc_bits[j] holds the outcomes
     // of draft j's L tests as a bit mask (bit i: eta_{j,i} < h_{j,i}); lane j holds the lengths at
     // which draft j was tested and rejected (its entries of H) and its test states (2 bits per length: 1 tested,
@@ -170,15 +213,17 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
         }
         if (lane == k) { st_lo = tested; st_hi = skipped; rejected = tested & ~acc_k; }
     }
-    if (lane < K)
+    if (write && lane < K)
         for (int i = 1; i <= L; ++i)
-            state_out[base + lane * L + i - 1] =
+            io.state_out[base + lane * L + i - 1] =
                 static_cast<int32_t>(((st_lo >> i) & 1ull) | (((st_hi >> i) & 1ull) << 1));
 
     const int kf = f < 0 ? 0 : f;
     if (lane == 0) {
-        accepted_len[b] = tau;
-        accepted_draft_idx[b] = f;
+        if (write) {
+            io.accepted_len[b] = tau;
+            io.accepted_draft_idx[b] = f;
+        }
         Selection sl;
         sl.tau = tau;
         sl.target_row = (static_cast<long long>(b) * K + kf) * (L + 1) + tau;
@@ -191,10 +236,14 @@ k_decide(const int32_t *__restrict__ tokens, int K, int L, uint64_t seed, uint64
             sl.shift_q = rintf(static_cast<float>(lse2_q));         // integral: partial sums rescale exactly
             sl.lse2_q = lse2_q;
         }
-        sel[b] = sl;
+        *sel_out = sl;
     }
-    for (int j = lane; j <= L; j += kWave)
-        out_tokens[static_cast<long long>(b) * (L + 1) + j] = j < tau ? tok[kf * L + j] : -1;
+    // position tau belongs to the final token, which the locating workgroup writes
+    if (write)
+        for (int j = lane; j <= L; j += kWave)
+            if (j != tau) io.out_tokens[static_cast<long long>(b) * (L + 1) + j] = j < tau ? tok[kf * L + j] : -1;
+    }
+    __syncthreads();
 }
 
 // ------------------------------------------------------------ final token
@@ -218,21 +267,33 @@ __device__ __forceinline__ void load8(const T *row, long long e0, int V, float (
     }
 }
 
-// Weights of this lane's 8 entries of segment `seg` relative to 2^m2 (w: the weights the
-// token is drawn from; wq: plain target weights).  With m2 = NaN on entry for the bonus row
-// the segment's own maximum is used as reference and returned.
+// This lane's 8 logits of segment `seg` from the target row and (unless the bonus row is
+// drawn from) the draft row; entries at or beyond V read as -inf / 0.
 template <typename T, bool VEC>
-__device__ __forceinline__ float segment_weights(const T *target, const T *draft, const Selection &sl, int V,
-                                                 int K, float c, int seg, int lane, float m2_in,
-                                                 float (&w)[8], float (&wq)[8])
+__device__ __forceinline__ void segment_load(const T *target, const T *draft, const Selection &sl, int V, int seg,
+                                             int lane, float (&zq)[8], float (&zp)[8])
 {
     const long long e0 = static_cast<long long>(seg) * kSegElems + lane * 8;
-    float zq[8];
     if (e0 < V) load8<T, VEC>(target + sl.target_row * V, e0, V, zq);
     else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) zq[j] = -INFINITY;
     }
+    if (sl.draft_row >= 0 && e0 < V) load8<T, VEC>(draft + sl.draft_row * V, e0, V, zp);
+    else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) zp[j] = 0.0f;
+    }
+}
+
+// Weights of this lane's 8 entries of segment `seg` relative to 2^m2 (w: the weights the
+// token is drawn from; wq: plain target weights).  With m2 = NaN on entry for the bonus row
+// the segment's own maximum is used as reference and returned.
+__device__ __forceinline__ float segment_weigh(const Selection &sl, int V, int K, float c, int seg, int lane,
+                                               float m2_in, const float (&zq)[8], const float (&zp)[8],
+                                               float (&w)[8], float (&wq)[8])
+{
+    const long long e0 = static_cast<long long>(seg) * kSegElems + lane * 8;
     if (sl.draft_row < 0) {
         float m2 = m2_in;
         if (!(m2 == m2)) {                      // reference not fixed yet: this segment's maximum
@@ -244,12 +305,6 @@ __device__ __forceinline__ float segment_weights(const T *target, const T *draft
 #pragma unroll
         for (int j = 0; j < 8; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -m2)); w[j] = wq[j]; }
         return m2;
-    }
-    float zp[8];
-    if (e0 < V) load8<T, VEC>(draft + sl.draft_row * V, e0, V, zp);
-    else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) zp[j] = 0.0f;
     }
     const float m2 = sl.shift_q;
     const RatioConst rc(sl.C2);
@@ -264,63 +319,144 @@ __device__ __forceinline__ float segment_weights(const T *target, const T *draft
     return m2;
 }
 
-template <typename T, bool VEC>
-__global__ void __launch_bounds__(kSegThreads)
-k_res_partial(const T *__restrict__ target, const T *__restrict__ draft, const Selection *__restrict__ sel,
-              int V, int K, float c, int nseg, SegPartial *__restrict__ partial)
+// Partial sums travel between workgroups of one kernel, possibly on different dies with
+// separate L2 caches: they are written and read with device-scope relaxed atomic accesses
+// (which bypass the non-coherent cache levels) instead of being published with a device-scope
+// fence, which on this hardware writes back the whole L2 and costs microseconds per wave.
+__device__ __forceinline__ void partial_store(SegPartial *dst, double sum_w, double sum_q, float m2)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int seg = blockIdx.x * (kSegThreads / kWave) + threadIdx.x / kWave, b = blockIdx.y;
-    if (seg >= nseg) return;                    // whole wave; the kernel has no barrier
-    const Selection sl = sel[b];
-    float w[8], wq[8];
-    const float m2 = segment_weights<T, VEC>(target, draft, sl, V, K, c, seg, lane, __builtin_nanf(""), w, wq);
-    double sw = 0.0, sq = 0.0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { sw += static_cast<double>(w[j]); sq += static_cast<double>(wq[j]); }
-    sw = wave_sum(sw);
-    sq = wave_sum(sq);
-    if (lane == 0) {
-        SegPartial pt;
-        pt.sum_w = sw; pt.sum_q = sq; pt.m2 = m2; pt.pad = 0.0f;
-        partial[static_cast<long long>(b) * nseg + seg] = pt;
-    }
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(&dst->sum_w), static_cast<unsigned long long>(__double_as_longlong(sum_w)),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(&dst->sum_q), static_cast<unsigned long long>(__double_as_longlong(sum_q)),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(reinterpret_cast<unsigned *>(&dst->m2), __float_as_uint(m2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ double partial_load_d(const double *src)
+{
+    return __longlong_as_double(static_cast<long long>(__hip_atomic_load(
+        reinterpret_cast<const unsigned long long *>(src), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+}
+__device__ __forceinline__ float partial_load_m2(const SegPartial *src)
+{
+    return __uint_as_float(__hip_atomic_load(reinterpret_cast<const unsigned *>(&src->m2), __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT));
+}
+
+struct FinalOut {
+    Selection *sel;              // [batch] what the final token of each prefix is drawn from (kept for inspection)
+    SegPartial *partial;         // [batch, nseg]
+    int32_t *counter;            // [batch] workgroups of the prefix that have stored their partial sums
+    double *res_norm, *u_final, *margin;
+    int32_t *fallback;
+    double *carry;
+    int32_t *mcount;
+};
 
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kSegThreads)
-k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Selection *__restrict__ sel,
-             int V, int K, int L, float c, int nseg, const SegPartial *__restrict__ partial,
-             uint64_t seed, uint64_t offset, int32_t *__restrict__ out_tokens,
-             double *__restrict__ res_norm, double *__restrict__ u_final, double *__restrict__ margin_out,
-             int32_t *__restrict__ fallback_out, double *__restrict__ carry_out, int32_t *__restrict__ mcount_out)
+k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, FinalOut fo, int V, int K, int L,
+        float c, int nseg, uint64_t seed, uint64_t offset)
 {
+    static_assert(kSegThreads == kDecideThreads, "the decision runs on the whole workgroup");
+    extern __shared__ double lds_decide[];
+    __shared__ Selection sh_sel;
+    __shared__ double sh_u;
+    __shared__ int sh_is_last;
     __shared__ double sh_d[kSegThreads / kWave];
     __shared__ double sh_scan[kSegThreads / kWave];
     __shared__ float sh_f[kSegThreads / kWave];
     __shared__ int sh_seg, sh_winner, sh_last_pos;
     __shared__ double sh_local_target, sh_total;
-    const int b = blockIdx.x, tid = threadIdx.x;
+    __shared__ float sh_seg_m2;
+    const int b = blockIdx.y, tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wid = tid / kWave;
-    const Selection sl = sel[b];
-    const SegPartial *pp = partial + static_cast<long long>(b) * nseg;
+    int32_t *__restrict__ out_tokens = io.out_tokens;
+    double *__restrict__ res_norm = fo.res_norm, *__restrict__ u_final = fo.u_final, *__restrict__ margin_out = fo.margin;
+    int32_t *__restrict__ fallback_out = fo.fallback, *__restrict__ mcount_out = fo.mcount;
+    double *__restrict__ carry_out = fo.carry;
 
-    // thread t owns the contiguous segments [t*chunk, (t+1)*chunk)
+    // ---- 1. decision (redundantly per workgroup; the first one of the prefix writes it out)
+    decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u);
+    const Selection sl = sh_sel;
+    if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
+
+    // ---- 2. partial sums of this workgroup's segments: kSegPerWave consecutive segments per wave
+    {
+        const int seg0 = (blockIdx.x * (kSegThreads / kWave) + wid) * kSegPerWave;
+        double sw[kSegPerWave], sq[kSegPerWave];
+        float m2[kSegPerWave];
+        float zq[kSegPerWave][8], zp[kSegPerWave][8];
+#pragma unroll
+        for (int i = 0; i < kSegPerWave; ++i)            // all loads first: one memory latency, not four
+            if (seg0 + i < nseg) segment_load<T, VEC>(target, draft, sl, V, seg0 + i, lane, zq[i], zp[i]);
+#pragma unroll
+        for (int i = 0; i < kSegPerWave; ++i) {
+            sw[i] = 0.0; sq[i] = 0.0; m2[i] = 0.0f;
+            if (seg0 + i < nseg) {                      // wave-uniform
+                float w[8], wq[8];
+                m2[i] = segment_weigh(sl, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[i], w, wq);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { sw[i] += static_cast<double>(w[j]); sq[i] += static_cast<double>(wq[j]); }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kSegPerWave; ++i) {
+            if (seg0 + i < nseg) {
+                const double a = wave_sum(sw[i]), bq = wave_sum(sq[i]);
+                if (lane == 0) partial_store(&fo.partial[static_cast<long long>(b) * nseg + seg0 + i], a, bq, m2[i]);
+            }
+        }
+    }
+    // ---- 3. the last workgroup of the prefix to get here locates the token.  The partial
+    // stores above are device-scope accesses; the workgroup-scope release fence waits until
+    // they have completed, the barrier orders them before the first thread's counter update.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0) {
+        const int arrived = __hip_atomic_fetch_add(&fo.counter[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sh_is_last = arrived == static_cast<int>(gridDim.x) - 1;
+    }
+    __syncthreads();
+    if (!sh_is_last) return;
+    const SegPartial *pp = fo.partial + static_cast<long long>(b) * nseg;
+
+    // thread t owns the contiguous segments [t*chunk, (t+1)*chunk); the first kKeep of them stay
+    // in registers (all of them up to V = 256K), later ones are read again when needed
+    constexpr int kKeep = 2;
     const int chunk = (nseg + kSegThreads - 1) / kSegThreads;
     const int s0 = tid * chunk, s1 = min(nseg, s0 + chunk);
+    float km2[kKeep];
+    double kw[kKeep], kq[kKeep];
     float mloc = -3.0e38f;
-    for (int s = s0; s < s1; ++s) mloc = fmaxf(mloc, pp[s].m2);
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+        km2[i] = -3.0e38f; kw[i] = 0.0; kq[i] = 0.0;
+        if (s0 + i < s1) {
+            km2[i] = partial_load_m2(&pp[s0 + i]);
+            kw[i] = partial_load_d(&pp[s0 + i].sum_w); kq[i] = partial_load_d(&pp[s0 + i].sum_q);
+            mloc = fmaxf(mloc, km2[i]);
+        }
+    }
+    for (int s = s0 + kKeep; s < s1; ++s) mloc = fmaxf(mloc, partial_load_m2(&pp[s]));
     const float M = block_max(mloc, sh_f);
     double tw = 0.0, tqs = 0.0;
-    for (int s = s0; s < s1; ++s) {
-        const int sh = static_cast<int>(pp[s].m2 - M);      // both integral, difference <= 0
-        tw += ldexp(pp[s].sum_w, sh); tqs += ldexp(pp[s].sum_q, sh);
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+        if (s0 + i < s1) {
+            const int sh = static_cast<int>(km2[i] - M);                       // both integral, difference <= 0
+            kw[i] = ldexp(kw[i], sh); kq[i] = ldexp(kq[i], sh);               // now relative to 2^M
+            tw += kw[i]; tqs += kq[i];
+        }
+    }
+    for (int s = s0 + kKeep; s < s1; ++s) {
+        const int sh = static_cast<int>(partial_load_m2(&pp[s]) - M);
+        tw += ldexp(partial_load_d(&pp[s].sum_w), sh); tqs += ldexp(partial_load_d(&pp[s].sum_q), sh);
     }
     const double Ww = block_sum(tw, sh_d);
     const double Wq = block_sum(tqs, sh_d);
     const bool use_q = !(Ww > 0.0);           // every residual weight is zero: draw from q
     const double W = use_q ? Wq : Ww;
-    const double u = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(K * L));
+    const double u = sh_u;
     const double goal = u * W;
 
     // first thread, then first segment, whose running total exceeds the goal
@@ -343,16 +479,29 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
     if (tid == win_t) {
         double cum = excl_t, cum_before = excl_t;
         int found = -1, last_pos = s0 < nseg ? s0 : 0;
+        float found_m2 = km2[0], last_m2 = km2[0];
         double cum_before_last = excl_t;
-        for (int s = s0; s < s1; ++s) {
-            const double v = ldexp(use_q ? pp[s].sum_q : pp[s].sum_w, static_cast<int>(pp[s].m2 - M));
-            if (v > 0.0) { last_pos = s; cum_before_last = cum; }
-            if (cum + v > goal) { found = s; cum_before = cum; break; }
-            cum += v;
+        bool open = true;
+#pragma unroll
+        for (int i = 0; i < kKeep; ++i) {
+            if (open && s0 + i < s1) {
+                const double v = use_q ? kq[i] : kw[i];
+                if (v > 0.0) { last_pos = s0 + i; last_m2 = km2[i]; cum_before_last = cum; }
+                if (cum + v > goal) { found = s0 + i; found_m2 = km2[i]; cum_before = cum; open = false; }
+                else cum += v;
+            }
         }
-        if (found < 0) { found = last_pos; cum_before = cum_before_last; }
-        const int up = static_cast<int>(M - pp[found].m2);
+        for (int s = s0 + kKeep; open && s < s1; ++s) {
+            const float m2s = partial_load_m2(&pp[s]);
+            const double v = ldexp(partial_load_d(use_q ? &pp[s].sum_q : &pp[s].sum_w), static_cast<int>(m2s - M));
+            if (v > 0.0) { last_pos = s; last_m2 = m2s; cum_before_last = cum; }
+            if (cum + v > goal) { found = s; found_m2 = m2s; cum_before = cum; open = false; }
+            else cum += v;
+        }
+        if (found < 0) { found = last_pos; found_m2 = last_m2; cum_before = cum_before_last; }
+        const int up = static_cast<int>(M - found_m2);
         sh_seg = found;
+        sh_seg_m2 = found_m2;
         sh_local_target = ldexp(goal - cum_before, up);    // goal in the segment's own scale
         sh_total = ldexp(W, up);
     }
@@ -363,7 +512,11 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
     const int seg = sh_seg;
     const double local_target = sh_local_target;
     float w[8], wq[8];
-    segment_weights<T, VEC>(target, draft, sl, V, K, c, seg, lane, pp[seg].m2, w, wq);
+    {
+        float zq[8], zp[8];
+        segment_load<T, VEC>(target, draft, sl, V, seg, lane, zq, zp);
+        segment_weigh(sl, V, K, c, seg, lane, sh_seg_m2, zq, zp, w, wq);
+    }
     double ws[8];
     double mine = 0.0;
 #pragma unroll
@@ -405,7 +558,7 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
         fallback_out[b] = use_q ? 1 : 0;
         // total weight in probability units: weights are relative to 2^M, the target row's
         // normaliser is 2^lse2_q (bonus row: the total is the normaliser itself)
-        res_norm[b] = sl.draft_row < 0 ? 1.0 : W * exp2(static_cast<double>(M) - sl.lse2_q);
+        res_norm[b] = sl.draft_row < 0 ? 1.0 : W * exp2_small(static_cast<double>(M) - sl.lse2_q);
         // Algorithm 2 conditions the next iteration on (t^tau, y): the block ratio extended by
         // the final token, ln [nu_tau q_tau[y] / p_tau[y]], and the number of rows it modifies
         double carry = 0.0;
@@ -420,36 +573,43 @@ k_res_locate(const T *__restrict__ target, const T *__restrict__ draft, const Se
 }
 
 template <typename T>
-hipError_t launch_sample_typed(const Problem &p)
+hipError_t launch_final_typed(const Problem &p)
 {
     const T *target = static_cast<const T *>(p.target);
     const T *draft = static_cast<const T *>(p.draft);
-    const Selection *sel = reinterpret_cast<const Selection *>(p.ws + p.lay.sel);
-    SegPartial *partial = reinterpret_cast<SegPartial *>(p.ws + p.lay.partial);
     const bool vec = (p.V % Elem<T>::kPerVec) == 0 &&
                      (reinterpret_cast<uintptr_t>(p.target) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(p.draft) % 16 == 0);
-    constexpr int kSegPerBlock = kSegThreads / kWave;
+    constexpr int kSegPerBlock = kSegThreads / kWave * kSegPerWave;
     const dim3 g(static_cast<unsigned>((p.lay.nseg + kSegPerBlock - 1) / kSegPerBlock), static_cast<unsigned>(p.batch));
-    double *res_norm = reinterpret_cast<double *>(p.ws + p.lay.res_norm);
-    double *u_final = reinterpret_cast<double *>(p.ws + p.lay.u_final);
-    double *margin = reinterpret_cast<double *>(p.ws + p.lay.margin);
-    int32_t *fallback = reinterpret_cast<int32_t *>(p.ws + p.lay.fallback);
-    double *carry = reinterpret_cast<double *>(p.ws + p.lay.carry);
-    int32_t *mcount = reinterpret_cast<int32_t *>(p.ws + p.lay.mcount);
-    if (vec) {
-        hipLaunchKernelGGL((k_res_partial<T, true>), g, dim3(kSegThreads), 0, p.stream, target, draft, sel,
-                           p.V, p.K, p.c, p.lay.nseg, partial);
-        hipLaunchKernelGGL((k_res_locate<T, true>), dim3(p.batch), dim3(kSegThreads), 0, p.stream, target,
-                           draft, sel, p.V, p.K, p.L, p.c, p.lay.nseg, partial, p.seed, p.offset,
-                           p.out_tokens, res_norm, u_final, margin, fallback, carry, mcount);
-    } else {
-        hipLaunchKernelGGL((k_res_partial<T, false>), g, dim3(kSegThreads), 0, p.stream, target, draft, sel,
-                           p.V, p.K, p.c, p.lay.nseg, partial);
-        hipLaunchKernelGGL((k_res_locate<T, false>), dim3(p.batch), dim3(kSegThreads), 0, p.stream, target,
-                           draft, sel, p.V, p.K, p.L, p.c, p.lay.nseg, partial, p.seed, p.offset,
-                           p.out_tokens, res_norm, u_final, margin, fallback, carry, mcount);
-    }
+    DecideIO io;
+    io.tokens = p.tokens;
+    io.stats = reinterpret_cast<const RowStat *>(p.ws + p.lay.stats);
+    io.s_arr = reinterpret_cast<const double *>(p.ws + p.lay.s);
+    io.log_nu_out = reinterpret_cast<double *>(p.ws + p.lay.log_nu);
+    io.log_P_out = reinterpret_cast<double *>(p.ws + p.lay.log_P);
+    io.h_out = reinterpret_cast<double *>(p.ws + p.lay.h);
+    io.eta_out = reinterpret_cast<double *>(p.ws + p.lay.eta);
+    io.state_out = reinterpret_cast<int32_t *>(p.ws + p.lay.state);
+    io.accepted_len = p.accepted_len; io.accepted_draft_idx = p.accepted_draft_idx; io.out_tokens = p.out_tokens;
+    FinalOut fo;
+    fo.sel = reinterpret_cast<Selection *>(p.ws + p.lay.sel);
+    fo.partial = reinterpret_cast<SegPartial *>(p.ws + p.lay.partial);
+    fo.counter = reinterpret_cast<int32_t *>(p.ws + p.lay.counter);
+    fo.res_norm = reinterpret_cast<double *>(p.ws + p.lay.res_norm);
+    fo.u_final = reinterpret_cast<double *>(p.ws + p.lay.u_final);
+    fo.margin = reinterpret_cast<double *>(p.ws + p.lay.margin);
+    fo.fallback = reinterpret_cast<int32_t *>(p.ws + p.lay.fallback);
+    fo.carry = reinterpret_cast<double *>(p.ws + p.lay.carry);
+    fo.mcount = reinterpret_cast<int32_t *>(p.ws + p.lay.mcount);
+    const int KL = p.K * p.L;
+    const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
+    if (vec)
+        hipLaunchKernelGGL((k_final<T, true>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K,
+                           p.L, p.c, p.lay.nseg, p.seed, p.offset);
+    else
+        hipLaunchKernelGGL((k_final<T, false>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K,
+                           p.L, p.c, p.lay.nseg, p.seed, p.offset);
     return hipGetLastError();
 }
 
@@ -457,21 +617,7 @@ hipError_t launch_sample_typed(const Problem &p)
 
 hipError_t launch_decide_and_sample(const Problem &p)
 {
-    const int KL = p.K * p.L;
-    const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
-    hipLaunchKernelGGL(k_decide, dim3(p.batch), dim3(kDecideThreads), lds, p.stream, p.tokens, p.K, p.L, p.seed,
-                       p.offset, reinterpret_cast<const RowStat *>(p.ws + p.lay.stats),
-                       reinterpret_cast<const double *>(p.ws + p.lay.s),
-                       reinterpret_cast<double *>(p.ws + p.lay.log_nu),
-                       reinterpret_cast<double *>(p.ws + p.lay.log_P),
-                       reinterpret_cast<double *>(p.ws + p.lay.h),
-                       reinterpret_cast<double *>(p.ws + p.lay.eta),
-                       reinterpret_cast<int32_t *>(p.ws + p.lay.state),
-                       reinterpret_cast<Selection *>(p.ws + p.lay.sel), p.accepted_len,
-                       p.accepted_draft_idx, p.out_tokens);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    return p.dtype == 1 ? launch_sample_typed<uint16_t>(p) : launch_sample_typed<float>(p);
+    return p.dtype == 1 ? launch_final_typed<uint16_t>(p) : launch_final_typed<float>(p);
 }
 
 }  // namespace specgbv

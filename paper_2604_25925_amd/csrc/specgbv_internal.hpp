@@ -26,6 +26,8 @@ struct Workspace {
     size_t fallback;   // int32  [B]
     size_t carry;      // double [B]  ln of q(t^tau, y) / p(t^tau, y) for Algorithm 2 (0 when tau = L)
     size_t mcount;     // int32  [B]  L - tau - 1 rows of the next iteration to modify (0 when tau >= L - 1)
+    size_t counter;    // int32  [B]  final-token workgroups that have stored their partial sums; zeroed by the
+                       //             streaming kernels of every call
     size_t total;
     int nseg;
 };
@@ -65,8 +67,10 @@ hipError_t launch_chain_main(const Problem &p);
 hipError_t launch_decide_and_sample(const Problem &p);
 
 // Distribution modification (Algorithm 2); all pointers are device pointers, optional ones may be null.
-hipError_t launch_modify(const void *target, const void *draft, const int32_t *tokens, int K, int M, int V, int batch,
-                         int dtype, float c, const double *carry, const int32_t *count, float *out_logq,
-                         float *out_logp, double *norm_out, int32_t *fallback_out, hipStream_t stream);
+// `ws` holds modify_workspace_bytes(batch, K, M, bonus) bytes.
+size_t modify_workspace_bytes(int batch, int K, int M, int bonus);
+hipError_t launch_modify(const void *target, const void *draft, const int32_t *tokens, int K, int M, int bonus, int V,
+                         int batch, int dtype, float c, const double *carry, const int32_t *count, float *out_logq,
+                         float *out_logp, double *norm_out, int32_t *fallback_out, char *ws, hipStream_t stream);
 
 }  // namespace specgbv

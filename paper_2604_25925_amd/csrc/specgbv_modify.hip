@@ -6,173 +6,311 @@
 //     q_new[x] = w[x] / sum_x w[x],   w[x] = q_r[x] max(1 - p_r[x] / (nu q_r[x]), 0)^K
 // (Algorithm 2 divided through by the joint probability of the conditioning block: the same
 // per-token form as Eq. (pres)), with nu = [q(t^tau, y) / p(t^tau, y)] continued along the new
-// draft's own tokens with the original target probabilities.  One workgroup walks the rows of
-// one (prefix, draft) pair, because row r needs the normalisers of rows < r; per row it makes
-// three passes (statistics, normaliser of w, write), the second and third over lines it has
-// just read.  Output: natural-log probabilities in float32 (-inf where the probability is 0).
+// draft's own tokens with the original target probabilities.
+//
+// Three streaming kernels, each with one workgroup per row (pair), so that any batch size
+// fills the chip:
+//   k_mod_stats : per row, log2 sum_x 2^(c z[x]) and the drafted token's scaled logit
+//   k_mod_norm  : per modified row pair, nu (a prefix sum over the statistics of the rows
+//                 before it) and the normaliser sum_x w[x]
+//   k_mod_write : per row pair, natural-log probabilities in float32 (-inf where the
+//                 probability is 0): ln q_new for modified rows, ln q otherwise, and ln p.
+// An optional extra target row (the bonus row of the verification) is converted to
+// log-probabilities as well, so that the whole output can be verified at temperature 1.
 #include "specgbv_internal.hpp"
 
 namespace specgbv {
 namespace {
 
 constexpr int kModThreads = 512;
-constexpr int kModWaves = kModThreads / kWave;
 
-struct Pair { double a, b; };
+struct ModStat { double lse2, tok2; };       // base-2 log-normaliser, scaled logit of the row's token
 
-// Two workgroup-wide double sums; every thread gets both (wave-uniform values in SGPR-friendly form).
-__device__ __forceinline__ Pair block_sum_pair(double a, double b, double *scratch)
+// Workspace of one call: statistics of the target rows, of the draft rows, normalisers, flags.
+struct ModLayout {
+    size_t tstat, dstat, norm, fb, total;
+};
+__host__ __device__ inline size_t mod_align(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+inline ModLayout mod_layout(int batch, int K, int M, int bonus)
 {
-    const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
-    a = wave_sum(a); b = wave_sum(b);
-    __syncthreads();
-    if (lane == 0) { scratch[2 * wid] = a; scratch[2 * wid + 1] = b; }
-    __syncthreads();
-    Pair r{0.0, 0.0};
-#pragma unroll
-    for (int w = 0; w < kModWaves; ++w) { r.a += scratch[2 * w]; r.b += scratch[2 * w + 1]; }
-    return r;
+    ModLayout l{};
+    const size_t bk = static_cast<size_t>(batch) * K;
+    size_t off = 0;
+    l.tstat = off; off = mod_align(off + bk * (M + bonus) * sizeof(ModStat));
+    l.dstat = off; off = mod_align(off + bk * M * sizeof(ModStat));
+    l.norm = off; off = mod_align(off + bk * M * sizeof(double));
+    l.fb = off; off = mod_align(off + bk * M * sizeof(int32_t));
+    l.total = off;
+    return l;
 }
 
-// Applies f(x0, zq[8 or fewer], zp[...], n) to consecutive groups of the row pair.
-template <typename T, bool VEC, typename F>
-__device__ __forceinline__ void for_each_group(const T *rq, const T *rp, int V, F f)
+// Per-thread running sum of 2^(c z - m2) with a running reference exponent m2 (updated once
+// per 16-byte vector; the partial sum is rescaled when the reference moves).
+struct RunningSum {
+    float m2 = -3.0e38f;          // finite, so that -inf logits give 2^(-inf) = 0, not NaN
+    float Z = 0.0f;
+    template <int N>
+    __device__ __forceinline__ void add(const float (&z)[N], float c) {
+        float vm = z[0];
+#pragma unroll
+        for (int j = 1; j < N; ++j) vm = fmaxf(vm, z[j]);
+        const float n2 = fmaxf(m2, vm * c);
+        float a = 0.0f;
+#pragma unroll
+        for (int j = 0; j < N; ++j) a += exp2_fast(fmaf(z[j], c, -n2));
+        Z = fmaf(Z, exp2_fast(m2 - n2), a);
+        m2 = n2;
+    }
+};
+
+// grid.x = target rows followed by draft rows
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kModThreads)
+k_mod_stats(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
+            int M, int bonus, int V, float c, long long n_trows, ModStat *__restrict__ tstat,
+            ModStat *__restrict__ dstat)
 {
+    __shared__ double sh_d[kModThreads / kWave];
+    __shared__ float sh_f[kModThreads / kWave];
+    const long long id = blockIdx.x;
+    const bool is_draft = id >= n_trows;
+    const long long row = is_draft ? id - n_trows : id;
+    const T *z_row = (is_draft ? draft : target) + row * static_cast<long long>(V);
+    const int rows_t = M + bonus;
+    const int r = static_cast<int>(row % (is_draft ? M : rows_t));
+    const long long bk = row / (is_draft ? M : rows_t);
     constexpr int PV = Elem<T>::kPerVec;
+    RunningSum acc;
     if (VEC) {
         const int nvec = V / PV;
-        for (int v = threadIdx.x; v < nvec; v += kModThreads) {
-            float zq[PV], zp[PV];
-            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
-            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
-#pragma unroll
-            for (int j = 0; j < PV; ++j) f(v * PV + j, zq[j], zp[j]);
+        int v = threadIdx.x;
+        for (; v + kModThreads < nvec; v += 2 * kModThreads) {          // two loads in flight per thread
+            const U4 a = load16(z_row + static_cast<long long>(v) * PV);
+            const U4 b = load16(z_row + static_cast<long long>(v + kModThreads) * PV);
+            float z[PV];
+            Elem<T>::unpack(a, z); acc.add(z, c);
+            Elem<T>::unpack(b, z); acc.add(z, c);
+        }
+        if (v < nvec) {
+            float z[PV];
+            Elem<T>::unpack(load16(z_row + static_cast<long long>(v) * PV), z);
+            acc.add(z, c);
         }
     } else {
-        for (int x = threadIdx.x; x < V; x += kModThreads) f(x, Elem<T>::scalar(rq + x), Elem<T>::scalar(rp + x));
+        for (int x = threadIdx.x; x < V; x += kModThreads) {
+            const float z[1] = {Elem<T>::scalar(z_row + x)};
+            acc.add(z, c);
+        }
+    }
+    const float Mx = block_max(acc.m2, sh_f);
+    const double total = block_sum(static_cast<double>(acc.Z * exp2_fast(acc.m2 - Mx)), sh_d);
+    if (threadIdx.x == 0) {
+        ModStat st;
+        st.lse2 = static_cast<double>(Mx) + log2(total);
+        st.tok2 = 0.0;
+        if (r < M) {                                   // the bonus row has no token
+            int tok = tokens[bk * M + r];
+            tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+            st.tok2 = static_cast<double>(Elem<T>::scalar(z_row + tok)) * static_cast<double>(c);
+        }
+        (is_draft ? dstat : tstat)[row] = st;
     }
 }
 
+// log2 of the block ratio in front of row r of draft bk: the carried ratio times the token
+// ratios of rows 0..r-1 (original target probabilities).
+__device__ __forceinline__ double mod_log2nu(const ModStat *tstat, const ModStat *dstat, long long bk, int rows_t,
+                                             int M, int r, double carry_ln)
+{
+    double l = carry_ln * 1.44269504088896340736;
+    for (int j = 0; j < r; ++j) {
+        const ModStat a = tstat[bk * rows_t + j], b = dstat[bk * M + j];
+        l += (a.tok2 - a.lse2) - (b.tok2 - b.lse2);
+    }
+    return l;
+}
+
+template <typename T, bool VEC, typename F>
+__device__ __forceinline__ void for_each_pair(const T *rq, const T *rp, int V, F f)
+{
+    constexpr int PV = Elem<T>::kPerVec;
+    if constexpr (VEC) {
+        const int nvec = V / PV;
+        int v = threadIdx.x;
+        for (; v + kModThreads < nvec; v += 2 * kModThreads) {          // four loads in flight per thread
+            const U4 q0 = load16(rq + static_cast<long long>(v) * PV), p0 = load16(rp + static_cast<long long>(v) * PV);
+            const U4 q1 = load16(rq + static_cast<long long>(v + kModThreads) * PV);
+            const U4 p1 = load16(rp + static_cast<long long>(v + kModThreads) * PV);
+            float zq[PV], zp[PV];
+            Elem<T>::unpack(q0, zq); Elem<T>::unpack(p0, zp); f(v * PV, zq, zp);
+            Elem<T>::unpack(q1, zq); Elem<T>::unpack(p1, zp); f((v + kModThreads) * PV, zq, zp);
+        }
+        if (v < nvec) {
+            float zq[PV], zp[PV];
+            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
+            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
+            f(v * PV, zq, zp);
+        }
+    } else {
+        for (int x = threadIdx.x; x < V; x += kModThreads) {
+            const float zq[1] = {Elem<T>::scalar(rq + x)}, zp[1] = {Elem<T>::scalar(rp + x)};
+            f(x, zq, zp);
+        }
+    }
+}
+
+// grid.x = batch * K * M; row pairs with r >= count leave at once
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kModThreads)
-k_modify(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
-         int K, int M, int V, float c, const double *__restrict__ carry_log_nu,
-         const int32_t *__restrict__ modify_count, float *__restrict__ out_logq, float *__restrict__ out_logp,
-         double *__restrict__ norm_out, int32_t *__restrict__ fallback_out)
+k_mod_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, int M, int bonus, int V, float c,
+           const double *__restrict__ carry_log_nu, const int32_t *__restrict__ modify_count,
+           const ModStat *__restrict__ tstat, const ModStat *__restrict__ dstat, double *__restrict__ norm,
+           int32_t *__restrict__ fb_out)
 {
-    __shared__ double sh_d[2 * kModWaves];
-    __shared__ float sh_f[2 * kModWaves];
-    constexpr double kLn2 = 0.693147180559945309417, kLog2e = 1.44269504088896340736;
-    const long long bk = blockIdx.x;
+    __shared__ double sh_d[kModThreads / kWave];
+    const long long drow = blockIdx.x;
+    const int r = static_cast<int>(drow % M);
+    const long long bk = drow / M;
     const int b = static_cast<int>(bk / K);
-    int count = modify_count[b];
-    count = count < 0 ? 0 : (count > M ? M : count);
-    double log2nu = carry_log_nu[b] * kLog2e;
-
-    for (int r = 0; r < M; ++r) {
-        const long long row = bk * M + r;
-        const T *rq = target + row * static_cast<long long>(V);
-        const T *rp = draft + row * static_cast<long long>(V);
-
-        // ---- pass 1: row maxima, then the normalisers relative to them
-        float mq = -3.0e38f, mp = -3.0e38f;
-        for_each_group<T, VEC>(rq, rp, V, [&](int, float zq, float zp) { mq = fmaxf(mq, zq); mp = fmaxf(mp, zp); });
-        mq = wave_max(mq); mp = wave_max(mp);
-        __syncthreads();
-        if ((threadIdx.x & (kWave - 1)) == 0) { sh_f[2 * (threadIdx.x / kWave)] = mq; sh_f[2 * (threadIdx.x / kWave) + 1] = mp; }
-        __syncthreads();
-        mq = sh_f[0]; mp = sh_f[1];
+    const int rows_t = M + bonus;
+    if (r >= modify_count[b]) {                       // uniform over the workgroup
+        if (threadIdx.x == 0) { norm[drow] = 1.0; fb_out[drow] = 0; }
+        return;
+    }
+    const ModStat sq = tstat[bk * rows_t + r], sp = dstat[drow];
+    const float shift_q = static_cast<float>(sq.lse2);
+    const RatioConst rc(sp.lse2 - sq.lse2 + mod_log2nu(tstat, dstat, bk, rows_t, M, r, carry_log_nu[b]));
+    const T *rq = target + (bk * rows_t + r) * static_cast<long long>(V);
+    const T *rp = draft + drow * static_cast<long long>(V);
+    constexpr int N = VEC ? Elem<T>::kPerVec : 1;
+    float acc = 0.0f;
+    for_each_pair<T, VEC>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
 #pragma unroll
-        for (int w = 1; w < kModWaves; ++w) { mq = fmaxf(mq, sh_f[2 * w]); mp = fmaxf(mp, sh_f[2 * w + 1]); }
-        const float ref_q = mq * c, ref_p = mp * c;
-        float Zq = 0.0f, Zp = 0.0f;
-        for_each_group<T, VEC>(rq, rp, V, [&](int, float zq, float zp) {
-            Zq += exp2_fast(fmaf(zq, c, -ref_q));
-            Zp += exp2_fast(fmaf(zp, c, -ref_p));
-        });
-        const Pair Z = block_sum_pair(static_cast<double>(Zq), static_cast<double>(Zp), sh_d);
-        const double lse2_q = static_cast<double>(ref_q) + log2(Z.a), lse2_p = static_cast<double>(ref_p) + log2(Z.b);
-        // log2 q[x] = fma(z, c, -sq) - dq with a float reference sq and its float64 remainder dq
-        const float sq = static_cast<float>(lse2_q), sp = static_cast<float>(lse2_p);
-        const float dq = static_cast<float>(lse2_q - static_cast<double>(sq));
-        const float dp = static_cast<float>(lse2_p - static_cast<double>(sp));
+        for (int j = 0; j < N; ++j)
+            acc = fmaf(exp2_fast(fmaf(zq[j], c, -shift_q)), powi_uniform(rc.one_minus_ratio(zp[j] - zq[j], c), K), acc);
+    });
+    const double S = block_sum(static_cast<double>(acc), sh_d);           // relative to 2^shift_q
+    if (threadIdx.x == 0) {
+        const double W = S * exp2(static_cast<double>(shift_q) - sq.lse2);
+        const bool zero = !(W > 0.0);                // every weight is zero: the row stays q
+        norm[drow] = zero ? 1.0 : W;
+        fb_out[drow] = zero ? 1 : 0;
+    }
+}
 
-        float *oq = out_logq + row * static_cast<long long>(V);
-        float *op = out_logp ? out_logp + row * static_cast<long long>(V) : nullptr;
-        const bool modified = r < count;
-        double W = 1.0;
-        int fb = 0;
-        if (modified) {
-            // ---- pass 2: normaliser of the weights
-            const RatioConst rc(lse2_p - lse2_q + log2nu);
-            float acc = 0.0f;
-            for_each_group<T, VEC>(rq, rp, V, [&](int, float zq, float zp) {
-                const float eq = exp2_fast(fmaf(zq, c, -sq));
-                acc = fmaf(eq, powi_uniform(rc.one_minus_ratio(zp - zq, c), K), acc);
-            });
-            const Pair S = block_sum_pair(static_cast<double>(acc), 0.0, sh_d);
-            W = S.a * exp2(static_cast<double>(sq) - lse2_q);
-            fb = !(W > 0.0);
-            if (fb) W = 1.0;
-            // ---- pass 3: ln q_new = ln q + K ln t - ln W (all-zero weights: the row stays q)
-            const float log2W = fb ? 0.0f : static_cast<float>(log2(S.a));     // relative to 2^sq like acc
-            const float Kf = static_cast<float>(K);
-            for_each_group<T, VEC>(rq, rp, V, [&](int x, float zq, float zp) {
-                const float x2 = fmaf(zq, c, -sq);
-                float l2;
-                if (fb) l2 = x2 - dq;
-                else l2 = fmaf(Kf, __log2f(rc.one_minus_ratio(zp - zq, c)), x2) - log2W;
-                oq[x] = l2 * static_cast<float>(kLn2);
-                if (op) op[x] = (fmaf(zp, c, -sp) - dp) * static_cast<float>(kLn2);
-            });
-        } else {
-            for_each_group<T, VEC>(rq, rp, V, [&](int x, float zq, float zp) {
-                oq[x] = (fmaf(zq, c, -sq) - dq) * static_cast<float>(kLn2);
-                if (op) op[x] = (fmaf(zp, c, -sp) - dp) * static_cast<float>(kLn2);
-            });
-        }
-        if (threadIdx.x == 0) {
-            if (norm_out) norm_out[row] = W;
-            if (fallback_out) fallback_out[row] = fb;
-        }
-        // extend the block by this row's token
-        int tok = tokens[row];
-        tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-        const double tq = static_cast<double>(Elem<T>::scalar(rq + tok)) * static_cast<double>(c) - lse2_q;
-        const double tp = static_cast<double>(Elem<T>::scalar(rp + tok)) * static_cast<double>(c) - lse2_p;
-        log2nu += tq - tp;
+// 8 (or 4) consecutive floats of an output row
+template <int N>
+__device__ __forceinline__ void store_vals(float *dst, const float (&v)[N])
+{
+    if (N % 4 == 0) {
+#pragma unroll
+        for (int j = 0; j < N; j += 4) *reinterpret_cast<float4 *>(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < N; ++j) dst[j] = v[j];
+    }
+}
+
+// grid.x = batch * K * (M + bonus) target rows
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kModThreads)
+k_mod_write(const T *__restrict__ target, const T *__restrict__ draft, int K, int M, int bonus, int V, float c,
+            const double *__restrict__ carry_log_nu, const int32_t *__restrict__ modify_count,
+            const ModStat *__restrict__ tstat, const ModStat *__restrict__ dstat, const double *__restrict__ norm,
+            const int32_t *__restrict__ fb_in, float *__restrict__ out_logq, float *__restrict__ out_logp)
+{
+    constexpr float kLn2f = 0.693147180559945309417f;
+    const long long trow = blockIdx.x;
+    const int rows_t = M + bonus;
+    const int r = static_cast<int>(trow % rows_t);
+    const long long bk = trow / rows_t;
+    const int b = static_cast<int>(bk / K);
+    const bool has_draft = r < M;
+    const long long drow = bk * M + (has_draft ? r : M - 1);          // bonus row: any valid draft row, unused
+    const ModStat sq = tstat[trow], sp = dstat[drow];
+    // log2 q[x] = fma(z, c, -hq) - dq with a float reference hq and its float64 remainder dq
+    const float hq = static_cast<float>(sq.lse2), hp = static_cast<float>(sp.lse2);
+    const float dq = static_cast<float>(sq.lse2 - static_cast<double>(hq));
+    const float dp = static_cast<float>(sp.lse2 - static_cast<double>(hp));
+    const bool modified = has_draft && r < modify_count[b] && fb_in[drow] == 0;
+    const T *rq = target + trow * static_cast<long long>(V);
+    const T *rp = has_draft ? draft + drow * static_cast<long long>(V) : rq;   // bonus row: no second stream
+    float *oq = out_logq + trow * static_cast<long long>(V);
+    float *op = (out_logp && has_draft) ? out_logp + drow * static_cast<long long>(V) : nullptr;
+    constexpr int N = VEC ? Elem<T>::kPerVec : 1;
+    if (modified) {
+        // ln q_new = ln q + K ln t - ln W
+        const RatioConst rc(sp.lse2 - sq.lse2 + mod_log2nu(tstat, dstat, bk, rows_t, M, r, carry_log_nu[b]));
+        const float log2W = static_cast<float>(log2(norm[drow]) + sq.lse2 - static_cast<double>(hq));   // relative to 2^hq
+        const float Kf = static_cast<float>(K);
+        for_each_pair<T, VEC>(rq, rp, V, [&](int x, const float (&zq)[N], const float (&zp)[N]) {
+            float a[N], bb[N];
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                a[j] = (fmaf(Kf, __log2f(rc.one_minus_ratio(zp[j] - zq[j], c)), fmaf(zq[j], c, -hq)) - log2W) * kLn2f;
+                bb[j] = (fmaf(zp[j], c, -hp) - dp) * kLn2f;
+            }
+            store_vals(oq + x, a);
+            if (op) store_vals(op + x, bb);
+        });
+    } else {
+        for_each_pair<T, VEC>(rq, rp, V, [&](int x, const float (&zq)[N], const float (&zp)[N]) {
+            float a[N], bb[N];
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                a[j] = (fmaf(zq[j], c, -hq) - dq) * kLn2f;
+                bb[j] = (fmaf(zp[j], c, -hp) - dp) * kLn2f;
+            }
+            store_vals(oq + x, a);
+            if (op) store_vals(op + x, bb);
+        });
     }
 }
 
 template <typename T>
-hipError_t launch_modify_typed(const void *target, const void *draft, const int32_t *tokens, int K, int M, int V,
-                               int batch, float c, const double *carry, const int32_t *count, float *out_logq,
-                               float *out_logp, double *norm_out, int32_t *fallback_out, hipStream_t stream)
+hipError_t launch_modify_typed(const void *target_v, const void *draft_v, const int32_t *tokens, int K, int M,
+                               int bonus, int V, int batch, float c, const double *carry, const int32_t *count,
+                               float *out_logq, float *out_logp, double *norm_out, int32_t *fallback_out,
+                               char *ws, hipStream_t stream)
 {
-    const bool vec = (V % Elem<T>::kPerVec) == 0 && reinterpret_cast<uintptr_t>(target) % 16 == 0 &&
-                     reinterpret_cast<uintptr_t>(draft) % 16 == 0;
-    const dim3 grid(static_cast<unsigned>(static_cast<long long>(batch) * K));
-    if (vec)
-        hipLaunchKernelGGL((k_modify<T, true>), grid, dim3(kModThreads), 0, stream, static_cast<const T *>(target),
-                           static_cast<const T *>(draft), tokens, K, M, V, c, carry, count, out_logq, out_logp,
-                           norm_out, fallback_out);
-    else
-        hipLaunchKernelGGL((k_modify<T, false>), grid, dim3(kModThreads), 0, stream, static_cast<const T *>(target),
-                           static_cast<const T *>(draft), tokens, K, M, V, c, carry, count, out_logq, out_logp,
-                           norm_out, fallback_out);
+    const T *target = static_cast<const T *>(target_v), *draft = static_cast<const T *>(draft_v);
+    const ModLayout lay = mod_layout(batch, K, M, bonus);
+    ModStat *tstat = reinterpret_cast<ModStat *>(ws + lay.tstat), *dstat = reinterpret_cast<ModStat *>(ws + lay.dstat);
+    double *norm = norm_out ? norm_out : reinterpret_cast<double *>(ws + lay.norm);
+    int32_t *fb = fallback_out ? fallback_out : reinterpret_cast<int32_t *>(ws + lay.fb);
+    const bool vec = (V % Elem<T>::kPerVec) == 0 && reinterpret_cast<uintptr_t>(target_v) % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(draft_v) % 16 == 0 && reinterpret_cast<uintptr_t>(out_logq) % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(out_logp) % 16 == 0;
+    const long long bk = static_cast<long long>(batch) * K;
+    const long long n_t = bk * (M + bonus), n_d = bk * M;
+    const dim3 blk(kModThreads);
+#define SPECGBV_MOD_LAUNCH(VEC)                                                                                   \
+    do {                                                                                                          \
+        hipLaunchKernelGGL((k_mod_stats<T, VEC>), dim3(static_cast<unsigned>(n_t + n_d)), blk, 0, stream, target,  \
+                           draft, tokens, M, bonus, V, c, n_t, tstat, dstat);                                     \
+        hipLaunchKernelGGL((k_mod_norm<T, VEC>), dim3(static_cast<unsigned>(n_d)), blk, 0, stream, target, draft,  \
+                           K, M, bonus, V, c, carry, count, tstat, dstat, norm, fb);                              \
+        hipLaunchKernelGGL((k_mod_write<T, VEC>), dim3(static_cast<unsigned>(n_t)), blk, 0, stream, target, draft, \
+                           K, M, bonus, V, c, carry, count, tstat, dstat, norm, fb, out_logq, out_logp);          \
+    } while (0)
+    if (vec) SPECGBV_MOD_LAUNCH(true);
+    else SPECGBV_MOD_LAUNCH(false);
+#undef SPECGBV_MOD_LAUNCH
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_modify(const void *target, const void *draft, const int32_t *tokens, int K, int M, int V, int batch,
-                         int dtype, float c, const double *carry, const int32_t *count, float *out_logq,
-                         float *out_logp, double *norm_out, int32_t *fallback_out, hipStream_t stream)
+size_t modify_workspace_bytes(int batch, int K, int M, int bonus) { return mod_layout(batch, K, M, bonus).total; }
+
+hipError_t launch_modify(const void *target, const void *draft, const int32_t *tokens, int K, int M, int bonus, int V,
+                         int batch, int dtype, float c, const double *carry, const int32_t *count, float *out_logq,
+                         float *out_logp, double *norm_out, int32_t *fallback_out, char *ws, hipStream_t stream)
 {
-    return dtype == 1 ? launch_modify_typed<uint16_t>(target, draft, tokens, K, M, V, batch, c, carry, count, out_logq,
-                                                      out_logp, norm_out, fallback_out, stream)
-                      : launch_modify_typed<float>(target, draft, tokens, K, M, V, batch, c, carry, count, out_logq,
-                                                   out_logp, norm_out, fallback_out, stream);
+    return dtype == 1 ? launch_modify_typed<uint16_t>(target, draft, tokens, K, M, bonus, V, batch, c, carry, count,
+                                                      out_logq, out_logp, norm_out, fallback_out, ws, stream)
+                      : launch_modify_typed<float>(target, draft, tokens, K, M, bonus, V, batch, c, carry, count,
+                                                   out_logq, out_logp, norm_out, fallback_out, ws, stream);
 }
 
 }  // namespace specgbv

@@ -45,8 +45,8 @@ struct OnlineSum {
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kStatThreads)
 k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
-            const int32_t *__restrict__ tokens, int L, int V, float c,
-            RowStat *__restrict__ stats)
+            const int32_t *__restrict__ tokens, int K, int L, int V, float c,
+            RowStat *__restrict__ stats, int32_t *__restrict__ final_counter)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ float sh_f[kStatThreads / kWave];
@@ -54,6 +54,8 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
     const int r = static_cast<int>(pair % L);
     const long long bk = pair / L;
     const bool is_draft = blockIdx.y == 1;
+    if (threadIdx.x == 0 && !is_draft && pair % (static_cast<long long>(K) * L) == 0)
+        final_counter[pair / (static_cast<long long>(K) * L)] = 0;      // arrival counter of the final-token kernel
     const T *row = is_draft ? draft + (bk * L + r) * static_cast<long long>(V)
                             : target + (bk * (L + 1) + r) * static_cast<long long>(V);
     constexpr int PV = Elem<T>::kPerVec;
@@ -134,6 +136,7 @@ hipError_t launch_typed(const Problem &p)
     const T *draft = static_cast<const T *>(p.draft);
     RowStat *stats = reinterpret_cast<RowStat *>(p.ws + p.lay.stats);
     double *s = reinterpret_cast<double *>(p.ws + p.lay.s);
+    int32_t *counter = reinterpret_cast<int32_t *>(p.ws + p.lay.counter);
     const long long pairs = static_cast<long long>(p.batch) * p.K * p.L;
     const bool vec = (p.V % Elem<T>::kPerVec) == 0 &&
                      (reinterpret_cast<uintptr_t>(p.target) % 16 == 0) &&
@@ -141,10 +144,10 @@ hipError_t launch_typed(const Problem &p)
     const dim3 g1(static_cast<unsigned>(pairs), 2);
     if (vec)
         hipLaunchKernelGGL((k_row_stats<T, true>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
-                           p.tokens, p.L, p.V, p.c, stats);
+                           p.tokens, p.K, p.L, p.V, p.c, stats, counter);
     else
         hipLaunchKernelGGL((k_row_stats<T, false>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
-                           p.tokens, p.L, p.V, p.c, stats);
+                           p.tokens, p.K, p.L, p.V, p.c, stats, counter);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.L < 2) return e;
     const long long rows = static_cast<long long>(p.batch) * p.K * (p.L - 1);

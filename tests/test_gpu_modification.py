@@ -29,7 +29,7 @@ def _gpu_modify(t, d, tok, T, carry, count, want_logp=True):
     ct = torch.from_numpy(np.ascontiguousarray(count, dtype=np.int32)).cuda()
     res = sg.specgbv_modify_target(tl, dl, tk, T, cr, ct, want_logp=want_logp, want_norm=True)
     torch.cuda.synchronize()
-    return {k: v.cpu().numpy() for k, v in res.items()}
+    return {k: v.cpu().numpy() for k, v in res.items() if k != "workspace"}
 
 
 def _check_modify(t, d, tok, T, carry, count, label):
@@ -149,8 +149,7 @@ def test_two_iterations_carry_through_the_workspace():
     t2, d2, tok2 = make_inputs(w, seed=32)
     t2l, d2l, tk2 = to_torch(t2), to_torch(d2), to_torch(tok2)
     M = w.L
-    mod = sg.specgbv_modify_target(t2l[:, :, :M].contiguous(), d2l, tk2, T, carry_ptr, count_ptr, want_logp=True,
-                                   want_norm=True)
+    mod = sg.specgbv_modify_target(t2l, d2l, tk2, T, carry_ptr, count_ptr, want_logp=True, want_norm=True)
     torch.cuda.synchronize()
     inter = sg.specgbv_read_intermediates(ws, w.batch, w.K, w.L, w.V, 1)
     ora1 = oracle.verify(t1, d1, tok1, T, 17, 0, debug=True)
@@ -163,12 +162,14 @@ def test_two_iterations_carry_through_the_workspace():
     ora_mod = oracle.modify(np.ascontiguousarray(t2[:, :, :M]), d2, tok2, T, inter["carry_log_nu"], inter["modify_count"])
     np.testing.assert_allclose(mod["norm"].cpu().numpy(), ora_mod["norm"], rtol=RTOL)
     # stage 3: verification against the modified rows (float32 log-probabilities, temperature 1);
-    # the bonus row L is the unmodified target row, as log-probabilities
-    logq = mod["logq"].cpu().numpy()
+    # the bonus row L is the unmodified target row, converted to log-probabilities by the same call
+    tq = mod["logq"].cpu().numpy()
     logp = mod["logp"].cpu().numpy()
-    z = (t2[:, :, M].astype(np.uint32) << 16).view(np.float32).astype(np.float64) / np.float64(np.float32(T))
-    bonus = (z - np.log(np.exp(z - z.max(-1, keepdims=True)).sum(-1, keepdims=True)) - z.max(-1, keepdims=True))
-    tq = np.concatenate([logq, bonus[:, :, None, :].astype(np.float32)], axis=2)
+    assert tq.shape == (w.batch, w.K, M + 1, w.V)
+    z = (t2[:, :, M].astype(np.uint32) << 16).view(np.float32)
+    for b in range(w.batch):
+        lq, _ = oracle.log_softmax(z[b, 0], T)
+        np.testing.assert_allclose(tq[b, 0, M], lq, rtol=0, atol=3e-5)
     from parity_util import check_case
     rep, gpu, ora = check_case(np.ascontiguousarray(tq), np.ascontiguousarray(logp), tok2, 1.0, 17, 1, "auto",
                                "iteration 2 on modified rows")

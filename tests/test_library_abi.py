@@ -78,15 +78,20 @@ def test_modify_target_argument_errors():
     P = 1 << 20
 
     def call(**kw):
-        a = dict(t=P, d=P, tok=P, K=2, M=3, V=64, B=1, dt=0, T=1.0, carry=P, count=P, out=P)
+        a = dict(t=P, d=P, tok=P, K=2, M=3, bonus=0, V=64, B=1, dt=0, T=1.0, carry=P, count=P, out=P, ws=P,
+                 wsb=1 << 30)
         a.update(kw)
-        return lib.specgbv_modify_target(a["t"], a["d"], a["tok"], a["K"], a["M"], a["V"], a["B"], a["dt"],
-                                         ctypes.c_float(a["T"]), a["carry"], a["count"], a["out"], None, None, None, None)
+        return lib.specgbv_modify_target(a["t"], a["d"], a["tok"], a["K"], a["M"], a["bonus"], a["V"], a["B"], a["dt"],
+                                         ctypes.c_float(a["T"]), a["carry"], a["count"], a["out"], None, None, None,
+                                         a["ws"], a["wsb"], None)
     assert call(K=0) == 1 and call(M=0) == 1 and call(V=0) == 1 and call(B=-1) == 1
-    assert call(dt=2) == 1 and call(T=-1.0) == 1
+    assert call(dt=2) == 1 and call(T=-1.0) == 1 and call(bonus=2) == 1
     assert call(carry=None) == 1 and call(out=None) == 1 and call(t=None) == 1
-    assert call(K=65) == 2
+    assert call(K=65) == 2 and call(M=63) == 2
+    assert call(ws=None) == 3 and call(ws=P + 8) == 3 and call(wsb=64) == 3
     assert call(B=0) == 0
+    assert 0 < sg.specgbv_modify_workspace_bytes(32, 8, 8, 1) < 1 << 20
+    assert sg.specgbv_modify_workspace_bytes(32, 8, 0, 0) == 0
     a, b = ctypes.c_void_p(), ctypes.c_void_p()
     need = sg.specgbv_workspace_bytes(4, 2, 3, 64, 0)
     assert lib.specgbv_workspace_carry(P, need, 4, 2, 3, 64, ctypes.byref(a), ctypes.byref(b)) == 0
