@@ -91,6 +91,39 @@ def bench_modify(a, w, sg, torch, tl, dl, tk, ws, out):
     }
 
 
+def bench_sample(a, w, sg, torch, dl):
+    """One step = one specgbv_sample_tokens call: one token for each of the batch * K draft rows of one position."""
+    rows = dl[:, :, 0].contiguous().view(w.batch * w.K, w.V)
+    tok, ws = sg.specgbv_sample_tokens(rows, w.temperature, a.seed, 0, 0)
+    for i in range(a.warmup):
+        sg.specgbv_sample_tokens(rows, w.temperature, a.seed, i, 0, out=tok, workspace=ws)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    t0 = time.perf_counter()
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        sg.specgbv_sample_tokens(rows, w.temperature, a.seed, a.warmup + i, 0, out=tok, workspace=ws)
+        e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+    ker = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    avg = sum(ker) / len(ker)
+    n = w.batch * w.K
+    bytes_ = n * w.V * w.elem_bytes                         # every row once
+    achieved = bytes_ / (avg * 1e-3) / 1e9
+    return {
+        "metric": "draft tokens drawn/sec (Algorithm 3 drafting step) and achieved HBM GB/s (% of peak) at V=128256",
+        "value": n / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d draft rows (batch %d x K=%d) of one position, V=%d, %s logits, T=%g" % (
+            w.name, n, w.batch, w.K, w.V, w.dtype, w.temperature)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "k_zero_counters + k_final (sampler mode)",
+                     "kernel_ms_avg": avg, "kernel_ms_min": ker[0], "algorithmic_bytes_per_launch": bytes_},
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,9 +131,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--algo", default="auto", choices=["auto", "split", "chain"])
-    ap.add_argument("--op", default="verify", choices=["verify", "modify"],
+    ap.add_argument("--op", default="verify", choices=["verify", "modify", "sample"],
                     help="verify: the verification call (the benchmark); modify: the distribution modification "
-                         "(Algorithm 2) for the drafts of the next iteration, on the same tensors")
+                         "(Algorithm 2) for the drafts of the next iteration, on the same tensors; "
+                         "sample: the draft-side token draw of one position (Algorithm 3) over the batch * K draft rows")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -140,6 +174,9 @@ def main() -> int:
         sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, offset, workspace=ws, out=out, algo=a.algo,
                              events=events)
 
+    if a.op == "sample":
+        print(json.dumps(bench_sample(a, w, sg, torch, dl)))
+        return 0
     if a.op == "modify":
         print(json.dumps(bench_modify(a, w, sg, torch, tl, dl, tk, ws, out)))
         return 0

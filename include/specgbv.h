@@ -224,6 +224,41 @@ specgbv_status specgbv_modify_target(
 /* Bytes of device workspace specgbv_modify_target needs (0 if the shape is invalid). */
 size_t specgbv_modify_workspace_bytes(int batch, int K, int M, int bonus_row);
 
+/*
+ * Draft-side sampling (Algorithm 3, the step "sample x_1^L, ..., x_K^L ~ p i.i.d."): one token
+ * per row from softmax(logits[row, :] / temperature).  Called once per draft position with the
+ * batch * K draft rows of that position, it draws the K i.i.d. continuations of every prefix.
+ *
+ * The token of row r is the first id whose running weight sum exceeds u * total (the rule of
+ * the final token of specgbv_verify), with u the Philox4x32-10 uniform of key = rng_seed and
+ * counter = (rng_offset low, rng_offset high, r, 2^31 + position): slots at or above 2^31 are
+ * never used by specgbv_verify, so one (seed, offset) pair can serve a whole decoding iteration.
+ *
+ *   logits       device, [rows, V], dense; -inf entries have probability 0
+ *   rows, V      rows >= 0 (0: nothing is launched), rows <= 65535, V >= 1
+ *   position     draft position the rows belong to, below 2^31 (selects the Philox slot)
+ *   out_tokens   device out, [rows] int32
+ *   workspace    device, >= specgbv_sample_workspace_bytes(rows, V) bytes, 256-byte aligned,
+ *                contents need not be initialised
+ */
+specgbv_status specgbv_sample_tokens(
+    const void *logits, int rows, int V, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset, uint32_t position, int32_t *out_tokens,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device workspace specgbv_sample_tokens needs (0 if the shape is invalid). */
+size_t specgbv_sample_workspace_bytes(int rows, int V);
+
+/*
+ * Copies to HOST buffers (either may be NULL) the uniforms [rows] and the inverse-CDF margins
+ * [rows] (distance of u * total to the nearer end of the drawn token's interval, over total)
+ * of the last specgbv_sample_tokens call that used `workspace`, and waits for the copies.
+ * Debug/parity aid.
+ */
+specgbv_status specgbv_read_sample_intermediates(
+    const void *workspace, size_t workspace_bytes, int rows, int V,
+    double *u_host, double *margin_host, void *hip_stream);
+
 /* Message of the last failing call made by this thread ("" if none); static storage. */
 const char *specgbv_last_error(void);
 

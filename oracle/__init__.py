@@ -80,6 +80,9 @@ def lib() -> ctypes.CDLL:
                                             c_float, POINTER(c_double), POINTER(c_int32), POINTER(c_double),
                                             POINTER(c_double), POINTER(c_int32)]
         L.specgbv_oracle_modify.restype = c_int
+        L.specgbv_oracle_sample_rows.argtypes = [c_void_p, c_int, c_int, c_int, c_float, c_uint64, c_uint64, c_uint32,
+                                                 POINTER(c_int32), POINTER(c_double), POINTER(c_double)]
+        L.specgbv_oracle_sample_rows.restype = c_int
         L.specgbv_oracle_num_procs.argtypes = []
         L.specgbv_oracle_num_procs.restype = c_int
         _lib = L
@@ -234,6 +237,20 @@ def modify(target_logits: np.ndarray, draft_logits: np.ndarray, tokens: np.ndarr
                                      _dp(res["norm"]), _ip(res["fallback"]))
     if rc != 0:
         raise ValueError("specgbv_oracle_modify rejected its arguments (code %d)" % rc)
+    return res
+
+
+def sample_rows(logits: np.ndarray, temperature: float, rng_seed: int, rng_offset: int, position: int):
+    """The drafting step of Algorithm 3 on host arrays: one token per row of logits [rows, V]
+    (float32, or uint16 holding bfloat16 bits).  Returns tokens, the uniforms and the margins."""
+    lg, dt = to_raw(logits)
+    assert lg.ndim == 2
+    rows, V = lg.shape
+    res = {"tokens": np.full(rows, -9, np.int32), "u": np.full(rows, np.nan), "margin": np.full(rows, np.nan)}
+    rc = lib().specgbv_oracle_sample_rows(lg.ctypes.data_as(c_void_p), rows, V, dt, c_float(temperature), rng_seed,
+                                          rng_offset, position, _ip(res["tokens"]), _dp(res["u"]), _dp(res["margin"]))
+    if rc != 0:
+        raise ValueError("specgbv_oracle_sample_rows rejected its arguments (code %d)" % rc)
     return res
 
 

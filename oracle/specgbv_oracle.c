@@ -9,9 +9,9 @@
  * What it computes (paper, Section 4.2): Algorithm 1 "SpecTr-GBV" with the
  * acceptance probabilities of Eq. (hik) [sub-block] and Eq. (hLk) [whole
  * block] and the residual distribution of Eq. (pres), for a batch of
- * independent prefixes, and Algorithm 2 "Distribution Modification" (the
+ * independent prefixes, Algorithm 2 "Distribution Modification" (the
  * target distribution of the first L - tau - 1 positions of the next
- * iteration).  Everything is written in the order and notation of the paper;
+ * iteration), and the drafting step of Algorithm 3 (one token per draft row).  Everything is written in the order and notation of the paper;
  * there is no blocking, fusion or reordering.
  *
  * Notation.  For one prefix and one draft k: row r (0-based) of the target
@@ -560,5 +560,44 @@ int specgbv_oracle_modify(const void *target_logits, const void *draft_logits,
         }
     }
     free(z); free(lq); free(lp); free(w);
+    return 0;
+}
+
+/* ------------------------------------------- draft-side sampling (Algorithm 3) */
+
+/*
+ * The drafting step of Algorithm 3 ("sample x_1^L, ..., x_K^L ~ p i.i.d."): one token per row
+ * from p_r = softmax(z_r / T), by the same inverse-CDF rule as the final token,
+ *     y = min{ j : sum_{x<=j} p_r[x] > u },
+ * with u the Philox uniform of (seed, offset, row r, slot 2^31 + position): slots from 2^31
+ * upwards are never used by the verification, so the K drafts of a prefix (K rows with
+ * different row indices) get independent uniforms.
+ *
+ *   logits [rows, V] (dtype as in specgbv_oracle_verify), out_tokens [rows],
+ *   u_out, margin_out [rows] (may be NULL).  Returns 0, or 1 for invalid arguments.
+ */
+int specgbv_oracle_sample_rows(const void *logits, int rows, int V, int dtype,
+                               float temperature, uint64_t rng_seed, uint64_t rng_offset,
+                               uint32_t position, int32_t *out_tokens, double *u_out,
+                               double *margin_out)
+{
+    if (!logits || !out_tokens || rows < 0 || V < 1) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (!(temperature > 0.0f) || !isfinite(temperature) || position >= 0x80000000u) return 1;
+    const double T = (double)temperature;
+    double *z = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)V);
+    double *w = (double *)malloc(sizeof(double) * (size_t)V);
+    for (int r = 0; r < rows; ++r) {
+        load_row(logits, dtype, (size_t)r, V, z);
+        specgbv_oracle_log_softmax(z, V, T, lp);
+        for (int x = 0; x < V; ++x) w[x] = exp(lp[x]);
+        const double u = specgbv_oracle_uniform(rng_seed, rng_offset, (uint32_t)r, 0x80000000u + position);
+        double W = 0.0, margin = 0.0;
+        out_tokens[r] = specgbv_oracle_sample_cdf(w, V, u, &W, &margin);
+        if (u_out) u_out[r] = u;
+        if (margin_out) margin_out[r] = margin;
+    }
+    free(z); free(lp); free(w);
     return 0;
 }

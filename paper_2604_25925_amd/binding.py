@@ -21,7 +21,8 @@ ALGO_AUTO, ALGO_SPLIT, ALGO_CHAIN = 0, 1, 2
 _ALGO = {"auto": ALGO_AUTO, "split": ALGO_SPLIT, "chain": ALGO_CHAIN}
 
 EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_ex", "specgbv_read_intermediates",
-           "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_modify_workspace_bytes", "specgbv_last_error", "specgbv_version")
+           "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_modify_workspace_bytes", "specgbv_sample_tokens", "specgbv_sample_workspace_bytes",
+           "specgbv_read_sample_intermediates", "specgbv_last_error", "specgbv_version")
 
 
 class SpecGBVError(RuntimeError):
@@ -74,6 +75,14 @@ def load_library() -> ctypes.CDLL:
     L.specgbv_modify_target.restype = c_int
     L.specgbv_modify_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int]
     L.specgbv_modify_workspace_bytes.restype = c_size_t
+    L.specgbv_sample_tokens.argtypes = [c_void_p, c_int, c_int, c_int, c_float, c_uint64, c_uint64, ctypes.c_uint32,
+                                        c_void_p, c_void_p, c_size_t, c_void_p]
+    L.specgbv_sample_tokens.restype = c_int
+    L.specgbv_sample_workspace_bytes.argtypes = [c_int, c_int]
+    L.specgbv_sample_workspace_bytes.restype = c_size_t
+    L.specgbv_read_sample_intermediates.argtypes = [c_void_p, c_size_t, c_int, c_int, POINTER(c_double),
+                                                    POINTER(c_double), c_void_p]
+    L.specgbv_read_sample_intermediates.restype = c_int
     L.specgbv_last_error.argtypes = []
     L.specgbv_last_error.restype = c_char_p
     L.specgbv_version.argtypes = []
@@ -284,3 +293,44 @@ def specgbv_modify_target(target_logits, draft_logits, draft_tokens, temperature
                                    workspace.numel() * workspace.element_size(), stream)
     _check(st)
     return res
+
+
+def specgbv_sample_workspace_bytes(rows: int, V: int) -> int:
+    return int(load_library().specgbv_sample_workspace_bytes(rows, V))
+
+
+def specgbv_sample_tokens(logits, temperature: float, rng_seed: int, rng_offset: int, position: int, *, out=None,
+                          workspace=None, stream: Optional[int] = None):
+    """Enqueue the draw of one token per row of logits [rows, V] (or [..., V], flattened);
+    returns (tokens [rows] int32, workspace)."""
+    import torch
+    lib = load_library()
+    if not logits.is_cuda or not logits.is_contiguous() or logits.dim() < 2:
+        raise ValueError("logits must be a contiguous GPU tensor [rows, V]")
+    V = logits.shape[-1]
+    rows = logits.numel() // V if V else 0
+    dev = logits.device
+    if out is None:
+        out = torch.empty(rows, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(specgbv_sample_workspace_bytes(rows, V), 256), dtype=torch.uint8, device=dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    st = lib.specgbv_sample_tokens(logits.data_ptr(), rows, V, _dtype_code(logits), c_float(temperature), rng_seed,
+                                   rng_offset, position, out.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), stream)
+    _check(st)
+    return out, workspace
+
+
+def specgbv_read_sample_intermediates(workspace, rows: int, V: int, stream: Optional[int] = None) -> Dict[str, np.ndarray]:
+    import torch
+    lib = load_library()
+    if stream is None:
+        stream = torch.cuda.current_stream(workspace.device).cuda_stream
+    u, m = np.empty(rows, np.float64), np.empty(rows, np.float64)
+    st = lib.specgbv_read_sample_intermediates(workspace.data_ptr(), workspace.numel() * workspace.element_size(), rows,
+                                               V, u.ctypes.data_as(POINTER(c_double)), m.ctypes.data_as(POINTER(c_double)),
+                                               stream)
+    _check(st)
+    return {"u": u, "margin": m}

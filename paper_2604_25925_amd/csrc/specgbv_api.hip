@@ -274,6 +274,64 @@ specgbv_status specgbv_modify_target(
     return SPECGBV_OK;
 }
 
+static specgbv_status check_sample_shape(int rows, int V)
+{
+    if (rows < 0 || V < 1) return fail(SPECGBV_EINVAL, "bad shape rows=%d V=%d", rows, V);
+    if (rows > 65535) return fail(SPECGBV_EUNSUPPORTED, "rows=%d is too large for one launch (at most 65535)", rows);
+    return SPECGBV_OK;
+}
+
+size_t specgbv_sample_workspace_bytes(int rows, int V)
+{
+    if (check_sample_shape(rows, V) != SPECGBV_OK) return 0;
+    return make_workspace(rows < 1 ? 1 : rows, 1, 1, V).total;
+}
+
+specgbv_status specgbv_sample_tokens(
+    const void *logits, int rows, int V, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset, uint32_t position, int32_t *out_tokens,
+    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const specgbv_status st = check_sample_shape(rows, V);
+    if (st != SPECGBV_OK) return st;
+    if (dtype != SPECGBV_F32 && dtype != SPECGBV_BF16) return fail(SPECGBV_EINVAL, "unknown dtype %d", static_cast<int>(dtype));
+    if (!(temperature > 0.0f) || !std::isfinite(temperature)) return fail(SPECGBV_EINVAL, "temperature must be positive and finite");
+    if (position >= 0x80000000u) return fail(SPECGBV_EINVAL, "position must be below 2^31");
+    if (rows == 0) return SPECGBV_OK;
+    if (!logits || !out_tokens) return fail(SPECGBV_EINVAL, "null pointer");
+    const size_t esz = dtype == SPECGBV_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(logits) % esz || reinterpret_cast<uintptr_t>(out_tokens) % 4)
+        return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
+    const Workspace lay = make_workspace(rows, 1, 1, V);
+    if (!workspace) return fail(SPECGBV_EWORKSPACE, "workspace is null (need %zu bytes)", lay.total);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(SPECGBV_EWORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < lay.total) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, lay.total);
+    const float c = static_cast<float>(1.44269504088896340736 / static_cast<double>(temperature));
+    const hipError_t e = launch_sample_rows(logits, rows, V, dtype == SPECGBV_BF16 ? 1 : 0, c, rng_seed, rng_offset,
+                                            0x80000000u | position, out_tokens, static_cast<char *>(workspace), lay,
+                                            static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "sampling kernel launch: %s", hipGetErrorString(e));
+    return SPECGBV_OK;
+}
+
+specgbv_status specgbv_read_sample_intermediates(const void *workspace, size_t workspace_bytes, int rows, int V,
+                                                 double *u_host, double *margin_host, void *hip_stream)
+{
+    if (check_sample_shape(rows, V) != SPECGBV_OK || rows < 1) return fail(SPECGBV_EINVAL, "bad shape");
+    if (!workspace) return fail(SPECGBV_EINVAL, "null pointer");
+    const Workspace lay = make_workspace(rows, 1, 1, V);
+    if (workspace_bytes < lay.total) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, lay.total);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const char *ws = static_cast<const char *>(workspace);
+    hipError_t e = hipSuccess;
+    if (u_host) e = hipMemcpyAsync(u_host, ws + lay.u_final, rows * sizeof(double), hipMemcpyDeviceToHost, stream);
+    if (margin_host && e == hipSuccess)
+        e = hipMemcpyAsync(margin_host, ws + lay.margin, rows * sizeof(double), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "copy of the sampling intermediates: %s", hipGetErrorString(e));
+    return SPECGBV_OK;
+}
+
 const char *specgbv_last_error(void) { return g_err; }
 
 const char *specgbv_version(void) { return "specgbv 0.2 (gfx950)"; }

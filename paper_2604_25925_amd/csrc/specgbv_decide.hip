@@ -352,10 +352,13 @@ struct FinalOut {
     int32_t *mcount;
 };
 
-template <typename T, bool VEC>
+// SAMPLE = true turns the kernel into a plain row sampler (used for drawing draft tokens): no
+// decision, "prefix" b draws one token from softmax row b of `target` with the uniform of
+// Philox slot `sample_slot`, and the token goes to out_tokens[b] (the caller passes L = 0).
+template <typename T, bool VEC, bool SAMPLE>
 __global__ void __launch_bounds__(kSegThreads)
 k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, FinalOut fo, int V, int K, int L,
-        float c, int nseg, uint64_t seed, uint64_t offset)
+        float c, int nseg, uint64_t seed, uint64_t offset, uint32_t sample_slot)
 {
     static_assert(kSegThreads == kDecideThreads, "the decision runs on the whole workgroup");
     extern __shared__ double lds_decide[];
@@ -376,7 +379,17 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     double *__restrict__ carry_out = fo.carry;
 
     // ---- 1. decision (redundantly per workgroup; the first one of the prefix writes it out)
-    decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u);
+    if constexpr (SAMPLE) {
+        if (tid == 0) {
+            Selection s0;
+            s0.target_row = b; s0.draft_row = -1; s0.C2 = 0.0; s0.lse2_q = 0.0; s0.shift_q = 0.0f; s0.tau = 0;
+            sh_sel = s0;
+            sh_u = philox_uniform(seed, offset, static_cast<uint32_t>(b), sample_slot);
+        }
+        __syncthreads();
+    } else {
+        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u);
+    }
     const Selection sl = sh_sel;
     if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
 
@@ -572,6 +585,27 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     }
 }
 
+__global__ void k_zero_counters(int32_t *counter, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) counter[i] = 0;
+}
+
+FinalOut final_out(char *ws, const Workspace &lay)
+{
+    FinalOut fo;
+    fo.sel = reinterpret_cast<Selection *>(ws + lay.sel);
+    fo.partial = reinterpret_cast<SegPartial *>(ws + lay.partial);
+    fo.counter = reinterpret_cast<int32_t *>(ws + lay.counter);
+    fo.res_norm = reinterpret_cast<double *>(ws + lay.res_norm);
+    fo.u_final = reinterpret_cast<double *>(ws + lay.u_final);
+    fo.margin = reinterpret_cast<double *>(ws + lay.margin);
+    fo.fallback = reinterpret_cast<int32_t *>(ws + lay.fallback);
+    fo.carry = reinterpret_cast<double *>(ws + lay.carry);
+    fo.mcount = reinterpret_cast<int32_t *>(ws + lay.mcount);
+    return fo;
+}
+
 template <typename T>
 hipError_t launch_final_typed(const Problem &p)
 {
@@ -592,24 +626,36 @@ hipError_t launch_final_typed(const Problem &p)
     io.eta_out = reinterpret_cast<double *>(p.ws + p.lay.eta);
     io.state_out = reinterpret_cast<int32_t *>(p.ws + p.lay.state);
     io.accepted_len = p.accepted_len; io.accepted_draft_idx = p.accepted_draft_idx; io.out_tokens = p.out_tokens;
-    FinalOut fo;
-    fo.sel = reinterpret_cast<Selection *>(p.ws + p.lay.sel);
-    fo.partial = reinterpret_cast<SegPartial *>(p.ws + p.lay.partial);
-    fo.counter = reinterpret_cast<int32_t *>(p.ws + p.lay.counter);
-    fo.res_norm = reinterpret_cast<double *>(p.ws + p.lay.res_norm);
-    fo.u_final = reinterpret_cast<double *>(p.ws + p.lay.u_final);
-    fo.margin = reinterpret_cast<double *>(p.ws + p.lay.margin);
-    fo.fallback = reinterpret_cast<int32_t *>(p.ws + p.lay.fallback);
-    fo.carry = reinterpret_cast<double *>(p.ws + p.lay.carry);
-    fo.mcount = reinterpret_cast<int32_t *>(p.ws + p.lay.mcount);
+    const FinalOut fo = final_out(p.ws, p.lay);
     const int KL = p.K * p.L;
     const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
     if (vec)
-        hipLaunchKernelGGL((k_final<T, true>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K,
-                           p.L, p.c, p.lay.nseg, p.seed, p.offset);
+        hipLaunchKernelGGL((k_final<T, true, false>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V,
+                           p.K, p.L, p.c, p.lay.nseg, p.seed, p.offset, 0u);
     else
-        hipLaunchKernelGGL((k_final<T, false>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K,
-                           p.L, p.c, p.lay.nseg, p.seed, p.offset);
+        hipLaunchKernelGGL((k_final<T, false, false>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V,
+                           p.K, p.L, p.c, p.lay.nseg, p.seed, p.offset, 0u);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_sample_typed(const void *logits, int rows, int V, float c, uint64_t seed, uint64_t offset,
+                               uint32_t slot, int32_t *out_tokens, char *ws, const Workspace &lay, hipStream_t stream)
+{
+    const T *rowsp = static_cast<const T *>(logits);
+    const bool vec = (V % Elem<T>::kPerVec) == 0 && reinterpret_cast<uintptr_t>(logits) % 16 == 0;
+    constexpr int kSegPerBlock = kSegThreads / kWave * kSegPerWave;
+    const dim3 g(static_cast<unsigned>((lay.nseg + kSegPerBlock - 1) / kSegPerBlock), static_cast<unsigned>(rows));
+    DecideIO io{};
+    io.out_tokens = out_tokens;
+    const FinalOut fo = final_out(ws, lay);
+    hipLaunchKernelGGL(k_zero_counters, dim3((rows + 255) / 256), dim3(256), 0, stream, fo.counter, rows);
+    if (vec)
+        hipLaunchKernelGGL((k_final<T, true, true>), g, dim3(kSegThreads), 0, stream, rowsp, rowsp, io, fo, V, 1, 0, c,
+                           lay.nseg, seed, offset, slot);
+    else
+        hipLaunchKernelGGL((k_final<T, false, true>), g, dim3(kSegThreads), 0, stream, rowsp, rowsp, io, fo, V, 1, 0, c,
+                           lay.nseg, seed, offset, slot);
     return hipGetLastError();
 }
 
@@ -618,6 +664,13 @@ hipError_t launch_final_typed(const Problem &p)
 hipError_t launch_decide_and_sample(const Problem &p)
 {
     return p.dtype == 1 ? launch_final_typed<uint16_t>(p) : launch_final_typed<float>(p);
+}
+
+hipError_t launch_sample_rows(const void *logits, int rows, int V, int dtype, float c, uint64_t seed, uint64_t offset,
+                              uint32_t slot, int32_t *out_tokens, char *ws, const Workspace &lay, hipStream_t stream)
+{
+    return dtype == 1 ? launch_sample_typed<uint16_t>(logits, rows, V, c, seed, offset, slot, out_tokens, ws, lay, stream)
+                      : launch_sample_typed<float>(logits, rows, V, c, seed, offset, slot, out_tokens, ws, lay, stream);
 }
 
 }  // namespace specgbv
