@@ -24,6 +24,7 @@ namespace {
 
 constexpr int kDecideThreads = 256;
 constexpr int kSegPerWave = 4;               // residual segments per wave of the final-token kernel
+constexpr int kSegPerWaveSampler = 8;        // ... in its sampler mode (whole rows, nothing else to wait for)
 
 // ---------------------------------------------------------------- k_decide
 
@@ -355,7 +356,7 @@ struct FinalOut {
 // SAMPLE = true turns the kernel into a plain row sampler (used for drawing draft tokens): no
 // decision, "prefix" b draws one token from softmax row b of `target` with the uniform of
 // Philox slot `sample_slot`, and the token goes to out_tokens[b] (the caller passes L = 0).
-template <typename T, bool VEC, bool SAMPLE>
+template <typename T, bool VEC, bool SAMPLE, int SPW>
 __global__ void __launch_bounds__(kSegThreads)
 k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, FinalOut fo, int V, int K, int L,
         float c, int nseg, uint64_t seed, uint64_t offset, uint32_t sample_slot)
@@ -393,29 +394,29 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     const Selection sl = sh_sel;
     if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
 
-    // ---- 2. partial sums of this workgroup's segments: kSegPerWave consecutive segments per wave
+    // ---- 2. partial sums of this workgroup's segments: SPW consecutive segments per wave
     {
-        const int seg0 = (blockIdx.x * (kSegThreads / kWave) + wid) * kSegPerWave;
-        double sw[kSegPerWave], sq[kSegPerWave];
-        float m2[kSegPerWave];
-        float zq[kSegPerWave][8], zp[kSegPerWave][8];
+        const int seg0 = (blockIdx.x * (kSegThreads / kWave) + wid) * SPW;
+        double sw[SPW], sq[SPW];
+        float m2[SPW];
+        float zq[SPW][8], zp[SAMPLE ? 1 : SPW][8];   // the sampler has no draft row
 #pragma unroll
-        for (int i = 0; i < kSegPerWave; ++i)            // all loads first: one memory latency, not four
-            if (seg0 + i < nseg) segment_load<T, VEC>(target, draft, sl, V, seg0 + i, lane, zq[i], zp[i]);
+        for (int i = 0; i < SPW; ++i)            // all loads first: one memory latency, not four
+            if (seg0 + i < nseg) segment_load<T, VEC>(target, draft, sl, V, seg0 + i, lane, zq[i], zp[SAMPLE ? 0 : i]);
 #pragma unroll
-        for (int i = 0; i < kSegPerWave; ++i) {
+        for (int i = 0; i < SPW; ++i) {
             sw[i] = 0.0; sq[i] = 0.0; m2[i] = 0.0f;
             if (seg0 + i < nseg) {                      // wave-uniform
                 float w[8], wq[8];
-                m2[i] = segment_weigh(sl, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[i], w, wq);
+                m2[i] = segment_weigh(sl, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[SAMPLE ? 0 : i], w, wq);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) { sw[i] += static_cast<double>(w[j]); sq[i] += static_cast<double>(wq[j]); }
             }
         }
 #pragma unroll
-        for (int i = 0; i < kSegPerWave; ++i) {
+        for (int i = 0; i < SPW; ++i) {
             if (seg0 + i < nseg) {
-                const double a = wave_sum(sw[i]), bq = wave_sum(sq[i]);
+                const double a = wave_sum(sw[i]), bq = SAMPLE ? a : wave_sum(sq[i]);   // sampler: w is q
                 if (lane == 0) partial_store(&fo.partial[static_cast<long long>(b) * nseg + seg0 + i], a, bq, m2[i]);
             }
         }
@@ -630,10 +631,10 @@ hipError_t launch_final_typed(const Problem &p)
     const int KL = p.K * p.L;
     const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
     if (vec)
-        hipLaunchKernelGGL((k_final<T, true, false>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V,
+        hipLaunchKernelGGL((k_final<T, true, false, kSegPerWave>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V,
                            p.K, p.L, p.c, p.lay.nseg, p.seed, p.offset, 0u);
     else
-        hipLaunchKernelGGL((k_final<T, false, false>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V,
+        hipLaunchKernelGGL((k_final<T, false, false, kSegPerWave>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V,
                            p.K, p.L, p.c, p.lay.nseg, p.seed, p.offset, 0u);
     return hipGetLastError();
 }
@@ -644,17 +645,17 @@ hipError_t launch_sample_typed(const void *logits, int rows, int V, float c, uin
 {
     const T *rowsp = static_cast<const T *>(logits);
     const bool vec = (V % Elem<T>::kPerVec) == 0 && reinterpret_cast<uintptr_t>(logits) % 16 == 0;
-    constexpr int kSegPerBlock = kSegThreads / kWave * kSegPerWave;
+    constexpr int kSegPerBlock = kSegThreads / kWave * kSegPerWaveSampler;
     const dim3 g(static_cast<unsigned>((lay.nseg + kSegPerBlock - 1) / kSegPerBlock), static_cast<unsigned>(rows));
     DecideIO io{};
     io.out_tokens = out_tokens;
     const FinalOut fo = final_out(ws, lay);
     hipLaunchKernelGGL(k_zero_counters, dim3((rows + 255) / 256), dim3(256), 0, stream, fo.counter, rows);
     if (vec)
-        hipLaunchKernelGGL((k_final<T, true, true>), g, dim3(kSegThreads), 0, stream, rowsp, rowsp, io, fo, V, 1, 0, c,
+        hipLaunchKernelGGL((k_final<T, true, true, kSegPerWaveSampler>), g, dim3(kSegThreads), 0, stream, rowsp, rowsp, io, fo, V, 1, 0, c,
                            lay.nseg, seed, offset, slot);
     else
-        hipLaunchKernelGGL((k_final<T, false, true>), g, dim3(kSegThreads), 0, stream, rowsp, rowsp, io, fo, V, 1, 0, c,
+        hipLaunchKernelGGL((k_final<T, false, true, kSegPerWaveSampler>), g, dim3(kSegThreads), 0, stream, rowsp, rowsp, io, fo, V, 1, 0, c,
                            lay.nseg, seed, offset, slot);
     return hipGetLastError();
 }
