@@ -243,6 +243,19 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": main_bytes},
     }
 
+    # The same kernel against the vector-ALU issue rate (it is limited by instruction issue, not by HBM, for
+    # bfloat16 logits): lane-instructions the formulation needs per (target, draft) entry pair -- v_exp_f32
+    # counts two issue slots -- over the 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz the chip issues without packed
+    # float32 instructions.
+    unpack = 2 if w.dtype == "bf16" else 0
+    nmul = (w.K.bit_length() - 1) + bin(w.K).count("1") - 1
+    slots = (unpack + 8) + (w.L - 1) / w.L * (unpack + 9 + nmul)
+    alu_peak = 256 * 4 * 16 * 2.4e9 / 1e12
+    alu_ach = slots * w.row_pairs * w.V / (main_avg * 1e-3) / 1e12
+    res["roofline_alu"] = {"bound": "alu", "achieved": alu_ach, "peak": alu_peak, "unit": "Tlane-instr/s",
+                           "frac": alu_ach / alu_peak, "slots_per_entry_pair": slots,
+                           "note": "unpacked float32 issue rate; the published 157.3 TFLOP/s counts packed FMA"}
+
     if not a.no_cpu_baseline:
         import oracle
         # bounded sample: time two prefixes, then as many as fit the CPU-time target
