@@ -1,0 +1,76 @@
+"""The entry points under HIP graph capture: a serving loop records one decoding iteration's
+library calls once and replays them.  Every call is asynchronous on the caller's stream,
+allocates nothing and records no memset, so it can be captured; each replay (with eager work
+and synchronisations in between, and new inputs copied into the captured buffers) must
+reproduce the eager result bit for bit."""
+import numpy as np
+import pytest
+
+from parity_util import to_torch
+from specgbv_synth import Workload, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def test_verify_modify_sample_replay_under_graph_capture():
+    import torch
+    import paper_2604_25925_amd as sg
+    w = Workload("graph", 6, 4, 4, 8192, "bf16", 2.5, 0.9, head=20, temperature=0.9)
+    sets = [make_inputs(w, seed=s) for s in (41, 42, 43)]
+    T, B, K, L, V = w.temperature, w.batch, w.K, w.L, w.V
+    dev = torch.device("cuda")
+    # static buffers of the captured iteration
+    tl, dl, tk = (to_torch(a) for a in sets[0])
+    ws = torch.empty(sg.specgbv_workspace_bytes(B, K, L, V, 1), dtype=torch.uint8, device=dev)
+    out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+           torch.empty((B, L + 1), dtype=torch.int32, device=dev))
+    carry_ptr, count_ptr = sg.specgbv_workspace_carry(ws, B, K, L, V)
+    mod = {"logq": torch.empty((B, K, L + 1, V), dtype=torch.float32, device=dev),
+           "logp": torch.empty((B, K, L, V), dtype=torch.float32, device=dev),
+           "workspace": torch.empty(sg.specgbv_modify_workspace_bytes(B, K, L, 1), dtype=torch.uint8, device=dev)}
+    rows = dl[:, :, 0].contiguous().view(B * K, V)
+    stok = torch.empty(B * K, dtype=torch.int32, device=dev)
+    sws = torch.empty(sg.specgbv_sample_workspace_bytes(B * K, V), dtype=torch.uint8, device=dev)
+
+    def iteration():
+        sg.specgbv_verify_ex(tl, dl, tk, T, 5, 2, workspace=ws, out=out)
+        sg.specgbv_modify_target(tl, dl, tk, T, carry_ptr, count_ptr, want_logp=True, out=mod)
+        sg.specgbv_sample_tokens(rows, T, 5, 2, 0, out=stok, workspace=sws)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (*out, mod["logq"], mod["logp"], stok)]
+
+    def load(inputs):
+        a, b, c = (to_torch(x) for x in inputs)
+        tl.copy_(a); dl.copy_(b); tk.copy_(c)
+        rows.copy_(dl[:, :, 0].reshape(B * K, V))
+
+    eager = []
+    for inputs in sets:
+        load(inputs)
+        iteration()
+        eager.append(snapshot())
+
+    load(sets[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        iteration()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        iteration()
+    for rep, inputs in enumerate(sets + sets[:1]):
+        load(inputs)
+        for t in (*out, stok):
+            t.fill_(-7)                               # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        want = eager[rep % len(sets)]
+        for g, e in zip(got, want):
+            assert torch.equal(g, e) or (g.dtype.is_floating_point and
+                                         torch.equal(torch.nan_to_num(g, neginf=-1e30), torch.nan_to_num(e, neginf=-1e30))), \
+                "replay %d differs from the eager result" % rep
