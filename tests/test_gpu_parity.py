@@ -107,6 +107,15 @@ def test_shapes_and_ragged_tails(algo, B, K, L, V, dtype):
         _algo_or_skip(algo, lambda: check_case(t, d, tok, T, 3, off, algo, "edge %s" % ((B, K, L, V, dtype),)))
 
 
+@pytest.mark.parametrize("K,V,dtype", [(1, 32768, "bf16"), (2, 16384, "f32"), (3, 40960, "bf16"), (4, 32768, "bf16"),
+                                        (5, 32768, "bf16"), (16, 16384, "f32"), (8, 94208, "bf16"), (3, 65536, "f32")])
+def test_chain_schedule_draft_counts(K, V, dtype):
+    # the on-chip schedule has one unrolled variant per common draft count (and a generic one) and
+    # three register-slot counts chosen by V; K = 1 is single-draft greedy block verification
+    t, d, tok, T = _gauss_case(3, K, 4, V, dtype, seed=20 + K)
+    check_case(t, d, tok, T, 4, 1, "chain", "chain K=%d V=%d %s" % (K, V, dtype))
+
+
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("T", [0.1, 0.4, 2.0])
 def test_temperature(algo, T):
