@@ -225,6 +225,44 @@ specgbv_status specgbv_modify_target(
 size_t specgbv_modify_workspace_bytes(int batch, int K, int M, int bonus_row);
 
 /*
+ * Book-keeping of Algorithm 3's "q <- DistributionModification(q, p, L, t^tau, y)" over several
+ * iterations.  The statement updates q in place, so a modification made after iteration n is
+ * still in force for its remaining rows when iteration n+1 emits fewer tokens than it has rows,
+ * and iteration n+1's own modification then applies ON TOP of it.  A prefix therefore carries up
+ * to L-1 pending modifications (carry_log_nu, modify_count), innermost (oldest) first; the rows
+ * to verify are obtained by applying them in that order with specgbv_modify_target (the first
+ * on the models' logits, each later one on the previous call's out_logq / out_logp at
+ * temperature 1), and after the verification every pending one is advanced by this function:
+ *
+ *   tau = accepted_len[b], f = max(accepted_draft_idx[b], 0),
+ *   e_j = draft_tokens[b, f, j] for j < tau, e_tau = out_tokens[b, tau]      (the emitted tokens)
+ *   if modify_count[b] > tau + 1 and tau < M:
+ *       carry_log_nu[b] += sum_{j=0..tau} ln q_j[e_j] - ln p_j[e_j],   modify_count[b] -= tau + 1
+ *   else modify_count[b] = 0                                   (the modification has expired)
+ *
+ * with q_j = softmax(rows_q[b, f, j, :] / temperature), the distribution THIS pending
+ * modification modifies (the models' target rows for the innermost one, the out_logq of the
+ * call below it otherwise), and p_j = softmax(rows_p[b, f, j, :] / temperature).  The newest
+ * modification is the pair the verification leaves in its workspace (specgbv_workspace_carry;
+ * copy it out before the workspace is reused).
+ *
+ *   rows_q        device, [batch, K, M + bonus_row, V];  rows_p  device, [batch, K, M, V]
+ *   draft_tokens  device, [batch, K, M];  accepted_len, accepted_draft_idx  device, [batch];
+ *   out_tokens    device, [batch, M + 1]  (all three as written by specgbv_verify with L = M)
+ *   carry_log_nu  device in/out, [batch] float64;  modify_count  device in/out, [batch] int32
+ *   workspace     device, >= specgbv_carry_workspace_bytes(batch, M) bytes, 256-byte aligned
+ *   batch <= 65535; limits and error behaviour as for specgbv_modify_target
+ */
+specgbv_status specgbv_carry_advance(
+    const void *rows_q, const void *rows_p, const int32_t *draft_tokens,
+    const int32_t *accepted_len, const int32_t *accepted_draft_idx, const int32_t *out_tokens,
+    int K, int M, int bonus_row, int V, int batch, specgbv_dtype dtype, float temperature,
+    double *carry_log_nu, int32_t *modify_count, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of device workspace specgbv_carry_advance needs (0 if the shape is invalid). */
+size_t specgbv_carry_workspace_bytes(int batch, int M);
+
+/*
  * Draft-side sampling (Algorithm 3, the step "sample x_1^L, ..., x_K^L ~ p i.i.d."): one token
  * per row from softmax(logits[row, :] / temperature).  Called once per draft position with the
  * batch * K draft rows of that position, it draws the K i.i.d. continuations of every prefix.

@@ -83,6 +83,10 @@ def lib() -> ctypes.CDLL:
         L.specgbv_oracle_sample_rows.argtypes = [c_void_p, c_int, c_int, c_int, c_float, c_uint64, c_uint64, c_uint32,
                                                  POINTER(c_int32), POINTER(c_double), POINTER(c_double)]
         L.specgbv_oracle_sample_rows.restype = c_int
+        L.specgbv_oracle_carry_advance.argtypes = [c_void_p, c_void_p, POINTER(c_int32), POINTER(c_int32), POINTER(c_int32),
+                                                   POINTER(c_int32), c_int, c_int, c_int, c_int, c_int, c_int, c_float,
+                                                   POINTER(c_double), POINTER(c_int32)]
+        L.specgbv_oracle_carry_advance.restype = c_int
         L.specgbv_oracle_num_procs.argtypes = []
         L.specgbv_oracle_num_procs.restype = c_int
         _lib = L
@@ -252,6 +256,31 @@ def sample_rows(logits: np.ndarray, temperature: float, rng_seed: int, rng_offse
     if rc != 0:
         raise ValueError("specgbv_oracle_sample_rows rejected its arguments (code %d)" % rc)
     return res
+
+
+def carry_advance(rows_q: np.ndarray, rows_p: np.ndarray, tokens, accepted_len, accepted_idx, out_tokens,
+                  temperature: float, carry_log_nu, count):
+    """Advance one pending modification along the emitted tokens (see the C function).
+    Returns new (carry_log_nu, count) arrays; the inputs are not changed."""
+    rq, dt = to_raw(rows_q)
+    rp, dt2 = to_raw(rows_p)
+    assert dt == dt2
+    B, K, M, V = rp.shape
+    bonus = rq.shape[2] - M
+    assert rq.shape == (B, K, M + bonus, V) and bonus in (0, 1)
+    tok = np.ascontiguousarray(tokens, dtype=np.int32)
+    al = np.ascontiguousarray(accepted_len, dtype=np.int32)
+    ai = np.ascontiguousarray(accepted_idx, dtype=np.int32)
+    ot = np.ascontiguousarray(out_tokens, dtype=np.int32)
+    assert tok.shape == (B, K, M) and al.shape == (B,) and ai.shape == (B,) and ot.shape == (B, M + 1)
+    carry = np.array(carry_log_nu, dtype=np.float64)
+    cnt = np.array(count, dtype=np.int32)
+    rc = lib().specgbv_oracle_carry_advance(rq.ctypes.data_as(c_void_p), rp.ctypes.data_as(c_void_p), _ip(tok), _ip(al),
+                                            _ip(ai), _ip(ot), K, M, bonus, V, B, dt, c_float(temperature), _dp(carry),
+                                            _ip(cnt))
+    if rc != 0:
+        raise ValueError("specgbv_oracle_carry_advance rejected its arguments (code %d)" % rc)
+    return carry, cnt
 
 
 def num_procs() -> int:

@@ -26,7 +26,9 @@ def joint(table: Table, block: Block) -> Fraction:
 
 
 def _one_minus_min_pow(pb: Fraction, qb: Fraction, K: int) -> Fraction:
-    """(1 - min{p/q, 1})^K."""
+    """(1 - min{p/q, 1})^K; a block the target gives probability 0 has min{p/q, 1} = 1."""
+    if qb == 0:
+        return Fraction(0)
     ratio = pb / qb
     return (1 - min(ratio, Fraction(1))) ** K
 
@@ -183,6 +185,60 @@ def enumerate_full_output(p_of: Table, q_of: Table, V: int, L: int, K: int):
 
     for key, pr in dist.items():
         extend(key, pr)
+    assert sum(out.values()) == 1
+    return out
+
+
+def enumerate_decoding(p_of: Table, q_of: Table, V: int, L: int, K: int, iters: int, compose: bool = True):
+    """Exact law of the text decoded by `iters` iterations of Algorithm 3 (draft, verify with
+    Algorithm 1, update q with Algorithm 2), as {token tuple: probability}.
+
+    Algorithm 3 updates q in place, so the target of an iteration is the q left by all earlier
+    modifications, and Algorithm 2 is evaluated with that q: a modification whose rows are not
+    used up when the next iteration ends is thereby carried into the next one.
+    compose=False is the reading that does NOT do this: the block ratio of (t^tau, y) is taken
+    from the iteration as it was verified, but the rows being modified, and the continuation of
+    the ratio along them, are the ORIGINAL q.  It exists to show that the readings differ."""
+    out: Dict[Block, Fraction] = {}
+
+    def run(prefix: Block, pr: Fraction, target_of: Table, it: int):
+        if it == iters:
+            out[prefix] = out.get(prefix, Fraction(0)) + pr
+            return
+        n0 = len(prefix)
+        p_rel = lambda b: p_of(prefix + tuple(b))
+        q_rel = lambda b: target_of(prefix + tuple(b))
+        dist, _, _ = enumerate_alg1(p_rel, q_rel, V, L, K)
+        for key, w in dist.items():
+            tau = len(key) - 1
+            count = L - tau - 1 if tau < L else 0
+            new_prefix = prefix + key
+            memo: Dict[Block, list] = {}
+
+            def new_target(block, _np=new_prefix, _count=count, _memo=memo, _key=key):
+                block = tuple(block)
+                j = len(block) - len(_np)
+                if not (0 <= j < _count and block[:len(_np)] == _np):
+                    return target_of(block) if compose else q_of(block)
+                if block not in _memo:
+                    if compose:
+                        # Algorithm 2 as printed: joint probabilities of (t^tau, y, x^(i-1), x) from the
+                        # start of the iteration, under the q that iteration verified against
+                        _memo[block] = residual_literal(p_rel, q_rel, block[n0:], V, K)[0]
+                    else:
+                        Qj, Pj = joint(q_rel, _key), joint(p_rel, _key)
+                        for i in range(len(_np), len(block)):
+                            Qj *= q_of(block[:i])[block[i]]
+                            Pj *= p_of(block[:i])[block[i]]
+                        wts = [Qj * q_of(block)[x] * _one_minus_min_pow(Pj * p_of(block)[x], Qj * q_of(block)[x], K)
+                               for x in range(V)]
+                        tot = sum(wts)
+                        _memo[block] = [v / tot for v in wts] if tot != 0 else list(q_of(block))
+                return _memo[block]
+
+            run(new_prefix, pr * w, new_target, it + 1)
+
+    run((), Fraction(1), q_of, 0)
     assert sum(out.values()) == 1
     return out
 

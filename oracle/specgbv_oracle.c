@@ -601,3 +601,56 @@ int specgbv_oracle_sample_rows(const void *logits, int rows, int V, int dtype,
     free(z); free(lp); free(w);
     return 0;
 }
+
+/* ------------------------- pending modifications across iterations (Algorithm 3) */
+
+/*
+ * Algorithm 3 updates q in place ("q <- DistributionModification(q, p, L, t^tau, y)"), so a
+ * modification that still has rows left when the next iteration ends stays in force and the
+ * next one applies on top of it.  This advances ONE pending modification (carry_log_nu, count)
+ * of every prefix along the tokens the iteration emitted: e_j = tokens[b, f, j] for j < tau,
+ * e_tau = out_tokens[b, tau] (f = accepted draft, draft 0 when tau = 0).  With
+ * q_j = softmax(rows_q[b, f, j] / T) -- the rows this modification modifies -- and p_j likewise,
+ *     count > tau + 1 and tau < M:  carry += sum_{j<=tau} ln q_j[e_j] - ln p_j[e_j],  count -= tau + 1
+ *     otherwise:                    count = 0   (expired)
+ * because the block ratio of Algorithm 2 runs over the whole sequence (t^tau, y, x^(i-1)).
+ *   rows_q [batch, K, M + bonus, V], rows_p [batch, K, M, V], tokens [batch, K, M],
+ *   accepted_len, accepted_idx [batch], out_tokens [batch, M + 1].  Returns 0, or 1.
+ */
+int specgbv_oracle_carry_advance(const void *rows_q, const void *rows_p, const int32_t *tokens,
+                                 const int32_t *accepted_len, const int32_t *accepted_idx,
+                                 const int32_t *out_tokens, int K, int M, int bonus, int V,
+                                 int batch, int dtype, float temperature, double *carry_log_nu,
+                                 int32_t *count)
+{
+    if (!rows_q || !rows_p || !tokens || !accepted_len || !accepted_idx || !out_tokens || !carry_log_nu || !count)
+        return 1;
+    if (K < 1 || M < 1 || V < 1 || batch < 0 || (bonus != 0 && bonus != 1)) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (!(temperature > 0.0f) || !isfinite(temperature)) return 1;
+    const double T = (double)temperature;
+    double *z = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lq = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)V);
+    for (int b = 0; b < batch; ++b) {
+        const int tau = accepted_len[b];
+        if (tau < 0 || tau > M) { free(z); free(lq); free(lp); return 1; }
+        if (tau == M || count[b] <= tau + 1) { count[b] = 0; continue; }
+        const int f = accepted_idx[b] < 0 ? 0 : accepted_idx[b];
+        if (f >= K) { free(z); free(lq); free(lp); return 1; }
+        double c = carry_log_nu[b];
+        for (int j = 0; j <= tau; ++j) {
+            const int32_t e = j < tau ? tokens[((size_t)b * K + f) * M + j] : out_tokens[(size_t)b * (M + 1) + tau];
+            if (e < 0 || e >= V) { free(z); free(lq); free(lp); return 1; }
+            load_row(rows_q, dtype, ((size_t)b * K + f) * (size_t)(M + bonus) + (size_t)j, V, z);
+            specgbv_oracle_log_softmax(z, V, T, lq);
+            load_row(rows_p, dtype, ((size_t)b * K + f) * (size_t)M + (size_t)j, V, z);
+            specgbv_oracle_log_softmax(z, V, T, lp);
+            c += lq[e] - lp[e];
+        }
+        carry_log_nu[b] = c;
+        count[b] -= tau + 1;
+    }
+    free(z); free(lq); free(lp);
+    return 0;
+}

@@ -22,7 +22,7 @@ _ALGO = {"auto": ALGO_AUTO, "split": ALGO_SPLIT, "chain": ALGO_CHAIN}
 
 EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_ex", "specgbv_read_intermediates",
            "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_modify_workspace_bytes", "specgbv_sample_tokens", "specgbv_sample_workspace_bytes",
-           "specgbv_read_sample_intermediates", "specgbv_last_error", "specgbv_version")
+           "specgbv_read_sample_intermediates", "specgbv_carry_advance", "specgbv_carry_workspace_bytes", "specgbv_last_error", "specgbv_version")
 
 
 class SpecGBVError(RuntimeError):
@@ -83,6 +83,11 @@ def load_library() -> ctypes.CDLL:
     L.specgbv_read_sample_intermediates.argtypes = [c_void_p, c_size_t, c_int, c_int, POINTER(c_double),
                                                     POINTER(c_double), c_void_p]
     L.specgbv_read_sample_intermediates.restype = c_int
+    L.specgbv_carry_advance.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int,
+                                        c_int, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    L.specgbv_carry_advance.restype = c_int
+    L.specgbv_carry_workspace_bytes.argtypes = [c_int, c_int]
+    L.specgbv_carry_workspace_bytes.restype = c_size_t
     L.specgbv_last_error.argtypes = []
     L.specgbv_last_error.restype = c_char_p
     L.specgbv_version.argtypes = []
@@ -140,7 +145,7 @@ def _shapes(target_logits, draft_logits, draft_tokens):
 
 def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int,
                       rng_offset: int, *, workspace=None, out: Optional[Tuple] = None, algo="auto",
-                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None, _debug: int = 0):
+                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None):
     """Enqueue one verification on the current (or given) HIP stream.
 
     Returns (accepted_len [B], accepted_draft_idx [B], out_tokens [B, L+1], workspace), all
@@ -161,7 +166,7 @@ def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: fl
     acc_len, acc_idx, out_tokens = out
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
-    opt = _Options(_ALGO[algo] if isinstance(algo, str) else int(algo), _debug,
+    opt = _Options(_ALGO[algo] if isinstance(algo, str) else int(algo), 0,
                    events[0] if events else None, events[1] if events else None)
     st = lib.specgbv_verify_ex(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V,
                                B, dt, c_float(temperature), rng_seed, rng_offset, acc_len.data_ptr(),
@@ -334,3 +339,40 @@ def specgbv_read_sample_intermediates(workspace, rows: int, V: int, stream: Opti
                                                stream)
     _check(st)
     return {"u": u, "margin": m}
+
+
+def specgbv_carry_workspace_bytes(batch: int, M: int) -> int:
+    return int(load_library().specgbv_carry_workspace_bytes(batch, M))
+
+
+def specgbv_carry_advance(rows_q, rows_p, draft_tokens, accepted_len, accepted_draft_idx, out_tokens,
+                          temperature: float, carry_log_nu, modify_count, *, workspace=None,
+                          stream: Optional[int] = None):
+    """Advance one pending modification (carry_log_nu [B] float64, modify_count [B] int32, both updated in
+    place) along the tokens the last verification emitted; rows_q [B, K, M or M+1, V] are the rows that
+    modification modifies, rows_p [B, K, M, V] the draft rows."""
+    import torch
+    lib = load_library()
+    B, K, M, V = rows_p.shape
+    bonus = rows_q.shape[2] - M
+    if bonus not in (0, 1) or tuple(rows_q.shape) != (B, K, M + bonus, V) or rows_q.dtype != rows_p.dtype:
+        raise ValueError("expected rows_p [B, K, M, V] and rows_q [B, K, M or M+1, V] of one dtype")
+    if tuple(draft_tokens.shape) != (B, K, M) or tuple(out_tokens.shape) != (B, M + 1):
+        raise ValueError("draft_tokens must be [B, K, M] and out_tokens [B, M+1]")
+    for t, dt in ((draft_tokens, torch.int32), (accepted_len, torch.int32), (accepted_draft_idx, torch.int32),
+                  (out_tokens, torch.int32), (carry_log_nu, torch.float64), (modify_count, torch.int32)):
+        if t.dtype != dt or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("integer tensors must be int32, carry_log_nu float64, all contiguous on the GPU")
+    if not (rows_q.is_cuda and rows_p.is_cuda and rows_q.is_contiguous() and rows_p.is_contiguous()):
+        raise ValueError("rows must be contiguous GPU tensors")
+    if workspace is None:
+        workspace = torch.empty(max(specgbv_carry_workspace_bytes(B, M), 256), dtype=torch.uint8, device=rows_q.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(rows_q.device).cuda_stream
+    st = lib.specgbv_carry_advance(rows_q.data_ptr(), rows_p.data_ptr(), draft_tokens.data_ptr(), accepted_len.data_ptr(),
+                                   accepted_draft_idx.data_ptr(), out_tokens.data_ptr(), K, M, bonus, V, B,
+                                   _dtype_code(rows_q), c_float(temperature), carry_log_nu.data_ptr(),
+                                   modify_count.data_ptr(), workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), stream)
+    _check(st)
+    return workspace

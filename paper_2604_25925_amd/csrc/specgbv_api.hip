@@ -116,7 +116,6 @@ specgbv_status specgbv_verify_ex(
     p.K = K; p.L = L; p.V = V; p.batch = batch; p.dtype = dtype == SPECGBV_BF16 ? 1 : 0;
     p.c = static_cast<float>(1.4426950408889634074 / static_cast<double>(temperature));
     p.seed = rng_seed; p.offset = rng_offset;
-    p.debug = options ? options->reserved : 0;
     p.accepted_len = accepted_len; p.accepted_draft_idx = accepted_draft_idx; p.out_tokens = out_tokens;
     p.ws = static_cast<char *>(workspace);
     p.stream = static_cast<hipStream_t>(hip_stream);
@@ -271,6 +270,42 @@ specgbv_status specgbv_modify_target(
                                        norm_out, fallback_out, static_cast<char *>(workspace),
                                        static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(SPECGBV_EHIP, "modification kernel launch: %s", hipGetErrorString(e));
+    return SPECGBV_OK;
+}
+
+size_t specgbv_carry_workspace_bytes(int batch, int M)
+{
+    if (batch < 0 || M < 1 || M > SPECGBV_MAX_L) return 0;
+    return align256(static_cast<size_t>(batch < 1 ? 1 : batch) * M * sizeof(double));
+}
+
+specgbv_status specgbv_carry_advance(
+    const void *rows_q, const void *rows_p, const int32_t *draft_tokens,
+    const int32_t *accepted_len, const int32_t *accepted_draft_idx, const int32_t *out_tokens,
+    int K, int M, int bonus_row, int V, int batch, specgbv_dtype dtype, float temperature,
+    double *carry_log_nu, int32_t *modify_count, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const specgbv_status st = check_modify_shape(batch, K, M, bonus_row, V);
+    if (st != SPECGBV_OK) return st;
+    if (dtype != SPECGBV_F32 && dtype != SPECGBV_BF16) return fail(SPECGBV_EINVAL, "unknown dtype %d", static_cast<int>(dtype));
+    if (!(temperature > 0.0f) || !std::isfinite(temperature)) return fail(SPECGBV_EINVAL, "temperature must be positive and finite");
+    if (batch > 65535) return fail(SPECGBV_EUNSUPPORTED, "batch=%d is too large for one launch", batch);
+    if (batch == 0) return SPECGBV_OK;
+    if (!rows_q || !rows_p || !draft_tokens || !accepted_len || !accepted_draft_idx || !out_tokens || !carry_log_nu || !modify_count)
+        return fail(SPECGBV_EINVAL, "null pointer");
+    const size_t esz = dtype == SPECGBV_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(rows_q) % esz || reinterpret_cast<uintptr_t>(rows_p) % esz ||
+        reinterpret_cast<uintptr_t>(carry_log_nu) % 8 || reinterpret_cast<uintptr_t>(modify_count) % 4)
+        return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
+    const size_t need = specgbv_carry_workspace_bytes(batch, M);
+    if (!workspace) return fail(SPECGBV_EWORKSPACE, "workspace is null (need %zu bytes)", need);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(SPECGBV_EWORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < need) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, need);
+    const float c = static_cast<float>(1.44269504088896340736 / static_cast<double>(temperature));
+    const hipError_t e = launch_carry_advance(rows_q, rows_p, draft_tokens, accepted_len, accepted_draft_idx, out_tokens, K, M,
+                                              bonus_row, V, batch, dtype == SPECGBV_BF16 ? 1 : 0, c, carry_log_nu, modify_count,
+                                              static_cast<double *>(workspace), static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "carry kernel launch: %s", hipGetErrorString(e));
     return SPECGBV_OK;
 }
 

@@ -321,7 +321,7 @@ template <typename T, int KP, int RS>
 __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
         int K, int L, int V, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
-        int32_t *__restrict__ final_counter, int dbg)
+        int32_t *__restrict__ final_counter)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
@@ -418,7 +418,6 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             log2nu = uniform_d(log2nu + ((tok2_q - lse2_q) - (tok2_p - lse2_p)));
         }
     }
-    (void)dbg;
 }
 
 template <typename T, int KP>
@@ -432,7 +431,7 @@ hipError_t launch_kp(const Problem &p)
     const int full_slots = (p.V / Elem<T>::kPerVec) / kChainThreads;
 #define SPECGBV_LAUNCH(RS)                                                                              \
     hipLaunchKernelGGL((k_chain<T, KP, RS>), grid, dim3(kChainThreads), 0, p.stream, target, draft,    \
-                       p.tokens, p.K, p.L, p.V, p.c, stats, s, reinterpret_cast<int32_t *>(p.ws + p.lay.counter), p.debug)
+                       p.tokens, p.K, p.L, p.V, p.c, stats, s, reinterpret_cast<int32_t *>(p.ws + p.lay.counter))
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);

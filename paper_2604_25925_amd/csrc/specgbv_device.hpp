@@ -127,6 +127,27 @@ __device__ __forceinline__ double powi_uniform(double t, int K) {
     return acc;
 }
 
+// ------------------------------------------------------------ running sum
+
+// Per-thread running sum of 2^(c z - m2) with a running reference exponent m2 (updated once
+// per 16-byte vector; the partial sum is rescaled when the reference moves).
+struct RunningSum {
+    float m2 = -3.0e38f;          // finite, so that -inf logits give 2^(-inf) = 0, not NaN
+    float Z = 0.0f;
+    template <int N>
+    __device__ __forceinline__ void add(const float (&z)[N], float c) {
+        float vm = z[0];
+#pragma unroll
+        for (int j = 1; j < N; ++j) vm = fmaxf(vm, z[j]);
+        const float n2 = fmaxf(m2, vm * c);
+        float a = 0.0f;
+#pragma unroll
+        for (int j = 0; j < N; ++j) a += exp2_fast(fmaf(z[j], c, -n2));
+        Z = fmaf(Z, exp2_fast(m2 - n2), a);
+        m2 = n2;
+    }
+};
+
 // ------------------------------------------------------------- reductions
 
 // Wave-wide reductions with data-parallel-primitive moves instead of LDS permutes: shifts by

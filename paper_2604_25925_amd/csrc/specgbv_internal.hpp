@@ -45,7 +45,6 @@ struct Problem {
     int dtype;          // 0 = float32, 1 = bfloat16
     float c;            // log2(e) / temperature
     uint64_t seed, offset;
-    int debug;          // experiment switches (0 in production)
     int32_t *accepted_len;
     int32_t *accepted_draft_idx;
     int32_t *out_tokens;
@@ -77,5 +76,12 @@ size_t modify_workspace_bytes(int batch, int K, int M, int bonus);
 hipError_t launch_modify(const void *target, const void *draft, const int32_t *tokens, int K, int M, int bonus, int V,
                          int batch, int dtype, float c, const double *carry, const int32_t *count, float *out_logq,
                          float *out_logp, double *norm_out, int32_t *fallback_out, char *ws, hipStream_t stream);
+
+
+// Advances a pending modification (carry, count) along the tokens an iteration emitted; `delta` holds batch * M doubles.
+hipError_t launch_carry_advance(const void *rows_q, const void *rows_p, const int32_t *tokens, const int32_t *accepted_len,
+                                const int32_t *accepted_idx, const int32_t *out_tokens, int K, int M, int bonus, int V,
+                                int batch, int dtype, float c, double *carry, int32_t *count, double *delta,
+                                hipStream_t stream);
 
 }  // namespace specgbv

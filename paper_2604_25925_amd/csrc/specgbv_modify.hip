@@ -44,25 +44,6 @@ inline ModLayout mod_layout(int batch, int K, int M, int bonus)
     return l;
 }
 
-// Per-thread running sum of 2^(c z - m2) with a running reference exponent m2 (updated once
-// per 16-byte vector; the partial sum is rescaled when the reference moves).
-struct RunningSum {
-    float m2 = -3.0e38f;          // finite, so that -inf logits give 2^(-inf) = 0, not NaN
-    float Z = 0.0f;
-    template <int N>
-    __device__ __forceinline__ void add(const float (&z)[N], float c) {
-        float vm = z[0];
-#pragma unroll
-        for (int j = 1; j < N; ++j) vm = fmaxf(vm, z[j]);
-        const float n2 = fmaxf(m2, vm * c);
-        float a = 0.0f;
-#pragma unroll
-        for (int j = 0; j < N; ++j) a += exp2_fast(fmaf(z[j], c, -n2));
-        Z = fmaf(Z, exp2_fast(m2 - n2), a);
-        m2 = n2;
-    }
-};
-
 // grid.x = target rows followed by draft rows
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kModThreads)
@@ -299,6 +280,95 @@ hipError_t launch_modify_typed(const void *target_v, const void *draft_v, const 
     return hipGetLastError();
 }
 
+// ---- advancing a pending modification's block ratio along the tokens an iteration emitted
+//
+// grid (M, batch).  Workgroup (j, b) handles emitted position j of prefix b: the token is draft
+// f's j-th token for j < tau and the final token for j = tau; its log-ratio
+// ln q_j[e] - ln p_j[e] under the rows the pending modification modifies goes to delta[b, j].
+// Nothing is computed for prefixes whose modification expires with this iteration
+// (count <= tau + 1) or that accepted a whole block.
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kModThreads)
+k_carry_rows(const T *__restrict__ rows_q, const T *__restrict__ rows_p, const int32_t *__restrict__ tokens,
+             const int32_t *__restrict__ accepted_len, const int32_t *__restrict__ accepted_idx,
+             const int32_t *__restrict__ out_tokens, const int32_t *__restrict__ count, int K, int M, int rows_t,
+             int V, float c, double *__restrict__ delta)
+{
+    __shared__ double sh_d[kModThreads / kWave];
+    __shared__ float sh_f[kModThreads / kWave];
+    const int j = blockIdx.x, b = blockIdx.y;
+    const int tau = accepted_len[b];
+    if (tau >= M || j > tau || count[b] <= tau + 1) return;          // uniform over the workgroup
+    int f = accepted_idx[b];
+    f = f < 0 ? 0 : (f >= K ? K - 1 : f);
+    int e = j < tau ? tokens[(static_cast<long long>(b) * K + f) * M + j] : out_tokens[static_cast<long long>(b) * (M + 1) + tau];
+    e = e < 0 ? 0 : (e >= V ? V - 1 : e);
+    const T *rq = rows_q + ((static_cast<long long>(b) * K + f) * rows_t + j) * static_cast<long long>(V);
+    const T *rp = rows_p + ((static_cast<long long>(b) * K + f) * M + j) * static_cast<long long>(V);
+    constexpr int PV = Elem<T>::kPerVec;
+    RunningSum aq, ap;
+    if constexpr (VEC) {
+        const int nvec = V / PV;
+        for (int v = threadIdx.x; v < nvec; v += kModThreads) {
+            float z[PV];
+            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), z); aq.add(z, c);
+            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), z); ap.add(z, c);
+        }
+    } else {
+        for (int x = threadIdx.x; x < V; x += kModThreads) {
+            const float zq[1] = {Elem<T>::scalar(rq + x)}, zp[1] = {Elem<T>::scalar(rp + x)};
+            aq.add(zq, c); ap.add(zp, c);
+        }
+    }
+    const float Mq = block_max(aq.m2, sh_f);
+    const double Zq = block_sum(static_cast<double>(aq.Z * exp2_fast(aq.m2 - Mq)), sh_d);
+    const float Mp = block_max(ap.m2, sh_f);
+    const double Zp = block_sum(static_cast<double>(ap.Z * exp2_fast(ap.m2 - Mp)), sh_d);
+    if (threadIdx.x == 0) {
+        const double l2q = static_cast<double>(Elem<T>::scalar(rq + e)) * static_cast<double>(c) - (static_cast<double>(Mq) + log2(Zq));
+        const double l2p = static_cast<double>(Elem<T>::scalar(rp + e)) * static_cast<double>(c) - (static_cast<double>(Mp) + log2(Zp));
+        delta[static_cast<long long>(b) * M + j] = (l2q - l2p) * 0.693147180559945309417;
+    }
+}
+
+// one thread per prefix: sums the log-ratios in position order and shortens the row count
+__global__ void k_carry_apply(const int32_t *__restrict__ accepted_len, int M, int batch, const double *__restrict__ delta,
+                              double *__restrict__ carry, int32_t *__restrict__ count)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    const int tau = accepted_len[b], n = count[b];
+    if (tau < M && n > tau + 1) {
+        double a = carry[b];
+        for (int j = 0; j <= tau; ++j) a += delta[static_cast<long long>(b) * M + j];
+        carry[b] = a;
+        count[b] = n - (tau + 1);
+    } else {
+        count[b] = 0;                                     // expired: its ratio is not used again
+    }
+}
+
+template <typename T>
+hipError_t launch_carry_typed(const void *rows_q, const void *rows_p, const int32_t *tokens, const int32_t *accepted_len,
+                              const int32_t *accepted_idx, const int32_t *out_tokens, int K, int M, int bonus, int V,
+                              int batch, float c, double *carry, int32_t *count, double *delta, hipStream_t stream)
+{
+    const bool vec = (V % Elem<T>::kPerVec) == 0 && reinterpret_cast<uintptr_t>(rows_q) % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(rows_p) % 16 == 0;
+    const dim3 g(static_cast<unsigned>(M), static_cast<unsigned>(batch));
+    if (vec)
+        hipLaunchKernelGGL((k_carry_rows<T, true>), g, dim3(kModThreads), 0, stream, static_cast<const T *>(rows_q),
+                           static_cast<const T *>(rows_p), tokens, accepted_len, accepted_idx, out_tokens, count, K, M,
+                           M + bonus, V, c, delta);
+    else
+        hipLaunchKernelGGL((k_carry_rows<T, false>), g, dim3(kModThreads), 0, stream, static_cast<const T *>(rows_q),
+                           static_cast<const T *>(rows_p), tokens, accepted_len, accepted_idx, out_tokens, count, K, M,
+                           M + bonus, V, c, delta);
+    hipLaunchKernelGGL(k_carry_apply, dim3((batch + 255) / 256), dim3(256), 0, stream, accepted_len, M, batch, delta, carry,
+                       count);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 size_t modify_workspace_bytes(int batch, int K, int M, int bonus) { return mod_layout(batch, K, M, bonus).total; }
@@ -311,6 +381,17 @@ hipError_t launch_modify(const void *target, const void *draft, const int32_t *t
                                                       out_logq, out_logp, norm_out, fallback_out, ws, stream)
                       : launch_modify_typed<float>(target, draft, tokens, K, M, bonus, V, batch, c, carry, count,
                                                    out_logq, out_logp, norm_out, fallback_out, ws, stream);
+}
+
+hipError_t launch_carry_advance(const void *rows_q, const void *rows_p, const int32_t *tokens, const int32_t *accepted_len,
+                                const int32_t *accepted_idx, const int32_t *out_tokens, int K, int M, int bonus, int V,
+                                int batch, int dtype, float c, double *carry, int32_t *count, double *delta,
+                                hipStream_t stream)
+{
+    return dtype == 1 ? launch_carry_typed<uint16_t>(rows_q, rows_p, tokens, accepted_len, accepted_idx, out_tokens, K, M,
+                                                     bonus, V, batch, c, carry, count, delta, stream)
+                      : launch_carry_typed<float>(rows_q, rows_p, tokens, accepted_len, accepted_idx, out_tokens, K, M,
+                                                  bonus, V, batch, c, carry, count, delta, stream);
 }
 
 }  // namespace specgbv

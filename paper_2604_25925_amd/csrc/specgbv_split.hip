@@ -15,33 +15,6 @@ namespace {
 
 constexpr int kStatThreads = 512;
 
-// Per-thread running sum of 2^(c z - m2) with a running reference exponent m2.
-struct OnlineSum {
-    float m2 = -3.0e38f;          // finite, so that -inf logits give 2^(-inf) = 0, not NaN
-    float Z = 0.0f;
-    template <int N>
-    __device__ __forceinline__ void add(const float (&z)[N], float c) {
-        float vm = z[0];
-#pragma unroll
-        for (int j = 1; j < N; ++j) vm = fmaxf(vm, z[j]);
-        const float vm2 = vm * c;
-        if (vm2 > m2) {
-            Z *= exp2_fast(m2 - vm2);     // first use: Z is 0 and stays 0
-            m2 = vm2;
-        }
-#pragma unroll
-        for (int j = 0; j < N; ++j) Z += exp2_fast(fmaf(z[j], c, -m2));
-    }
-    __device__ __forceinline__ void add1(float z, float c) {
-        const float z2 = z * c;
-        if (z2 > m2) {
-            Z *= exp2_fast(m2 - z2);
-            m2 = z2;
-        }
-        Z += exp2_fast(fmaf(z, c, -m2));
-    }
-};
-
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kStatThreads)
 k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
@@ -59,7 +32,7 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
     const T *row = is_draft ? draft + (bk * L + r) * static_cast<long long>(V)
                             : target + (bk * (L + 1) + r) * static_cast<long long>(V);
     constexpr int PV = Elem<T>::kPerVec;
-    OnlineSum acc;
+    RunningSum acc;
     if (VEC) {
         const int nvec = V / PV;
         for (int i = threadIdx.x; i < nvec; i += kStatThreads) {
@@ -68,7 +41,10 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
             acc.add(z, c);
         }
     } else {
-        for (int x = threadIdx.x; x < V; x += kStatThreads) acc.add1(Elem<T>::scalar(row + x), c);
+        for (int x = threadIdx.x; x < V; x += kStatThreads) {
+            const float z[1] = {Elem<T>::scalar(row + x)};
+            acc.add(z, c);
+        }
     }
     const float M = block_max(acc.m2, sh_f);
     const double part = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));

@@ -174,3 +174,26 @@ def test_two_iterations_carry_through_the_workspace():
     rep, gpu, ora = check_case(np.ascontiguousarray(tq), np.ascontiguousarray(logp), tok2, 1.0, 17, 1, "auto",
                                "iteration 2 on modified rows")
     assert np.isneginf(tq).any()
+
+
+@pytest.mark.parametrize("dtype,V,T", [("f32", 515, 1.0), ("bf16", 8192, 0.8), ("f32", 64, 1.0)])
+def test_carry_advance_matches_oracle(dtype, V, T):
+    import torch
+    import paper_2604_25925_amd as sg
+    w = Workload("adv", 24, 3, 4, V, dtype, 2.0, 0.7, temperature=T)
+    t, d, tok = make_inputs(w, seed=51)
+    tl, dl, tk = to_torch(t), to_torch(d), to_torch(tok)
+    acc, f, out, ws = sg.specgbv_verify(tl, dl, tk, T, 8, 0)
+    rng = np.random.default_rng(3)
+    carry0 = rng.normal(0, 0.5, w.batch)
+    count0 = rng.integers(0, w.L, w.batch).astype(np.int32)
+    carry, count = torch.from_numpy(carry0.copy()).cuda(), torch.from_numpy(count0.copy()).cuda()
+    sg.specgbv_carry_advance(tl, dl, tk, acc, f, out, T, carry, count)
+    torch.cuda.synchronize()
+    want_c, want_n = oracle.carry_advance(t, d, tok, acc.cpu().numpy(), f.cpu().numpy(), out.cpu().numpy(), T, carry0, count0)
+    assert np.array_equal(count.cpu().numpy(), want_n)
+    live = want_n > 0
+    assert live.any() and (~live).any()
+    np.testing.assert_allclose(carry.cpu().numpy()[live], want_c[live], rtol=0, atol=(w.L + 1) * RTOL)
+    # expired modifications keep their (unused) ratio
+    np.testing.assert_array_equal(carry.cpu().numpy()[~live], carry0[~live])

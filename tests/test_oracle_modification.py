@@ -122,3 +122,68 @@ def test_verify_reports_the_carried_ratio_and_count():
         assert res["modify_count"][b] == L - tau - 1
         want = float(np.log(float(ee.joint(q_of, out) / ee.joint(p_of, out))))
         assert abs(res["carry_log_nu"][b] - want) < 1e-5               # tables pass through float32 logits
+
+
+# ------------------------------------------------ several iterations (Algorithm 3)
+
+def _prefix_law(text_law, m):
+    law = {}
+    for text, pr in text_law.items():
+        law[text[:m]] = law.get(text[:m], F(0)) + pr
+    return law
+
+
+@pytest.mark.parametrize("V,L,iters", [(2, 2, 3), (2, 3, 3), (3, 3, 2)])
+def test_decoded_text_is_target_distributed_over_several_iterations_at_k1(V, L, iters):
+    """Algorithm 3 with q updated in place (pending modifications stay in force and compose):
+    the first `iters` decoded tokens follow the target model exactly."""
+    rng = np.random.default_rng(40 + 10 * V + L)
+    p2, q2 = ee.random_tables(rng, V, 2)
+    p_of = lambda b: p2(tuple(b[-2:]))
+    q_of = lambda b: q2(tuple(b[-2:]))
+    law = _prefix_law(ee.enumerate_decoding(p_of, q_of, V, L, 1, iters), iters)
+    for blk in itertools.product(range(V), repeat=iters):
+        assert law.get(blk, F(0)) == ee.joint(q_of, blk)
+
+
+def test_forgetting_a_pending_modification_changes_the_law():
+    # L = 3: after tau = 0 two rows are modified; if the next iteration emits one token, the second
+    # modified row must survive into the third iteration.  Laying each modification over the
+    # original q instead is not distribution preserving.
+    rng = np.random.default_rng(62)
+    p2, q2 = ee.random_tables(rng, 2, 2)
+    p_of = lambda b: p2(tuple(b[-2:]))
+    q_of = lambda b: q2(tuple(b[-2:]))
+    law = _prefix_law(ee.enumerate_decoding(p_of, q_of, 2, 3, 1, 3, compose=False), 3)
+    tv = sum(abs(law.get(b, F(0)) - ee.joint(q_of, b)) for b in itertools.product(range(2), repeat=3)) / 2
+    assert tv > F(1, 1000)
+    # with L = 2 a modification never outlives the next iteration: both readings coincide
+    a = ee.enumerate_decoding(p_of, q_of, 2, 2, 1, 3, compose=False)
+    b = ee.enumerate_decoding(p_of, q_of, 2, 2, 1, 3, compose=True)
+    assert a == b
+
+
+def test_carry_advance_follows_the_joint_ratio():
+    """The pending block ratio after an iteration is the joint ratio q/p of everything emitted since
+    the modification was made, under the rows that modification modifies."""
+    rng = np.random.default_rng(17)
+    V, L, K, n = 3, 4, 2, 300
+    p_of, q_of = ee.random_tables(rng, V, L + 1)
+    target, draft, tokens = tables_to_inputs(p_of, q_of, V, L, K, n, seed=9)
+    res = oracle.verify(target, draft, tokens, 1.0, 21, 0, debug=True)
+    carry0 = rng.normal(0, 0.3, n)
+    count0 = rng.integers(0, L, n).astype(np.int32)
+    carry, count = oracle.carry_advance(target, draft, tokens, res["accepted_len"], res["accepted_draft_idx"],
+                                        res["out_tokens"], 1.0, carry0, count0)
+    seen = 0
+    for b in range(n):
+        tau = int(res["accepted_len"][b])
+        if tau == L or count0[b] <= tau + 1:
+            assert count[b] == 0
+            continue
+        seen += 1
+        emitted = tuple(int(v) for v in res["out_tokens"][b, :tau + 1])
+        want = carry0[b] + float(np.log(float(ee.joint(q_of, emitted) / ee.joint(p_of, emitted))))
+        assert count[b] == count0[b] - (tau + 1)
+        assert abs(carry[b] - want) < 1e-5                  # tables pass through float32 logits
+    assert seen > 10
