@@ -119,7 +119,7 @@ def bench_sample(a, w, sg, torch, dl):
         "config": {"workload": "%s: %d draft rows (batch %d x K=%d) of one position, V=%d, %s logits, T=%g" % (
             w.name, n, w.batch, w.K, w.V, w.dtype, w.temperature)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "k_zero_counters + k_final (sampler mode)",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "k_sample_rows",
                      "kernel_ms_avg": avg, "kernel_ms_min": ker[0], "algorithmic_bytes_per_launch": bytes_},
     }
 

@@ -273,7 +273,7 @@ size_t specgbv_carry_workspace_bytes(int batch, int M);
  * never used by specgbv_verify, so one (seed, offset) pair can serve a whole decoding iteration.
  *
  *   logits       device, [rows, V], dense; -inf entries have probability 0
- *   rows, V      rows >= 0 (0: nothing is launched), rows <= 65535, V >= 1
+ *   rows, V      rows >= 0 (0: nothing is launched), 1 <= V <= 1048576
  *   position     draft position the rows belong to, below 2^31 (selects the Philox slot)
  *   out_tokens   device out, [rows] int32
  *   workspace    device, >= specgbv_sample_workspace_bytes(rows, V) bytes, 256-byte aligned,

@@ -312,14 +312,17 @@ specgbv_status specgbv_carry_advance(
 static specgbv_status check_sample_shape(int rows, int V)
 {
     if (rows < 0 || V < 1) return fail(SPECGBV_EINVAL, "bad shape rows=%d V=%d", rows, V);
-    if (rows > 65535) return fail(SPECGBV_EUNSUPPORTED, "rows=%d is too large for one launch (at most 65535)", rows);
+    if (V > sample_max_vocab()) return fail(SPECGBV_EUNSUPPORTED, "V=%d exceeds the sampler's limit of %d", V, sample_max_vocab());
     return SPECGBV_OK;
 }
+
+// sampler workspace: uniforms [rows] and margins [rows], float64
+static size_t sample_margin_offset(int rows) { return align256(static_cast<size_t>(rows) * sizeof(double)); }
 
 size_t specgbv_sample_workspace_bytes(int rows, int V)
 {
     if (check_sample_shape(rows, V) != SPECGBV_OK) return 0;
-    return make_workspace(rows < 1 ? 1 : rows, 1, 1, V).total;
+    return 2 * sample_margin_offset(rows < 1 ? 1 : rows);
 }
 
 specgbv_status specgbv_sample_tokens(
@@ -337,13 +340,15 @@ specgbv_status specgbv_sample_tokens(
     const size_t esz = dtype == SPECGBV_BF16 ? 2 : 4;
     if (reinterpret_cast<uintptr_t>(logits) % esz || reinterpret_cast<uintptr_t>(out_tokens) % 4)
         return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
-    const Workspace lay = make_workspace(rows, 1, 1, V);
-    if (!workspace) return fail(SPECGBV_EWORKSPACE, "workspace is null (need %zu bytes)", lay.total);
+    const size_t need = specgbv_sample_workspace_bytes(rows, V);
+    if (!workspace) return fail(SPECGBV_EWORKSPACE, "workspace is null (need %zu bytes)", need);
     if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(SPECGBV_EWORKSPACE, "workspace must be 256-byte aligned");
-    if (workspace_bytes < lay.total) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, lay.total);
+    if (workspace_bytes < need) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, need);
     const float c = static_cast<float>(1.44269504088896340736 / static_cast<double>(temperature));
+    char *ws = static_cast<char *>(workspace);
     const hipError_t e = launch_sample_rows(logits, rows, V, dtype == SPECGBV_BF16 ? 1 : 0, c, rng_seed, rng_offset,
-                                            0x80000000u | position, out_tokens, static_cast<char *>(workspace), lay,
+                                            0x80000000u | position, out_tokens, reinterpret_cast<double *>(ws),
+                                            reinterpret_cast<double *>(ws + sample_margin_offset(rows)),
                                             static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(SPECGBV_EHIP, "sampling kernel launch: %s", hipGetErrorString(e));
     return SPECGBV_OK;
@@ -354,14 +359,14 @@ specgbv_status specgbv_read_sample_intermediates(const void *workspace, size_t w
 {
     if (check_sample_shape(rows, V) != SPECGBV_OK || rows < 1) return fail(SPECGBV_EINVAL, "bad shape");
     if (!workspace) return fail(SPECGBV_EINVAL, "null pointer");
-    const Workspace lay = make_workspace(rows, 1, 1, V);
-    if (workspace_bytes < lay.total) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, lay.total);
+    const size_t need = specgbv_sample_workspace_bytes(rows, V);
+    if (workspace_bytes < need) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, need);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const char *ws = static_cast<const char *>(workspace);
     hipError_t e = hipSuccess;
-    if (u_host) e = hipMemcpyAsync(u_host, ws + lay.u_final, rows * sizeof(double), hipMemcpyDeviceToHost, stream);
+    if (u_host) e = hipMemcpyAsync(u_host, ws, rows * sizeof(double), hipMemcpyDeviceToHost, stream);
     if (margin_host && e == hipSuccess)
-        e = hipMemcpyAsync(margin_host, ws + lay.margin, rows * sizeof(double), hipMemcpyDeviceToHost, stream);
+        e = hipMemcpyAsync(margin_host, ws + sample_margin_offset(rows), rows * sizeof(double), hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail(SPECGBV_EHIP, "copy of the sampling intermediates: %s", hipGetErrorString(e));
     return SPECGBV_OK;

@@ -24,7 +24,6 @@ namespace {
 
 constexpr int kDecideThreads = 256;
 constexpr int kSegPerWave = 4;               // residual segments per wave of the final-token kernel
-constexpr int kSegPerWaveSampler = 8;        // ... in its sampler mode (whole rows, nothing else to wait for)
 
 // ---------------------------------------------------------------- k_decide
 
@@ -353,13 +352,10 @@ struct FinalOut {
     int32_t *mcount;
 };
 
-// SAMPLE = true turns the kernel into a plain row sampler (used for drawing draft tokens): no
-// decision, "prefix" b draws one token from softmax row b of `target` with the uniform of
-// Philox slot `sample_slot`, and the token goes to out_tokens[b] (the caller passes L = 0).
-template <typename T, bool VEC, bool SAMPLE, int SPW>
+template <typename T, bool VEC>
 __global__ void __launch_bounds__(kSegThreads)
 k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, FinalOut fo, int V, int K, int L,
-        float c, int nseg, uint64_t seed, uint64_t offset, uint32_t sample_slot)
+        float c, int nseg, uint64_t seed, uint64_t offset)
 {
     static_assert(kSegThreads == kDecideThreads, "the decision runs on the whole workgroup");
     extern __shared__ double lds_decide[];
@@ -380,43 +376,33 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     double *__restrict__ carry_out = fo.carry;
 
     // ---- 1. decision (redundantly per workgroup; the first one of the prefix writes it out)
-    if constexpr (SAMPLE) {
-        if (tid == 0) {
-            Selection s0;
-            s0.target_row = b; s0.draft_row = -1; s0.C2 = 0.0; s0.lse2_q = 0.0; s0.shift_q = 0.0f; s0.tau = 0;
-            sh_sel = s0;
-            sh_u = philox_uniform(seed, offset, static_cast<uint32_t>(b), sample_slot);
-        }
-        __syncthreads();
-    } else {
-        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u);
-    }
+    decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u);
     const Selection sl = sh_sel;
     if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
 
-    // ---- 2. partial sums of this workgroup's segments: SPW consecutive segments per wave
+    // ---- 2. partial sums of this workgroup's segments: kSegPerWave consecutive segments per wave
     {
-        const int seg0 = (blockIdx.x * (kSegThreads / kWave) + wid) * SPW;
-        double sw[SPW], sq[SPW];
-        float m2[SPW];
-        float zq[SPW][8], zp[SAMPLE ? 1 : SPW][8];   // the sampler has no draft row
+        const int seg0 = (blockIdx.x * (kSegThreads / kWave) + wid) * kSegPerWave;
+        double sw[kSegPerWave], sq[kSegPerWave];
+        float m2[kSegPerWave];
+        float zq[kSegPerWave][8], zp[kSegPerWave][8];
 #pragma unroll
-        for (int i = 0; i < SPW; ++i)            // all loads first: one memory latency, not four
-            if (seg0 + i < nseg) segment_load<T, VEC>(target, draft, sl, V, seg0 + i, lane, zq[i], zp[SAMPLE ? 0 : i]);
+        for (int i = 0; i < kSegPerWave; ++i)            // all loads first: one memory latency, not four
+            if (seg0 + i < nseg) segment_load<T, VEC>(target, draft, sl, V, seg0 + i, lane, zq[i], zp[i]);
 #pragma unroll
-        for (int i = 0; i < SPW; ++i) {
+        for (int i = 0; i < kSegPerWave; ++i) {
             sw[i] = 0.0; sq[i] = 0.0; m2[i] = 0.0f;
             if (seg0 + i < nseg) {                      // wave-uniform
                 float w[8], wq[8];
-                m2[i] = segment_weigh(sl, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[SAMPLE ? 0 : i], w, wq);
+                m2[i] = segment_weigh(sl, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[i], w, wq);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) { sw[i] += static_cast<double>(w[j]); sq[i] += static_cast<double>(wq[j]); }
             }
         }
 #pragma unroll
-        for (int i = 0; i < SPW; ++i) {
+        for (int i = 0; i < kSegPerWave; ++i) {
             if (seg0 + i < nseg) {
-                const double a = wave_sum(sw[i]), bq = SAMPLE ? a : wave_sum(sq[i]);   // sampler: w is q
+                const double a = wave_sum(sw[i]), bq = wave_sum(sq[i]);
                 if (lane == 0) partial_store(&fo.partial[static_cast<long long>(b) * nseg + seg0 + i], a, bq, m2[i]);
             }
         }
@@ -586,27 +572,6 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     }
 }
 
-__global__ void k_zero_counters(int32_t *counter, int n)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) counter[i] = 0;
-}
-
-FinalOut final_out(char *ws, const Workspace &lay)
-{
-    FinalOut fo;
-    fo.sel = reinterpret_cast<Selection *>(ws + lay.sel);
-    fo.partial = reinterpret_cast<SegPartial *>(ws + lay.partial);
-    fo.counter = reinterpret_cast<int32_t *>(ws + lay.counter);
-    fo.res_norm = reinterpret_cast<double *>(ws + lay.res_norm);
-    fo.u_final = reinterpret_cast<double *>(ws + lay.u_final);
-    fo.margin = reinterpret_cast<double *>(ws + lay.margin);
-    fo.fallback = reinterpret_cast<int32_t *>(ws + lay.fallback);
-    fo.carry = reinterpret_cast<double *>(ws + lay.carry);
-    fo.mcount = reinterpret_cast<int32_t *>(ws + lay.mcount);
-    return fo;
-}
-
 template <typename T>
 hipError_t launch_final_typed(const Problem &p)
 {
@@ -627,36 +592,24 @@ hipError_t launch_final_typed(const Problem &p)
     io.eta_out = reinterpret_cast<double *>(p.ws + p.lay.eta);
     io.state_out = reinterpret_cast<int32_t *>(p.ws + p.lay.state);
     io.accepted_len = p.accepted_len; io.accepted_draft_idx = p.accepted_draft_idx; io.out_tokens = p.out_tokens;
-    const FinalOut fo = final_out(p.ws, p.lay);
+    FinalOut fo;
+    fo.sel = reinterpret_cast<Selection *>(p.ws + p.lay.sel);
+    fo.partial = reinterpret_cast<SegPartial *>(p.ws + p.lay.partial);
+    fo.counter = reinterpret_cast<int32_t *>(p.ws + p.lay.counter);
+    fo.res_norm = reinterpret_cast<double *>(p.ws + p.lay.res_norm);
+    fo.u_final = reinterpret_cast<double *>(p.ws + p.lay.u_final);
+    fo.margin = reinterpret_cast<double *>(p.ws + p.lay.margin);
+    fo.fallback = reinterpret_cast<int32_t *>(p.ws + p.lay.fallback);
+    fo.carry = reinterpret_cast<double *>(p.ws + p.lay.carry);
+    fo.mcount = reinterpret_cast<int32_t *>(p.ws + p.lay.mcount);
     const int KL = p.K * p.L;
     const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
     if (vec)
-        hipLaunchKernelGGL((k_final<T, true, false, kSegPerWave>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V,
-                           p.K, p.L, p.c, p.lay.nseg, p.seed, p.offset, 0u);
+        hipLaunchKernelGGL((k_final<T, true>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K,
+                           p.L, p.c, p.lay.nseg, p.seed, p.offset);
     else
-        hipLaunchKernelGGL((k_final<T, false, false, kSegPerWave>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V,
-                           p.K, p.L, p.c, p.lay.nseg, p.seed, p.offset, 0u);
-    return hipGetLastError();
-}
-
-template <typename T>
-hipError_t launch_sample_typed(const void *logits, int rows, int V, float c, uint64_t seed, uint64_t offset,
-                               uint32_t slot, int32_t *out_tokens, char *ws, const Workspace &lay, hipStream_t stream)
-{
-    const T *rowsp = static_cast<const T *>(logits);
-    const bool vec = (V % Elem<T>::kPerVec) == 0 && reinterpret_cast<uintptr_t>(logits) % 16 == 0;
-    constexpr int kSegPerBlock = kSegThreads / kWave * kSegPerWaveSampler;
-    const dim3 g(static_cast<unsigned>((lay.nseg + kSegPerBlock - 1) / kSegPerBlock), static_cast<unsigned>(rows));
-    DecideIO io{};
-    io.out_tokens = out_tokens;
-    const FinalOut fo = final_out(ws, lay);
-    hipLaunchKernelGGL(k_zero_counters, dim3((rows + 255) / 256), dim3(256), 0, stream, fo.counter, rows);
-    if (vec)
-        hipLaunchKernelGGL((k_final<T, true, true, kSegPerWaveSampler>), g, dim3(kSegThreads), 0, stream, rowsp, rowsp, io, fo, V, 1, 0, c,
-                           lay.nseg, seed, offset, slot);
-    else
-        hipLaunchKernelGGL((k_final<T, false, true, kSegPerWaveSampler>), g, dim3(kSegThreads), 0, stream, rowsp, rowsp, io, fo, V, 1, 0, c,
-                           lay.nseg, seed, offset, slot);
+        hipLaunchKernelGGL((k_final<T, false>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K,
+                           p.L, p.c, p.lay.nseg, p.seed, p.offset);
     return hipGetLastError();
 }
 
@@ -665,13 +618,6 @@ hipError_t launch_sample_typed(const void *logits, int rows, int V, float c, uin
 hipError_t launch_decide_and_sample(const Problem &p)
 {
     return p.dtype == 1 ? launch_final_typed<uint16_t>(p) : launch_final_typed<float>(p);
-}
-
-hipError_t launch_sample_rows(const void *logits, int rows, int V, int dtype, float c, uint64_t seed, uint64_t offset,
-                              uint32_t slot, int32_t *out_tokens, char *ws, const Workspace &lay, hipStream_t stream)
-{
-    return dtype == 1 ? launch_sample_typed<uint16_t>(logits, rows, V, c, seed, offset, slot, out_tokens, ws, lay, stream)
-                      : launch_sample_typed<float>(logits, rows, V, c, seed, offset, slot, out_tokens, ws, lay, stream);
 }
 
 }  // namespace specgbv

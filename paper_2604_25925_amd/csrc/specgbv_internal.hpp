@@ -66,9 +66,10 @@ hipError_t launch_chain_main(const Problem &p);
 hipError_t launch_decide_and_sample(const Problem &p);
 
 // One token per row from softmax(logits / T) by inverse CDF with the uniform of Philox slot `slot` of "prefix"
-// row (the final-token kernel in its sampler mode); `lay` = make_workspace(rows, 1, 1, V).
+// row; u_out and margin_out receive the uniform and the inverse-CDF margin of every row.
+int sample_max_vocab();
 hipError_t launch_sample_rows(const void *logits, int rows, int V, int dtype, float c, uint64_t seed, uint64_t offset,
-                              uint32_t slot, int32_t *out_tokens, char *ws, const Workspace &lay, hipStream_t stream);
+                              uint32_t slot, int32_t *out_tokens, double *u_out, double *margin_out, hipStream_t stream);
 
 // Distribution modification (Algorithm 2); all pointers are device pointers, optional ones may be null.
 // `ws` holds modify_workspace_bytes(batch, K, M, bonus) bytes.
