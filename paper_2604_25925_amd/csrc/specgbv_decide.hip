@@ -365,7 +365,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     __shared__ double sh_d[kSegThreads / kWave];
     __shared__ double sh_scan[kSegThreads / kWave];
     __shared__ float sh_f[kSegThreads / kWave];
-    __shared__ int sh_seg, sh_winner, sh_last_pos;
+    __shared__ int sh_seg, sh_first[kSegThreads / kWave], sh_last[kSegThreads / kWave];
     __shared__ double sh_local_target, sh_total;
     __shared__ float sh_seg_m2;
     const int b = blockIdx.y, tid = threadIdx.x;
@@ -461,20 +461,25 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
 
     // first thread, then first segment, whose running total exceeds the goal
     const double mine_seg = use_q ? tqs : tw;
-    if (tid == 0) { sh_winner = kSegThreads; sh_last_pos = -1; }
     const double incl_t = wave_inclusive_sum(mine_seg);
     if (lane == kWave - 1) sh_scan[wid] = incl_t;
     __syncthreads();
     double wave_off = 0.0;
     for (int wv = 0; wv < wid; ++wv) wave_off += sh_scan[wv];
     const double excl_t = wave_off + incl_t - mine_seg;
-    if (mine_seg > 0.0) {
-        atomicMax(&sh_last_pos, tid);
-        if (excl_t + mine_seg > goal) atomicMin(&sh_winner, tid);
+    // per wave: first thread whose running total exceeds the goal, last thread with any weight
+    // (ballots; same-address LDS atomics from every lane serialise and cost microseconds)
+    const unsigned long long has = __ballot(mine_seg > 0.0);
+    const unsigned long long over = __ballot(mine_seg > 0.0 && excl_t + mine_seg > goal);
+    if (lane == 0) {
+        sh_first[wid] = over ? wid * kWave + __ffsll(static_cast<long long>(over)) - 1 : kSegThreads;
+        sh_last[wid] = has ? wid * kWave + 63 - __clzll(static_cast<long long>(has)) : -1;
     }
     __syncthreads();
-    int win_t = sh_winner;
-    if (win_t == kSegThreads) win_t = sh_last_pos < 0 ? 0 : sh_last_pos;   // rounding pushed the goal past the end
+    int win_t = kSegThreads, last_t = -1;
+#pragma unroll
+    for (int wv = 0; wv < kSegThreads / kWave; ++wv) { win_t = min(win_t, sh_first[wv]); last_t = max(last_t, sh_last[wv]); }
+    if (win_t == kSegThreads) win_t = last_t < 0 ? 0 : last_t;   // rounding pushed the goal past the end
     __syncthreads();
     if (tid == win_t) {
         double cum = excl_t, cum_before = excl_t;

@@ -61,7 +61,7 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
     __shared__ double sh_d[kSampWaves];
     __shared__ double sh_scan[kSampWaves];
     __shared__ float sh_f[kSampWaves];
-    __shared__ int sh_seg, sh_winner, sh_last_pos;
+    __shared__ int sh_seg, sh_first[kSampWaves], sh_last[kSampWaves];
     __shared__ double sh_local_target, sh_total;
     const int row_id = blockIdx.x, tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wid = tid / kWave;
@@ -103,20 +103,25 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
     const double W = block_sum(mine_seg, sh_d);
     const double u = philox_uniform(seed, offset, static_cast<uint32_t>(row_id), slot);
     const double goal = u * W;
-    if (tid == 0) { sh_winner = kSampThreads; sh_last_pos = -1; }
     const double incl_t = wave_inclusive_sum(mine_seg);
     if (lane == kWave - 1) sh_scan[wid] = incl_t;
     __syncthreads();
     double wave_off = 0.0;
     for (int wv = 0; wv < wid; ++wv) wave_off += sh_scan[wv];
     const double excl_t = wave_off + incl_t - mine_seg;
-    if (mine_seg > 0.0) {
-        atomicMax(&sh_last_pos, tid);
-        if (excl_t + mine_seg > goal) atomicMin(&sh_winner, tid);
+    // per wave: first thread whose running total exceeds the goal, last thread with any weight
+    // (ballots; same-address LDS atomics from every lane serialise and cost microseconds)
+    const unsigned long long has = __ballot(mine_seg > 0.0);
+    const unsigned long long over = __ballot(mine_seg > 0.0 && excl_t + mine_seg > goal);
+    if (lane == 0) {
+        sh_first[wid] = over ? wid * kWave + __ffsll(static_cast<long long>(over)) - 1 : kSampThreads;
+        sh_last[wid] = has ? wid * kWave + 63 - __clzll(static_cast<long long>(has)) : -1;
     }
     __syncthreads();
-    int win_t = sh_winner;
-    if (win_t == kSampThreads) win_t = sh_last_pos < 0 ? 0 : sh_last_pos;     // rounding pushed the goal past the end
+    int win_t = kSampThreads, last_t = -1;
+#pragma unroll
+    for (int wv = 0; wv < kSampWaves; ++wv) { win_t = min(win_t, sh_first[wv]); last_t = max(last_t, sh_last[wv]); }
+    if (win_t == kSampThreads) win_t = last_t < 0 ? 0 : last_t;     // rounding pushed the goal past the end
     if (tid == win_t) {
         double cum = excl_t, cum_before = excl_t, cum_before_last = excl_t;
         int found = -1, last_pos = s0 < nseg ? s0 : 0;
