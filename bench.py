@@ -48,6 +48,17 @@ def generate(name: str, seed: int, workers: int):
     return target, draft, tokens
 
 
+def committed_traffic(tag: str):
+    """HBM bytes per call from the committed rocprofv3 --pmc summary profiles/hbm_traffic_<tag>.txt (FETCH_SIZE +
+    WRITE_SIZE, calibrated against a plain copy), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % tag)
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    return None
+
+
 def bench_modify(a, w, sg, torch, tl, dl, tk, ws, out):
     """One step = one specgbv_modify_target call over the whole batch: M = L draft rows plus the bonus row per
     draft, float32 log-probabilities of both models written.  The carried ratios and row counts are those a
@@ -84,7 +95,8 @@ def bench_modify(a, w, sg, torch, tl, dl, tk, ws, out):
                        w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
                    "mean_rows_modified": float(np.mean(counts)), "outputs": "logq [B,K,L+1,V] and logp [B,K,L,V], float32"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "k_modify",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": committed_traffic("modify_" + w.name),
+                     "kernel": "k_mod_stats + k_mod_norm + k_mod_write",
                      "kernel_ms_avg": avg, "kernel_ms_min": ker[0],
                      "algorithmic_bytes_per_launch": read_b + write_b,
                      "algorithmic_read_bytes": read_b, "algorithmic_write_bytes": write_b},
@@ -119,7 +131,8 @@ def bench_sample(a, w, sg, torch, dl):
         "config": {"workload": "%s: %d draft rows (batch %d x K=%d) of one position, V=%d, %s logits, T=%g" % (
             w.name, n, w.batch, w.K, w.V, w.dtype, w.temperature)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "k_sample_rows",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": committed_traffic("sample_" + w.name),
+                     "kernel": "k_sample_rows",
                      "kernel_ms_avg": avg, "kernel_ms_min": ker[0], "algorithmic_bytes_per_launch": bytes_},
     }
 
@@ -174,13 +187,6 @@ def main() -> int:
         sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, offset, workspace=ws, out=out, algo=a.algo,
                              events=events)
 
-    if a.op == "sample":
-        print(json.dumps(bench_sample(a, w, sg, torch, dl)))
-        return 0
-    if a.op == "modify":
-        print(json.dumps(bench_modify(a, w, sg, torch, tl, dl, tk, ws, out)))
-        return 0
-
     if a.calibrate_copy_mib > 0:
         src = torch.empty(a.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -188,6 +194,13 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if a.op == "sample":
+        print(json.dumps(bench_sample(a, w, sg, torch, dl)))
+        return 0
+    if a.op == "modify":
+        print(json.dumps(bench_modify(a, w, sg, torch, tl, dl, tk, ws, out)))
+        return 0
 
     for i in range(a.warmup):
         step(i)
@@ -217,12 +230,7 @@ def main() -> int:
 
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE +
     # WRITE_SIZE, calibrated against a plain copy), if one exists for this workload and schedule
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % a.workload)
-    if os.path.exists(tpath):
-        for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = float(line.split(":", 1)[1])
+    traffic = committed_traffic(a.workload) if a.algo != "split" else None
 
     res = {
         "metric": "verifications/sec and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",
