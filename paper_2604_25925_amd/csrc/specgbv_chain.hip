@@ -320,7 +320,7 @@ __device__ __forceinline__ void run_steps(std::integer_sequence<int, Js...>, con
 template <typename T, int KP, int RS>
 __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
-        int K, int L, int V, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
+        int K, int L, int V, long long nchains, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
         int32_t *__restrict__ final_counter)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
@@ -332,14 +332,16 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     const unsigned lds_wave_addr = static_cast<unsigned>(
         reinterpret_cast<uintptr_t>(static_cast<void *>(&lds_all[tid & ~(kWave - 1u)])));
     const LdsSlots lds{lds_all, static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(lds_wave_addr)))};
-    const long long bk = blockIdx.x;                       // b*K + k
-    if (tid == 0 && bk % K == 0) final_counter[bk / K] = 0;   // arrival counter of the final-token kernel
     const int nvec = V / PV;                               // host guarantees nvec >= RS * 512
     const int rem = nvec - static_cast<int>(tid);          // slot j holds a vector of this thread iff j*512 < rem
     const int nslots = (nvec + kChainThreads - 1) / kChainThreads;
     const int n_on = nslots < NS ? nslots : NS;            // on-chip slots in use
-    const T *trow0 = target + bk * (L + 1) * static_cast<long long>(V);
-    const T *drow0 = draft + bk * L * static_cast<long long>(V);
+    // This workgroup walks the (prefix, draft) chains blockIdx.x, blockIdx.x + gridDim.x, ... one after
+    // the other as ONE sequence of rows: the last sum of a chain overlaps the first loads of the next.
+    // (32-bit arithmetic: the host checks that batch * K * (L + 1) stays below 2^31)
+    const int nmine = static_cast<int>((nchains - blockIdx.x + gridDim.x - 1) / gridDim.x);
+    const int nrows = nmine * L;                           // rows of this workgroup, in the order it visits them
+    auto chain_of = [&](int g) { return static_cast<long long>(blockIdx.x) + static_cast<long long>(g / L) * gridDim.x; };
 
     U4 rq[RS], rp[RS];
 #pragma unroll
@@ -350,24 +352,31 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     double Zq_prev = 1.0;                                  // target normaliser of the row in sweep 2
     double log2nu = 0.0;                                   // block ratio of the rows before the row being loaded
 
-    // Iteration `it` overlaps three things slot by slot: sweep 2 of row it-1 (its Eq. (hik)
-    // sum, rows >= 1), the load of row it into the slot that sweep 2 just released, and
-    // sweep 1 of row it on the slot loaded kLag steps earlier.  Loads are therefore issued
-    // evenly over the whole row period and the memory pipeline never drains between rows.
-    for (int it = 0; it <= L; ++it) {
-        const bool do_new = it < L;                        // a row is being loaded and gets its statistics
-        const bool do_sum = it >= 2;                       // row it-1 >= 1 gets its Eq. (hik) sum
-        const int r_new = do_new ? it : L - 1;             // keeps every address in bounds
-        const T *qnew = trow0 + static_cast<long long>(r_new) * V;
-        const T *pnew = drow0 + static_cast<long long>(r_new) * V;
-        const T *qold = trow0 + static_cast<long long>(it >= 1 ? it - 1 : 0) * V;
-        const T *pold = drow0 + static_cast<long long>(it >= 1 ? it - 1 : 0) * V;
+    // Iteration g overlaps three things slot by slot: sweep 2 of row g-1 (its Eq. (hik) sum, unless it
+    // is the first row of its chain), the load of row g into the slot that sweep 2 just released, and
+    // sweep 1 of row g on the slot loaded kLag steps earlier.  Loads are therefore issued evenly over
+    // the whole row period and the memory pipeline never drains between rows.
+    for (int g = 0; g <= nrows; ++g) {
+        const bool do_new = g < nrows;                     // a row is being loaded and gets its statistics
+        const int g_new = do_new ? g : nrows - 1;          // keeps every address in bounds
+        const long long bk_new = chain_of(g_new);
+        const int r_new = g_new % L;
+        const int g_old = g >= 1 ? g - 1 : 0;
+        const long long bk_old = chain_of(g_old);
+        const int r_old = g_old % L;
+        const bool do_sum = g >= 1 && r_old >= 1;          // rows >= 1 get their Eq. (hik) sum
+        const T *qnew = target + (bk_new * (L + 1) + r_new) * static_cast<long long>(V);
+        const T *pnew = draft + (bk_new * L + r_new) * static_cast<long long>(V);
+        const T *qold = target + (bk_old * (L + 1) + r_old) * static_cast<long long>(V);
+        const T *pold = draft + (bk_old * L + r_old) * static_cast<long long>(V);
         const unsigned off_new = do_new ? tid * 16u : 0u;  // after the last row: one harmless line
+        if (do_new && r_new == 0 && tid == 0 && bk_new % K == 0)
+            final_counter[bk_new / K] = 0;                 // arrival counter of the final-token kernel
 
         // Reference exponents of the new row: its token's logits (the drafted token was
         // sampled from this draft row, so no entry can exceed it by a factor near 2^127
         // unless the row is extremely peaked; that case is caught below).
-        int tok = tokens[bk * L + r_new];
+        int tok = tokens[bk_new * L + r_new];
         tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
         const float zq_tok = Elem<T>::scalar(qnew + tok), zp_tok = Elem<T>::scalar(pnew + tok);
         RowConsts rc_new;
@@ -388,8 +397,9 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp), s_tot = static_cast<double>(acc);
         block_sum3(Zq_tot, Zp_tot, s_tot, sh_d);
         Zq_tot = uniform_d(Zq_tot); Zp_tot = uniform_d(Zp_tot); s_tot = uniform_d(s_tot);
-        if (do_sum && tid == 0) s_out[bk * L + it - 1] = s_tot / Zq_prev;
+        if (do_sum && tid == 0) s_out[bk_old * L + r_old] = s_tot / Zq_prev;
         if (do_new) {
+            if (r_new == 0) log2nu = 0.0;                  // a new chain starts from the empty block
             float ref_q = -rc_new.nref_q, ref_p = -rc_new.nref_p;
             if (!(Zq_tot < 1.0e37) || !(Zq_tot > 0.0)) {   // float32 overflow with the token reference
                 const ExactStats e = exact_row_stats<T>(qnew, nvec, c, sh_d);
@@ -406,7 +416,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             if (tid == 0) {
                 RowStat st;
                 st.lse2_q = lse2_q; st.lse2_p = lse2_p; st.tok2_q = tok2_q; st.tok2_p = tok2_p;
-                stats[bk * L + it] = st;
+                stats[bk_new * L + r_new] = st;
             }
             // constants of this row's sweep 2 (next iteration)
             const double C2 = lse2_p - lse2_q + log2nu;
@@ -420,18 +430,33 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     }
 }
 
+// Workgroups that can be resident at once: one per compute unit (a workgroup takes 144 KiB of LDS).
+int resident_workgroups()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+    }
+    return cached[dev];
+}
+
 template <typename T, int KP>
 hipError_t launch_kp(const Problem &p)
 {
     RowStat *stats = reinterpret_cast<RowStat *>(p.ws + p.lay.stats);
     double *s = reinterpret_cast<double *>(p.ws + p.lay.s);
-    const dim3 grid(static_cast<unsigned>(static_cast<long long>(p.batch) * p.K));
+    const long long nchains = static_cast<long long>(p.batch) * p.K;
+    const long long cus = resident_workgroups();
+    const dim3 grid(static_cast<unsigned>(nchains < cus ? nchains : cus));
     const T *target = static_cast<const T *>(p.target);
     const T *draft = static_cast<const T *>(p.draft);
     const int full_slots = (p.V / Elem<T>::kPerVec) / kChainThreads;
 #define SPECGBV_LAUNCH(RS)                                                                              \
     hipLaunchKernelGGL((k_chain<T, KP, RS>), grid, dim3(kChainThreads), 0, p.stream, target, draft,    \
-                       p.tokens, p.K, p.L, p.V, p.c, stats, s, reinterpret_cast<int32_t *>(p.ws + p.lay.counter))
+                       p.tokens, p.K, p.L, p.V, nchains, p.c, stats, s, reinterpret_cast<int32_t *>(p.ws + p.lay.counter))
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);
