@@ -125,7 +125,7 @@ specgbv_status specgbv_verify_ex(
         if (!chain_supported(p)) return fail(SPECGBV_EUNSUPPORTED, "the chain schedule does not support this shape");
         use_chain = true;
     } else if (algo == SPECGBV_ALGO_AUTO) {
-        use_chain = chain_supported(p) && static_cast<long long>(batch) * K >= 128;
+        use_chain = chain_preferred(p);
     }
 
     hipError_t e;

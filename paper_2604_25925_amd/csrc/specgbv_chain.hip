@@ -487,6 +487,14 @@ bool chain_supported(const Problem &p)
            reinterpret_cast<uintptr_t>(p.target) % 16 == 0 && reinterpret_cast<uintptr_t>(p.draft) % 16 == 0;
 }
 
+// The chain schedule takes about the same time for any number of chains up to one per compute unit
+// (each workgroup streams its own rows), the two-pass schedule takes time in proportion to the
+// bytes: measured at V = 128256, bf16, L = 8 on 256 compute units they cross at 140 chains.
+bool chain_preferred(const Problem &p)
+{
+    return chain_supported(p) && static_cast<long long>(p.batch) * p.K * 20 >= static_cast<long long>(resident_workgroups()) * 11;
+}
+
 hipError_t launch_chain_main(const Problem &p)
 {
     return p.dtype == 1 ? launch_typed<uint16_t>(p) : launch_typed<float>(p);

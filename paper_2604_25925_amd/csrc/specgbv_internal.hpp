@@ -60,6 +60,7 @@ hipError_t launch_split_main(const Problem &p);
 // the statistics sweep and the Eq. (hik) sweep.  chain_supported() says whether the shape
 // fits the kernel's static limits.
 bool chain_supported(const Problem &p);
+bool chain_preferred(const Problem &p);      // supported, and enough chains for it to beat the two-pass schedule
 hipError_t launch_chain_main(const Problem &p);
 
 // Decision scan (Algorithm 1) and final-token kernels (Eq. (pres) / bonus token).
