@@ -279,6 +279,13 @@ def main() -> int:
                                "sample": "first %d of %d prefixes of the same batch, float64, 1 thread, %.1f s" % (
                                    n, w.batch, cpu_s),
                                "host_cpus": os.cpu_count()}
+        # the same oracle with one thread per host core (prefixes distributed over threads), whole batch
+        nthr = min(os.cpu_count() or 1, oracle.num_procs(), w.batch)
+        if nthr > 1:
+            t0 = time.perf_counter()
+            oracle.verify(target, draft, tokens, w.temperature, a.seed, 0, nthreads=nthr)
+            res["cpu_baseline"]["all_cores"] = {"value": w.batch / (time.perf_counter() - t0), "cores": nthr,
+                                                "sample": "all %d prefixes" % w.batch}
         # the last timed step used the same counters: report agreement on the sample
         step(a.warmup + a.steps - 1)
         torch.cuda.synchronize()
