@@ -2,8 +2,9 @@
 (specgbv_verify), modify the next iteration's target rows (specgbv_modify_target), repeat.
 
 With one draft per prefix the decoded text must be distributed exactly as the target model
-(Theorem 4.2 applied iteration after iteration), which this test checks on the first three
-decoded tokens of many independent prefixes that share small conditional tables.  The only
+(Theorem 4.2 applied iteration after iteration); with K >= 2 drafts it follows the law of the
+printed algorithm, obtained by enumerating three iterations in exact rationals.  The test checks
+the first three decoded tokens of many independent prefixes that share small conditional tables.  The only
 host-side work is looking up each row's logits in the tables, i.e. playing the two models."""
 import itertools
 
@@ -23,8 +24,8 @@ def _markov_tables(rng, V):
     return (lambda block: p2(last(block))), (lambda block: q2(last(block)))
 
 
-@pytest.mark.parametrize("K,L", [(1, 2), (1, 3), (1, 4)])
-def test_three_iterations_decode_the_target_law(K, L):
+@pytest.mark.parametrize("V,K,L", [(3, 1, 2), (3, 1, 3), (3, 1, 4), (2, 2, 2), (2, 2, 3)])
+def test_three_iterations_decode_the_exact_law(V, K, L):
     """Algorithm 3 updates q in place ("q <- DistributionModification(q, ...)"), so a modification
     made after one iteration is still in force for its remaining positions when the next iteration
     ends early, and the next modification applies on top of it.  The driver below therefore keeps
@@ -34,8 +35,8 @@ def test_three_iterations_decode_the_target_law(K, L):
     obtained by applying them one after the other with specgbv_modify_target."""
     import torch
     import paper_2604_25925_amd as sg
-    rng = np.random.default_rng(100 + L)
-    V, n, iters, m = 3, 60000, 3, 3
+    rng = np.random.default_rng(100 + L + 10 * K)
+    n, iters, m = 60000, 3, 3
     p_of, q_of = _markov_tables(rng, V)
     ctx = [c for r in range(3) for c in itertools.product(range(V), repeat=r)]
     row_id = {c: i for i, c in enumerate(ctx)}
@@ -86,15 +87,21 @@ def test_three_iterations_decode_the_target_law(K, L):
             sg.specgbv_carry_advance(level_rows[lvl], dl, tk, acc, f, out, 1.0, carry, count)
         pending.append((torch.from_numpy(inter["carry_log_nu"]).to(dev), torch.from_numpy(inter["modify_count"]).to(dev)))
         pending = [pc for pc in pending if bool(pc[1].any())][-(L - 1):] if L > 1 else []
-    # ---- the first m decoded tokens against the target model's joint law
+    # ---- the first m decoded tokens against the exact law: the target model's joint law for one draft
+    # (Theorem 4.2, iteration after iteration), the enumerated law of the printed algorithm for K >= 2
+    if K == 1:
+        law = {blk: ee.joint(q_of, blk) for blk in itertools.product(range(V), repeat=m)}
+    else:
+        law = {}
+        for t, pr in ee.enumerate_decoding(p_of, q_of, V, L, K, iters).items():
+            law[t[:m]] = law.get(t[:m], 0) + pr
     counts = {}
     for t in text:
         counts[t[:m]] = counts.get(t[:m], 0) + 1
-    stat = 0.0
-    for blk in itertools.product(range(V), repeat=m):
-        e = float(ee.joint(q_of, blk)) * n
-        stat += (counts.get(blk, 0) - e) ** 2 / e
-    assert stat < chi2.ppf(1 - 1e-6, V ** m - 1), "chi-squared %.1f on %d degrees of freedom" % (stat, V ** m - 1)
+    assert set(counts) <= {b for b, pr in law.items() if pr > 0}
+    stat = sum((counts.get(blk, 0) - float(pr) * n) ** 2 / (float(pr) * n) for blk, pr in law.items() if pr > 0)
+    dof = sum(1 for pr in law.values() if pr > 0) - 1
+    assert stat < chi2.ppf(1 - 1e-6, dof), "chi-squared %.1f on %d degrees of freedom" % (stat, dof)
     # and the draft model's law is clearly different (the test can tell them apart)
     stat_p = sum((counts.get(blk, 0) - float(ee.joint(p_of, blk)) * n) ** 2 / (float(ee.joint(p_of, blk)) * n)
                  for blk in itertools.product(range(V), repeat=m))
