@@ -386,11 +386,27 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         float Zq = 0.0f, Zp = 0.0f, acc = 0.0f;
         StepCtx<T> cx{qnew, pnew, rc_sum, rc_new, tid, off_new, nvec, rem, n_on, do_new, do_sum};
         run_steps<T, KP, RS>(std::make_integer_sequence<int, NS + kLag>{}, cx, rq, rp, lds, Zq, Zp, acc);
-        // vectors that do not fit on chip: read for the statistics now, once more for the sum
-        for (int j = NS; j < nslots; ++j) {
-            if (j * kChainThreads < rem) {
-                if (do_new) sweep1_vec<T>(load_slot(qnew, j, tid), load_slot(pnew, j, tid), rc_new, Zq, Zp);
-                if (do_sum) sweep2_vec<T, KP>(load_slot(qold, j, tid), load_slot(pold, j, tid), rc_sum, acc);
+        // vectors that do not fit on chip: read for the statistics now, once more for the sum; the
+        // loads of the next slot are issued before the arithmetic of the current one
+        if (NS < nslots) {
+            const U4 zero{0, 0, 0, 0};
+            auto fetch = [&](int j, U4 &a, U4 &b, U4 &cc, U4 &dd) {
+                const bool live = j < nslots && j * kChainThreads < rem;
+                a = (live && do_new) ? load_slot(qnew, j, tid) : zero;
+                b = (live && do_new) ? load_slot(pnew, j, tid) : zero;
+                cc = (live && do_sum) ? load_slot(qold, j, tid) : zero;
+                dd = (live && do_sum) ? load_slot(pold, j, tid) : zero;
+            };
+            U4 a0, b0, c0, d0;
+            fetch(NS, a0, b0, c0, d0);
+            for (int j = NS; j < nslots; ++j) {
+                U4 a1, b1, c1, d1;
+                fetch(j + 1, a1, b1, c1, d1);
+                if (j * kChainThreads < rem) {
+                    if (do_new) sweep1_vec<T>(a0, b0, rc_new, Zq, Zp);
+                    if (do_sum) sweep2_vec<T, KP>(c0, d0, rc_sum, acc);
+                }
+                a0 = a1; b0 = b1; c0 = c1; d0 = d1;
             }
         }
 
