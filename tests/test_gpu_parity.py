@@ -116,6 +116,14 @@ def test_chain_schedule_draft_counts(K, V, dtype):
     check_case(t, d, tok, T, 4, 1, "chain", "chain K=%d V=%d %s" % (K, V, dtype))
 
 
+@pytest.mark.parametrize("B,K,L,V,dtype", [(75, 4, 3, 32768, "bf16"), (130, 2, 2, 16384, "f32"), (43, 7, 2, 29696, "bf16")])
+def test_chain_schedule_more_chains_than_compute_units(B, K, L, V, dtype):
+    # above one chain per compute unit a workgroup walks several chains as one row sequence
+    # (300, 260 and 301 chains on 256 compute units: uneven shares, chain boundaries inside the pipeline)
+    t, d, tok, T = _gauss_case(B, K, L, V, dtype, seed=33)
+    check_case(t, d, tok, T, 6, 2, "chain", "chain %d chains V=%d %s" % (B * K, V, dtype))
+
+
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("T", [0.1, 0.4, 2.0])
 def test_temperature(algo, T):
