@@ -108,7 +108,8 @@ def test_shapes_and_ragged_tails(algo, B, K, L, V, dtype):
 
 
 @pytest.mark.parametrize("K,V,dtype", [(1, 32768, "bf16"), (2, 16384, "f32"), (3, 40960, "bf16"), (4, 32768, "bf16"),
-                                        (5, 32768, "bf16"), (16, 16384, "f32"), (8, 94208, "bf16"), (3, 65536, "f32")])
+                                        (5, 32768, "bf16"), (16, 16384, "f32"), (8, 94208, "bf16"), (3, 65536, "f32"),
+                                        (2, 100000, "f32"), (4, 200064, "bf16")])   # rows larger than the on-chip slots
 def test_chain_schedule_draft_counts(K, V, dtype):
     # the on-chip schedule has one unrolled variant per common draft count (and a generic one) and
     # three register-slot counts chosen by V; K = 1 is single-draft greedy block verification
