@@ -127,7 +127,16 @@ __device__ __forceinline__ void sweep2_vec(const U4 &q, const U4 &p, const RowCo
 // no per-load vector address arithmetic, no 64-bit address registers).
 __device__ __forceinline__ U4 load_vec(const void *base_uniform, unsigned lane_byte_off)
 {
-    return *reinterpret_cast<const U4 *>(static_cast<const char *>(base_uniform) + lane_byte_off);
+    // The base is pinned to a scalar register pair: otherwise the compiler folds it into a
+    // 64-bit per-lane address first and then spends vector adds on each slot's constant.
+    // (The pointer keeps its global address space through the opaque copy; a generic pointer
+    // would turn the access into a flat load.)
+    typedef unsigned int V4 __attribute__((ext_vector_type(4)));
+    typedef const __attribute__((address_space(1))) char *GlobalBytes;
+    GlobalBytes b = (GlobalBytes)base_uniform;
+    asm volatile("" : "+s"(b));
+    const V4 v = *(const __attribute__((address_space(1))) V4 *)(b + lane_byte_off);
+    return U4{v.x, v.y, v.z, v.w};
 }
 template <typename T>
 __device__ __forceinline__ U4 load_slot(const T *row, int slot, unsigned lane)
