@@ -103,6 +103,46 @@ def bench_modify(a, w, sg, torch, tl, dl, tk, ws, out):
     }
 
 
+def bench_pending(a, w, sg, torch, tl, dl, tk, ws, out):
+    """One step = one specgbv_verify_ex call that applies a pending distribution modification on the fly
+    (Algorithm 2 inside the verification of the next iteration).  The carried ratios and row counts are those
+    a verification of the same batch leaves in its workspace (the tensors stand in for the next iteration's)."""
+    sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 0, workspace=ws, out=out, algo=a.algo)
+    torch.cuda.synchronize()
+    dt = 1 if w.dtype == "bf16" else 0
+    inter = sg.specgbv_read_intermediates(ws, w.batch, w.K, w.L, w.V, dt)
+    pend = (torch.from_numpy(inter["carry_log_nu"]).to(tl.device), torch.from_numpy(inter["modify_count"]).to(tl.device))
+    for i in range(a.warmup):
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1 + i, workspace=ws, out=out, pending=pend)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    t0 = time.perf_counter()
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1 + a.warmup + i, workspace=ws, out=out, pending=pend)
+        e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+    ker = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    avg = sum(ker) / len(ker)
+    bytes_ = w.batch * w.K * w.L * 2 * w.V * w.elem_bytes     # every (target, draft) row pair once
+    achieved = bytes_ / (avg * 1e-3) / 1e9
+    return {
+        "metric": "verifications/sec under a pending distribution modification applied on the fly (Algorithms 1 + 2) "
+                  "and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",
+        "value": w.batch / (ms_per_step * 1e-3), "unit": "verifications/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: batch %d, K=%d, L=%d, V=%d, %s logits, T=%g" % (
+                       w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
+                   "mean_rows_modified": float(np.mean(inter["modify_count"])), "schedule": "two-pass"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": committed_traffic("pending_" + w.name),
+                     "kernel": "k_row_stats + k_pend_norm + k_ot_sum + k_final (whole call)",
+                     "kernel_ms_avg": avg, "kernel_ms_min": ker[0], "algorithmic_bytes_per_launch": bytes_},
+    }
+
+
 def bench_sample(a, w, sg, torch, dl):
     """One step = one specgbv_sample_tokens call: one token for each of the batch * K draft rows of one position."""
     rows = dl[:, :, 0].contiguous().view(w.batch * w.K, w.V)
@@ -144,10 +184,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--algo", default="auto", choices=["auto", "split", "chain"])
-    ap.add_argument("--op", default="verify", choices=["verify", "modify", "sample"],
+    ap.add_argument("--op", default="verify", choices=["verify", "modify", "sample", "pending"],
                     help="verify: the verification call (the benchmark); modify: the distribution modification "
                          "(Algorithm 2) for the drafts of the next iteration, on the same tensors; "
-                         "sample: the draft-side token draw of one position (Algorithm 3) over the batch * K draft rows")
+                         "sample: the draft-side token draw of one position (Algorithm 3) over the batch * K draft rows; "
+                         "pending: the verification with a pending modification applied on the fly")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -200,6 +241,9 @@ def main() -> int:
         return 0
     if a.op == "modify":
         print(json.dumps(bench_modify(a, w, sg, torch, tl, dl, tk, ws, out)))
+        return 0
+    if a.op == "pending":
+        print(json.dumps(bench_pending(a, w, sg, torch, tl, dl, tk, ws, out)))
         return 0
 
     for i in range(a.warmup):

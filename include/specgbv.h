@@ -114,6 +114,21 @@ typedef struct specgbv_options {
     void *ev_main_start;       /* hipEvent_t or NULL: recorded on the stream immediately    */
     void *ev_main_stop;        /*   before / after the vocabulary-streaming kernels that    */
                                /*   compute the statistics and the sums of Eq. (hik)        */
+    /*
+     * Pending distribution modification (Algorithm 2) applied on the fly: both NULL (none) or both
+     * device pointers.  The first pending_count[b] rows of every draft of prefix b are verified
+     * against q_new of Algorithm 2 (computed from the same target and draft rows, never written
+     * out) instead of the target rows, with the block ratio starting from
+     * exp(pending_carry_log_nu[b]); the outputs are those of specgbv_modify_target followed by a
+     * verification of its rows.  The pair is what the previous iteration left in its workspace
+     * (specgbv_workspace_carry; the pointers may point into the workspace passed to this call:
+     * they are read before the new values are written), possibly advanced by
+     * specgbv_carry_advance.  One pending modification only: where two are pending on the same
+     * rows, apply them with specgbv_modify_target.  Runs on the two-pass schedule
+     * (SPECGBV_ALGO_CHAIN is rejected).  A modified row whose weights are all zero stays q.
+     */
+    const double *pending_carry_log_nu;   /* device, [batch] */
+    const int32_t *pending_count;         /* device, [batch], values below 0 or above L are clamped */
 } specgbv_options;
 
 /* specgbv_verify with explicit options (options == NULL means defaults). */

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "specgbv_oracle.c")
 _LIB = os.path.join(_HERE, "libspecgbv_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F64 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -157,12 +157,15 @@ def sample_cdf(w, u: float):
 
 
 def to_raw(logits: np.ndarray):
-    """(contiguous array, dtype code) for float32 arrays or uint16 bfloat16 bit patterns."""
+    """(contiguous array, dtype code) for float32 arrays, uint16 bfloat16 bit patterns, or float64
+    arrays (one oracle result fed to another oracle function without rounding)."""
     if logits.dtype == np.float32:
         return np.ascontiguousarray(logits), F32
+    if logits.dtype == np.float64:
+        return np.ascontiguousarray(logits), F64
     if logits.dtype == np.uint16:
         return np.ascontiguousarray(logits), BF16
-    raise TypeError("logits must be float32 or uint16 (bfloat16 bits), got %s" % logits.dtype)
+    raise TypeError("logits must be float32, float64 or uint16 (bfloat16 bits), got %s" % logits.dtype)
 
 
 def verify(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np.ndarray,

@@ -62,6 +62,7 @@
 
 #define ORACLE_F32 0
 #define ORACLE_BF16 1
+#define ORACLE_F64 2      /* float64 rows: lets one oracle result (log-probabilities) feed another exactly */
 
 /* ------------------------------------------------------------------ Philox */
 
@@ -121,6 +122,8 @@ static void load_row(const void *base, int dtype, size_t row, int V, double *z)
     if (dtype == ORACLE_BF16) {
         const uint16_t *p = (const uint16_t *)base + row * (size_t)V;
         for (int x = 0; x < V; ++x) z[x] = bf16_to_double(p[x]);
+    } else if (dtype == ORACLE_F64) {
+        memcpy(z, (const double *)base + row * (size_t)V, sizeof(double) * (size_t)V);
     } else {
         const float *p = (const float *)base + row * (size_t)V;
         for (int x = 0; x < V; ++x) z[x] = (double)p[x];
@@ -442,7 +445,7 @@ static void verify_one(const void *target_logits, const void *draft_logits,
 /*
  * Host-pointer twin of the GPU entry point.
  *   target_logits [batch, K, L+1, V], draft_logits [batch, K, L, V] (dtype:
- *   0 = float32, 1 = bfloat16 bit patterns), draft_tokens [batch, K, L].
+ *   0 = float32, 1 = bfloat16 bit patterns, 2 = float64), draft_tokens [batch, K, L].
  *   Outputs accepted_len [batch], accepted_draft_idx [batch] (-1 when 0
  *   tokens are accepted), out_tokens [batch, L+1] (accepted tokens, the final
  *   token, then -1).  prefix_ids (may be NULL) gives the Philox prefix counter of each
@@ -462,7 +465,7 @@ int specgbv_oracle_verify(const void *target_logits, const void *draft_logits,
         !accepted_draft_idx || !out_tokens)
         return 1;
     if (K < 1 || L < 1 || V < 1 || batch < 0) return 1;
-    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F64) return 1;
     if (!(temperature > 0.0f) || !isfinite(temperature)) return 1;
     for (size_t j = 0; j < (size_t)batch * K * L; ++j)
         if (draft_tokens[j] < 0 || draft_tokens[j] >= V) return 1;
@@ -519,7 +522,7 @@ int specgbv_oracle_modify(const void *target_logits, const void *draft_logits,
 {
     if (!target_logits || !draft_logits || !tokens || !carry_log_nu || !count || !out_logq) return 1;
     if (K < 1 || M < 1 || V < 1 || batch < 0) return 1;
-    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F64) return 1;
     if (!(temperature > 0.0f) || !isfinite(temperature)) return 1;
     const double T = (double)temperature;
     double *z = (double *)malloc(sizeof(double) * (size_t)V);
@@ -582,7 +585,7 @@ int specgbv_oracle_sample_rows(const void *logits, int rows, int V, int dtype,
                                double *margin_out)
 {
     if (!logits || !out_tokens || rows < 0 || V < 1) return 1;
-    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F64) return 1;
     if (!(temperature > 0.0f) || !isfinite(temperature) || position >= 0x80000000u) return 1;
     const double T = (double)temperature;
     double *z = (double *)malloc(sizeof(double) * (size_t)V);
@@ -626,7 +629,7 @@ int specgbv_oracle_carry_advance(const void *rows_q, const void *rows_p, const i
     if (!rows_q || !rows_p || !tokens || !accepted_len || !accepted_idx || !out_tokens || !carry_log_nu || !count)
         return 1;
     if (K < 1 || M < 1 || V < 1 || batch < 0 || (bonus != 0 && bonus != 1)) return 1;
-    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F64) return 1;
     if (!(temperature > 0.0f) || !isfinite(temperature)) return 1;
     const double T = (double)temperature;
     double *z = (double *)malloc(sizeof(double) * (size_t)V);

@@ -32,7 +32,8 @@ class SpecGBVError(RuntimeError):
 
 
 class _Options(ctypes.Structure):
-    _fields_ = [("algo", c_int32), ("reserved", c_int32), ("ev_main_start", c_void_p), ("ev_main_stop", c_void_p)]
+    _fields_ = [("algo", c_int32), ("reserved", c_int32), ("ev_main_start", c_void_p), ("ev_main_stop", c_void_p),
+                ("pending_carry_log_nu", c_void_p), ("pending_count", c_void_p)]
 
 
 class _Intermediates(ctypes.Structure):
@@ -145,12 +146,14 @@ def _shapes(target_logits, draft_logits, draft_tokens):
 
 def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int,
                       rng_offset: int, *, workspace=None, out: Optional[Tuple] = None, algo="auto",
-                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None):
+                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None, pending=None):
     """Enqueue one verification on the current (or given) HIP stream.
 
     Returns (accepted_len [B], accepted_draft_idx [B], out_tokens [B, L+1], workspace), all
     device tensors; nothing is synchronised.  `events` is a pair of raw hipEvent_t handles
-    recorded around the vocabulary-streaming kernels.
+    recorded around the vocabulary-streaming kernels.  `pending` is a pair (carry_log_nu, count)
+    of [B] float64 / int32 device tensors or raw device addresses: a pending distribution
+    modification (Algorithm 2) applied on the fly to the first count[b] rows of every draft.
     """
     import torch
     lib = load_library()
@@ -166,8 +169,14 @@ def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: fl
     acc_len, acc_idx, out_tokens = out
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
+    if pending is not None:
+        for t, dtp in ((pending[0], torch.float64), (pending[1], torch.int32)):
+            if not isinstance(t, int) and (t.dtype != dtp or tuple(t.shape) != (B,) or not t.is_cuda):
+                raise ValueError("pending must be ([B] float64, [B] int32) GPU tensors or raw device addresses")
     opt = _Options(_ALGO[algo] if isinstance(algo, str) else int(algo), 0,
-                   events[0] if events else None, events[1] if events else None)
+                   events[0] if events else None, events[1] if events else None,
+                   _dev_ptr(pending[0]) if pending is not None else None,
+                   _dev_ptr(pending[1]) if pending is not None else None)
     st = lib.specgbv_verify_ex(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V,
                                B, dt, c_float(temperature), rng_seed, rng_offset, acc_len.data_ptr(),
                                acc_idx.data_ptr(), out_tokens.data_ptr(), workspace.data_ptr(),

@@ -45,6 +45,7 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.carry = take(static_cast<size_t>(batch) * sizeof(double));
     w.mcount = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.counter = take(static_cast<size_t>(batch) * sizeof(int32_t));
+    w.pend = take(n * sizeof(PendRow));
     w.total = off;
     return w;
 }
@@ -120,8 +121,19 @@ specgbv_status specgbv_verify_ex(
     p.ws = static_cast<char *>(workspace);
     p.stream = static_cast<hipStream_t>(hip_stream);
 
+    p.pend_carry = options ? static_cast<const double *>(options->pending_carry_log_nu) : nullptr;
+    p.pend_count = options ? static_cast<const int32_t *>(options->pending_count) : nullptr;
+    if ((p.pend_carry == nullptr) != (p.pend_count == nullptr))
+        return fail(SPECGBV_EINVAL, "pending_carry_log_nu and pending_count must be given together");
+    if (p.pend_carry && (reinterpret_cast<uintptr_t>(p.pend_carry) % 8 || reinterpret_cast<uintptr_t>(p.pend_count) % 4))
+        return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
+    if (p.pend_carry && algo == SPECGBV_ALGO_CHAIN)
+        return fail(SPECGBV_EUNSUPPORTED, "a pending modification runs on the two-pass schedule only");
+
     bool use_chain = false;
-    if (algo == SPECGBV_ALGO_CHAIN) {
+    if (p.pend_carry) {
+        use_chain = false;
+    } else if (algo == SPECGBV_ALGO_CHAIN) {
         if (!chain_supported(p)) return fail(SPECGBV_EUNSUPPORTED, "the chain schedule does not support this shape");
         use_chain = true;
     } else if (algo == SPECGBV_ALGO_AUTO) {
@@ -374,6 +386,6 @@ specgbv_status specgbv_read_sample_intermediates(const void *workspace, size_t w
 
 const char *specgbv_last_error(void) { return g_err; }
 
-const char *specgbv_version(void) { return "specgbv 0.2 (gfx950)"; }
+const char *specgbv_version(void) { return "specgbv 0.3 (gfx950)"; }
 
 }  // extern "C"

@@ -106,6 +106,7 @@ __device__ double clamp01(double h)
 struct DecideIO {
     const int32_t *tokens;
     const RowStat *stats;
+    const PendRow *pend;        // rows under a pending modification, or null
     const double *s_arr;
     double *log_nu_out, *log_P_out, *h_out, *eta_out;
     int32_t *state_out;
@@ -139,6 +140,7 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
     for (int idx = tid; idx < KL; idx += kDecideThreads) {
         const RowStat st = stats[base + idx];
         tq[idx] = st.tok2_q - st.lse2_q;
+        if (io.pend) tq[idx] += io.pend[base + idx].tokadj - io.pend[base + idx].log2N;   // log2 q'[token]
         tp[idx] = st.tok2_p - st.lse2_p;
         lq[idx] = st.lse2_q; lp[idx] = st.lse2_p;
         tok[idx] = tokens[base + idx];
@@ -226,6 +228,7 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         }
         Selection sl;
         sl.tau = tau;
+        sl.C1 = 0.0; sl.pend = 0; sl.pad = 0;
         sl.target_row = (static_cast<long long>(b) * K + kf) * (L + 1) + tau;
         if (tau == L) {
             sl.draft_row = -1; sl.C2 = 0.0; sl.shift_q = 0.0f; sl.lse2_q = 0.0;
@@ -235,6 +238,13 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
             sl.C2 = lse2_p - lse2_q + (tau == 0 ? 0.0 : l2nu[kf * L + tau - 1]);
             sl.shift_q = rintf(static_cast<float>(lse2_q));         // integral: partial sums rescale exactly
             sl.lse2_q = lse2_q;
+            if (io.pend && io.pend[base + kf * L + tau].flag) {     // the row is q' = q t^K / N
+                const PendRow pr = io.pend[base + kf * L + tau];
+                sl.pend = 1;
+                sl.C1 = lse2_p - lse2_q + pr.log2mu;
+                sl.C2 -= pr.log2N;
+                sl.lse2_q = lse2_q + pr.log2N;
+            }
         }
         *sel_out = sl;
     }
@@ -289,6 +299,7 @@ __device__ __forceinline__ void segment_load(const T *target, const T *draft, co
 // Weights of this lane's 8 entries of segment `seg` relative to 2^m2 (w: the weights the
 // token is drawn from; wq: plain target weights).  With m2 = NaN on entry for the bonus row
 // the segment's own maximum is used as reference and returned.
+template <bool PEND>
 __device__ __forceinline__ float segment_weigh(const Selection &sl, int V, int K, float c, int seg, int lane,
                                                float m2_in, const float (&zq)[8], const float (&zp)[8],
                                                float (&w)[8], float (&wq)[8])
@@ -308,6 +319,24 @@ __device__ __forceinline__ float segment_weigh(const Selection &sl, int V, int K
     }
     const float m2 = sl.shift_q;
     const RatioConst rc(sl.C2);
+    if (PEND && sl.pend) {
+        // modified row: plain weights q t1^K, residual weights q t1^K max(1 - p/(nu q'), 0)^K
+        const RatioConst rc1(sl.C1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool live = e0 + j < V;
+            float t1K = 0.0f, t2 = 0.0f, eq = 0.0f;
+            if (live) {
+                const float d = zp[j] - zq[j];
+                eq = exp2_fast(fmaf(zq[j], c, -m2));
+                t1K = powi_uniform(rc1.one_minus_ratio(d, c), K);
+                t2 = pend_second_factor(exp2_fast(fmaf(d, c, -rc.C2_hi)), t1K, rc.neg_kappa);
+            }
+            wq[j] = eq * t1K;
+            w[j] = wq[j] * powi_uniform(t2, K);
+        }
+        return m2;
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const bool live = e0 + j < V;
@@ -352,7 +381,7 @@ struct FinalOut {
     int32_t *mcount;
 };
 
-template <typename T, bool VEC>
+template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kSegThreads)
 k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, FinalOut fo, int V, int K, int L,
         float c, int nseg, uint64_t seed, uint64_t offset)
@@ -394,7 +423,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
             sw[i] = 0.0; sq[i] = 0.0; m2[i] = 0.0f;
             if (seg0 + i < nseg) {                      // wave-uniform
                 float w[8], wq[8];
-                m2[i] = segment_weigh(sl, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[i], w, wq);
+                m2[i] = segment_weigh<PEND>(sl, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[i], w, wq);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) { sw[i] += static_cast<double>(w[j]); sq[i] += static_cast<double>(wq[j]); }
             }
@@ -520,7 +549,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     {
         float zq[8], zp[8];
         segment_load<T, VEC>(target, draft, sl, V, seg, lane, zq, zp);
-        segment_weigh(sl, V, K, c, seg, lane, sh_seg_m2, zq, zp, w, wq);
+        segment_weigh<PEND>(sl, V, K, c, seg, lane, sh_seg_m2, zq, zp, w, wq);
     }
     double ws[8];
     double mine = 0.0;
@@ -570,7 +599,12 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
         if (sl.draft_row >= 0) {
             const double zq = static_cast<double>(Elem<T>::scalar(target + sl.target_row * V + tokid));
             const double zp = static_cast<double>(Elem<T>::scalar(draft + sl.draft_row * V + tokid));
-            carry = (sl.C2 + static_cast<double>(c) * (zq - zp)) * 0.693147180559945309417;
+            double l2 = sl.C2 + static_cast<double>(c) * (zq - zp);        // log2 of nu_tau q[y] / p[y]
+            if (PEND && sl.pend) {                                         // q'[y] = q[y] t1[y]^K / N (N is in C2)
+                const double t1 = 1.0 - exp2_small(static_cast<double>(c) * (zp - zq) - sl.C1);
+                l2 = t1 > 0.0 ? l2 + static_cast<double>(K) * log2(t1) : -INFINITY;
+            }
+            carry = l2 * 0.693147180559945309417;
         }
         carry_out[b] = carry;
         mcount_out[b] = sl.draft_row < 0 ? 0 : L - sl.tau - 1;
@@ -590,6 +624,7 @@ hipError_t launch_final_typed(const Problem &p)
     DecideIO io;
     io.tokens = p.tokens;
     io.stats = reinterpret_cast<const RowStat *>(p.ws + p.lay.stats);
+    io.pend = p.pend_carry ? reinterpret_cast<const PendRow *>(p.ws + p.lay.pend) : nullptr;
     io.s_arr = reinterpret_cast<const double *>(p.ws + p.lay.s);
     io.log_nu_out = reinterpret_cast<double *>(p.ws + p.lay.log_nu);
     io.log_P_out = reinterpret_cast<double *>(p.ws + p.lay.log_P);
@@ -609,12 +644,12 @@ hipError_t launch_final_typed(const Problem &p)
     fo.mcount = reinterpret_cast<int32_t *>(p.ws + p.lay.mcount);
     const int KL = p.K * p.L;
     const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
-    if (vec)
-        hipLaunchKernelGGL((k_final<T, true>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K,
-                           p.L, p.c, p.lay.nseg, p.seed, p.offset);
-    else
-        hipLaunchKernelGGL((k_final<T, false>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K,
-                           p.L, p.c, p.lay.nseg, p.seed, p.offset);
+#define SPECGBV_FINAL_LAUNCH(VEC, PEND)                                                                              \
+    hipLaunchKernelGGL((k_final<T, VEC, PEND>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K, \
+                       p.L, p.c, p.lay.nseg, p.seed, p.offset)
+    if (p.pend_carry) { if (vec) SPECGBV_FINAL_LAUNCH(true, true); else SPECGBV_FINAL_LAUNCH(false, true); }
+    else { if (vec) SPECGBV_FINAL_LAUNCH(true, false); else SPECGBV_FINAL_LAUNCH(false, false); }
+#undef SPECGBV_FINAL_LAUNCH
     return hipGetLastError();
 }
 

@@ -27,6 +27,17 @@ struct RowStat {
     double tok2_p;   // c * z_p[token of this row]
 };
 
+// A row of a verification that runs under a pending distribution modification (Algorithm 2
+// applied on the fly): the row's target distribution is q'[x] = q[x] t[x]^K / N with
+// t[x] = max(1 - p[x] / (mu q[x]), 0).  All in base-2 logarithms.
+struct PendRow {
+    double log2mu;   // block ratio Algorithm 2 uses at this row (carried ratio continued with the original q)
+    double log2N;    // log2 of N = sum_x q[x] t[x]^K (0 when the row is not modified)
+    double tokadj;   // K log2 t[token of this row]: log2 q'[token] = log2 q[token] + tokadj - log2N (0 when not modified)
+    int32_t flag;    // 1: the row is modified; 0: it is q itself (beyond the count, or N = 0)
+    int32_t pad;
+};
+
 // What the final-token kernels need to know about one prefix.
 struct Selection {
     long long target_row;   // row index into target_logits (in rows of V elements)
@@ -35,6 +46,9 @@ struct Selection {
     double lse2_q;          // log2 normaliser of the target row (0 for the bonus row)
     float shift_q;          // reference exponent for target-row weights (unused for the bonus row)
     int tau;
+    double C1;              // modified row only: log2 of mu * Z_p / Z_q (C2 and lse2_q then refer to q')
+    int pend;               // 1: the row is modified by a pending modification
+    int pad;
 };
 
 // Partial sums of one residual segment, relative to 2^m2.
@@ -105,6 +119,15 @@ struct RatioConst {
         return __builtin_amdgcn_fmed3f(fmaf(r, neg_kappa, 1.0f), 0.0f, 1.0f);
     }
 };
+
+// max(1 - kappa r / tK, 0) for the second ratio of a row under a pending modification: r / tK is
+// formed with the hardware reciprocal (1 ulp); tK = 0, an overflowing quotient and 0/0-like cases
+// (the entry's weight q tK is then zero or negligible) give 0.
+__device__ __forceinline__ float pend_second_factor(float r, float tK, float neg_kappa) {
+    const float q2 = r * __builtin_amdgcn_rcpf(tK);
+    const float t2 = __builtin_amdgcn_fmed3f(fmaf(q2, neg_kappa, 1.0f), 0.0f, 1.0f);
+    return (tK > 0.0f && q2 < 4.0f) ? t2 : 0.0f;       // kappa < 2: beyond 4 the factor is 0 anyway
+}
 
 // t^K for a wave-uniform integer K >= 1 (square and multiply).
 __device__ __forceinline__ float powi_uniform(float t, int K) {

@@ -140,7 +140,8 @@ __device__ __forceinline__ void for_each_pair(const T *rq, const T *rp, int V, F
     }
 }
 
-// grid.x = batch * K * M; row pairs with r >= count leave at once
+// grid.x = batch * K * M, row index slowest (the live workgroups, rows below the prefix's count, are then
+// consecutive and spread over all dies whatever M is); row pairs with r >= count leave at once
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kModThreads)
 k_mod_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, int M, int bonus, int V, float c,
@@ -149,9 +150,10 @@ k_mod_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, int
            int32_t *__restrict__ fb_out)
 {
     __shared__ double sh_d[kModThreads / kWave];
-    const long long drow = blockIdx.x;
-    const int r = static_cast<int>(drow % M);
-    const long long bk = drow / M;
+    const long long nbk = gridDim.x / M;
+    const int r = static_cast<int>(blockIdx.x / nbk);
+    const long long bk = blockIdx.x % nbk;
+    const long long drow = bk * M + r;
     const int b = static_cast<int>(bk / K);
     const int rows_t = M + bonus;
     if (r >= modify_count[b]) {                       // uniform over the workgroup

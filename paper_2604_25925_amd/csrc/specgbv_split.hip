@@ -5,6 +5,13 @@
 //   k_ot_sum    : per row pair i = 1..L-1, the vocabulary sum of Eq. (hik) divided by
 //                 q(x^i):  s_i = sum_x q_i[x] max(1 - p_i[x] / (nu_i q_i[x]), 0)^K
 //
+// With a pending distribution modification (Algorithm 2 applied on the fly) a third kernel
+// runs between the two:
+//   k_pend_norm : per modified row, the block ratio mu Algorithm 2 uses there, the normaliser
+//                 N = sum_x q[x] max(1 - p[x] / (mu q[x]), 0)^K of q_new, and the drafted
+//                 token's factor,
+// and k_ot_sum evaluates its sum against q_new = q t^K / N formed per entry.
+//
 // Any V and any alignment is accepted (rows whose byte length is not a multiple of 16
 // take the scalar-load path).  This schedule reads every row pair twice; it is the
 // general fallback and the reference schedule for the on-chip "chain" kernel.
@@ -59,10 +66,88 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
     }
 }
 
+// One entry's term of the sum against a modified row: q t1^K (relative to 2^shift_q) times
+// max(1 - p / (nu q'), 0)^K with q' = q t1^K / N, i.e. the second ratio is the first kind of
+// ratio (constant rc2, which carries nu / N) divided by t1^K.
+__device__ __forceinline__ float pend_term(float zq, float zp, float c, float shift_q, const RatioConst &rc1,
+                                           const RatioConst &rc2, int K, float *wq_out = nullptr)
+{
+    const float d = zp - zq;
+    const float eq = exp2_fast(fmaf(zq, c, -shift_q));
+    const float tK = powi_uniform(rc1.one_minus_ratio(d, c), K);
+    const float wq = eq * tK;
+    if (wq_out) *wq_out = wq;
+    return wq * powi_uniform(pend_second_factor(exp2_fast(fmaf(d, c, -rc2.C2_hi)), tK, rc2.neg_kappa), K);
+}
+
+// grid.x = batch * K * L row pairs, row index slowest: the live workgroups (rows below the prefix's
+// count) are then consecutive and spread over all dies, whatever L is; the others leave at once
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kStatThreads)
+k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
+            const double *__restrict__ pend_carry, const int32_t *__restrict__ pend_count,
+            const RowStat *__restrict__ stats, PendRow *__restrict__ pend)
+{
+    __shared__ double sh_d[kStatThreads / kWave];
+    const long long nbk = gridDim.x / L;
+    const int r = static_cast<int>(blockIdx.x / nbk);
+    const long long bk = blockIdx.x % nbk;
+    const long long pair = bk * L + r;            // (b*K + k)*L + r
+    const int b = static_cast<int>(bk / K);
+    PendRow out;
+    out.log2mu = 0.0; out.log2N = 0.0; out.tokadj = 0.0; out.flag = 0; out.pad = 0;
+    if (r >= pend_count[b]) {                     // uniform over the workgroup
+        if (threadIdx.x == 0) pend[pair] = out;
+        return;
+    }
+    // block ratio in front of row r: the carried one continued with the ORIGINAL target probabilities
+    double log2mu = pend_carry[b] * 1.44269504088896340736;
+    for (int j = 0; j < r; ++j) {
+        const RowStat a = stats[bk * L + j];
+        log2mu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
+    }
+    const RowStat st = stats[pair];
+    const float shift_q = static_cast<float>(st.lse2_q);
+    const RatioConst rc(st.lse2_p - st.lse2_q + log2mu);
+    const T *rq = target + (bk * (L + 1) + r) * static_cast<long long>(V);
+    const T *rp = draft + pair * static_cast<long long>(V);
+    constexpr int PV = Elem<T>::kPerVec;
+    float acc = 0.0f;
+    if (VEC) {
+        const int nvec = V / PV;
+        for (int v = threadIdx.x; v < nvec; v += kStatThreads) {
+            float zq[PV], zp[PV];
+            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
+            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
+#pragma unroll
+            for (int j = 0; j < PV; ++j)
+                acc = fmaf(exp2_fast(fmaf(zq[j], c, -shift_q)), powi_uniform(rc.one_minus_ratio(zp[j] - zq[j], c), K), acc);
+        }
+    } else {
+        for (int x = threadIdx.x; x < V; x += kStatThreads) {
+            const float zq = Elem<T>::scalar(rq + x), zp = Elem<T>::scalar(rp + x);
+            acc = fmaf(exp2_fast(fmaf(zq, c, -shift_q)), powi_uniform(rc.one_minus_ratio(zp - zq, c), K), acc);
+        }
+    }
+    const double S = block_sum(static_cast<double>(acc), sh_d);           // relative to 2^shift_q
+    if (threadIdx.x == 0) {
+        const double W = S * exp2(static_cast<double>(shift_q) - st.lse2_q);
+        out.log2mu = log2mu;
+        if (W > 0.0) {                            // otherwise every weight is zero and the row stays q
+            out.flag = 1;
+            out.log2N = log2(W);
+            const double ratio = exp2((st.tok2_p - st.lse2_p) - (st.tok2_q - st.lse2_q) - log2mu);
+            const double t = 1.0 - ratio;
+            out.tokadj = t > 0.0 ? static_cast<double>(K) * log2(t) : -INFINITY;
+        }
+        pend[pair] = out;
+    }
+}
+
+template <typename T, bool VEC, bool PEND>
+__global__ void __launch_bounds__(kStatThreads)
 k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
-         const RowStat *__restrict__ stats, double *__restrict__ s_out)
+         const RowStat *__restrict__ stats, const PendRow *__restrict__ pend, double *__restrict__ s_out)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     const long long idx = blockIdx.x;             // bk*(L-1) + (i-1)
@@ -73,14 +158,37 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
     for (int j = 0; j < i; ++j) {
         const RowStat st = stats[bk * L + j];
         log2nu += (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);
+        if (PEND) log2nu += pend[bk * L + j].tokadj - pend[bk * L + j].log2N;
     }
     const RowStat st = stats[bk * L + i];
     const float shift_q = static_cast<float>(st.lse2_q);
-    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu);
     const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
     const T *rp = draft + (bk * L + i) * static_cast<long long>(V);
     constexpr int PV = Elem<T>::kPerVec;
     float acc = 0.0f;
+    if (PEND && pend[bk * L + i].flag) {          // uniform over the workgroup
+        const PendRow pr = pend[bk * L + i];
+        const RatioConst rc1(st.lse2_p - st.lse2_q + pr.log2mu);
+        const RatioConst rc2(st.lse2_p - st.lse2_q + log2nu - pr.log2N);
+        if (VEC) {
+            const int nvec = V / PV;
+            for (int v = threadIdx.x; v < nvec; v += kStatThreads) {
+                float zq[PV], zp[PV];
+                Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
+                Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
+#pragma unroll
+                for (int j = 0; j < PV; ++j) acc += pend_term(zq[j], zp[j], c, shift_q, rc1, rc2, K);
+            }
+        } else {
+            for (int x = threadIdx.x; x < V; x += kStatThreads)
+                acc += pend_term(Elem<T>::scalar(rq + x), Elem<T>::scalar(rp + x), c, shift_q, rc1, rc2, K);
+        }
+        const double total = block_sum(static_cast<double>(acc), sh_d);
+        if (threadIdx.x == 0)
+            s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - pr.log2N);
+        return;
+    }
+    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu);
     if (VEC) {
         const int nvec = V / PV;
         for (int v = threadIdx.x; v < nvec; v += kStatThreads) {
@@ -125,15 +233,28 @@ hipError_t launch_typed(const Problem &p)
         hipLaunchKernelGGL((k_row_stats<T, false>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
                            p.tokens, p.K, p.L, p.V, p.c, stats, counter);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.L < 2) return e;
+    if (e != hipSuccess) return e;
+    PendRow *pend = reinterpret_cast<PendRow *>(p.ws + p.lay.pend);
+    if (p.pend_carry) {
+        const dim3 gp(static_cast<unsigned>(pairs));
+        if (vec)
+            hipLaunchKernelGGL((k_pend_norm<T, true>), gp, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L,
+                               p.V, p.c, p.pend_carry, p.pend_count, stats, pend);
+        else
+            hipLaunchKernelGGL((k_pend_norm<T, false>), gp, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L,
+                               p.V, p.c, p.pend_carry, p.pend_count, stats, pend);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (p.L < 2) return hipSuccess;
     const long long rows = static_cast<long long>(p.batch) * p.K * (p.L - 1);
     const dim3 g2(static_cast<unsigned>(rows));
-    if (vec)
-        hipLaunchKernelGGL((k_ot_sum<T, true>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K,
-                           p.L, p.V, p.c, stats, s);
-    else
-        hipLaunchKernelGGL((k_ot_sum<T, false>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K,
-                           p.L, p.V, p.c, stats, s);
+#define SPECGBV_OT_LAUNCH(VEC, PEND)                                                                           \
+    hipLaunchKernelGGL((k_ot_sum<T, VEC, PEND>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L, \
+                       p.V, p.c, stats, pend, s)
+    if (p.pend_carry) { if (vec) SPECGBV_OT_LAUNCH(true, true); else SPECGBV_OT_LAUNCH(false, true); }
+    else { if (vec) SPECGBV_OT_LAUNCH(true, false); else SPECGBV_OT_LAUNCH(false, false); }
+#undef SPECGBV_OT_LAUNCH
     return hipGetLastError();
 }
 

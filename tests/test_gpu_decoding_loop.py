@@ -24,15 +24,18 @@ def _markov_tables(rng, V):
     return (lambda block: p2(last(block))), (lambda block: q2(last(block)))
 
 
-@pytest.mark.parametrize("V,K,L", [(3, 1, 2), (3, 1, 3), (3, 1, 4), (2, 2, 2), (2, 2, 3)])
-def test_three_iterations_decode_the_exact_law(V, K, L):
+@pytest.mark.parametrize("V,K,L,fused", [(3, 1, 2, False), (3, 1, 3, False), (3, 1, 4, False), (2, 2, 2, False),
+                                           (2, 2, 3, False), (3, 1, 3, True), (3, 1, 4, True), (2, 2, 3, True)])
+def test_three_iterations_decode_the_exact_law(V, K, L, fused):
     """Algorithm 3 updates q in place ("q <- DistributionModification(q, ...)"), so a modification
     made after one iteration is still in force for its remaining positions when the next iteration
     ends early, and the next modification applies on top of it.  The driver below therefore keeps
     up to L - 1 pending modifications per prefix, innermost first: each has its carried block ratio
     (extended along every emitted token with the probabilities of the distribution it modifies:
     specgbv_carry_advance) and its remaining row count, and the rows handed to the verification are
-    obtained by applying them one after the other with specgbv_modify_target."""
+    obtained by applying them one after the other with specgbv_modify_target.  With fused = True the
+    outermost pending modification is not written out: the verification applies it on the fly
+    (the pending option of specgbv_verify_ex)."""
     import torch
     import paper_2604_25925_amd as sg
     rng = np.random.default_rng(100 + L + 10 * K)
@@ -70,11 +73,15 @@ def test_three_iterations_decode_the_exact_law(V, K, L):
         # (the tables hold normalised probabilities, so their logits are log-probabilities at T = 1)
         level_rows = [tl]
         cur = tl
-        for carry, count in pending:
+        on_the_fly = pending[-1] if (fused and pending) else None
+        for carry, count in (pending[:-1] if on_the_fly else pending):
             cur = sg.specgbv_modify_target(cur, dl, tk, 1.0, carry, count)["logq"]
             level_rows.append(cur)
         # ---- verification against the modified rows
-        acc, f, out, ws = sg.specgbv_verify(cur, dl, tk, 1.0, 1234, it)
+        if on_the_fly:
+            acc, f, out, ws = sg.specgbv_verify_ex(cur, dl, tk, 1.0, 1234, it, pending=on_the_fly)
+        else:
+            acc, f, out, ws = sg.specgbv_verify(cur, dl, tk, 1.0, 1234, it)
         cptr, nptr = sg.specgbv_workspace_carry(ws, n, K, L, V)
         assert cptr and nptr
         torch.cuda.synchronize()

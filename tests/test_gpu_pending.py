@@ -1,0 +1,174 @@
+"""GPU <-> oracle parity of a verification that applies a pending distribution modification
+(Algorithm 2) on the fly, through the C ABI.
+
+Expected values: the oracle's Algorithm 2 on the same rows (float64 log-probabilities), then the
+oracle's Algorithm 1 on those rows at temperature 1 -- the composition the on-the-fly path
+replaces.  The GPU reads the raw logits and the carried (ratio, count) pair only.  Bar: the one
+of the plain verification (decisions and tokens bit-exact except below the 1e-6 margins,
+probabilities to 1e-5 relative); the log-normalisers of the target rows are not compared (the
+oracle sees normalised rows, the library reports those of the raw rows).
+
+Conditioning.  The modified probability of a drafted token is q'[x] = q[x] t^K / N with
+t = 1 - r, r = p[x] / (mu q[x]); any float32 evaluation of the row statistics leaves a relative
+error of up to EPS_R = 1e-6 on r, i.e. K EPS_R r / (1 - r) on ln q'[x], which is unbounded as
+r -> 1 (such a token has almost no mass under q' and its block is all but never accepted).  That
+amount, accumulated along the block, is admitted on ln nu_i on top of the 1e-5 and propagated to
+s, h, the residual normaliser and the carried ratio by parity_util.compare; a prefix with a
+drafted token within 4 EPS_R of r = 1 (where even the sign of t is undecided) is left out and counted.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from parity_util import compare, run_gpu
+from specgbv_synth import WORKLOADS, Workload, make_inputs, with_batch
+
+pytestmark = pytest.mark.gpu
+
+
+def _as_f64(raw):
+    if raw.dtype == np.uint16:
+        return (raw.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return raw.astype(np.float64)
+
+
+def oracle_pending(t, d, tok, T, seed, offset, carry, count, prefix_ids=None):
+    """Algorithm 2, then Algorithm 1 on its rows (both the oracle's), without any rounding in between."""
+    B, K, L1, V = t.shape
+    L = L1 - 1
+    mod = oracle.modify(np.ascontiguousarray(t[:, :, :L]), d, tok, T, carry, count)
+    Tf = float(np.float32(T))                           # the oracle widens the float32 temperature
+    tq = np.empty((B, K, L + 1, V), np.float64)
+    tq[:, :, :L] = mod["logq"]
+    tq[:, :, L] = _as_f64(t[:, :, L]) / Tf              # bonus row: plain logits over T, used at temperature 1
+    dq = _as_f64(d) / Tf
+    return oracle.verify(tq, dq, tok, 1.0, seed, offset, debug=True, nthreads=8, prefix_ids=prefix_ids), mod
+
+
+EPS_R = 1e-6
+
+
+def conditioning(t, d, tok, T, carry, count, mod, ora):
+    """(nu_extra [B, K, L], carry_extra [B], undecided [B]) from the oracle's float64 values: the error
+    K EPS_R r / (1 - r) of ln q'[token] accumulated along each block, the same for the final token,
+    and the prefixes with a drafted token whose r is within 4 EPS_R of 1."""
+    B, K, L = tok.shape
+    Tf = float(np.float32(T))
+    nu_extra = np.zeros((B, K, L))
+    carry_extra = np.zeros(B)
+    undecided = np.zeros(B, bool)
+
+    def token_term(b, k, j, x, ln_mu):
+        lq, _ = oracle.log_softmax(_as_f64(t[b, k, j]), Tf)
+        lp, _ = oracle.log_softmax(_as_f64(d[b, k, j]), Tf)
+        r = np.exp(lp[x] - lq[x] - ln_mu)
+        return lq[x] - lp[x], r
+
+    for b in range(B):
+        for k in range(K):
+            ln_mu, acc = float(carry[b]), 0.0
+            for j in range(min(int(count[b]), L)):
+                step, r = token_term(b, k, j, int(tok[b, k, j]), ln_mu)
+                if not mod["fallback"][b, k, j]:
+                    if abs(1.0 - r) < 4 * EPS_R * r:
+                        undecided[b] = True
+                    elif r < 1.0:
+                        acc += K * EPS_R * r / (1.0 - r)
+                nu_extra[b, k, j:] = acc
+                ln_mu += step
+        tau, kf = int(ora["accepted_len"][b]), max(int(ora["accepted_draft_idx"][b]), 0)
+        if tau < min(int(count[b]), L) and not mod["fallback"][b, kf, tau]:
+            ln_mu = float(carry[b])
+            for j in range(tau):
+                ln_mu += token_term(b, kf, j, int(tok[b, kf, j]), ln_mu)[0]
+            r = token_term(b, kf, tau, int(ora["out_tokens"][b, tau]), ln_mu)[1]
+            carry_extra[b] = K * EPS_R * r / (1.0 - r) if r < 1.0 else 0.0
+    return nu_extra, carry_extra, undecided
+
+
+def check_pending(t, d, tok, T, seed, offset, carry, count, label, gpu_slice=None):
+    gpu = run_gpu(t, d, tok, T, seed, offset, pending=(carry, count))
+    if gpu_slice is not None:
+        idx = np.asarray(gpu_slice)
+        t, d, tok, carry, count = t[idx], d[idx], tok[idx], carry[idx], count[idx]
+        ora, mod = oracle_pending(t, d, tok, T, seed, offset, carry, count, prefix_ids=idx.astype(np.int32))
+        gpu = {k: v[idx] for k, v in gpu.items()}
+    else:
+        ora, mod = oracle_pending(t, d, tok, T, seed, offset, carry, count)
+    nu_extra, carry_extra, undecided = conditioning(t, d, tok, T, carry, count, mod, ora)
+    keep = ~undecided
+    rep = compare({k: v[keep] for k, v in gpu.items()}, {k: v[keep] for k, v in ora.items()}, tok[keep], label=label,
+                  skip=("lse_q",), nu_extra=nu_extra[keep], carry_extra=carry_extra[keep])
+    rep["undecided_prefixes"] = int(undecided.sum())
+    rep["max_nu_extra"] = float(nu_extra[keep].max()) if keep.any() else 0.0
+    assert undecided.sum() <= 1
+    print("[parity] %s: %s" % (label, rep), flush=True)
+    return rep, gpu, ora, mod
+
+
+@pytest.mark.parametrize("B,K,L,V,dtype,T", [
+    (16, 3, 4, 515, "f32", 1.0),          # scalar-load path
+    (12, 4, 5, 8192, "bf16", 0.8),
+    (16, 1, 3, 4096, "f32", 0.6),         # K = 1: greedy block verification under a modification
+    (8, 2, 1, 1000, "f32", 1.0),          # L = 1: nothing to modify (count is 0 or clamped away)
+    (6, 8, 8, 32000, "f32", 0.4),
+])
+def test_pending_verification_matches_oracle(B, K, L, V, dtype, T):
+    w = Workload("pend", B, K, L, V, dtype, 2.5, 0.8, head=20, temperature=T)
+    t, d, tok = make_inputs(w, seed=61)
+    rng = np.random.default_rng(7)
+    carry = rng.normal(1.5, 0.8, B)                     # ratios around 4: most drafted tokens keep some mass
+    count = rng.integers(0, L + 1, B).astype(np.int32)
+    count[0] = 0
+    if B > 1:
+        count[1] = max(L - 1, 0)
+    rep, gpu, ora, mod = check_pending(t, d, tok, T, 5, 3, carry, count, "pending %s V=%d K=%d L=%d" % (dtype, V, K, L))
+    assert rep["decision_mismatches"] <= 1 and rep["token_mismatches"] <= 1
+    if L > 1:
+        assert (mod["norm"][count > 0] < 1.0).any()          # something was really modified
+        assert (ora["accepted_len"] > 0).any()
+
+
+def test_pending_with_zero_count_is_the_plain_verification():
+    w = Workload("pend0", 8, 3, 4, 4096, "bf16", 2.5, 0.8, head=20, temperature=0.9)
+    t, d, tok = make_inputs(w, seed=62)
+    plain = run_gpu(t, d, tok, w.temperature, 9, 1, algo="split")
+    pend = run_gpu(t, d, tok, w.temperature, 9, 1, pending=(np.zeros(8), np.zeros(8, np.int32)))
+    for k in plain:
+        assert np.array_equal(plain[k], pend[k], equal_nan=True), k
+
+
+def test_pending_all_zero_weights_and_zero_probability_tokens():
+    """A carried ratio so small that every weight of a modified row vanishes leaves the row q
+    (the oracle's rule); one so that drafted tokens get probability zero under q_new gives
+    blocks of likelihood ratio zero, which are never accepted."""
+    w = Workload("pendz", 6, 2, 3, 2048, "f32", 2.5, 0.8, head=20, temperature=1.0)
+    t, d, tok = make_inputs(w, seed=63)
+    carry = np.array([-200.0, -200.0, -3.0, -3.0, 0.0, 40.0])
+    count = np.array([2, 1, 2, 3, 2, 2], np.int32)
+    rep, gpu, ora, mod = check_pending(t, d, tok, 1.0, 2, 0, carry, count, "pending degenerate")
+    assert mod["fallback"][0].any() and mod["fallback"][1, :, 0].all()
+    assert np.isneginf(ora["log_nu"]).any()
+    assert rep["decision_mismatches"] == 0
+
+
+def test_pending_cfg4_rows():
+    """Full-size rows (V = 128256, bf16, K = L = 8) in the default launch configuration; the
+    oracle recomputes two of the prefixes."""
+    w = with_batch(WORKLOADS["cfg4"], 4)
+    t, d, tok = make_inputs(w, seed=64)
+    carry = np.array([0.3, -0.4, 0.0, 1.1])
+    count = np.array([3, 7, 1, 5], np.int32)
+    rep, gpu, ora, mod = check_pending(t, d, tok, w.temperature, 3, 2, carry, count, "pending cfg4 rows", gpu_slice=[1, 3])
+    assert rep["decision_mismatches"] == 0
+
+
+def test_pending_chain_schedule_is_rejected():
+    import paper_2604_25925_amd as sg
+    import torch
+    from parity_util import to_torch
+    w = Workload("pendc", 2, 2, 2, 8192, "bf16", 2.5, 0.8, temperature=1.0)
+    t, d, tok = make_inputs(w, seed=65)
+    pend = (torch.zeros(2, dtype=torch.float64, device="cuda"), torch.ones(2, dtype=torch.int32, device="cuda"))
+    with pytest.raises(sg.SpecGBVError):
+        sg.specgbv_verify_ex(to_torch(t), to_torch(d), to_torch(tok), 1.0, 0, 0, algo="chain", pending=pend)

@@ -73,6 +73,21 @@ def test_argument_errors_are_caught_before_any_launch():
     assert _call(lib, B=0) == 0                             # empty batch: nothing to do
 
 
+def test_pending_option_errors_are_caught_before_any_launch():
+    from paper_2604_25925_amd.binding import _Options
+    lib = sg.load_library()
+    P = 1 << 20
+
+    def call(algo, carry, count):
+        opt = _Options(algo, 0, None, None, carry, count)
+        return lib.specgbv_verify_ex(P, P, P, 2, 3, 64, 1, 0, ctypes.c_float(1.0), 0, 0, P, P, P, P, 1 << 30, None,
+                                     ctypes.byref(opt))
+    assert call(0, P, None) == 1 and "together" in sg.specgbv_last_error()      # one pointer without the other
+    assert call(0, None, P) == 1
+    assert call(0, P + 4, P) == 1                                               # misaligned float64 pointer
+    assert call(2, P, P) == 2 and "two-pass" in sg.specgbv_last_error()         # chain schedule: unsupported
+
+
 def test_modify_target_argument_errors():
     lib = sg.load_library()
     P = 1 << 20
