@@ -198,8 +198,8 @@ def main() -> int:
                          "region: under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE readings calibrate the counters")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path is embarrassingly parallel over prefixes; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path is independent over prefixes: more GPUs would "
+              "each verify their share of the batch); run with --gpus 1", file=sys.stderr)
         return 2
 
     w = WORKLOADS[a.workload]

@@ -25,6 +25,8 @@ def test_verify_modify_sample_replay_under_graph_capture():
     out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
            torch.empty((B, L + 1), dtype=torch.int32, device=dev))
     carry_ptr, count_ptr = sg.specgbv_workspace_carry(ws, B, K, L, V)
+    ws2 = torch.empty_like(ws)
+    out2 = tuple(torch.empty_like(t) for t in out)
     mod = {"logq": torch.empty((B, K, L + 1, V), dtype=torch.float32, device=dev),
            "logp": torch.empty((B, K, L, V), dtype=torch.float32, device=dev),
            "workspace": torch.empty(sg.specgbv_modify_workspace_bytes(B, K, L, 1), dtype=torch.uint8, device=dev)}
@@ -36,10 +38,12 @@ def test_verify_modify_sample_replay_under_graph_capture():
         sg.specgbv_verify_ex(tl, dl, tk, T, 5, 2, workspace=ws, out=out)
         sg.specgbv_modify_target(tl, dl, tk, T, carry_ptr, count_ptr, want_logp=True, out=mod)
         sg.specgbv_sample_tokens(rows, T, 5, 2, 0, out=stok, workspace=sws)
+        # the same modification applied on the fly by a second verification (its own workspace and outputs)
+        sg.specgbv_verify_ex(tl, dl, tk, T, 5, 3, workspace=ws2, out=out2, pending=(carry_ptr, count_ptr))
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (*out, mod["logq"], mod["logp"], stok)]
+        return [t.clone() for t in (*out, mod["logq"], mod["logp"], stok, *out2)]
 
     def load(inputs):
         a, b, c = (to_torch(x) for x in inputs)
@@ -64,7 +68,7 @@ def test_verify_modify_sample_replay_under_graph_capture():
         iteration()
     for rep, inputs in enumerate(sets + sets[:1]):
         load(inputs)
-        for t in (*out, stok):
+        for t in (*out, stok, *out2):
             t.fill_(-7)                               # eager work between the replays
         torch.cuda.synchronize()
         graph.replay()

@@ -5,7 +5,9 @@ over many independent prefixes that share small conditional tables, the frequenc
 outputs (t^tau, y) produced by libspecgbv.so must match the law obtained by enumerating every
 draft tuple and every accept/reject branch of Algorithm 1 in exact rationals.  For K = 1 that
 law is the target distribution itself (Theorem 4.2); for K >= 2 it is the law of the printed
-algorithm (which is not the target distribution: see the design doc, reading R11).
+algorithm (which is not the target distribution: already for two tokens, one position and two
+drafts the exact enumeration gives 5/36 where the target has 1/5 -- case CE1 of
+tests/golden/alg1_small_cases.json).
 """
 from fractions import Fraction as F
 

@@ -299,6 +299,30 @@ def test_oracle_bf16_inputs_equal_their_float32_values():
     assert bits.tolist() == [0x3F80, 0x3F80, 0x3F82, 0xC020, 0x4049]
 
 
+def test_oracle_float64_inputs_equal_their_float32_values():
+    """float64 rows are an input format only (they let one oracle result feed another without
+    rounding): values that float32 represents exactly give identical results either way."""
+    rng = np.random.default_rng(12)
+    t = rng.normal(0, 2, (3, 2, 4, 40)).astype(np.float32)
+    d = rng.normal(0, 2, (3, 2, 3, 40)).astype(np.float32)
+    tok = rng.integers(0, 40, (3, 2, 3)).astype(np.int32)
+    a = oracle.verify(t, d, tok, 0.7, 3, 1, debug=True)
+    b = oracle.verify(t.astype(np.float64), d.astype(np.float64), tok, 0.7, 3, 1, debug=True)
+    for k in a:
+        assert np.array_equal(a[k], b[k], equal_nan=True), k
+    carry, count = np.array([0.3, -0.2, 1.0]), np.array([2, 1, 3], np.int32)
+    ma = oracle.modify(t[:, :, :3].copy(), d, tok, 0.7, carry, count)
+    mb = oracle.modify(t[:, :, :3].astype(np.float64), d.astype(np.float64), tok, 0.7, carry, count)
+    for k in ma:
+        assert np.array_equal(ma[k], mb[k], equal_nan=True), k
+    # and a genuinely float64 value is not rounded on the way in: log-probabilities of a row whose
+    # float32 rounding would move the normaliser
+    z = np.log(np.array([[[[0.1, 0.2, 0.7]]]]))
+    zz = np.concatenate([z, z], axis=2)
+    r = oracle.verify(zz, z, np.zeros((1, 1, 1), np.int32), 1.0, 0, 0, debug=True)
+    assert abs(r["lse_q"][0, 0, 0]) < 1e-15
+
+
 def test_oracle_rejects_bad_arguments():
     t = np.zeros((1, 1, 2, 4), np.float32)
     d = np.zeros((1, 1, 1, 4), np.float32)
