@@ -322,29 +322,13 @@ __device__ __forceinline__ float segment_weigh(const Selection &sl, int V, int K
     if (PEND && sl.pend) {
         // modified row: plain weights q t1^K, residual weights q t1^K max(1 - p/(nu q'), 0)^K
         const RatioConst rc1(sl.C1);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const bool live = e0 + j < V;
-            float t1K = 0.0f, t2 = 0.0f, eq = 0.0f;
-            if (live) {
-                const float d = zp[j] - zq[j];
-                eq = exp2_fast(fmaf(zq[j], c, -m2));
-                t1K = powi_uniform(rc1.one_minus_ratio(d, c), K);
-                t2 = pend_second_factor(exp2_fast(fmaf(d, c, -rc.C2_hi)), t1K, rc.neg_kappa);
-            }
-            wq[j] = eq * t1K;
-            w[j] = wq[j] * powi_uniform(t2, K);
-        }
-        return m2;
+        pending_weights(zq, zp, c, m2, rc1, rc, K, wq, w);
+    } else {
+        ot_weights(zq, zp, c, m2, rc, K, wq, w);
     }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const bool live = e0 + j < V;
-        const float eq = live ? exp2_fast(fmaf(zq[j], c, -m2)) : 0.0f;
-        const float t = live ? rc.one_minus_ratio(zp[j] - zq[j], c) : 0.0f;
-        wq[j] = eq;
-        w[j] = eq * powi_uniform(t, K);
-    }
+    for (int j = 0; j < 8; ++j)
+        if (!(e0 + j < V)) { wq[j] = 0.0f; w[j] = 0.0f; }
     return m2;
 }
 

@@ -150,6 +150,115 @@ __device__ __forceinline__ double powi_uniform(double t, int K) {
     return acc;
 }
 
+// t[j] <- t[j]^K for a wave-uniform integer K >= 1, all N entries together: the entries' multiply chains are
+// independent, so one uniform loop over the bits of K serves them all (a loop per entry would serialise
+// N short dependent chains behind N sets of branches).
+template <int N>
+__device__ __forceinline__ void pow_array(float (&t)[N], int K) {
+    if (K == 1) return;
+    if (K == 2 || K == 4 || K == 8 || K == 16) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) t[j] *= t[j];
+        if (K >= 4) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) t[j] *= t[j];
+        }
+        if (K >= 8) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) t[j] *= t[j];
+        }
+        if (K >= 16) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) t[j] *= t[j];
+        }
+        return;
+    }
+    float base[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) { base[j] = t[j]; t[j] = (K & 1) ? t[j] : 1.0f; }
+    for (int k = K >> 1; k; k >>= 1) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) base[j] *= base[j];
+        if (k & 1) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) t[j] *= base[j];
+        }
+    }
+}
+
+// Weights of N entries of a (target, draft) row pair relative to 2^shift_q:
+//   wq[j] = 2^(c z_q[j] - shift_q)                      (plain target weight)
+//   w[j]  = wq[j] max(1 - p[j] / (nu q[j]), 0)^K        (the terms of Eq. (hik) / Eq. (pres)), nu in rc.
+template <int N>
+__device__ __forceinline__ void ot_weights(const float (&zq)[N], const float (&zp)[N], float c, float shift_q,
+                                           const RatioConst &rc, int K, float (&wq)[N], float (&w)[N]) {
+    float t[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) t[j] = rc.one_minus_ratio(zp[j] - zq[j], c);
+    pow_array(t, K);
+#pragma unroll
+    for (int j = 0; j < N; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -shift_q)); w[j] = wq[j] * t[j]; }
+}
+
+// The same for a row under a pending modification, q' = q t1^K / N with t1 = max(1 - p / (mu q), 0) (mu in rc1):
+//   wq[j] = 2^(c z_q[j] - shift_q) t1[j]^K              (plain weight of q', up to 1/N)
+//   w[j]  = wq[j] max(1 - p[j] / (nu q'[j]), 0)^K       with nu / N in rc2: the second ratio is the first kind
+//                                                       of exponential divided by t1^K.
+template <int N>
+__device__ __forceinline__ void pending_weights(const float (&zq)[N], const float (&zp)[N], float c, float shift_q,
+                                                const RatioConst &rc1, const RatioConst &rc2, int K, float (&wq)[N],
+                                                float (&w)[N]) {
+    float t1[N], r[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const float d = zp[j] - zq[j];
+        t1[j] = rc1.one_minus_ratio(d, c);
+        r[j] = exp2_fast(fmaf(d, c, -rc2.C2_hi));
+    }
+    pow_array(t1, K);
+    float t2[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) t2[j] = pend_second_factor(r[j], t1[j], rc2.neg_kappa);
+    pow_array(t2, K);
+#pragma unroll
+    for (int j = 0; j < N; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -shift_q)) * t1[j]; w[j] = wq[j] * t2[j]; }
+}
+
+// ------------------------------------------------------- row-pair streaming
+
+// f(first entry index, z_q[N], z_p[N]) for every entry of a (target, draft) row pair, N = 8 or 4 entries of
+// one 16-byte vector (VEC) or 1; the workgroup's THREADS threads stride over the row, each keeping the loads
+// of two vectors of either row in flight.
+template <typename T, bool VEC, int THREADS, typename F>
+__device__ __forceinline__ void for_each_pair(const T *rq, const T *rp, int V, F f)
+{
+    constexpr int PV = Elem<T>::kPerVec;
+    if constexpr (VEC) {
+        const int nvec = V / PV;
+        int v = threadIdx.x;
+        for (; v + THREADS < nvec; v += 2 * THREADS) {          // four loads in flight per thread
+            const U4 q0 = load16(rq + static_cast<long long>(v) * PV), p0 = load16(rp + static_cast<long long>(v) * PV);
+            const U4 q1 = load16(rq + static_cast<long long>(v + THREADS) * PV);
+            const U4 p1 = load16(rp + static_cast<long long>(v + THREADS) * PV);
+            float zq[PV], zp[PV];
+            Elem<T>::unpack(q0, zq); Elem<T>::unpack(p0, zp); f(v * PV, zq, zp);
+            Elem<T>::unpack(q1, zq); Elem<T>::unpack(p1, zp); f((v + THREADS) * PV, zq, zp);
+        }
+        if (v < nvec) {
+            float zq[PV], zp[PV];
+            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
+            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
+            f(v * PV, zq, zp);
+        }
+    } else {
+        for (int x = threadIdx.x; x < V; x += THREADS) {
+            const float zq[1] = {Elem<T>::scalar(rq + x)}, zp[1] = {Elem<T>::scalar(rp + x)};
+            f(x, zq, zp);
+        }
+    }
+}
+
+
 // ------------------------------------------------------------ running sum
 
 // Per-thread running sum of 2^(c z - m2) with a running reference exponent m2 (updated once

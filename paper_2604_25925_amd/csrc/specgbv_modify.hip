@@ -111,35 +111,6 @@ __device__ __forceinline__ double mod_log2nu(const ModStat *tstat, const ModStat
     return l;
 }
 
-template <typename T, bool VEC, typename F>
-__device__ __forceinline__ void for_each_pair(const T *rq, const T *rp, int V, F f)
-{
-    constexpr int PV = Elem<T>::kPerVec;
-    if constexpr (VEC) {
-        const int nvec = V / PV;
-        int v = threadIdx.x;
-        for (; v + kModThreads < nvec; v += 2 * kModThreads) {          // four loads in flight per thread
-            const U4 q0 = load16(rq + static_cast<long long>(v) * PV), p0 = load16(rp + static_cast<long long>(v) * PV);
-            const U4 q1 = load16(rq + static_cast<long long>(v + kModThreads) * PV);
-            const U4 p1 = load16(rp + static_cast<long long>(v + kModThreads) * PV);
-            float zq[PV], zp[PV];
-            Elem<T>::unpack(q0, zq); Elem<T>::unpack(p0, zp); f(v * PV, zq, zp);
-            Elem<T>::unpack(q1, zq); Elem<T>::unpack(p1, zp); f((v + kModThreads) * PV, zq, zp);
-        }
-        if (v < nvec) {
-            float zq[PV], zp[PV];
-            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
-            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
-            f(v * PV, zq, zp);
-        }
-    } else {
-        for (int x = threadIdx.x; x < V; x += kModThreads) {
-            const float zq[1] = {Elem<T>::scalar(rq + x)}, zp[1] = {Elem<T>::scalar(rp + x)};
-            f(x, zq, zp);
-        }
-    }
-}
-
 // grid.x = batch * K * M, row index slowest (the live workgroups, rows below the prefix's count, are then
 // consecutive and spread over all dies whatever M is); row pairs with r >= count leave at once
 template <typename T, bool VEC>
@@ -167,10 +138,11 @@ k_mod_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, int
     const T *rp = draft + drow * static_cast<long long>(V);
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
     float acc = 0.0f;
-    for_each_pair<T, VEC>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+    for_each_pair<T, VEC, kModThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+        float wq[N], w[N];
+        ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
 #pragma unroll
-        for (int j = 0; j < N; ++j)
-            acc = fmaf(exp2_fast(fmaf(zq[j], c, -shift_q)), powi_uniform(rc.one_minus_ratio(zp[j] - zq[j], c), K), acc);
+        for (int j = 0; j < N; ++j) acc += w[j];
     });
     const double S = block_sum(static_cast<double>(acc), sh_d);           // relative to 2^shift_q
     if (threadIdx.x == 0) {
@@ -226,7 +198,7 @@ k_mod_write(const T *__restrict__ target, const T *__restrict__ draft, int K, in
         const RatioConst rc(sp.lse2 - sq.lse2 + mod_log2nu(tstat, dstat, bk, rows_t, M, r, carry_log_nu[b]));
         const float log2W = static_cast<float>(log2(norm[drow]) + sq.lse2 - static_cast<double>(hq));   // relative to 2^hq
         const float Kf = static_cast<float>(K);
-        for_each_pair<T, VEC>(rq, rp, V, [&](int x, const float (&zq)[N], const float (&zp)[N]) {
+        for_each_pair<T, VEC, kModThreads>(rq, rp, V, [&](int x, const float (&zq)[N], const float (&zp)[N]) {
             float a[N], bb[N];
 #pragma unroll
             for (int j = 0; j < N; ++j) {
@@ -237,7 +209,7 @@ k_mod_write(const T *__restrict__ target, const T *__restrict__ draft, int K, in
             if (op) store_vals(op + x, bb);
         });
     } else {
-        for_each_pair<T, VEC>(rq, rp, V, [&](int x, const float (&zq)[N], const float (&zp)[N]) {
+        for_each_pair<T, VEC, kModThreads>(rq, rp, V, [&](int x, const float (&zq)[N], const float (&zp)[N]) {
             float a[N], bb[N];
 #pragma unroll
             for (int j = 0; j < N; ++j) {

@@ -66,20 +66,6 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
     }
 }
 
-// One entry's term of the sum against a modified row: q t1^K (relative to 2^shift_q) times
-// max(1 - p / (nu q'), 0)^K with q' = q t1^K / N, i.e. the second ratio is the first kind of
-// ratio (constant rc2, which carries nu / N) divided by t1^K.
-__device__ __forceinline__ float pend_term(float zq, float zp, float c, float shift_q, const RatioConst &rc1,
-                                           const RatioConst &rc2, int K, float *wq_out = nullptr)
-{
-    const float d = zp - zq;
-    const float eq = exp2_fast(fmaf(zq, c, -shift_q));
-    const float tK = powi_uniform(rc1.one_minus_ratio(d, c), K);
-    const float wq = eq * tK;
-    if (wq_out) *wq_out = wq;
-    return wq * powi_uniform(pend_second_factor(exp2_fast(fmaf(d, c, -rc2.C2_hi)), tK, rc2.neg_kappa), K);
-}
-
 // grid.x = batch * K * L row pairs, row index slowest: the live workgroups (rows below the prefix's
 // count) are then consecutive and spread over all dies, whatever L is; the others leave at once
 template <typename T, bool VEC>
@@ -111,24 +97,14 @@ k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, in
     const RatioConst rc(st.lse2_p - st.lse2_q + log2mu);
     const T *rq = target + (bk * (L + 1) + r) * static_cast<long long>(V);
     const T *rp = draft + pair * static_cast<long long>(V);
-    constexpr int PV = Elem<T>::kPerVec;
+    constexpr int N = VEC ? Elem<T>::kPerVec : 1;
     float acc = 0.0f;
-    if (VEC) {
-        const int nvec = V / PV;
-        for (int v = threadIdx.x; v < nvec; v += kStatThreads) {
-            float zq[PV], zp[PV];
-            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
-            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
+    for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+        float wq[N], w[N];
+        ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
 #pragma unroll
-            for (int j = 0; j < PV; ++j)
-                acc = fmaf(exp2_fast(fmaf(zq[j], c, -shift_q)), powi_uniform(rc.one_minus_ratio(zp[j] - zq[j], c), K), acc);
-        }
-    } else {
-        for (int x = threadIdx.x; x < V; x += kStatThreads) {
-            const float zq = Elem<T>::scalar(rq + x), zp = Elem<T>::scalar(rp + x);
-            acc = fmaf(exp2_fast(fmaf(zq, c, -shift_q)), powi_uniform(rc.one_minus_ratio(zp - zq, c), K), acc);
-        }
-    }
+        for (int j = 0; j < N; ++j) acc += w[j];
+    });
     const double S = block_sum(static_cast<double>(acc), sh_d);           // relative to 2^shift_q
     if (threadIdx.x == 0) {
         const double W = S * exp2(static_cast<double>(shift_q) - st.lse2_q);
@@ -164,50 +140,30 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
     const float shift_q = static_cast<float>(st.lse2_q);
     const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
     const T *rp = draft + (bk * L + i) * static_cast<long long>(V);
-    constexpr int PV = Elem<T>::kPerVec;
+    constexpr int N = VEC ? Elem<T>::kPerVec : 1;
     float acc = 0.0f;
     if (PEND && pend[bk * L + i].flag) {          // uniform over the workgroup
         const PendRow pr = pend[bk * L + i];
         const RatioConst rc1(st.lse2_p - st.lse2_q + pr.log2mu);
         const RatioConst rc2(st.lse2_p - st.lse2_q + log2nu - pr.log2N);
-        if (VEC) {
-            const int nvec = V / PV;
-            for (int v = threadIdx.x; v < nvec; v += kStatThreads) {
-                float zq[PV], zp[PV];
-                Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
-                Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
+        for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+            float wq[N], w[N];
+            pending_weights(zq, zp, c, shift_q, rc1, rc2, K, wq, w);
 #pragma unroll
-                for (int j = 0; j < PV; ++j) acc += pend_term(zq[j], zp[j], c, shift_q, rc1, rc2, K);
-            }
-        } else {
-            for (int x = threadIdx.x; x < V; x += kStatThreads)
-                acc += pend_term(Elem<T>::scalar(rq + x), Elem<T>::scalar(rp + x), c, shift_q, rc1, rc2, K);
-        }
+            for (int j = 0; j < N; ++j) acc += w[j];
+        });
         const double total = block_sum(static_cast<double>(acc), sh_d);
         if (threadIdx.x == 0)
             s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - pr.log2N);
         return;
     }
     const RatioConst rc(st.lse2_p - st.lse2_q + log2nu);
-    if (VEC) {
-        const int nvec = V / PV;
-        for (int v = threadIdx.x; v < nvec; v += kStatThreads) {
-            float zq[PV], zp[PV];
-            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
-            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
+    for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+        float wq[N], w[N];
+        ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
 #pragma unroll
-            for (int j = 0; j < PV; ++j) {
-                const float eq = exp2_fast(fmaf(zq[j], c, -shift_q));
-                acc = fmaf(eq, powi_uniform(rc.one_minus_ratio(zp[j] - zq[j], c), K), acc);
-            }
-        }
-    } else {
-        for (int x = threadIdx.x; x < V; x += kStatThreads) {
-            const float zq = Elem<T>::scalar(rq + x), zp = Elem<T>::scalar(rp + x);
-            const float eq = exp2_fast(fmaf(zq, c, -shift_q));
-            acc = fmaf(eq, powi_uniform(rc.one_minus_ratio(zp - zq, c), K), acc);
-        }
-    }
+        for (int j = 0; j < N; ++j) acc += w[j];
+    });
     const double total = block_sum(static_cast<double>(acc), sh_d);
     if (threadIdx.x == 0)
         s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q);
