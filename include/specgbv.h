@@ -107,28 +107,42 @@ specgbv_status specgbv_verify(
     int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+#define SPECGBV_MAX_PENDING 8   /* pending distribution modifications applied on the fly at most */
+
 /* Extra controls for specgbv_verify_ex; zero-initialise for the defaults. */
 typedef struct specgbv_options {
     int32_t algo;              /* specgbv_algo                                              */
-    int32_t reserved;
+    int32_t pending_levels;    /* see pending_carry_log_nu                                  */
     void *ev_main_start;       /* hipEvent_t or NULL: recorded on the stream immediately    */
     void *ev_main_stop;        /*   before / after the vocabulary-streaming kernels that    */
                                /*   compute the statistics and the sums of Eq. (hik)        */
     /*
-     * Pending distribution modification (Algorithm 2) applied on the fly: both NULL (none) or both
-     * device pointers.  The first pending_count[b] rows of every draft of prefix b are verified
-     * against q_new of Algorithm 2 (computed from the same target and draft rows, never written
-     * out) instead of the target rows, with the block ratio starting from
-     * exp(pending_carry_log_nu[b]); the outputs are those of specgbv_modify_target followed by a
-     * verification of its rows.  The pair is what the previous iteration left in its workspace
-     * (specgbv_workspace_carry; the pointers may point into the workspace passed to this call:
-     * they are read before the new values are written), possibly advanced by
-     * specgbv_carry_advance.  One pending modification only: where two are pending on the same
-     * rows, apply them with specgbv_modify_target.  Runs on the two-pass schedule
-     * (SPECGBV_ALGO_CHAIN is rejected).  A modified row whose weights are all zero stays q.
+     * Pending distribution modifications (Algorithm 2) applied on the fly: both pointers NULL (none) or
+     * both device pointers to pending_levels arrays of [batch] values, innermost level first
+     * (pending_levels = 0 with pointers given means 1; at most SPECGBV_MAX_PENDING).  Level l makes the
+     * first pending_count[l][b] rows of every draft of prefix b the distribution q_new of Algorithm 2,
+     * computed from the rows as the levels before it left them and from the same draft rows, with the
+     * block ratio starting from exp(pending_carry_log_nu[l][b]); nothing is written out, and the
+     * outputs are those of specgbv_modify_target applied level by level followed by a verification
+     * of its rows.  One level is what the previous iteration left in its workspace
+     * (specgbv_workspace_carry; the pointers may point into the workspace passed to this call: they
+     * are read before the new values are written); several levels arise when an iteration ends
+     * before the previous modification's rows are used up (Algorithm 3 updates q in place).
+     * Runs on the two-pass schedule (SPECGBV_ALGO_CHAIN is rejected).  A modified row whose weights
+     * are all zero stays as it was.
      */
-    const double *pending_carry_log_nu;   /* device, [batch] */
-    const int32_t *pending_count;         /* device, [batch], values below 0 or above L are clamped */
+    const double *pending_carry_log_nu;   /* device, [pending_levels][batch] */
+    const int32_t *pending_count;         /* device, [pending_levels][batch], values below 0 or above L are clamped */
+    /*
+     * Or (instead of the two pointers above, which must then be NULL): the whole bookkeeping of
+     * Algorithm 3 on the device.  pending_state is a device buffer of
+     * specgbv_pending_state_bytes(batch) bytes, all zero before the first iteration of a prefix; the
+     * call applies the modifications it holds and then updates it in place: every level's ratio is
+     * moved along the tokens this iteration emits and its count reduced (specgbv_carry_advance),
+     * levels whose rows are used up are dropped, and the modification this iteration creates is
+     * appended.  Needs L - 1 <= SPECGBV_MAX_PENDING.  Calls on one state must not overlap.
+     */
+    void *pending_state;
 } specgbv_options;
 
 /* specgbv_verify with explicit options (options == NULL means defaults). */
@@ -139,6 +153,10 @@ specgbv_status specgbv_verify_ex(
     int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
     void *workspace, size_t workspace_bytes, void *hip_stream,
     const specgbv_options *options);
+
+/* Bytes of the pending_state buffer of specgbv_options for `batch` prefixes (0 if batch < 0): SPECGBV_MAX_PENDING
+ * carried ratios (float64) and row counts (int32) per prefix, level-major.  Section 4.2, Algorithms 2 and 3. */
+size_t specgbv_pending_state_bytes(int batch);
 
 /*
  * HOST buffers receiving the intermediates of the most recent call that used a

@@ -22,7 +22,7 @@ _ALGO = {"auto": ALGO_AUTO, "split": ALGO_SPLIT, "chain": ALGO_CHAIN}
 
 EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_ex", "specgbv_read_intermediates",
            "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_modify_workspace_bytes", "specgbv_sample_tokens", "specgbv_sample_workspace_bytes",
-           "specgbv_read_sample_intermediates", "specgbv_carry_advance", "specgbv_carry_workspace_bytes", "specgbv_last_error", "specgbv_version")
+           "specgbv_read_sample_intermediates", "specgbv_carry_advance", "specgbv_carry_workspace_bytes", "specgbv_pending_state_bytes", "specgbv_last_error", "specgbv_version")
 
 
 class SpecGBVError(RuntimeError):
@@ -32,8 +32,8 @@ class SpecGBVError(RuntimeError):
 
 
 class _Options(ctypes.Structure):
-    _fields_ = [("algo", c_int32), ("reserved", c_int32), ("ev_main_start", c_void_p), ("ev_main_stop", c_void_p),
-                ("pending_carry_log_nu", c_void_p), ("pending_count", c_void_p)]
+    _fields_ = [("algo", c_int32), ("pending_levels", c_int32), ("ev_main_start", c_void_p), ("ev_main_stop", c_void_p),
+                ("pending_carry_log_nu", c_void_p), ("pending_count", c_void_p), ("pending_state", c_void_p)]
 
 
 class _Intermediates(ctypes.Structure):
@@ -64,6 +64,8 @@ def load_library() -> ctypes.CDLL:
     L.specgbv_verify.restype = c_int
     L.specgbv_verify_ex.argtypes = verify_args + [POINTER(_Options)]
     L.specgbv_verify_ex.restype = c_int
+    L.specgbv_pending_state_bytes.argtypes = [c_int]
+    L.specgbv_pending_state_bytes.restype = c_size_t
     L.specgbv_read_intermediates.argtypes = [c_void_p, c_size_t, c_int, c_int, c_int, c_int, c_int,
                                              POINTER(_Intermediates), c_void_p]
     L.specgbv_read_intermediates.restype = c_int
@@ -146,14 +148,18 @@ def _shapes(target_logits, draft_logits, draft_tokens):
 
 def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int,
                       rng_offset: int, *, workspace=None, out: Optional[Tuple] = None, algo="auto",
-                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None, pending=None):
+                      events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None, pending=None,
+                      pending_state=None):
     """Enqueue one verification on the current (or given) HIP stream.
 
     Returns (accepted_len [B], accepted_draft_idx [B], out_tokens [B, L+1], workspace), all
     device tensors; nothing is synchronised.  `events` is a pair of raw hipEvent_t handles
     recorded around the vocabulary-streaming kernels.  `pending` is a pair (carry_log_nu, count)
-    of [B] float64 / int32 device tensors or raw device addresses: a pending distribution
-    modification (Algorithm 2) applied on the fly to the first count[b] rows of every draft.
+    of [B] (one level) or [levels, B] float64 / int32 device tensors, or raw device addresses of
+    one level: pending distribution modifications (Algorithm 2) applied on the fly, innermost
+    first.  `pending_state` (instead) is a zero-initialised uint8 device tensor of
+    specgbv_pending_state_bytes(B) bytes that the call reads and updates in place: the whole
+    bookkeeping of Algorithm 3's modifications.
     """
     import torch
     lib = load_library()
@@ -169,20 +175,36 @@ def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: fl
     acc_len, acc_idx, out_tokens = out
     if stream is None:
         stream = torch.cuda.current_stream(dev).cuda_stream
+    levels = 0
     if pending is not None:
         for t, dtp in ((pending[0], torch.float64), (pending[1], torch.int32)):
-            if not isinstance(t, int) and (t.dtype != dtp or tuple(t.shape) != (B,) or not t.is_cuda):
-                raise ValueError("pending must be ([B] float64, [B] int32) GPU tensors or raw device addresses")
-    opt = _Options(_ALGO[algo] if isinstance(algo, str) else int(algo), 0,
+            if isinstance(t, int):
+                continue
+            if t.dtype != dtp or not t.is_cuda or not t.is_contiguous() or t.shape[-1] != B or t.dim() not in (1, 2):
+                raise ValueError("pending must be ([B] or [levels, B] float64, int32) contiguous GPU tensors or raw device addresses")
+            lv = 1 if t.dim() == 1 else int(t.shape[0])
+            if levels not in (0, lv):
+                raise ValueError("pending carry and count disagree on the number of levels")
+            levels = lv
+    if pending_state is not None:
+        if not pending_state.is_cuda or not pending_state.is_contiguous() or \
+                pending_state.numel() * pending_state.element_size() < specgbv_pending_state_bytes(B):
+            raise ValueError("pending_state must be a contiguous GPU tensor of specgbv_pending_state_bytes(B) bytes")
+    opt = _Options(_ALGO[algo] if isinstance(algo, str) else int(algo), levels,
                    events[0] if events else None, events[1] if events else None,
                    _dev_ptr(pending[0]) if pending is not None else None,
-                   _dev_ptr(pending[1]) if pending is not None else None)
+                   _dev_ptr(pending[1]) if pending is not None else None,
+                   pending_state.data_ptr() if pending_state is not None else None)
     st = lib.specgbv_verify_ex(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V,
                                B, dt, c_float(temperature), rng_seed, rng_offset, acc_len.data_ptr(),
                                acc_idx.data_ptr(), out_tokens.data_ptr(), workspace.data_ptr(),
                                workspace.numel() * workspace.element_size(), stream, ctypes.byref(opt))
     _check(st)
     return acc_len, acc_idx, out_tokens, workspace
+
+
+def specgbv_pending_state_bytes(batch: int) -> int:
+    return int(load_library().specgbv_pending_state_bytes(batch))
 
 
 def specgbv_verify(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int, rng_offset: int,

@@ -45,7 +45,7 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.carry = take(static_cast<size_t>(batch) * sizeof(double));
     w.mcount = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.counter = take(static_cast<size_t>(batch) * sizeof(int32_t));
-    w.pend = take(n * sizeof(PendRow));
+    w.pend = take(n * kMaxPend * sizeof(PendRow));
     w.total = off;
     return w;
 }
@@ -78,6 +78,13 @@ size_t specgbv_workspace_bytes(int batch, int K, int L, int V, specgbv_dtype dty
     if (!shape_ok(batch, K, L, V) || (dtype != SPECGBV_F32 && dtype != SPECGBV_BF16)) return 0;
     if (check_limits(batch, K, L, V) != SPECGBV_OK) return 0;
     return make_workspace(batch < 1 ? 1 : batch, K, L, V).total;
+}
+
+size_t specgbv_pending_state_bytes(int batch)
+{
+    if (batch < 0) return 0;
+    const size_t b = static_cast<size_t>(batch < 1 ? 1 : batch);
+    return align256(b * kMaxPend * (sizeof(double) + sizeof(int32_t)));
 }
 
 specgbv_status specgbv_verify_ex(
@@ -121,17 +128,38 @@ specgbv_status specgbv_verify_ex(
     p.ws = static_cast<char *>(workspace);
     p.stream = static_cast<hipStream_t>(hip_stream);
 
-    p.pend_carry = options ? static_cast<const double *>(options->pending_carry_log_nu) : nullptr;
-    p.pend_count = options ? static_cast<const int32_t *>(options->pending_count) : nullptr;
+    static_assert(SPECGBV_MAX_PENDING == kMaxPend, "header and kernels disagree on the number of pending levels");
+    p.pend_carry = options ? options->pending_carry_log_nu : nullptr;
+    p.pend_count = options ? options->pending_count : nullptr;
+    p.pend_levels = 0;
+    p.state_carry = nullptr; p.state_count = nullptr;
     if ((p.pend_carry == nullptr) != (p.pend_count == nullptr))
         return fail(SPECGBV_EINVAL, "pending_carry_log_nu and pending_count must be given together");
-    if (p.pend_carry && (reinterpret_cast<uintptr_t>(p.pend_carry) % 8 || reinterpret_cast<uintptr_t>(p.pend_count) % 4))
-        return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
-    if (p.pend_carry && algo == SPECGBV_ALGO_CHAIN)
-        return fail(SPECGBV_EUNSUPPORTED, "a pending modification runs on the two-pass schedule only");
+    if (p.pend_carry) {
+        if (options->pending_state) return fail(SPECGBV_EINVAL, "give pending_state or the pending arrays, not both");
+        if (reinterpret_cast<uintptr_t>(p.pend_carry) % 8 || reinterpret_cast<uintptr_t>(p.pend_count) % 4)
+            return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
+        if (options->pending_levels < 0 || options->pending_levels > SPECGBV_MAX_PENDING)
+            return fail(SPECGBV_EUNSUPPORTED, "pending_levels=%d exceeds SPECGBV_MAX_PENDING=%d", options->pending_levels,
+                        SPECGBV_MAX_PENDING);
+        p.pend_levels = options->pending_levels > 0 ? options->pending_levels : 1;
+    } else if (options && options->pending_levels != 0) {
+        return fail(SPECGBV_EINVAL, "pending_levels given without the pending arrays");
+    } else if (options && options->pending_state) {
+        if (reinterpret_cast<uintptr_t>(options->pending_state) % 8)
+            return fail(SPECGBV_EINVAL, "pending_state must be 8-byte aligned");
+        if (L - 1 > SPECGBV_MAX_PENDING)
+            return fail(SPECGBV_EUNSUPPORTED, "pending_state needs L - 1 <= SPECGBV_MAX_PENDING=%d (L=%d)", SPECGBV_MAX_PENDING, L);
+        p.state_carry = static_cast<double *>(options->pending_state);
+        p.state_count = reinterpret_cast<int32_t *>(p.state_carry + static_cast<size_t>(kMaxPend) * batch);
+        p.pend_carry = p.state_carry; p.pend_count = p.state_count;
+        p.pend_levels = L - 1;               // at most L - 1 modifications are alive at once; 0 for L = 1
+    }
+    if ((p.pend_levels > 0 || p.state_carry) && algo == SPECGBV_ALGO_CHAIN)
+        return fail(SPECGBV_EUNSUPPORTED, "pending modifications run on the two-pass schedule only");
 
     bool use_chain = false;
-    if (p.pend_carry) {
+    if (p.pend_levels > 0 || p.state_carry) {
         use_chain = false;
     } else if (algo == SPECGBV_ALGO_CHAIN) {
         if (!chain_supported(p)) return fail(SPECGBV_EUNSUPPORTED, "the chain schedule does not support this shape");
@@ -386,6 +414,6 @@ specgbv_status specgbv_read_sample_intermediates(const void *workspace, size_t w
 
 const char *specgbv_last_error(void) { return g_err; }
 
-const char *specgbv_version(void) { return "specgbv 0.3 (gfx950)"; }
+const char *specgbv_version(void) { return "specgbv 0.4 (gfx950)"; }
 
 }  // extern "C"

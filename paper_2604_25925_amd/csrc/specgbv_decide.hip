@@ -106,7 +106,9 @@ __device__ double clamp01(double h)
 struct DecideIO {
     const int32_t *tokens;
     const RowStat *stats;
-    const PendRow *pend;        // rows under a pending modification, or null
+    const PendRow *pend;        // rows under pending modifications [nlev][n_rows], or null
+    long long n_rows;           // batch * K * L
+    int nlev;
     const double *s_arr;
     double *log_nu_out, *log_P_out, *h_out, *eta_out;
     int32_t *state_out;
@@ -118,7 +120,8 @@ struct DecideIO {
 // write = true stores outputs and intermediates.  *u_final_out (shared memory) receives the uniform
 // of the final token (Philox slot K*L), drawn here so that the generator is instantiated once.
 __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, int L, uint64_t seed, uint64_t offset,
-                                              bool write, double *lds, Selection *sel_out, double *u_final_out)
+                                              bool write, double *lds, Selection *sel_out, double *u_final_out,
+                                              PendTable *tab_out)
 {
     const int32_t *__restrict__ tokens = io.tokens;
     const RowStat *__restrict__ stats = io.stats;
@@ -140,7 +143,7 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
     for (int idx = tid; idx < KL; idx += kDecideThreads) {
         const RowStat st = stats[base + idx];
         tq[idx] = st.tok2_q - st.lse2_q;
-        if (io.pend) tq[idx] += io.pend[base + idx].tokadj - io.pend[base + idx].log2N;   // log2 q'[token]
+        if (io.pend) tq[idx] += pend_token_adjust(io.pend, io.n_rows, io.nlev, base + idx);   // log2 q'[token]
         tp[idx] = st.tok2_p - st.lse2_p;
         lq[idx] = st.lse2_q; lp[idx] = st.lse2_p;
         tok[idx] = tokens[base + idx];
@@ -228,7 +231,8 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         }
         Selection sl;
         sl.tau = tau;
-        sl.C1 = 0.0; sl.pend = 0; sl.pad = 0;
+        sl.npend = 0; sl.pad = 0;
+        tab_out->n = 0;
         sl.target_row = (static_cast<long long>(b) * K + kf) * (L + 1) + tau;
         if (tau == L) {
             sl.draft_row = -1; sl.C2 = 0.0; sl.shift_q = 0.0f; sl.lse2_q = 0.0;
@@ -238,12 +242,22 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
             sl.C2 = lse2_p - lse2_q + (tau == 0 ? 0.0 : l2nu[kf * L + tau - 1]);
             sl.shift_q = rintf(static_cast<float>(lse2_q));         // integral: partial sums rescale exactly
             sl.lse2_q = lse2_q;
-            if (io.pend && io.pend[base + kf * L + tau].flag) {     // the row is q' = q t^K / N
-                const PendRow pr = io.pend[base + kf * L + tau];
-                sl.pend = 1;
-                sl.C1 = lse2_p - lse2_q + pr.log2mu;
-                sl.C2 -= pr.log2N;
-                sl.lse2_q = lse2_q + pr.log2N;
+            if (io.pend) {                                          // levels that modify the row: q' = q prod t_l^K / N_l
+                double sumN = 0.0;
+                int n = 0;
+                for (int l = 0; l < io.nlev; ++l) {
+                    const PendRow pr = io.pend[l * io.n_rows + base + kf * L + tau];
+                    if (pr.flag) {
+                        sl.Cl[n] = lse2_p - lse2_q + pr.log2mu - sumN;
+                        pend_table_set(*tab_out, n, sl.Cl[n]);
+                        ++n;
+                        sumN += pr.log2N;
+                    }
+                }
+                sl.npend = n;
+                tab_out->n = n;
+                sl.C2 -= sumN;
+                sl.lse2_q = lse2_q + sumN;
             }
         }
         *sel_out = sl;
@@ -300,8 +314,8 @@ __device__ __forceinline__ void segment_load(const T *target, const T *draft, co
 // token is drawn from; wq: plain target weights).  With m2 = NaN on entry for the bonus row
 // the segment's own maximum is used as reference and returned.
 template <bool PEND>
-__device__ __forceinline__ float segment_weigh(const Selection &sl, int V, int K, float c, int seg, int lane,
-                                               float m2_in, const float (&zq)[8], const float (&zp)[8],
+__device__ __forceinline__ float segment_weigh(const Selection &sl, const PendTable &tab, int V, int K, float c, int seg,
+                                               int lane, float m2_in, const float (&zq)[8], const float (&zp)[8],
                                                float (&w)[8], float (&wq)[8])
 {
     const long long e0 = static_cast<long long>(seg) * kSegElems + lane * 8;
@@ -319,10 +333,9 @@ __device__ __forceinline__ float segment_weigh(const Selection &sl, int V, int K
     }
     const float m2 = sl.shift_q;
     const RatioConst rc(sl.C2);
-    if (PEND && sl.pend) {
-        // modified row: plain weights q t1^K, residual weights q t1^K max(1 - p/(nu q'), 0)^K
-        const RatioConst rc1(sl.C1);
-        pending_weights(zq, zp, c, m2, rc1, rc, K, wq, w);
+    if (PEND && tab.n > 0) {
+        // modified row: plain weights q prod t_l^K, residual weights those times max(1 - p/(nu q'), 0)^K
+        pending_weights(zq, zp, c, m2, tab, rc, K, wq, w);
     } else {
         ot_weights(zq, zp, c, m2, rc, K, wq, w);
     }
@@ -373,6 +386,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     static_assert(kSegThreads == kDecideThreads, "the decision runs on the whole workgroup");
     extern __shared__ double lds_decide[];
     __shared__ Selection sh_sel;
+    __shared__ PendTable sh_tab;
     __shared__ double sh_u;
     __shared__ int sh_is_last;
     __shared__ double sh_d[kSegThreads / kWave];
@@ -389,7 +403,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     double *__restrict__ carry_out = fo.carry;
 
     // ---- 1. decision (redundantly per workgroup; the first one of the prefix writes it out)
-    decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u);
+    decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
     const Selection sl = sh_sel;
     if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
 
@@ -407,7 +421,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
             sw[i] = 0.0; sq[i] = 0.0; m2[i] = 0.0f;
             if (seg0 + i < nseg) {                      // wave-uniform
                 float w[8], wq[8];
-                m2[i] = segment_weigh<PEND>(sl, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[i], w, wq);
+                m2[i] = segment_weigh<PEND>(sl, sh_tab, V, K, c, seg0 + i, lane, __builtin_nanf(""), zq[i], zp[i], w, wq);
 #pragma unroll
                 for (int j = 0; j < 8; ++j) { sw[i] += static_cast<double>(w[j]); sq[i] += static_cast<double>(wq[j]); }
             }
@@ -533,7 +547,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     {
         float zq[8], zp[8];
         segment_load<T, VEC>(target, draft, sl, V, seg, lane, zq, zp);
-        segment_weigh<PEND>(sl, V, K, c, seg, lane, sh_seg_m2, zq, zp, w, wq);
+        segment_weigh<PEND>(sl, sh_tab, V, K, c, seg, lane, sh_seg_m2, zq, zp, w, wq);
     }
     double ws[8];
     double mine = 0.0;
@@ -584,9 +598,13 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
             const double zq = static_cast<double>(Elem<T>::scalar(target + sl.target_row * V + tokid));
             const double zp = static_cast<double>(Elem<T>::scalar(draft + sl.draft_row * V + tokid));
             double l2 = sl.C2 + static_cast<double>(c) * (zq - zp);        // log2 of nu_tau q[y] / p[y]
-            if (PEND && sl.pend) {                                         // q'[y] = q[y] t1[y]^K / N (N is in C2)
-                const double t1 = 1.0 - exp2_small(static_cast<double>(c) * (zp - zq) - sl.C1);
-                l2 = t1 > 0.0 ? l2 + static_cast<double>(K) * log2(t1) : -INFINITY;
+            if (PEND) {                                     // q'[y] = q[y] prod_l t_l[y]^K / N_l (the N_l are in C2)
+                double log2T = 0.0;
+                for (int l = 0; l < sl.npend; ++l) {
+                    const double t = 1.0 - exp2_small(static_cast<double>(c) * (zp - zq) - sl.Cl[l] - log2T);
+                    log2T = t > 0.0 ? log2T + static_cast<double>(K) * log2(t) : -INFINITY;
+                }
+                l2 += log2T;
             }
             carry = l2 * 0.693147180559945309417;
         }
@@ -608,7 +626,9 @@ hipError_t launch_final_typed(const Problem &p)
     DecideIO io;
     io.tokens = p.tokens;
     io.stats = reinterpret_cast<const RowStat *>(p.ws + p.lay.stats);
-    io.pend = p.pend_carry ? reinterpret_cast<const PendRow *>(p.ws + p.lay.pend) : nullptr;
+    io.pend = p.pend_levels > 0 ? reinterpret_cast<const PendRow *>(p.ws + p.lay.pend) : nullptr;
+    io.n_rows = static_cast<long long>(p.batch) * p.K * p.L;
+    io.nlev = p.pend_levels;
     io.s_arr = reinterpret_cast<const double *>(p.ws + p.lay.s);
     io.log_nu_out = reinterpret_cast<double *>(p.ws + p.lay.log_nu);
     io.log_P_out = reinterpret_cast<double *>(p.ws + p.lay.log_P);
@@ -631,7 +651,7 @@ hipError_t launch_final_typed(const Problem &p)
 #define SPECGBV_FINAL_LAUNCH(VEC, PEND)                                                                              \
     hipLaunchKernelGGL((k_final<T, VEC, PEND>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K, \
                        p.L, p.c, p.lay.nseg, p.seed, p.offset)
-    if (p.pend_carry) { if (vec) SPECGBV_FINAL_LAUNCH(true, true); else SPECGBV_FINAL_LAUNCH(false, true); }
+    if (p.pend_levels > 0) { if (vec) SPECGBV_FINAL_LAUNCH(true, true); else SPECGBV_FINAL_LAUNCH(false, true); }
     else { if (vec) SPECGBV_FINAL_LAUNCH(true, false); else SPECGBV_FINAL_LAUNCH(false, false); }
 #undef SPECGBV_FINAL_LAUNCH
     return hipGetLastError();

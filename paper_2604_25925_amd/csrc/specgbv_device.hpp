@@ -27,15 +27,25 @@ struct RowStat {
     double tok2_p;   // c * z_p[token of this row]
 };
 
-// A row of a verification that runs under a pending distribution modification (Algorithm 2
-// applied on the fly): the row's target distribution is q'[x] = q[x] t[x]^K / N with
-// t[x] = max(1 - p[x] / (mu q[x]), 0).  All in base-2 logarithms.
+// Pending distribution modifications (Algorithm 2 applied on the fly, possibly several on top of
+// each other: Algorithm 3 updates q in place).  Level l turns the row's distribution q^(l) into
+//   q^(l+1)[x] = q^(l)[x] t_l[x]^K / N_l,   t_l[x] = max(1 - p[x] / (mu_l q^(l)[x]), 0),   q^(0) = q,
+// for the first count_l rows of every draft.  Per (level, prefix, draft, row), in base-2 logarithms:
+constexpr int kMaxPend = 8;      // levels applied on the fly at most
 struct PendRow {
-    double log2mu;   // block ratio Algorithm 2 uses at this row (carried ratio continued with the original q)
-    double log2N;    // log2 of N = sum_x q[x] t[x]^K (0 when the row is not modified)
-    double tokadj;   // K log2 t[token of this row]: log2 q'[token] = log2 q[token] + tokadj - log2N (0 when not modified)
-    int32_t flag;    // 1: the row is modified; 0: it is q itself (beyond the count, or N = 0)
+    double log2mu;   // block ratio mu_l in front of this row (carried ratio continued along the drafted tokens with q^(l))
+    double log2N;    // log2 of N_l = sum_x q^(l)[x] t_l[x]^K (0 when the level does not modify the row)
+    double tokadj;   // K log2 t_l[token of this row]: log2 q^(l+1)[token] = log2 q^(l)[token] + tokadj - log2N (0 when not modified)
+    int32_t flag;    // 1: the level modifies the row; 0: row beyond its count, or N_l = 0 (the row stays q^(l))
     int32_t pad;
+};
+
+// Constants of the levels that modify one row, in order (workgroup-uniform; kept in LDS):
+// p[x] / (mu_l q^(l)[x]) = 2^(c (z_p - z_q) - C_hi[l]) kappa_l / T_l[x] with T_l = prod_{m<l} t_m^K.
+struct PendTable {
+    int n;
+    float C_hi[kMaxPend];
+    float neg_kappa[kMaxPend];
 };
 
 // What the final-token kernels need to know about one prefix.
@@ -46,9 +56,9 @@ struct Selection {
     double lse2_q;          // log2 normaliser of the target row (0 for the bonus row)
     float shift_q;          // reference exponent for target-row weights (unused for the bonus row)
     int tau;
-    double C1;              // modified row only: log2 of mu * Z_p / Z_q (C2 and lse2_q then refer to q')
-    int pend;               // 1: the row is modified by a pending modification
+    int npend;              // levels of pending modifications that modify the row (C2 and lse2_q then refer to the modified row)
     int pad;
+    double Cl[kMaxPend];    // per such level: log2 of mu_l Z_p / Z_q minus the log2 N of the levels before it
 };
 
 // Partial sums of one residual segment, relative to 2^m2.
@@ -200,28 +210,73 @@ __device__ __forceinline__ void ot_weights(const float (&zq)[N], const float (&z
     for (int j = 0; j < N; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -shift_q)); w[j] = wq[j] * t[j]; }
 }
 
-// The same for a row under a pending modification, q' = q t1^K / N with t1 = max(1 - p / (mu q), 0) (mu in rc1):
-//   wq[j] = 2^(c z_q[j] - shift_q) t1[j]^K              (plain weight of q', up to 1/N)
-//   w[j]  = wq[j] max(1 - p[j] / (nu q'[j]), 0)^K       with nu / N in rc2: the second ratio is the first kind
-//                                                       of exponential divided by t1^K.
+// The same for a row under pending modifications (tab: the levels that modify it, at least one): with T = prod_l t_l^K,
+//   wq[j] = 2^(c z_q[j] - shift_q) T[j]                 (plain weight of the modified row, up to 1 / prod N_l)
+//   w[j]  = wq[j] max(1 - p[j] / (nu q'[j]), 0)^K       with nu / prod N_l in rc: every level's ratio is the first
+//                                                       kind of exponential divided by the running product T.
 template <int N>
 __device__ __forceinline__ void pending_weights(const float (&zq)[N], const float (&zp)[N], float c, float shift_q,
-                                                const RatioConst &rc1, const RatioConst &rc2, int K, float (&wq)[N],
+                                                const PendTable &tab, const RatioConst &rc, int K, float (&wq)[N],
                                                 float (&w)[N]) {
-    float t1[N], r[N];
+    float T[N], d[N];
+    {                                                 // level 0 (tab.n >= 1): T = 1, no quotient
+        const float C_hi = tab.C_hi[0], neg_kappa = tab.neg_kappa[0];
 #pragma unroll
-    for (int j = 0; j < N; ++j) {
-        const float d = zp[j] - zq[j];
-        t1[j] = rc1.one_minus_ratio(d, c);
-        r[j] = exp2_fast(fmaf(d, c, -rc2.C2_hi));
+        for (int j = 0; j < N; ++j) {
+            d[j] = zp[j] - zq[j];
+            T[j] = __builtin_amdgcn_fmed3f(fmaf(exp2_fast(fmaf(d[j], c, -C_hi)), neg_kappa, 1.0f), 0.0f, 1.0f);
+        }
+        pow_array(T, K);
     }
-    pow_array(t1, K);
-    float t2[N];
+    for (int l = 1; l < tab.n; ++l) {                 // uniform
+        const float C_hi = tab.C_hi[l], neg_kappa = tab.neg_kappa[l];
+        float t[N];
 #pragma unroll
-    for (int j = 0; j < N; ++j) t2[j] = pend_second_factor(r[j], t1[j], rc2.neg_kappa);
-    pow_array(t2, K);
+        for (int j = 0; j < N; ++j) t[j] = pend_second_factor(exp2_fast(fmaf(d[j], c, -C_hi)), T[j], neg_kappa);
+        pow_array(t, K);
 #pragma unroll
-    for (int j = 0; j < N; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -shift_q)) * t1[j]; w[j] = wq[j] * t2[j]; }
+        for (int j = 0; j < N; ++j) T[j] *= t[j];
+    }
+    float t[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) t[j] = pend_second_factor(exp2_fast(fmaf(d[j], c, -rc.C2_hi)), T[j], rc.neg_kappa);
+    pow_array(t, K);
+#pragma unroll
+    for (int j = 0; j < N; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -shift_q)) * T[j]; w[j] = wq[j] * t[j]; }
+}
+
+// Entry l of a PendTable from the float64 constant C (same split as RatioConst).
+__device__ __forceinline__ void pend_table_set(PendTable &tab, int l, double C) {
+    const RatioConst rc(C);
+    tab.C_hi[l] = rc.C2_hi;
+    tab.neg_kappa[l] = rc.neg_kappa;
+}
+
+// The levels (0 .. nlev-1, arrays level-major with n_rows entries each) that modify row `pair`, as a table of
+// constants; base = log2 Z_p - log2 Z_q of the row.  Returns the sum of their log2 N.
+__device__ __forceinline__ double pend_build_table(const PendRow *pend, long long n_rows, int nlev, long long pair, double base,
+                                   PendTable &tab)
+{
+    double sumN = 0.0;
+    int n = 0;
+    for (int l = 0; l < nlev; ++l) {
+        const PendRow pr = pend[l * n_rows + pair];
+        if (pr.flag) {
+            pend_table_set(tab, n, base + pr.log2mu - sumN);
+            ++n;
+            sumN += pr.log2N;
+        }
+    }
+    tab.n = n;
+    return sumN;
+}
+
+// log2 q^(nlev)[token] - log2 q[token] of row `pair`: what levels 0 .. nlev-1 do to the drafted token's probability.
+__device__ __forceinline__ double pend_token_adjust(const PendRow *pend, long long n_rows, int nlev, long long pair)
+{
+    double a = 0.0;
+    for (int l = 0; l < nlev; ++l) a += pend[l * n_rows + pair].tokadj - pend[l * n_rows + pair].log2N;
+    return a;
 }
 
 // ------------------------------------------------------- row-pair streaming

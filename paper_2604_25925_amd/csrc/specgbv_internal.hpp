@@ -28,7 +28,7 @@ struct Workspace {
     size_t mcount;     // int32  [B]  L - tau - 1 rows of the next iteration to modify (0 when tau >= L - 1)
     size_t counter;    // int32  [B]  final-token workgroups that have stored their partial sums; zeroed by the
                        //             streaming kernels of every call
-    size_t pend;       // PendRow [B*K*L]  rows under a pending modification (written only by calls that carry one)
+    size_t pend;       // PendRow [kMaxPend][B*K*L]  rows under pending modifications (written only by calls that carry some)
     size_t total;
     int nseg;
 };
@@ -52,9 +52,13 @@ struct Problem {
     char *ws;
     Workspace lay;
     hipStream_t stream;
-    // pending modification of the first pend_count[b] rows of every draft (both null: none)
-    const double *pend_carry;      // [batch] ln of the block ratio Algorithm 2 starts from
-    const int32_t *pend_count;     // [batch]
+    // pending modifications, innermost first: level l changes the first pend_count[l][b] rows of every draft
+    int pend_levels;               // 0: none
+    const double *pend_carry;      // [pend_levels][batch] ln of the block ratio Algorithm 2 starts from
+    const int32_t *pend_count;     // [pend_levels][batch]
+    // when not null: the state the call updates in place (kMaxPend levels: carried ratios, then counts)
+    double *state_carry;           // [kMaxPend][batch]
+    int32_t *state_count;          // [kMaxPend][batch]
 };
 
 // Schedule "split": statistics kernel, then a second pass for the sums of Eq. (hik).

@@ -66,15 +66,18 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
     }
 }
 
+// One level of pending modification (the levels below it are done: their PendRow entries are read).
 // grid.x = batch * K * L row pairs, row index slowest: the live workgroups (rows below the prefix's
-// count) are then consecutive and spread over all dies, whatever L is; the others leave at once
+// count) are then consecutive and spread over all dies, whatever L is; the others leave at once.
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kStatThreads)
 k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
-            const double *__restrict__ pend_carry, const int32_t *__restrict__ pend_count,
-            const RowStat *__restrict__ stats, PendRow *__restrict__ pend)
+            const double *__restrict__ carry_l, const int32_t *__restrict__ count_l,
+            const RowStat *__restrict__ stats, PendRow *pend, long long n_rows, int level)
 {
     __shared__ double sh_d[kStatThreads / kWave];
+    __shared__ PendTable sh_tab;
+    __shared__ double sh_log2mu, sh_sumN;
     const long long nbk = gridDim.x / L;
     const int r = static_cast<int>(blockIdx.x / nbk);
     const long long bk = blockIdx.x % nbk;
@@ -82,91 +85,119 @@ k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, in
     const int b = static_cast<int>(bk / K);
     PendRow out;
     out.log2mu = 0.0; out.log2N = 0.0; out.tokadj = 0.0; out.flag = 0; out.pad = 0;
-    if (r >= pend_count[b]) {                     // uniform over the workgroup
-        if (threadIdx.x == 0) pend[pair] = out;
+    if (r >= count_l[b]) {                        // uniform over the workgroup
+        if (threadIdx.x == 0) pend[level * n_rows + pair] = out;
         return;
     }
-    // block ratio in front of row r: the carried one continued with the ORIGINAL target probabilities
-    double log2mu = pend_carry[b] * 1.44269504088896340736;
-    for (int j = 0; j < r; ++j) {
-        const RowStat a = stats[bk * L + j];
-        log2mu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
-    }
     const RowStat st = stats[pair];
+    if (threadIdx.x == 0) {
+        // block ratio in front of row r: the carried one continued along the drafted tokens with the
+        // distribution this level modifies (the target rows as modified by the levels below)
+        double log2mu = carry_l[b] * 1.44269504088896340736;
+        for (int j = 0; j < r; ++j) {
+            const RowStat a = stats[bk * L + j];
+            log2mu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p) + pend_token_adjust(pend, n_rows, level, bk * L + j);
+        }
+        sh_log2mu = log2mu;
+        sh_sumN = pend_build_table(pend, n_rows, level, pair, st.lse2_p - st.lse2_q, sh_tab);
+    }
+    __syncthreads();
+    const double log2mu = sh_log2mu, sumN = sh_sumN;
     const float shift_q = static_cast<float>(st.lse2_q);
-    const RatioConst rc(st.lse2_p - st.lse2_q + log2mu);
+    const RatioConst rc(st.lse2_p - st.lse2_q + log2mu - sumN);
     const T *rq = target + (bk * (L + 1) + r) * static_cast<long long>(V);
     const T *rp = draft + pair * static_cast<long long>(V);
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
     float acc = 0.0f;
-    for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
-        float wq[N], w[N];
-        ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
+    if (sh_tab.n == 0) {
+        for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+            float wq[N], w[N];
+            ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
 #pragma unroll
-        for (int j = 0; j < N; ++j) acc += w[j];
-    });
+            for (int j = 0; j < N; ++j) acc += w[j];
+        });
+    } else {
+        for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+            float wq[N], w[N];
+            pending_weights(zq, zp, c, shift_q, sh_tab, rc, K, wq, w);
+#pragma unroll
+            for (int j = 0; j < N; ++j) acc += w[j];
+        });
+    }
     const double S = block_sum(static_cast<double>(acc), sh_d);           // relative to 2^shift_q
     if (threadIdx.x == 0) {
-        const double W = S * exp2(static_cast<double>(shift_q) - st.lse2_q);
+        const double W = S * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);   // mass of q^(level) t^K
         out.log2mu = log2mu;
-        if (W > 0.0) {                            // otherwise every weight is zero and the row stays q
+        if (W > 0.0) {                            // otherwise every weight is zero and the row stays q^(level)
             out.flag = 1;
             out.log2N = log2(W);
-            const double ratio = exp2((st.tok2_p - st.lse2_p) - (st.tok2_q - st.lse2_q) - log2mu);
+            const double tq_eff = (st.tok2_q - st.lse2_q) + pend_token_adjust(pend, n_rows, level, pair);
+            const double ratio = exp2((st.tok2_p - st.lse2_p) - tq_eff - log2mu);
             const double t = 1.0 - ratio;
             out.tokadj = t > 0.0 ? static_cast<double>(K) * log2(t) : -INFINITY;
         }
-        pend[pair] = out;
+        pend[level * n_rows + pair] = out;
     }
 }
 
 template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kStatThreads)
 k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
-         const RowStat *__restrict__ stats, const PendRow *__restrict__ pend, double *__restrict__ s_out)
+         const RowStat *__restrict__ stats, const PendRow *__restrict__ pend, long long n_rows, int nlev,
+         double *__restrict__ s_out)
 {
     __shared__ double sh_d[kStatThreads / kWave];
+    __shared__ PendTable sh_tab;
+    __shared__ double sh_log2nu, sh_sumN;
     const long long idx = blockIdx.x;             // bk*(L-1) + (i-1)
     const int i = static_cast<int>(idx % (L - 1)) + 1;
     const long long bk = idx / (L - 1);
-    // block likelihood ratio of the length-i block, from the rows before row i
-    double log2nu = 0.0;
-    for (int j = 0; j < i; ++j) {
-        const RowStat st = stats[bk * L + j];
-        log2nu += (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);
-        if (PEND) log2nu += pend[bk * L + j].tokadj - pend[bk * L + j].log2N;
-    }
     const RowStat st = stats[bk * L + i];
+    // block likelihood ratio of the length-i block, from the rows before row i (their token
+    // probabilities under the modified rows where levels are pending)
+    double log2nu = 0.0, sumN = 0.0;
+    if (PEND) {
+        if (threadIdx.x == 0) {
+            double l2 = 0.0;
+            for (int j = 0; j < i; ++j) {
+                const RowStat a = stats[bk * L + j];
+                l2 += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p) + pend_token_adjust(pend, n_rows, nlev, bk * L + j);
+            }
+            sh_log2nu = l2;
+            sh_sumN = pend_build_table(pend, n_rows, nlev, bk * L + i, st.lse2_p - st.lse2_q, sh_tab);
+        }
+        __syncthreads();
+        log2nu = sh_log2nu; sumN = sh_sumN;
+    } else {
+        for (int j = 0; j < i; ++j) {
+            const RowStat a = stats[bk * L + j];
+            log2nu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
+        }
+    }
     const float shift_q = static_cast<float>(st.lse2_q);
     const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
     const T *rp = draft + (bk * L + i) * static_cast<long long>(V);
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
+    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu - sumN);
     float acc = 0.0f;
-    if (PEND && pend[bk * L + i].flag) {          // uniform over the workgroup
-        const PendRow pr = pend[bk * L + i];
-        const RatioConst rc1(st.lse2_p - st.lse2_q + pr.log2mu);
-        const RatioConst rc2(st.lse2_p - st.lse2_q + log2nu - pr.log2N);
+    if (PEND && sh_tab.n > 0) {                   // uniform over the workgroup
         for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
             float wq[N], w[N];
-            pending_weights(zq, zp, c, shift_q, rc1, rc2, K, wq, w);
+            pending_weights(zq, zp, c, shift_q, sh_tab, rc, K, wq, w);
 #pragma unroll
             for (int j = 0; j < N; ++j) acc += w[j];
         });
-        const double total = block_sum(static_cast<double>(acc), sh_d);
-        if (threadIdx.x == 0)
-            s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - pr.log2N);
-        return;
-    }
-    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu);
-    for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
-        float wq[N], w[N];
-        ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
+    } else {
+        for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+            float wq[N], w[N];
+            ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
 #pragma unroll
-        for (int j = 0; j < N; ++j) acc += w[j];
-    });
+            for (int j = 0; j < N; ++j) acc += w[j];
+        });
+    }
     const double total = block_sum(static_cast<double>(acc), sh_d);
     if (threadIdx.x == 0)
-        s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q);
+        s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
 }
 
 template <typename T>
@@ -191,14 +222,16 @@ hipError_t launch_typed(const Problem &p)
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     PendRow *pend = reinterpret_cast<PendRow *>(p.ws + p.lay.pend);
-    if (p.pend_carry) {
+    for (int level = 0; level < p.pend_levels; ++level) {
         const dim3 gp(static_cast<unsigned>(pairs));
+        const double *carry_l = p.pend_carry + static_cast<size_t>(level) * p.batch;
+        const int32_t *count_l = p.pend_count + static_cast<size_t>(level) * p.batch;
         if (vec)
             hipLaunchKernelGGL((k_pend_norm<T, true>), gp, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L,
-                               p.V, p.c, p.pend_carry, p.pend_count, stats, pend);
+                               p.V, p.c, carry_l, count_l, stats, pend, pairs, level);
         else
             hipLaunchKernelGGL((k_pend_norm<T, false>), gp, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L,
-                               p.V, p.c, p.pend_carry, p.pend_count, stats, pend);
+                               p.V, p.c, carry_l, count_l, stats, pend, pairs, level);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -207,8 +240,8 @@ hipError_t launch_typed(const Problem &p)
     const dim3 g2(static_cast<unsigned>(rows));
 #define SPECGBV_OT_LAUNCH(VEC, PEND)                                                                           \
     hipLaunchKernelGGL((k_ot_sum<T, VEC, PEND>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L, \
-                       p.V, p.c, stats, pend, s)
-    if (p.pend_carry) { if (vec) SPECGBV_OT_LAUNCH(true, true); else SPECGBV_OT_LAUNCH(false, true); }
+                       p.V, p.c, stats, pend, pairs, p.pend_levels, s)
+    if (p.pend_levels > 0) { if (vec) SPECGBV_OT_LAUNCH(true, true); else SPECGBV_OT_LAUNCH(false, true); }
     else { if (vec) SPECGBV_OT_LAUNCH(true, false); else SPECGBV_OT_LAUNCH(false, false); }
 #undef SPECGBV_OT_LAUNCH
     return hipGetLastError();

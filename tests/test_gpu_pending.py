@@ -32,70 +32,100 @@ def _as_f64(raw):
     return raw.astype(np.float64)
 
 
+def _levels(carry, count):
+    carry, count = np.asarray(carry, np.float64), np.asarray(count, np.int32)
+    return (carry[None], count[None]) if carry.ndim == 1 else (carry, count)
+
+
 def oracle_pending(t, d, tok, T, seed, offset, carry, count, prefix_ids=None):
-    """Algorithm 2, then Algorithm 1 on its rows (both the oracle's), without any rounding in between."""
+    """Algorithm 2 level by level (innermost first), then Algorithm 1 on its rows (all the oracle's),
+    without any rounding in between.  Returns the verification's outputs and, per level, what
+    oracle.modify returned plus the rows it modified as log-probabilities."""
+    carry, count = _levels(carry, count)
     B, K, L1, V = t.shape
     L = L1 - 1
-    mod = oracle.modify(np.ascontiguousarray(t[:, :, :L]), d, tok, T, carry, count)
     Tf = float(np.float32(T))                           # the oracle widens the float32 temperature
-    tq = np.empty((B, K, L + 1, V), np.float64)
-    tq[:, :, :L] = mod["logq"]
-    tq[:, :, L] = _as_f64(t[:, :, L]) / Tf              # bonus row: plain logits over T, used at temperature 1
     dq = _as_f64(d) / Tf
-    return oracle.verify(tq, dq, tok, 1.0, seed, offset, debug=True, nthreads=8, prefix_ids=prefix_ids), mod
+    lnp = np.empty((B, K, L, V), np.float64)
+    lnq = np.empty((B, K, L, V), np.float64)
+    for b in range(B):
+        for k in range(K):
+            for r in range(L):
+                lnp[b, k, r] = oracle.log_softmax(dq[b, k, r], 1.0)[0]
+                lnq[b, k, r] = oracle.log_softmax(_as_f64(t[b, k, r]), Tf)[0]
+    mods = []
+    cur = lnq
+    for l in range(carry.shape[0]):
+        if l == 0:
+            mod = oracle.modify(np.ascontiguousarray(t[:, :, :L]), d, tok, T, carry[l], count[l])
+        else:
+            mod = oracle.modify(cur, dq, tok, 1.0, carry[l], count[l])
+        mod["lnq_in"] = cur
+        mods.append(mod)
+        cur = mod["logq"]
+    tq = np.empty((B, K, L + 1, V), np.float64)
+    tq[:, :, :L] = cur
+    tq[:, :, L] = _as_f64(t[:, :, L]) / Tf              # bonus row: plain logits over T, used at temperature 1
+    ora = oracle.verify(tq, dq, tok, 1.0, seed, offset, debug=True, nthreads=8, prefix_ids=prefix_ids)
+    return ora, mods, lnp
 
 
 EPS_R = 1e-6
 
 
-def conditioning(t, d, tok, T, carry, count, mod, ora):
-    """(nu_extra [B, K, L], carry_extra [B], undecided [B]) from the oracle's float64 values: the error
-    K EPS_R r / (1 - r) of ln q'[token] accumulated along each block, the same for the final token,
-    and the prefixes with a drafted token whose r is within 4 EPS_R of 1."""
-    B, K, L = tok.shape
-    Tf = float(np.float32(T))
+def conditioning(tok, K, carry, count, mods, lnp, ora):
+    """(nu_extra [B, K, L], carry_extra [B], undecided [B]) from the oracle's float64 values.  A level
+    multiplies a token's probability by t^K / N, t = 1 - r, r = p / (mu q): a relative error e on r
+    (EPS_R of the float32 evaluation, plus the errors the token probability and the block ratio
+    already carry from the levels and rows before) becomes K e r / (1 - r) on the logarithm.  The
+    bounds are accumulated over levels and along each block; a prefix with a drafted token within
+    4 EPS_R of r = 1 at some level (even the sign of t is undecided there) is reported separately."""
+    carry, count = _levels(carry, count)
+    B, _, L = tok.shape
     nu_extra = np.zeros((B, K, L))
     carry_extra = np.zeros(B)
     undecided = np.zeros(B, bool)
-
-    def token_term(b, k, j, x, ln_mu):
-        lq, _ = oracle.log_softmax(_as_f64(t[b, k, j]), Tf)
-        lp, _ = oracle.log_softmax(_as_f64(d[b, k, j]), Tf)
-        r = np.exp(lp[x] - lq[x] - ln_mu)
-        return lq[x] - lp[x], r
-
     for b in range(B):
-        for k in range(K):
-            ln_mu, acc = float(carry[b]), 0.0
-            for j in range(min(int(count[b]), L)):
-                step, r = token_term(b, k, j, int(tok[b, k, j]), ln_mu)
-                if not mod["fallback"][b, k, j]:
-                    if abs(1.0 - r) < 4 * EPS_R * r:
-                        undecided[b] = True
-                    elif r < 1.0:
-                        acc += K * EPS_R * r / (1.0 - r)
-                nu_extra[b, k, j:] = acc
-                ln_mu += step
         tau, kf = int(ora["accepted_len"][b]), max(int(ora["accepted_draft_idx"][b]), 0)
-        if tau < min(int(count[b]), L) and not mod["fallback"][b, kf, tau]:
-            ln_mu = float(carry[b])
-            for j in range(tau):
-                ln_mu += token_term(b, kf, j, int(tok[b, kf, j]), ln_mu)[0]
-            r = token_term(b, kf, tau, int(ora["out_tokens"][b, tau]), ln_mu)[1]
-            carry_extra[b] = K * EPS_R * r / (1.0 - r) if r < 1.0 else 0.0
+        for k in range(K):
+            e_tok = np.zeros(L)                          # error bound of ln q^(l)[token] per row, level by level
+            e_y = 0.0                                    # the same for the final token (row tau of draft kf)
+            for l, mod in enumerate(mods):
+                ln_mu, e_mu = float(carry[l, b]), 0.0
+                for j in range(min(int(count[l, b]), L)):
+                    x = int(tok[b, k, j])
+                    lq, lp = mod["lnq_in"][b, k, j], lnp[b, k, j]
+                    if not mod["fallback"][b, k, j]:
+                        if k == kf and j == tau and tau < L:
+                            y = int(ora["out_tokens"][b, tau])
+                            ry = np.exp(lp[y] - lq[y] - ln_mu)
+                            if ry < 1.0:
+                                e_y += K * (EPS_R + e_y + e_mu) * ry / (1.0 - ry)
+                        r = np.exp(lp[x] - lq[x] - ln_mu)
+                        if abs(1.0 - r) < 4 * (EPS_R + e_tok[j] + e_mu) * r:
+                            undecided[b] = True
+                        elif r < 1.0:
+                            e_tok[j] += K * (EPS_R + e_tok[j] + e_mu) * r / (1.0 - r)
+                    e_mu += e_tok[j] if l > 0 else 0.0
+                    ln_mu += lq[x] - lp[x]
+            nu_extra[b, k] = np.cumsum(e_tok)
+            if k == kf:
+                carry_extra[b] = e_y
     return nu_extra, carry_extra, undecided
 
 
 def check_pending(t, d, tok, T, seed, offset, carry, count, label, gpu_slice=None):
-    gpu = run_gpu(t, d, tok, T, seed, offset, pending=(carry, count))
+    carry, count = _levels(carry, count)
+    pend = (carry[0], count[0]) if carry.shape[0] == 1 else (carry, count)
+    gpu = run_gpu(t, d, tok, T, seed, offset, pending=pend)
     if gpu_slice is not None:
         idx = np.asarray(gpu_slice)
-        t, d, tok, carry, count = t[idx], d[idx], tok[idx], carry[idx], count[idx]
-        ora, mod = oracle_pending(t, d, tok, T, seed, offset, carry, count, prefix_ids=idx.astype(np.int32))
+        t, d, tok, carry, count = t[idx], d[idx], tok[idx], carry[:, idx], count[:, idx]
+        ora, mods, lnp = oracle_pending(t, d, tok, T, seed, offset, carry, count, prefix_ids=idx.astype(np.int32))
         gpu = {k: v[idx] for k, v in gpu.items()}
     else:
-        ora, mod = oracle_pending(t, d, tok, T, seed, offset, carry, count)
-    nu_extra, carry_extra, undecided = conditioning(t, d, tok, T, carry, count, mod, ora)
+        ora, mods, lnp = oracle_pending(t, d, tok, T, seed, offset, carry, count)
+    nu_extra, carry_extra, undecided = conditioning(tok, t.shape[1], carry, count, mods, lnp, ora)
     keep = ~undecided
     rep = compare({k: v[keep] for k, v in gpu.items()}, {k: v[keep] for k, v in ora.items()}, tok[keep], label=label,
                   skip=("lse_q",), nu_extra=nu_extra[keep], carry_extra=carry_extra[keep])
@@ -103,7 +133,7 @@ def check_pending(t, d, tok, T, seed, offset, carry, count, label, gpu_slice=Non
     rep["max_nu_extra"] = float(nu_extra[keep].max()) if keep.any() else 0.0
     assert undecided.sum() <= 1
     print("[parity] %s: %s" % (label, rep), flush=True)
-    return rep, gpu, ora, mod
+    return rep, gpu, ora, mods[-1] if len(mods) == 1 else mods
 
 
 @pytest.mark.parametrize("B,K,L,V,dtype,T", [
@@ -160,6 +190,35 @@ def test_pending_cfg4_rows():
     carry = np.array([0.3, -0.4, 0.0, 1.1])
     count = np.array([3, 7, 1, 5], np.int32)
     rep, gpu, ora, mod = check_pending(t, d, tok, w.temperature, 3, 2, carry, count, "pending cfg4 rows", gpu_slice=[1, 3])
+    assert rep["decision_mismatches"] == 0
+
+
+@pytest.mark.parametrize("B,K,L,V,dtype,T,levels", [
+    (12, 3, 5, 2048, "f32", 1.0, 2),
+    (8, 4, 6, 8192, "bf16", 0.8, 3),
+    (6, 2, 8, 1003, "f32", 0.7, 8),        # as many levels as the library takes, scalar-load path
+])
+def test_several_pending_levels_match_oracle(B, K, L, V, dtype, T, levels):
+    """Modifications on top of each other (Algorithm 3 updates q in place): level l is Algorithm 2
+    applied to the rows as level l - 1 left them."""
+    w = Workload("pendl", B, K, L, V, dtype, 2.5, 0.8, head=20, temperature=T)
+    t, d, tok = make_inputs(w, seed=71)
+    rng = np.random.default_rng(11)
+    carry = rng.normal(2.0, 0.8, (levels, B))
+    count = rng.integers(0, L, (levels, B)).astype(np.int32)
+    count[:, 0] = 0
+    rep, gpu, ora, mods = check_pending(t, d, tok, T, 6, 4, carry, count, "pending %d levels %s V=%d K=%d L=%d" % (levels, dtype, V, K, L))
+    assert rep["decision_mismatches"] <= 1 and rep["token_mismatches"] <= 1
+    assert sum(int((m["norm"] < 1.0).any()) for m in mods) >= 2          # at least two levels really modify rows
+    assert (ora["accepted_len"] > 0).any()
+
+
+def test_two_pending_levels_cfg4_rows():
+    w = with_batch(WORKLOADS["cfg4"], 3)
+    t, d, tok = make_inputs(w, seed=72)
+    carry = np.array([[0.8, 1.5, 0.2], [1.9, 0.4, 2.5]])
+    count = np.array([[2, 6, 0], [5, 3, 7]], np.int32)
+    rep, gpu, ora, mods = check_pending(t, d, tok, w.temperature, 3, 2, carry, count, "pending 2 levels cfg4 rows", gpu_slice=[0, 1])
     assert rep["decision_mismatches"] == 0
 
 
