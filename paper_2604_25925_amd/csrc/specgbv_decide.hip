@@ -376,7 +376,114 @@ struct FinalOut {
     int32_t *fallback;
     double *carry;
     int32_t *mcount;
+    double *state_carry;         // pending state updated in place ([kMaxPend][batch] each), or null
+    int32_t *state_count;
 };
+
+// A double of lane `src` (wave-uniform) in every lane.
+__device__ __forceinline__ double lane_value(double v, int src)
+{
+    const long long bits = __double_as_longlong(v);
+    const unsigned lo = __builtin_amdgcn_readlane(static_cast<int>(bits), src);
+    const unsigned hi = __builtin_amdgcn_readlane(static_cast<int>(bits >> 32), src);
+    return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
+}
+
+// Sum over aligned groups of 8 lanes (every lane of a group gets its group's sum).
+__device__ __forceinline__ double group8_sum(double v)
+{
+    v += __shfl_xor(v, 1);
+    v += __shfl_xor(v, 2);
+    v += __shfl_xor(v, 4);
+    return v;
+}
+
+// Algorithm 3's bookkeeping for prefix b after its final token is known, by the whole first wave of
+// the locating workgroup: every pending level's block ratio is continued along the tokens this
+// iteration emitted (draft f's tokens 0 .. tau-1, then the final token y), with the token
+// probabilities under the distribution THAT level modifies (the target rows as the levels below it
+// left them); its row count shrinks by tau + 1; used-up levels are dropped, the others move down,
+// and the modification this iteration creates (carry_new, count_new) is appended.  Lane 8 m + j
+// looks after level m and row j (at most kMaxPend levels; a surviving level has tau + 1 < count <= L - 1,
+// so only rows j <= tau <= 6 matter).
+template <typename T>
+__device__ __forceinline__ void update_pending_state(const T *target, const T *draft, const DecideIO &io, const FinalOut &fo,
+                                                     const Selection &sl, int b, int K, int L, int V, float c, int winner,
+                                                     int tokid_w, double carry_w, int mcount_w)
+{
+    constexpr double kLn2 = 0.693147180559945309417;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int m = lane >> 3, j = lane & 7;
+    const int nlev = io.nlev, tau = sl.tau;
+    const int batch = static_cast<int>(gridDim.y);
+    const int tokid = __builtin_amdgcn_readlane(tokid_w, winner);
+    const int count_new = __builtin_amdgcn_readlane(mcount_w, winner);
+    const double carry_new = lane_value(carry_w, winner);
+    // old state of level m (read by every lane of its group before anything is written)
+    int count_m = 0;
+    double carry_m = 0.0;
+    if (m < nlev) { count_m = fo.state_count[static_cast<size_t>(m) * batch + b]; carry_m = fo.state_carry[static_cast<size_t>(m) * batch + b]; }
+    double val = 0.0;            // what level m does to the log2 probability of the token emitted at row j
+    double base = 0.0;           // group 0: log2 q_j[e_j] - log2 p_j[e_j] under the unmodified rows
+    const bool some_may_survive = tau + 2 <= L - 1 && tau < 7;   // a level survives only if tau + 1 < count <= L - 1
+    if (some_may_survive) {      // uniform; otherwise (in particular after a whole accepted block) every level ends
+        const int kf = static_cast<int>(sl.draft_row / L - static_cast<long long>(b) * K);
+        const long long row0 = (static_cast<long long>(b) * K + kf) * L;
+        PendRow pr;
+        pr.log2mu = 0.0; pr.log2N = 0.0; pr.tokadj = 0.0; pr.flag = 0; pr.pad = 0;
+        if (m < nlev && j <= tau) pr = io.pend[m * io.n_rows + row0 + j];
+        RowStat st;
+        st.lse2_q = 0.0; st.lse2_p = 0.0; st.tok2_q = 0.0; st.tok2_p = 0.0;
+        if (j <= tau) st = io.stats[row0 + j];
+        const double zq_y = static_cast<double>(Elem<T>::scalar(target + sl.target_row * V + tokid)) * static_cast<double>(c);
+        const double zp_y = static_cast<double>(Elem<T>::scalar(draft + sl.draft_row * V + tokid)) * static_cast<double>(c);
+        if (j < tau) { base = (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p); val = pr.tokadj - pr.log2N; }
+        const double lse_q_tau = lane_value(st.lse2_q, tau), lse_p_tau = lane_value(st.lse2_p, tau);   // lane tau: m = 0, j = tau
+        const double by = (zq_y - lse_q_tau) - (zp_y - lse_p_tau);
+        if (j == tau) base = by;
+        // the levels' factors at the final token, one level after the other (wave-uniform loop)
+        double log2T = 0.0, sumN = 0.0;
+        for (int l = 0; l < nlev; ++l) {
+            const int src = l * 8 + tau;
+            const int flag = __builtin_amdgcn_readlane(pr.flag, src);
+            if (!flag) continue;
+            const double log2mu = lane_value(pr.log2mu, src), log2N = lane_value(pr.log2N, src);
+            const double t = 1.0 - exp2_small(-by - log2mu + sumN - log2T);        // 1 - p[y] / (mu_l q^(l)[y])
+            const double adj = t > 0.0 ? static_cast<double>(K) * log2(t) : -INFINITY;
+            if (lane == src) val = adj - log2N;
+            log2T += adj;
+            sumN += log2N;
+        }
+    }
+    const double S = group8_sum(m < nlev ? val : 0.0);       // level m: sum over the emitted rows
+    const double B = lane_value(group8_sum(base), 0);        // unmodified rows (group 0 holds the terms)
+    // levels in order: the ratio of level l moves by B plus what the levels below it contribute
+    double run = B;
+    int pos = 0;
+    for (int l = 0; l < nlev; ++l) {
+        const int cnt = __builtin_amdgcn_readlane(count_m, l * 8);
+        const double car = lane_value(carry_m, l * 8);
+        if (some_may_survive && cnt > tau + 1) {
+            if (lane == 0) {
+                fo.state_carry[static_cast<size_t>(pos) * batch + b] = car + run * kLn2;
+                fo.state_count[static_cast<size_t>(pos) * batch + b] = cnt - (tau + 1);
+            }
+            ++pos;
+        }
+        run += lane_value(S, l * 8);
+    }
+    if (count_new > 0 && pos < kMaxPend) {
+        if (lane == 0) {
+            fo.state_carry[static_cast<size_t>(pos) * batch + b] = carry_new;
+            fo.state_count[static_cast<size_t>(pos) * batch + b] = count_new;
+        }
+        ++pos;
+    }
+    if (lane >= pos && lane < kMaxPend) {
+        fo.state_carry[static_cast<size_t>(lane) * batch + b] = 0.0;
+        fo.state_count[static_cast<size_t>(lane) * batch + b] = 0;
+    }
+}
 
 template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kSegThreads)
@@ -564,6 +671,8 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     if (cross) winner = __ffsll(static_cast<long long>(cross)) - 1;
     else if (pos) winner = 63 - __clzll(static_cast<long long>(pos));
     else winner = 0;
+    int tokid_w = 0, mcount_w = 0;               // the winner lane's results, for the state update below
+    double carry_w = 0.0;
     if (lane == winner) {
         const long long e0 = static_cast<long long>(seg) * kSegElems + lane * 8;
         double run = excl;
@@ -610,7 +719,9 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
         }
         carry_out[b] = carry;
         mcount_out[b] = sl.draft_row < 0 ? 0 : L - sl.tau - 1;
+        tokid_w = static_cast<int>(tokid); carry_w = carry; mcount_w = sl.draft_row < 0 ? 0 : L - sl.tau - 1;
     }
+    if (PEND && fo.state_carry) update_pending_state<T>(target, draft, io, fo, sl, b, K, L, V, c, winner, tokid_w, carry_w, mcount_w);
 }
 
 template <typename T>
@@ -646,6 +757,7 @@ hipError_t launch_final_typed(const Problem &p)
     fo.fallback = reinterpret_cast<int32_t *>(p.ws + p.lay.fallback);
     fo.carry = reinterpret_cast<double *>(p.ws + p.lay.carry);
     fo.mcount = reinterpret_cast<int32_t *>(p.ws + p.lay.mcount);
+    fo.state_carry = p.state_carry; fo.state_count = p.state_count;
     const int KL = p.K * p.L;
     const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
 #define SPECGBV_FINAL_LAUNCH(VEC, PEND)                                                                              \

@@ -25,7 +25,8 @@ def _markov_tables(rng, V):
 
 
 @pytest.mark.parametrize("V,K,L,fused", [(3, 1, 2, False), (3, 1, 3, False), (3, 1, 4, False), (2, 2, 2, False),
-                                           (2, 2, 3, False), (3, 1, 3, True), (3, 1, 4, True), (2, 2, 3, True)])
+                                           (2, 2, 3, False), (3, 1, 3, True), (3, 1, 4, True), (2, 2, 3, True),
+                                           (3, 1, 3, "state"), (3, 1, 4, "state"), (3, 1, 5, "state"), (2, 2, 3, "state")])
 def test_three_iterations_decode_the_exact_law(V, K, L, fused):
     """Algorithm 3 updates q in place ("q <- DistributionModification(q, ...)"), so a modification
     made after one iteration is still in force for its remaining positions when the next iteration
@@ -35,7 +36,9 @@ def test_three_iterations_decode_the_exact_law(V, K, L, fused):
     specgbv_carry_advance) and its remaining row count, and the rows handed to the verification are
     obtained by applying them one after the other with specgbv_modify_target.  With fused = True the
     outermost pending modification is not written out: the verification applies it on the fly
-    (the pending option of specgbv_verify_ex)."""
+    (the pending option of specgbv_verify_ex).  With fused = "state" the library does all of it: the
+    loop only hands the same pending_state buffer to every verification (no specgbv_modify_target,
+    no specgbv_carry_advance, no q_new tensor)."""
     import torch
     import paper_2604_25925_amd as sg
     rng = np.random.default_rng(100 + L + 10 * K)
@@ -50,6 +53,7 @@ def test_three_iterations_decode_the_exact_law(V, K, L, fused):
 
     text = [() for _ in range(n)]                       # decoded tokens per prefix
     pending = []                                        # [(carry [n] float64, count [n] int32)] on the GPU, innermost first
+    state = torch.zeros(sg.specgbv_pending_state_bytes(n), dtype=torch.uint8, device=dev) if fused == "state" else None
     for it in range(iters):
         # ---- drafting: K i.i.d. blocks per prefix, one position at a time
         blocks = [[text[i] for _ in range(K)] for i in range(n)]
@@ -71,6 +75,12 @@ def test_three_iterations_decode_the_exact_law(V, K, L, fused):
         tk = torch.from_numpy(tokens).to(dev)
         # ---- the pending modifications, innermost first; level_rows[l] is what level l modifies
         # (the tables hold normalised probabilities, so their logits are log-probabilities at T = 1)
+        if state is not None:
+            acc, f, out, ws = sg.specgbv_verify_ex(tl, dl, tk, 1.0, 1234, it, pending_state=state)
+            torch.cuda.synchronize()
+            tau, out_h = acc.cpu().numpy(), out.cpu().numpy()
+            text = [text[i] + tuple(int(v) for v in out_h[i, :tau[i] + 1]) for i in range(n)]
+            continue
         level_rows = [tl]
         cur = tl
         on_the_fly = pending[-1] if (fused and pending) else None

@@ -222,6 +222,76 @@ def test_two_pending_levels_cfg4_rows():
     assert rep["decision_mismatches"] == 0
 
 
+def _state_tensor(carry, count, B):
+    """The pending_state buffer of the C ABI for the given levels (level-major, 8 slots per prefix)."""
+    import torch
+    import paper_2604_25925_amd as sg
+    buf = np.zeros(sg.specgbv_pending_state_bytes(B), np.uint8)
+    c = buf[:8 * B * 8].view(np.float64).reshape(8, B)
+    n = buf[8 * B * 8:8 * B * 12].view(np.int32).reshape(8, B)
+    c[:carry.shape[0]] = carry
+    n[:count.shape[0]] = count
+    return torch.from_numpy(buf).cuda()
+
+
+def _read_state(state, B):
+    buf = state.cpu().numpy()
+    return buf[:8 * B * 8].view(np.float64).reshape(8, B).copy(), buf[8 * B * 8:8 * B * 12].view(np.int32).reshape(8, B).copy()
+
+
+@pytest.mark.parametrize("B,K,L,V,dtype,T", [(24, 3, 6, 2048, "f32", 1.0), (16, 2, 8, 8192, "bf16", 0.8), (12, 4, 9, 515, "f32", 0.9)])
+def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype, T):
+    """The in-place state (pending_state) after one call: every level advanced along the emitted tokens
+    with the oracle's carry_advance on the rows that level modifies, used-up levels dropped, the new
+    modification appended; and the call's outputs equal those of the same levels passed read-only."""
+    import torch
+    import paper_2604_25925_amd as sg
+    from parity_util import to_torch
+    w = Workload("pends", B, K, L, V, dtype, 2.5, 0.8, head=20, temperature=T)
+    t, d, tok = make_inputs(w, seed=81)
+    rng = np.random.default_rng(13)
+    nlev = 3
+    carry = rng.normal(2.0, 0.8, (nlev, B))
+    count = np.sort(rng.integers(1, L, (nlev, B)).astype(np.int32), axis=0)      # alive levels, none empty
+    count[:, 0] = 0                                                              # one prefix with nothing pending
+    count[1:, 1] = 0                                                             # one with a single level
+    state = _state_tensor(carry, count, B)
+    tl, dl, tk = to_torch(t), to_torch(d), to_torch(tok)
+    acc, f, out, ws = sg.specgbv_verify_ex(tl, dl, tk, T, 8, 5, pending_state=state)
+    torch.cuda.synchronize()
+    ro = run_gpu(t, d, tok, T, 8, 5, pending=(carry, count))
+    acc, f, out = acc.cpu().numpy(), f.cpu().numpy(), out.cpu().numpy()
+    assert np.array_equal(acc, ro["accepted_len"]) and np.array_equal(f, ro["accepted_draft_idx"]) and np.array_equal(out, ro["out_tokens"])
+    new_carry, new_count = _read_state(state, B)
+    # expected bookkeeping, level by level, on the rows each level modifies (float64, from the oracle)
+    ora, mods, lnp = oracle_pending(t, d, tok, T, 8, 5, carry, count)
+    Tf = float(np.float32(T))
+    want_c, want_n = np.zeros((8, B)), np.zeros((8, B), np.int32)
+    fill = np.zeros(B, int)
+    for l, mod in enumerate(mods):
+        rows_q = np.ascontiguousarray(mod["lnq_in"])
+        c_adv, n_adv = oracle.carry_advance(rows_q, _as_f64(d) / Tf, tok, acc, f, out, 1.0, carry[l].copy(), count[l].copy())
+        for b in range(B):
+            if n_adv[b] > 0:
+                want_c[fill[b], b], want_n[fill[b], b] = c_adv[b], n_adv[b]
+                fill[b] += 1
+    for b in range(B):
+        if ro["modify_count"][b] > 0:
+            want_c[fill[b], b], want_n[fill[b], b] = ro["carry_log_nu"][b], ro["modify_count"][b]
+            fill[b] += 1
+    assert np.array_equal(new_count, want_n)
+    assert (want_n[1] > 0).any() and (want_n[2] == 0).any()                      # several levels survive somewhere, levels are dropped somewhere
+    fin = np.isfinite(want_c)
+    assert np.array_equal(new_carry[~fin], want_c[~fin])
+    nu_extra, carry_extra, undecided = conditioning(tok, K, carry, count, mods, lnp, ora)
+    tol = 2e-5 + nu_extra.max(axis=(1, 2)) + carry_extra
+    err = np.abs(new_carry - want_c)
+    err[~fin] = 0.0
+    ok = undecided | (err <= tol[None, :]).all(axis=0)
+    assert ok.all(), "carried ratios differ: worst %.3g (tolerance %.3g)" % (err.max(), tol.min())
+    assert (want_n > 0).sum() > B                                                # the comparison is not vacuous
+
+
 def test_pending_chain_schedule_is_rejected():
     import paper_2604_25925_amd as sg
     import torch
