@@ -143,6 +143,46 @@ def bench_pending(a, w, sg, torch, tl, dl, tk, ws, out):
     }
 
 
+def bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out):
+    """One step = one specgbv_verify_ex call with the pending state: the verification under every distribution
+    modification still pending for each prefix, and Algorithm 3's bookkeeping, all on the device.  The state
+    starts empty and evolves from call to call (the same synthetic tensors stand in for every iteration's
+    drafts, so modifications pile up more than they would behind real models: a pessimistic steady state)."""
+    state = torch.zeros(sg.specgbv_pending_state_bytes(w.batch), dtype=torch.uint8, device=tl.device)
+    for i in range(max(a.warmup, 2 * w.L)):                  # long enough for the number of levels to settle
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, i, workspace=ws, out=out, pending_state=state)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    t0 = time.perf_counter()
+    for i, (e0, e1) in enumerate(evs):
+        e0.record()
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1000 + i, workspace=ws, out=out, pending_state=state)
+        e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+    ker = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    avg = sum(ker) / len(ker)
+    buf = state.cpu().numpy()
+    cnt = buf[8 * w.batch * 8:8 * w.batch * 12].view(np.int32).reshape(8, w.batch)
+    bytes_ = w.batch * w.K * w.L * 2 * w.V * w.elem_bytes     # every (target, draft) row pair once
+    achieved = bytes_ / (avg * 1e-3) / 1e9
+    return {
+        "metric": "decoding iterations/sec: verification under all pending distribution modifications plus Algorithm 3's "
+                  "bookkeeping on the device, and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",
+        "value": w.batch / (ms_per_step * 1e-3), "unit": "verifications/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": max(a.warmup, 2 * w.L), "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: batch %d, K=%d, L=%d, V=%d, %s logits, T=%g" % (
+                       w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
+                   "mean_levels_pending": float((cnt > 0).sum(0).mean()), "max_levels_pending": int((cnt > 0).sum(0).max()),
+                   "mean_rows_modified": float(cnt.max(0).mean()), "schedule": "two-pass"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "k_row_stats + (L-1) x k_pend_norm + k_ot_sum + k_final (whole call)",
+                     "kernel_ms_avg": avg, "kernel_ms_min": ker[0], "algorithmic_bytes_per_launch": bytes_},
+    }
+
+
 def bench_sample(a, w, sg, torch, dl):
     """One step = one specgbv_sample_tokens call: one token for each of the batch * K draft rows of one position."""
     rows = dl[:, :, 0].contiguous().view(w.batch * w.K, w.V)
@@ -184,11 +224,12 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--algo", default="auto", choices=["auto", "split", "chain"])
-    ap.add_argument("--op", default="verify", choices=["verify", "modify", "sample", "pending"],
+    ap.add_argument("--op", default="verify", choices=["verify", "modify", "sample", "pending", "iterate"],
                     help="verify: the verification call (the benchmark); modify: the distribution modification "
                          "(Algorithm 2) for the drafts of the next iteration, on the same tensors; "
                          "sample: the draft-side token draw of one position (Algorithm 3) over the batch * K draft rows; "
-                         "pending: the verification with a pending modification applied on the fly")
+                         "pending: the verification with a pending modification applied on the fly; "
+                         "iterate: the verification with the pending state (all pending modifications and their bookkeeping)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -244,6 +285,9 @@ def main() -> int:
         return 0
     if a.op == "pending":
         print(json.dumps(bench_pending(a, w, sg, torch, tl, dl, tk, ws, out)))
+        return 0
+    if a.op == "iterate":
+        print(json.dumps(bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out)))
         return 0
 
     for i in range(a.warmup):

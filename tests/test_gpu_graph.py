@@ -27,6 +27,14 @@ def test_verify_modify_sample_replay_under_graph_capture():
     carry_ptr, count_ptr = sg.specgbv_workspace_carry(ws, B, K, L, V)
     ws2 = torch.empty_like(ws)
     out2 = tuple(torch.empty_like(t) for t in out)
+    ws3 = torch.empty_like(ws)
+    out3 = tuple(torch.empty_like(t) for t in out)
+    rng = np.random.default_rng(5)
+    state0 = np.zeros(sg.specgbv_pending_state_bytes(B), np.uint8)        # two levels pending for every prefix
+    state0[:8 * B * 8].view(np.float64).reshape(8, B)[:2] = rng.normal(2.0, 0.5, (2, B))
+    state0[8 * B * 8:8 * B * 12].view(np.int32).reshape(8, B)[:2] = [[1] * B, [3] * B]
+    state0 = torch.from_numpy(state0).to(dev)
+    state = torch.empty_like(state0)
     mod = {"logq": torch.empty((B, K, L + 1, V), dtype=torch.float32, device=dev),
            "logp": torch.empty((B, K, L, V), dtype=torch.float32, device=dev),
            "workspace": torch.empty(sg.specgbv_modify_workspace_bytes(B, K, L, 1), dtype=torch.uint8, device=dev)}
@@ -40,10 +48,13 @@ def test_verify_modify_sample_replay_under_graph_capture():
         sg.specgbv_sample_tokens(rows, T, 5, 2, 0, out=stok, workspace=sws)
         # the same modification applied on the fly by a second verification (its own workspace and outputs)
         sg.specgbv_verify_ex(tl, dl, tk, T, 5, 3, workspace=ws2, out=out2, pending=(carry_ptr, count_ptr))
+        # and a verification that reads and updates a pending state (reset first, so that every replay starts alike)
+        state.copy_(state0)
+        sg.specgbv_verify_ex(tl, dl, tk, T, 5, 4, workspace=ws3, out=out3, pending_state=state)
 
     def snapshot():
         torch.cuda.synchronize()
-        return [t.clone() for t in (*out, mod["logq"], mod["logp"], stok, *out2)]
+        return [t.clone() for t in (*out, mod["logq"], mod["logp"], stok, *out2, *out3, state)]
 
     def load(inputs):
         a, b, c = (to_torch(x) for x in inputs)
@@ -68,7 +79,7 @@ def test_verify_modify_sample_replay_under_graph_capture():
         iteration()
     for rep, inputs in enumerate(sets + sets[:1]):
         load(inputs)
-        for t in (*out, stok, *out2):
+        for t in (*out, stok, *out2, *out3):
             t.fill_(-7)                               # eager work between the replays
         torch.cuda.synchronize()
         graph.replay()
