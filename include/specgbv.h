@@ -128,8 +128,9 @@ typedef struct specgbv_options {
      * (specgbv_workspace_carry; the pointers may point into the workspace passed to this call: they
      * are read before the new values are written); several levels arise when an iteration ends
      * before the previous modification's rows are used up (Algorithm 3 updates q in place).
-     * Runs on the two-pass schedule (SPECGBV_ALGO_CHAIN is rejected).  A modified row whose weights
-     * are all zero stays as it was.
+     * SPECGBV_ALGO_AUTO takes the two-pass schedule; SPECGBV_ALGO_CHAIN applies the levels by extra
+     * sweeps over the on-chip row pair (rows that do not fit on chip are rejected), which is faster
+     * while few rows are modified.  A modified row whose weights are all zero stays as it was.
      */
     const double *pending_carry_log_nu;   /* device, [pending_levels][batch] */
     const int32_t *pending_count;         /* device, [pending_levels][batch], values below 0 or above L are clamped */

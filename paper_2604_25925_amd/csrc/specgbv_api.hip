@@ -155,17 +155,18 @@ specgbv_status specgbv_verify_ex(
         p.pend_carry = p.state_carry; p.pend_count = p.state_count;
         p.pend_levels = L - 1;               // at most L - 1 modifications are alive at once; 0 for L = 1
     }
-    if ((p.pend_levels > 0 || p.state_carry) && algo == SPECGBV_ALGO_CHAIN)
-        return fail(SPECGBV_EUNSUPPORTED, "pending modifications run on the two-pass schedule only");
-
+    const bool pending = p.pend_levels > 0;
     bool use_chain = false;
-    if (p.pend_levels > 0 || p.state_carry) {
-        use_chain = false;
-    } else if (algo == SPECGBV_ALGO_CHAIN) {
-        if (!chain_supported(p)) return fail(SPECGBV_EUNSUPPORTED, "the chain schedule does not support this shape");
+    if (algo == SPECGBV_ALGO_CHAIN) {
+        if (!(pending ? chain_supports_pending(p) : chain_supported(p)))
+            return fail(SPECGBV_EUNSUPPORTED, pending ? "the chain schedule with pending modifications needs the whole row pair on chip"
+                                                      : "the chain schedule does not support this shape");
         use_chain = true;
     } else if (algo == SPECGBV_ALGO_AUTO) {
-        use_chain = chain_preferred(p);
+        // With pending modifications the two-pass schedule is the default: its extra passes spread over the whole
+        // chip, while a chain pays for its modified rows alone (measured: the chain is ahead only while at most
+        // about three rows per draft are modified, and a batch waits for its most modified prefix).
+        use_chain = !pending && chain_preferred(p);
     }
 
     hipError_t e;

@@ -18,10 +18,16 @@
 // the chain is walked inside one workgroup, nu_i is available without any exchange
 // between workgroups.
 //
-// The reference exponents ref_q, ref_p are the workgroup-wide maxima over each thread's
-// first vector (a 4096-entry sample) instead of the exact row maxima; should a row
-// overflow float32 with that reference (possible only for extremely peaked rows), its
-// statistics are recomputed from memory with the exact maximum.
+// The reference exponents ref_q, ref_p are the scaled logits of the row's drafted token
+// instead of the exact row maxima; should a row overflow float32 with that reference
+// (possible only for extremely peaked rows), its statistics are recomputed from memory with
+// the exact maximum.
+//
+// Pending distribution modifications (Algorithm 2 applied on the fly, PEND variants): once a
+// row's statistics are known and while the whole row pair is still on chip, every level that
+// modifies the row gets its normaliser from one more sweep over the on-chip copy (no memory
+// traffic), and so does the row's Eq. (hik) sum against the modified row; such a row's slots
+// are then simply reloaded in the next iteration.  Needs the whole row pair on chip.
 #include <utility>
 
 #include "specgbv_internal.hpp"
@@ -207,15 +213,6 @@ __device__ __forceinline__ double uniform_d(double v)
     return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
 }
 
-// log2 of a positive finite double from its exponent and a float log of the mantissa
-// (absolute error about 1e-7).
-__device__ __forceinline__ double log2_cheap(double z)
-{
-    int e;
-    const double m = frexp(z, &e);              // z = m * 2^e, m in [0.5, 1)
-    return static_cast<double>(e) + static_cast<double>(__log2f(static_cast<float>(m)));
-}
-
 // Exact-maximum statistics of one row straight from memory (overflow fallback).  Results are
 // returned by value: reference parameters of a function that is not inlined would pin the
 // caller's variables to scratch memory for the whole kernel.
@@ -326,14 +323,127 @@ __device__ __forceinline__ void run_steps(std::integer_sequence<int, Js...>, con
     (pipeline_step<T, KP, RS, Js>(cx, rq, rp, lds, Zq, Zp, acc), ...);
 }
 
-template <typename T, int KP, int RS>
+// log2 of a positive finite double from its exponent and a float log of the mantissa
+// (absolute error about 1e-7).
+__device__ __forceinline__ double log2_cheap(double z)
+{
+    int e;
+    const double m = frexp(z, &e);              // z = m * 2^e, m in [0.5, 1)
+    return static_cast<double>(e) + static_cast<double>(__log2f(static_cast<float>(m)));
+}
+
+// float64 scalars of the row whose pending levels are being applied (LDS; thread 0 writes, all read).
+struct PendScalars {
+    double lse2_q, lse2_p, tok2_q, tok2_p;   // statistics of the raw row pair
+    double log2nu;                           // block ratio in front of the row (under the modified rows before it)
+    double sumN, tok_adj;                    // so far: sum of the levels' log2 N; what they did to log2 q[token]
+    double C;                                // constant of the current pass
+    float ref_q, rc_hi, rc_nk;               // reference exponent of the target weights; the constant split as in RatioConst
+};
+
+// Constant of a pass whose ratio starts from 2^log2r: log2 (r Z_p / Z_q) minus the levels' log2 N so far.
+__device__ __noinline__ void pend_pass_begin(PendScalars &row, double log2r)
+{
+    // (as RatioConst, with the small exponential: the library routine would claim registers that hold row data)
+    row.C = row.lse2_p - row.lse2_q + log2r - row.sumN;
+    row.rc_hi = static_cast<float>(row.C);
+    const double kappa = exp2_small(static_cast<double>(row.rc_hi) - row.C);
+    row.rc_nk = (kappa > 0.5 && kappa < 2.0) ? -static_cast<float>(kappa) : -1.0f;
+}
+
+// A level's pass is summed (S, relative to 2^ref_q): its normaliser, the drafted token's factor, the table entry
+// for the passes after it, and the level's ratio moved along this row's token under the distribution it modifies.
+__device__ __noinline__ PendRow pend_pass_level(PendScalars &row, PendTable &tab, double &log2mu_l, double S, int K)
+{
+    PendRow out;
+    out.log2mu = log2mu_l; out.log2N = 0.0; out.tokadj = 0.0; out.flag = 0; out.pad = 0;
+    const double W = S * exp2_small(static_cast<double>(row.ref_q) - row.lse2_q - row.sumN);   // mass of q^(l) t^K
+    const double tq_eff = row.tok2_q - row.lse2_q + row.tok_adj, tp = row.tok2_p - row.lse2_p;
+    log2mu_l = out.log2mu + tq_eff - tp;
+    if (W > 0.0) {                               // otherwise every weight is zero and the row stays q^(l)
+        out.flag = 1;
+        out.log2N = log2_cheap(W);
+        const double t = 1.0 - exp2_small(tp - tq_eff - out.log2mu);
+        out.tokadj = t > 0.0 ? static_cast<double>(K) * log2_cheap(t) : -INFINITY;
+        tab.C_hi[tab.n] = row.rc_hi; tab.neg_kappa[tab.n] = row.rc_nk;
+        tab.n += 1;
+        row.sumN += out.log2N;
+        row.tok_adj += out.tokadj - out.log2N;
+    }
+    return out;
+}
+
+// The Eq. (hik) sum of a modified row from its pass (S relative to 2^ref_q).
+__device__ __noinline__ double pend_pass_sum(const PendScalars &row, double S)
+{
+    return S * exp2_small(static_cast<double>(row.ref_q) - row.lse2_q - row.sumN);
+}
+
+// Pending modifications as the chain kernel sees them (nlev = 0: none).
+struct ChainPend {
+    const double *carry;       // [nlev][batch]
+    const int32_t *count;      // [nlev][batch]
+    PendRow *rows;             // [nlev][batch * K * L], written for the final-token kernel
+    int nlev, batch;
+};
+
+// sum over this thread's on-chip vectors of the row pair of the weights w (ot_weights, or pending_weights
+// when tab holds levels), relative to 2^shift_q.  Register slots are all full (the host picks RS so).
+template <typename T, int RS, int... Js>
+__device__ __forceinline__ float onchip_sum(std::integer_sequence<int, Js...>, U4 (&rq)[RS], U4 (&rp)[RS],
+                                            const LdsSlots &lds, unsigned tid, int rem, int n_on, float c, float shift_q,
+                                            const PendTable &tab, const RatioConst &rc, int K)
+{
+    constexpr int PV = Elem<T>::kPerVec;
+    float acc = 0.0f;
+    const bool plain = tab.n == 0;
+    // Four entries at a time and one slot strictly after the other (the opaque touch of the accumulator keeps
+    // the compiler from interleaving slots): the slots themselves occupy most of the register file.
+    auto one = [&](const U4 &q, const U4 &p) {
+        float zq[PV], zp[PV], wq[PV], w[PV];
+        Elem<T>::unpack(q, zq);
+        Elem<T>::unpack(p, zp);
+        if (plain) ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
+        else pending_weights(zq, zp, c, shift_q, tab, rc, K, wq, w);
+        float a = 0.0f;
+#pragma unroll
+        for (int j = 0; j < PV; ++j) a += w[j];
+        acc += a;
+        asm volatile("" : "+v"(acc));
+    };
+    // Register slots one strictly after the other: the opaque touch makes a slot's registers (and the running
+    // sum) pass through a point in program order, so that no slot's unpacked values are formed ahead of time.
+    auto reg = [&](U4 &q, U4 &p) {
+        asm volatile("" : "+v"(q.x), "+v"(q.y), "+v"(q.z), "+v"(q.w), "+v"(acc));
+        asm volatile("" : "+v"(p.x), "+v"(p.y), "+v"(p.z), "+v"(p.w), "+v"(acc));
+        one(q, p);
+    };
+    (reg(rq[Js], rp[Js]), ...);
+    for (int s = 0; s < kLdsSlots; ++s) {
+        const int J = RS + s;
+        if (J < n_on && J * kChainThreads < rem) one(lds_vec(lds, s, 0, tid), lds_vec(lds, s, 1, tid));
+    }
+    return acc;
+}
+
+template <typename T, int KP, int RS, bool PEND>
 __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
         int K, int L, int V, long long nchains, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
-        int32_t *__restrict__ final_counter)
+        int32_t *__restrict__ final_counter, ChainPend pend)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
+    __shared__ PendTable sh_tab;                           // PEND only: levels that modify the current row
+    __shared__ double sh_mu[kMaxPend];                     //            log2 block ratio of every level in front of the current row
+    __shared__ int sh_cnt[kMaxPend];                       //            rows every level modifies (this prefix)
+    __shared__ PendScalars sh_row;                         //            float64 scalars of the current row
+    __shared__ ChainPend sh_pend;                          //            the kernel argument, kept out of the scalar registers
+    __shared__ int sh_sum_done;                            //            the row in sweep 2 already has its sum (modified row)
+    if constexpr (PEND) {
+        if (threadIdx.x == 0) { sh_pend = pend; sh_sum_done = 0; }
+        __syncthreads();
+    }
 
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
@@ -373,7 +483,8 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         const int g_old = g >= 1 ? g - 1 : 0;
         const long long bk_old = chain_of(g_old);
         const int r_old = g_old % L;
-        const bool do_sum = g >= 1 && r_old >= 1;          // rows >= 1 get their Eq. (hik) sum
+        bool do_sum = g >= 1 && r_old >= 1;                // rows >= 1 get their Eq. (hik) sum
+        if constexpr (PEND) do_sum = do_sum && __builtin_amdgcn_readfirstlane(sh_sum_done) == 0;
         const T *qnew = target + (bk_new * (L + 1) + r_new) * static_cast<long long>(V);
         const T *pnew = draft + (bk_new * L + r_new) * static_cast<long long>(V);
         const T *qold = target + (bk_old * (L + 1) + r_old) * static_cast<long long>(V);
@@ -443,6 +554,51 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
                 st.lse2_q = lse2_q; st.lse2_p = lse2_p; st.tok2_q = tok2_q; st.tok2_p = tok2_p;
                 stats[bk_new * L + r_new] = st;
             }
+            double tok_adj = 0.0;                          // what the pending levels do to log2 q[token] of this row
+            if constexpr (PEND) {
+                // All float64 work of the levels is done by thread 0 in a function of its own (values travel through
+                // LDS): the other threads only sweep their on-chip vectors, so the register slots need not be spilled.
+                const int b = static_cast<int>(bk_new / K);
+                const int nlev_u = __builtin_amdgcn_readfirstlane(sh_pend.nlev);
+                const long long n_rows = static_cast<long long>(sh_pend.batch) * K * L, pair = bk_new * L + r_new;
+                __syncthreads();
+                if (r_new == 0 && tid < static_cast<unsigned>(nlev_u)) {
+                    sh_mu[tid] = sh_pend.carry[static_cast<size_t>(tid) * sh_pend.batch + b] * 1.44269504088896340736;
+                    sh_cnt[tid] = sh_pend.count[static_cast<size_t>(tid) * sh_pend.batch + b];
+                }
+                if (tid == 0) {
+                    sh_tab.n = 0;
+                    sh_row.lse2_q = lse2_q; sh_row.lse2_p = lse2_p; sh_row.tok2_q = tok2_q; sh_row.tok2_p = tok2_p;
+                    sh_row.log2nu = log2nu; sh_row.sumN = 0.0; sh_row.tok_adj = 0.0; sh_row.ref_q = ref_q;
+                }
+                __syncthreads();
+                for (int l = 0; l <= nlev_u; ++l) {     // uniform; pass nlev is the row's Eq. (hik) sum against the modified row
+                    const bool is_sum = l == nlev_u;
+                    const bool live = is_sum ? (sh_tab.n > 0 && r_new >= 1) : (r_new < sh_cnt[l]);
+                    if (live) {
+                        if (tid == 0) pend_pass_begin(sh_row, is_sum ? sh_row.log2nu : sh_mu[l]);
+                        __syncthreads();
+                        RatioConst rc(0.0);
+                        rc.C2_hi = sh_row.rc_hi; rc.neg_kappa = sh_row.rc_nk;
+                        double S = static_cast<double>(onchip_sum<T, RS>(std::make_integer_sequence<int, RS>{}, rq, rp, lds, tid, rem,
+                                                                         n_on, c, ref_q, sh_tab, rc, K));
+                        double unused = 0.0;
+                        block_sum2(S, unused, sh_d);
+                        if (tid == 0) {
+                            if (is_sum) s_out[pair] = pend_pass_sum(sh_row, S);
+                            else sh_pend.rows[l * n_rows + pair] = pend_pass_level(sh_row, sh_tab, sh_mu[l], S, K);
+                        }
+                        __syncthreads();
+                    } else if (!is_sum && tid == 0) {
+                        PendRow out;
+                        out.log2mu = 0.0; out.log2N = 0.0; out.tokadj = 0.0; out.flag = 0; out.pad = 0;
+                        sh_pend.rows[l * n_rows + pair] = out;
+                    }
+                }
+                __syncthreads();
+                if (tid == 0) sh_sum_done = sh_tab.n > 0;  // a modified row has its sum (or needs none: row 0)
+                tok_adj = sh_row.tok_adj;
+            }
             // constants of this row's sweep 2 (next iteration)
             const double C2 = lse2_p - lse2_q + log2nu;
             rc_sum.nref_q = -ref_q;
@@ -450,7 +606,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             const double dk = (static_cast<double>(rc_sum.C2_hi) - C2) * 0.693147180559945309417;
             rc_sum.neg_kappa = (dk > -0.25 && dk < 0.25) ? -static_cast<float>(1.0 + dk + 0.5 * dk * dk) : -1.0f;
             Zq_prev = uniform_d(Zq_tot);
-            log2nu = uniform_d(log2nu + ((tok2_q - lse2_q) - (tok2_p - lse2_p)));
+            log2nu = uniform_d(log2nu + ((tok2_q - lse2_q + tok_adj) - (tok2_p - lse2_p)));
         }
     }
 }
@@ -468,7 +624,7 @@ int resident_workgroups()
     return cached[dev];
 }
 
-template <typename T, int KP>
+template <typename T, int KP, bool PEND>
 hipError_t launch_kp(const Problem &p)
 {
     RowStat *stats = reinterpret_cast<RowStat *>(p.ws + p.lay.stats);
@@ -479,9 +635,14 @@ hipError_t launch_kp(const Problem &p)
     const T *target = static_cast<const T *>(p.target);
     const T *draft = static_cast<const T *>(p.draft);
     const int full_slots = (p.V / Elem<T>::kPerVec) / kChainThreads;
-#define SPECGBV_LAUNCH(RS)                                                                              \
-    hipLaunchKernelGGL((k_chain<T, KP, RS>), grid, dim3(kChainThreads), 0, p.stream, target, draft,    \
-                       p.tokens, p.K, p.L, p.V, nchains, p.c, stats, s, reinterpret_cast<int32_t *>(p.ws + p.lay.counter))
+    ChainPend pend;
+    pend.carry = p.pend_carry; pend.count = p.pend_count;
+    pend.rows = reinterpret_cast<PendRow *>(p.ws + p.lay.pend);
+    pend.nlev = PEND ? p.pend_levels : 0; pend.batch = p.batch;
+#define SPECGBV_LAUNCH(RS)                                                                                  \
+    hipLaunchKernelGGL((k_chain<T, KP, RS, PEND>), grid, dim3(kChainThreads), 0, p.stream, target, draft,  \
+                       p.tokens, p.K, p.L, p.V, nchains, p.c, stats, s,                                    \
+                       reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend)
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);
@@ -492,14 +653,16 @@ hipError_t launch_kp(const Problem &p)
 template <typename T>
 hipError_t launch_typed(const Problem &p)
 {
+    if (p.pend_levels > 0)              // pending modifications: two variants only
+        return p.K == 8 ? launch_kp<T, 8, true>(p) : launch_kp<T, 0, true>(p);
     switch (p.K) {                      // the power t^K unrolled for the common draft counts
-    case 1: return launch_kp<T, 1>(p);
-    case 2: return launch_kp<T, 2>(p);
-    case 3: return launch_kp<T, 3>(p);
-    case 4: return launch_kp<T, 4>(p);
-    case 8: return launch_kp<T, 8>(p);
-    case 16: return launch_kp<T, 16>(p);
-    default: return launch_kp<T, 0>(p);
+    case 1: return launch_kp<T, 1, false>(p);
+    case 2: return launch_kp<T, 2, false>(p);
+    case 3: return launch_kp<T, 3, false>(p);
+    case 4: return launch_kp<T, 4, false>(p);
+    case 8: return launch_kp<T, 8, false>(p);
+    case 16: return launch_kp<T, 16, false>(p);
+    default: return launch_kp<T, 0, false>(p);
     }
 }
 
@@ -510,6 +673,16 @@ bool chain_supported(const Problem &p)
     const int pv = p.dtype == 1 ? 8 : 4;
     return p.V % pv == 0 && (p.V / pv) >= 7 * kChainThreads &&
            reinterpret_cast<uintptr_t>(p.target) % 16 == 0 && reinterpret_cast<uintptr_t>(p.draft) % 16 == 0;
+}
+
+// With pending modifications the whole row pair must be on chip (the extra sweeps read the on-chip copy only).
+bool chain_supports_pending(const Problem &p)
+{
+    if (!chain_supported(p)) return false;
+    const int nvec = p.V / (p.dtype == 1 ? 8 : 4);
+    const int full_slots = nvec / kChainThreads, nslots = (nvec + kChainThreads - 1) / kChainThreads;
+    const int RS = full_slots >= 23 ? 23 : (full_slots >= 15 ? 15 : 7);
+    return nslots <= RS + kLdsSlots;
 }
 
 // The chain schedule takes about the same time for any number of chains up to one per compute unit

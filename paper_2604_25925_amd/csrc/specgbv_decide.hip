@@ -72,31 +72,6 @@ __device__ __forceinline__ unsigned long long uniform_u64(unsigned long long v)
            static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<unsigned>(v)));
 }
 
-// 2^x in float64 (0 below x = -1000, infinity above x = 1000) by a degree-12 polynomial on [-1/2, 1/2] and an exponent shift
-// (relative error about 1e-15; far less code than the general library routine, which matters
-// in a kernel whose run time is mostly instruction fetch).
-__device__ __forceinline__ double exp2_small(double x)
-{
-    if (!(x > -1000.0)) return 0.0;
-    if (x > 1000.0) return INFINITY;
-    const double n = rint(x);
-    const double f = (x - n) * 0.693147180559945309417;      // |f| <= 0.3466
-    double p = 1.0 / 479001600.0;
-    p = fma(p, f, 1.0 / 39916800.0);
-    p = fma(p, f, 1.0 / 3628800.0);
-    p = fma(p, f, 1.0 / 362880.0);
-    p = fma(p, f, 1.0 / 40320.0);
-    p = fma(p, f, 1.0 / 5040.0);
-    p = fma(p, f, 1.0 / 720.0);
-    p = fma(p, f, 1.0 / 120.0);
-    p = fma(p, f, 1.0 / 24.0);
-    p = fma(p, f, 1.0 / 6.0);
-    p = fma(p, f, 0.5);
-    p = fma(p, f, 1.0);
-    p = fma(p, f, 1.0);
-    return ldexp(p, static_cast<int>(n));
-}
-
 __device__ double clamp01(double h)
 {
     if (!(h > 0.0)) return 0.0;

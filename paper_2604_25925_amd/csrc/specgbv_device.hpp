@@ -130,6 +130,32 @@ struct RatioConst {
     }
 };
 
+// 2^x in float64 (0 below x = -1000, infinity above x = 1000) by a degree-12 polynomial on [-1/2, 1/2] and an exponent shift
+// (relative error about 1e-15; far less code than the general library routine, which matters
+// in kernels whose run time is mostly instruction fetch, and few registers, which matters where
+// the register file is full of data).
+__device__ __forceinline__ double exp2_small(double x)
+{
+    if (!(x > -1000.0)) return 0.0;
+    if (x > 1000.0) return INFINITY;
+    const double n = rint(x);
+    const double f = (x - n) * 0.693147180559945309417;      // |f| <= 0.3466
+    double p = 1.0 / 479001600.0;
+    p = fma(p, f, 1.0 / 39916800.0);
+    p = fma(p, f, 1.0 / 3628800.0);
+    p = fma(p, f, 1.0 / 362880.0);
+    p = fma(p, f, 1.0 / 40320.0);
+    p = fma(p, f, 1.0 / 5040.0);
+    p = fma(p, f, 1.0 / 720.0);
+    p = fma(p, f, 1.0 / 120.0);
+    p = fma(p, f, 1.0 / 24.0);
+    p = fma(p, f, 1.0 / 6.0);
+    p = fma(p, f, 0.5);
+    p = fma(p, f, 1.0);
+    p = fma(p, f, 1.0);
+    return ldexp(p, static_cast<int>(n));
+}
+
 // max(1 - kappa r / tK, 0) for the second ratio of a row under a pending modification: r / tK is
 // formed with the hardware reciprocal (1 ulp); tK = 0, an overflowing quotient and 0/0-like cases
 // (the entry's weight q tK is then zero or negligible) give 0.

@@ -69,6 +69,7 @@ hipError_t launch_split_main(const Problem &p);
 // fits the kernel's static limits.
 bool chain_supported(const Problem &p);
 bool chain_preferred(const Problem &p);      // supported, and enough chains for it to beat the two-pass schedule
+bool chain_supports_pending(const Problem &p);   // supported, and the whole row pair fits on chip (pending modifications)
 hipError_t launch_chain_main(const Problem &p);
 
 // Decision scan (Algorithm 1) and final-token kernels (Eq. (pres) / bonus token).

@@ -292,6 +292,28 @@ def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype,
     assert (want_n > 0).sum() > B                                                # the comparison is not vacuous
 
 
+@pytest.mark.parametrize("dtype,V,K,levels", [("bf16", 128256, 8, 1), ("bf16", 65536, 3, 3), ("f32", 32000, 8, 2), ("f32", 4 * 7 * 512, 2, 2)])
+def test_pending_on_the_chain_schedule(dtype, V, K, levels):
+    """The chain schedule applies pending levels by extra sweeps over the on-chip row pair: same bar."""
+    B, L = 3, 5
+    w = Workload("pendc", B, K, L, V, dtype, 2.5, 0.8, head=20, temperature=0.9)
+    t, d, tok = make_inputs(w, seed=91)
+    rng = np.random.default_rng(17)
+    carry = rng.normal(2.0, 0.8, (levels, B))
+    count = rng.integers(1, L, (levels, B)).astype(np.int32)
+    count[0, 0] = 0
+    gpu_c = run_gpu(t, d, tok, w.temperature, 4, 1, algo="chain", pending=(carry, count))
+    gpu_s = run_gpu(t, d, tok, w.temperature, 4, 1, algo="split", pending=(carry, count))
+    ora, mods, lnp = oracle_pending(t, d, tok, w.temperature, 4, 1, carry, count)
+    nu_extra, carry_extra, undecided = conditioning(tok, K, carry, count, mods, lnp, ora)
+    keep = ~undecided
+    for name, gpu in (("chain", gpu_c), ("split", gpu_s)):
+        rep = compare({k: v[keep] for k, v in gpu.items()}, {k: v[keep] for k, v in ora.items()}, tok[keep],
+                      label="pending %s %s V=%d" % (name, dtype, V), skip=("lse_q",), nu_extra=nu_extra[keep],
+                      carry_extra=carry_extra[keep])
+        print("[parity] pending on %s: %s" % (name, rep), flush=True)
+
+
 def test_pending_chain_schedule_is_rejected():
     import paper_2604_25925_amd as sg
     import torch

@@ -85,7 +85,7 @@ def test_pending_option_errors_are_caught_before_any_launch():
     assert call(0, P, None) == 1 and "together" in sg.specgbv_last_error()      # one pointer without the other
     assert call(0, None, P) == 1
     assert call(0, P + 4, P) == 1                                               # misaligned float64 pointer
-    assert call(2, P, P) == 2 and "two-pass" in sg.specgbv_last_error()         # chain schedule: unsupported
+    assert call(2, P, P) == 2 and "on chip" in sg.specgbv_last_error()          # chain schedule: row too short for it
 
     def call2(levels, carry, count, state, L=3):
         opt = _Options(0, levels, None, None, carry, count, state)
