@@ -78,6 +78,15 @@ __device__ double clamp01(double h)
     return h < 1.0 ? h : 1.0;
 }
 
+// A double of lane `src` (wave-uniform) in every lane.
+__device__ __forceinline__ double lane_value(double v, int src)
+{
+    const long long bits = __double_as_longlong(v);
+    const unsigned lo = __builtin_amdgcn_readlane(static_cast<int>(bits), src);
+    const unsigned hi = __builtin_amdgcn_readlane(static_cast<int>(bits >> 32), src);
+    return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
+}
+
 struct DecideIO {
     const int32_t *tokens;
     const RowStat *stats;
@@ -199,6 +208,10 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
                 static_cast<int32_t>(((st_lo >> i) & 1ull) | (((st_hi >> i) & 1ull) << 1));
 
     const int kf = f < 0 ? 0 : f;
+    // the levels' entries of the selected row, one lane per level (independent loads instead of a serial walk)
+    PendRow prl;
+    prl.log2mu = 0.0; prl.log2N = 0.0; prl.tokadj = 0.0; prl.flag = 0; prl.pad = 0;
+    if (io.pend && tau < L && lane < io.nlev) prl = io.pend[lane * io.n_rows + base + kf * L + tau];
     if (lane == 0) {
         if (write) {
             io.accepted_len[b] = tau;
@@ -221,12 +234,11 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
                 double sumN = 0.0;
                 int n = 0;
                 for (int l = 0; l < io.nlev; ++l) {
-                    const PendRow pr = io.pend[l * io.n_rows + base + kf * L + tau];
-                    if (pr.flag) {
-                        sl.Cl[n] = lse2_p - lse2_q + pr.log2mu - sumN;
+                    if (__builtin_amdgcn_readlane(prl.flag, l)) {
+                        sl.Cl[n] = lse2_p - lse2_q + lane_value(prl.log2mu, l) - sumN;
                         pend_table_set(*tab_out, n, sl.Cl[n]);
                         ++n;
-                        sumN += pr.log2N;
+                        sumN += lane_value(prl.log2N, l);
                     }
                 }
                 sl.npend = n;
@@ -354,15 +366,6 @@ struct FinalOut {
     double *state_carry;         // pending state updated in place ([kMaxPend][batch] each), or null
     int32_t *state_count;
 };
-
-// A double of lane `src` (wave-uniform) in every lane.
-__device__ __forceinline__ double lane_value(double v, int src)
-{
-    const long long bits = __double_as_longlong(v);
-    const unsigned lo = __builtin_amdgcn_readlane(static_cast<int>(bits), src);
-    const unsigned hi = __builtin_amdgcn_readlane(static_cast<int>(bits >> 32), src);
-    return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
-}
 
 // Sum over aligned groups of 8 lanes (every lane of a group gets its group's sum).
 __device__ __forceinline__ double group8_sum(double v)

@@ -286,7 +286,7 @@ __device__ __forceinline__ double pend_build_table(const PendRow *pend, long lon
     double sumN = 0.0;
     int n = 0;
     for (int l = 0; l < nlev; ++l) {
-        const PendRow pr = pend[l * n_rows + pair];
+        const PendRow pr = pend[static_cast<long long>(l) * n_rows + pair];
         if (pr.flag) {
             pend_table_set(tab, n, base + pr.log2mu - sumN);
             ++n;
@@ -421,6 +421,27 @@ __device__ __forceinline__ double block_sum(double v, double *scratch) {
     double r = 0.0;
     for (int w = 0; w < nw; ++w) r += scratch[w];
     return r;
+}
+
+// log2 of the block ratio in front of row i of the draft whose rows start at row0: the sum over rows j < i of
+// log2 q'_j[token] - log2 p_j[token], with q' the target row as levels 0 .. nlev-1 of the pending modifications
+// leave it (pend may be null when nlev = 0).  All threads of the workgroup take part (every term is one
+// independent load; a single thread walking them would pay each load's latency in turn).
+__device__ __forceinline__ double pend_block_ratio(const RowStat *stats, const PendRow *pend, long long n_rows, int nlev,
+                                                   long long row0, int i, double *scratch) {
+    double v = 0.0;
+    const int per = nlev + 1;
+    for (int t = threadIdx.x; t < i * per; t += blockDim.x) {
+        const int j = t / per, l = t % per;
+        if (l == nlev) {
+            const RowStat a = stats[row0 + j];
+            v += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
+        } else {
+            const PendRow pr = pend[l * n_rows + row0 + j];
+            v += pr.tokadj - pr.log2N;
+        }
+    }
+    return block_sum(v, scratch);
 }
 
 __device__ __forceinline__ float block_max(float v, float *scratch) {

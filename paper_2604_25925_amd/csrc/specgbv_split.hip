@@ -77,6 +77,7 @@ k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, in
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ PendTable sh_tab;
+    __shared__ PendRow sh_pr[kMaxPend];           // the levels below, at this row
     __shared__ double sh_log2mu, sh_sumN;
     const long long nbk = gridDim.x / L;
     const int r = static_cast<int>(blockIdx.x / nbk);
@@ -90,16 +91,14 @@ k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, in
         return;
     }
     const RowStat st = stats[pair];
+    // block ratio in front of row r: the carried one continued along the drafted tokens with the
+    // distribution this level modifies (the target rows as modified by the levels below)
+    const double ahead = pend_block_ratio(stats, pend, n_rows, level, bk * L, r, sh_d);
+    if (static_cast<int>(threadIdx.x) < level) sh_pr[threadIdx.x] = pend[static_cast<long long>(threadIdx.x) * n_rows + pair];
+    __syncthreads();
     if (threadIdx.x == 0) {
-        // block ratio in front of row r: the carried one continued along the drafted tokens with the
-        // distribution this level modifies (the target rows as modified by the levels below)
-        double log2mu = carry_l[b] * 1.44269504088896340736;
-        for (int j = 0; j < r; ++j) {
-            const RowStat a = stats[bk * L + j];
-            log2mu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p) + pend_token_adjust(pend, n_rows, level, bk * L + j);
-        }
-        sh_log2mu = log2mu;
-        sh_sumN = pend_build_table(pend, n_rows, level, pair, st.lse2_p - st.lse2_q, sh_tab);
+        sh_log2mu = carry_l[b] * 1.44269504088896340736 + ahead;
+        sh_sumN = pend_build_table(sh_pr, 1, level, 0, st.lse2_p - st.lse2_q, sh_tab);
     }
     __syncthreads();
     const double log2mu = sh_log2mu, sumN = sh_sumN;
@@ -131,7 +130,7 @@ k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, in
         if (W > 0.0) {                            // otherwise every weight is zero and the row stays q^(level)
             out.flag = 1;
             out.log2N = log2(W);
-            const double tq_eff = (st.tok2_q - st.lse2_q) + pend_token_adjust(pend, n_rows, level, pair);
+            const double tq_eff = (st.tok2_q - st.lse2_q) + pend_token_adjust(sh_pr, 1, level, 0);
             const double ratio = exp2((st.tok2_p - st.lse2_p) - tq_eff - log2mu);
             const double t = 1.0 - ratio;
             out.tokadj = t > 0.0 ? static_cast<double>(K) * log2(t) : -INFINITY;
@@ -148,7 +147,8 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ PendTable sh_tab;
-    __shared__ double sh_log2nu, sh_sumN;
+    __shared__ PendRow sh_pr[kMaxPend];           // the levels, at this row
+    __shared__ double sh_sumN;
     const long long idx = blockIdx.x;             // bk*(L-1) + (i-1)
     const int i = static_cast<int>(idx % (L - 1)) + 1;
     const long long bk = idx / (L - 1);
@@ -157,17 +157,12 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
     // probabilities under the modified rows where levels are pending)
     double log2nu = 0.0, sumN = 0.0;
     if (PEND) {
-        if (threadIdx.x == 0) {
-            double l2 = 0.0;
-            for (int j = 0; j < i; ++j) {
-                const RowStat a = stats[bk * L + j];
-                l2 += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p) + pend_token_adjust(pend, n_rows, nlev, bk * L + j);
-            }
-            sh_log2nu = l2;
-            sh_sumN = pend_build_table(pend, n_rows, nlev, bk * L + i, st.lse2_p - st.lse2_q, sh_tab);
-        }
+        log2nu = pend_block_ratio(stats, pend, n_rows, nlev, bk * L, i, sh_d);
+        if (static_cast<int>(threadIdx.x) < nlev) sh_pr[threadIdx.x] = pend[static_cast<long long>(threadIdx.x) * n_rows + bk * L + i];
         __syncthreads();
-        log2nu = sh_log2nu; sumN = sh_sumN;
+        if (threadIdx.x == 0) sh_sumN = pend_build_table(sh_pr, 1, nlev, 0, st.lse2_p - st.lse2_q, sh_tab);
+        __syncthreads();
+        sumN = sh_sumN;
     } else {
         for (int j = 0; j < i; ++j) {
             const RowStat a = stats[bk * L + j];
