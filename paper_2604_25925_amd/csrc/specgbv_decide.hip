@@ -217,7 +217,7 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
             io.accepted_len[b] = tau;
             io.accepted_draft_idx[b] = f;
         }
-        Selection sl;
+        Selection &sl = *sel_out;                // built in place (LDS): the level constants are indexed at run time
         sl.tau = tau;
         sl.npend = 0; sl.pad = 0;
         tab_out->n = 0;
@@ -247,7 +247,6 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
                 sl.lse2_q = lse2_q + sumN;
             }
         }
-        *sel_out = sl;
     }
     // position tau belongs to the final token, which the locating workgroup writes
     if (write)
@@ -688,7 +687,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
             if (PEND) {                                     // q'[y] = q[y] prod_l t_l[y]^K / N_l (the N_l are in C2)
                 double log2T = 0.0;
                 for (int l = 0; l < sl.npend; ++l) {
-                    const double t = 1.0 - exp2_small(static_cast<double>(c) * (zp - zq) - sl.Cl[l] - log2T);
+                    const double t = 1.0 - exp2_small(static_cast<double>(c) * (zp - zq) - sh_sel.Cl[l] - log2T);   // (LDS: run-time index)
                     log2T = t > 0.0 ? log2T + static_cast<double>(K) * log2(t) : -INFINITY;
                 }
                 l2 += log2T;
