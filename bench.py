@@ -177,7 +177,7 @@ def bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out):
                    "mean_levels_pending": float((cnt > 0).sum(0).mean()), "max_levels_pending": int((cnt > 0).sum(0).max()),
                    "mean_rows_modified": float(cnt.max(0).mean()), "schedule": "two-pass"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": committed_traffic("iterate_" + w.name),
                      "kernel": "k_row_stats + (L-1) x k_pend_norm + k_ot_sum + k_final (whole call)",
                      "kernel_ms_avg": avg, "kernel_ms_min": ker[0], "algorithmic_bytes_per_launch": bytes_},
     }
