@@ -239,8 +239,9 @@ def _read_state(state, B):
     return buf[:8 * B * 8].view(np.float64).reshape(8, B).copy(), buf[8 * B * 8:8 * B * 12].view(np.int32).reshape(8, B).copy()
 
 
-@pytest.mark.parametrize("B,K,L,V,dtype,T", [(24, 3, 6, 2048, "f32", 1.0), (16, 2, 8, 8192, "bf16", 0.8), (12, 4, 9, 515, "f32", 0.9)])
-def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype, T):
+@pytest.mark.parametrize("B,K,L,V,dtype,T,algo", [(24, 3, 6, 2048, "f32", 1.0, "auto"), (16, 2, 8, 8192, "bf16", 0.8, "auto"),
+                                                   (12, 4, 9, 515, "f32", 0.9, "auto"), (10, 2, 6, 4 * 7 * 512, "f32", 0.9, "chain")])
+def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype, T, algo):
     """The in-place state (pending_state) after one call: every level advanced along the emitted tokens
     with the oracle's carry_advance on the rows that level modifies, used-up levels dropped, the new
     modification appended; and the call's outputs equal those of the same levels passed read-only."""
@@ -257,9 +258,9 @@ def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype,
     count[1:, 1] = 0                                                             # one with a single level
     state = _state_tensor(carry, count, B)
     tl, dl, tk = to_torch(t), to_torch(d), to_torch(tok)
-    acc, f, out, ws = sg.specgbv_verify_ex(tl, dl, tk, T, 8, 5, pending_state=state)
+    acc, f, out, ws = sg.specgbv_verify_ex(tl, dl, tk, T, 8, 5, pending_state=state, algo=algo)
     torch.cuda.synchronize()
-    ro = run_gpu(t, d, tok, T, 8, 5, pending=(carry, count))
+    ro = run_gpu(t, d, tok, T, 8, 5, pending=(carry, count), algo=algo)
     acc, f, out = acc.cpu().numpy(), f.cpu().numpy(), out.cpu().numpy()
     assert np.array_equal(acc, ro["accepted_len"]) and np.array_equal(f, ro["accepted_draft_idx"]) and np.array_equal(out, ro["out_tokens"])
     new_carry, new_count = _read_state(state, B)
