@@ -162,8 +162,7 @@ def bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out):
     ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
     ker = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
     avg = sum(ker) / len(ker)
-    buf = state.cpu().numpy()
-    cnt = buf[8 * w.batch * 8:8 * w.batch * 12].view(np.int32).reshape(8, w.batch)
+    cnt = sg.pending_state_views(state.cpu().numpy(), w.batch)[1]
     bytes_ = w.batch * w.K * w.L * 2 * w.V * w.elem_bytes     # every (target, draft) row pair once
     achieved = bytes_ / (avg * 1e-3) / 1e9
     return {

@@ -107,7 +107,7 @@ specgbv_status specgbv_verify(
     int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
-#define SPECGBV_MAX_PENDING 8   /* pending distribution modifications applied on the fly at most */
+#define SPECGBV_MAX_PENDING 16  /* pending distribution modifications applied on the fly at most */
 
 /* Extra controls for specgbv_verify_ex; zero-initialise for the defaults. */
 typedef struct specgbv_options {

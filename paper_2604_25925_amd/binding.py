@@ -203,8 +203,18 @@ def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: fl
     return acc_len, acc_idx, out_tokens, workspace
 
 
+MAX_PENDING = 16          # SPECGBV_MAX_PENDING of the C header
+
+
 def specgbv_pending_state_bytes(batch: int) -> int:
     return int(load_library().specgbv_pending_state_bytes(batch))
+
+
+def pending_state_views(buf: np.ndarray, batch: int):
+    """(carry_log_nu [MAX_PENDING, batch] float64, count [MAX_PENDING, batch] int32) views of a host copy of a
+    pending_state buffer (uint8 numpy array): the layout specgbv_pending_state_bytes describes."""
+    n = MAX_PENDING * batch
+    return buf[:n * 8].view(np.float64).reshape(MAX_PENDING, batch), buf[n * 8:n * 12].view(np.int32).reshape(MAX_PENDING, batch)
 
 
 def specgbv_verify(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int, rng_offset: int,

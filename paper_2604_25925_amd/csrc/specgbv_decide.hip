@@ -366,12 +366,11 @@ struct FinalOut {
     int32_t *state_count;
 };
 
-// Sum over aligned groups of 8 lanes (every lane of a group gets its group's sum).
-__device__ __forceinline__ double group8_sum(double v)
+// Sum over aligned groups of 4 lanes (every lane of a group gets its group's sum).
+__device__ __forceinline__ double group4_sum(double v)
 {
     v += __shfl_xor(v, 1);
     v += __shfl_xor(v, 2);
-    v += __shfl_xor(v, 4);
     return v;
 }
 
@@ -380,17 +379,17 @@ __device__ __forceinline__ double group8_sum(double v)
 // iteration emitted (draft f's tokens 0 .. tau-1, then the final token y), with the token
 // probabilities under the distribution THAT level modifies (the target rows as the levels below it
 // left them); its row count shrinks by tau + 1; used-up levels are dropped, the others move down,
-// and the modification this iteration creates (carry_new, count_new) is appended.  Lane 8 m + j
-// looks after level m and row j (at most kMaxPend levels; a surviving level has tau + 1 < count <= L - 1,
-// so only rows j <= tau <= 6 matter).
+// and the modification this iteration creates (carry_new, count_new) is appended.  Lanes 4 m .. 4 m + 3
+// look after level m (at most kMaxPend = 16 levels), lane 4 m + q after its emitted rows j = q, q + 4, ...
 template <typename T>
 __device__ __forceinline__ void update_pending_state(const T *target, const T *draft, const DecideIO &io, const FinalOut &fo,
                                                      const Selection &sl, int b, int K, int L, int V, float c, int winner,
                                                      int tokid_w, double carry_w, int mcount_w)
 {
+    static_assert(kMaxPend * 4 == kWave, "four lanes per level");
     constexpr double kLn2 = 0.693147180559945309417;
     const int lane = threadIdx.x & (kWave - 1);
-    const int m = lane >> 3, j = lane & 7;
+    const int m = lane >> 2, q = lane & 3;
     const int nlev = io.nlev, tau = sl.tau;
     const int batch = static_cast<int>(gridDim.y);
     const int tokid = __builtin_amdgcn_readlane(tokid_w, winner);
@@ -400,46 +399,52 @@ __device__ __forceinline__ void update_pending_state(const T *target, const T *d
     int count_m = 0;
     double carry_m = 0.0;
     if (m < nlev) { count_m = fo.state_count[static_cast<size_t>(m) * batch + b]; carry_m = fo.state_carry[static_cast<size_t>(m) * batch + b]; }
-    double val = 0.0;            // what level m does to the log2 probability of the token emitted at row j
-    double base = 0.0;           // group 0: log2 q_j[e_j] - log2 p_j[e_j] under the unmodified rows
-    const bool some_may_survive = tau + 2 <= L - 1 && tau < 7;   // a level survives only if tau + 1 < count <= L - 1
+    double val = 0.0;            // what level m does to the log2 probability of the tokens emitted at this lane's rows
+    double base = 0.0;           // log2 q_j[e_j] - log2 p_j[e_j] under the unmodified rows, row j = lane
+    const bool some_may_survive = tau + 2 <= L - 1;   // a level survives only if tau + 1 < count <= L - 1
     if (some_may_survive) {      // uniform; otherwise (in particular after a whole accepted block) every level ends
         const int kf = static_cast<int>(sl.draft_row / L - static_cast<long long>(b) * K);
         const long long row0 = (static_cast<long long>(b) * K + kf) * L;
-        PendRow pr;
-        pr.log2mu = 0.0; pr.log2N = 0.0; pr.tokadj = 0.0; pr.flag = 0; pr.pad = 0;
-        if (m < nlev && j <= tau) pr = io.pend[m * io.n_rows + row0 + j];
-        RowStat st;
-        st.lse2_q = 0.0; st.lse2_p = 0.0; st.tok2_q = 0.0; st.tok2_p = 0.0;
-        if (j <= tau) st = io.stats[row0 + j];
+        // accepted draft tokens: rows j < tau
+        if (m < nlev)
+            for (int j = q; j < tau; j += 4) {
+                const PendRow pr = io.pend[m * io.n_rows + row0 + j];
+                val += pr.tokadj - pr.log2N;
+            }
+        if (lane < tau) {
+            const RowStat st = io.stats[row0 + lane];
+            base = (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);
+        }
+        // the final token y at row tau: its probabilities under the unmodified rows ...
+        const RowStat st_tau = io.stats[row0 + tau];
         const double zq_y = static_cast<double>(Elem<T>::scalar(target + sl.target_row * V + tokid)) * static_cast<double>(c);
         const double zp_y = static_cast<double>(Elem<T>::scalar(draft + sl.draft_row * V + tokid)) * static_cast<double>(c);
-        if (j < tau) { base = (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p); val = pr.tokadj - pr.log2N; }
-        const double lse_q_tau = lane_value(st.lse2_q, tau), lse_p_tau = lane_value(st.lse2_p, tau);   // lane tau: m = 0, j = tau
-        const double by = (zq_y - lse_q_tau) - (zp_y - lse_p_tau);
-        if (j == tau) base = by;
-        // the levels' factors at the final token, one level after the other (wave-uniform loop)
+        const double by = (zq_y - st_tau.lse2_q) - (zp_y - st_tau.lse2_p);
+        if (lane == tau) base = by;
+        // ... and the levels' factors there, one level after the other (wave-uniform loop; lane 4 l holds level l's entry)
+        PendRow pt;
+        pt.log2mu = 0.0; pt.log2N = 0.0; pt.tokadj = 0.0; pt.flag = 0; pt.pad = 0;
+        if (m < nlev && q == 0) pt = io.pend[m * io.n_rows + row0 + tau];
         double log2T = 0.0, sumN = 0.0;
         for (int l = 0; l < nlev; ++l) {
-            const int src = l * 8 + tau;
-            const int flag = __builtin_amdgcn_readlane(pr.flag, src);
-            if (!flag) continue;
-            const double log2mu = lane_value(pr.log2mu, src), log2N = lane_value(pr.log2N, src);
+            const int src = l * 4;
+            if (!__builtin_amdgcn_readlane(pt.flag, src)) continue;
+            const double log2mu = lane_value(pt.log2mu, src), log2N = lane_value(pt.log2N, src);
             const double t = 1.0 - exp2_small(-by - log2mu + sumN - log2T);        // 1 - p[y] / (mu_l q^(l)[y])
             const double adj = t > 0.0 ? static_cast<double>(K) * log2(t) : -INFINITY;
-            if (lane == src) val = adj - log2N;
+            if (lane == src) val += adj - log2N;
             log2T += adj;
             sumN += log2N;
         }
     }
-    const double S = group8_sum(m < nlev ? val : 0.0);       // level m: sum over the emitted rows
-    const double B = lane_value(group8_sum(base), 0);        // unmodified rows (group 0 holds the terms)
+    const double S = group4_sum(val);                        // level m: sum over the emitted rows
+    const double B = wave_sum(base);                         // unmodified rows
     // levels in order: the ratio of level l moves by B plus what the levels below it contribute
     double run = B;
     int pos = 0;
     for (int l = 0; l < nlev; ++l) {
-        const int cnt = __builtin_amdgcn_readlane(count_m, l * 8);
-        const double car = lane_value(carry_m, l * 8);
+        const int cnt = __builtin_amdgcn_readlane(count_m, l * 4);
+        const double car = lane_value(carry_m, l * 4);
         if (some_may_survive && cnt > tau + 1) {
             if (lane == 0) {
                 fo.state_carry[static_cast<size_t>(pos) * batch + b] = car + run * kLn2;
@@ -447,7 +452,7 @@ __device__ __forceinline__ void update_pending_state(const T *target, const T *d
             }
             ++pos;
         }
-        run += lane_value(S, l * 8);
+        run += lane_value(S, l * 4);
     }
     if (count_new > 0 && pos < kMaxPend) {
         if (lane == 0) {

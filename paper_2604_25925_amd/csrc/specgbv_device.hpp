@@ -31,7 +31,7 @@ struct RowStat {
 // each other: Algorithm 3 updates q in place).  Level l turns the row's distribution q^(l) into
 //   q^(l+1)[x] = q^(l)[x] t_l[x]^K / N_l,   t_l[x] = max(1 - p[x] / (mu_l q^(l)[x]), 0),   q^(0) = q,
 // for the first count_l rows of every draft.  Per (level, prefix, draft, row), in base-2 logarithms:
-constexpr int kMaxPend = 8;      // levels applied on the fly at most
+constexpr int kMaxPend = 16;     // levels applied on the fly at most
 struct PendRow {
     double log2mu;   // block ratio mu_l in front of this row (carried ratio continued along the drafted tokens with q^(l))
     double log2N;    // log2 of N_l = sum_x q^(l)[x] t_l[x]^K (0 when the level does not modify the row)

@@ -31,8 +31,9 @@ def test_verify_modify_sample_replay_under_graph_capture():
     out3 = tuple(torch.empty_like(t) for t in out)
     rng = np.random.default_rng(5)
     state0 = np.zeros(sg.specgbv_pending_state_bytes(B), np.uint8)        # two levels pending for every prefix
-    state0[:8 * B * 8].view(np.float64).reshape(8, B)[:2] = rng.normal(2.0, 0.5, (2, B))
-    state0[8 * B * 8:8 * B * 12].view(np.int32).reshape(8, B)[:2] = [[1] * B, [3] * B]
+    c0, n0 = sg.pending_state_views(state0, B)
+    c0[:2] = rng.normal(2.0, 0.5, (2, B))
+    n0[:2] = [[1] * B, [3] * B]
     state0 = torch.from_numpy(state0).to(dev)
     state = torch.empty_like(state0)
     mod = {"logq": torch.empty((B, K, L + 1, V), dtype=torch.float32, device=dev),

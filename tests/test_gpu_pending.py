@@ -196,7 +196,8 @@ def test_pending_cfg4_rows():
 @pytest.mark.parametrize("B,K,L,V,dtype,T,levels", [
     (12, 3, 5, 2048, "f32", 1.0, 2),
     (8, 4, 6, 8192, "bf16", 0.8, 3),
-    (6, 2, 8, 1003, "f32", 0.7, 8),        # as many levels as the library takes, scalar-load path
+    (6, 2, 8, 1003, "f32", 0.7, 8),        # scalar-load path
+    (4, 2, 12, 2048, "f32", 0.8, 16),      # as many levels as the library takes
 ])
 def test_several_pending_levels_match_oracle(B, K, L, V, dtype, T, levels):
     """Modifications on top of each other (Algorithm 3 updates q in place): level l is Algorithm 2
@@ -223,24 +224,25 @@ def test_two_pending_levels_cfg4_rows():
 
 
 def _state_tensor(carry, count, B):
-    """The pending_state buffer of the C ABI for the given levels (level-major, 8 slots per prefix)."""
+    """The pending_state buffer of the C ABI for the given levels."""
     import torch
     import paper_2604_25925_amd as sg
     buf = np.zeros(sg.specgbv_pending_state_bytes(B), np.uint8)
-    c = buf[:8 * B * 8].view(np.float64).reshape(8, B)
-    n = buf[8 * B * 8:8 * B * 12].view(np.int32).reshape(8, B)
+    c, n = sg.pending_state_views(buf, B)
     c[:carry.shape[0]] = carry
     n[:count.shape[0]] = count
     return torch.from_numpy(buf).cuda()
 
 
 def _read_state(state, B):
-    buf = state.cpu().numpy()
-    return buf[:8 * B * 8].view(np.float64).reshape(8, B).copy(), buf[8 * B * 8:8 * B * 12].view(np.int32).reshape(8, B).copy()
+    import paper_2604_25925_amd as sg
+    c, n = sg.pending_state_views(state.cpu().numpy(), B)
+    return c.copy(), n.copy()
 
 
 @pytest.mark.parametrize("B,K,L,V,dtype,T,algo", [(24, 3, 6, 2048, "f32", 1.0, "auto"), (16, 2, 8, 8192, "bf16", 0.8, "auto"),
-                                                   (12, 4, 9, 515, "f32", 0.9, "auto"), (10, 2, 6, 4 * 7 * 512, "f32", 0.9, "chain")])
+                                                   (12, 4, 9, 515, "f32", 0.9, "auto"), (10, 2, 6, 4 * 7 * 512, "f32", 0.9, "chain"),
+                                                   (12, 2, 12, 2048, "f32", 1.0, "auto"), (8, 2, 17, 1024, "f32", 1.0, "auto")])
 def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype, T, algo):
     """The in-place state (pending_state) after one call: every level advanced along the emitted tokens
     with the oracle's carry_advance on the rows that level modifies, used-up levels dropped, the new
@@ -251,7 +253,7 @@ def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype,
     w = Workload("pends", B, K, L, V, dtype, 2.5, 0.8, head=20, temperature=T)
     t, d, tok = make_inputs(w, seed=81)
     rng = np.random.default_rng(13)
-    nlev = 3
+    nlev = 3 if L < 12 else 6
     carry = rng.normal(2.0, 0.8, (nlev, B))
     count = np.sort(rng.integers(1, L, (nlev, B)).astype(np.int32), axis=0)      # alive levels, none empty
     count[:, 0] = 0                                                              # one prefix with nothing pending
@@ -267,7 +269,7 @@ def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype,
     # expected bookkeeping, level by level, on the rows each level modifies (float64, from the oracle)
     ora, mods, lnp = oracle_pending(t, d, tok, T, 8, 5, carry, count)
     Tf = float(np.float32(T))
-    want_c, want_n = np.zeros((8, B)), np.zeros((8, B), np.int32)
+    want_c, want_n = np.zeros((sg.MAX_PENDING, B)), np.zeros((sg.MAX_PENDING, B), np.int32)
     fill = np.zeros(B, int)
     for l, mod in enumerate(mods):
         rows_q = np.ascontiguousarray(mod["lnq_in"])

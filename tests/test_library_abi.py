@@ -91,12 +91,12 @@ def test_pending_option_errors_are_caught_before_any_launch():
         opt = _Options(0, levels, None, None, carry, count, state)
         return lib.specgbv_verify_ex(P, P, P, 2, L, 64, 1, 0, ctypes.c_float(1.0), 0, 0, P, P, P, P, 1 << 30, None,
                                      ctypes.byref(opt))
-    assert call2(9, P, P, None) == 2 and "SPECGBV_MAX_PENDING" in sg.specgbv_last_error()
+    assert call2(17, P, P, None) == 2 and "SPECGBV_MAX_PENDING" in sg.specgbv_last_error()
     assert call2(2, None, None, None) == 1                                      # levels without the arrays
     assert call2(0, P, P, P) == 1 and "not both" in sg.specgbv_last_error()
     assert call2(0, None, None, P + 4) == 1                                     # misaligned state
-    assert call2(0, None, None, P, L=10) == 2                                   # more levels than the state holds
-    assert sg.specgbv_pending_state_bytes(32) >= 32 * 8 * 12 and sg.specgbv_pending_state_bytes(-1) == 0
+    assert call2(0, None, None, P, L=18) == 2                                   # more levels than the state holds
+    assert sg.specgbv_pending_state_bytes(32) >= 32 * sg.MAX_PENDING * 12 and sg.specgbv_pending_state_bytes(-1) == 0
 
 
 def test_modify_target_argument_errors():
