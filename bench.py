@@ -113,13 +113,13 @@ def bench_pending(a, w, sg, torch, tl, dl, tk, ws, out):
     inter = sg.specgbv_read_intermediates(ws, w.batch, w.K, w.L, w.V, dt)
     pend = (torch.from_numpy(inter["carry_log_nu"]).to(tl.device), torch.from_numpy(inter["modify_count"]).to(tl.device))
     for i in range(a.warmup):
-        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1 + i, workspace=ws, out=out, pending=pend)
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1 + i, workspace=ws, out=out, pending=pend, algo=a.algo)
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
     t0 = time.perf_counter()
     for i, (e0, e1) in enumerate(evs):
         e0.record()
-        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1 + a.warmup + i, workspace=ws, out=out, pending=pend)
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1 + a.warmup + i, workspace=ws, out=out, pending=pend, algo=a.algo)
         e1.record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
@@ -135,7 +135,8 @@ def bench_pending(a, w, sg, torch, tl, dl, tk, ws, out):
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: batch %d, K=%d, L=%d, V=%d, %s logits, T=%g" % (
                        w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
-                   "mean_rows_modified": float(np.mean(inter["modify_count"])), "schedule": "two-pass"},
+                   "mean_rows_modified": float(np.mean(inter["modify_count"])),
+                   "schedule": "chain" if a.algo == "chain" else "two-pass"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": committed_traffic("pending_" + w.name),
                      "kernel": "k_row_stats + k_pend_norm + k_ot_sum + k_final (whole call)",
@@ -150,13 +151,13 @@ def bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out):
     drafts, so modifications pile up more than they would behind real models: a pessimistic steady state)."""
     state = torch.zeros(sg.specgbv_pending_state_bytes(w.batch), dtype=torch.uint8, device=tl.device)
     for i in range(max(a.warmup, 2 * w.L)):                  # long enough for the number of levels to settle
-        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, i, workspace=ws, out=out, pending_state=state)
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, i, workspace=ws, out=out, pending_state=state, algo=a.algo)
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
     t0 = time.perf_counter()
     for i, (e0, e1) in enumerate(evs):
         e0.record()
-        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1000 + i, workspace=ws, out=out, pending_state=state)
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1000 + i, workspace=ws, out=out, pending_state=state, algo=a.algo)
         e1.record()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
@@ -174,7 +175,7 @@ def bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out):
         "config": {"workload": "%s: batch %d, K=%d, L=%d, V=%d, %s logits, T=%g" % (
                        w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
                    "mean_levels_pending": float((cnt > 0).sum(0).mean()), "max_levels_pending": int((cnt > 0).sum(0).max()),
-                   "mean_rows_modified": float(cnt.max(0).mean()), "schedule": "two-pass"},
+                   "mean_rows_modified": float(cnt.max(0).mean()), "schedule": "chain" if a.algo == "chain" else "two-pass"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": committed_traffic("iterate_" + w.name),
                      "kernel": "k_row_stats + (L-1) x k_pend_norm + k_ot_sum + k_final (whole call)",
