@@ -295,10 +295,12 @@ def test_pending_state_is_updated_like_the_oracle_bookkeeping(B, K, L, V, dtype,
     assert (want_n > 0).sum() > B                                                # the comparison is not vacuous
 
 
-@pytest.mark.parametrize("dtype,V,K,levels", [("bf16", 128256, 8, 1), ("bf16", 65536, 3, 3), ("f32", 32000, 8, 2), ("f32", 4 * 7 * 512, 2, 2)])
-def test_pending_on_the_chain_schedule(dtype, V, K, levels):
-    """The chain schedule applies pending levels by extra sweeps over the on-chip row pair: same bar."""
-    B, L = 3, 5
+@pytest.mark.parametrize("dtype,V,K,levels,B,L", [("bf16", 128256, 8, 1, 3, 5), ("bf16", 65536, 3, 3, 3, 5), ("f32", 32000, 8, 2, 3, 5),
+                                                  ("f32", 4 * 7 * 512, 2, 2, 3, 5),
+                                                  ("f32", 4 * 7 * 512, 8, 2, 41, 3)])   # more chains than compute units
+def test_pending_on_the_chain_schedule(dtype, V, K, levels, B, L):
+    """The chain schedule applies pending levels by extra sweeps over the on-chip row pair: same bar.  With more
+    chains than compute units a workgroup walks several chains of different prefixes one after the other."""
     w = Workload("pendc", B, K, L, V, dtype, 2.5, 0.8, head=20, temperature=0.9)
     t, d, tok = make_inputs(w, seed=91)
     rng = np.random.default_rng(17)
