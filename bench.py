@@ -230,6 +230,10 @@ def main() -> int:
                          "sample: the draft-side token draw of one position (Algorithm 3) over the batch * K draft rows; "
                          "pending: the verification with a pending modification applied on the fly; "
                          "iterate: the verification with the pending state (all pending modifications and their bookkeeping)")
+    ap.add_argument("--shared-row0", type=int, default=0, choices=[0, 1],
+                    help="verify only: tell the library that rows 0 of a prefix's K drafts are copies of one another "
+                         "(they are in these inputs, as in Algorithm 3); the chain schedule then reads them once per "
+                         "prefix, and the algorithmic bytes are counted accordingly")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -267,7 +271,7 @@ def main() -> int:
 
     def step(offset, events=None):
         sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, offset, workspace=ws, out=out, algo=a.algo,
-                             events=events)
+                             events=events, shared_row0=bool(a.shared_row0))
 
     if a.calibrate_copy_mib > 0:
         src = torch.empty(a.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -314,11 +318,14 @@ def main() -> int:
     main_ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
     main_avg = sum(main_ms) / len(main_ms)
     main_bytes = w.row_pairs * w.V * 2 * w.elem_bytes       # every (target, draft) row pair once
+    dedup = bool(a.shared_row0) and a.algo != "split" and w.L >= 2
+    if dedup:                                               # rows 0 once per prefix instead of once per draft
+        main_bytes = w.batch * (w.K * (w.L - 1) + 1) * w.V * 2 * w.elem_bytes
     achieved = main_bytes / (main_avg * 1e-3) / 1e9
 
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE +
     # WRITE_SIZE, calibrated against a plain copy), if one exists for this workload and schedule
-    traffic = committed_traffic(a.workload) if a.algo != "split" else None
+    traffic = committed_traffic(a.workload + ("_shared_row0" if dedup else "")) if a.algo != "split" else None
 
     res = {
         "metric": "verifications/sec and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",
@@ -329,7 +336,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: batch %d, K=%d, L=%d, V=%d, %s logits, T=%g" % (
                        w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
-                   "algo": a.algo, "row_pairs_per_s": w.row_pairs / (ms_per_step * 1e-3),
+                   "algo": a.algo, "shared_row0": bool(a.shared_row0), "row_pairs_per_s": w.row_pairs / (ms_per_step * 1e-3),
                    "whole_call_algorithmic_GBps": w.algorithmic_bytes / (ms_per_step * 1e-3) / 1e9,
                    "mean_accepted_len": tau_mean, "input_generation_s": round(gen_s, 1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -345,9 +352,11 @@ def main() -> int:
     # float32 instructions.
     unpack = 2 if w.dtype == "bf16" else 0
     nmul = (w.K.bit_length() - 1) + bin(w.K).count("1") - 1
-    slots = (unpack + 8) + (w.L - 1) / w.L * (unpack + 9 + nmul)
+    pairs1 = w.batch * (w.K * (w.L - 1) + 1) if dedup else w.row_pairs      # row pairs that get statistics
+    pairs2 = w.batch * w.K * (w.L - 1)                                      # row pairs that get an Eq. (hik) sum
+    slots = ((unpack + 8) * pairs1 + (unpack + 9 + nmul) * pairs2) / pairs1
     alu_peak = 256 * 4 * 16 * 2.4e9 / 1e12
-    alu_ach = slots * w.row_pairs * w.V / (main_avg * 1e-3) / 1e12
+    alu_ach = slots * pairs1 * w.V / (main_avg * 1e-3) / 1e12
     res["roofline_alu"] = {"bound": "alu", "achieved": alu_ach, "peak": alu_peak, "unit": "Tlane-instr/s",
                            "frac": alu_ach / alu_peak, "slots_per_entry_pair": slots,
                            "note": "unpacked float32 issue rate; the published 157.3 TFLOP/s counts packed FMA"}

@@ -144,6 +144,16 @@ typedef struct specgbv_options {
      * appended.  Needs L - 1 <= SPECGBV_MAX_PENDING.  Calls on one state must not overlap.
      */
     void *pending_state;
+    /*
+     * Nonzero: the caller states that rows 0 of the K drafts of a prefix are copies of one another in both
+     * tensors (they are in Algorithm 3: the K drafts of an iteration extend the same prefix, so
+     * position 0 of every draft is conditioned on that prefix alone; Section 4).  The chain schedule then reads
+     * rows 0 once per prefix (the copy of draft 0) instead of once per draft; other schedules, and calls
+     * with pending modifications, ignore the hint.  With rows 0 that differ the results are those of
+     * draft 0's rows 0 used for every draft's statistics of position 0.
+     */
+    int32_t shared_row0;
+    int32_t reserved;          /* 0 */
 } specgbv_options;
 
 /* specgbv_verify with explicit options (options == NULL means defaults). */

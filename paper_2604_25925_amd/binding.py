@@ -33,7 +33,8 @@ class SpecGBVError(RuntimeError):
 
 class _Options(ctypes.Structure):
     _fields_ = [("algo", c_int32), ("pending_levels", c_int32), ("ev_main_start", c_void_p), ("ev_main_stop", c_void_p),
-                ("pending_carry_log_nu", c_void_p), ("pending_count", c_void_p), ("pending_state", c_void_p)]
+                ("pending_carry_log_nu", c_void_p), ("pending_count", c_void_p), ("pending_state", c_void_p),
+                ("shared_row0", c_int32), ("reserved", c_int32)]
 
 
 class _Intermediates(ctypes.Structure):
@@ -149,7 +150,7 @@ def _shapes(target_logits, draft_logits, draft_tokens):
 def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int,
                       rng_offset: int, *, workspace=None, out: Optional[Tuple] = None, algo="auto",
                       events: Optional[Tuple[int, int]] = None, stream: Optional[int] = None, pending=None,
-                      pending_state=None):
+                      pending_state=None, shared_row0: bool = False):
     """Enqueue one verification on the current (or given) HIP stream.
 
     Returns (accepted_len [B], accepted_draft_idx [B], out_tokens [B, L+1], workspace), all
@@ -159,7 +160,9 @@ def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: fl
     one level: pending distribution modifications (Algorithm 2) applied on the fly, innermost
     first.  `pending_state` (instead) is a zero-initialised uint8 device tensor of
     specgbv_pending_state_bytes(B) bytes that the call reads and updates in place: the whole
-    bookkeeping of Algorithm 3's modifications.
+    bookkeeping of Algorithm 3's modifications.  `shared_row0` states that rows 0 of a prefix's K drafts
+    are copies of one another (Algorithm 3: position 0 is conditioned on the prefix alone), which lets the
+    chain schedule read them once per prefix.
     """
     import torch
     lib = load_library()
@@ -194,7 +197,8 @@ def specgbv_verify_ex(target_logits, draft_logits, draft_tokens, temperature: fl
                    events[0] if events else None, events[1] if events else None,
                    _dev_ptr(pending[0]) if pending is not None else None,
                    _dev_ptr(pending[1]) if pending is not None else None,
-                   pending_state.data_ptr() if pending_state is not None else None)
+                   pending_state.data_ptr() if pending_state is not None else None,
+                   1 if shared_row0 else 0, 0)
     st = lib.specgbv_verify_ex(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V,
                                B, dt, c_float(temperature), rng_seed, rng_offset, acc_len.data_ptr(),
                                acc_idx.data_ptr(), out_tokens.data_ptr(), workspace.data_ptr(),

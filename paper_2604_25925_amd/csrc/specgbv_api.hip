@@ -46,6 +46,7 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.mcount = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.counter = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.pend = take(n * kMaxPend * sizeof(PendRow));
+    w.row0 = take(static_cast<size_t>(batch) * 2 * kRow0Parts * sizeof(Row0Part));
     w.total = off;
     return w;
 }
@@ -156,6 +157,7 @@ specgbv_status specgbv_verify_ex(
         p.pend_levels = L - 1;               // at most L - 1 modifications are alive at once; 0 for L = 1
     }
     const bool pending = p.pend_levels > 0;
+    p.shared_row0 = options && options->shared_row0 != 0 && !pending;
     bool use_chain = false;
     if (algo == SPECGBV_ALGO_CHAIN) {
         if (!(pending ? chain_supports_pending(p) : chain_supported(p)))

@@ -380,6 +380,96 @@ __device__ __noinline__ double pend_pass_sum(const PendScalars &row, double S)
 }
 
 // Pending modifications as the chain kernel sees them (nlev = 0: none).
+constexpr int kRow0Threads = 256;
+
+// Partial statistics of the rows 0 that the K drafts of a prefix share (position 0 of every draft is
+// conditioned on the prefix alone; Algorithm 3).  grid (kRow0Parts, batch, 2): workgroup (i, b, m) reduces
+// slice i of row 0 of draft 0 of prefix b, in the target (m = 0) or draft (m = 1) tensor, to
+// sum_x 2^(c z[x] - ref) with an integral reference exponent, so that the slices combine exactly.
+template <typename T>
+__global__ void __launch_bounds__(kRow0Threads)
+k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
+             Row0Part *__restrict__ parts)
+{
+    __shared__ double sh_d[kRow0Threads / kWave];
+    __shared__ float sh_f[kRow0Threads / kWave];
+    const int part = blockIdx.x, b = blockIdx.y, m = blockIdx.z;
+    const long long bk0 = static_cast<long long>(b) * K;
+    const T *row = m ? draft + bk0 * L * static_cast<long long>(V) : target + bk0 * (L + 1) * static_cast<long long>(V);
+    constexpr int PV = Elem<T>::kPerVec;
+    const int nvec = V / PV;
+    const int per = (nvec + kRow0Parts - 1) / kRow0Parts;
+    const int lo = part * per, hi = lo + per < nvec ? lo + per : nvec;
+    RunningSum acc;
+    for (int i = lo + static_cast<int>(threadIdx.x); i < hi; i += 4 * kRow0Threads) {     // four loads in flight per thread
+        U4 v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = i + j * kRow0Threads;
+            v[j] = load16(row + static_cast<long long>(idx < hi ? idx : i) * PV);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i + j * kRow0Threads < hi) {
+                float z[PV];
+                Elem<T>::unpack(v[j], z);
+                acc.add(z, c);
+            }
+        }
+    }
+    const float M = block_max(acc.m2, sh_f);
+    const double mine = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));
+    const double total = block_sum(acc.Z > 0.0f ? mine : 0.0, sh_d);
+    if (threadIdx.x == 0) {
+        Row0Part out;
+        out.ref = floor(static_cast<double>(M));
+        out.Z = total * exp2(static_cast<double>(M) - out.ref);
+        parts[(static_cast<long long>(b) * 2 + m) * kRow0Parts + part] = out;
+    }
+}
+
+__device__ __forceinline__ double lane_d(double v, int lane)
+{
+    const long long bits = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_readlane(static_cast<int>(bits), lane);
+    const int hi = __builtin_amdgcn_readlane(static_cast<int>(bits >> 32), lane);
+    return __longlong_as_double((static_cast<long long>(hi) << 32) | static_cast<unsigned>(lo));
+}
+
+// Position 0 of chain bk when the prefix's drafts share their rows 0: the row statistics from the slices'
+// partial sums (lanes 0..15 of every wave take the target slices, lanes 16..31 the draft slices; the same
+// butterfly in every workgroup, so every draft of the prefix gets the same bits), the chain's own token
+// read from draft 0's rows.  Every wave computes the same values; thread 0 stores the RowStat.  Returns the
+// log2 block ratio after that token.
+template <typename T>
+__device__ __forceinline__ double row0_from_parts(const Row0Part *parts, const T *target, const T *draft,
+                                                  const int32_t *tokens, long long bk, int K, int L, int V, float c,
+                                                  RowStat *stats)
+{
+    static_assert(kRow0Parts == 16, "one 16-lane row per tensor");
+    const long long b = bk / K;
+    const int lane = threadIdx.x & 31;
+    const Row0Part pt = parts[b * 2 * kRow0Parts + lane];
+    const bool live = pt.Z > 0.0;
+    double ref = live ? pt.ref : -1.0e300;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) ref = fmax(ref, __shfl_xor(ref, o));
+    const double d = pt.ref - ref;                            // an integer <= 0
+    double Z = (live && d > -2000.0) ? ldexp(pt.Z, static_cast<int>(d)) : 0.0;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) Z += __shfl_xor(Z, o);
+    const double lse2 = ref + log2_cheap(Z);
+    int tok = tokens[bk * L];
+    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    const long long bk0 = b * K;
+    RowStat st;
+    st.lse2_q = lane_d(lse2, 0); st.lse2_p = lane_d(lse2, 16);
+    st.tok2_q = static_cast<double>(Elem<T>::scalar(target + bk0 * (L + 1) * static_cast<long long>(V) + tok)) * static_cast<double>(c);
+    st.tok2_p = static_cast<double>(Elem<T>::scalar(draft + bk0 * L * static_cast<long long>(V) + tok)) * static_cast<double>(c);
+    if (threadIdx.x == 0) stats[bk * L] = st;
+    return (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);
+}
+
 struct ChainPend {
     const double *carry;       // [nlev][batch]
     const int32_t *count;      // [nlev][batch]
@@ -430,7 +520,7 @@ template <typename T, int KP, int RS, bool PEND>
 __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
         int K, int L, int V, long long nchains, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
-        int32_t *__restrict__ final_counter, ChainPend pend)
+        int32_t *__restrict__ final_counter, ChainPend pend, int first_row, const Row0Part *__restrict__ row0)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
@@ -459,8 +549,11 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     // the other as ONE sequence of rows: the last sum of a chain overlaps the first loads of the next.
     // (32-bit arithmetic: the host checks that batch * K * (L + 1) stays below 2^31)
     const int nmine = static_cast<int>((nchains - blockIdx.x + gridDim.x - 1) / gridDim.x);
-    const int nrows = nmine * L;                           // rows of this workgroup, in the order it visits them
-    auto chain_of = [&](int g) { return static_cast<long long>(blockIdx.x) + static_cast<long long>(g / L) * gridDim.x; };
+    // first_row = 1: the prefix's drafts share their rows 0, whose statistics come from k_row0_parts, and a
+    // chain is its rows 1 .. L-1 (the host guarantees L >= 2 then)
+    const int rpc = L - first_row;                         // rows per chain
+    const int nrows = nmine * rpc;                         // rows of this workgroup, in the order it visits them
+    auto chain_of = [&](int g) { return static_cast<long long>(blockIdx.x) + static_cast<long long>(g / rpc) * gridDim.x; };
 
     U4 rq[RS], rp[RS];
 #pragma unroll
@@ -479,10 +572,10 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         const bool do_new = g < nrows;                     // a row is being loaded and gets its statistics
         const int g_new = do_new ? g : nrows - 1;          // keeps every address in bounds
         const long long bk_new = chain_of(g_new);
-        const int r_new = g_new % L;
+        const int r_new = first_row + g_new % rpc;
         const int g_old = g >= 1 ? g - 1 : 0;
         const long long bk_old = chain_of(g_old);
-        const int r_old = g_old % L;
+        const int r_old = first_row + g_old % rpc;
         bool do_sum = g >= 1 && r_old >= 1;                // rows >= 1 get their Eq. (hik) sum
         if constexpr (PEND) do_sum = do_sum && __builtin_amdgcn_readfirstlane(sh_sum_done) == 0;
         const T *qnew = target + (bk_new * (L + 1) + r_new) * static_cast<long long>(V);
@@ -490,7 +583,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         const T *qold = target + (bk_old * (L + 1) + r_old) * static_cast<long long>(V);
         const T *pold = draft + (bk_old * L + r_old) * static_cast<long long>(V);
         const unsigned off_new = do_new ? tid * 16u : 0u;  // after the last row: one harmless line
-        if (do_new && r_new == 0 && tid == 0 && bk_new % K == 0)
+        if (do_new && r_new == first_row && tid == 0 && bk_new % K == 0)
             final_counter[bk_new / K] = 0;                 // arrival counter of the final-token kernel
 
         // Reference exponents of the new row: its token's logits (the drafted token was
@@ -535,7 +628,11 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         Zq_tot = uniform_d(Zq_tot); Zp_tot = uniform_d(Zp_tot); s_tot = uniform_d(s_tot);
         if (do_sum && tid == 0) s_out[bk_old * L + r_old] = s_tot / Zq_prev;
         if (do_new) {
-            if (r_new == 0) log2nu = 0.0;                  // a new chain starts from the empty block
+            if (r_new == first_row) {                      // a new chain starts from the empty block ...
+                log2nu = 0.0;
+                if (first_row)                             // ... or from its token at the shared position 0
+                    log2nu = uniform_d(row0_from_parts<T>(row0, target, draft, tokens, bk_new, K, L, V, c, stats));
+            }
             float ref_q = -rc_new.nref_q, ref_p = -rc_new.nref_p;
             if (!(Zq_tot < 1.0e37) || !(Zq_tot > 0.0)) {   // float32 overflow with the token reference
                 const ExactStats e = exact_row_stats<T>(qnew, nvec, c, sh_d);
@@ -639,10 +736,16 @@ hipError_t launch_kp(const Problem &p)
     pend.carry = p.pend_carry; pend.count = p.pend_count;
     pend.rows = reinterpret_cast<PendRow *>(p.ws + p.lay.pend);
     pend.nlev = PEND ? p.pend_levels : 0; pend.batch = p.batch;
+    // rows 0 shared by a prefix's drafts: reduced once per prefix by a small kernel of their own
+    const int first_row = (!PEND && p.shared_row0 && p.L >= 2) ? 1 : 0;
+    Row0Part *row0 = reinterpret_cast<Row0Part *>(p.ws + p.lay.row0);
+    if (first_row)
+        hipLaunchKernelGGL((k_row0_parts<T>), dim3(kRow0Parts, static_cast<unsigned>(p.batch), 2), dim3(kRow0Threads), 0,
+                           p.stream, target, draft, p.K, p.L, p.V, p.c, row0);
 #define SPECGBV_LAUNCH(RS)                                                                                  \
     hipLaunchKernelGGL((k_chain<T, KP, RS, PEND>), grid, dim3(kChainThreads), 0, p.stream, target, draft,  \
                        p.tokens, p.K, p.L, p.V, nchains, p.c, stats, s,                                    \
-                       reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend)
+                       reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend, first_row, row0)
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);

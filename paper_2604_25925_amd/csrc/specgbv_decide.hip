@@ -311,7 +311,7 @@ __device__ __forceinline__ float segment_weigh(const Selection &sl, const PendTa
             float m = -3.0e38f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) m = fmaxf(m, zq[j]);
-            m2 = ceilf(wave_max(m) * c);          // integral: partial sums rescale exactly
+            m2 = integral_reference(wave_max(m), c);
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -m2)); w[j] = wq[j]; }
@@ -559,13 +559,13 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
 #pragma unroll
     for (int i = 0; i < kKeep; ++i) {
         if (s0 + i < s1) {
-            const int sh = static_cast<int>(km2[i] - M);                       // both integral, difference <= 0
+            const int sh = reference_shift(km2[i], M);                         // both integral, difference <= 0
             kw[i] = ldexp(kw[i], sh); kq[i] = ldexp(kq[i], sh);               // now relative to 2^M
             tw += kw[i]; tqs += kq[i];
         }
     }
     for (int s = s0 + kKeep; s < s1; ++s) {
-        const int sh = static_cast<int>(partial_load_m2(&pp[s]) - M);
+        const int sh = reference_shift(partial_load_m2(&pp[s]), M);
         tw += ldexp(partial_load_d(&pp[s].sum_w), sh); tqs += ldexp(partial_load_d(&pp[s].sum_q), sh);
     }
     const double Ww = block_sum(tw, sh_d);
@@ -614,13 +614,13 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
         }
         for (int s = s0 + kKeep; open && s < s1; ++s) {
             const float m2s = partial_load_m2(&pp[s]);
-            const double v = ldexp(partial_load_d(use_q ? &pp[s].sum_q : &pp[s].sum_w), static_cast<int>(m2s - M));
+            const double v = ldexp(partial_load_d(use_q ? &pp[s].sum_q : &pp[s].sum_w), reference_shift(m2s, M));
             if (v > 0.0) { last_pos = s; last_m2 = m2s; cum_before_last = cum; }
             if (cum + v > goal) { found = s; found_m2 = m2s; cum_before = cum; open = false; }
             else cum += v;
         }
         if (found < 0) { found = last_pos; found_m2 = last_m2; cum_before = cum_before_last; }
-        const int up = static_cast<int>(M - found_m2);
+        const int up = -reference_shift(found_m2, M);
         sh_seg = found;
         sh_seg_m2 = found_m2;
         sh_local_target = ldexp(goal - cum_before, up);    // goal in the segment's own scale

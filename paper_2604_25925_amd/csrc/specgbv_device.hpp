@@ -361,6 +361,15 @@ struct RunningSum {
     }
 };
 
+// Integral reference exponent of a group of entries whose largest logit is m (partial sums taken relative to
+// integral references rescale exactly).  A group without a finite entry (m = -3e38 or -inf: every entry
+// masked) gets the finite reference -3e38, against which all its weights are 2^(-inf) = 0.
+__device__ __forceinline__ float integral_reference(float m, float c) { return ceilf(fmaxf(m * c, -3.0e38f)); }
+
+// Exponent shift from one integral reference to a larger one, bounded so that the conversion to int is defined;
+// below 2^-4000 every partial sum is 0 in float64 anyway.
+__device__ __forceinline__ int reference_shift(float from, float to) { return static_cast<int>(fmaxf(from - to, -4000.0f)); }
+
 // ------------------------------------------------------------- reductions
 
 // Wave-wide reductions with data-parallel-primitive moves instead of LDS permutes: shifts by

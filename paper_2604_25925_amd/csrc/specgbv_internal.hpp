@@ -29,9 +29,13 @@ struct Workspace {
     size_t counter;    // int32  [B]  final-token workgroups that have stored their partial sums; zeroed by the
                        //             streaming kernels of every call
     size_t pend;       // PendRow [kMaxPend][B*K*L]  rows under pending modifications (written only by calls that carry some)
+    size_t row0;       // Row0Part [B][2][kRow0Parts]  partial statistics of the rows 0 a prefix's drafts share (chain schedule)
     size_t total;
     int nseg;
 };
+
+constexpr int kRow0Parts = 16;                 // slices a shared row 0 is reduced in
+struct Row0Part { double ref; double Z; };     // sum over the slice of 2^(c z - ref), ref an integer
 
 constexpr int kSegThreads = 256;               // final-token kernels: 4 waves per workgroup
 constexpr int kSegElems = kWave * 8;           // vocabulary entries per residual segment (one wave)
@@ -59,6 +63,7 @@ struct Problem {
     // when not null: the state the call updates in place (kMaxPend levels: carried ratios, then counts)
     double *state_carry;           // [kMaxPend][batch]
     int32_t *state_count;          // [kMaxPend][batch]
+    bool shared_row0;              // rows 0 of a prefix's drafts are copies of one another (caller's statement)
 };
 
 // Schedule "split": statistics kernel, then a second pass for the sums of Eq. (hik).

@@ -44,7 +44,7 @@ __device__ __forceinline__ float samp_weigh(const float (&z)[8], float c, float 
         float m = -3.0e38f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) m = fmaxf(m, z[j]);
-        m2 = ceilf(wave_max(m) * c);             // integral: sums rescale exactly
+        m2 = integral_reference(wave_max(m), c);
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) w[j] = exp2_fast(fmaf(z[j], c, -m2));
@@ -99,7 +99,7 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
     for (int s = s0; s < s1; ++s) mloc = fmaxf(mloc, sh_m2[s]);
     const float M = block_max(mloc, sh_f);
     double mine_seg = 0.0;
-    for (int s = s0; s < s1; ++s) mine_seg += ldexp(sh_sum[s], static_cast<int>(sh_m2[s] - M));
+    for (int s = s0; s < s1; ++s) mine_seg += ldexp(sh_sum[s], reference_shift(sh_m2[s], M));
     const double W = block_sum(mine_seg, sh_d);
     const double u = philox_uniform(seed, offset, static_cast<uint32_t>(row_id), slot);
     const double goal = u * W;
@@ -126,13 +126,13 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
         double cum = excl_t, cum_before = excl_t, cum_before_last = excl_t;
         int found = -1, last_pos = s0 < nseg ? s0 : 0;
         for (int s = s0; s < s1; ++s) {
-            const double v = ldexp(sh_sum[s], static_cast<int>(sh_m2[s] - M));
+            const double v = ldexp(sh_sum[s], reference_shift(sh_m2[s], M));
             if (v > 0.0) { last_pos = s; cum_before_last = cum; }
             if (cum + v > goal) { found = s; cum_before = cum; break; }
             cum += v;
         }
         if (found < 0) { found = last_pos; cum_before = cum_before_last; }
-        const int up = static_cast<int>(M - sh_m2[found]);
+        const int up = -reference_shift(sh_m2[found], M);
         sh_seg = found;
         sh_local_target = ldexp(goal - cum_before, up);        // goal in the segment's own scale
         sh_total = ldexp(W, up);

@@ -27,9 +27,10 @@ def to_torch(a: np.ndarray, device="cuda"):
     return torch.from_numpy(a).to(device)
 
 
-def run_gpu(target, draft, tokens, T, seed, offset, algo="auto", plain=False, pending=None):
+def run_gpu(target, draft, tokens, T, seed, offset, algo="auto", plain=False, pending=None, shared_row0=False):
     """Run the library on numpy inputs; returns outputs and intermediates as numpy.  `pending` is a
-    pair of numpy arrays (carry_log_nu [B], count [B]): a pending modification applied on the fly."""
+    pair of numpy arrays (carry_log_nu [B], count [B]): a pending modification applied on the fly.
+    `shared_row0`: tell the library that rows 0 of a prefix's drafts are copies of one another."""
     import torch
     import paper_2604_25925_amd as sg
     tl, dl, tk = to_torch(target), to_torch(draft), to_torch(np.ascontiguousarray(tokens, dtype=np.int32))
@@ -42,7 +43,7 @@ def run_gpu(target, draft, tokens, T, seed, offset, algo="auto", plain=False, pe
         if pending is not None:
             pend = (torch.from_numpy(np.ascontiguousarray(pending[0], dtype=np.float64)).to(tl.device),
                     torch.from_numpy(np.ascontiguousarray(pending[1], dtype=np.int32)).to(tl.device))
-        a, f, o, ws = sg.specgbv_verify_ex(tl, dl, tk, T, seed, offset, algo=algo, pending=pend)
+        a, f, o, ws = sg.specgbv_verify_ex(tl, dl, tk, T, seed, offset, algo=algo, pending=pend, shared_row0=shared_row0)
     torch.cuda.synchronize()
     res = {"accepted_len": a.cpu().numpy(), "accepted_draft_idx": f.cpu().numpy(), "out_tokens": o.cpu().numpy()}
     if B > 0:
@@ -196,11 +197,11 @@ def compare(gpu, ora, tokens, label="", skip=(), nu_extra=None, carry_extra=None
 
 
 def check_case(target, draft, tokens, T, seed=0, offset=0, algo="auto", label="", prefix_ids=None,
-               gpu_slice=None, nthreads=8):
+               gpu_slice=None, nthreads=8, shared_row0=False):
     """GPU vs oracle on one set of inputs.  With gpu_slice (indices into the batch), the GPU
     runs the whole batch and the oracle only the listed prefixes."""
     import oracle
-    gpu = run_gpu(target, draft, tokens, T, seed, offset, algo=algo)
+    gpu = run_gpu(target, draft, tokens, T, seed, offset, algo=algo, shared_row0=shared_row0)
     if gpu_slice is not None:
         idx = np.asarray(gpu_slice)
         ora = oracle.verify(target[idx], draft[idx], tokens[idx], T, seed, offset, debug=True,

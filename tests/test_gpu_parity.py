@@ -205,6 +205,38 @@ def test_masked_logits_minus_infinity(algo, dtype, V):
         assert np.all(ora["h"][1, 2, 1:] == 0.0) and np.all(gpu["h"][1, 2, 1:] == 0.0)
 
 
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_whole_segments_masked_in_every_row(algo, dtype):
+    # vocabulary padding longer than a 512-entry residual segment, masked with -inf in both models: a segment
+    # without a finite entry must weigh nothing, in the residual rows and in the bonus row alike (prefix 0 has
+    # identical models: either its whole block is accepted or every residual weight vanishes and the token comes
+    # from the target row; at every offset some prefix accepts a whole block and draws from the bonus row).
+    t, d, tok, T = _gauss_case(4, 3, 3, 16384, "f32", seed=17)
+    V = t.shape[-1]
+    rng = np.random.default_rng(18)
+    d[0] = t[0, :, :3]
+    for a in (t, d):
+        a[..., :1100] = -np.inf
+        a[..., 6000:7700] = -np.inf
+        a[..., V - 2048:] = -np.inf
+    t[1] -= 500.0                                  # both models far from zero, by the same offset
+    d[1] -= 500.0
+    B, K, L = tok.shape
+    for b in range(B):
+        for k in range(K):
+            for r in range(L):
+                while not np.isfinite(d[b, k, r, tok[b, k, r]]):
+                    tok[b, k, r] = rng.integers(1100, 6000)
+    if dtype == "bf16":
+        t, d = f32_to_bf16_bits(t), f32_to_bf16_bits(d)
+    for off in (0, 1, 2):
+        rep, gpu, ora = _algo_or_skip(algo, lambda: check_case(t, d, tok, T, 3, off, algo, "masked segments %s" % dtype))
+        assert np.any(ora["accepted_len"] == L), "no prefix reaches the bonus row: case does not test what it should"
+        y = gpu["out_tokens"][np.arange(B), gpu["accepted_len"]]
+        assert np.all(((y >= 1100) & (y < 6000)) | ((y >= 7700) & (y < V - 2048)))
+
+
 def test_plain_entry_point_matches_ex_and_offsets_differ():
     w = with_batch(WORKLOADS["cfg2"], 4)
     t, d, tok = make_inputs(w, seed=2)

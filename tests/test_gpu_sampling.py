@@ -50,6 +50,26 @@ def test_sampling_matches_oracle(rows, V, dtype, T):
         _check(z, T, 11, position + 2, position, "sample %s pos %d" % ((rows, V, dtype, T), position))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sampling_with_whole_segments_masked(dtype):
+    # vocabulary padding longer than a 512-entry segment, masked with -inf, at either end and in the middle:
+    # such a segment has no finite entry to take its reference exponent from and must weigh nothing
+    rng = np.random.default_rng(77)
+    rows, V = 12, 16384
+    z = rng.normal(0, 2.5, (rows, V)).astype(np.float32)
+    z[:, :1100] = -np.inf
+    z[::2, 6000:7700] = -np.inf
+    z[:, V - 2048:] = -np.inf
+    z[3] -= 500.0
+    z[4] += 500.0
+    if dtype == "bf16":
+        z = f32_to_bf16_bits(z)
+    for position in (0, 3):
+        tok, _ = _gpu_sample(z, 1.0, 5, position, position)
+        assert np.all((tok >= 1100) & (tok < V - 2048))
+        _check(z, 1.0, 5, position, position, "sample masked segments %s pos %d" % (dtype, position))
+
+
 def test_sampling_cfg4_draft_rows():
     """The batch * K = 256 draft rows of one position of the benchmark configuration (V = 128256, bf16);
     the oracle recomputes the first 24 of them (its row index is the Philox counter)."""
