@@ -417,6 +417,6 @@ specgbv_status specgbv_read_sample_intermediates(const void *workspace, size_t w
 
 const char *specgbv_last_error(void) { return g_err; }
 
-const char *specgbv_version(void) { return "specgbv 0.4 (gfx950)"; }
+const char *specgbv_version(void) { return "specgbv 0.5 (gfx950)"; }
 
 }  // extern "C"
