@@ -90,3 +90,51 @@ def test_verify_modify_sample_replay_under_graph_capture():
             assert torch.equal(g, e) or (g.dtype.is_floating_point and
                                          torch.equal(torch.nan_to_num(g, neginf=-1e30), torch.nan_to_num(e, neginf=-1e30))), \
                 "replay %d differs from the eager result" % rep
+
+
+def test_chain_schedule_with_shared_rows_0_under_graph_capture():
+    # two kernels in the streaming part (the reduction of the shared rows 0, then the chains): both are captured
+    import torch
+    import paper_2604_25925_amd as sg
+    w = Workload("graph", 5, 4, 3, 32768, "bf16", 2.5, 0.9, head=20, temperature=1.1)
+    sets = [make_inputs(w, seed=s) for s in (51, 52)]
+    T, B, K, L, V = w.temperature, w.batch, w.K, w.L, w.V
+    dev = torch.device("cuda")
+    tl, dl, tk = (to_torch(a) for a in sets[0])
+    ws = torch.empty(sg.specgbv_workspace_bytes(B, K, L, V, 1), dtype=torch.uint8, device=dev)
+    out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+           torch.empty((B, L + 1), dtype=torch.int32, device=dev))
+
+    def iteration():
+        sg.specgbv_verify_ex(tl, dl, tk, T, 9, 1, workspace=ws, out=out, algo="chain", shared_row0=True)
+
+    def load(inputs):
+        a, b, c = (to_torch(x) for x in inputs)
+        tl.copy_(a); dl.copy_(b); tk.copy_(c)
+
+    eager = []
+    for inputs in sets:
+        load(inputs)
+        iteration()
+        torch.cuda.synchronize()
+        eager.append([t.clone() for t in out])
+    load(sets[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        iteration()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        iteration()
+    for rep, inputs in enumerate(sets + sets):
+        load(inputs)
+        for t in out:
+            t.fill_(-7)
+        ws.fill_(rep)                                 # the workspace carries nothing from one call to the next
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for g, e in zip(out, eager[rep % len(sets)]):
+            assert torch.equal(g, e), "replay %d differs from the eager result" % rep
