@@ -100,6 +100,8 @@ def _gauss_case(B, K, L, V, dtype, sigma_t=2.5, sigma_d=0.8, seed=1, T=1.0, head
     (1, 64, 2, 64, "f32"),        # K at its limit
     (1, 2, 62, 40, "f32"),        # L at its limit
     (5, 4, 3, 70001, "f32"),      # odd V larger than one pass of a workgroup
+    (2, 2, 2, 300032, "bf16"),    # more residual segments than the locating workgroup keeps in registers
+    (1, 2, 2, 524288, "f32"),
 ])
 def test_shapes_and_ragged_tails(algo, B, K, L, V, dtype):
     t, d, tok, T = _gauss_case(B, K, L, V, dtype)
@@ -126,7 +128,7 @@ def test_chain_schedule_more_chains_than_compute_units(B, K, L, V, dtype):
 
 
 @pytest.mark.parametrize("algo", ALGOS)
-@pytest.mark.parametrize("T", [0.1, 0.4, 2.0])
+@pytest.mark.parametrize("T", [0.02, 0.1, 0.4, 2.0, 30.0])
 def test_temperature(algo, T):
     t, d, tok, _ = _gauss_case(3, 4, 5, 8192, "bf16", T=T)
     _algo_or_skip(algo, lambda: check_case(t, d, tok, T, 0, 0, algo, "T=%g" % T))
