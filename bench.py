@@ -144,18 +144,24 @@ def bench_pending(a, w, sg, torch, tl, dl, tk, ws, out):
     }
 
 
-def bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out):
+def bench_iterate(a, w, sg, torch, sets, ws, out):
     """One step = one specgbv_verify_ex call with the pending state: the verification under every distribution
     modification still pending for each prefix, and Algorithm 3's bookkeeping, all on the device.  The state
-    starts empty and evolves from call to call (the same synthetic tensors stand in for every iteration's
-    drafts, so modifications pile up more than they would behind real models: a pessimistic steady state)."""
+    starts empty and evolves from call to call.  With one input set the same synthetic tensors stand in for every
+    iteration's drafts, so a prefix accepts about the same length every time and modifications pile up more than
+    they would behind real models (a pessimistic steady state); with --input-sets N the iterations cycle through
+    N independent sets, so accepted lengths vary from iteration to iteration as they do in decoding."""
+    tl = sets[0][0]
     state = torch.zeros(sg.specgbv_pending_state_bytes(w.batch), dtype=torch.uint8, device=tl.device)
-    for i in range(max(a.warmup, 2 * w.L)):                  # long enough for the number of levels to settle
+    nwarm = max(a.warmup, 2 * w.L)                           # long enough for the number of levels to settle
+    for i in range(nwarm):
+        tl, dl, tk = sets[i % len(sets)]
         sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, i, workspace=ws, out=out, pending_state=state, algo=a.algo)
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
     t0 = time.perf_counter()
     for i, (e0, e1) in enumerate(evs):
+        tl, dl, tk = sets[(nwarm + i) % len(sets)]
         e0.record()
         sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 1000 + i, workspace=ws, out=out, pending_state=state, algo=a.algo)
         e1.record()
@@ -163,21 +169,30 @@ def bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out):
     ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
     ker = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
     avg = sum(ker) / len(ker)
-    cnt = sg.pending_state_views(state.cpu().numpy(), w.batch)[1]
+    # levels and rows pending, averaged over one more cycle of untimed iterations
+    lev, rows_mod, lev_max = [], [], 0
+    for i in range(max(len(sets), 4)):
+        cnt = sg.pending_state_views(state.cpu().numpy(), w.batch)[1]
+        lev.append(float((cnt > 0).sum(0).mean())); rows_mod.append(float(cnt.max(0).mean()))
+        lev_max = max(lev_max, int((cnt > 0).sum(0).max()))
+        tl, dl, tk = sets[(nwarm + a.steps + i) % len(sets)]
+        sg.specgbv_verify_ex(tl, dl, tk, w.temperature, a.seed, 5000 + i, workspace=ws, out=out, pending_state=state, algo=a.algo)
+    torch.cuda.synchronize()
     bytes_ = w.batch * w.K * w.L * 2 * w.V * w.elem_bytes     # every (target, draft) row pair once
     achieved = bytes_ / (avg * 1e-3) / 1e9
     return {
         "metric": "decoding iterations/sec: verification under all pending distribution modifications plus Algorithm 3's "
                   "bookkeeping on the device, and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",
         "value": w.batch / (ms_per_step * 1e-3), "unit": "verifications/s", "n_gpus": 1, "steps": a.steps,
-        "warmup": max(a.warmup, 2 * w.L), "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "warmup": nwarm, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: batch %d, K=%d, L=%d, V=%d, %s logits, T=%g" % (
                        w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
-                   "mean_levels_pending": float((cnt > 0).sum(0).mean()), "max_levels_pending": int((cnt > 0).sum(0).max()),
-                   "mean_rows_modified": float(cnt.max(0).mean()), "schedule": "chain" if a.algo == "chain" else "two-pass"},
+                   "input_sets": len(sets), "mean_levels_pending": sum(lev) / len(lev), "max_levels_pending": lev_max,
+                   "mean_rows_modified": sum(rows_mod) / len(rows_mod), "schedule": "chain" if a.algo == "chain" else "two-pass"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": committed_traffic("iterate_" + w.name),
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": committed_traffic("iterate_" + w.name) if len(sets) == 1 else None,
                      "kernel": "k_row_stats + (L-1) x k_pend_norm + k_ot_sum + k_final (whole call)",
                      "kernel_ms_avg": avg, "kernel_ms_min": ker[0], "algorithmic_bytes_per_launch": bytes_},
     }
@@ -234,6 +249,8 @@ def main() -> int:
                     help="verify only: tell the library that rows 0 of a prefix's K drafts are copies of one another "
                          "(they are in these inputs, as in Algorithm 3); the chain schedule then reads them once per "
                          "prefix, and the algorithmic bytes are counted accordingly")
+    ap.add_argument("--input-sets", type=int, default=1,
+                    help="iterate only: cycle through this many independent input sets (seeds seed, seed+1, ...)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -252,6 +269,10 @@ def main() -> int:
     t0 = time.time()
     target, draft, tokens = generate(a.workload, a.seed, workers=a.workers or min(16, os.cpu_count() or 1))
     gen_s = time.time() - t0
+    more_sets = []
+    if a.op == "iterate":
+        more_sets = [generate(a.workload, a.seed + j, workers=a.workers or min(16, os.cpu_count() or 1))
+                     for j in range(1, max(1, a.input_sets))]
 
     import torch
     import paper_2604_25925_amd as sg
@@ -291,7 +312,8 @@ def main() -> int:
         print(json.dumps(bench_pending(a, w, sg, torch, tl, dl, tk, ws, out)))
         return 0
     if a.op == "iterate":
-        print(json.dumps(bench_iterate(a, w, sg, torch, tl, dl, tk, ws, out)))
+        sets = [(tl, dl, tk)] + [tuple(up(x) for x in more) for more in more_sets]
+        print(json.dumps(bench_iterate(a, w, sg, torch, sets, ws, out)))
         return 0
 
     for i in range(a.warmup):

@@ -46,6 +46,9 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.mcount = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.counter = take(static_cast<size_t>(batch) * sizeof(int32_t));
     w.pend = take(n * kMaxPend * sizeof(PendRow));
+    w.pend_off = take(static_cast<size_t>(kMaxPend) * (static_cast<size_t>(batch) + 1) * sizeof(int32_t));
+    w.pend_part = take(n * kPendParts * sizeof(double));
+    w.pend_cnt = take(n * sizeof(int32_t));
     w.row0 = take(static_cast<size_t>(batch) * 2 * kRow0Parts * sizeof(Row0Part));
     w.total = off;
     return w;

@@ -307,17 +307,16 @@ __device__ __forceinline__ double pend_token_adjust(const PendRow *pend, long lo
 
 // ------------------------------------------------------- row-pair streaming
 
-// f(first entry index, z_q[N], z_p[N]) for every entry of a (target, draft) row pair, N = 8 or 4 entries of
-// one 16-byte vector (VEC) or 1; the workgroup's THREADS threads stride over the row, each keeping the loads
-// of two vectors of either row in flight.
+// f(first entry index, z_q[N], z_p[N]) for the entries of a (target, draft) row pair in the unit range [lo, hi),
+// N = 8 or 4 entries of one 16-byte vector (VEC; a unit is a vector) or 1 (a unit is an entry); the workgroup's
+// THREADS threads stride over the range, each keeping the loads of two vectors of either row in flight.
 template <typename T, bool VEC, int THREADS, typename F>
-__device__ __forceinline__ void for_each_pair(const T *rq, const T *rp, int V, F f)
+__device__ __forceinline__ void for_each_pair_range(const T *rq, const T *rp, int lo, int hi, F f)
 {
     constexpr int PV = Elem<T>::kPerVec;
     if constexpr (VEC) {
-        const int nvec = V / PV;
-        int v = threadIdx.x;
-        for (; v + THREADS < nvec; v += 2 * THREADS) {          // four loads in flight per thread
+        int v = lo + static_cast<int>(threadIdx.x);
+        for (; v + THREADS < hi; v += 2 * THREADS) {             // four loads in flight per thread
             const U4 q0 = load16(rq + static_cast<long long>(v) * PV), p0 = load16(rp + static_cast<long long>(v) * PV);
             const U4 q1 = load16(rq + static_cast<long long>(v + THREADS) * PV);
             const U4 p1 = load16(rp + static_cast<long long>(v + THREADS) * PV);
@@ -325,18 +324,25 @@ __device__ __forceinline__ void for_each_pair(const T *rq, const T *rp, int V, F
             Elem<T>::unpack(q0, zq); Elem<T>::unpack(p0, zp); f(v * PV, zq, zp);
             Elem<T>::unpack(q1, zq); Elem<T>::unpack(p1, zp); f((v + THREADS) * PV, zq, zp);
         }
-        if (v < nvec) {
+        if (v < hi) {
             float zq[PV], zp[PV];
             Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), zq);
             Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), zp);
             f(v * PV, zq, zp);
         }
     } else {
-        for (int x = threadIdx.x; x < V; x += THREADS) {
+        for (int x = lo + static_cast<int>(threadIdx.x); x < hi; x += THREADS) {
             const float zq[1] = {Elem<T>::scalar(rq + x)}, zp[1] = {Elem<T>::scalar(rp + x)};
             f(x, zq, zp);
         }
     }
+}
+
+// The whole row pair.
+template <typename T, bool VEC, int THREADS, typename F>
+__device__ __forceinline__ void for_each_pair(const T *rq, const T *rp, int V, F f)
+{
+    for_each_pair_range<T, VEC, THREADS>(rq, rp, 0, VEC ? V / Elem<T>::kPerVec : V, f);
 }
 
 

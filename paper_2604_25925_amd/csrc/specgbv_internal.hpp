@@ -29,11 +29,15 @@ struct Workspace {
     size_t counter;    // int32  [B]  final-token workgroups that have stored their partial sums; zeroed by the
                        //             streaming kernels of every call
     size_t pend;       // PendRow [kMaxPend][B*K*L]  rows under pending modifications (written only by calls that carry some)
+    size_t pend_off;   // int32  [kMaxPend][B+1]  per level: rows the level modifies in the prefixes before b (two-pass schedule)
+    size_t pend_part;  // double [B*K*L][kPendParts]  partial normalisers of a modified row shared among workgroups
+    size_t pend_cnt;   // int32  [B*K*L]  workgroups of a shared row that have stored their partial normaliser
     size_t row0;       // Row0Part [B][2][kRow0Parts]  partial statistics of the rows 0 a prefix's drafts share (chain schedule)
     size_t total;
     int nseg;
 };
 
+constexpr int kPendParts = 16;                 // workgroups a modified row's normaliser is shared among, at most
 constexpr int kRow0Parts = 16;                 // slices a shared row 0 is reduced in
 struct Row0Part { double ref; double Z; };     // sum over the slice of 2^(c z - ref), ref an integer
 

@@ -22,20 +22,61 @@ namespace {
 
 constexpr int kStatThreads = 512;
 
+// What the level passes need before they start (pending modifications only): per level l and prefix b the
+// number of rows the level modifies in the prefixes before b, K * sum_{b' < b} clamp(count[l][b'], 0, L), with the
+// level's total at position batch.  One workgroup per level.
+__device__ __forceinline__ void pend_offsets(const int32_t *count_l, int K, int L, int batch, int32_t *off_l)
+{
+    __shared__ double sh_scan[kStatThreads / kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wid = tid / kWave;
+    const int chunk = (batch + kStatThreads - 1) / kStatThreads;
+    const int b0 = tid * chunk, b1 = b0 + chunk < batch ? b0 + chunk : batch;
+    double mine = 0.0;                                 // small integers: exact in float64
+    for (int b = b0; b < b1; ++b) {
+        const int cnt = count_l[b];
+        mine += static_cast<double>(K) * static_cast<double>(cnt < 0 ? 0 : (cnt > L ? L : cnt));
+    }
+    const double incl = wave_inclusive_sum(mine);
+    if (lane == kWave - 1) sh_scan[wid] = incl;
+    __syncthreads();
+    double before = incl - mine;
+    for (int w = 0; w < wid; ++w) before += sh_scan[w];
+    for (int b = b0; b < b1; ++b) {
+        off_l[b] = static_cast<int32_t>(before);
+        const int cnt = count_l[b];
+        before += static_cast<double>(K) * static_cast<double>(cnt < 0 ? 0 : (cnt > L ? L : cnt));
+    }
+    if (tid == kStatThreads - 1) off_l[batch] = static_cast<int32_t>(before);     // the last thread's end is the total
+}
+
+// grid (row pairs + pending levels, 2): blocks (pair, 0 / 1) reduce the target / draft row of the pair; with
+// pending modifications blocks (pairs + l, 0) compute level l's offsets (pend_offsets) and the row blocks clear
+// the arrival counters of the level passes.
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kStatThreads)
 k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
             const int32_t *__restrict__ tokens, int K, int L, int V, float c,
-            RowStat *__restrict__ stats, int32_t *__restrict__ final_counter)
+            RowStat *__restrict__ stats, int32_t *__restrict__ final_counter, long long n_rows, int batch,
+            const int32_t *__restrict__ pend_count, int32_t *__restrict__ pend_off, int32_t *__restrict__ pend_cnt)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ float sh_f[kStatThreads / kWave];
     const long long pair = blockIdx.x;            // (b*K + k)*L + r
+    const bool is_draft = blockIdx.y == 1;
+    if (pair >= n_rows) {                         // uniform: one of the offset blocks
+        const int level = static_cast<int>(pair - n_rows);
+        if (!is_draft)
+            pend_offsets(pend_count + static_cast<size_t>(level) * batch, K, L, batch,
+                         pend_off + static_cast<size_t>(level) * (batch + 1));
+        return;
+    }
     const int r = static_cast<int>(pair % L);
     const long long bk = pair / L;
-    const bool is_draft = blockIdx.y == 1;
-    if (threadIdx.x == 0 && !is_draft && pair % (static_cast<long long>(K) * L) == 0)
-        final_counter[pair / (static_cast<long long>(K) * L)] = 0;      // arrival counter of the final-token kernel
+    if (threadIdx.x == 0 && !is_draft) {
+        if (pair % (static_cast<long long>(K) * L) == 0)
+            final_counter[pair / (static_cast<long long>(K) * L)] = 0;  // arrival counter of the final-token kernel
+        if (pend_cnt) pend_cnt[pair] = 0;
+    }
     const T *row = is_draft ? draft + (bk * L + r) * static_cast<long long>(V)
                             : target + (bk * (L + 1) + r) * static_cast<long long>(V);
     constexpr int PV = Elem<T>::kPerVec;
@@ -67,29 +108,48 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
 }
 
 // One level of pending modification (the levels below it are done: their PendRow entries are read).
-// grid.x = batch * K * L row pairs, row index slowest: the live workgroups (rows below the prefix's
-// count) are then consecutive and spread over all dies, whatever L is; the others leave at once.
+// grid.x = batch * K * L.  Workgroup w first writes the empty entry of row pair w if the level leaves that row
+// alone.  Then it takes a unit of work: the T rows the level modifies are enumerated prefix by prefix (off[b] rows
+// before prefix b; within a prefix row index slowest) and each is shared among P = min(grid / T, kPendParts)
+// workgroups, so that a level with few rows left still occupies the chip (one workgroup streaming a whole row
+// pair with several levels of arithmetic per entry takes 100 - 200 us).  Unit u = blockIdx.x < T * P is part
+// u % P of row u / P; the parts' sums meet in the workspace (device-scope relaxed atomic accesses) and the
+// workgroup that arrives last at the row's counter finishes the row.  No workgroup waits for another one.
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kStatThreads)
 k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
             const double *__restrict__ carry_l, const int32_t *__restrict__ count_l,
-            const RowStat *__restrict__ stats, PendRow *pend, long long n_rows, int level)
+            const RowStat *__restrict__ stats, PendRow *pend, long long n_rows, int level,
+            const int32_t *__restrict__ off, int batch, double *part_buf, int32_t *arrive)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ PendTable sh_tab;
     __shared__ PendRow sh_pr[kMaxPend];           // the levels below, at this row
     __shared__ double sh_log2mu, sh_sumN;
-    const long long nbk = gridDim.x / L;
-    const int r = static_cast<int>(blockIdx.x / nbk);
-    const long long bk = blockIdx.x % nbk;
-    const long long pair = bk * L + r;            // (b*K + k)*L + r
-    const int b = static_cast<int>(bk / K);
+    __shared__ int sh_b, sh_last;
     PendRow out;
     out.log2mu = 0.0; out.log2N = 0.0; out.tokadj = 0.0; out.flag = 0; out.pad = 0;
-    if (r >= count_l[b]) {                        // uniform over the workgroup
-        if (threadIdx.x == 0) pend[level * n_rows + pair] = out;
-        return;
+    {
+        const long long pair0 = blockIdx.x;
+        const int r0 = static_cast<int>(pair0 % L);
+        if (threadIdx.x == 0 && r0 >= count_l[(pair0 / L) / K]) pend[level * n_rows + pair0] = out;
     }
+    const int T_live = off[batch];
+    if (T_live <= 0) return;                      // uniform over the grid
+    int P = static_cast<int>(gridDim.x / static_cast<unsigned>(T_live));
+    P = P > kPendParts ? kPendParts : P;          // >= 1: the modified rows are among the grid's rows
+    if (static_cast<long long>(blockIdx.x) >= static_cast<long long>(T_live) * P) return;
+    const int item = static_cast<int>(blockIdx.x) / P, part = static_cast<int>(blockIdx.x) % P;
+    for (int base = 0; base < batch; base += kStatThreads) {
+        const int bb = base + static_cast<int>(threadIdx.x);
+        if (bb < batch && off[bb] <= item && item < off[bb + 1]) sh_b = bb;          // exactly one thread
+    }
+    __syncthreads();
+    const int b = sh_b;
+    const int j = item - off[b];
+    const int r = j / K;
+    const long long bk = static_cast<long long>(b) * K + j % K;
+    const long long pair = bk * L + r;            // (b*K + k)*L + r
     const RowStat st = stats[pair];
     // block ratio in front of row r: the carried one continued along the drafted tokens with the
     // distribution this level modifies (the target rows as modified by the levels below)
@@ -107,23 +167,48 @@ k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, in
     const T *rq = target + (bk * (L + 1) + r) * static_cast<long long>(V);
     const T *rp = draft + pair * static_cast<long long>(V);
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
+    const int units = VEC ? V / N : V;
+    const int per = (units + P - 1) / P;
+    const int lo = part * per, hi = lo + per < units ? lo + per : units;
     float acc = 0.0f;
     if (sh_tab.n == 0) {
-        for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+        for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
             float wq[N], w[N];
             ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
 #pragma unroll
-            for (int j = 0; j < N; ++j) acc += w[j];
+            for (int jj = 0; jj < N; ++jj) acc += w[jj];
         });
     } else {
-        for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+        for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
             float wq[N], w[N];
             pending_weights(zq, zp, c, shift_q, sh_tab, rc, K, wq, w);
 #pragma unroll
-            for (int j = 0; j < N; ++j) acc += w[j];
+            for (int jj = 0; jj < N; ++jj) acc += w[jj];
         });
     }
-    const double S = block_sum(static_cast<double>(acc), sh_d);           // relative to 2^shift_q
+    double S = block_sum(static_cast<double>(acc), sh_d);                 // relative to 2^shift_q
+    if (P > 1) {
+        // the store is a device-scope access; the workgroup-scope release fence waits until it has completed,
+        // so the counter update that follows (same thread) cannot be seen before it
+        if (threadIdx.x == 0) {
+            __hip_atomic_store(reinterpret_cast<unsigned long long *>(part_buf + pair * kPendParts + part),
+                               static_cast<unsigned long long>(__double_as_longlong(S)), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            const int arrived = __hip_atomic_fetch_add(&arrive[pair], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh_last = arrived == P - 1;
+        }
+        __syncthreads();
+        if (!sh_last) return;
+        if (threadIdx.x == 0) {
+            S = 0.0;
+            for (int q = 0; q < P; ++q)                                   // in part order: the same bits whoever finishes
+                S += __longlong_as_double(static_cast<long long>(__hip_atomic_load(
+                    reinterpret_cast<const unsigned long long *>(part_buf + pair * kPendParts + q), __ATOMIC_RELAXED,
+                    __HIP_MEMORY_SCOPE_AGENT)));
+            __hip_atomic_store(&arrive[pair], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next level's pass
+        }
+    }
     if (threadIdx.x == 0) {
         const double W = S * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);   // mass of q^(level) t^K
         out.log2mu = log2mu;
@@ -207,13 +292,16 @@ hipError_t launch_typed(const Problem &p)
     const bool vec = (p.V % Elem<T>::kPerVec) == 0 &&
                      (reinterpret_cast<uintptr_t>(p.target) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(p.draft) % 16 == 0);
-    const dim3 g1(static_cast<unsigned>(pairs), 2);
+    int32_t *pend_off = reinterpret_cast<int32_t *>(p.ws + p.lay.pend_off);
+    int32_t *pend_cnt = p.pend_levels > 0 ? reinterpret_cast<int32_t *>(p.ws + p.lay.pend_cnt) : nullptr;
+    double *pend_part = reinterpret_cast<double *>(p.ws + p.lay.pend_part);
+    const dim3 g1(static_cast<unsigned>(pairs + p.pend_levels), 2);
     if (vec)
         hipLaunchKernelGGL((k_row_stats<T, true>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
-                           p.tokens, p.K, p.L, p.V, p.c, stats, counter);
+                           p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt);
     else
         hipLaunchKernelGGL((k_row_stats<T, false>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
-                           p.tokens, p.K, p.L, p.V, p.c, stats, counter);
+                           p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     PendRow *pend = reinterpret_cast<PendRow *>(p.ws + p.lay.pend);
@@ -221,12 +309,13 @@ hipError_t launch_typed(const Problem &p)
         const dim3 gp(static_cast<unsigned>(pairs));
         const double *carry_l = p.pend_carry + static_cast<size_t>(level) * p.batch;
         const int32_t *count_l = p.pend_count + static_cast<size_t>(level) * p.batch;
+        const int32_t *off_l = pend_off + static_cast<size_t>(level) * (p.batch + 1);
         if (vec)
             hipLaunchKernelGGL((k_pend_norm<T, true>), gp, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L,
-                               p.V, p.c, carry_l, count_l, stats, pend, pairs, level);
+                               p.V, p.c, carry_l, count_l, stats, pend, pairs, level, off_l, p.batch, pend_part, pend_cnt);
         else
             hipLaunchKernelGGL((k_pend_norm<T, false>), gp, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L,
-                               p.V, p.c, carry_l, count_l, stats, pend, pairs, level);
+                               p.V, p.c, carry_l, count_l, stats, pend, pairs, level, off_l, p.batch, pend_part, pend_cnt);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
