@@ -132,12 +132,12 @@ k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, in
     {
         const long long pair0 = blockIdx.x;
         const int r0 = static_cast<int>(pair0 % L);
-        if (threadIdx.x == 0 && r0 >= count_l[(pair0 / L) / K]) pend[level * n_rows + pair0] = out;
+        if (threadIdx.x == 0 && pair0 < n_rows && r0 >= count_l[(pair0 / L) / K]) pend[level * n_rows + pair0] = out;
     }
     const int T_live = off[batch];
     if (T_live <= 0) return;                      // uniform over the grid
-    int P = static_cast<int>(gridDim.x / static_cast<unsigned>(T_live));
-    P = P > kPendParts ? kPendParts : P;          // >= 1: the modified rows are among the grid's rows
+    int P = static_cast<int>(gridDim.x / static_cast<unsigned>(T_live));   // >= 1: the modified rows are among the grid's rows
+    P = P > kPendParts ? kPendParts : P;
     if (static_cast<long long>(blockIdx.x) >= static_cast<long long>(T_live) * P) return;
     const int item = static_cast<int>(blockIdx.x) / P, part = static_cast<int>(blockIdx.x) % P;
     for (int base = 0; base < batch; base += kStatThreads) {
