@@ -214,6 +214,26 @@ def test_several_pending_levels_match_oracle(B, K, L, V, dtype, T, levels):
     assert (ora["accepted_len"] > 0).any()
 
 
+@pytest.mark.parametrize("B,K,L,V,dtype,alive", [(33, 5, 8, 3072, "bf16", 0.2), (40, 3, 6, 1531, "f32", 0.06),
+                                                  (9, 2, 4, 16384, "bf16", 0.5)])
+def test_levels_with_few_rows_left(B, K, L, V, dtype, alive):
+    """The level passes share a modified row among as many workgroups as the grid allows for the rows the level
+    has left: the higher levels here are alive in a small fraction of the prefixes only, so every pass works with
+    another number of parts per row (from one to the maximum), and the parts are ragged (V is not a multiple of
+    the part count times the vector width)."""
+    w = Workload("pendf", B, K, L, V, dtype, 2.5, 0.8, head=20, temperature=0.9)
+    t, d, tok = make_inputs(w, seed=73)
+    rng = np.random.default_rng(13)
+    levels = min(L - 1, 5)
+    carry = rng.normal(1.8, 0.8, (levels, B))
+    count = rng.integers(1, L, (levels, B)).astype(np.int32)
+    count[1:] *= (rng.random((levels - 1, B)) < alive)
+    count[-1, :] = 0
+    count[-1, B // 2] = L - 1                     # the last level: one prefix only
+    rep, gpu, ora, mods = check_pending(t, d, tok, 0.9, 8, 2, carry, count, "pending, few rows left %s V=%d" % (dtype, V))
+    assert rep["decision_mismatches"] <= 1 and rep["token_mismatches"] <= 1
+
+
 def test_two_pending_levels_cfg4_rows():
     w = with_batch(WORKLOADS["cfg4"], 3)
     t, d, tok = make_inputs(w, seed=72)
