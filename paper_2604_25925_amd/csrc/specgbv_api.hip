@@ -49,6 +49,7 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.pend_off = take(static_cast<size_t>(kMaxPend) * (static_cast<size_t>(batch) + 1) * sizeof(int32_t));
     w.pend_part = take(n * kPendParts * sizeof(double));
     w.pend_cnt = take(n * sizeof(int32_t));
+    w.stat_part = take(n * 2 * kRowParts * sizeof(Row0Part));
     w.row0 = take(static_cast<size_t>(batch) * 2 * kRow0Parts * sizeof(Row0Part));
     w.total = off;
     return w;
@@ -173,6 +174,8 @@ specgbv_status specgbv_verify_ex(
         // about three rows per draft are modified, and a batch waits for its most modified prefix).
         use_chain = !pending && chain_preferred(p);
     }
+
+    p.s_parts = use_chain ? 1 : split_sum_parts(p);
 
     hipError_t e;
     if (options && options->ev_main_start) {

@@ -94,6 +94,9 @@ struct DecideIO {
     long long n_rows;           // batch * K * L
     int nlev;
     const double *s_arr;
+    const double *s_part;       // s_parts > 1: the sums arrive as s_parts partial sums per row ([n_rows][kPendParts])
+    double *s_store;            //              and the complete ones are stored here by the writing workgroup
+    int s_parts;
     double *log_nu_out, *log_P_out, *h_out, *eta_out;
     int32_t *state_out;
     int32_t *accepted_len, *accepted_draft_idx, *out_tokens;
@@ -137,7 +140,15 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
         if (idx == KL) { *u_final_out = e; continue; }
         const int k = idx / L, i = idx % L + 1;
-        const double s = i < L ? s_arr[base + k * L + i] : 0.0;
+        double s = 0.0;
+        if (i < L) {
+            if (io.s_parts > 1) {                           // in part order: the same bits in every workgroup
+                for (int q = 0; q < io.s_parts; ++q) s += io.s_part[(base + k * L + i) * kPendParts + q];
+                if (write) io.s_store[base + k * L + i] = s;
+            } else {
+                s = s_arr[base + k * L + i];
+            }
+        }
         double log2nu = 0.0, log2P = 0.0;
         for (int j = 0; j < i; ++j) {
             log2nu += tq[k * L + j] - tp[k * L + j];
@@ -723,6 +734,9 @@ hipError_t launch_final_typed(const Problem &p)
     io.n_rows = static_cast<long long>(p.batch) * p.K * p.L;
     io.nlev = p.pend_levels;
     io.s_arr = reinterpret_cast<const double *>(p.ws + p.lay.s);
+    io.s_part = reinterpret_cast<const double *>(p.ws + p.lay.pend_part);
+    io.s_store = reinterpret_cast<double *>(p.ws + p.lay.s);
+    io.s_parts = p.s_parts;
     io.log_nu_out = reinterpret_cast<double *>(p.ws + p.lay.log_nu);
     io.log_P_out = reinterpret_cast<double *>(p.ws + p.lay.log_P);
     io.h_out = reinterpret_cast<double *>(p.ws + p.lay.h);

@@ -32,12 +32,14 @@ struct Workspace {
     size_t pend_off;   // int32  [kMaxPend][B+1]  per level: rows the level modifies in the prefixes before b (two-pass schedule)
     size_t pend_part;  // double [B*K*L][kPendParts]  partial normalisers of a modified row shared among workgroups
     size_t pend_cnt;   // int32  [B*K*L]  workgroups of a shared row that have stored their partial normaliser
+    size_t stat_part;  // Row0Part [B*K*L][2][kRowParts]  partial row statistics (two-pass schedule, small batches)
     size_t row0;       // Row0Part [B][2][kRow0Parts]  partial statistics of the rows 0 a prefix's drafts share (chain schedule)
     size_t total;
     int nseg;
 };
 
 constexpr int kPendParts = 16;                 // workgroups a modified row's normaliser is shared among, at most
+constexpr int kRowParts = 16;                  // workgroups a row is shared among at most when the batch is small
 constexpr int kRow0Parts = 16;                 // slices a shared row 0 is reduced in
 struct Row0Part { double ref; double Z; };     // sum over the slice of 2^(c z - ref), ref an integer
 
@@ -68,10 +70,13 @@ struct Problem {
     double *state_carry;           // [kMaxPend][batch]
     int32_t *state_count;          // [kMaxPend][batch]
     bool shared_row0;              // rows 0 of a prefix's drafts are copies of one another (caller's statement)
+    int s_parts;                   // > 1: the sums of Eq. (hik) are left as this many partial sums per row (small batches)
 };
 
 // Schedule "split": statistics kernel, then a second pass for the sums of Eq. (hik).
 hipError_t launch_split_main(const Problem &p);
+// Parts the two-pass schedule leaves every Eq. (hik) sum in for this problem (1: the sums are complete).
+int split_sum_parts(const Problem &p);
 
 // Schedule "chain": one workgroup per (prefix, draft) keeps each row pair on chip between
 // the statistics sweep and the Eq. (hik) sweep.  chain_supported() says whether the shape

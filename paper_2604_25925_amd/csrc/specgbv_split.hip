@@ -21,6 +21,8 @@ namespace specgbv {
 namespace {
 
 constexpr int kStatThreads = 512;
+constexpr int kMaxRows = 64;         // rows of a draft (L <= 62)
+static_assert(kRowParts <= kPendParts, "the partial Eq. (hik) sums use the level passes' buffer");
 
 // What the level passes need before they start (pending modifications only): per level l and prefix b the
 // number of rows the level modifies in the prefixes before b, K * sum_{b' < b} clamp(count[l][b'], 0, L), with the
@@ -105,6 +107,148 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
         if (is_draft) { stats[pair].lse2_p = lse2; stats[pair].tok2_p = tok2; }
         else { stats[pair].lse2_q = lse2; stats[pair].tok2_q = tok2; }
     }
+}
+
+// ---- small batches: rows shared among workgroups
+//
+// With few rows a workgroup per row leaves most of the chip idle and every workgroup pays the latency of
+// streaming a whole row alone (16 - 21 us per kernel at one prefix, whatever the bandwidth).  Each row (pair) is
+// then cut into P parts: k_row_stats_parts leaves partial statistics with integral reference exponents,
+// k_ot_sum_parts combines the ones each of its workgroups needs (and stores the RowStat entries) and leaves P
+// partial sums per row, which the final-token kernel adds up in part order.  No workgroup waits for another one.
+
+// grid (row pairs * P, 2): block (pair * P + part, 0 / 1) reduces part `part` of the target / draft row of the pair
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kStatThreads)
+k_row_stats_parts(const T *__restrict__ target, const T *__restrict__ draft, int L, int V, float c, int P,
+                  Row0Part *__restrict__ parts)
+{
+    __shared__ double sh_d[kStatThreads / kWave];
+    __shared__ float sh_f[kStatThreads / kWave];
+    const long long pair = blockIdx.x / P;        // (b*K + k)*L + r
+    const int part = static_cast<int>(blockIdx.x % P);
+    const int r = static_cast<int>(pair % L);
+    const long long bk = pair / L;
+    const bool is_draft = blockIdx.y == 1;
+    const T *row = is_draft ? draft + (bk * L + r) * static_cast<long long>(V)
+                            : target + (bk * (L + 1) + r) * static_cast<long long>(V);
+    constexpr int PV = Elem<T>::kPerVec;
+    const int units = VEC ? V / PV : V;
+    const int per = (units + P - 1) / P;
+    const int lo = part * per, hi = lo + per < units ? lo + per : units;
+    RunningSum acc;
+    if (VEC) {
+        int i = lo + static_cast<int>(threadIdx.x);
+        for (; i + kStatThreads < hi; i += 2 * kStatThreads) {            // two loads in flight per thread
+            const U4 a = load16(row + static_cast<long long>(i) * PV);
+            const U4 b2 = load16(row + static_cast<long long>(i + kStatThreads) * PV);
+            float z[PV];
+            Elem<T>::unpack(a, z); acc.add(z, c);
+            Elem<T>::unpack(b2, z); acc.add(z, c);
+        }
+        if (i < hi) {
+            float z[PV];
+            Elem<T>::unpack(load16(row + static_cast<long long>(i) * PV), z);
+            acc.add(z, c);
+        }
+    } else {
+        for (int x = lo + static_cast<int>(threadIdx.x); x < hi; x += kStatThreads) {
+            const float z[1] = {Elem<T>::scalar(row + x)};
+            acc.add(z, c);
+        }
+    }
+    const float M = block_max(acc.m2, sh_f);
+    const double mine = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));
+    const double total = block_sum(acc.Z > 0.0f ? mine : 0.0, sh_d);
+    if (threadIdx.x == 0) {
+        Row0Part out;
+        out.ref = floor(static_cast<double>(M));
+        out.Z = total * exp2(static_cast<double>(M) - out.ref);
+        parts[(pair * 2 + (is_draft ? 1 : 0)) * kRowParts + part] = out;
+    }
+}
+
+// log2 sum_x 2^(c z[x]) of a row from its parts' sums (combined in part order: the same bits wherever it is done)
+__device__ __forceinline__ double lse2_from_parts(const Row0Part *pp, int P)
+{
+    double ref = -1.0e300;
+    for (int q = 0; q < P; ++q)
+        if (pp[q].Z > 0.0 && pp[q].ref > ref) ref = pp[q].ref;
+    double Z = 0.0;
+    for (int q = 0; q < P; ++q) {
+        const double d = pp[q].ref - ref;                     // an integer <= 0
+        if (pp[q].Z > 0.0 && d > -2000.0) Z += ldexp(pp[q].Z, static_cast<int>(d));
+    }
+    return ref + log2(Z);
+}
+
+// grid rows * P, rows = batch * K * (L - 1): block row * P + part sums part `part` of the Eq. (hik) terms of row
+// pair i = 1 .. L-1 of a draft.  With stat_P > 1 the statistics of the draft's rows 0 .. i are still in parts
+// (k_row_stats_parts): every workgroup combines the ones it needs, and part 0 stores the RowStat entry of its
+// row (the workgroup of row 1 also that of row 0, and clears the arrival counter of the final-token kernel).
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(kStatThreads)
+k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int K, int L,
+               int V, float c, int P, const Row0Part *__restrict__ stat_parts, int stat_P, RowStat *stats,
+               int32_t *__restrict__ final_counter, double *__restrict__ s_part)
+{
+    __shared__ double sh_d[kStatThreads / kWave];
+    __shared__ double sh_lse[2 * kMaxRows], sh_tok[2 * kMaxRows];
+    const long long idx = blockIdx.x / P;         // bk*(L-1) + (i-1)
+    const int part = static_cast<int>(blockIdx.x % P);
+    const int i = static_cast<int>(idx % (L - 1)) + 1;
+    const long long bk = idx / (L - 1);
+    const long long pair = bk * L + i;
+    RowStat st;
+    double log2nu = 0.0;
+    if (stat_P > 1) {
+        for (int t = threadIdx.x; t < 2 * (i + 1); t += kStatThreads) {
+            const int j = t >> 1, m = t & 1;
+            const long long pj = bk * L + j;
+            sh_lse[t] = lse2_from_parts(stat_parts + (pj * 2 + m) * kRowParts, stat_P);
+            int tok = tokens[pj];
+            tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+            const T *row = m ? draft + pj * static_cast<long long>(V) : target + (bk * (L + 1) + j) * static_cast<long long>(V);
+            sh_tok[t] = static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c);
+        }
+        __syncthreads();
+        st.lse2_q = sh_lse[2 * i]; st.lse2_p = sh_lse[2 * i + 1];
+        st.tok2_q = sh_tok[2 * i]; st.tok2_p = sh_tok[2 * i + 1];
+        for (int j = 0; j < i; ++j) log2nu += (sh_tok[2 * j] - sh_lse[2 * j]) - (sh_tok[2 * j + 1] - sh_lse[2 * j + 1]);
+        if (part == 0 && threadIdx.x == 0) {
+            stats[pair] = st;
+            if (i == 1) {
+                RowStat s0;
+                s0.lse2_q = sh_lse[0]; s0.lse2_p = sh_lse[1]; s0.tok2_q = sh_tok[0]; s0.tok2_p = sh_tok[1];
+                stats[bk * L] = s0;
+                if (bk % K == 0) final_counter[bk / K] = 0;
+            }
+        }
+    } else {
+        st = stats[pair];
+        for (int j = 0; j < i; ++j) {
+            const RowStat a = stats[bk * L + j];
+            log2nu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
+        }
+    }
+    const float shift_q = static_cast<float>(st.lse2_q);
+    const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
+    const T *rp = draft + pair * static_cast<long long>(V);
+    constexpr int N = VEC ? Elem<T>::kPerVec : 1;
+    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu);
+    const int units = VEC ? V / N : V;
+    const int per = (units + P - 1) / P;
+    const int lo = part * per, hi = lo + per < units ? lo + per : units;
+    float acc = 0.0f;
+    for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+        float wq[N], w[N];
+        ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc += w[j];
+    });
+    const double total = block_sum(static_cast<double>(acc), sh_d);
+    if (threadIdx.x == 0)
+        s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q);
 }
 
 // One level of pending modification (the levels below it are done: their PendRow entries are read).
@@ -280,6 +424,27 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
         s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
 }
 
+int compute_units()
+{
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+    }
+    return cached[dev];
+}
+
+// Parts a row is cut into so that about four workgroups per compute unit are launched (1: one workgroup per row).
+int row_parts(long long workgroups_per_row_unit, int V)
+{
+    if (V < 8192 || workgroups_per_row_unit < 1) return 1;         // short rows: nothing to share
+    const long long want = 4LL * compute_units() / workgroups_per_row_unit;
+    // below four parts the partial sums' extra steps cost what the sharing gains (measured)
+    return static_cast<int>(want < 4 ? 1 : (want > kRowParts ? kRowParts : want));
+}
+
 template <typename T>
 hipError_t launch_typed(const Problem &p)
 {
@@ -295,13 +460,26 @@ hipError_t launch_typed(const Problem &p)
     int32_t *pend_off = reinterpret_cast<int32_t *>(p.ws + p.lay.pend_off);
     int32_t *pend_cnt = p.pend_levels > 0 ? reinterpret_cast<int32_t *>(p.ws + p.lay.pend_cnt) : nullptr;
     double *pend_part = reinterpret_cast<double *>(p.ws + p.lay.pend_part);
-    const dim3 g1(static_cast<unsigned>(pairs + p.pend_levels), 2);
-    if (vec)
-        hipLaunchKernelGGL((k_row_stats<T, true>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
-                           p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt);
-    else
-        hipLaunchKernelGGL((k_row_stats<T, false>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
-                           p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt);
+    // rows shared among workgroups (small batches); the sums' kernel then finishes the statistics, so L >= 2
+    const int stat_parts = (p.pend_levels > 0 || p.s_parts < 2) ? 1 : row_parts(2 * pairs, p.V);
+    Row0Part *stat_part = reinterpret_cast<Row0Part *>(p.ws + p.lay.stat_part);
+    if (stat_parts > 1) {
+        const dim3 gs(static_cast<unsigned>(pairs * stat_parts), 2);
+        if (vec)
+            hipLaunchKernelGGL((k_row_stats_parts<T, true>), gs, dim3(kStatThreads), 0, p.stream, target, draft, p.L, p.V,
+                               p.c, stat_parts, stat_part);
+        else
+            hipLaunchKernelGGL((k_row_stats_parts<T, false>), gs, dim3(kStatThreads), 0, p.stream, target, draft, p.L, p.V,
+                               p.c, stat_parts, stat_part);
+    } else {
+        const dim3 g1(static_cast<unsigned>(pairs + p.pend_levels), 2);
+        if (vec)
+            hipLaunchKernelGGL((k_row_stats<T, true>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
+                               p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt);
+        else
+            hipLaunchKernelGGL((k_row_stats<T, false>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
+                               p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     PendRow *pend = reinterpret_cast<PendRow *>(p.ws + p.lay.pend);
@@ -321,6 +499,16 @@ hipError_t launch_typed(const Problem &p)
     }
     if (p.L < 2) return hipSuccess;
     const long long rows = static_cast<long long>(p.batch) * p.K * (p.L - 1);
+    if (p.s_parts > 1) {                            // small batch: partial sums, added up by the final-token kernel
+        const dim3 gq(static_cast<unsigned>(rows * p.s_parts));
+        if (vec)
+            hipLaunchKernelGGL((k_ot_sum_parts<T, true>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, p.K,
+                               p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part);
+        else
+            hipLaunchKernelGGL((k_ot_sum_parts<T, false>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, p.K,
+                               p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part);
+        return hipGetLastError();
+    }
     const dim3 g2(static_cast<unsigned>(rows));
 #define SPECGBV_OT_LAUNCH(VEC, PEND)                                                                           \
     hipLaunchKernelGGL((k_ot_sum<T, VEC, PEND>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L, \
@@ -332,6 +520,12 @@ hipError_t launch_typed(const Problem &p)
 }
 
 }  // namespace
+
+int split_sum_parts(const Problem &p)
+{
+    if (p.pend_levels > 0 || p.L < 2) return 1;
+    return row_parts(static_cast<long long>(p.batch) * p.K * (p.L - 1), p.V);
+}
 
 hipError_t launch_split_main(const Problem &p)
 {

@@ -62,6 +62,17 @@ def test_cfg5_reduced_batch(algo):
     _algo_or_skip(algo, lambda: check_case(t, d, tok, w.temperature, 0, 0, algo, "cfg5/B2"))
 
 
+@pytest.mark.parametrize("B", [1, 2, 3])
+@pytest.mark.parametrize("name", ["cfg4", "cfg3"])
+def test_small_batches_share_rows_among_workgroups(name, B):
+    # with a handful of prefixes the two-pass schedule cuts every row into parts (partial statistics and partial
+    # sums of Eq. (hik), combined in part order); batch 1 is the common serving case
+    w = with_batch(WORKLOADS[name], B)
+    t, d, tok = make_inputs(w, seed=3)
+    for off in (0, 1):
+        check_case(t, d, tok, w.temperature, 0, off, "auto", "%s/B%d small batch" % (name, B))
+
+
 def test_cfg4_full_size_sampled_prefixes():
     """The benchmark configuration at full size in the launch configuration bench.py times
     (default schedule); the oracle recomputes 4 of the 32 prefixes."""
