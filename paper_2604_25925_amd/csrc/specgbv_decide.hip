@@ -134,11 +134,8 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         tp[idx] = st.tok2_p - st.lse2_p;
         lq[idx] = st.lse2_q; lp[idx] = st.lse2_p;
         tok[idx] = tokens[base + idx];
-    }
-    __syncthreads();
-    for (int idx = tid; idx <= KL; idx += kDecideThreads) {
-        const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
-        if (idx == KL) { *u_final_out = e; continue; }
+        // the Eq. (hik) sum this thread needs for entry idx of the table below, loaded alongside the statistics
+        // (one memory latency instead of two); parked where the entry's log2 nu goes afterwards
         const int k = idx / L, i = idx % L + 1;
         double s = 0.0;
         if (i < L) {
@@ -149,6 +146,14 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
                 s = s_arr[base + k * L + i];
             }
         }
+        l2nu[idx] = s;
+    }
+    __syncthreads();
+    for (int idx = tid; idx <= KL; idx += kDecideThreads) {
+        const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
+        if (idx == KL) { *u_final_out = e; continue; }
+        const int k = idx / L, i = idx % L + 1;
+        const double s = l2nu[idx];                         // parked by this thread above
         double log2nu = 0.0, log2P = 0.0;
         for (int j = 0; j < i; ++j) {
             log2nu += tq[k * L + j] - tp[k * L + j];
