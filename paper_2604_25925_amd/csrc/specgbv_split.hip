@@ -183,16 +183,21 @@ __device__ __forceinline__ double lse2_from_parts(const Row0Part *pp, int P)
 }
 
 // grid rows * P, rows = batch * K * (L - 1): block row * P + part sums part `part` of the Eq. (hik) terms of row
-// pair i = 1 .. L-1 of a draft.  With stat_P > 1 the statistics of the draft's rows 0 .. i are still in parts
+// pair i = 1 .. L-1 of a draft (PEND: against the row as the pending levels leave it, exactly as k_ot_sum does).
+// With stat_P > 1 the statistics of the draft's rows 0 .. i are still in parts
 // (k_row_stats_parts): every workgroup combines the ones it needs, and part 0 stores the RowStat entry of its
 // row (the workgroup of row 1 also that of row 0, and clears the arrival counter of the final-token kernel).
-template <typename T, bool VEC>
+template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kStatThreads)
 k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int K, int L,
                int V, float c, int P, const Row0Part *__restrict__ stat_parts, int stat_P, RowStat *stats,
-               int32_t *__restrict__ final_counter, double *__restrict__ s_part)
+               int32_t *__restrict__ final_counter, double *__restrict__ s_part, const PendRow *__restrict__ pend,
+               long long n_rows, int nlev)
 {
     __shared__ double sh_d[kStatThreads / kWave];
+    __shared__ PendTable sh_tab;                  // PEND: the levels that modify this row
+    __shared__ PendRow sh_pr[kMaxPend];
+    __shared__ double sh_sumN;
     __shared__ double sh_lse[2 * kMaxRows], sh_tok[2 * kMaxRows];
     const long long idx = blockIdx.x / P;         // bk*(L-1) + (i-1)
     const int part = static_cast<int>(blockIdx.x % P);
@@ -226,34 +231,53 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
         }
     } else {
         st = stats[pair];
-        for (int j = 0; j < i; ++j) {
-            const RowStat a = stats[bk * L + j];
-            log2nu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
-        }
+        if (!PEND)
+            for (int j = 0; j < i; ++j) {
+                const RowStat a = stats[bk * L + j];
+                log2nu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
+            }
+    }
+    double sumN = 0.0;
+    if (PEND) {                                   // as in k_ot_sum: the row as the pending levels leave it
+        log2nu = pend_block_ratio(stats, pend, n_rows, nlev, bk * L, i, sh_d);
+        if (static_cast<int>(threadIdx.x) < nlev) sh_pr[threadIdx.x] = pend[static_cast<long long>(threadIdx.x) * n_rows + pair];
+        __syncthreads();
+        if (threadIdx.x == 0) sh_sumN = pend_build_table(sh_pr, 1, nlev, 0, st.lse2_p - st.lse2_q, sh_tab);
+        __syncthreads();
+        sumN = sh_sumN;
     }
     const float shift_q = static_cast<float>(st.lse2_q);
     const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
     const T *rp = draft + pair * static_cast<long long>(V);
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
-    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu);
+    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu - sumN);
     const int units = VEC ? V / N : V;
     const int per = (units + P - 1) / P;
     const int lo = part * per, hi = lo + per < units ? lo + per : units;
     float acc = 0.0f;
-    for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
-        float wq[N], w[N];
-        ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
+    if (PEND && sh_tab.n > 0) {                   // uniform over the workgroup
+        for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+            float wq[N], w[N];
+            pending_weights(zq, zp, c, shift_q, sh_tab, rc, K, wq, w);
 #pragma unroll
-        for (int j = 0; j < N; ++j) acc += w[j];
-    });
+            for (int j = 0; j < N; ++j) acc += w[j];
+        });
+    } else {
+        for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+            float wq[N], w[N];
+            ot_weights(zq, zp, c, shift_q, rc, K, wq, w);
+#pragma unroll
+            for (int j = 0; j < N; ++j) acc += w[j];
+        });
+    }
     const double total = block_sum(static_cast<double>(acc), sh_d);
     if (threadIdx.x == 0)
-        s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q);
+        s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
 }
 
 // One level of pending modification (the levels below it are done: their PendRow entries are read).
-// grid.x = batch * K * L.  Workgroup w first writes the empty entry of row pair w if the level leaves that row
-// alone.  Then it takes a unit of work: the T rows the level modifies are enumerated prefix by prefix (off[b] rows
+// grid.x >= batch * K * L.  Workgroup w first writes the empty entry of row pair w (if there is one) if the level
+// leaves that row alone.  Then it takes a unit of work: the T rows the level modifies are enumerated prefix by prefix (off[b] rows
 // before prefix b; within a prefix row index slowest) and each is shared among P = min(grid / T, kPendParts)
 // workgroups, so that a level with few rows left still occupies the chip (one workgroup streaming a whole row
 // pair with several levels of arithmetic per entry takes 100 - 200 us).  Unit u = blockIdx.x < T * P is part
@@ -484,7 +508,9 @@ hipError_t launch_typed(const Problem &p)
     if (e != hipSuccess) return e;
     PendRow *pend = reinterpret_cast<PendRow *>(p.ws + p.lay.pend);
     for (int level = 0; level < p.pend_levels; ++level) {
-        const dim3 gp(static_cast<unsigned>(pairs));
+        // one workgroup per row pair, but at least about four per compute unit, so that a small batch's rows can be shared
+        const long long min_grid = 4LL * compute_units();
+        const dim3 gp(static_cast<unsigned>(pairs > min_grid ? pairs : min_grid));
         const double *carry_l = p.pend_carry + static_cast<size_t>(level) * p.batch;
         const int32_t *count_l = p.pend_count + static_cast<size_t>(level) * p.batch;
         const int32_t *off_l = pend_off + static_cast<size_t>(level) * (p.batch + 1);
@@ -501,12 +527,13 @@ hipError_t launch_typed(const Problem &p)
     const long long rows = static_cast<long long>(p.batch) * p.K * (p.L - 1);
     if (p.s_parts > 1) {                            // small batch: partial sums, added up by the final-token kernel
         const dim3 gq(static_cast<unsigned>(rows * p.s_parts));
-        if (vec)
-            hipLaunchKernelGGL((k_ot_sum_parts<T, true>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, p.K,
-                               p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part);
-        else
-            hipLaunchKernelGGL((k_ot_sum_parts<T, false>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, p.K,
-                               p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part);
+#define SPECGBV_OTP_LAUNCH(VEC, PEND)                                                                                 \
+    hipLaunchKernelGGL((k_ot_sum_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, p.K, \
+                       p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part, pend, pairs,         \
+                       p.pend_levels)
+        if (p.pend_levels > 0) { if (vec) SPECGBV_OTP_LAUNCH(true, true); else SPECGBV_OTP_LAUNCH(false, true); }
+        else { if (vec) SPECGBV_OTP_LAUNCH(true, false); else SPECGBV_OTP_LAUNCH(false, false); }
+#undef SPECGBV_OTP_LAUNCH
         return hipGetLastError();
     }
     const dim3 g2(static_cast<unsigned>(rows));
@@ -523,7 +550,7 @@ hipError_t launch_typed(const Problem &p)
 
 int split_sum_parts(const Problem &p)
 {
-    if (p.pend_levels > 0 || p.L < 2) return 1;
+    if (p.L < 2) return 1;
     return row_parts(static_cast<long long>(p.batch) * p.K * (p.L - 1), p.V);
 }
 
