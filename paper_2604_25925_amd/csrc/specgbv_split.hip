@@ -10,7 +10,11 @@
 //   k_pend_norm : per modified row, the block ratio mu Algorithm 2 uses there, the normaliser
 //                 N = sum_x q[x] max(1 - p[x] / (mu q[x]), 0)^K of q_new, and the drafted
 //                 token's factor,
-// and k_ot_sum evaluates its sum against q_new = q t^K / N formed per entry.
+// and k_ot_sum evaluates its sum against q_new = q t^K / N formed per entry (one pass of k_pend_norm per
+// pending level; a level's rows are shared among workgroups when it has few of them left).
+//
+// Small batches, where a workgroup per row would leave most of the chip idle, use k_row_stats_parts and
+// k_ot_sum_parts instead: every row is cut into parts, combined in part order by the consumers.
 //
 // Any V and any alignment is accepted (rows whose byte length is not a multiple of 16
 // take the scalar-load path).  This schedule reads every row pair twice; it is the
