@@ -21,7 +21,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-from specgbv_synth import WORKLOADS, make_prefix  # noqa: E402
+from specgbv_synth import WORKLOADS, make_prefix, with_batch  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 
@@ -31,8 +31,10 @@ def _gen(args):
     return make_prefix(WORKLOADS[name], seed, b)
 
 
-def generate(name: str, seed: int, workers: int):
+def generate(name: str, seed: int, workers: int, batch: int = 0):
     w = WORKLOADS[name]
+    if batch > 0:
+        w = with_batch(w, batch)                       # the first `batch` prefixes of the workload
     store = np.uint16 if w.dtype == "bf16" else np.float32
     target = np.empty((w.batch, w.K, w.L + 1, w.V), dtype=store)
     draft = np.empty((w.batch, w.K, w.L, w.V), dtype=store)
@@ -48,9 +50,14 @@ def generate(name: str, seed: int, workers: int):
     return target, draft, tokens
 
 
+FULL_WORKLOAD = True        # False with --batch: the committed traffic figures are those of the whole workload
+
+
 def committed_traffic(tag: str):
     """HBM bytes per call from the committed rocprofv3 --pmc summary profiles/hbm_traffic_<tag>.txt (FETCH_SIZE +
     WRITE_SIZE, calibrated against a plain copy), or None."""
+    if not FULL_WORKLOAD:
+        return None
     path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % tag)
     if os.path.exists(path):
         for line in open(path):
@@ -251,6 +258,9 @@ def main() -> int:
                          "prefix, and the algorithmic bytes are counted accordingly")
     ap.add_argument("--input-sets", type=int, default=1,
                     help="iterate only: cycle through this many independent input sets (seeds seed, seed+1, ...)")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="use only the first N prefixes of the workload (0 = all); a reduced batch is not the benchmark "
+                         "configuration: for latency measurements at small batches")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -265,13 +275,20 @@ def main() -> int:
         return 2
 
     w = WORKLOADS[a.workload]
+    if a.batch > 0:
+        if a.batch > w.batch:
+            print("bench.py: --batch exceeds the workload's %d prefixes" % w.batch, file=sys.stderr)
+            return 2
+        w = with_batch(w, a.batch)
+        global FULL_WORKLOAD
+        FULL_WORKLOAD = False
     # inputs are generated on the host before the GPU is touched (worker processes fork here)
     t0 = time.time()
-    target, draft, tokens = generate(a.workload, a.seed, workers=a.workers or min(16, os.cpu_count() or 1))
+    target, draft, tokens = generate(a.workload, a.seed, workers=a.workers or min(16, os.cpu_count() or 1), batch=a.batch)
     gen_s = time.time() - t0
     more_sets = []
     if a.op == "iterate":
-        more_sets = [generate(a.workload, a.seed + j, workers=a.workers or min(16, os.cpu_count() or 1))
+        more_sets = [generate(a.workload, a.seed + j, workers=a.workers or min(16, os.cpu_count() or 1), batch=a.batch)
                      for j in range(1, max(1, a.input_sets))]
 
     import torch
