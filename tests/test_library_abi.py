@@ -135,3 +135,31 @@ def test_python_binding_validates_tensors():
         sg.specgbv_verify(t, d, tok, 1.0, 0, 0)             # CPU tensors: no silent fallback
     with pytest.raises(ValueError):
         sg.specgbv_verify(t, d[:, :, :2], tok, 1.0, 0, 0)
+
+
+def test_ctypes_structures_match_the_c_header(tmp_path):
+    """The binding's ctypes mirrors of specgbv_options and specgbv_intermediates have the layout the C compiler
+    gives the header's structures (sizes and every field offset), so a field added on one side only is caught."""
+    import ctypes
+    import shutil
+    import subprocess
+    from paper_2604_25925_amd import binding
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    header = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "specgbv.h")
+    lines = ['#include <stddef.h>', '#include <stdio.h>', '#include "%s"' % header, 'int main(void) {']
+    for cname, cls in (("specgbv_options", binding._Options), ("specgbv_intermediates", binding._Intermediates)):
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (cname, cname))
+        for field, _ in cls._fields_:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (cname, field, cname, field))
+    lines += ['return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run([cc, "-std=c99", "-o", str(exe), str(src)], check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, cls in (("specgbv_options", binding._Options), ("specgbv_intermediates", binding._Intermediates)):
+        assert int(got[cname]) == ctypes.sizeof(cls), cname
+        for field, _ in cls._fields_:
+            assert int(got["%s.%s" % (cname, field)]) == getattr(cls, field).offset, "%s.%s" % (cname, field)
