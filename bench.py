@@ -242,8 +242,11 @@ def bench_sample(a, w, sg, torch, dl):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # defaults: 0.15 s of GPU work.  The shader clock needs some tens of milliseconds of sustained load to settle
+    # (a serving GPU is always under load); 50 steps after 5 warm-up calls, 15 ms in all, measure the ramp instead
+    # and read 8 - 10 % slower
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--algo", default="auto", choices=["auto", "split", "chain"])
     ap.add_argument("--op", default="verify", choices=["verify", "modify", "sample", "pending", "iterate"],
