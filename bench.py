@@ -242,9 +242,9 @@ def bench_sample(a, w, sg, torch, dl):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # defaults: 0.15 s of GPU work.  The shader clock needs some tens of milliseconds of sustained load to settle
-    # (a serving GPU is always under load); 50 steps after 5 warm-up calls, 15 ms in all, measure the ramp instead
-    # and read 8 - 10 % slower
+    # defaults: 0.15 s of GPU work.  Under the streaming kernel's load the shader clock takes some tens of
+    # milliseconds to settle (a serving GPU runs such kernels all the time); 50 steps after 5 warm-up calls, 15 ms
+    # in all, measure mostly that transient and read 8 - 10 % slower
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
