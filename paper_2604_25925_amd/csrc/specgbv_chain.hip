@@ -81,7 +81,7 @@ __device__ __forceinline__ void pow_inplace(float (&t)[N], int K)
 // (Its own vmcnt arithmetic does not see these loads, so its waits are conservative.)
 __device__ __forceinline__ void lds_fill16(const void *src_base_uniform, unsigned lane_byte_off, unsigned lds_dst_wave_uniform)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
                  :
                  : "v"(lane_byte_off), "s"(src_base_uniform), "s"(lds_dst_wave_uniform)
                  : "memory", "m0");
@@ -141,7 +141,7 @@ __device__ __forceinline__ U4 load_vec(const void *base_uniform, unsigned lane_b
     typedef const __attribute__((address_space(1))) char *GlobalBytes;
     GlobalBytes b = (GlobalBytes)base_uniform;
     asm volatile("" : "+s"(b));
-    const V4 v = *(const __attribute__((address_space(1))) V4 *)(b + lane_byte_off);
+    const V4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) V4 *)(b + lane_byte_off));
     return U4{v.x, v.y, v.z, v.w};
 }
 template <typename T>
@@ -224,14 +224,14 @@ __device__ __noinline__ ExactStats exact_row_stats(const T *row, int nvec, float
     constexpr int PV = Elem<T>::kPerVec;
     float m = -3.0e38f;
     for (int v = threadIdx.x; v < nvec; v += kChainThreads)
-        m = fmaxf(m, vec_max<T>(load16(row + static_cast<long long>(v) * PV)));
+        m = fmaxf(m, vec_max<T>(load16_stream(row + static_cast<long long>(v) * PV)));
     float dummy = m;
     block_max2(m, dummy, sh_f);
     const float ref = m * c;
     float Z = 0.0f;
     for (int v = threadIdx.x; v < nvec; v += kChainThreads) {
         float z[PV];
-        Elem<T>::unpack(load16(row + static_cast<long long>(v) * PV), z);
+        Elem<T>::unpack(load16_stream(row + static_cast<long long>(v) * PV), z);
 #pragma unroll
         for (int j = 0; j < PV; ++j) Z += exp2_fast(fmaf(z[j], c, -ref));
     }
@@ -406,7 +406,7 @@ k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, int K, i
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int idx = i + j * kRow0Threads;
-            v[j] = load16(row + static_cast<long long>(idx < hi ? idx : i) * PV);
+            v[j] = load16_stream(row + static_cast<long long>(idx < hi ? idx : i) * PV);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {

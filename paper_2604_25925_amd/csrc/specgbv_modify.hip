@@ -66,15 +66,15 @@ k_mod_stats(const T *__restrict__ target, const T *__restrict__ draft, const int
         const int nvec = V / PV;
         int v = threadIdx.x;
         for (; v + kModThreads < nvec; v += 2 * kModThreads) {          // two loads in flight per thread
-            const U4 a = load16(z_row + static_cast<long long>(v) * PV);
-            const U4 b = load16(z_row + static_cast<long long>(v + kModThreads) * PV);
+            const U4 a = load16_stream(z_row + static_cast<long long>(v) * PV);
+            const U4 b = load16_stream(z_row + static_cast<long long>(v + kModThreads) * PV);
             float z[PV];
             Elem<T>::unpack(a, z); acc.add(z, c);
             Elem<T>::unpack(b, z); acc.add(z, c);
         }
         if (v < nvec) {
             float z[PV];
-            Elem<T>::unpack(load16(z_row + static_cast<long long>(v) * PV), z);
+            Elem<T>::unpack(load16_stream(z_row + static_cast<long long>(v) * PV), z);
             acc.add(z, c);
         }
     } else {
@@ -285,8 +285,8 @@ k_carry_rows(const T *__restrict__ rows_q, const T *__restrict__ rows_p, const i
         const int nvec = V / PV;
         for (int v = threadIdx.x; v < nvec; v += kModThreads) {
             float z[PV];
-            Elem<T>::unpack(load16(rq + static_cast<long long>(v) * PV), z); aq.add(z, c);
-            Elem<T>::unpack(load16(rp + static_cast<long long>(v) * PV), z); ap.add(z, c);
+            Elem<T>::unpack(load16_stream(rq + static_cast<long long>(v) * PV), z); aq.add(z, c);
+            Elem<T>::unpack(load16_stream(rp + static_cast<long long>(v) * PV), z); ap.add(z, c);
         }
     } else {
         for (int x = threadIdx.x; x < V; x += kModThreads) {

@@ -91,7 +91,7 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
         const int nvec = V / PV;
         for (int i = threadIdx.x; i < nvec; i += kStatThreads) {
             float z[PV];
-            Elem<T>::unpack(load16(row + static_cast<long long>(i) * PV), z);
+            Elem<T>::unpack(load16_stream(row + static_cast<long long>(i) * PV), z);
             acc.add(z, c);
         }
     } else {
@@ -144,15 +144,15 @@ k_row_stats_parts(const T *__restrict__ target, const T *__restrict__ draft, int
     if (VEC) {
         int i = lo + static_cast<int>(threadIdx.x);
         for (; i + kStatThreads < hi; i += 2 * kStatThreads) {            // two loads in flight per thread
-            const U4 a = load16(row + static_cast<long long>(i) * PV);
-            const U4 b2 = load16(row + static_cast<long long>(i + kStatThreads) * PV);
+            const U4 a = load16_stream(row + static_cast<long long>(i) * PV);
+            const U4 b2 = load16_stream(row + static_cast<long long>(i + kStatThreads) * PV);
             float z[PV];
             Elem<T>::unpack(a, z); acc.add(z, c);
             Elem<T>::unpack(b2, z); acc.add(z, c);
         }
         if (i < hi) {
             float z[PV];
-            Elem<T>::unpack(load16(row + static_cast<long long>(i) * PV), z);
+            Elem<T>::unpack(load16_stream(row + static_cast<long long>(i) * PV), z);
             acc.add(z, c);
         }
     } else {
