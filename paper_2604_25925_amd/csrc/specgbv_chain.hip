@@ -790,10 +790,10 @@ bool chain_supports_pending(const Problem &p)
 
 // The chain schedule takes about the same time for any number of chains up to one per compute unit
 // (each workgroup streams its own rows), the two-pass schedule takes time in proportion to the
-// bytes: measured at V = 128256, bf16, L = 8 on 256 compute units they cross at 150 chains.
+// bytes: measured at V = 128256, bf16, L = 8 on 256 compute units they cross at about 170 chains.
 bool chain_preferred(const Problem &p)
 {
-    return chain_supported(p) && static_cast<long long>(p.batch) * p.K * 100 >= static_cast<long long>(resident_workgroups()) * 59;
+    return chain_supported(p) && static_cast<long long>(p.batch) * p.K * 100 >= static_cast<long long>(resident_workgroups()) * 66;
 }
 
 hipError_t launch_chain_main(const Problem &p)
