@@ -529,11 +529,13 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     __shared__ int sh_cnt[kMaxPend];                       //            rows every level modifies (this prefix)
     __shared__ PendScalars sh_row;                         //            float64 scalars of the current row
     __shared__ ChainPend sh_pend;                          //            the kernel argument, kept out of the scalar registers
-    __shared__ int sh_sum_done;                            //            the row in sweep 2 already has its sum (modified row)
     if constexpr (PEND) {
-        if (threadIdx.x == 0) { sh_pend = pend; sh_sum_done = 0; }
+        if (threadIdx.x == 0) sh_pend = pend;
         __syncthreads();
     }
+    // PEND only: the row that sweep 2 would take next already has its sum (a modified row gets it from the extra
+    // sweeps over the on-chip copy).  Every thread reads the flag between two barriers and carries it in a register.
+    bool sum_done = false;
 
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
@@ -577,7 +579,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         const long long bk_old = chain_of(g_old);
         const int r_old = first_row + g_old % rpc;
         bool do_sum = g >= 1 && r_old >= 1;                // rows >= 1 get their Eq. (hik) sum
-        if constexpr (PEND) do_sum = do_sum && __builtin_amdgcn_readfirstlane(sh_sum_done) == 0;
+        if constexpr (PEND) do_sum = do_sum && !sum_done;
         const T *qnew = target + (bk_new * (L + 1) + r_new) * static_cast<long long>(V);
         const T *pnew = draft + (bk_new * L + r_new) * static_cast<long long>(V);
         const T *qold = target + (bk_old * (L + 1) + r_old) * static_cast<long long>(V);
@@ -693,7 +695,10 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
                     }
                 }
                 __syncthreads();
-                if (tid == 0) sh_sum_done = sh_tab.n > 0;  // a modified row has its sum (or needs none: row 0)
+                // a modified row has its sum (or needs none: row 0).  sh_tab.n is final here and is not written
+                // again before the barrier that opens the next row's level passes, which every thread reaches
+                // only after this read.
+                sum_done = __builtin_amdgcn_readfirstlane(sh_tab.n) > 0;
                 tok_adj = sh_row.tok_adj;
             }
             // constants of this row's sweep 2 (next iteration)

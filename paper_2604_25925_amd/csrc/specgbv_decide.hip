@@ -246,22 +246,33 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
             sl.C2 = lse2_p - lse2_q + (tau == 0 ? 0.0 : l2nu[kf * L + tau - 1]);
             sl.shift_q = rintf(static_cast<float>(lse2_q));         // integral: partial sums rescale exactly
             sl.lse2_q = lse2_q;
-            if (io.pend) {                                          // levels that modify the row: q' = q prod t_l^K / N_l
-                double sumN = 0.0;
-                int n = 0;
-                for (int l = 0; l < io.nlev; ++l) {
-                    if (__builtin_amdgcn_readlane(prl.flag, l)) {
-                        sl.Cl[n] = lse2_p - lse2_q + lane_value(prl.log2mu, l) - sumN;
-                        pend_table_set(*tab_out, n, sl.Cl[n]);
-                        ++n;
-                        sumN += lane_value(prl.log2N, l);
-                    }
+        }
+    }
+    // Levels that modify the selected row: q' = q prod t_l^K / N_l.  The whole wave walks the levels (tau, kf and
+    // nlev are wave-uniform), so that every cross-lane read of the levels' entries happens with all lanes active
+    // and outside any divergent branch; lane 0 alone patches the selection.
+    if (io.pend && tau < L) {
+        const double lse2_q = lq[kf * L + tau], lse2_p = lp[kf * L + tau];
+        double sumN = 0.0;
+        int n = 0;
+        for (int l = 0; l < io.nlev; ++l) {
+            const int flag_l = __builtin_amdgcn_readlane(prl.flag, l);
+            const double mu_l = lane_value(prl.log2mu, l), N_l = lane_value(prl.log2N, l);
+            if (flag_l) {
+                const double Cl = lse2_p - lse2_q + mu_l - sumN;
+                if (lane == 0) {
+                    sel_out->Cl[n] = Cl;
+                    pend_table_set(*tab_out, n, Cl);
                 }
-                sl.npend = n;
-                tab_out->n = n;
-                sl.C2 -= sumN;
-                sl.lse2_q = lse2_q + sumN;
+                ++n;
+                sumN += N_l;
             }
+        }
+        if (lane == 0) {
+            sel_out->npend = n;
+            tab_out->n = n;
+            sel_out->C2 -= sumN;
+            sel_out->lse2_q = lse2_q + sumN;
         }
     }
     // position tau belongs to the final token, which the locating workgroup writes
