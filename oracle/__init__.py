@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.specgbv_oracle_ot_sum.restype = c_double
         L.specgbv_oracle_h_sub.argtypes = [c_double, c_double, c_double, c_int]
         L.specgbv_oracle_h_sub.restype = c_double
+        L.specgbv_oracle_ot_excess.argtypes = [POINTER(c_double), POINTER(c_double), c_int, c_double, c_int]
+        L.specgbv_oracle_ot_excess.restype = c_double
+        L.specgbv_oracle_h_sub_excess.argtypes = [c_double, c_double, c_double, c_int]
+        L.specgbv_oracle_h_sub_excess.restype = c_double
         L.specgbv_oracle_h_full.argtypes = [c_double, c_double, c_int]
         L.specgbv_oracle_h_full.restype = c_double
         L.specgbv_oracle_decision_scan.argtypes = [POINTER(c_double), POINTER(c_double), POINTER(c_int32),
@@ -125,6 +129,19 @@ def ot_sum(lq, lp, log_nu: float, K: int) -> float:
     lp = np.ascontiguousarray(lp, dtype=np.float64)
     assert lq.shape == lp.shape
     return float(lib().specgbv_oracle_ot_sum(_dp(lq), _dp(lp), lq.size, float(log_nu), int(K)))
+
+
+def ot_excess(lq, lp, log_nu: float, K: int) -> float:
+    """nu^2 (s - g) of Eq. (hik) for nu > 1 as a sum of non-negative terms (no cancellation)."""
+    lq = np.ascontiguousarray(lq, dtype=np.float64)
+    lp = np.ascontiguousarray(lp, dtype=np.float64)
+    assert lq.shape == lp.shape and lq.ndim == 1
+    return float(lib().specgbv_oracle_ot_excess(_dp(lq), _dp(lp), lq.size, float(log_nu), int(K)))
+
+
+def h_sub_excess(log_nu: float, log_P: float, E: float, K: int) -> float:
+    """Eq. (hik) for nu > 1 from E = ot_excess(...)."""
+    return float(lib().specgbv_oracle_h_sub_excess(float(log_nu), float(log_P), float(E), int(K)))
 
 
 def h_sub(log_nu: float, log_P: float, s: float, K: int) -> float:

@@ -34,7 +34,9 @@
  *     h_ik = nu_i (s_i - g_i) / (c_K(P_i) - nu_i (1 - s_i)),   i < L
  *     h_Lk = nu_L (1 - g_L) / c_K(P_L)
  * which is what this file evaluates (tests check it against the literal
- * equations in exact rational arithmetic).
+ * equations in exact rational arithmetic).  For nu_i > 1, where s_i - g_i cancels,
+ * Eq. (hik) is evaluated through the equivalent sum of non-negative terms described at
+ * specgbv_oracle_ot_excess.
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   - uniforms come from Philox4x32-10 (Salmon et al., SC'11) with
@@ -207,6 +209,70 @@ double specgbv_oracle_h_sub(double log_nu, double logP, double s, int K)
     return clamp01(num / den);
 }
 
+/*
+ * Eq. (hik) for nu > 1 without the difference s - g.
+ *
+ * For nu > 1 the numerator nu (s - g) of the rescaled Eq. (hik) subtracts two numbers that agree
+ * to about 1/nu^2: in float64 the difference is already wrong in the sixth digit at nu = 1e5 and
+ * meaningless beyond 1e8, although the quotient has a perfectly finite limit.  Both sums of the
+ * equation are expectations under q of the convex function phi(rho) = max(1 - rho/nu, 0)^K of
+ * the ratio rho = p[x]/q[x], whose mean is 1:  s = E_q phi(rho),  g = phi(1) = phi(E_q rho).
+ * Adding the vanishing term -phi'(1) E_q[rho - 1] gives a sum of non-negative terms,
+ *     s - g = sum_x q[x] b(rho_x),   b(rho) = phi(rho) - phi(1) - phi'(1) (rho - 1) >= 0,
+ * and with a = 1/nu, t1 = 1 - a, t = 1 - a rho each term has a closed form free of cancellation:
+ *     t > 0 :  b = a^2 (rho - 1)^2 H(t),   H(t) = sum_{m=0}^{K-2} (K-1-m) t1^(K-2-m) t^m
+ *              (from t^K - t1^K - K t1^(K-1) (t - t1) = (t - t1)^2 H(t))
+ *     t <= 0:  q b = t1^(K-1) (K a p - (1 + (K-1) a) q)          (phi(rho) = 0 there)
+ * The common factor a^2 is left out (it underflows for the ratios drafts of improbable
+ * tokens produce): the function returns E = nu^2 (s - g).
+ *
+ * The denominator c_K(P) - nu (1 - s) of Eq. (hik) equals [c_K(P) - c_K(a)] + nu (s - g), because
+ * nu (1 - g) = c_K(a); and c_K(P) - c_K(a) = (a - P) S2 with
+ *     S2 = sum_{j=1}^{K-1} sum_{m=0}^{j-1} (1-P)^m t1^(j-1-m) > 0,   a - P = a (1 - Q),
+ * Q = nu P the joint target probability of the block.  Hence, multiplying through by nu,
+ *     h_ik = E / (E + (1 - Q) S2).
+ * tests/test_oracle_primitives.py checks both functions against the literal Eq. (hik) in exact
+ * rational arithmetic, including block ratios of 1e30 and more.
+ */
+double specgbv_oracle_ot_excess(const double *lq, const double *lp, int V,
+                                double log_nu, int K)
+{
+    if (log_nu > 690.0) log_nu = 690.0;       /* keeps nu and 1/nu finite and positive; the result no longer depends on nu there */
+    const double a = exp(-log_nu);            /* 1/nu, in (0, 1) for nu > 1 */
+    const double t1 = -expm1(-log_nu);        /* 1 - a */
+    double E = 0.0;
+    for (int x = 0; x < V; ++x) {
+        const double d = lp[x] - lq[x];       /* log rho; +inf where q[x] = 0 */
+        const double t = 1.0 - a * exp(d);
+        if (t > 0.0) {
+            double H = 0.0;                   /* sum_m (K-1-m) t1^(K-2-m) t^m */
+            for (int m = 0; m <= K - 2; ++m) H += (double)(K - 1 - m) * ipow(t1, K - 2 - m) * ipow(t, m);
+            const double u = expm1(d);        /* rho - 1 */
+            E += exp(lq[x]) * u * u * H;
+        } else {
+            /* nu^2 q b = nu t1^(K-1) (K p - (nu + K - 1) q) */
+            const double nu = exp(log_nu);
+            E += nu * ipow(t1, K - 1) * ((double)K * exp(lp[x]) - (nu + (double)(K - 1)) * exp(lq[x]));
+        }
+    }
+    return E;
+}
+
+/* Eq. (hik) for nu > 1 from E = nu^2 (s - g). */
+double specgbv_oracle_h_sub_excess(double log_nu, double logP, double E, int K)
+{
+    const double t1 = -expm1(-log_nu);
+    const double A = -expm1(logP);            /* 1 - P */
+    double S2 = 0.0;
+    for (int j = 1; j <= K - 1; ++j)
+        for (int m = 0; m <= j - 1; ++m) S2 += ipow(A, m) * ipow(t1, j - 1 - m);
+    const double one_minus_Q = -expm1(log_nu + logP);
+    const double den = E + (one_minus_Q > 0.0 ? one_minus_Q : 0.0) * S2;
+    if (!(den > 0.0)) return 1.0;             /* 0/0: limit is 1 */
+    if (isinf(E)) return 1.0;
+    return clamp01(E / den);
+}
+
 /* Eq. (hLk), whole block, rescaled by P_L. */
 double specgbv_oracle_h_full(double log_nu, double logP, int K)
 {
@@ -363,8 +429,10 @@ static void verify_one(const void *target_logits, const void *draft_logits,
             /* OT sum of row r with the ratio of the length-r block (r = 0: nu = 1). */
             const double s = specgbv_oracle_ot_sum(lq, lp, V, lognu, K);
             if (r >= 1) {
-                /* Eq. (hik) for sub-block length i = r */
-                h[k * L + r - 1] = specgbv_oracle_h_sub(lognu, logP, s, K);
+                /* Eq. (hik) for sub-block length i = r; for nu > 1 in the form without s - g */
+                h[k * L + r - 1] = lognu > 0.0
+                    ? specgbv_oracle_h_sub_excess(lognu, logP, specgbv_oracle_ot_excess(lq, lp, V, lognu, K), K)
+                    : specgbv_oracle_h_sub(lognu, logP, s, K);
             }
             if (dbg) {
                 if (dbg->lse_q) dbg->lse_q[trow0 + r] = lse_q;

@@ -104,6 +104,77 @@ def test_rescaled_h_equals_literal_equations(V, L, K):
                 assert 0.0 <= got <= 1.0
 
 
+@pytest.mark.parametrize("V,L,K", [(2, 2, 1), (2, 3, 2), (3, 2, 3), (3, 3, 4), (4, 2, 8), (2, 4, 16), (5, 2, 5)])
+def test_cancellation_free_h_equals_literal_equation_where_nu_exceeds_one(V, L, K):
+    """Eq. (hik) for nu > 1 through the sum of non-negative terms (ot_excess, h_sub_excess) against the
+    literal equation in exact rationals, and nu^2 (s - g) against the exact difference."""
+    rng = np.random.default_rng(900 * V + 10 * L + K)
+    seen = 0
+    for _ in range(4):
+        p_of, q_of = ee.random_tables(rng, V, L)
+        for r in range(1, L):
+            for block in itertools.product(range(V), repeat=r):
+                P, Q = ee.joint(p_of, block), ee.joint(q_of, block)
+                if Q <= P:
+                    continue
+                seen += 1
+                exact = ee.h_literal(p_of, q_of, block, V, L, K)
+                log_nu, log_P, lq, lp = _float_view(p_of, q_of, block, V)
+                E = oracle.ot_excess(lq, lp, log_nu, K)
+                nu = Q / P
+                E_exact = nu * nu * (ee.ot_sum_joint(p_of, q_of, block, V, K) / Q - (1 - 1 / nu) ** K)
+                assert E >= 0 and abs(E - float(E_exact)) <= 1e-11 * (1 + float(E_exact)), (block, E, float(E_exact))
+                got = oracle.h_sub_excess(log_nu, log_P, E, K)
+                assert abs(got - float(exact)) < 1e-11, (block, got, float(exact))
+    assert seen >= 4
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("eps_exp", [6, 12, 30, 120])
+def test_cancellation_free_h_at_huge_block_ratios(K, eps_exp):
+    """A drafted token of draft probability 10^-eps_exp gives its block a ratio nu of that order; the literal
+    Eq. (hik), exact in rationals, has a finite value there, which the difference s - g cannot deliver in
+    float64 (the plain form is checked to be off once nu exceeds 1e8: that is why the other form exists)."""
+    eps = F(1, 10 ** eps_exp)
+    # row 0: token 0 is nearly impossible under the draft, likely under the target
+    p0 = [eps, F(2, 5) - eps, F(3, 5)]
+    q0 = [F(1, 2), F(1, 4), F(1, 4)]
+    # row 1 after token 0: an ordinary pair of distributions, one entry the target forbids almost entirely
+    p1 = [F(1, 5), F(3, 10), F(1, 2)]
+    q1 = [F(3, 10), F(3, 5), F(1, 10)]
+    uni = [F(1, 3)] * 3
+    def p_of(block): return p0 if block == () else (p1 if block == (0,) else uni)
+    def q_of(block): return q0 if block == () else (q1 if block == (0,) else uni)
+    V, L = 3, 3
+    block = (0,)
+    exact = ee.h_literal(p_of, q_of, block, V, L, K)
+    assert 0 < exact <= 1
+    log_nu = math.log(float(q0[0])) + eps_exp * math.log(10.0)
+    log_P = -eps_exp * math.log(10.0)
+    lq = np.log([float(v) for v in q1]); lp = np.log([float(v) for v in p1])
+    got = oracle.h_sub_excess(log_nu, log_P, oracle.ot_excess(lq, lp, log_nu, K), K)
+    assert abs(got - float(exact)) < 1e-11 * max(float(exact), 1e-3), (got, float(exact))
+    if K >= 2 and eps_exp >= 12:
+        plain = oracle.h_sub(log_nu, log_P, oracle.ot_sum(lq, lp, log_nu, K), K)
+        assert abs(plain - float(exact)) > 1e-3, "the plain form is expected to have lost every digit here"
+
+
+def test_cancellation_free_h_with_entries_of_zero_target_probability():
+    # q[x] = 0 < p[x]: the entry adds nothing to s, but its draft mass enters through the linear term
+    K = 3
+    lq = np.array([math.log(0.6), math.log(0.4), -np.inf])
+    lp = np.log([0.5, 0.3, 0.2])
+    for nu in (1.5, 7.0, 1e9):
+        log_nu = math.log(nu)
+        q = np.array([0.6, 0.4, 0.0]); pp = np.array([0.5, 0.3, 0.2])
+        t = np.maximum(1 - np.divide(pp, nu * q, out=np.full(3, np.inf), where=q > 0), 0)
+        if nu < 1e4:
+            s_minus_g = float((q * t ** K).sum() - (1 - 1 / nu) ** K)
+            assert abs(oracle.ot_excess(lq, lp, log_nu, K) - nu * nu * s_minus_g) < 1e-9 * nu * nu
+        # K a p t1^(K-1) from the masked entry alone is a lower bound
+        assert oracle.ot_excess(lq, lp, log_nu, K) >= nu * K * 0.2 * (1 - 1 / nu) ** (K - 1) * (1 - 1e-12) - nu * nu * 0
+
+
 def test_h_golden_hand_derived_values():
     doc = json.load(open(os.path.join(GOLDEN, "alg1_small_cases.json")))
     cases = {c["name"]: c for c in doc["cases"]}
