@@ -31,6 +31,8 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.nseg = (V + kSegElems - 1) / kSegElems;
     w.stats = take(n * sizeof(RowStat));
     w.s = take(n * sizeof(double));
+    w.excess = take(n * sizeof(double));
+    w.excess_part = take(n * kPendParts * sizeof(double));
     w.log_nu = take(n * sizeof(double));
     w.log_P = take(n * sizeof(double));
     w.h = take(n * sizeof(double));
@@ -127,7 +129,9 @@ specgbv_status specgbv_verify_ex(
         return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, p.lay.total);
     p.target = target_logits; p.draft = draft_logits; p.tokens = draft_tokens;
     p.K = K; p.L = L; p.V = V; p.batch = batch; p.dtype = dtype == SPECGBV_BF16 ? 1 : 0;
-    p.c = static_cast<float>(1.4426950408889634074 / static_cast<double>(temperature));
+    const double c_exact = 1.4426950408889634074 / static_cast<double>(temperature);
+    p.c = static_cast<float>(c_exact);
+    p.c_rel = c_exact / static_cast<double>(p.c) - 1.0;
     p.seed = rng_seed; p.offset = rng_offset;
     p.accepted_len = accepted_len; p.accepted_draft_idx = accepted_draft_idx; p.out_tokens = out_tokens;
     p.ws = static_cast<char *>(workspace);

@@ -19,9 +19,10 @@
 // between workgroups.
 //
 // The reference exponents ref_q, ref_p are the scaled logits of the row's drafted token
-// instead of the exact row maxima; should a row overflow float32 with that reference
-// (possible only for extremely peaked rows), its statistics are recomputed from memory with
-// the exact maximum.
+// instead of the exact row maxima; should a row's sum exceed 2^30 times the token's weight
+// (a drafted token of probability below 1e-9: very low temperatures, extremely peaked rows;
+// float32 overflow is the extreme case), its statistics are recomputed from memory with the
+// exact maximum, because exponents that large lose absolute accuracy in float32.
 //
 // Pending distribution modifications (Algorithm 2 applied on the fly, PEND variants): once a
 // row's statistics are known and while the whole row pair is still on chip, every level that
@@ -240,7 +241,40 @@ __device__ __noinline__ ExactStats exact_row_stats(const T *row, int nvec, float
     return ExactStats{ref, a};
 }
 
+// E = nu^2 (s - g) of one row pair straight from memory (rows whose s and g nearly cancel; see ExcessConst).
+// The constants travel through LDS, the result is returned by value, for the reasons given at exact_row_stats.
+template <typename T>
+__device__ __noinline__ double excess_row(const T *qrow, const T *prow, int nvec, const ExcessConst *ec_lds, double *sh_d)
+{
+    constexpr int PV = Elem<T>::kPerVec;
+    const ExcessConst ec = *ec_lds;
+    float acc = 0.0f;
+    for (int v = threadIdx.x; v < nvec; v += kChainThreads) {
+        float zq[PV], zp[PV];
+        Elem<T>::unpack(load16(qrow + static_cast<long long>(v) * PV), zq);
+        Elem<T>::unpack(load16(prow + static_cast<long long>(v) * PV), zp);
+        // two entries at a time, one pair strictly after the other: this function runs while the caller's
+        // registers hold a whole row pair, and must make do with the few that are left
+#pragma unroll
+        for (int j = 0; j < PV; j += 2) {
+            const float q2[2] = {zq[j], zq[j + 1]}, p2[2] = {zp[j], zp[j + 1]};
+            acc += excess_terms(q2, p2, ec);
+            asm volatile("" : "+v"(acc));
+        }
+    }
+    double a = static_cast<double>(acc), b = 0.0;
+    block_sum2(a, b, sh_d);
+    return a * ec.scale;
+}
+
+// Thread 0 only, in a function of its own (float64 constants stay out of the kernel's loop): the constants of that sum.
+__device__ __noinline__ void excess_prepare(const double *row, int K, float c, ExcessConst *out)
+{
+    *out = make_excess_const(row[1], row[2], row[0], K, c);
+}
+
 constexpr int kLag = 6;    // slots between the load of a vector and its first use
+constexpr double kTokenRefLimit = 1073741824.0;   // 2^30: largest row sum accepted relative to the drafted token's weight
 
 struct LdsSlots {
     U4 *all;                 // [kLdsSlots][2][kChainThreads]: slot s, half 0 = target vectors, half 1 = draft vectors
@@ -330,6 +364,20 @@ __device__ __forceinline__ double log2_cheap(double z)
     int e;
     const double m = frexp(z, &e);              // z = m * 2^e, m in [0.5, 1)
     return static_cast<double>(e) + static_cast<double>(__log2f(static_cast<float>(m)));
+}
+
+// log2 of a positive finite double to float64 accuracy: the float logarithm above, then one Newton step on
+// 2^y = m with the small float64 exponential (the error is squared: about 1e-14).  A function of its own, so that
+// its float64 constants stay out of the kernel's loop, whose registers hold a whole row pair.  A row's
+// log-normaliser enters every block ratio after it, and sub-block acceptance probabilities can be several times
+// more sensitive to the block ratio than 1:1, so the 1e-7 of the float logarithm is not good enough there.
+__device__ __noinline__ double log2_refined(double z)
+{
+    int e;
+    const double m = frexp(z, &e);              // z = m * 2^e, m in [0.5, 1)
+    const double y0 = static_cast<double>(__log2f(static_cast<float>(m)));
+    const double y = y0 + (m * exp2_small(-y0) - 1.0) * 1.44269504088896340736;
+    return static_cast<double>(e) + y;
 }
 
 // float64 scalars of the row whose pending levels are being applied (LDS; thread 0 writes, all read).
@@ -444,7 +492,7 @@ __device__ __forceinline__ double lane_d(double v, int lane)
 template <typename T>
 __device__ __forceinline__ double row0_from_parts(const Row0Part *parts, const T *target, const T *draft,
                                                   const int32_t *tokens, long long bk, int K, int L, int V, float c,
-                                                  RowStat *stats)
+                                                  double c_rel, RowStat *stats)
 {
     static_assert(kRow0Parts == 16, "one 16-lane row per tensor");
     const long long b = bk / K;
@@ -458,14 +506,14 @@ __device__ __forceinline__ double row0_from_parts(const Row0Part *parts, const T
     double Z = (live && d > -2000.0) ? ldexp(pt.Z, static_cast<int>(d)) : 0.0;
 #pragma unroll
     for (int o = 1; o < 16; o <<= 1) Z += __shfl_xor(Z, o);
-    const double lse2 = ref + log2_cheap(Z);
+    const double lse2 = ref + log2_refined(Z);
     int tok = tokens[bk * L];
     tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
     const long long bk0 = b * K;
     RowStat st;
     st.lse2_q = lane_d(lse2, 0); st.lse2_p = lane_d(lse2, 16);
-    st.tok2_q = static_cast<double>(Elem<T>::scalar(target + bk0 * (L + 1) * static_cast<long long>(V) + tok)) * static_cast<double>(c);
-    st.tok2_p = static_cast<double>(Elem<T>::scalar(draft + bk0 * L * static_cast<long long>(V) + tok)) * static_cast<double>(c);
+    st.tok2_q = token_scaled(static_cast<double>(Elem<T>::scalar(target + bk0 * (L + 1) * static_cast<long long>(V) + tok)) * static_cast<double>(c), st.lse2_q, c_rel);
+    st.tok2_p = token_scaled(static_cast<double>(Elem<T>::scalar(draft + bk0 * L * static_cast<long long>(V) + tok)) * static_cast<double>(c), st.lse2_p, c_rel);
     if (threadIdx.x == 0) stats[bk * L] = st;
     return (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);
 }
@@ -520,22 +568,25 @@ template <typename T, int KP, int RS, bool PEND>
 __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
         int K, int L, int V, long long nchains, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
-        int32_t *__restrict__ final_counter, ChainPend pend, int first_row, const Row0Part *__restrict__ row0)
+        double *__restrict__ e_out,
+        int32_t *__restrict__ final_counter, ChainPend pend, int first_row, const Row0Part *__restrict__ row0, double c_rel)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
+    __shared__ ExcessConst sh_ec;                          // constants of a row whose Eq. (hik) sum is taken again without cancellation
+    __shared__ double sh_sumrow[2][3];                     // block ratio and log-normalisers of the row in sweep 2 (log2): written by
+                                                           // thread 0 when the row's statistics are known, in the buffer of the
+                                                           // iteration's parity, and read one iteration later
     __shared__ PendTable sh_tab;                           // PEND only: levels that modify the current row
     __shared__ double sh_mu[kMaxPend];                     //            log2 block ratio of every level in front of the current row
     __shared__ int sh_cnt[kMaxPend];                       //            rows every level modifies (this prefix)
     __shared__ PendScalars sh_row;                         //            float64 scalars of the current row
     __shared__ ChainPend sh_pend;                          //            the kernel argument, kept out of the scalar registers
+    __shared__ int sh_sum_done;                            //            the row in sweep 2 already has its sum (modified row)
     if constexpr (PEND) {
-        if (threadIdx.x == 0) sh_pend = pend;
+        if (threadIdx.x == 0) { sh_pend = pend; sh_sum_done = 0; }
         __syncthreads();
     }
-    // PEND only: the row that sweep 2 would take next already has its sum (a modified row gets it from the extra
-    // sweeps over the on-chip copy).  Every thread reads the flag between two barriers and carries it in a register.
-    bool sum_done = false;
 
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
@@ -579,7 +630,9 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         const long long bk_old = chain_of(g_old);
         const int r_old = first_row + g_old % rpc;
         bool do_sum = g >= 1 && r_old >= 1;                // rows >= 1 get their Eq. (hik) sum
-        if constexpr (PEND) do_sum = do_sum && !sum_done;
+        // (written by thread 0 before the barrier that ends the previous row's level passes, and not again before
+        // the barriers of this iteration's row-end reduction, which every wave passes after this read)
+        if constexpr (PEND) do_sum = do_sum && __builtin_amdgcn_readfirstlane(sh_sum_done) == 0;
         const T *qnew = target + (bk_new * (L + 1) + r_new) * static_cast<long long>(V);
         const T *pnew = draft + (bk_new * L + r_new) * static_cast<long long>(V);
         const T *qold = target + (bk_old * (L + 1) + r_old) * static_cast<long long>(V);
@@ -628,26 +681,50 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp), s_tot = static_cast<double>(acc);
         block_sum3(Zq_tot, Zp_tot, s_tot, sh_d);
         Zq_tot = uniform_d(Zq_tot); Zp_tot = uniform_d(Zp_tot); s_tot = uniform_d(s_tot);
-        if (do_sum && tid == 0) s_out[bk_old * L + r_old] = s_tot / Zq_prev;
+        if (do_sum) {
+            // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term (rare:
+            // peaked rows, large block ratios); the row has left the chip by now and is read again.  The test runs
+            // in float32 on every thread (the branch is uniform); only thread 0 forms the float64 quotient it stores.
+            double e_val = -1.0;
+            if constexpr (!PEND) {
+                const double *row = sh_sumrow[(g - 1) & 1];
+                const float s_f = static_cast<float>(s_tot) * __builtin_amdgcn_rcpf(static_cast<float>(Zq_prev));
+                const float l_f = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(static_cast<float>(row[0]))));
+                if (excess_wanted(l_f, s_f, K)) {                   // uniform
+                    __syncthreads();
+                    if (tid == 0) excess_prepare(row, K, c, &sh_ec);
+                    __syncthreads();
+                    e_val = excess_row<T>(qold, pold, nvec, &sh_ec, sh_d);
+                }
+            }
+            if (tid == 0) { s_out[bk_old * L + r_old] = s_tot / Zq_prev; e_out[bk_old * L + r_old] = e_val; }
+        }
         if (do_new) {
             if (r_new == first_row) {                      // a new chain starts from the empty block ...
                 log2nu = 0.0;
                 if (first_row)                             // ... or from its token at the shared position 0
-                    log2nu = uniform_d(row0_from_parts<T>(row0, target, draft, tokens, bk_new, K, L, V, c, stats));
+                    log2nu = uniform_d(row0_from_parts<T>(row0, target, draft, tokens, bk_new, K, L, V, c, c_rel, stats));
             }
             float ref_q = -rc_new.nref_q, ref_p = -rc_new.nref_p;
-            if (!(Zq_tot < 1.0e37) || !(Zq_tot > 0.0)) {   // float32 overflow with the token reference
+            // A sum far above 1 means that the entries that matter lie far above the token's logit: their
+            // exponents, formed in float32, then carry an absolute error of half an ulp of a large number
+            // (3.8e-6 at 2^6), which a row dominated by one entry passes on to its log-normaliser in full.
+            // Beyond 2^30 (a drafted token of probability below 1e-9, or float32 overflow) the row is
+            // summed again with its exact maximum as reference.
+            if (!(Zq_tot < kTokenRefLimit) || !(Zq_tot > 0.0)) {
                 const ExactStats e = exact_row_stats<T>(qnew, nvec, c, sh_d);
                 ref_q = e.ref; Zq_tot = e.Z;
             }
-            if (!(Zp_tot < 1.0e37) || !(Zp_tot > 0.0)) {
+            if (!(Zp_tot < kTokenRefLimit) || !(Zp_tot > 0.0)) {
                 const ExactStats e = exact_row_stats<T>(pnew, nvec, c, sh_d);
                 ref_p = e.ref; Zp_tot = e.Z;
             }
-            const double lse2_q = static_cast<double>(ref_q) + log2_cheap(Zq_tot);
-            const double lse2_p = static_cast<double>(ref_p) + log2_cheap(Zp_tot);
-            const double tok2_q = static_cast<double>(zq_tok) * static_cast<double>(c);
-            const double tok2_p = static_cast<double>(zp_tok) * static_cast<double>(c);
+            // both logarithms in one go: even lanes take the target's sum, odd lanes the draft's
+            const double lg = log2_refined((tid & 1) ? Zp_tot : Zq_tot);
+            const double lse2_q = static_cast<double>(ref_q) + lane_d(lg, 0);
+            const double lse2_p = static_cast<double>(ref_p) + lane_d(lg, 1);
+            const double tok2_q = token_scaled(static_cast<double>(zq_tok) * static_cast<double>(c), lse2_q, c_rel);
+            const double tok2_p = token_scaled(static_cast<double>(zp_tok) * static_cast<double>(c), lse2_p, c_rel);
             if (tid == 0) {
                 RowStat st;
                 st.lse2_q = lse2_q; st.lse2_p = lse2_p; st.tok2_q = tok2_q; st.tok2_p = tok2_p;
@@ -684,7 +761,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
                         double unused = 0.0;
                         block_sum2(S, unused, sh_d);
                         if (tid == 0) {
-                            if (is_sum) s_out[pair] = pend_pass_sum(sh_row, S);
+                            if (is_sum) { s_out[pair] = pend_pass_sum(sh_row, S); e_out[pair] = -1.0; }
                             else sh_pend.rows[l * n_rows + pair] = pend_pass_level(sh_row, sh_tab, sh_mu[l], S, K);
                         }
                         __syncthreads();
@@ -694,11 +771,10 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
                         sh_pend.rows[l * n_rows + pair] = out;
                     }
                 }
+                // a modified row has its sum (or needs none: row 0); thread 0 is the only writer of sh_tab.n, which is
+                // final here, and the barrier below publishes the flag before any wave starts the next row
+                if (tid == 0) sh_sum_done = sh_tab.n > 0;
                 __syncthreads();
-                // a modified row has its sum (or needs none: row 0).  sh_tab.n is final here and is not written
-                // again before the barrier that opens the next row's level passes, which every thread reaches
-                // only after this read.
-                sum_done = __builtin_amdgcn_readfirstlane(sh_tab.n) > 0;
                 tok_adj = sh_row.tok_adj;
             }
             // constants of this row's sweep 2 (next iteration)
@@ -708,6 +784,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             const double dk = (static_cast<double>(rc_sum.C2_hi) - C2) * 0.693147180559945309417;
             rc_sum.neg_kappa = (dk > -0.25 && dk < 0.25) ? -static_cast<float>(1.0 + dk + 0.5 * dk * dk) : -1.0f;
             Zq_prev = uniform_d(Zq_tot);
+            if (tid == 0) { sh_sumrow[g & 1][0] = log2nu; sh_sumrow[g & 1][1] = lse2_q; sh_sumrow[g & 1][2] = lse2_p; }
             log2nu = uniform_d(log2nu + ((tok2_q - lse2_q + tok_adj) - (tok2_p - lse2_p)));
         }
     }
@@ -750,7 +827,8 @@ hipError_t launch_kp(const Problem &p)
 #define SPECGBV_LAUNCH(RS)                                                                                  \
     hipLaunchKernelGGL((k_chain<T, KP, RS, PEND>), grid, dim3(kChainThreads), 0, p.stream, target, draft,  \
                        p.tokens, p.K, p.L, p.V, nchains, p.c, stats, s,                                    \
-                       reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend, first_row, row0)
+                       reinterpret_cast<double *>(p.ws + p.lay.excess),                                    \
+                       reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend, first_row, row0, p.c_rel)
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);

@@ -94,12 +94,15 @@ struct DecideIO {
     long long n_rows;           // batch * K * L
     int nlev;
     const double *s_arr;
+    const double *e_arr;        // nu^2 (s - g) of Eq. (hik) where the sum kernels took it without cancellation, else negative
+    const double *e_part;       // s_parts > 1: the same in parts (every part negative: not taken)
     const double *s_part;       // s_parts > 1: the sums arrive as s_parts partial sums per row ([n_rows][kPendParts])
     double *s_store;            //              and the complete ones are stored here by the writing workgroup
     int s_parts;
     double *log_nu_out, *log_P_out, *h_out, *eta_out;
     int32_t *state_out;
     int32_t *accepted_len, *accepted_draft_idx, *out_tokens;
+    double c_rel;               // relative rounding error of the float scale c (token_scaled)
 };
 
 // Decision of prefix b by the whole workgroup (kDecideThreads threads); the result is left in
@@ -119,9 +122,10 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
     double *tp = lds + 2 * KL;                              // [K*L] log2 p_r[token of row r]
     double *lq = lds + 3 * KL;                              // [K*L] log2 normaliser of target row r
     double *lp = lds + 4 * KL;                              // [K*L] log2 normaliser of draft row r
-    unsigned long long *acc_bits = reinterpret_cast<unsigned long long *>(lds + 5 * KL);   // [K] bit i: eta_{k,i} < h_{k,i}
+    double *ex = lds + 5 * KL;                              // [K*L] nu^2 (s - g) where it was summed without cancellation, else < 0
+    unsigned long long *acc_bits = reinterpret_cast<unsigned long long *>(lds + 6 * KL);   // [K] bit i: eta_{k,i} < h_{k,i}
     int *tok = reinterpret_cast<int *>(acc_bits + K);       // [K*L]
-    int *cpl = tok + KL;                                    // [K*K] common prefix lengths
+    unsigned char *cpl = reinterpret_cast<unsigned char *>(tok + KL);   // [K*K] common prefix lengths (at most L <= 62)
     const int tid = threadIdx.x;
     const long long base = static_cast<long long>(b) * KL;
     constexpr double kLn2 = 0.693147180559945309417;
@@ -137,16 +141,22 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         // the Eq. (hik) sum this thread needs for entry idx of the table below, loaded alongside the statistics
         // (one memory latency instead of two); parked where the entry's log2 nu goes afterwards
         const int k = idx / L, i = idx % L + 1;
-        double s = 0.0;
+        double s = 0.0, e = -1.0;
         if (i < L) {
             if (io.s_parts > 1) {                           // in part order: the same bits in every workgroup
-                for (int q = 0; q < io.s_parts; ++q) s += io.s_part[(base + k * L + i) * kPendParts + q];
+                e = 0.0;
+                for (int q = 0; q < io.s_parts; ++q) {
+                    s += io.s_part[(base + k * L + i) * kPendParts + q];
+                    e += io.e_part[(base + k * L + i) * kPendParts + q];
+                }
                 if (write) io.s_store[base + k * L + i] = s;
             } else {
                 s = s_arr[base + k * L + i];
+                e = io.e_arr[base + k * L + i];
             }
         }
         l2nu[idx] = s;
+        ex[idx] = e;
     }
     __syncthreads();
     for (int idx = tid; idx <= KL; idx += kDecideThreads) {
@@ -165,7 +175,26 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         const double nu = 1.0 / inv_nu;
         const double g = g_K(inv_nu, K), cK = c_K(P, K);
         double hv;
-        if (i < L) {
+        if (i < L && log2nu > 0.0) {
+            // Block ratio above one: the denominator c_K(P) - nu (1 - s) equals [c_K(P) - c_K(1/nu)] + nu (s - g),
+            // and c_K(P) - c_K(1/nu) = (1 - Q) S2 / nu with Q = nu P the block's joint target probability and
+            // S2 = sum_{j=1}^{K-1} sum_{m<j} (1-P)^m (1 - 1/nu)^(j-1-m) (by the recurrence U_1 = 1,
+            // U_{j+1} = (1-P) U_j + (1 - 1/nu)^j), every term non-negative.  With E = nu^2 (s - g):
+            // h = E / (E + (1 - Q) S2), where E comes from the sum kernels when s and g nearly cancel.
+            const double A = 1.0 - P, t1 = 1.0 - inv_nu;
+            double U = 1.0, S2 = 0.0, pw = 1.0;
+            for (int j = 1; j <= K - 1; ++j) { S2 += U; pw *= t1; U = fma(A, U, pw); }
+            const double one_Q = fmax(1.0 - exp2_small(log2nu + log2P), 0.0);
+            const double E = ex[idx];
+            if (E >= 0.0) {
+                const double den = E + one_Q * S2;
+                hv = !(E < 1.0e300) ? 1.0 : (den > 0.0 ? clamp01(E / den) : 1.0);
+            } else {
+                const double num = nu * (s - g);
+                const double den = inv_nu * one_Q * S2 + num;
+                hv = den > 0.0 ? clamp01(num / den) : 1.0;
+            }
+        } else if (i < L) {
             const double num = nu * (s - g);
             const double den = cK - nu * (1.0 - s);
             hv = den > 0.0 ? clamp01(num / den) : 1.0;
@@ -183,7 +212,7 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         const int k1 = idx / K, k2 = idx % K;
         int n = 0;
         while (n < L && tok[k1 * L + n] == tok[k2 * L + n]) ++n;
-        cpl[idx] = n;
+        cpl[idx] = static_cast<unsigned char>(n);
     }
     __syncthreads();
     if (tid < kWave) {
@@ -239,13 +268,14 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         tab_out->n = 0;
         sl.target_row = (static_cast<long long>(b) * K + kf) * (L + 1) + tau;
         if (tau == L) {
-            sl.draft_row = -1; sl.C2 = 0.0; sl.shift_q = 0.0f; sl.lse2_q = 0.0;
+            sl.draft_row = -1; sl.C2 = 0.0; sl.shift_q = 0.0f; sl.lse2_q = 0.0; sl.lse2_pq = 0.0;
         } else {
             sl.draft_row = (static_cast<long long>(b) * K + kf) * L + tau;
             const double lse2_q = lq[kf * L + tau], lse2_p = lp[kf * L + tau];
             sl.C2 = lse2_p - lse2_q + (tau == 0 ? 0.0 : l2nu[kf * L + tau - 1]);
             sl.shift_q = rintf(static_cast<float>(lse2_q));         // integral: partial sums rescale exactly
             sl.lse2_q = lse2_q;
+            sl.lse2_pq = lse2_p - lse2_q;
         }
     }
     // Levels that modify the selected row: q' = q prod t_l^K / N_l.  The whole wave walks the levels (tau, kf and
@@ -446,7 +476,7 @@ __device__ __forceinline__ void update_pending_state(const T *target, const T *d
         const RowStat st_tau = io.stats[row0 + tau];
         const double zq_y = static_cast<double>(Elem<T>::scalar(target + sl.target_row * V + tokid)) * static_cast<double>(c);
         const double zp_y = static_cast<double>(Elem<T>::scalar(draft + sl.draft_row * V + tokid)) * static_cast<double>(c);
-        const double by = (zq_y - st_tau.lse2_q) - (zp_y - st_tau.lse2_p);
+        const double by = ((zq_y - st_tau.lse2_q) - (zp_y - st_tau.lse2_p)) * (1.0 + io.c_rel);
         if (lane == tau) base = by;
         // ... and the levels' factors there, one level after the other (wave-uniform loop; lane 4 l holds level l's entry)
         PendRow pt;
@@ -716,6 +746,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
             const double zq = static_cast<double>(Elem<T>::scalar(target + sl.target_row * V + tokid));
             const double zp = static_cast<double>(Elem<T>::scalar(draft + sl.draft_row * V + tokid));
             double l2 = sl.C2 + static_cast<double>(c) * (zq - zp);        // log2 of nu_tau q[y] / p[y]
+            l2 += io.c_rel * (static_cast<double>(c) * (zq - zp) + sl.lse2_pq);   // y's two log-probabilities at the caller's temperature (token_scaled)
             if (PEND) {                                     // q'[y] = q[y] prod_l t_l[y]^K / N_l (the N_l are in C2)
                 double log2T = 0.0;
                 for (int l = 0; l < sl.npend; ++l) {
@@ -750,6 +781,8 @@ hipError_t launch_final_typed(const Problem &p)
     io.n_rows = static_cast<long long>(p.batch) * p.K * p.L;
     io.nlev = p.pend_levels;
     io.s_arr = reinterpret_cast<const double *>(p.ws + p.lay.s);
+    io.e_arr = reinterpret_cast<const double *>(p.ws + p.lay.excess);
+    io.e_part = reinterpret_cast<const double *>(p.ws + p.lay.excess_part);
     io.s_part = reinterpret_cast<const double *>(p.ws + p.lay.pend_part);
     io.s_store = reinterpret_cast<double *>(p.ws + p.lay.s);
     io.s_parts = p.s_parts;
@@ -759,6 +792,7 @@ hipError_t launch_final_typed(const Problem &p)
     io.eta_out = reinterpret_cast<double *>(p.ws + p.lay.eta);
     io.state_out = reinterpret_cast<int32_t *>(p.ws + p.lay.state);
     io.accepted_len = p.accepted_len; io.accepted_draft_idx = p.accepted_draft_idx; io.out_tokens = p.out_tokens;
+    io.c_rel = p.c_rel;
     FinalOut fo;
     fo.sel = reinterpret_cast<Selection *>(p.ws + p.lay.sel);
     fo.partial = reinterpret_cast<SegPartial *>(p.ws + p.lay.partial);
@@ -771,7 +805,7 @@ hipError_t launch_final_typed(const Problem &p)
     fo.mcount = reinterpret_cast<int32_t *>(p.ws + p.lay.mcount);
     fo.state_carry = p.state_carry; fo.state_count = p.state_count;
     const int KL = p.K * p.L;
-    const size_t lds = sizeof(double) * (5 * KL + p.K) + sizeof(int) * (KL + p.K * p.K);
+    const size_t lds = sizeof(double) * (6 * KL + p.K) + sizeof(int) * KL + ((static_cast<size_t>(p.K) * p.K + 7) & ~static_cast<size_t>(7));
 #define SPECGBV_FINAL_LAUNCH(VEC, PEND)                                                                              \
     hipLaunchKernelGGL((k_final<T, VEC, PEND>), g, dim3(kSegThreads), lds, p.stream, target, draft, io, fo, p.V, p.K, \
                        p.L, p.c, p.lay.nseg, p.seed, p.offset)

@@ -58,6 +58,7 @@ struct Selection {
     int tau;
     int npend;              // levels of pending modifications that modify the row (C2 and lse2_q then refer to the modified row)
     int pad;
+    double lse2_pq;         // log2 Z_p - log2 Z_q of the unmodified row pair (0 for the bonus row)
     double Cl[kMaxPend];    // per such level: log2 of mu_l Z_p / Z_q minus the log2 N of the levels before it
 };
 
@@ -68,6 +69,14 @@ struct SegPartial {
     float m2;        // reference exponent of both sums
     float pad;
 };
+
+// The drafted token's scaled logit as RowStat keeps it: c z[token], adjusted so that tok2 - lse2 is the token's
+// log2 probability at the caller's temperature.  The kernels scale logits with the float c, which differs from
+// log2(e) / T by the relative amount c_rel (at most 6e-8 in magnitude); a token far below the bulk of its row
+// (hundreds of base-2 units at a low temperature) would carry that relative error into the block ratio in
+// full.  To first order the log-probability of such a token is proportional to the scale, so it is rescaled;
+// for tokens near the bulk the adjustment is far below the arithmetic's own error.
+__device__ __forceinline__ double token_scaled(double tok2, double lse2, double c_rel) { return tok2 + c_rel * (tok2 - lse2); }
 
 // ------------------------------------------------------------------- loads
 
@@ -278,6 +287,92 @@ __device__ __forceinline__ void pending_weights(const float (&zq)[N], const floa
     pow_array(t, K);
 #pragma unroll
     for (int j = 0; j < N; ++j) { wq[j] = exp2_fast(fmaf(zq[j], c, -shift_q)) * T[j]; w[j] = wq[j] * t[j]; }
+}
+
+// ---- Eq. (hik) for a block ratio nu > 1 without the difference s - g.
+//
+// s = E_q phi(rho) and g = phi(1) = phi(E_q rho) with phi(rho) = max(1 - rho/nu, 0)^K convex and rho = p[x]/q[x]
+// of mean one under q, so s - g = sum_x q[x] b(rho_x) with the non-negative convexity remainder
+// b(rho) = phi(rho) - phi(1) - phi'(1) (rho - 1).  With a = 1/nu, t1 = 1 - a, t = 1 - a rho:
+//     t > 0 :  b = a^2 (rho - 1)^2 H(t),   H(t) = sum_{m=0}^{K-2} (K-1-m) t1^(K-2-m) t^m
+//     t <= 0:  q b = t1^(K-1) (K a p - (1 + (K-1) a) q)
+// The kernels sum E = nu^2 (s - g), i.e. the terms without the factor a^2 (which underflows for the ratios that
+// drafts of improbable tokens produce); the decision then takes h = E / (E + (1 - Q) S2).  When s and g agree to
+// several digits (peaked rows, large nu) this is the only way to get h right in float32 arithmetic, so the sum
+// kernels evaluate it for exactly those rows (excess_wanted) on top of s.
+struct ExcessConst {
+    float c;
+    float shift_q, shift_p;    // reference exponents: q[x] ~ 2^(c z_q - shift_q), p[x] ~ 2^(c z_p - shift_p) in the same units
+    float C1_hi, kappa;        // rho = kappa 2^(c (z_p - z_q) - C1_hi), C1 = log2 Z_p - log2 Z_q
+    float a, t1, nu;           // 1/nu (not below 1e-30), 1 - a, nu (not above 1e30)
+    float Kk, nuK1, lead;      // K kappa_p; nu + K - 1; nu t1^(K-1)
+    int K;
+    double scale;              // 2^(shift_q - log2 Z_q): the sum of the terms times this is E
+};
+
+__device__ __forceinline__ ExcessConst make_excess_const(double lse2_q, double lse2_p, double log2nu, int K, float c)
+{
+    ExcessConst ec;
+    ec.c = c; ec.K = K;
+    ec.shift_q = rintf(static_cast<float>(lse2_q));
+    const double C1 = lse2_p - lse2_q;
+    const RatioConst rc(C1);
+    ec.C1_hi = rc.C2_hi; ec.kappa = -rc.neg_kappa;
+    const double sp = static_cast<double>(ec.shift_q) + C1;
+    ec.shift_p = static_cast<float>(sp);
+    const double kp = exp2_small(static_cast<double>(ec.shift_p) - sp);      // what rounding shift_p leaves out
+    double a = exp2_small(-log2nu);
+    if (!(a > 1.0e-30)) a = 1.0e-30;
+    const double nu = 1.0 / a, t1 = 1.0 - a;
+    ec.a = static_cast<float>(a); ec.t1 = static_cast<float>(t1); ec.nu = static_cast<float>(nu);
+    ec.Kk = static_cast<float>(static_cast<double>(K) * ((kp > 0.5 && kp < 2.0) ? kp : 1.0));
+    ec.nuK1 = static_cast<float>(nu + static_cast<double>(K - 1));
+    ec.lead = static_cast<float>(nu * powi_uniform(t1, K - 1));
+    ec.scale = exp2_small(static_cast<double>(ec.shift_q) - lse2_q);
+    return ec;
+}
+
+// Sum over N entries of the terms of E.
+template <int N>
+__device__ __forceinline__ float excess_terms(const float (&zq)[N], const float (&zp)[N], const ExcessConst &ec)
+{
+    float rho[N], eq[N], t[N], H[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        rho[j] = ec.kappa * exp2_fast(fmaf(zp[j] - zq[j], ec.c, -ec.C1_hi));     // +inf where q[x] = 0
+        eq[j] = exp2_fast(fmaf(zq[j], ec.c, -ec.shift_q));
+        t[j] = fmaf(-ec.a, rho[j], 1.0f);
+        H[j] = ec.K >= 2 ? 1.0f : 0.0f;                                          // coefficient of t^(K-2)
+    }
+    float pw = 1.0f;                                                             // t1^(K-2-m)
+    for (int m = ec.K - 3; m >= 0; --m) {                                        // uniform; Horner in t
+        pw *= ec.t1;
+        const float cm = static_cast<float>(ec.K - 1 - m) * pw;
+#pragma unroll
+        for (int j = 0; j < N; ++j) H[j] = fmaf(H[j], t[j], cm);
+    }
+    float acc = 0.0f;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const float u = rho[j] - 1.0f;
+        const float open = (eq[j] * u) * u * H[j];
+        const float ep = exp2_fast(fmaf(zp[j], ec.c, -ec.shift_p));
+        const float shut = ec.lead * fmaf(ec.Kk, ep, -ec.nuK1 * eq[j]);
+        acc += (t[j] > 0.0f) ? open : fmaxf(shut, 0.0f);                         // entries masked in both models: 0
+    }
+    return acc;
+}
+
+// Do s and g agree so closely (block ratio above one) that nu (s - g) needs the sum E?  The plain sum s carries a
+// relative error of a few 1e-8; below (s - g) / s = 1/64 that is no longer negligible against 1e-5.
+// (float32 throughout: the threshold need not be sharp, and float64 constants in a kernel whose registers hold a
+// whole row pair end up in scratch memory)
+__device__ __forceinline__ bool excess_wanted(float l, float sf, int K)
+{
+    if (!(l > 0.0f)) return false;
+    const float t1 = 1.0f - exp2_fast(-l);
+    const float g = powi_uniform(t1, K);
+    return (sf - g) * 64.0f < sf;
 }
 
 // Entry l of a PendTable from the float64 constant C (same split as RatioConst).

@@ -13,6 +13,8 @@ namespace specgbv {
 struct Workspace {
     size_t stats;      // RowStat [B*K*L]
     size_t s;          // double  [B*K*L]   (position i = row i; position 0 unused)
+    size_t excess;     // double  [B*K*L]   nu^2 (s - g) summed without cancellation where the sum kernels took it, else -1
+    size_t excess_part;// double  [B*K*L][kPendParts]  the same in parts (small batches)
     size_t log_nu;     // double  [B*K*L]
     size_t log_P;      // double  [B*K*L]
     size_t h;          // double  [B*K*L]
@@ -55,6 +57,7 @@ struct Problem {
     int K, L, V, batch;
     int dtype;          // 0 = float32, 1 = bfloat16
     float c;            // log2(e) / temperature
+    double c_rel;       // (log2(e) / temperature) / c - 1: what the rounding of c to float32 leaves out (token_scaled)
     uint64_t seed, offset;
     int32_t *accepted_len;
     int32_t *accepted_draft_idx;

@@ -63,7 +63,8 @@ __global__ void __launch_bounds__(kStatThreads)
 k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
             const int32_t *__restrict__ tokens, int K, int L, int V, float c,
             RowStat *__restrict__ stats, int32_t *__restrict__ final_counter, long long n_rows, int batch,
-            const int32_t *__restrict__ pend_count, int32_t *__restrict__ pend_off, int32_t *__restrict__ pend_cnt)
+            const int32_t *__restrict__ pend_count, int32_t *__restrict__ pend_off, int32_t *__restrict__ pend_cnt,
+            double c_rel)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ float sh_f[kStatThreads / kWave];
@@ -107,7 +108,7 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
         const double lse2 = static_cast<double>(M) + log2(total);
         int tok = tokens[pair];
         tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-        const double tok2 = static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c);
+        const double tok2 = token_scaled(static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c), lse2, c_rel);
         if (is_draft) { stats[pair].lse2_p = lse2; stats[pair].tok2_p = tok2; }
         else { stats[pair].lse2_q = lse2; stats[pair].tok2_q = tok2; }
     }
@@ -195,8 +196,8 @@ template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kStatThreads)
 k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int K, int L,
                int V, float c, int P, const Row0Part *__restrict__ stat_parts, int stat_P, RowStat *stats,
-               int32_t *__restrict__ final_counter, double *__restrict__ s_part, const PendRow *__restrict__ pend,
-               long long n_rows, int nlev)
+               int32_t *__restrict__ final_counter, double *__restrict__ s_part, double *__restrict__ e_part,
+               const PendRow *__restrict__ pend, long long n_rows, int nlev, double c_rel)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ PendTable sh_tab;                  // PEND: the levels that modify this row
@@ -218,7 +219,7 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
             int tok = tokens[pj];
             tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
             const T *row = m ? draft + pj * static_cast<long long>(V) : target + (bk * (L + 1) + j) * static_cast<long long>(V);
-            sh_tok[t] = static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c);
+            sh_tok[t] = token_scaled(static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c), sh_lse[t], c_rel);
         }
         __syncthreads();
         st.lse2_q = sh_lse[2 * i]; st.lse2_p = sh_lse[2 * i + 1];
@@ -275,8 +276,22 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
         });
     }
     const double total = block_sum(static_cast<double>(acc), sh_d);
-    if (threadIdx.x == 0)
+    // A part cannot tell whether the row's s and g nearly cancel, so for every block ratio above one the terms of
+    // nu^2 (s - g) are summed too (a second sweep over the part: this kernel serves small batches, where time is
+    // latency, not arithmetic); -1 in every part marks a row without it.
+    double e_val = -1.0;
+    if (!(PEND && sh_tab.n > 0) && log2nu > 0.0) {                              // uniform over the workgroup
+        const ExcessConst ec = make_excess_const(st.lse2_q, st.lse2_p, log2nu, K, c);
+        float acc2 = 0.0f;
+        for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+            acc2 += excess_terms(zq, zp, ec);
+        });
+        e_val = block_sum(static_cast<double>(acc2), sh_d) * ec.scale;
+    }
+    if (threadIdx.x == 0) {
         s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
+        e_part[pair * kPendParts + part] = e_val;
+    }
 }
 
 // One level of pending modification (the levels below it are done: their PendRow entries are read).
@@ -400,7 +415,7 @@ template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kStatThreads)
 k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
          const RowStat *__restrict__ stats, const PendRow *__restrict__ pend, long long n_rows, int nlev,
-         double *__restrict__ s_out)
+         double *__restrict__ s_out, double *__restrict__ e_out)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ PendTable sh_tab;
@@ -448,8 +463,19 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
         });
     }
     const double total = block_sum(static_cast<double>(acc), sh_d);
-    if (threadIdx.x == 0)
-        s_out[bk * L + i] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
+    const double s_val = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
+    // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term: a second sweep
+    // over the row pair (rare: peaked rows, large block ratios; rows under pending modifications keep the plain sum)
+    double e_val = -1.0;
+    if (!(PEND && sh_tab.n > 0) && excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_val), K)) {   // uniform over the workgroup
+        const ExcessConst ec = make_excess_const(st.lse2_q, st.lse2_p, log2nu, K, c);
+        float acc2 = 0.0f;
+        for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+            acc2 += excess_terms(zq, zp, ec);
+        });
+        e_val = block_sum(static_cast<double>(acc2), sh_d) * ec.scale;
+    }
+    if (threadIdx.x == 0) { s_out[bk * L + i] = s_val; e_out[bk * L + i] = e_val; }
 }
 
 int compute_units()
@@ -503,10 +529,10 @@ hipError_t launch_typed(const Problem &p)
         const dim3 g1(static_cast<unsigned>(pairs + p.pend_levels), 2);
         if (vec)
             hipLaunchKernelGGL((k_row_stats<T, true>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
-                               p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt);
+                               p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt, p.c_rel);
         else
             hipLaunchKernelGGL((k_row_stats<T, false>), g1, dim3(kStatThreads), 0, p.stream, target, draft,
-                               p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt);
+                               p.tokens, p.K, p.L, p.V, p.c, stats, counter, pairs, p.batch, p.pend_count, pend_off, pend_cnt, p.c_rel);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -533,8 +559,9 @@ hipError_t launch_typed(const Problem &p)
         const dim3 gq(static_cast<unsigned>(rows * p.s_parts));
 #define SPECGBV_OTP_LAUNCH(VEC, PEND)                                                                                 \
     hipLaunchKernelGGL((k_ot_sum_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, p.K, \
-                       p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part, pend, pairs,         \
-                       p.pend_levels)
+                       p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part,                     \
+                       reinterpret_cast<double *>(p.ws + p.lay.excess_part), pend, pairs,                              \
+                       p.pend_levels, p.c_rel)
         if (p.pend_levels > 0) { if (vec) SPECGBV_OTP_LAUNCH(true, true); else SPECGBV_OTP_LAUNCH(false, true); }
         else { if (vec) SPECGBV_OTP_LAUNCH(true, false); else SPECGBV_OTP_LAUNCH(false, false); }
 #undef SPECGBV_OTP_LAUNCH
@@ -543,7 +570,7 @@ hipError_t launch_typed(const Problem &p)
     const dim3 g2(static_cast<unsigned>(rows));
 #define SPECGBV_OT_LAUNCH(VEC, PEND)                                                                           \
     hipLaunchKernelGGL((k_ot_sum<T, VEC, PEND>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L, \
-                       p.V, p.c, stats, pend, pairs, p.pend_levels, s)
+                       p.V, p.c, stats, pend, pairs, p.pend_levels, s, reinterpret_cast<double *>(p.ws + p.lay.excess))
     if (p.pend_levels > 0) { if (vec) SPECGBV_OT_LAUNCH(true, true); else SPECGBV_OT_LAUNCH(false, true); }
     else { if (vec) SPECGBV_OT_LAUNCH(true, false); else SPECGBV_OT_LAUNCH(false, false); }
 #undef SPECGBV_OT_LAUNCH
