@@ -107,6 +107,31 @@ specgbv_status specgbv_verify(
     int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
     void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * specgbv_verify for callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: same arguments, semantics and outputs as specgbv_verify
+ * (default schedule), without the workspace.  The kernels' scratch memory (row statistics, the sums of Eq. (hik),
+ * partial sums and arrival counters of the final-token search) lives in a buffer of
+ * SPECGBV_STATIC_SCRATCH_BYTES built into the library's device image: every GPU the library runs on holds its own
+ * copy until the process ends.  The call allocates and frees nothing.
+ *
+ *   - A shape with specgbv_workspace_bytes(batch, K, L, V, dtype) > SPECGBV_STATIC_SCRATCH_BYTES is refused with
+ *     SPECGBV_EUNSUPPORTED before anything is launched.
+ *   - All calls on one GPU share that GPU's buffer: two calls that overlap in time on one GPU (different streams,
+ *     or different host threads) race and give undefined results; calls on one stream are ordered and safe.  The
+ *     buffer keeps the previous call's contents; every call rewrites what it reads (the arrival counters are
+ *     cleared by the call's first kernel), so no clearing is needed between calls.
+ *   - The buffer's address on a GPU is looked up on the first call with that GPU current (not an allocation, but
+ *     make that first call outside a graph capture).
+ *   - specgbv_read_intermediates and specgbv_workspace_carry need a caller-owned workspace and do not apply.
+ */
+#define SPECGBV_STATIC_SCRATCH_BYTES (8u << 20)
+specgbv_status specgbv_verify_static(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int L, int V, int batch, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset,
+    int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens, void *hip_stream);
+
 #define SPECGBV_MAX_PENDING 16  /* pending distribution modifications applied on the fly at most */
 
 /* Extra controls for specgbv_verify_ex; zero-initialise for the defaults. */

@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 ALGO_AUTO, ALGO_SPLIT, ALGO_CHAIN = 0, 1, 2
 _ALGO = {"auto": ALGO_AUTO, "split": ALGO_SPLIT, "chain": ALGO_CHAIN}
 
-EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_ex", "specgbv_read_intermediates",
+EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_static", "specgbv_verify_ex", "specgbv_read_intermediates",
            "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_modify_workspace_bytes", "specgbv_sample_tokens", "specgbv_sample_workspace_bytes",
            "specgbv_read_sample_intermediates", "specgbv_carry_advance", "specgbv_carry_workspace_bytes", "specgbv_pending_state_bytes", "specgbv_last_error", "specgbv_version")
 
@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
                    c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     L.specgbv_verify.argtypes = verify_args
     L.specgbv_verify.restype = c_int
+    L.specgbv_verify_static.argtypes = verify_args[:14] + [c_void_p]
+    L.specgbv_verify_static.restype = c_int
     L.specgbv_verify_ex.argtypes = verify_args + [POINTER(_Options)]
     L.specgbv_verify_ex.restype = c_int
     L.specgbv_pending_state_bytes.argtypes = [c_int]
@@ -242,6 +244,26 @@ def specgbv_verify(target_logits, draft_logits, draft_tokens, temperature: float
                             stream)
     _check(st)
     return out[0], out[1], out[2], workspace
+
+
+STATIC_SCRATCH_BYTES = 8 << 20      # SPECGBV_STATIC_SCRATCH_BYTES of the C header
+
+
+def specgbv_verify_static(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int, rng_offset: int,
+                          *, out: Tuple, stream: Optional[int] = None):
+    """specgbv_verify_static of the C ABI: the verification on the library's built-in scratch buffer.  The
+    caller passes the three output tensors; nothing is allocated here or in the library."""
+    import torch
+    lib = load_library()
+    B, K, L, V = _shapes(target_logits, draft_logits, draft_tokens)
+    dt = _dtype_code(target_logits)
+    if stream is None:
+        stream = torch.cuda.current_stream(target_logits.device).cuda_stream
+    st = lib.specgbv_verify_static(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V, B,
+                                   dt, c_float(temperature), rng_seed, rng_offset, out[0].data_ptr(), out[1].data_ptr(),
+                                   out[2].data_ptr(), stream)
+    _check(st)
+    return out
 
 
 def specgbv_read_intermediates(workspace, batch: int, K: int, L: int, V: int, dtype: int,

@@ -1,4 +1,5 @@
 // C ABI of libspecgbv.so: argument checks, workspace layout, kernel sequencing.
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -21,6 +22,12 @@ static specgbv_status fail(specgbv_status st, const char *fmt, ...)
 }
 
 static size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+// Scratch memory of specgbv_verify_static: the verification workspace for callers that cannot allocate one.
+// One copy per GPU the library runs on, held until the process ends; every call on a GPU shares that GPU's copy.
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char g_static_scratch[SPECGBV_STATIC_SCRATCH_BYTES];
+static std::atomic<void *> g_static_scratch_ptr[kMaxDevices];     // device address per GPU, looked up on first use
 
 Workspace make_workspace(int batch, int K, int L, int V)
 {
@@ -423,6 +430,41 @@ specgbv_status specgbv_read_sample_intermediates(const void *workspace, size_t w
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail(SPECGBV_EHIP, "copy of the sampling intermediates: %s", hipGetErrorString(e));
     return SPECGBV_OK;
+}
+
+specgbv_status specgbv_verify_static(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int L, int V, int batch, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset,
+    int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens, void *hip_stream)
+{
+    if (!shape_ok(batch, K, L, V))
+        return fail(SPECGBV_EINVAL, "sizes must satisfy batch >= 0, K, L, V >= 1 (got batch=%d K=%d L=%d V=%d)",
+                    batch, K, L, V);
+    const specgbv_status st = check_limits(batch, K, L, V);
+    if (st != SPECGBV_OK) return st;
+    const size_t need = make_workspace(batch < 1 ? 1 : batch, K, L, V).total;
+    if (need > sizeof g_static_scratch)
+        return fail(SPECGBV_EUNSUPPORTED,
+                    "this shape needs %zu bytes of scratch memory, the built-in buffer holds SPECGBV_STATIC_SCRATCH_BYTES = %zu: "
+                    "use specgbv_verify with a caller-owned workspace",
+                    need, sizeof g_static_scratch);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SPECGBV_EUNSUPPORTED, "device index %d is beyond %d", dev, kMaxDevices - 1);
+    // Every GPU holds its own copy of the array at its own address: looked up once per device, with that device
+    // current; from then on only the looked-up address is used (the array's name is not a device address in host code).
+    void *scratch = g_static_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!scratch) {
+        e = hipGetSymbolAddress(&scratch, HIP_SYMBOL(g_static_scratch));
+        if (e != hipSuccess || !scratch)
+            return fail(SPECGBV_EHIP, "hipGetSymbolAddress(built-in scratch buffer): %s", hipGetErrorString(e));
+        g_static_scratch_ptr[dev].store(scratch, std::memory_order_release);
+    }
+    return specgbv_verify_ex(target_logits, draft_logits, draft_tokens, K, L, V, batch, dtype, temperature, rng_seed,
+                             rng_offset, accepted_len, accepted_draft_idx, out_tokens, scratch, sizeof g_static_scratch,
+                             hip_stream, nullptr);
 }
 
 const char *specgbv_last_error(void) { return g_err; }
