@@ -45,6 +45,13 @@ class _Debug(ctypes.Structure):
     ]
 
 
+class _KseqDebug(ctypes.Structure):
+    _fields_ = [("rho", POINTER(c_double)), ("beta", POINTER(c_double)), ("retained", POINTER(c_int32)),
+                ("lead", POINTER(c_int32)), ("accept", POINTER(c_double)), ("eta", POINTER(c_double)),
+                ("state", POINTER(c_int32)), ("res_norm", POINTER(c_double)), ("u_final", POINTER(c_double)),
+                ("margin", POINTER(c_double)), ("rho_all", POINTER(c_double)), ("beta_all", POINTER(c_double))]
+
+
 _lib = None
 
 
@@ -91,6 +98,17 @@ def lib() -> ctypes.CDLL:
                                                    POINTER(c_int32), c_int, c_int, c_int, c_int, c_int, c_int, c_float,
                                                    POINTER(c_double), POINTER(c_int32)]
         L.specgbv_oracle_carry_advance.restype = c_int
+        L.specgbv_oracle_kseq_beta.argtypes = [POINTER(c_double), POINTER(c_double), c_int, c_double]
+        L.specgbv_oracle_kseq_beta.restype = c_double
+        L.specgbv_oracle_kseq_rho.argtypes = [POINTER(c_double), POINTER(c_double), c_int, c_int]
+        L.specgbv_oracle_kseq_rho.restype = c_double
+        L.specgbv_oracle_verify_kseq.argtypes = [c_void_p, c_void_p, POINTER(c_int32), c_int, c_int, c_int, c_int, c_int,
+                                                 c_float, c_uint64, c_uint64, c_int, POINTER(c_int32), POINTER(c_int32),
+                                                 POINTER(c_int32), POINTER(_KseqDebug), POINTER(c_int32), c_int]
+        L.specgbv_oracle_verify_kseq.restype = c_int
+        L.specgbv_oracle_verify_token_sd.argtypes = [c_void_p, c_void_p, POINTER(c_int32), c_int, c_int, c_int, c_int,
+                                                     c_int, c_float, c_uint64, c_uint64, POINTER(c_int32), POINTER(c_int32)]
+        L.specgbv_oracle_verify_token_sd.restype = c_int
         L.specgbv_oracle_num_procs.argtypes = []
         L.specgbv_oracle_num_procs.restype = c_int
         _lib = L
@@ -234,6 +252,84 @@ def verify(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np
         _ip(pids) if pids is not None else None, int(nthreads))
     if rc != 0:
         raise ValueError("specgbv_oracle_verify rejected its arguments (code %d)" % rc)
+    return res
+
+
+def kseq_beta(lq, lp, rho: float) -> float:
+    """beta(rho) = sum_x min{p[x], q[x]/rho} (Section 3.2) from log-probability rows."""
+    lq = np.ascontiguousarray(lq, dtype=np.float64)
+    lp = np.ascontiguousarray(lp, dtype=np.float64)
+    assert lq.shape == lp.shape and lq.ndim == 1
+    return float(lib().specgbv_oracle_kseq_beta(_dp(lq), _dp(lp), lq.size, float(rho)))
+
+
+def kseq_rho(lq, lp, k: int) -> float:
+    """The root of 1 - (1 - beta(rho))^k = rho beta(rho) in [1, k] (Section 3.2)."""
+    lq = np.ascontiguousarray(lq, dtype=np.float64)
+    lp = np.ascontiguousarray(lp, dtype=np.float64)
+    assert lq.shape == lp.shape and lq.ndim == 1
+    return float(lib().specgbv_oracle_kseq_rho(_dp(lq), _dp(lp), lq.size, int(k)))
+
+
+def verify_kseq(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np.ndarray, temperature: float,
+                rng_seed: int, rng_offset: int, ndrafts=None, debug: bool = False, eager: bool = False,
+                nthreads: int = 1, prefix_ids=None):
+    """SpecTr K-SEQ verification (Section 3.2) with the first `ndrafts` drafts (default all K; 1 = token-level
+    speculative decoding) on the inputs of verify().  eager=True also fills rho_all / beta_all [B, K, L]."""
+    tl, dt = to_raw(target_logits)
+    dl, dt2 = to_raw(draft_logits)
+    assert dt == dt2
+    B, K, L1, V = tl.shape
+    L = L1 - 1
+    assert dl.shape == (B, K, L, V)
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    assert tok.shape == (B, K, L)
+    nd = K if ndrafts is None else int(ndrafts)
+    res = {"accepted_len": np.full(B, -9, np.int32), "accepted_draft_idx": np.full(B, -9, np.int32),
+           "out_tokens": np.full((B, L + 1), -9, np.int32)}
+    pids = None
+    if prefix_ids is not None:
+        pids = np.ascontiguousarray(prefix_ids, dtype=np.int32)
+        assert pids.shape == (B,)
+    dbg = None
+    if debug or eager:
+        nan = np.nan
+        res.update(rho=np.full((B, L), nan), beta=np.full((B, L), nan), retained=np.zeros((B, L), np.int32),
+                   lead=np.full((B, L), -1, np.int32), accept=np.full((B, K, L), nan), eta=np.full((B, K, L), nan),
+                   state=np.zeros((B, K, L), np.int32), res_norm=np.full(B, nan), u_final=np.full(B, nan),
+                   margin=np.full(B, nan))
+        if eager:
+            res.update(rho_all=np.full((B, K, L), nan), beta_all=np.full((B, K, L), nan))
+        null_d = ctypes.cast(None, POINTER(c_double))
+        dbg = _KseqDebug(_dp(res["rho"]), _dp(res["beta"]), _ip(res["retained"]), _ip(res["lead"]), _dp(res["accept"]),
+                         _dp(res["eta"]), _ip(res["state"]), _dp(res["res_norm"]), _dp(res["u_final"]),
+                         _dp(res["margin"]), _dp(res["rho_all"]) if eager else null_d,
+                         _dp(res["beta_all"]) if eager else null_d)
+    rc = lib().specgbv_oracle_verify_kseq(tl.ctypes.data_as(c_void_p), dl.ctypes.data_as(c_void_p), _ip(tok), K, L, V, B,
+                                          dt, c_float(temperature), rng_seed, rng_offset, nd, _ip(res["accepted_len"]),
+                                          _ip(res["accepted_draft_idx"]), _ip(res["out_tokens"]),
+                                          ctypes.byref(dbg) if dbg is not None else None,
+                                          _ip(pids) if pids is not None else None, int(nthreads))
+    if rc != 0:
+        raise ValueError("specgbv_oracle_verify_kseq rejected its arguments (code %d)" % rc)
+    return res
+
+
+def verify_token_sd(target_logits: np.ndarray, draft_logits: np.ndarray, draft_tokens: np.ndarray, temperature: float,
+                    rng_seed: int, rng_offset: int):
+    """Token-level speculative decoding (Section 3.1) on draft 0 of the inputs of verify()."""
+    tl, dt = to_raw(target_logits)
+    dl, dt2 = to_raw(draft_logits)
+    assert dt == dt2
+    B, K, L1, V = tl.shape
+    L = L1 - 1
+    tok = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+    res = {"accepted_len": np.full(B, -9, np.int32), "out_tokens": np.full((B, L + 1), -9, np.int32)}
+    rc = lib().specgbv_oracle_verify_token_sd(tl.ctypes.data_as(c_void_p), dl.ctypes.data_as(c_void_p), _ip(tok), K, L, V,
+                                              B, dt, c_float(temperature), rng_seed, rng_offset,
+                                              _ip(res["accepted_len"]), _ip(res["out_tokens"]))
+    if rc != 0:
+        raise ValueError("specgbv_oracle_verify_token_sd rejected its arguments (code %d)" % rc)
     return res
 
 

@@ -269,3 +269,80 @@ def random_tables(rng, V: int, L: int, denom: int = 12):
             p[block] = rand_dist()
             q[block] = rand_dist()
     return table_from_dict(p), table_from_dict(q)
+
+
+# ---------------------------------------------------------------------------
+# SpecTr K-SEQ (Section 3.2): brute force in float64 (rho is the root of a polynomial-like equation and is
+# irrational in general, so this part cannot be exact rationals; every other step is a finite enumeration).
+
+def kseq_rho_float(p, q, k: int) -> float:
+    """Root of 1 - (1 - beta(rho))^k = rho beta(rho), beta(rho) = sum_x min{p[x], q[x]/rho}, in [1, k]."""
+    if k <= 1:
+        return 1.0
+
+    def f(rho):
+        b = sum(min(float(px), float(qx) / rho) for px, qx in zip(p, q))
+        return rho * b - 1.0 + (1.0 - b) ** k
+
+    lo, hi = 1.0, float(k)
+    if f(lo) >= 0.0:
+        return lo
+    for _ in range(200):
+        mid = 0.5 * (lo + hi)
+        if not (lo < mid < hi):
+            break
+        if f(mid) >= 0.0:
+            hi = mid
+        else:
+            lo = mid
+    return hi
+
+
+def enumerate_kseq(p_of: Table, q_of: Table, V: int, L: int, K: int, retained_reading: bool = True):
+    """Law of the K-SEQ procedure's output (Section 3.2) on autoregressive tables, by enumeration of every draft
+    tuple and every accept/reject branch.  Returns (dist, E_tau): dist maps the emitted token tuple (accepted
+    tokens followed by the residual or bonus token) to its probability.  With retained_reading=False the root is
+    taken for k = K at every position instead of the number of drafts still retained (shown by the tests to
+    break the output law: this is why the other reading is the one implemented)."""
+    dist: Dict[Block, float] = {}
+    E_tau = 0.0
+    blocks = list(itertools.product(range(V), repeat=L))
+    for drafts in itertools.product(blocks, repeat=K):
+        pd = 1.0
+        for d in drafts:
+            pd *= float(joint(p_of, d))
+        if pd == 0.0:
+            continue
+
+        def rec(i, alive, accepted, pr):
+            nonlocal E_tau
+            if pr == 0.0:
+                return
+            if i == L:                                   # every position accepted: bonus token from q(.|x^L)
+                qrow = [float(v) for v in q_of(accepted)]
+                E_tau += pr * L
+                for y in range(V):
+                    if qrow[y] > 0:
+                        dist[accepted + (y,)] = dist.get(accepted + (y,), 0.0) + pr * qrow[y]
+                return
+            p = [float(v) for v in p_of(accepted)]
+            q = [float(v) for v in q_of(accepted)]
+            rho = kseq_rho_float(p, q, len(alive) if retained_reading else K)
+            beta = sum(min(p[x], q[x] / rho) for x in range(V))
+            none_yet = pr
+            for j in alive:                              # candidates in draft order; the first accepted one wins
+                x = drafts[j][i]
+                a = min(1.0, q[x] / (rho * p[x])) if p[x] > 0 else 1.0
+                nxt = tuple(m for m in alive if drafts[m][i] == x)
+                rec(i + 1, nxt, accepted + (x,), none_yet * a)
+                none_yet *= 1.0 - a
+            if none_yet > 0.0:                           # all rejected: residual (q - rho min{p, q/rho}) / (1 - rho beta)
+                E_tau += none_yet * i
+                norm = 1.0 - rho * beta
+                for y in range(V):
+                    w = q[y] - rho * min(p[y], q[y] / rho)
+                    if w > 0 and norm > 0:
+                        dist[accepted + (y,)] = dist.get(accepted + (y,), 0.0) + none_yet * w / norm
+
+        rec(0, tuple(range(K)), (), pd)
+    return dist, E_tau

@@ -725,3 +725,283 @@ int specgbv_oracle_carry_advance(const void *rows_q, const void *rows_p, const i
     free(z); free(lq); free(lp);
     return 0;
 }
+
+/* ============================================================================
+ * Comparison verifiers (paper Section 3: the methods SpecTr-GBV is measured against).
+ *
+ * Section 3.1, token-level speculative decoding: one draft; token x^(i) is accepted with probability
+ * min{1, q(x^(i)|x^{i-1}) / p(x^(i)|x^{i-1})}; at the first rejection the replacement is drawn from
+ * norm(max{q - p, 0}) of that position; if all L tokens are accepted a bonus token comes from q(.|x^L).
+ *
+ * Section 3.2, SpecTr with the K-SEQ rule: K i.i.d. drafts, verified position by position.  At a position the
+ * candidates are the tokens of the drafts still retained (those that agree with everything accepted so far),
+ * taken in draft order; a candidate x is accepted with probability min{1, q(x) / (rho p(x))}, the first accepted
+ * one is emitted and the drafts that carry it stay retained; if none is accepted the replacement is drawn from
+ * (q - rho min{p, q/rho}) / (1 - rho beta(rho)) and the iteration ends.  rho in [1, k] solves
+ *     1 - (1 - beta(rho))^k = rho beta(rho),    beta(rho) = sum_x min{p(x), q(x)/rho}.
+ * Reading taken where the text is silent: k is the number of drafts retained AT THAT POSITION (K at the first
+ * one).  Only with this k is the printed residual the right one: the chance that a given token x is emitted
+ * by acceptance is [1 - (1-beta)^k] / beta * min{p(x), q(x)/rho}, which must not exceed q(x) and equals
+ * rho min{p, q/rho} exactly when the equation holds for the k candidates actually tested.  (Tests confirm by
+ * enumeration that the emitted token is then distributed as q for every K, and is not with a fixed k = K.)
+ * The distributions of a position are read from the rows of the retained draft of lowest index.
+ * k = 1 gives rho = 1, i.e. Section 3.1.
+ *
+ * Uniforms: test of draft j at position i uses Philox slot j*L + (i-1), the final token slot K*L (the scheme
+ * of the main verifier; the calls are separate, so sharing slots is harmless).
+ * ========================================================================== */
+
+/* beta(rho) = sum_x min{p[x], q[x]/rho}, plain left-to-right. */
+double specgbv_oracle_kseq_beta(const double *lq, const double *lp, int V, double rho)
+{
+    double b = 0.0;
+    for (int x = 0; x < V; ++x) {
+        const double p = exp(lp[x]), qr = exp(lq[x]) / rho;
+        b += p < qr ? p : qr;
+    }
+    return b;
+}
+
+/* f(rho) = rho beta(rho) - 1 + (1 - beta(rho))^k: non-positive at rho = 1, non-negative at rho = k, increasing. */
+static double kseq_f(const double *lq, const double *lp, int V, double rho, int k)
+{
+    const double b = specgbv_oracle_kseq_beta(lq, lp, V, rho);
+    return rho * b - 1.0 + ipow(1.0 - b, k);
+}
+
+/* The root of 1 - (1 - beta(rho))^k = rho beta(rho) in [1, k] by bisection (200 halvings at most: far below
+ * one unit in the last place; the function is increasing, so the root is unique; where it vanishes on a
+ * whole interval, e.g. p == q, the left end is returned). */
+double specgbv_oracle_kseq_rho(const double *lq, const double *lp, int V, int k)
+{
+    if (k <= 1) return 1.0;
+    double lo = 1.0, hi = (double)k;
+    if (kseq_f(lq, lp, V, lo, k) >= 0.0) return lo;
+    for (int it = 0; it < 200; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (!(mid > lo && mid < hi)) break;
+        if (kseq_f(lq, lp, V, mid, k) >= 0.0) hi = mid; else lo = mid;
+    }
+    return hi;
+}
+
+/* Optional intermediates of the comparison verifiers (any pointer may be NULL). */
+typedef struct {
+    double *rho;        /* [B, L] rho used at position i (index i-1); NaN where the position was not reached  */
+    double *beta;       /* [B, L] beta(rho) there                                                             */
+    int32_t *retained;  /* [B, L] number of drafts retained when position i was verified (0: not reached)     */
+    int32_t *lead;      /* [B, L] the retained draft of lowest index there (-1: not reached)                  */
+    double *accept;     /* [B, K, L] acceptance probability of draft j's token at position i where tested    */
+    double *eta;        /* [B, K, L] uniform of that test                                                     */
+    int32_t *state;     /* [B, K, L] 0 not tested, 1 tested                                                   */
+    double *res_norm;   /* [B] total weight the final token was drawn from (1 - rho beta, or 1 for the bonus) */
+    double *u_final;    /* [B] */
+    double *margin;     /* [B] */
+    double *rho_all;    /* [B, K, L] eager table: rho of row r of draft j with k = number of drafts sharing   */
+    double *beta_all;   /*            x_j^r (what a data-parallel implementation computes up front)          */
+} specgbv_oracle_kseq_debug;
+
+static void kseq_one(const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+                     int K, int L, int V, int b, uint32_t pid, int dtype, double T, uint64_t seed, uint64_t offset,
+                     int ndrafts, int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
+                     const specgbv_oracle_kseq_debug *dbg)
+{
+    const size_t KL = (size_t)K * L;
+    double *z = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lq = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)V);
+    double *w = (double *)malloc(sizeof(double) * (size_t)V);
+    int *alive = (int *)malloc(sizeof(int) * (size_t)K);
+    const int32_t *tokens = draft_tokens + (size_t)b * KL;
+    if (dbg) {
+        for (int i = 0; i < L; ++i) {
+            if (dbg->rho) dbg->rho[(size_t)b * L + i] = NAN;
+            if (dbg->beta) dbg->beta[(size_t)b * L + i] = NAN;
+            if (dbg->retained) dbg->retained[(size_t)b * L + i] = 0;
+            if (dbg->lead) dbg->lead[(size_t)b * L + i] = -1;
+        }
+        for (size_t j = 0; j < KL; ++j) {
+            if (dbg->accept) dbg->accept[(size_t)b * KL + j] = NAN;
+            if (dbg->eta) dbg->eta[(size_t)b * KL + j] = NAN;
+            if (dbg->state) dbg->state[(size_t)b * KL + j] = 0;
+        }
+    }
+    /* eager table for parity with data-parallel implementations: every (draft, row) with its own sharing count */
+    if (dbg && (dbg->rho_all || dbg->beta_all)) {
+        for (int j = 0; j < ndrafts; ++j)
+            for (int r = 0; r < L; ++r) {
+                int k = 0;
+                for (int m = 0; m < ndrafts; ++m) k += same_block(tokens + (size_t)m * L, tokens + (size_t)j * L, r);
+                load_row(target_logits, dtype, ((size_t)b * K + j) * (size_t)(L + 1) + r, V, z);
+                specgbv_oracle_log_softmax(z, V, T, lq);
+                load_row(draft_logits, dtype, ((size_t)b * K + j) * (size_t)L + r, V, z);
+                specgbv_oracle_log_softmax(z, V, T, lp);
+                const double rho = specgbv_oracle_kseq_rho(lq, lp, V, k);
+                if (dbg->rho_all) dbg->rho_all[(size_t)b * KL + (size_t)j * L + r] = rho;
+                if (dbg->beta_all) dbg->beta_all[(size_t)b * KL + (size_t)j * L + r] = specgbv_oracle_kseq_beta(lq, lp, V, rho);
+            }
+    }
+
+    int n = ndrafts, tau = 0, rejected = 0;
+    for (int j = 0; j < n; ++j) alive[j] = j;
+    double rho = 1.0, beta = 0.0;
+    for (int i = 1; i <= L && !rejected; ++i) {
+        const int r = i - 1, lead = alive[0];
+        load_row(target_logits, dtype, ((size_t)b * K + lead) * (size_t)(L + 1) + r, V, z);
+        specgbv_oracle_log_softmax(z, V, T, lq);
+        load_row(draft_logits, dtype, ((size_t)b * K + lead) * (size_t)L + r, V, z);
+        specgbv_oracle_log_softmax(z, V, T, lp);
+        rho = specgbv_oracle_kseq_rho(lq, lp, V, n);
+        beta = specgbv_oracle_kseq_beta(lq, lp, V, rho);
+        if (dbg) {
+            if (dbg->rho) dbg->rho[(size_t)b * L + r] = rho;
+            if (dbg->beta) dbg->beta[(size_t)b * L + r] = beta;
+            if (dbg->retained) dbg->retained[(size_t)b * L + r] = n;
+            if (dbg->lead) dbg->lead[(size_t)b * L + r] = lead;
+        }
+        int winner = -1;
+        for (int a = 0; a < n && winner < 0; ++a) {
+            const int j = alive[a];
+            const int32_t x = tokens[(size_t)j * L + r];
+            const double ratio = exp(lq[x] - lp[x]) / rho;
+            const double acc = ratio < 1.0 ? ratio : 1.0;
+            const double eta = specgbv_oracle_uniform(seed, offset, pid, (uint32_t)(j * L + r));
+            if (dbg) {
+                if (dbg->accept) dbg->accept[(size_t)b * KL + (size_t)j * L + r] = acc;
+                if (dbg->eta) dbg->eta[(size_t)b * KL + (size_t)j * L + r] = eta;
+                if (dbg->state) dbg->state[(size_t)b * KL + (size_t)j * L + r] = 1;
+            }
+            if (eta < acc) winner = j;
+        }
+        if (winner < 0) { rejected = 1; break; }
+        const int32_t t = tokens[(size_t)winner * L + r];
+        int m = 0;
+        for (int a = 0; a < n; ++a)
+            if (tokens[(size_t)alive[a] * L + r] == t) alive[m++] = alive[a];
+        n = m;
+        tau = i;
+    }
+    /* final token: the residual of the position where every candidate failed, or the bonus token */
+    const int lead = alive[0];
+    if (rejected) {
+        /* lq, lp, rho still hold that position: q - rho min{p, q/rho} = max{q - rho p, 0} */
+        for (int x = 0; x < V; ++x) {
+            const double q = exp(lq[x]), p = exp(lp[x]);
+            const double m = p < q / rho ? p : q / rho;
+            w[x] = q - rho * m;
+            if (w[x] < 0.0) w[x] = 0.0;
+        }
+    } else {
+        load_row(target_logits, dtype, ((size_t)b * K + lead) * (size_t)(L + 1) + L, V, z);
+        specgbv_oracle_log_softmax(z, V, T, lq);
+        for (int x = 0; x < V; ++x) w[x] = exp(lq[x]);
+    }
+    const double u = specgbv_oracle_uniform(seed, offset, pid, (uint32_t)KL);
+    double W = 0.0, margin = 0.0;
+    int32_t y = specgbv_oracle_sample_cdf(w, V, u, &W, &margin);
+    if (y < 0) {                                 /* only through rounding (a rejection needs 1 - rho beta > 0) */
+        for (int x = 0; x < V; ++x) w[x] = exp(lq[x]);
+        y = specgbv_oracle_sample_cdf(w, V, u, &W, &margin);
+    }
+    accepted_len[b] = tau;
+    if (accepted_draft_idx) accepted_draft_idx[b] = tau > 0 ? lead : -1;
+    for (int j = 0; j <= L; ++j) {
+        int32_t v = -1;
+        if (j < tau) v = tokens[(size_t)lead * L + j];
+        else if (j == tau) v = y;
+        out_tokens[(size_t)b * (L + 1) + j] = v;
+    }
+    if (dbg) {
+        if (dbg->res_norm) dbg->res_norm[b] = W;
+        if (dbg->u_final) dbg->u_final[b] = u;
+        if (dbg->margin) dbg->margin[b] = margin;
+    }
+    free(z); free(lq); free(lp); free(w); free(alive);
+}
+
+/*
+ * SpecTr K-SEQ verification (Section 3.2) on the inputs of specgbv_oracle_verify, using the first `ndrafts`
+ * of the K drafts (ndrafts = K: SpecTr; ndrafts = 1: rho = 1, i.e. token-level speculative decoding).
+ * accepted_draft_idx (may be NULL) receives the retained draft of lowest index, -1 when nothing was accepted.
+ * Returns 0, or 1 for invalid arguments.
+ */
+int specgbv_oracle_verify_kseq(const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+                               int K, int L, int V, int batch, int dtype, float temperature,
+                               uint64_t rng_seed, uint64_t rng_offset, int ndrafts,
+                               int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
+                               const specgbv_oracle_kseq_debug *dbg, const int32_t *prefix_ids, int nthreads)
+{
+    if (!target_logits || !draft_logits || !draft_tokens || !accepted_len || !out_tokens) return 1;
+    if (K < 1 || L < 1 || V < 1 || batch < 0 || ndrafts < 1 || ndrafts > K) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F64) return 1;
+    if (!(temperature > 0.0f) || !isfinite(temperature)) return 1;
+    for (size_t j = 0; j < (size_t)batch * K * L; ++j)
+        if (draft_tokens[j] < 0 || draft_tokens[j] >= V) return 1;
+    const double T = (double)temperature;
+    (void)nthreads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 1 ? nthreads : 1)
+#endif
+    for (int b = 0; b < batch; ++b)
+        kseq_one(target_logits, draft_logits, draft_tokens, K, L, V, b,
+                 prefix_ids ? (uint32_t)prefix_ids[b] : (uint32_t)b, dtype, T, rng_seed, rng_offset, ndrafts,
+                 accepted_len, accepted_draft_idx, out_tokens, dbg);
+    return 0;
+}
+
+/*
+ * Token-level speculative decoding (Section 3.1) written out from its own definition, on draft 0 of the same
+ * inputs: accept x^(i) with probability min{1, q/p}, residual norm(max{q - p, 0}), bonus token after L
+ * acceptances.  Same uniforms as specgbv_oracle_verify_kseq with ndrafts = 1 (slot i-1, final slot K*L), so the
+ * two must agree token for token: that is one of the pins of the K-SEQ code.
+ */
+int specgbv_oracle_verify_token_sd(const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+                                   int K, int L, int V, int batch, int dtype, float temperature,
+                                   uint64_t rng_seed, uint64_t rng_offset, int32_t *accepted_len, int32_t *out_tokens)
+{
+    if (!target_logits || !draft_logits || !draft_tokens || !accepted_len || !out_tokens) return 1;
+    if (K < 1 || L < 1 || V < 1 || batch < 0) return 1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16 && dtype != ORACLE_F64) return 1;
+    if (!(temperature > 0.0f) || !isfinite(temperature)) return 1;
+    const double T = (double)temperature;
+    double *z = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lq = (double *)malloc(sizeof(double) * (size_t)V);
+    double *lp = (double *)malloc(sizeof(double) * (size_t)V);
+    double *w = (double *)malloc(sizeof(double) * (size_t)V);
+    for (int b = 0; b < batch; ++b) {
+        const int32_t *tok = draft_tokens + (size_t)b * K * L;     /* draft 0 */
+        int tau = 0, rejected = 0;
+        for (int i = 1; i <= L; ++i) {
+            load_row(target_logits, dtype, ((size_t)b * K) * (size_t)(L + 1) + (i - 1), V, z);
+            specgbv_oracle_log_softmax(z, V, T, lq);
+            load_row(draft_logits, dtype, ((size_t)b * K) * (size_t)L + (i - 1), V, z);
+            specgbv_oracle_log_softmax(z, V, T, lp);
+            const int32_t x = tok[i - 1];
+            if (x < 0 || x >= V) { free(z); free(lq); free(lp); free(w); return 1; }
+            const double ratio = exp(lq[x] - lp[x]);
+            const double alpha = ratio < 1.0 ? ratio : 1.0;
+            if (specgbv_oracle_uniform(rng_seed, rng_offset, (uint32_t)b, (uint32_t)(i - 1)) < alpha) { tau = i; continue; }
+            for (int v = 0; v < V; ++v) {
+                const double d = exp(lq[v]) - exp(lp[v]);
+                w[v] = d > 0.0 ? d : 0.0;
+            }
+            rejected = 1;
+            break;
+        }
+        if (!rejected) {
+            load_row(target_logits, dtype, ((size_t)b * K) * (size_t)(L + 1) + L, V, z);
+            specgbv_oracle_log_softmax(z, V, T, lq);
+            for (int v = 0; v < V; ++v) w[v] = exp(lq[v]);
+        }
+        const double u = specgbv_oracle_uniform(rng_seed, rng_offset, (uint32_t)b, (uint32_t)(K * L));
+        int32_t y = specgbv_oracle_sample_cdf(w, V, u, NULL, NULL);
+        if (y < 0) {
+            for (int v = 0; v < V; ++v) w[v] = exp(lq[v]);
+            y = specgbv_oracle_sample_cdf(w, V, u, NULL, NULL);
+        }
+        accepted_len[b] = tau;
+        for (int j = 0; j <= L; ++j) out_tokens[(size_t)b * (L + 1) + j] = j < tau ? tok[j] : (j == tau ? y : -1);
+    }
+    free(z); free(lq); free(lp); free(w);
+    return 0;
+}
