@@ -55,7 +55,8 @@ FULL_WORKLOAD = True        # False with --batch: the committed traffic figures 
 
 def committed_traffic(tag: str):
     """HBM bytes per call from the committed rocprofv3 --pmc summary profiles/hbm_traffic_<tag>.txt (FETCH_SIZE +
-    WRITE_SIZE, calibrated against a plain copy), or None."""
+    WRITE_SIZE, calibrated against a plain copy), or None.  The figure is NOT measured in this run (counters need
+    the profiler): traffic_source() says which file it comes from and what that file says about its origin."""
     if not FULL_WORKLOAD:
         return None
     path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % tag)
@@ -64,6 +65,16 @@ def committed_traffic(tag: str):
             if line.startswith("traffic_bytes_per_launch:"):
                 return float(line.split(":", 1)[1])
     return None
+
+
+def traffic_source(tag: str):
+    """Provenance of committed_traffic(tag): the file and its `measured:` line (date, kernel source revision)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % tag)
+    if not FULL_WORKLOAD or not os.path.exists(path):
+        return None
+    measured = [ln.split(":", 1)[1].strip() for ln in open(path) if ln.startswith("measured:")]
+    return {"file": "profiles/hbm_traffic_%s.txt" % tag, "measured": measured[0] if measured else "not recorded",
+            "note": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, not of this run"}
 
 
 def bench_modify(a, w, sg, torch, tl, dl, tk, ws, out):
@@ -239,6 +250,57 @@ def bench_sample(a, w, sg, torch, dl):
     }
 
 
+def bench_compare(a, w, sg, torch, tl, dl, tk):
+    """Accepted tokens per iteration and verification time of the four verifiers the paper compares (its Table 1 /
+    Table 2 / Fig. 2, on synthetic logits): token-level speculative decoding (Section 3.1, draft 0), greedy block
+    verification (Section 3.3 = the main verifier at K = 1, draft 0), SpecTr K-SEQ (Section 3.2) and SpecTr-GBV
+    (Algorithm 1), each with the first k of the K drafts for k in a small sweep.  One 'call' verifies the whole
+    batch; accepted lengths are averaged over the batch and over --steps calls with different Philox offsets."""
+    dev = tl.device
+    ks = sorted({k for k in (1, 2, 3, 4, 5, 8, 16) if k <= w.K} | {w.K})
+    rows = []
+
+    def run(name, k, fn):
+        t_k = tl[:, :k].contiguous() if k < w.K else tl
+        d_k = dl[:, :k].contiguous() if k < w.K else dl
+        tok_k = tk[:, :k].contiguous() if k < w.K else tk
+        dt = 1 if w.dtype == "bf16" else 0
+        ws = torch.empty(sg.specgbv_workspace_bytes(w.batch, k, w.L, w.V, dt), dtype=torch.uint8, device=dev)
+        out = (torch.empty(w.batch, dtype=torch.int32, device=dev), torch.empty(w.batch, dtype=torch.int32, device=dev),
+               torch.empty((w.batch, w.L + 1), dtype=torch.int32, device=dev))
+        for i in range(max(a.warmup // 10, 3)):
+            fn(t_k, d_k, tok_k, i, ws, out)
+        torch.cuda.synchronize()
+        acc = torch.zeros((), dtype=torch.float64, device=dev)
+        t0 = time.perf_counter()
+        for i in range(a.steps):
+            fn(t_k, d_k, tok_k, 100 + i, ws, out)
+            acc += out[0].double().mean()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / a.steps
+        rows.append({"verifier": name, "drafts": k, "mean_accepted_len": float(acc.item()) / a.steps,
+                     "tokens_per_iteration": float(acc.item()) / a.steps + 1.0, "ms_per_call": ms})
+
+    gbv = lambda t, d, tok, off, ws, out: sg.specgbv_verify_ex(t, d, tok, w.temperature, a.seed, off, workspace=ws, out=out)
+    kseq = lambda t, d, tok, off, ws, out: sg.specgbv_verify_kseq(t, d, tok, w.temperature, a.seed, off, workspace=ws, out=out)
+    run("token-level SD (Section 3.1)", 1, kseq)
+    run("GBV (Section 3.3)", 1, gbv)
+    for k in ks:
+        if k > 1:
+            run("SpecTr K-SEQ (Section 3.2)", k, kseq)
+            run("SpecTr-GBV (Algorithm 1)", k, gbv)
+    best = max(r["tokens_per_iteration"] for r in rows)
+    return {
+        "metric": "accepted tokens per iteration and verification ms per call of the four verifiers of the paper's comparison",
+        "value": best, "unit": "tokens/iteration (best verifier)", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": rows[-1]["ms_per_call"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: batch %d, K=%d, L=%d, V=%d, %s logits, T=%g" % (
+            w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature)},
+        "table": rows,
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -249,12 +311,13 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg4", choices=sorted(WORKLOADS))
     ap.add_argument("--algo", default="auto", choices=["auto", "split", "chain"])
-    ap.add_argument("--op", default="verify", choices=["verify", "modify", "sample", "pending", "iterate"],
+    ap.add_argument("--op", default="verify", choices=["verify", "modify", "sample", "pending", "iterate", "compare"],
                     help="verify: the verification call (the benchmark); modify: the distribution modification "
                          "(Algorithm 2) for the drafts of the next iteration, on the same tensors; "
                          "sample: the draft-side token draw of one position (Algorithm 3) over the batch * K draft rows; "
                          "pending: the verification with a pending modification applied on the fly; "
-                         "iterate: the verification with the pending state (all pending modifications and their bookkeeping)")
+                         "iterate: the verification with the pending state (all pending modifications and their bookkeeping); "
+                         "compare: accepted lengths and times of token-level SD, GBV, SpecTr K-SEQ and SpecTr-GBV on the same inputs")
     ap.add_argument("--shared-row0", type=int, default=0, choices=[0, 1],
                     help="verify only: tell the library that rows 0 of a prefix's K drafts are copies of one another "
                          "(they are in these inputs, as in Algorithm 3); the chain schedule then reads them once per "
@@ -264,6 +327,10 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0,
                     help="use only the first N prefixes of the workload (0 = all); a reduced batch is not the benchmark "
                          "configuration: for latency measurements at small batches")
+    ap.add_argument("--settle-ms", type=float, default=80.0,
+                    help="verify only: before the --warmup calls, keep issuing the same call for this many milliseconds "
+                         "(untimed): under this kernel's load the shader clock takes some tens of milliseconds to settle, "
+                         "and a serving GPU is always in the settled state; 0 switches it off.  Reported in the JSON")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--workers", type=int, default=0, help="input-generation processes (0 = one per CPU, at most 16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -325,6 +392,9 @@ def main() -> int:
     if a.op == "sample":
         print(json.dumps(bench_sample(a, w, sg, torch, dl)))
         return 0
+    if a.op == "compare":
+        print(json.dumps(bench_compare(a, w, sg, torch, tl, dl, tk)))
+        return 0
     if a.op == "modify":
         print(json.dumps(bench_modify(a, w, sg, torch, tl, dl, tk, ws, out)))
         return 0
@@ -336,6 +406,14 @@ def main() -> int:
         print(json.dumps(bench_iterate(a, w, sg, torch, sets, ws, out)))
         return 0
 
+    settle_calls = 0
+    if a.settle_ms > 0:                                    # untimed: lets the clock reach its state under load
+        t_end = time.perf_counter() + a.settle_ms * 1e-3
+        while time.perf_counter() < t_end:
+            for _ in range(16):
+                step(1 << 20)
+            settle_calls += 16
+            torch.cuda.synchronize()
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -357,7 +435,8 @@ def main() -> int:
     for i, (e0, e1) in enumerate(evs):
         step(a.warmup + a.steps + i, events=(e0.cuda_event, e1.cuda_event))
     torch.cuda.synchronize()
-    main_ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    series = [e0.elapsed_time(e1) for e0, e1 in evs]        # in call order: shows the clock settling, if it does
+    main_ms = sorted(series)
     main_avg = sum(main_ms) / len(main_ms)
     main_bytes = w.row_pairs * w.V * 2 * w.elem_bytes       # every (target, draft) row pair once
     dedup = bool(a.shared_row0) and a.algo != "split" and w.L >= 2
@@ -367,7 +446,8 @@ def main() -> int:
 
     # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE +
     # WRITE_SIZE, calibrated against a plain copy), if one exists for this workload and schedule
-    traffic = committed_traffic(a.workload + ("_shared_row0" if dedup else "")) if a.algo != "split" else None
+    ttag = a.workload + ("_shared_row0" if dedup else "")
+    traffic = committed_traffic(ttag) if a.algo != "split" else None
 
     res = {
         "metric": "verifications/sec and achieved HBM GB/s (% of peak) at K=8, L=8, V=128256",
@@ -380,11 +460,19 @@ def main() -> int:
                        w.name, w.batch, w.K, w.L, w.V, w.dtype, w.temperature),
                    "algo": a.algo, "shared_row0": bool(a.shared_row0), "row_pairs_per_s": w.row_pairs / (ms_per_step * 1e-3),
                    "whole_call_algorithmic_GBps": w.algorithmic_bytes / (ms_per_step * 1e-3) / 1e9,
-                   "mean_accepted_len": tau_mean, "input_generation_s": round(gen_s, 1)},
+                   "mean_accepted_len": tau_mean, "input_generation_s": round(gen_s, 1),
+                   "settle": {"ms": a.settle_ms, "calls": settle_calls,
+                              "note": "untimed calls before the warm-up calls, so that the shader clock is in its state under load"}},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "vocabulary-streaming kernels (statistics + sums of Eq. (hik))",
                      "kernel_ms_avg": main_avg, "kernel_ms_min": main_ms[0],
+                     "kernel_ms_median": main_ms[len(main_ms) // 2],
+                     "kernel_ms_first5": [round(v, 4) for v in series[:5]],
+                     "kernel_ms_last5": [round(v, 4) for v in series[-5:]],
+                     "kernel_calls_above_1.05x_min": sum(1 for v in series if v > 1.05 * main_ms[0]),
+                     "kernel_calls": len(series),
+                     "traffic_source": traffic_source(ttag) if traffic is not None else None,
                      "algorithmic_bytes_per_launch": main_bytes},
     }
 
@@ -412,7 +500,7 @@ def main() -> int:
         n = int(max(2, min(w.batch, a.cpu_seconds / max(per, 1e-9))))
         t0 = time.perf_counter()
         ref = oracle.verify(target[:n], draft[:n], tokens[:n], w.temperature, a.seed, a.warmup + a.steps - 1,
-                            nthreads=1)
+                            nthreads=1, debug=True)
         cpu_s = time.perf_counter() - t0
         res["cpu_baseline"] = {"value": n / cpu_s, "unit": "verifications/s", "cores": 1, "kind": "oracle",
                                "sample": "first %d of %d prefixes of the same batch, float64, 1 thread, %.1f s" % (
@@ -431,6 +519,23 @@ def main() -> int:
         got = out[0][:n].cpu().numpy()
         res["config"]["sample_accepted_len_agree"] = int((got == ref["accepted_len"]).sum())
         res["config"]["sample_size"] = n
+        # the parity bar's counted events on the same sample: decisions and final tokens whose margin is below 1e-6
+        # (they may differ), and the differences actually seen
+        inter = sg.specgbv_read_intermediates(ws, w.batch, w.K, w.L, w.V, dt)
+        g_f, g_tok = out[1][:n].cpu().numpy(), out[2][:n].cpu().numpy()
+        tested = (ref["state"] == 1) | (inter["state"][:n] == 1)
+        dist = np.minimum(np.abs(ref["eta"] - ref["h"]), np.abs(inter["eta"][:n] - inter["h"][:n]))
+        low_dec = np.array([bool(np.any(dist[b][tested[b]] < 1e-6)) for b in range(n)])
+        same_dec = (got == ref["accepted_len"]) & (g_f == ref["accepted_draft_idx"])
+        low_tok = (ref["margin"] < 1e-6) | (inter["margin"][:n] < 1e-6)
+        same_tok = np.array([np.array_equal(g_tok[b], ref["out_tokens"][b]) for b in range(n)])
+        res["parity_sample"] = {
+            "prefixes": n, "low_margin_decisions": int(low_dec.sum()), "decision_mismatches": int((~same_dec).sum()),
+            "decision_mismatches_outside_margin": int((~same_dec & ~low_dec).sum()),
+            "low_margin_tokens": int((same_dec & low_tok).sum()), "token_mismatches": int((same_dec & ~same_tok).sum()),
+            "token_mismatches_outside_margin": int((same_dec & ~same_tok & ~low_tok).sum()),
+            "max_h_error_over_bar": float((np.abs(inter["h"][:n] - ref["h"]) / (1e-5 * np.abs(ref["h"]) + 1e-9)).max()),
+            "bar": "tau, f, tokens bit-exact unless a margin is below 1e-6; h within 1e-5 |h| + 1e-9"}
     print(json.dumps(res))
     return 0
 

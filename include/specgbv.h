@@ -132,6 +132,52 @@ specgbv_status specgbv_verify_static(
     uint64_t rng_seed, uint64_t rng_offset,
     int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens, void *hip_stream);
 
+/*
+ * Comparison verifiers on the same inputs (paper Section 3, the methods SpecTr-GBV is measured against):
+ * SpecTr's K-SEQ rule (Section 3.2) on the first `ndrafts` of the K drafts; ndrafts = 1 is token-level
+ * speculative decoding (Section 3.1: accept x with probability min{1, q/p}, residual norm(max{q - p, 0})).
+ *
+ * Position by position, the candidates are the tokens of the drafts still retained (those that agree with
+ * everything accepted so far), in draft order; candidate x is accepted with probability
+ * min{1, q(x) / (rho p(x))}; the first accepted one is emitted and the drafts carrying it stay retained; if none
+ * is accepted the replacement is drawn from (q - rho min{p, q/rho}) / (1 - rho beta(rho)) and the iteration ends;
+ * after L accepted positions a bonus token is drawn from target row L.  rho in [1, k] solves
+ * 1 - (1 - beta(rho))^k = rho beta(rho), beta(rho) = sum_x min{p(x), q(x)/rho}, with k the number of drafts
+ * retained at that position (K at the first one; this reading keeps the output distributed as the target).
+ * The distributions of a position are read from the rows of the retained draft of lowest index.
+ *
+ * Arguments, outputs, workspace (specgbv_workspace_bytes of the same shape) and error behaviour as specgbv_verify;
+ * accepted_draft_idx receives the retained draft of lowest index (-1 when nothing was accepted).  Uniforms:
+ * Philox slot j*L + (i-1) for draft j's test at position i, slot K*L for the final token.
+ */
+specgbv_status specgbv_verify_kseq(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int L, int V, int batch, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset, int ndrafts,
+    int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
+    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* HOST buffers receiving the intermediates of the last specgbv_verify_kseq call that used a workspace (any
+ * pointer may be NULL); Section 3.2. */
+typedef struct specgbv_kseq_intermediates {
+    double *rho_all;     /* [batch, K, L]  rho of row r of draft j, solved for the number of drafts sharing   */
+                         /*                draft j's first r tokens (drafts beyond ndrafts: not written)     */
+    double *beta_all;    /* [batch, K, L]  beta(rho) there                                                    */
+    double *accept;      /* [batch, K, L]  acceptance probability of draft j's token at position r+1          */
+    double *eta;         /* [batch, K, L]  uniform of that test                                               */
+    int32_t *state;      /* [batch, K, L]  1 where the test was performed                                     */
+    int32_t *retained;   /* [batch, L]     drafts retained when position r+1 was verified (0: not reached)    */
+    int32_t *lead;       /* [batch, L]     the lowest of them (-1: not reached)                               */
+    double *res_norm;    /* [batch] total weight the final token was drawn from                               */
+    double *u_final;     /* [batch] */
+    double *margin;      /* [batch] */
+} specgbv_kseq_intermediates;
+
+/* Copies them to host memory and waits for the copies (debug/parity aid). */
+specgbv_status specgbv_read_kseq_intermediates(
+    const void *workspace, size_t workspace_bytes, int batch, int K, int L, int V,
+    const specgbv_kseq_intermediates *host_out, void *hip_stream);
+
 #define SPECGBV_MAX_PENDING 16  /* pending distribution modifications applied on the fly at most */
 
 /* Extra controls for specgbv_verify_ex; zero-initialise for the defaults. */

@@ -8,7 +8,7 @@ from .binding import (ALGO_AUTO, ALGO_CHAIN, ALGO_SPLIT, MAX_PENDING, SpecGBVErr
                       specgbv_modify_target, specgbv_modify_workspace_bytes, specgbv_pending_state_bytes,
                       specgbv_read_intermediates,
                       specgbv_read_sample_intermediates, specgbv_sample_tokens, specgbv_sample_workspace_bytes,
-                      specgbv_verify, specgbv_verify_ex, specgbv_verify_static, specgbv_version, specgbv_workspace_bytes,
+                      specgbv_verify, specgbv_verify_ex, specgbv_verify_kseq, specgbv_read_kseq_intermediates, specgbv_verify_static, specgbv_version, specgbv_workspace_bytes,
                       specgbv_workspace_carry)
 
 __all__ = ["ALGO_AUTO", "ALGO_CHAIN", "ALGO_SPLIT", "MAX_PENDING", "SpecGBVError", "pending_state_views", "load_library", "specgbv_carry_advance",
@@ -16,5 +16,5 @@ __all__ = ["ALGO_AUTO", "ALGO_CHAIN", "ALGO_SPLIT", "MAX_PENDING", "SpecGBVError
            "specgbv_modify_target", "specgbv_modify_workspace_bytes", "specgbv_pending_state_bytes",
            "specgbv_read_intermediates",
            "specgbv_read_sample_intermediates", "specgbv_sample_tokens", "specgbv_sample_workspace_bytes",
-           "specgbv_verify", "specgbv_verify_ex", "specgbv_verify_static", "specgbv_version", "specgbv_workspace_bytes",
+           "specgbv_verify", "specgbv_verify_ex", "specgbv_verify_kseq", "specgbv_read_kseq_intermediates", "specgbv_verify_static", "specgbv_version", "specgbv_workspace_bytes",
            "specgbv_workspace_carry"]

@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 ALGO_AUTO, ALGO_SPLIT, ALGO_CHAIN = 0, 1, 2
 _ALGO = {"auto": ALGO_AUTO, "split": ALGO_SPLIT, "chain": ALGO_CHAIN}
 
-EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_static", "specgbv_verify_ex", "specgbv_read_intermediates",
+EXPORTS = ("specgbv_workspace_bytes", "specgbv_verify", "specgbv_verify_static", "specgbv_verify_ex", "specgbv_verify_kseq", "specgbv_read_kseq_intermediates", "specgbv_read_intermediates",
            "specgbv_workspace_carry", "specgbv_modify_target", "specgbv_modify_workspace_bytes", "specgbv_sample_tokens", "specgbv_sample_workspace_bytes",
            "specgbv_read_sample_intermediates", "specgbv_carry_advance", "specgbv_carry_workspace_bytes", "specgbv_pending_state_bytes", "specgbv_last_error", "specgbv_version")
 
@@ -35,6 +35,13 @@ class _Options(ctypes.Structure):
     _fields_ = [("algo", c_int32), ("pending_levels", c_int32), ("ev_main_start", c_void_p), ("ev_main_stop", c_void_p),
                 ("pending_carry_log_nu", c_void_p), ("pending_count", c_void_p), ("pending_state", c_void_p),
                 ("shared_row0", c_int32), ("reserved", c_int32)]
+
+
+class _KseqIntermediates(ctypes.Structure):
+    _fields_ = [("rho_all", POINTER(c_double)), ("beta_all", POINTER(c_double)), ("accept", POINTER(c_double)),
+                ("eta", POINTER(c_double)), ("state", POINTER(c_int32)), ("retained", POINTER(c_int32)),
+                ("lead", POINTER(c_int32)), ("res_norm", POINTER(c_double)), ("u_final", POINTER(c_double)),
+                ("margin", POINTER(c_double))]
 
 
 class _Intermediates(ctypes.Structure):
@@ -65,6 +72,11 @@ def load_library() -> ctypes.CDLL:
     L.specgbv_verify.restype = c_int
     L.specgbv_verify_static.argtypes = verify_args[:14] + [c_void_p]
     L.specgbv_verify_static.restype = c_int
+    L.specgbv_verify_kseq.argtypes = verify_args[:11] + [c_int] + verify_args[11:]
+    L.specgbv_verify_kseq.restype = c_int
+    L.specgbv_read_kseq_intermediates.argtypes = [c_void_p, c_size_t, c_int, c_int, c_int, c_int,
+                                                  POINTER(_KseqIntermediates), c_void_p]
+    L.specgbv_read_kseq_intermediates.restype = c_int
     L.specgbv_verify_ex.argtypes = verify_args + [POINTER(_Options)]
     L.specgbv_verify_ex.restype = c_int
     L.specgbv_pending_state_bytes.argtypes = [c_int]
@@ -244,6 +256,53 @@ def specgbv_verify(target_logits, draft_logits, draft_tokens, temperature: float
                             stream)
     _check(st)
     return out[0], out[1], out[2], workspace
+
+
+def specgbv_verify_kseq(target_logits, draft_logits, draft_tokens, temperature: float, rng_seed: int, rng_offset: int,
+                        ndrafts: Optional[int] = None, *, workspace=None, out: Optional[Tuple] = None,
+                        stream: Optional[int] = None):
+    """specgbv_verify_kseq of the C ABI: the comparison verifier (SpecTr's K-SEQ rule; ndrafts = 1 is token-level
+    speculative decoding) on the inputs of specgbv_verify.  Returns (accepted_len, accepted_draft_idx, out_tokens,
+    workspace)."""
+    import torch
+    lib = load_library()
+    B, K, L, V = _shapes(target_logits, draft_logits, draft_tokens)
+    dt = _dtype_code(target_logits)
+    dev = target_logits.device
+    if workspace is None:
+        workspace = torch.empty(max(specgbv_workspace_bytes(B, K, L, V, dt), 256), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty(B, dtype=torch.int32, device=dev), torch.empty(B, dtype=torch.int32, device=dev),
+               torch.empty((B, L + 1), dtype=torch.int32, device=dev))
+    if stream is None:
+        stream = torch.cuda.current_stream(dev).cuda_stream
+    st = lib.specgbv_verify_kseq(target_logits.data_ptr(), draft_logits.data_ptr(), draft_tokens.data_ptr(), K, L, V, B, dt,
+                                 c_float(temperature), rng_seed, rng_offset, K if ndrafts is None else int(ndrafts),
+                                 out[0].data_ptr(), out[1].data_ptr(), out[2].data_ptr(), workspace.data_ptr(),
+                                 workspace.numel() * workspace.element_size(), stream)
+    _check(st)
+    return out[0], out[1], out[2], workspace
+
+
+def specgbv_read_kseq_intermediates(workspace, batch: int, K: int, L: int, V: int,
+                                    stream: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """Copy the intermediates of the last specgbv_verify_kseq call out of `workspace` (synchronises the stream)."""
+    import torch
+    lib = load_library()
+    if stream is None:
+        stream = torch.cuda.current_stream(workspace.device).cuda_stream
+    res = {"rho_all": np.full((batch, K, L), np.nan), "beta_all": np.full((batch, K, L), np.nan),
+           "accept": np.full((batch, K, L), np.nan), "eta": np.full((batch, K, L), np.nan),
+           "state": np.zeros((batch, K, L), np.int32), "retained": np.zeros((batch, L), np.int32),
+           "lead": np.zeros((batch, L), np.int32), "res_norm": np.full(batch, np.nan), "u_final": np.full(batch, np.nan),
+           "margin": np.full(batch, np.nan)}
+    dp = lambda a: a.ctypes.data_as(POINTER(c_double))
+    ip = lambda a: a.ctypes.data_as(POINTER(c_int32))
+    out = _KseqIntermediates(dp(res["rho_all"]), dp(res["beta_all"]), dp(res["accept"]), dp(res["eta"]), ip(res["state"]),
+                             ip(res["retained"]), ip(res["lead"]), dp(res["res_norm"]), dp(res["u_final"]), dp(res["margin"]))
+    _check(lib.specgbv_read_kseq_intermediates(workspace.data_ptr(), workspace.numel() * workspace.element_size(), batch,
+                                               K, L, V, ctypes.byref(out), stream))
+    return res
 
 
 STATIC_SCRATCH_BYTES = 8 << 20      # SPECGBV_STATIC_SCRATCH_BYTES of the C header

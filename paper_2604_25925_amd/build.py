@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecgbv.so")
-SOURCES = ["specgbv_api.hip", "specgbv_split.hip", "specgbv_chain.hip", "specgbv_decide.hip", "specgbv_modify.hip", "specgbv_sample.hip"]
+SOURCES = ["specgbv_api.hip", "specgbv_split.hip", "specgbv_chain.hip", "specgbv_decide.hip", "specgbv_modify.hip", "specgbv_sample.hip", "specgbv_kseq.hip"]
 HEADERS = ["specgbv_device.hpp", "specgbv_internal.hpp", os.path.join("..", "..", "include", "specgbv.h")]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          # packed-FP32 instructions are not to be generated on the test machines

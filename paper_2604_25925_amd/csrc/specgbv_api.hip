@@ -60,6 +60,7 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.pend_cnt = take(n * sizeof(int32_t));
     w.stat_part = take(n * 2 * kRowParts * sizeof(Row0Part));
     w.row0 = take(static_cast<size_t>(batch) * 2 * kRow0Parts * sizeof(Row0Part));
+    w.kseq_pos = take(static_cast<size_t>(batch) * L * 2 * sizeof(int32_t));
     w.total = off;
     return w;
 }
@@ -201,6 +202,84 @@ specgbv_status specgbv_verify_ex(
     }
     e = launch_decide_and_sample(p);
     if (e != hipSuccess) return fail(SPECGBV_EHIP, "decision/sampling kernel launch: %s", hipGetErrorString(e));
+    return SPECGBV_OK;
+}
+
+specgbv_status specgbv_verify_kseq(
+    const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+    int K, int L, int V, int batch, specgbv_dtype dtype, float temperature,
+    uint64_t rng_seed, uint64_t rng_offset, int ndrafts,
+    int32_t *accepted_len, int32_t *accepted_draft_idx, int32_t *out_tokens,
+    void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!shape_ok(batch, K, L, V))
+        return fail(SPECGBV_EINVAL, "sizes must satisfy batch >= 0, K, L, V >= 1 (got batch=%d K=%d L=%d V=%d)",
+                    batch, K, L, V);
+    if (ndrafts < 1 || ndrafts > K) return fail(SPECGBV_EINVAL, "ndrafts must lie in [1, K] (got %d, K=%d)", ndrafts, K);
+    if (dtype != SPECGBV_F32 && dtype != SPECGBV_BF16) return fail(SPECGBV_EINVAL, "unknown dtype %d", (int)dtype);
+    if (!(temperature > 0.0f) || !std::isfinite(temperature))
+        return fail(SPECGBV_EINVAL, "temperature must be finite and > 0 (got %g)", (double)temperature);
+    specgbv_status st = check_limits(batch, K, L, V);
+    if (st != SPECGBV_OK) return st;
+    if (batch == 0) return SPECGBV_OK;
+    if (!target_logits || !draft_logits || !draft_tokens || !accepted_len || !accepted_draft_idx || !out_tokens)
+        return fail(SPECGBV_EINVAL, "null input or output pointer");
+    const size_t esz = dtype == SPECGBV_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(target_logits) % esz || reinterpret_cast<uintptr_t>(draft_logits) % esz ||
+        reinterpret_cast<uintptr_t>(draft_tokens) % 4 || reinterpret_cast<uintptr_t>(accepted_len) % 4 ||
+        reinterpret_cast<uintptr_t>(accepted_draft_idx) % 4 || reinterpret_cast<uintptr_t>(out_tokens) % 4)
+        return fail(SPECGBV_EINVAL, "pointer not aligned to its element size");
+    Problem p{};
+    p.lay = make_workspace(batch, K, L, V);
+    if (!workspace) return fail(SPECGBV_EWORKSPACE, "workspace is null (need %zu bytes)", p.lay.total);
+    if (reinterpret_cast<uintptr_t>(workspace) % 256) return fail(SPECGBV_EWORKSPACE, "workspace must be 256-byte aligned");
+    if (workspace_bytes < p.lay.total)
+        return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, p.lay.total);
+    p.target = target_logits; p.draft = draft_logits; p.tokens = draft_tokens;
+    p.K = K; p.L = L; p.V = V; p.batch = batch; p.dtype = dtype == SPECGBV_BF16 ? 1 : 0;
+    const double c_exact = 1.4426950408889634074 / static_cast<double>(temperature);
+    p.c = static_cast<float>(c_exact);
+    p.c_rel = c_exact / static_cast<double>(p.c) - 1.0;
+    p.seed = rng_seed; p.offset = rng_offset;
+    p.accepted_len = accepted_len; p.accepted_draft_idx = accepted_draft_idx; p.out_tokens = out_tokens;
+    p.ws = static_cast<char *>(workspace);
+    p.stream = static_cast<hipStream_t>(hip_stream);
+    p.s_parts = 1;
+    p.kseq_ndrafts = ndrafts;
+    hipError_t e = launch_kseq_rows(p, ndrafts);
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "root-finding kernel launch: %s", hipGetErrorString(e));
+    e = launch_decide_and_sample(p);
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "decision/sampling kernel launch: %s", hipGetErrorString(e));
+    return SPECGBV_OK;
+}
+
+specgbv_status specgbv_read_kseq_intermediates(
+    const void *workspace, size_t workspace_bytes, int batch, int K, int L, int V,
+    const specgbv_kseq_intermediates *out, void *hip_stream)
+{
+    if (!shape_ok(batch, K, L, V) || batch < 1) return fail(SPECGBV_EINVAL, "bad shape");
+    if (!workspace || !out) return fail(SPECGBV_EINVAL, "null pointer");
+    const Workspace lay = make_workspace(batch, K, L, V);
+    if (workspace_bytes < lay.total) return fail(SPECGBV_EWORKSPACE, "workspace has %zu bytes, need %zu", workspace_bytes, lay.total);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const char *ws = static_cast<const char *>(workspace);
+    const size_t n = static_cast<size_t>(batch) * K * L, m = static_cast<size_t>(batch) * L;
+    hipError_t e = hipSuccess;
+    auto copy = [&](void *dst, size_t off, size_t bytes) {
+        if (dst && e == hipSuccess) e = hipMemcpyAsync(dst, ws + off, bytes, hipMemcpyDeviceToHost, stream);
+    };
+    copy(out->rho_all, lay.s, n * sizeof(double));
+    copy(out->beta_all, lay.excess, n * sizeof(double));
+    copy(out->accept, lay.h, n * sizeof(double));
+    copy(out->eta, lay.eta, n * sizeof(double));
+    copy(out->state, lay.state, n * sizeof(int32_t));
+    copy(out->retained, lay.kseq_pos, m * sizeof(int32_t));
+    copy(out->lead, lay.kseq_pos + m * sizeof(int32_t), m * sizeof(int32_t));
+    copy(out->res_norm, lay.res_norm, batch * sizeof(double));
+    copy(out->u_final, lay.u_final, batch * sizeof(double));
+    copy(out->margin, lay.margin, batch * sizeof(double));
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail(SPECGBV_EHIP, "reading intermediates: %s", hipGetErrorString(e));
     return SPECGBV_OK;
 }
 

@@ -242,24 +242,32 @@ __device__ __noinline__ ExactStats exact_row_stats(const T *row, int nvec, float
 }
 
 // E = nu^2 (s - g) of one row pair straight from memory (rows whose s and g nearly cancel; see ExcessConst).
-// The constants travel through LDS, the result is returned by value, for the reasons given at exact_row_stats.
+// Runs after the row loop, when the registers no longer hold a row pair: several vector pairs in flight per thread.
 template <typename T>
-__device__ __noinline__ double excess_row(const T *qrow, const T *prow, int nvec, const ExcessConst *ec_lds, double *sh_d)
+__device__ __forceinline__ double excess_row(const T *qrow, const T *prow, int nvec, const ExcessConst &ec, double *sh_d)
 {
     constexpr int PV = Elem<T>::kPerVec;
-    const ExcessConst ec = *ec_lds;
+    constexpr int kAhead = 4;
     float acc = 0.0f;
-    for (int v = threadIdx.x; v < nvec; v += kChainThreads) {
-        float zq[PV], zp[PV];
-        Elem<T>::unpack(load16(qrow + static_cast<long long>(v) * PV), zq);
-        Elem<T>::unpack(load16(prow + static_cast<long long>(v) * PV), zp);
-        // two entries at a time, one pair strictly after the other: this function runs while the caller's
-        // registers hold a whole row pair, and must make do with the few that are left
+    U4 q[kAhead], p[kAhead];
+    const int last = nvec - 1;
 #pragma unroll
-        for (int j = 0; j < PV; j += 2) {
-            const float q2[2] = {zq[j], zq[j + 1]}, p2[2] = {zp[j], zp[j + 1]};
-            acc += excess_terms(q2, p2, ec);
-            asm volatile("" : "+v"(acc));
+    for (int j = 0; j < kAhead; ++j) {
+        const int v = static_cast<int>(threadIdx.x) + j * kChainThreads;
+        q[j] = load16(qrow + static_cast<long long>(v < nvec ? v : last) * PV);
+        p[j] = load16(prow + static_cast<long long>(v < nvec ? v : last) * PV);
+    }
+    for (int v0 = threadIdx.x; v0 < nvec; v0 += kAhead * kChainThreads) {
+#pragma unroll
+        for (int j = 0; j < kAhead; ++j) {
+            const int v = v0 + j * kChainThreads;
+            float zq[PV], zp[PV];
+            Elem<T>::unpack(q[j], zq);
+            Elem<T>::unpack(p[j], zp);
+            const int nx = v + kAhead * kChainThreads;                 // the pair this slot holds next
+            q[j] = load16(qrow + static_cast<long long>(nx < nvec ? nx : last) * PV);
+            p[j] = load16(prow + static_cast<long long>(nx < nvec ? nx : last) * PV);
+            if (v < nvec) acc += excess_terms(zq, zp, ec);
         }
     }
     double a = static_cast<double>(acc), b = 0.0;
@@ -267,11 +275,9 @@ __device__ __noinline__ double excess_row(const T *qrow, const T *prow, int nvec
     return a * ec.scale;
 }
 
-// Thread 0 only, in a function of its own (float64 constants stay out of the kernel's loop): the constants of that sum.
-__device__ __noinline__ void excess_prepare(const double *row, int K, float c, ExcessConst *out)
-{
-    *out = make_excess_const(row[1], row[2], row[0], K, c);
-}
+// Rows of this workgroup whose Eq. (hik) sum is taken again after the row loop (LDS; thread 0 appends).
+constexpr int kMaxLater = 96;
+struct LaterRow { long long bk; int r; int pad; double log2nu, lse2_q, lse2_p; };
 
 constexpr int kLag = 6;    // slots between the load of a vector and its first use
 constexpr double kTokenRefLimit = 1073741824.0;   // 2^30: largest row sum accepted relative to the drafted token's weight
@@ -573,7 +579,8 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
-    __shared__ ExcessConst sh_ec;                          // constants of a row whose Eq. (hik) sum is taken again without cancellation
+    __shared__ LaterRow sh_later[kMaxLater];               // rows whose Eq. (hik) sum is taken again without cancellation, after the loop
+    __shared__ int sh_nlater;
     __shared__ double sh_sumrow[2][3];                     // block ratio and log-normalisers of the row in sweep 2 (log2): written by
                                                            // thread 0 when the row's statistics are known, in the buffer of the
                                                            // iteration's parity, and read one iteration later
@@ -587,6 +594,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         if (threadIdx.x == 0) { sh_pend = pend; sh_sum_done = 0; }
         __syncthreads();
     }
+    if (threadIdx.x == 0) sh_nlater = 0;                   // (read again only after the barriers of the first row end)
 
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
@@ -681,23 +689,23 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp), s_tot = static_cast<double>(acc);
         block_sum3(Zq_tot, Zp_tot, s_tot, sh_d);
         Zq_tot = uniform_d(Zq_tot); Zp_tot = uniform_d(Zp_tot); s_tot = uniform_d(s_tot);
-        if (do_sum) {
+        if (do_sum && tid == 0) {
+            const double s_val = s_tot / Zq_prev;
+            s_out[bk_old * L + r_old] = s_val;
+            e_out[bk_old * L + r_old] = -1.0;
             // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term (rare:
-            // peaked rows, large block ratios); the row has left the chip by now and is read again.  The test runs
-            // in float32 on every thread (the branch is uniform); only thread 0 forms the float64 quotient it stores.
-            double e_val = -1.0;
+            // peaked rows, large block ratios).  The row has left the chip by now; it is noted down and read again
+            // after the row loop, when the registers are free for a proper streaming loop.  (A list that is full
+            // leaves the plain sum in force.)
             if constexpr (!PEND) {
                 const double *row = sh_sumrow[(g - 1) & 1];
-                const float s_f = static_cast<float>(s_tot) * __builtin_amdgcn_rcpf(static_cast<float>(Zq_prev));
-                const float l_f = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(static_cast<float>(row[0]))));
-                if (excess_wanted(l_f, s_f, K)) {                   // uniform
-                    __syncthreads();
-                    if (tid == 0) excess_prepare(row, K, c, &sh_ec);
-                    __syncthreads();
-                    e_val = excess_row<T>(qold, pold, nvec, &sh_ec, sh_d);
+                if (excess_wanted(static_cast<float>(row[0]), static_cast<float>(s_val), K) && sh_nlater < kMaxLater) {
+                    LaterRow lr;
+                    lr.bk = bk_old; lr.r = r_old; lr.pad = 0; lr.log2nu = row[0]; lr.lse2_q = row[1]; lr.lse2_p = row[2];
+                    sh_later[sh_nlater] = lr;
+                    sh_nlater = sh_nlater + 1;
                 }
             }
-            if (tid == 0) { s_out[bk_old * L + r_old] = s_tot / Zq_prev; e_out[bk_old * L + r_old] = e_val; }
         }
         if (do_new) {
             if (r_new == first_row) {                      // a new chain starts from the empty block ...
@@ -786,6 +794,17 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             Zq_prev = uniform_d(Zq_tot);
             if (tid == 0) { sh_sumrow[g & 1][0] = log2nu; sh_sumrow[g & 1][1] = lse2_q; sh_sumrow[g & 1][2] = lse2_p; }
             log2nu = uniform_d(log2nu + ((tok2_q - lse2_q + tok_adj) - (tok2_p - lse2_p)));
+        }
+    }
+    if constexpr (!PEND) {
+        __syncthreads();
+        const int nlater = sh_nlater;
+        for (int j = 0; j < nlater; ++j) {                 // uniform
+            const LaterRow lr = sh_later[j];
+            const ExcessConst ec = make_excess_const(lr.lse2_q, lr.lse2_p, lr.log2nu, K, c);
+            const double E = excess_row<T>(target + (lr.bk * (L + 1) + lr.r) * static_cast<long long>(V),
+                                           draft + (lr.bk * L + lr.r) * static_cast<long long>(V), nvec, ec, sh_d);
+            if (tid == 0) e_out[lr.bk * L + lr.r] = E;
         }
     }
 }

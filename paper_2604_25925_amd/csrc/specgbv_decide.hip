@@ -103,6 +103,9 @@ struct DecideIO {
     int32_t *state_out;
     int32_t *accepted_len, *accepted_draft_idx, *out_tokens;
     double c_rel;               // relative rounding error of the float scale c (token_scaled)
+    int kseq_ndrafts;           // > 0: comparison verifier (K-SEQ rule) on the first kseq_ndrafts drafts; s_arr then holds
+                                // rho and e_arr beta(rho) of every row pair
+    int32_t *kseq_pos;          // [2][batch * L] drafts retained at each position reached, and the lowest of them
 };
 
 // Decision of prefix b by the whole workgroup (kDecideThreads threads); the result is left in
@@ -310,6 +313,111 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         for (int j = lane; j <= L; j += kWave)
             if (j != tau) io.out_tokens[static_cast<long long>(b) * (L + 1) + j] = j < tau ? tok[kf * L + j] : -1;
     }
+    __syncthreads();
+}
+
+// ------------------------------------------------- comparison verifier: the K-SEQ scan (Section 3.2)
+
+// Decision of prefix b under the K-SEQ rule, by the whole workgroup; leaves the row the final token is drawn from
+// in *sel_out (its weights max{q - rho p, 0} are the K = 1 residual weights at block ratio 1/rho) and the final
+// uniform in *u_final_out.  For every (draft j, position i) the acceptance probability min{1, q(x)/(rho p(x))} of
+// draft j's token is formed from the rows of the LEAD draft of j's first i tokens (the lowest draft that shares
+// them: the drafts retained when the position is reached are exactly those sharing the accepted block), then one
+// thread walks the positions on bit masks: the lowest retained draft whose test succeeds wins the position, and the
+// drafts carrying its token stay retained.
+template <typename T>
+__device__ __forceinline__ void decide_kseq(const T *target, const T *draft, const DecideIO &io, int b, int K, int L, int V,
+                                            float c, uint64_t seed, uint64_t offset, bool write, double *lds,
+                                            Selection *sel_out, double *u_final_out, PendTable *tab_out)
+{
+    const int KL = K * L, nd = io.kseq_ndrafts;
+    double *acc = lds;                                                          // [K*L] acceptance probabilities
+    unsigned long long *eq = reinterpret_cast<unsigned long long *>(lds + KL);  // [K*L] drafts with draft j's token at position i
+    unsigned long long *won = reinterpret_cast<unsigned long long *>(lds + 2 * KL);   // [L] drafts whose test at position i succeeds
+    unsigned long long *tested = won + L;                                       // [L] drafts tested at position i
+    int *lead_of = reinterpret_cast<int *>(tested + L);                         // [K*L] (in all 3 K L + 2 L doubles of the 6 K L + K)
+    int *tok = lead_of + KL;                                                    // [K*L]
+    const int tid = threadIdx.x;
+    const long long base = static_cast<long long>(b) * KL;
+    for (int idx = tid; idx < KL; idx += kDecideThreads) tok[idx] = io.tokens[base + idx];
+    for (int idx = tid; idx < L; idx += kDecideThreads) { won[idx] = 0ull; tested[idx] = 0ull; }
+    __syncthreads();
+    for (int idx = tid; idx <= KL; idx += kDecideThreads) {
+        if (idx == KL) { *u_final_out = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(KL)); continue; }
+        const int j = idx / L, i = idx % L;
+        double a = 0.0, e = 0.0;
+        unsigned long long same_tok = 0ull;
+        int lead = j;
+        if (j < nd) {
+            for (int m = j - 1; m >= 0; --m) {                                  // lowest draft sharing the first i tokens
+                bool same = true;
+                for (int q = 0; q < i; ++q) same = same && tok[m * L + q] == tok[j * L + q];
+                if (same) lead = m;
+            }
+            for (int m = 0; m < nd; ++m) same_tok |= static_cast<unsigned long long>(tok[m * L + i] == tok[j * L + i]) << m;
+            int x = tok[idx];
+            x = x < 0 ? 0 : (x >= V ? V - 1 : x);
+            const long long lrow = (static_cast<long long>(b) * K + lead) * L + i;
+            const RowStat st = io.stats[lrow];
+            const double zq = static_cast<double>(Elem<T>::scalar(target + ((static_cast<long long>(b) * K + lead) * (L + 1) + i) * V + x));
+            const double zp = static_cast<double>(Elem<T>::scalar(draft + lrow * V + x));
+            const double l2 = ((static_cast<double>(c) * zq - st.lse2_q) - (static_cast<double>(c) * zp - st.lse2_p)) * (1.0 + io.c_rel);
+            const double ratio = exp2_small(l2) / io.s_arr[lrow];               // q(x) / (rho p(x))
+            a = ratio < 1.0 ? ratio : 1.0;
+            e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
+            if (e < a) atomicOr(&won[i], 1ull << j);
+        }
+        acc[idx] = a; eq[idx] = same_tok; lead_of[idx] = lead;
+        if (write) { io.h_out[base + idx] = a; io.eta_out[base + idx] = e; }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long alive = nd >= 64 ? ~0ull : ((1ull << nd) - 1ull);
+        int tau = 0;
+        for (int i = 0; i < L; ++i) {
+            const int lead = __ffsll(static_cast<long long>(alive)) - 1;
+            if (write) {
+                io.kseq_pos[static_cast<long long>(b) * L + i] = __popcll(alive);
+                io.kseq_pos[static_cast<long long>(gridDim.y) * L + static_cast<long long>(b) * L + i] = lead;
+            }
+            const unsigned long long cand = alive & won[i];
+            if (!cand) { tested[i] = alive; break; }
+            const int w = __ffsll(static_cast<long long>(cand)) - 1;
+            tested[i] = alive & ((2ull << w) - 1ull);
+            alive &= eq[w * L + i];
+            tau = i + 1;
+        }
+        if (write)
+            for (int i = tau + 1; i < L; ++i) {                                  // positions never reached
+                io.kseq_pos[static_cast<long long>(b) * L + i] = 0;
+                io.kseq_pos[static_cast<long long>(gridDim.y) * L + static_cast<long long>(b) * L + i] = -1;
+            }
+        const int lead = __ffsll(static_cast<long long>(alive)) - 1;
+        Selection &sl = *sel_out;
+        sl.tau = tau; sl.npend = 0; sl.pad = 0; tab_out->n = 0;
+        sl.target_row = (static_cast<long long>(b) * K + lead) * (L + 1) + tau;
+        if (tau == L) {
+            sl.draft_row = -1; sl.C2 = 0.0; sl.shift_q = 0.0f; sl.lse2_q = 0.0; sl.lse2_pq = 0.0;
+        } else {
+            const long long lrow = (static_cast<long long>(b) * K + lead) * L + tau;
+            const RowStat st = io.stats[lrow];
+            sl.draft_row = lrow;
+            sl.C2 = st.lse2_p - st.lse2_q - log2(io.s_arr[lrow]);                // rho p / q = 2^(c (z_p - z_q) - C2)
+            sl.shift_q = rintf(static_cast<float>(st.lse2_q));
+            sl.lse2_q = st.lse2_q;
+            sl.lse2_pq = st.lse2_p - st.lse2_q;
+        }
+        if (write) {
+            io.accepted_len[b] = tau;
+            io.accepted_draft_idx[b] = tau > 0 ? lead : -1;
+            for (int j = 0; j <= L; ++j)
+                if (j != tau) io.out_tokens[static_cast<long long>(b) * (L + 1) + j] = j < tau ? tok[lead * L + j] : -1;
+        }
+    }
+    __syncthreads();
+    if (write)
+        for (int idx = tid; idx < KL; idx += kDecideThreads)
+            io.state_out[base + idx] = static_cast<int32_t>((tested[idx % L] >> (idx / L)) & 1ull);
     __syncthreads();
 }
 
@@ -549,7 +657,12 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     double *__restrict__ carry_out = fo.carry;
 
     // ---- 1. decision (redundantly per workgroup; the first one of the prefix writes it out)
-    decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
+    if (io.kseq_ndrafts > 0) {             // comparison verifier: K-SEQ scan; its replacement weights are the K = 1 ones
+        decide_kseq<T>(target, draft, io, b, K, L, V, c, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
+        K = 1;
+    } else {
+        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
+    }
     const Selection sl = sh_sel;
     if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
 
@@ -793,6 +906,8 @@ hipError_t launch_final_typed(const Problem &p)
     io.state_out = reinterpret_cast<int32_t *>(p.ws + p.lay.state);
     io.accepted_len = p.accepted_len; io.accepted_draft_idx = p.accepted_draft_idx; io.out_tokens = p.out_tokens;
     io.c_rel = p.c_rel;
+    io.kseq_ndrafts = p.kseq_ndrafts;
+    io.kseq_pos = reinterpret_cast<int32_t *>(p.ws + p.lay.kseq_pos);
     FinalOut fo;
     fo.sel = reinterpret_cast<Selection *>(p.ws + p.lay.sel);
     fo.partial = reinterpret_cast<SegPartial *>(p.ws + p.lay.partial);

@@ -36,6 +36,7 @@ struct Workspace {
     size_t pend_cnt;   // int32  [B*K*L]  workgroups of a shared row that have stored their partial normaliser
     size_t stat_part;  // Row0Part [B*K*L][2][kRowParts]  partial row statistics (two-pass schedule, small batches)
     size_t row0;       // Row0Part [B][2][kRow0Parts]  partial statistics of the rows 0 a prefix's drafts share (chain schedule)
+    size_t kseq_pos;   // int32 [2][B*L]  comparison verifier: drafts retained at each position, and the lowest of them
     size_t total;
     int nseg;
 };
@@ -74,7 +75,12 @@ struct Problem {
     int32_t *state_count;          // [kMaxPend][batch]
     bool shared_row0;              // rows 0 of a prefix's drafts are copies of one another (caller's statement)
     int s_parts;                   // > 1: the sums of Eq. (hik) are left as this many partial sums per row (small batches)
+    int kseq_ndrafts;              // > 0: the comparison verifier (K-SEQ rule of Section 3.2) on the first kseq_ndrafts drafts
 };
+
+// Comparison verifier (Sections 3.1 / 3.2): per row pair the statistics and the root rho (left in lay.s, beta(rho) in
+// lay.excess); the scan over positions and the replacement token are a mode of launch_decide_and_sample.
+hipError_t launch_kseq_rows(const Problem &p, int ndrafts);
 
 // Schedule "split": statistics kernel, then a second pass for the sums of Eq. (hik).
 hipError_t launch_split_main(const Problem &p);
