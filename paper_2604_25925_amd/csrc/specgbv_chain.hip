@@ -300,34 +300,45 @@ struct StepCtx {
     bool do_new, do_sum;
 };
 
-// Step J of the slot pipeline (all indices are compile-time constants so that the slot
-// arrays stay in registers): sweep 2 of the old row on slot J, the load of the new row into
-// slot J, and sweep 1 of the new row on slot J - kLag.  Register slots are waited for by the
-// compiler; LDS slots were filled by asynchronous global->LDS loads, so a manual wait
-// precedes their first read: inside the pipeline exactly 2 * kLag vector-memory operations
-// were issued after the fill of slot J - kLag, and none may be pending once it drains.
-template <typename T, int KP, int RS, int J>
+// Order in which the on-chip slots of a row are visited: the LDS slots first, from the highest down (slots a short
+// row leaves unused thus come first and the used ones sit right in front of the register slots), then the register
+// slots.  The compiler counts the loads it issued itself when it places the wait for a register slot; it cannot see
+// the asynchronous global->LDS fills, which are inline assembly.  With the fills at the start of the row no fill
+// follows a register load inside an iteration, so the compiler's count for every register slot is exact, and it
+// never waits for more than the slot it is about to read.
+template <int RS>
+constexpr int slot_at(int i) { return i < kLdsSlots ? RS + kLdsSlots - 1 - i : i - kLdsSlots; }
+
+// Step I of the slot pipeline (all indices are compile-time constants so that the slot arrays stay in registers):
+// sweep 2 of the old row on slot J = slot_at(I), the load of the new row into slot J, and sweep 1 of the new row
+// on the slot of step I - kLag.  Register slots are waited for by the compiler.  LDS slots were filled by
+// asynchronous global->LDS loads, so a manual wait precedes their first read: every one of the kLag steps after the
+// fill of a used LDS slot issues two vector-memory operations (the used LDS slots are contiguous and the register
+// slots follow them), none of which may be pending once the fill has landed.
+template <typename T, int KP, int RS, int I>
 __device__ __forceinline__ void pipeline_step(const StepCtx<T> &cx, U4 (&rq)[RS], U4 (&rp)[RS],
                                               const LdsSlots &lds, float &Zq, float &Zp, float &acc)
 {
     constexpr int NS = RS + kLdsSlots;
+    static_assert(RS >= kLag, "the steps after the last LDS fill must all be register loads");
     constexpr size_t kSlotBytes = static_cast<size_t>(kChainThreads) * 16;
     // Opaque copies: everything derived from them is recomputed per step instead of being
     // hoisted out of the row loop and kept (or spilled) across it.
     unsigned t = cx.tid, off = cx.off_new;
     asm volatile("" : "+v"(t), "+v"(off));
-    if constexpr (J < RS) {
-        // Opaque touch of the slot: without it the compiler keeps the floats that sweep 1
-        // unpacked from these registers alive until sweep 2, which doubles the footprint of
-        // bf16 rows.
-        asm volatile("" : "+v"(rq[J].x), "+v"(rq[J].y), "+v"(rq[J].z), "+v"(rq[J].w));
-        asm volatile("" : "+v"(rp[J].x), "+v"(rp[J].y), "+v"(rp[J].z), "+v"(rp[J].w));
-        if (cx.do_sum) sweep2_vec<T, KP>(rq[J], rp[J], cx.rc_sum, acc);
-        asm volatile("" : "+v"(off) : "v"(acc));            // keep the loads behind this slot's arithmetic
-        rq[J] = load_vec(reinterpret_cast<const char *>(cx.qnew) + J * kSlotBytes, off);
-        rp[J] = load_vec(reinterpret_cast<const char *>(cx.pnew) + J * kSlotBytes, off);
-    } else if constexpr (J < NS) {
-        if (J < cx.n_on) {
+    if constexpr (I < NS) {
+        constexpr int J = slot_at<RS>(I);
+        if constexpr (J < RS) {
+            // Opaque touch of the slot: without it the compiler keeps the floats that sweep 1
+            // unpacked from these registers alive until sweep 2, which doubles the footprint of
+            // bf16 rows.
+            asm volatile("" : "+v"(rq[J].x), "+v"(rq[J].y), "+v"(rq[J].z), "+v"(rq[J].w));
+            asm volatile("" : "+v"(rp[J].x), "+v"(rp[J].y), "+v"(rp[J].z), "+v"(rp[J].w));
+            if (cx.do_sum) sweep2_vec<T, KP>(rq[J], rp[J], cx.rc_sum, acc);
+            asm volatile("" : "+v"(off) : "v"(acc));        // keep the loads behind this slot's arithmetic
+            rq[J] = load_vec(reinterpret_cast<const char *>(cx.qnew) + J * kSlotBytes, off);
+            rp[J] = load_vec(reinterpret_cast<const char *>(cx.pnew) + J * kSlotBytes, off);
+        } else if (J < cx.n_on) {
             if (cx.do_sum && J * kChainThreads < cx.rem)
                 sweep2_vec<T, KP>(lds_vec(lds, J - RS, 0, t), lds_vec(lds, J - RS, 1, t), cx.rc_sum, acc);
             if (cx.do_new) {
@@ -343,15 +354,19 @@ __device__ __forceinline__ void pipeline_step(const StepCtx<T> &cx, U4 (&rq)[RS]
             }
         }
     }
-    constexpr int JJ = J - kLag;                            // lagged sweep 1 of the new row
-    if constexpr (JJ >= 0 && JJ < RS) {
-        if (cx.do_new) sweep1_vec<T>(rq[JJ], rp[JJ], cx.rc_new, Zq, Zp);
-    } else if constexpr (JJ >= RS && JJ < NS) {
-        if (cx.do_new && JJ < cx.n_on) {
-            if (J < cx.n_on) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLag) : "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (JJ * kChainThreads < cx.rem)
-                sweep1_vec<T>(lds_vec(lds, JJ - RS, 0, t), lds_vec(lds, JJ - RS, 1, t), cx.rc_new, Zq, Zp);
+    constexpr int II = I - kLag;                            // lagged sweep 1 of the new row
+    if constexpr (II >= 0 && II < NS) {
+        constexpr int JJ = slot_at<RS>(II);
+        if constexpr (JJ < RS) {
+            if (cx.do_new) sweep1_vec<T>(rq[JJ], rp[JJ], cx.rc_new, Zq, Zp);
+        } else {
+            // (the loads of this step are issued before the wait that counts them)
+            __builtin_amdgcn_sched_barrier(0);
+            if (cx.do_new && JJ < cx.n_on) {
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLag) : "memory");
+                if (JJ * kChainThreads < cx.rem)
+                    sweep1_vec<T>(lds_vec(lds, JJ - RS, 0, t), lds_vec(lds, JJ - RS, 1, t), cx.rc_new, Zq, Zp);
+            }
         }
     }
 }
@@ -629,6 +644,20 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     // is the first row of its chain), the load of row g into the slot that sweep 2 just released, and
     // sweep 1 of row g on the slot loaded kLag steps earlier.  Loads are therefore issued evenly over
     // the whole row period and the memory pipeline never drains between rows.
+    // The drafted token's two logits (the reference exponents of a row's first sweep) are fetched one row ahead, as
+    // loaded: the wait for them then falls at the end of the previous iteration, where no other load is in flight,
+    // and not behind the first LDS fills of their own row, which it would drain.
+    auto token_logits = [&](int gg, uint32_t &zq, uint32_t &zp) {
+        const int gc = gg < nrows ? gg : nrows - 1;        // keeps every address in bounds
+        const long long bk = chain_of(gc);
+        const int r = first_row + gc % rpc;
+        int tok = tokens[bk * L + r];
+        tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+        zq = Elem<T>::bits(target + (bk * (L + 1) + r) * static_cast<long long>(V) + tok);
+        zp = Elem<T>::bits(draft + (bk * L + r) * static_cast<long long>(V) + tok);
+    };
+    uint32_t zq_tok_next = 0, zp_tok_next = 0;
+    if (nrows > 0) token_logits(0, zq_tok_next, zp_tok_next);
     for (int g = 0; g <= nrows; ++g) {
         const bool do_new = g < nrows;                     // a row is being loaded and gets its statistics
         const int g_new = do_new ? g : nrows - 1;          // keeps every address in bounds
@@ -652,9 +681,8 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         // Reference exponents of the new row: its token's logits (the drafted token was
         // sampled from this draft row, so no entry can exceed it by a factor near 2^127
         // unless the row is extremely peaked; that case is caught below).
-        int tok = tokens[bk_new * L + r_new];
-        tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-        const float zq_tok = Elem<T>::scalar(qnew + tok), zp_tok = Elem<T>::scalar(pnew + tok);
+        const float zq_tok = Elem<T>::from_bits(zq_tok_next), zp_tok = Elem<T>::from_bits(zp_tok_next);
+        if (do_new) token_logits(g + 1, zq_tok_next, zp_tok_next);   // (the last row's logits again after the last row)
         RowConsts rc_new;
         rc_new.c = c; rc_new.K = K; rc_new.C2_hi = 0.0f; rc_new.neg_kappa = -1.0f;
         rc_new.nref_q = -(zq_tok * c); rc_new.nref_p = -(zp_tok * c);
@@ -686,6 +714,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             }
         }
 
+        asm volatile("" : "+v"(zq_tok_next), "+v"(zp_tok_next));   // the next row's token logits have arrived by here
         double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp), s_tot = static_cast<double>(acc);
         block_sum3(Zq_tot, Zp_tot, s_tot, sh_d);
         Zq_tot = uniform_d(Zq_tot); Zp_tot = uniform_d(Zp_tot); s_tot = uniform_d(s_tot);

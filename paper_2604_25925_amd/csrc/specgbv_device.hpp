@@ -93,6 +93,9 @@ template <> struct Elem<float> {
         o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
     }
     __device__ static __forceinline__ float scalar(const float *p) { return *p; }
+    // one element as loaded (no arithmetic on it, so that nothing has to wait for the load) and its value
+    __device__ static __forceinline__ uint32_t bits(const float *p) { return *reinterpret_cast<const uint32_t *>(p); }
+    __device__ static __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b); }
 };
 template <> struct Elem<uint16_t> {
     static constexpr int kPerVec = 8;
@@ -103,6 +106,8 @@ template <> struct Elem<uint16_t> {
     __device__ static __forceinline__ float scalar(const uint16_t *p) {
         return __uint_as_float(static_cast<uint32_t>(*p) << 16);
     }
+    __device__ static __forceinline__ uint32_t bits(const uint16_t *p) { return *p; }
+    __device__ static __forceinline__ float from_bits(uint32_t b) { return __uint_as_float(b << 16); }
 };
 
 __device__ __forceinline__ U4 load16(const void *p) {
