@@ -268,16 +268,23 @@ def bench_compare(a, w, sg, torch, tl, dl, tk):
         ws = torch.empty(sg.specgbv_workspace_bytes(w.batch, k, w.L, w.V, dt), dtype=torch.uint8, device=dev)
         out = (torch.empty(w.batch, dtype=torch.int32, device=dev), torch.empty(w.batch, dtype=torch.int32, device=dev),
                torch.empty((w.batch, w.L + 1), dtype=torch.int32, device=dev))
-        for i in range(max(a.warmup // 10, 3)):
-            fn(t_k, d_k, tok_k, i, ws, out)
-        torch.cuda.synchronize()
         acc = torch.zeros((), dtype=torch.float64, device=dev)
+        for i in range(max(a.warmup, 3)):                  # (the reductions below are warmed up too)
+            fn(t_k, d_k, tok_k, i, ws, out)
+            acc += out[0].double().mean()
+        torch.cuda.synchronize()
+        # time: the verifier calls alone, back to back on the stream
         t0 = time.perf_counter()
+        for i in range(a.steps):
+            fn(t_k, d_k, tok_k, 100 + i, ws, out)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / a.steps
+        # accepted lengths: the same calls again, each followed by the batch mean of its result
+        acc.zero_()
         for i in range(a.steps):
             fn(t_k, d_k, tok_k, 100 + i, ws, out)
             acc += out[0].double().mean()
         torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) * 1e3 / a.steps
         rows.append({"verifier": name, "drafts": k, "mean_accepted_len": float(acc.item()) / a.steps,
                      "tokens_per_iteration": float(acc.item()) / a.steps + 1.0, "ms_per_call": ms})
 
