@@ -67,26 +67,61 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
     const int lane = tid & (kWave - 1), wid = tid / kWave;
     const T *row = logits + static_cast<long long>(row_id) * V;
 
-    // ---- pass over the row: four segments of this wave in flight at a time
-    constexpr int UN = 4;
+    // ---- pass over the row.  Aligned rows: a lane's 8 entries of a segment are kept as loaded (16-byte vectors), 16
+    // segments of this wave in flight at a time (8 for float32 rows): a workgroup streams its row alone on its compute
+    // unit, so the loads in flight are what hides the memory latency.  Other rows: four segments, entry by entry.
+    constexpr int PV = Elem<T>::kPerVec;
+    constexpr int NV = 8 / PV;                              // vectors per lane and segment
+    constexpr int UN = VEC ? 16 / NV : 4;
+    auto reduce_segment = [&](int s, const float (&z)[8]) {
+        float w[8];
+        const float m2 = samp_weigh(z, c, __builtin_nanf(""), w);
+        double a = 0.0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a += static_cast<double>(w[j]);
+        a = wave_sum(a);
+        if (lane == 0) { sh_sum[s] = a; sh_m2[s] = m2; }
+    };
     for (int s0 = wid; s0 < nseg; s0 += UN * kSampWaves) {
-        float z[UN][8];
+        if constexpr (VEC) {
+            // V is a multiple of the vector length, so a vector lies wholly inside the row or wholly beyond it
+            const uint32_t ninf = PV == 8 ? 0xFF80FF80u : 0xFF800000u;
+            U4 raw[UN][NV];
 #pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const int s = s0 + i * kSampWaves;
-            if (s < nseg) samp_load8<T, VEC>(row, static_cast<long long>(s) * kSegElems + lane * 8, V, z[i]);
-        }
+            for (int i = 0; i < UN; ++i) {
+                const int s = s0 + i * kSampWaves;
 #pragma unroll
-        for (int i = 0; i < UN; ++i) {
-            const int s = s0 + i * kSampWaves;
-            if (s < nseg) {                                   // wave-uniform
-                float w[8];
-                const float m2 = samp_weigh(z[i], c, __builtin_nanf(""), w);
-                double a = 0.0;
+                for (int v = 0; v < NV; ++v) {
+                    const long long e = static_cast<long long>(s) * kSegElems + lane * 8 + v * PV;
+                    raw[i][v] = (s < nseg && e < V) ? load16(row + e) : U4{ninf, ninf, ninf, ninf};
+                }
+            }
 #pragma unroll
-                for (int j = 0; j < 8; ++j) a += static_cast<double>(w[j]);
-                a = wave_sum(a);
-                if (lane == 0) { sh_sum[s] = a; sh_m2[s] = m2; }
+            for (int i = 0; i < UN; ++i) {
+                const int s = s0 + i * kSampWaves;
+                if (s < nseg) {                               // wave-uniform
+                    float z[8];
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) {
+                        float t[PV];
+                        Elem<T>::unpack(raw[i][v], t);
+#pragma unroll
+                        for (int j = 0; j < PV; ++j) z[v * PV + j] = t[j];
+                    }
+                    reduce_segment(s, z);
+                }
+            }
+        } else {
+            float z[UN][8];
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                const int s = s0 + i * kSampWaves;
+                if (s < nseg) samp_load8<T, VEC>(row, static_cast<long long>(s) * kSegElems + lane * 8, V, z[i]);
+            }
+#pragma unroll
+            for (int i = 0; i < UN; ++i) {
+                const int s = s0 + i * kSampWaves;
+                if (s < nseg) reduce_segment(s, z[i]);        // wave-uniform
             }
         }
     }
