@@ -30,8 +30,8 @@ struct KseqSums { double G, S, Dr; };
 
 // One sweep over the row pair at scale rho.  C1 = log2 Z_p - log2 Z_q; weights relative to 2^shift_q.
 template <typename T, bool VEC>
-__device__ __forceinline__ KseqSums kseq_sweep(const T *rq, const T *rp, int V, float c, float shift_q, double lse2_q,
-                                               double C1, double rho, double *sh_d)
+__device__ __forceinline__ KseqSums kseq_sweep(const T *rq, const T *rp, int V, float c, float shift_q, double C1,
+                                               double rho, double *sh_d)
 {
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
     const RatioConst rc(C1 - log2(rho));                  // rho p / q = 2^(c (z_p - z_q) - C2)
@@ -50,7 +50,6 @@ __device__ __forceinline__ KseqSums kseq_sweep(const T *rq, const T *rp, int V, 
             Dr += open ? e * r : 0.0f;
         }
     });
-    (void)lse2_q;
     KseqSums out;
     out.G = block_sum(static_cast<double>(G), sh_d);
     out.S = block_sum(static_cast<double>(S), sh_d);
@@ -119,7 +118,7 @@ k_kseq_rows(const T *__restrict__ target, const T *__restrict__ draft, const int
     // sums); every quantity is workgroup-uniform.
     double rho = 1.0, lo = 1.0, hi = static_cast<double>(n), beta = 0.0;
     for (int it = 0;; ++it) {
-        const KseqSums sm = kseq_sweep<T, VEC>(rq, rp, V, c, shift_q, lse2_q, C1, rho, sh_d);
+        const KseqSums sm = kseq_sweep<T, VEC>(rq, rp, V, c, shift_q, C1, rho, sh_d);
         beta = sm.G / rho;
         if (n <= 1) break;                                 // one candidate: rho = 1 (Section 3.1)
         const double b1 = beta < 1.0 ? beta : 1.0;
