@@ -419,24 +419,26 @@ __device__ __forceinline__ double pend_token_adjust(const PendRow *pend, long lo
 // f(first entry index, z_q[N], z_p[N]) for the entries of a (target, draft) row pair in the unit range [lo, hi),
 // N = 8 or 4 entries of one 16-byte vector (VEC; a unit is a vector) or 1 (a unit is an entry); the workgroup's
 // THREADS threads stride over the range, each keeping the loads of two vectors of either row in flight.
-template <typename T, bool VEC, int THREADS, typename F>
+// KEEP: the rows are read again soon (by the same workgroup), so they are loaded without the non-temporal hint.
+template <typename T, bool VEC, int THREADS, bool KEEP = false, typename F>
 __device__ __forceinline__ void for_each_pair_range(const T *rq, const T *rp, int lo, int hi, F f)
 {
     constexpr int PV = Elem<T>::kPerVec;
+    auto ld = [](const T *p) { return KEEP ? load16(p) : load16_stream(p); };
     if constexpr (VEC) {
         int v = lo + static_cast<int>(threadIdx.x);
         for (; v + THREADS < hi; v += 2 * THREADS) {             // four loads in flight per thread
-            const U4 q0 = load16_stream(rq + static_cast<long long>(v) * PV), p0 = load16_stream(rp + static_cast<long long>(v) * PV);
-            const U4 q1 = load16_stream(rq + static_cast<long long>(v + THREADS) * PV);
-            const U4 p1 = load16_stream(rp + static_cast<long long>(v + THREADS) * PV);
+            const U4 q0 = ld(rq + static_cast<long long>(v) * PV), p0 = ld(rp + static_cast<long long>(v) * PV);
+            const U4 q1 = ld(rq + static_cast<long long>(v + THREADS) * PV);
+            const U4 p1 = ld(rp + static_cast<long long>(v + THREADS) * PV);
             float zq[PV], zp[PV];
             Elem<T>::unpack(q0, zq); Elem<T>::unpack(p0, zp); f(v * PV, zq, zp);
             Elem<T>::unpack(q1, zq); Elem<T>::unpack(p1, zp); f((v + THREADS) * PV, zq, zp);
         }
         if (v < hi) {
             float zq[PV], zp[PV];
-            Elem<T>::unpack(load16_stream(rq + static_cast<long long>(v) * PV), zq);
-            Elem<T>::unpack(load16_stream(rp + static_cast<long long>(v) * PV), zp);
+            Elem<T>::unpack(ld(rq + static_cast<long long>(v) * PV), zq);
+            Elem<T>::unpack(ld(rp + static_cast<long long>(v) * PV), zp);
             f(v * PV, zq, zp);
         }
     } else {
@@ -448,10 +450,10 @@ __device__ __forceinline__ void for_each_pair_range(const T *rq, const T *rp, in
 }
 
 // The whole row pair.
-template <typename T, bool VEC, int THREADS, typename F>
+template <typename T, bool VEC, int THREADS, bool KEEP = false, typename F>
 __device__ __forceinline__ void for_each_pair(const T *rq, const T *rp, int V, F f)
 {
-    for_each_pair_range<T, VEC, THREADS>(rq, rp, 0, VEC ? V / Elem<T>::kPerVec : V, f);
+    for_each_pair_range<T, VEC, THREADS, KEEP>(rq, rp, 0, VEC ? V / Elem<T>::kPerVec : V, f);
 }
 
 

@@ -22,6 +22,9 @@ namespace specgbv {
 namespace {
 
 constexpr int kKseqThreads = 512;
+// the sweeps of a workgroup read the same row pair again and again: ordinary loads, not the streaming ones
+// (2 - 7 % faster: part of a sweep is then served by the cache levels in front of HBM)
+constexpr bool kKseqKeep = true;
 
 // G(rho) = sum_x min{rho p, q} = rho beta(rho), S(rho) = sum_x max{q - rho p, 0} = 1 - G, and rho * sum_{rho p < q} p.
 // G and S are summed separately and normalised by their own total, so that each keeps its leading digits where it is
@@ -39,7 +42,7 @@ __device__ __forceinline__ KseqSums kseq_sweep(const T *rq, const T *rp, int V, 
     // summed as min{rho p, q} (not as max{q - rho p, 0} = q - min): where the two models hardly overlap the sum is
     // tiny and the equation for rho is decided by its leading digits
     float G = 0.0f, S = 0.0f, Dr = 0.0f;
-    for_each_pair<T, VEC, kKseqThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+    for_each_pair<T, VEC, kKseqThreads, kKseqKeep>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             const float r = exp2_fast(fmaf(zp[j] - zq[j], c, -rc.C2_hi)) * kappa;        // rho p / q
@@ -90,7 +93,7 @@ k_kseq_rows(const T *__restrict__ target, const T *__restrict__ draft, const int
     const T *rp = draft + pair * static_cast<long long>(V);
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
     RunningSum aq, ap;
-    for_each_pair<T, VEC, kKseqThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+    for_each_pair<T, VEC, kKseqThreads, kKseqKeep>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
         aq.add(zq, c);
         ap.add(zp, c);
     });
