@@ -14,7 +14,8 @@
 // pending level; a level's rows are shared among workgroups when it has few of them left).
 //
 // Small batches, where a workgroup per row would leave most of the chip idle, use k_row_stats_parts and
-// k_ot_sum_parts instead: every row is cut into parts, combined in part order by the consumers.
+// k_ot_sum_parts (and k_excess_parts for the rows that need the cancellation-free sum) instead: every row is cut into
+// parts, combined in part order by the consumers.
 //
 // Any V and any alignment is accepted (rows whose byte length is not a multiple of 16
 // take the scalar-load path).  This schedule reads every row pair twice; it is the
@@ -196,7 +197,7 @@ template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kStatThreads)
 k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int K, int L,
                int V, float c, int P, const Row0Part *__restrict__ stat_parts, int stat_P, RowStat *stats,
-               int32_t *__restrict__ final_counter, double *__restrict__ s_part, double *__restrict__ e_part,
+               int32_t *__restrict__ final_counter, double *__restrict__ s_part,
                const PendRow *__restrict__ pend, long long n_rows, int nlev, double c_rel)
 {
     __shared__ double sh_d[kStatThreads / kWave];
@@ -276,22 +277,58 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
         });
     }
     const double total = block_sum(static_cast<double>(acc), sh_d);
-    // A part cannot tell whether the row's s and g nearly cancel, so for every block ratio above one the terms of
-    // nu^2 (s - g) are summed too (a second sweep over the part: this kernel serves small batches, where time is
-    // latency, not arithmetic); -1 in every part marks a row without it.
-    double e_val = -1.0;
-    if (!(PEND && sh_tab.n > 0) && log2nu > 0.0) {                              // uniform over the workgroup
-        const ExcessConst ec = make_excess_const(st.lse2_q, st.lse2_p, log2nu, K, c);
-        float acc2 = 0.0f;
-        for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
-            acc2 += excess_terms(zq, zp, ec);
-        });
-        e_val = block_sum(static_cast<double>(acc2), sh_d) * ec.scale;
+    // (whether the row's s and g nearly cancel, so that Eq. (hik) needs nu^2 (s - g) summed term by term, only the sum
+    // over all parts can tell: k_excess_parts looks at it once every part is in)
+    if (threadIdx.x == 0) s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
+}
+
+// grid rows * P as k_ot_sum_parts, launched after it: E = nu^2 (s - g) of the rows whose s and g nearly cancel, in the
+// same parts (-1 in every part marks a row without it).  Every workgroup adds up its row's partial sums and leaves at
+// once unless the row wants the sum (rare: peaked rows, large block ratios); the others sweep their part again.
+template <typename T, bool VEC, bool PEND>
+__global__ void __launch_bounds__(kStatThreads)
+k_excess_parts(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c, int P,
+               const RowStat *__restrict__ stats, const double *__restrict__ s_part, double *__restrict__ e_part,
+               const PendRow *__restrict__ pend, long long n_rows, int nlev)
+{
+    __shared__ double sh_d[kStatThreads / kWave];
+    const long long idx = blockIdx.x / P;         // bk*(L-1) + (i-1)
+    const int part = static_cast<int>(blockIdx.x % P);
+    const int i = static_cast<int>(idx % (L - 1)) + 1;
+    const long long bk = idx / (L - 1);
+    const long long pair = bk * L + i;
+    const RowStat st = stats[pair];
+    double log2nu = 0.0;
+    bool modified = false;                        // rows under pending modifications keep the plain sum
+    if (PEND) {
+        log2nu = pend_block_ratio(stats, pend, n_rows, nlev, bk * L, i, sh_d);
+        for (int l = 0; l < nlev; ++l) modified = modified || pend[static_cast<long long>(l) * n_rows + pair].flag != 0;
+    } else {
+        for (int j = 0; j < i; ++j) {
+            const RowStat a = stats[bk * L + j];
+            log2nu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
+        }
     }
-    if (threadIdx.x == 0) {
-        s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
-        e_part[pair * kPendParts + part] = e_val;
+    double s_val = 0.0;
+    for (int q = 0; q < P; ++q) s_val += s_part[pair * kPendParts + q];
+    // (every thread has read the same values: uniform over the workgroup)
+    if (modified || !excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_val), K)) {
+        if (threadIdx.x == 0) e_part[pair * kPendParts + part] = -1.0;
+        return;
     }
+    const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
+    const T *rp = draft + pair * static_cast<long long>(V);
+    constexpr int N = VEC ? Elem<T>::kPerVec : 1;
+    const int units = VEC ? V / N : V;
+    const int per = (units + P - 1) / P;
+    const int lo = part * per, hi = lo + per < units ? lo + per : units;
+    const ExcessConst ec = make_excess_const(st.lse2_q, st.lse2_p, log2nu, K, c);
+    float acc2 = 0.0f;
+    for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+        acc2 += excess_terms(zq, zp, ec);
+    });
+    const double e_val = block_sum(static_cast<double>(acc2), sh_d) * ec.scale;
+    if (threadIdx.x == 0) e_part[pair * kPendParts + part] = e_val;
 }
 
 // One level of pending modification (the levels below it are done: their PendRow entries are read).
@@ -558,10 +595,14 @@ hipError_t launch_typed(const Problem &p)
     if (p.s_parts > 1) {                            // small batch: partial sums, added up by the final-token kernel
         const dim3 gq(static_cast<unsigned>(rows * p.s_parts));
 #define SPECGBV_OTP_LAUNCH(VEC, PEND)                                                                                 \
-    hipLaunchKernelGGL((k_ot_sum_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, p.K, \
-                       p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part,                     \
-                       reinterpret_cast<double *>(p.ws + p.lay.excess_part), pend, pairs,                              \
-                       p.pend_levels, p.c_rel)
+    do {                                                                                                              \
+        hipLaunchKernelGGL((k_ot_sum_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, \
+                           p.K, p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part, pend, pairs, \
+                           p.pend_levels, p.c_rel);                                                                   \
+        hipLaunchKernelGGL((k_excess_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L, \
+                           p.V, p.c, p.s_parts, stats, pend_part, reinterpret_cast<double *>(p.ws + p.lay.excess_part),  \
+                           pend, pairs, p.pend_levels);                                                               \
+    } while (0)
         if (p.pend_levels > 0) { if (vec) SPECGBV_OTP_LAUNCH(true, true); else SPECGBV_OTP_LAUNCH(false, true); }
         else { if (vec) SPECGBV_OTP_LAUNCH(true, false); else SPECGBV_OTP_LAUNCH(false, false); }
 #undef SPECGBV_OTP_LAUNCH
