@@ -73,6 +73,28 @@ def test_argument_errors_are_caught_before_any_launch():
     assert _call(lib, B=0) == 0                             # empty batch: nothing to do
 
 
+def test_comparison_and_static_entry_point_errors_are_caught_before_any_launch():
+    lib = sg.load_library()
+    P = 1 << 20
+
+    def kseq(K=4, L=3, V=64, B=1, dt=0, T=1.0, nd=2, t=P, ws=P, wsb=1 << 30):
+        return lib.specgbv_verify_kseq(t, P, P, K, L, V, B, dt, ctypes.c_float(T), 0, 0, nd, P, P, P, ws, wsb, None)
+    assert kseq(nd=0) == 1 and "ndrafts" in sg.specgbv_last_error()
+    assert kseq(nd=5) == 1                                   # more drafts than the tensors hold
+    assert kseq(K=0) == 1 and kseq(T=-1.0) == 1 and kseq(dt=7) == 1 and kseq(t=None) == 1
+    assert kseq(K=65, nd=1) == 2
+    assert kseq(ws=None) == 3 and kseq(wsb=64) == 3 and "need" in sg.specgbv_last_error()
+    assert kseq(B=0) == 0
+
+    def static(K=8, L=8, V=128256, B=32, dt=1):
+        return lib.specgbv_verify_static(P, P, P, K, L, V, B, dt, ctypes.c_float(1.0), 0, 0, P, P, P, None)
+    assert static(K=0) == 1
+    assert static(K=65) == 2
+    # the built-in scratch buffer has a fixed size: larger shapes are refused with the size they would need
+    assert static(K=16, L=8, V=152064, B=128) == 2 and "SPECGBV_STATIC_SCRATCH_BYTES" in sg.specgbv_last_error()
+    assert sg.specgbv_workspace_bytes(128, 16, 8, 152064, 1) > sg.STATIC_SCRATCH_BYTES >= sg.specgbv_workspace_bytes(32, 8, 8, 128256, 1)
+
+
 def test_pending_option_errors_are_caught_before_any_launch():
     from paper_2604_25925_amd.binding import _Options
     lib = sg.load_library()
