@@ -110,6 +110,35 @@ def test_benchmark_configurations(name, B):
         check(t, d, tok, w.temperature, 0, off, None, "%s/B%d K-SEQ" % (name, B), rho_tol=3.0)
 
 
+def test_cfg4_full_size_sampled_prefixes():
+    """The benchmark configuration at full size, as bench.py --op compare times it (2048 row pairs, one workgroup
+    each); the oracle recomputes 3 of the 32 prefixes with their own Philox counters."""
+    import torch
+    import oracle
+    import paper_2604_25925_amd as sg
+    w = WORKLOADS["cfg4"]
+    t, d, tok = make_inputs(w, seed=0)
+    tl, dl, tk = to_torch(t), to_torch(d), to_torch(np.ascontiguousarray(tok, dtype=np.int32))
+    a, f, o, ws = sg.specgbv_verify_kseq(tl, dl, tk, w.temperature, 3, 1)
+    torch.cuda.synchronize()
+    full = {"accepted_len": a.cpu().numpy(), "accepted_draft_idx": f.cpu().numpy(), "out_tokens": o.cpu().numpy()}
+    full.update(sg.specgbv_read_kseq_intermediates(ws, w.batch, w.K, w.L, w.V))
+    ids = [0, 13, 31]
+    gpu = {k: np.ascontiguousarray(v[ids]) for k, v in full.items()}
+    ora = oracle.verify_kseq(t[ids], d[ids], tok[ids], w.temperature, 3, 1, debug=True, eager=True, nthreads=8,
+                             prefix_ids=np.asarray(ids, np.int32))
+    rep = compare(gpu, ora, tok[ids], w.K, "cfg4/full K-SEQ")
+    assert rep["max_err"]["rho_all"] <= 3.0
+    # properties that hold at any size, on all prefixes
+    tau, lead, out = full["accepted_len"], full["accepted_draft_idx"], full["out_tokens"]
+    assert np.all((tau >= 0) & (tau <= w.L)) and np.all((lead == -1) == (tau == 0)) and np.all(lead < w.K)
+    for b in range(w.batch):
+        assert np.array_equal(out[b, :tau[b]], tok[b, max(lead[b], 0), :tau[b]])
+        assert 0 <= out[b, tau[b]] < w.V and np.all(out[b, tau[b] + 1:] == -1)
+    assert np.all((full["rho_all"] >= 1.0 - 1e-12) & (full["rho_all"] <= w.K + 1e-9))
+    assert np.all((full["beta_all"] > 0.0) & (full["beta_all"] <= 1.0 + 1e-9))
+
+
 @pytest.mark.parametrize("nd", [1, 2, 3])
 def test_fewer_drafts_and_token_level_speculative_decoding(nd):
     import oracle
