@@ -520,6 +520,20 @@ __device__ __forceinline__ double wave_sum(double v) {
     return __longlong_as_double(static_cast<long long>((static_cast<unsigned long long>(hi) << 32) | lo));
 }
 
+// Sum over the wave in float32 (DPP adds fused into the moves); every lane gets the result.
+__device__ __forceinline__ float wave_sum_f32(float v) {
+#define SPECGBV_ADD_STEP(CTRL, ROW_MASK) \
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false))
+    SPECGBV_ADD_STEP(0x111, 0xf);
+    SPECGBV_ADD_STEP(0x112, 0xf);
+    SPECGBV_ADD_STEP(0x114, 0xf);
+    SPECGBV_ADD_STEP(0x118, 0xf);
+    SPECGBV_ADD_STEP(0x142, 0xa);
+    SPECGBV_ADD_STEP(0x143, 0xc);
+#undef SPECGBV_ADD_STEP
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 // Maximum over the wave; every lane gets the result.  Lanes without a source keep their own value.
 __device__ __forceinline__ float wave_max(float v) {
 #define SPECGBV_MAX_STEP(CTRL, ROW_MASK)                                                                   \

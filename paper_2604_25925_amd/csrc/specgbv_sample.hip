@@ -36,6 +36,19 @@ __device__ __forceinline__ void samp_load8(const T *row, long long e0, int V, fl
     }
 }
 
+// largest of the logits packed in one 16-byte vector
+template <typename T>
+__device__ __forceinline__ float vec_max_elem(const U4 &v)
+{
+    constexpr int PV = Elem<T>::kPerVec;
+    float t[PV];
+    Elem<T>::unpack(v, t);
+    float m = t[0];
+#pragma unroll
+    for (int j = 1; j < PV; ++j) m = fmaxf(m, t[j]);
+    return m;
+}
+
 // weights of a lane's 8 entries relative to 2^m2; m2 = NaN asks for the segment's own reference
 __device__ __forceinline__ float samp_weigh(const float (&z)[8], float c, float m2_in, float (&w)[8])
 {
@@ -73,14 +86,14 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NV = 8 / PV;                              // vectors per lane and segment
     constexpr int UN = VEC ? 16 / NV : 4;
-    auto reduce_segment = [&](int s, const float (&z)[8]) {
+    // m2 = NaN: the segment takes its own reference exponent; else the one given (shared by a batch of segments)
+    auto reduce_segment = [&](int s, const float (&z)[8], float m2_in) {
         float w[8];
-        const float m2 = samp_weigh(z, c, __builtin_nanf(""), w);
-        double a = 0.0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) a += static_cast<double>(w[j]);
-        a = wave_sum(a);
-        if (lane == 0) { sh_sum[s] = a; sh_m2[s] = m2; }
+        const float m2 = samp_weigh(z, c, m2_in, w);
+        // 512 weights of at most 2^1 each: float32 sums (8 per lane, then over the wave) are good to a few 1e-7 of
+        // the segment, far inside the 1e-6 of the total below which a draw counts as undecided
+        const float a = wave_sum_f32(((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7])));
+        if (lane == 0) { sh_sum[s] = static_cast<double>(a); sh_m2[s] = m2; }
     };
     for (int s0 = wid; s0 < nseg; s0 += UN * kSampWaves) {
         if constexpr (VEC) {
@@ -96,6 +109,14 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
                     raw[i][v] = (s < nseg && e < V) ? load16(row + e) : U4{ninf, ninf, ninf, ninf};
                 }
             }
+            // one reference exponent for the whole batch (its largest logit): a wave-wide maximum per batch instead
+            // of one per segment.  Entries 2^-126 below it round to weight 0, which they are against the total anyway.
+            float mb = -3.0e38f;
+#pragma unroll
+            for (int i = 0; i < UN; ++i)
+#pragma unroll
+                for (int v = 0; v < NV; ++v) mb = fmaxf(mb, vec_max_elem<T>(raw[i][v]));
+            const float m2_batch = integral_reference(wave_max(mb), c);
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int s = s0 + i * kSampWaves;
@@ -108,7 +129,7 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
 #pragma unroll
                         for (int j = 0; j < PV; ++j) z[v * PV + j] = t[j];
                     }
-                    reduce_segment(s, z);
+                    reduce_segment(s, z, m2_batch);
                 }
             }
         } else {
@@ -121,7 +142,7 @@ k_sample_rows(const T *__restrict__ logits, int V, float c, int nseg, uint64_t s
 #pragma unroll
             for (int i = 0; i < UN; ++i) {
                 const int s = s0 + i * kSampWaves;
-                if (s < nseg) reduce_segment(s, z[i]);        // wave-uniform
+                if (s < nseg) reduce_segment(s, z[i], __builtin_nanf(""));   // wave-uniform
             }
         }
     }
