@@ -859,7 +859,9 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
             const double zq = static_cast<double>(Elem<T>::scalar(target + sl.target_row * V + tokid));
             const double zp = static_cast<double>(Elem<T>::scalar(draft + sl.draft_row * V + tokid));
             double l2 = sl.C2 + static_cast<double>(c) * (zq - zp);        // log2 of nu_tau q[y] / p[y]
-            l2 += io.c_rel * (static_cast<double>(c) * (zq - zp) + sl.lse2_pq);   // y's two log-probabilities at the caller's temperature (token_scaled)
+            // y's two log-probabilities at the caller's temperature (token_scaled); p[y] = 0 leaves the ratio infinite
+            const double adj = static_cast<double>(c) * (zq - zp) + sl.lse2_pq;
+            if (adj - adj == 0.0) l2 += io.c_rel * adj;
             if (PEND) {                                     // q'[y] = q[y] prod_l t_l[y]^K / N_l (the N_l are in C2)
                 double log2T = 0.0;
                 for (int l = 0; l < sl.npend; ++l) {

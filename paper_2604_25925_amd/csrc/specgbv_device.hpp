@@ -76,7 +76,12 @@ struct SegPartial {
 // (hundreds of base-2 units at a low temperature) would carry that relative error into the block ratio in
 // full.  To first order the log-probability of such a token is proportional to the scale, so it is rescaled;
 // for tokens near the bulk the adjustment is far below the arithmetic's own error.
-__device__ __forceinline__ double token_scaled(double tok2, double lse2, double c_rel) { return tok2 + c_rel * (tok2 - lse2); }
+// A token the model gives probability zero (logit -inf) keeps its -inf.
+__device__ __forceinline__ double token_scaled(double tok2, double lse2, double c_rel)
+{
+    const double d = tok2 - lse2;
+    return (d - d == 0.0) ? tok2 + c_rel * d : tok2;      // (d - d is 0 for finite d and not a number otherwise)
+}
 
 // ------------------------------------------------------------------- loads
 
@@ -368,8 +373,10 @@ __device__ __forceinline__ float excess_terms(const float (&zq)[N], const float 
     return acc;
 }
 
-// Do s and g agree so closely (block ratio above one) that nu (s - g) needs the sum E?  The plain sum s carries a
-// relative error of a few 1e-8; below (s - g) / s = 1/64 that is no longer negligible against 1e-5.
+// Do s and g agree so closely (block ratio above one) that nu (s - g) needs the sum E?  The plain sum s of a row
+// that a few entries dominate carries the float32 exponential's error of those entries unaveraged, 1e-7 for each
+// of its two exponentials and K times that through the power (3e-7 observed at K = 4 on a 526-entry row); below
+// (s - g) / s = 1/16 that is no longer safely under the 1e-5 the acceptance probability is held to.
 // (float32 throughout: the threshold need not be sharp, and float64 constants in a kernel whose registers hold a
 // whole row pair end up in scratch memory)
 __device__ __forceinline__ bool excess_wanted(float l, float sf, int K)
@@ -377,7 +384,7 @@ __device__ __forceinline__ bool excess_wanted(float l, float sf, int K)
     if (!(l > 0.0f)) return false;
     const float t1 = 1.0f - exp2_fast(-l);
     const float g = powi_uniform(t1, K);
-    return (sf - g) * 64.0f < sf;
+    return (sf - g) * 16.0f < sf;
 }
 
 // Entry l of a PendTable from the float64 constant C (same split as RatioConst).

@@ -232,6 +232,34 @@ def test_masked_logits_minus_infinity(algo, dtype, V):
 
 
 @pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("T", [0.8, 0.56])
+def test_forbidden_tokens_at_other_temperatures(algo, T):
+    # Drafted tokens the target gives probability zero (nu = 0 from there on) and target-only tokens (p = 0, so the
+    # ratio carried to the next iteration is infinite when one is drawn), at temperatures whose float32 scale is
+    # rounded down (0.56) and up (0.8): the first-order correction for that rounding must leave infinities alone.
+    t, d, tok, _ = _gauss_case(6, 3, 4, 32768, "f32", seed=21, T=T)
+    rng = np.random.default_rng(22)
+    V = t.shape[-1]
+    d[..., rng.integers(0, V, V // 3)] = -np.inf           # a third of the vocabulary unknown to the draft model
+    B, K, L = tok.shape
+    for b in range(B):
+        for k in range(K):
+            for r in range(L):
+                while not np.isfinite(d[b, k, r, tok[b, k, r]]):
+                    tok[b, k, r] = rng.integers(0, V)
+    for b in range(B):
+        t[b, b % K, 1 + b % (L - 1), tok[b, b % K, 1 + b % (L - 1)]] = -np.inf
+    t, d = f32_to_bf16_bits(t), f32_to_bf16_bits(d)
+    seen_inf = False
+    for off in range(4):
+        rep, gpu, ora = _checked(algo, t, d, tok, T, 5, off, algo, "forbidden tokens T=%g" % T)
+        assert np.array_equal(np.isneginf(ora["log_nu"]), np.isneginf(gpu["log_nu"])) and np.isneginf(ora["log_nu"]).any()
+        seen_inf = seen_inf or bool(np.isposinf(ora["carry_log_nu"]).any())
+        assert np.array_equal(np.isposinf(ora["carry_log_nu"]), np.isposinf(gpu["carry_log_nu"]))
+    assert seen_inf                                          # some final token was one the draft model cannot produce
+
+
+@pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_whole_segments_masked_in_every_row(algo, dtype):
     # vocabulary padding longer than a 512-entry residual segment, masked with -inf in both models: a segment
