@@ -60,6 +60,7 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.pend_cnt = take(n * sizeof(int32_t));
     w.stat_part = take(n * 2 * kRowParts * sizeof(Row0Part));
     w.row0 = take(static_cast<size_t>(batch) * 2 * kRow0Parts * sizeof(Row0Part));
+    w.later = take(static_cast<size_t>(kMaxChainGrid) * 64 * sizeof(int32_t));
     w.kseq_pos = take(static_cast<size_t>(batch) * L * 2 * sizeof(int32_t));
     w.total = off;
     return w;
@@ -146,6 +147,7 @@ specgbv_status specgbv_verify_ex(
     p.stream = static_cast<hipStream_t>(hip_stream);
 
     static_assert(SPECGBV_MAX_PENDING == kMaxPend, "header and kernels disagree on the number of pending levels");
+    static_assert(SPECGBV_MAX_K == kMaxDrafts, "header and kernels disagree on the number of drafts");
     p.pend_carry = options ? options->pending_carry_log_nu : nullptr;
     p.pend_count = options ? options->pending_count : nullptr;
     p.pend_levels = 0;
@@ -188,6 +190,7 @@ specgbv_status specgbv_verify_ex(
     }
 
     p.s_parts = use_chain ? 1 : split_sum_parts(p);
+    p.e_parts = (use_chain && !pending) ? chain_excess_parts(p) : 0;
 
     hipError_t e;
     if (options && options->ev_main_start) {

@@ -95,8 +95,14 @@ struct RowConsts {
     int K;
 };
 
+// `tok_slot` (uniform): this slot of the row holds the drafted token's vector, in the lane for which `tok_mine`
+// holds.  That vector's weights are summed apart, from a copy fetched with the token's logits (see the row loop):
+// next to the token's weight, which is one, the float32 sums of its thread would lose the other entries' low bits,
+// and a row whose drafted token has probability 0.9999 needs exactly those (its remaining mass is what 1 - P and
+// 1 - Q in Eq. (hik) are made of).
 template <typename T>
-__device__ __forceinline__ void sweep1_vec(const U4 &q, const U4 &p, const RowConsts &rc, float &Zq, float &Zp)
+__device__ __forceinline__ void sweep1_vec(const U4 &q, const U4 &p, const RowConsts &rc, float &Zq, float &Zp,
+                                           bool tok_slot = false, bool tok_mine = false)
 {
     constexpr int PV = Elem<T>::kPerVec;
     float zq[PV], zp[PV];
@@ -108,7 +114,10 @@ __device__ __forceinline__ void sweep1_vec(const U4 &q, const U4 &p, const RowCo
         a += exp2_fast(fmaf(zq[j], rc.c, rc.nref_q));
         b += exp2_fast(fmaf(zp[j], rc.c, rc.nref_p));
     }
-    Zq += a; Zp += b;
+    if (!(tok_slot && tok_mine)) {
+        asm volatile("");                       // (keeps this a masked block: two adds, and scalar work for the mask)
+        Zq += a; Zp += b;
+    }
 }
 
 template <typename T, int KP>
@@ -241,43 +250,34 @@ __device__ __noinline__ ExactStats exact_row_stats(const T *row, int nvec, float
     return ExactStats{ref, a};
 }
 
-// E = nu^2 (s - g) of one row pair straight from memory (rows whose s and g nearly cancel; see ExcessConst).
-// Runs after the row loop, when the registers no longer hold a row pair: several vector pairs in flight per thread.
-template <typename T>
-__device__ __forceinline__ double excess_row(const T *qrow, const T *prow, int nvec, const ExcessConst &ec, double *sh_d)
+constexpr int kExcessThreads = 256;
+
+// Does the acceptance probability of a row whose s and g nearly cancel (excess_wanted) need the sum E at all?
+// With h = E / (E + D), D = (1 - Q) S2 / nu (the decision kernel's form of Eq. (hik) for a block ratio above one), a
+// relative error on E = nu (s - g) reaches h reduced by the factor 1 - h = D / (D + E): a block that is accepted
+// almost surely does not care how well s - g is known.  The test of excess_wanted, sharpened by that factor, which
+// is itself taken at the low end of what the plain s allows for s - g (1e-6 s below it; not above 0: needed).
+// (A function of its own, called by one thread for the few rows that pass the first test: its float64 registers
+// would otherwise be taken from the ones that hold the row pair.)
+__device__ __noinline__ bool excess_needed(double log2nu, double log2P, double s, int K)
 {
-    constexpr int PV = Elem<T>::kPerVec;
-    constexpr int kAhead = 4;
-    float acc = 0.0f;
-    U4 q[kAhead], p[kAhead];
-    const int last = nvec - 1;
-#pragma unroll
-    for (int j = 0; j < kAhead; ++j) {
-        const int v = static_cast<int>(threadIdx.x) + j * kChainThreads;
-        q[j] = load16(qrow + static_cast<long long>(v < nvec ? v : last) * PV);
-        p[j] = load16(prow + static_cast<long long>(v < nvec ? v : last) * PV);
-    }
-    for (int v0 = threadIdx.x; v0 < nvec; v0 += kAhead * kChainThreads) {
-#pragma unroll
-        for (int j = 0; j < kAhead; ++j) {
-            const int v = v0 + j * kChainThreads;
-            float zq[PV], zp[PV];
-            Elem<T>::unpack(q[j], zq);
-            Elem<T>::unpack(p[j], zp);
-            const int nx = v + kAhead * kChainThreads;                 // the pair this slot holds next
-            q[j] = load16(qrow + static_cast<long long>(nx < nvec ? nx : last) * PV);
-            p[j] = load16(prow + static_cast<long long>(nx < nvec ? nx : last) * PV);
-            if (v < nvec) acc += excess_terms(zq, zp, ec);
-        }
-    }
-    double a = static_cast<double>(acc), b = 0.0;
-    block_sum2(a, b, sh_d);
-    return a * ec.scale;
+    const double inv_nu = exp2_small(-log2nu), P = exp2_small(log2P);
+    const double t1 = 1.0 - inv_nu, A = 1.0 - P;
+    double g = 1.0;
+    for (int j = 0; j < K; ++j) g *= t1;
+    double U = 1.0, S2 = 0.0, pw = 1.0;
+    for (int j = 1; j <= K - 1; ++j) { S2 += U; pw *= t1; U = fma(A, U, pw); }
+    const double one_Q = fmax(1.0 - exp2_small(log2nu + log2P), 0.0);
+    const double D = inv_nu * one_Q * S2;
+    const double x = (s - g) - 1.0e-6 * s;
+    if (!(x > 0.0)) return true;
+    return x * 16.0 * (D + x / inv_nu) < s * D;
 }
 
-// Rows of this workgroup whose Eq. (hik) sum is taken again after the row loop (LDS; thread 0 appends).
-constexpr int kMaxLater = 96;
-struct LaterRow { long long bk; int r; int pad; double log2nu, lse2_q, lse2_p; };
+// Rows a workgroup of k_chain hands to k_chain_excess: entry 0 of its list is their number, then their row indices.
+constexpr int kMaxLater = 63;
+constexpr int kLaterStride = kMaxLater + 1;
+static_assert(kLaterStride == 64, "the workspace holds 64 entries per list");
 
 constexpr int kLag = 6;    // slots between the load of a vector and its first use
 constexpr double kTokenRefLimit = 1073741824.0;   // 2^30: largest row sum accepted relative to the drafted token's weight
@@ -298,6 +298,8 @@ struct StepCtx {
     unsigned tid, off_new;   // thread index; byte offset of this lane's vector within a slot of the new row (0 after the last row)
     int nvec, rem, n_on;
     bool do_new, do_sum;
+    int tok_slot;            // slot of the new row that holds the drafted token's vector (uniform)
+    bool tok_mine;           // ... and whether this lane's vector of that slot is the one
 };
 
 // Order in which the on-chip slots of a row are visited: the LDS slots first, from the highest down (slots a short
@@ -358,14 +360,15 @@ __device__ __forceinline__ void pipeline_step(const StepCtx<T> &cx, U4 (&rq)[RS]
     if constexpr (II >= 0 && II < NS) {
         constexpr int JJ = slot_at<RS>(II);
         if constexpr (JJ < RS) {
-            if (cx.do_new) sweep1_vec<T>(rq[JJ], rp[JJ], cx.rc_new, Zq, Zp);
+            if (cx.do_new) sweep1_vec<T>(rq[JJ], rp[JJ], cx.rc_new, Zq, Zp, JJ == cx.tok_slot, cx.tok_mine);
         } else {
             // (the loads of this step are issued before the wait that counts them)
             __builtin_amdgcn_sched_barrier(0);
             if (cx.do_new && JJ < cx.n_on) {
                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kLag) : "memory");
                 if (JJ * kChainThreads < cx.rem)
-                    sweep1_vec<T>(lds_vec(lds, JJ - RS, 0, t), lds_vec(lds, JJ - RS, 1, t), cx.rc_new, Zq, Zp);
+                    sweep1_vec<T>(lds_vec(lds, JJ - RS, 0, t), lds_vec(lds, JJ - RS, 1, t), cx.rc_new, Zq, Zp,
+                                  JJ == cx.tok_slot, cx.tok_mine);
             }
         }
     }
@@ -455,13 +458,18 @@ constexpr int kRow0Threads = 256;
 // conditioned on the prefix alone; Algorithm 3).  grid (kRow0Parts, batch, 2): workgroup (i, b, m) reduces
 // slice i of row 0 of draft 0 of prefix b, in the target (m = 0) or draft (m = 1) tensor, to
 // sum_x 2^(c z[x] - ref) with an integral reference exponent, so that the slices combine exactly.
+// The tokens the K drafts start with are left out of the float32 sums of the slice they fall in (leave_out); the
+// first wave adds the weight of each distinct one in float64.
 template <typename T>
 __global__ void __launch_bounds__(kRow0Threads)
-k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
-             Row0Part *__restrict__ parts)
+k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int K, int L,
+             int V, float c, Row0Part *__restrict__ parts)
 {
+    static_assert(kMaxDrafts <= kWave, "one lane of the first wave per draft");
     __shared__ double sh_d[kRow0Threads / kWave];
     __shared__ float sh_f[kRow0Threads / kWave];
+    __shared__ int sh_tok[kMaxDrafts];                     // the distinct first tokens that fall into this slice
+    __shared__ int sh_ntok;
     const int part = blockIdx.x, b = blockIdx.y, m = blockIdx.z;
     const long long bk0 = static_cast<long long>(b) * K;
     const T *row = m ? draft + bk0 * L * static_cast<long long>(V) : target + bk0 * (L + 1) * static_cast<long long>(V);
@@ -469,6 +477,31 @@ k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, int K, i
     const int nvec = V / PV;
     const int per = (nvec + kRow0Parts - 1) / kRow0Parts;
     const int lo = part * per, hi = lo + per < nvec ? lo + per : nvec;
+    double tok2_mine = -static_cast<double>(__builtin_inff());     // first wave: scaled logit of the lane's token, if it is listed
+    if (threadIdx.x < kWave) {
+        const int j = threadIdx.x;
+        int tok = j < K ? tokens[(bk0 + j) * L] : 0;
+        tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+        bool keep = j < K && tok / PV >= lo && tok / PV < hi;
+        for (int e = 0; e < K; ++e) {                          // not a token an earlier draft has too
+            const int other = __builtin_amdgcn_readlane(tok, e);
+            if (e < j && other == tok) keep = false;
+        }
+        const unsigned long long kept = __ballot(keep);
+        if (keep) {
+            sh_tok[__popcll(kept & ((1ull << j) - 1ull))] = tok;
+            tok2_mine = static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c);
+        }
+        if (j == 0) sh_ntok = __popcll(kept);
+    }
+    __syncthreads();
+    const int ntok = __builtin_amdgcn_readfirstlane(sh_ntok);
+    auto drop = [&](float (&z)[PV], int idx) {
+        for (int e = 0; e < ntok; ++e) {
+            const int tok = sh_tok[e];
+            leave_out(z, idx == tok / PV, tok % PV);
+        }
+    };
     RunningSum acc;
     for (int i = lo + static_cast<int>(threadIdx.x); i < hi; i += 4 * kRow0Threads) {     // four loads in flight per thread
         U4 v[4];
@@ -482,6 +515,7 @@ k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, int K, i
             if (i + j * kRow0Threads < hi) {
                 float z[PV];
                 Elem<T>::unpack(v[j], z);
+                drop(z, i + j * kRow0Threads);
                 acc.add(z, c);
             }
         }
@@ -489,11 +523,23 @@ k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, int K, i
     const float M = block_max(acc.m2, sh_f);
     const double mine = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));
     const double total = block_sum(acc.Z > 0.0f ? mine : 0.0, sh_d);
-    if (threadIdx.x == 0) {
-        Row0Part out;
-        out.ref = floor(static_cast<double>(M));
-        out.Z = total * exp2(static_cast<double>(M) - out.ref);
-        parts[(static_cast<long long>(b) * 2 + m) * kRow0Parts + part] = out;
+    if (threadIdx.x < kWave) {                                 // (uniform over the first wave)
+        // the listed tokens' weights, relative to the largest of them
+        double tmax = tok2_mine;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) tmax = fmax(tmax, __shfl_xor(tmax, o));
+        const double wsum = wave_sum(tok2_mine > -1.0e300 ? exp2(tok2_mine - tmax) : 0.0);
+        if (threadIdx.x == 0) {
+            double ref = static_cast<double>(M), Z = total;
+            if (tmax > -1.0e300) {                             // (-inf: none listed, or all of them masked entries)
+                ref = fmax(ref, tmax);
+                Z = (total > 0.0 ? total * exp2(static_cast<double>(M) - ref) : 0.0) + wsum * exp2(tmax - ref);
+            }
+            Row0Part out;
+            out.ref = floor(ref);
+            out.Z = Z * exp2(ref - out.ref);
+            parts[(static_cast<long long>(b) * 2 + m) * kRow0Parts + part] = out;
+        }
     }
 }
 
@@ -509,11 +555,11 @@ __device__ __forceinline__ double lane_d(double v, int lane)
 // partial sums (lanes 0..15 of every wave take the target slices, lanes 16..31 the draft slices; the same
 // butterfly in every workgroup, so every draft of the prefix gets the same bits), the chain's own token
 // read from draft 0's rows.  Every wave computes the same values; thread 0 stores the RowStat.  Returns the
-// log2 block ratio after that token.
+// log2 block ratio after that token (and in log2P the log2 of the token's draft probability).
 template <typename T>
 __device__ __forceinline__ double row0_from_parts(const Row0Part *parts, const T *target, const T *draft,
                                                   const int32_t *tokens, long long bk, int K, int L, int V, float c,
-                                                  double c_rel, RowStat *stats)
+                                                  double c_rel, RowStat *stats, double &log2P)
 {
     static_assert(kRow0Parts == 16, "one 16-lane row per tensor");
     const long long b = bk / K;
@@ -536,6 +582,7 @@ __device__ __forceinline__ double row0_from_parts(const Row0Part *parts, const T
     st.tok2_q = token_scaled(static_cast<double>(Elem<T>::scalar(target + bk0 * (L + 1) * static_cast<long long>(V) + tok)) * static_cast<double>(c), st.lse2_q, c_rel);
     st.tok2_p = token_scaled(static_cast<double>(Elem<T>::scalar(draft + bk0 * L * static_cast<long long>(V) + tok)) * static_cast<double>(c), st.lse2_p, c_rel);
     if (threadIdx.x == 0) stats[bk * L] = st;
+    log2P = st.tok2_p - st.lse2_p;
     return (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);
 }
 
@@ -590,15 +637,15 @@ __global__ void __launch_bounds__(kChainThreads)
 k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens,
         int K, int L, int V, long long nchains, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
         double *__restrict__ e_out,
-        int32_t *__restrict__ final_counter, ChainPend pend, int first_row, const Row0Part *__restrict__ row0, double c_rel)
+        int32_t *__restrict__ final_counter, ChainPend pend, int first_row, const Row0Part *__restrict__ row0, double c_rel,
+        int32_t *__restrict__ later)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
-    __shared__ LaterRow sh_later[kMaxLater];               // rows whose Eq. (hik) sum is taken again without cancellation, after the loop
-    __shared__ int sh_nlater;
-    __shared__ double sh_sumrow[2][3];                     // block ratio and log-normalisers of the row in sweep 2 (log2): written by
-                                                           // thread 0 when the row's statistics are known, in the buffer of the
-                                                           // iteration's parity, and read one iteration later
+    __shared__ double sh_sumrow[2][2];                     // log2 of the block ratio and of the drafts' joint probability in front
+                                                           // of the row in sweep 2: written by thread 0 when the row's statistics
+                                                           // are known, in the entry of the iteration's parity, read one iteration later
+    __shared__ int sh_nlater;                              // rows handed to k_chain_excess so far (thread 0 only)
     __shared__ PendTable sh_tab;                           // PEND only: levels that modify the current row
     __shared__ double sh_mu[kMaxPend];                     //            log2 block ratio of every level in front of the current row
     __shared__ int sh_cnt[kMaxPend];                       //            rows every level modifies (this prefix)
@@ -609,8 +656,8 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         if (threadIdx.x == 0) { sh_pend = pend; sh_sum_done = 0; }
         __syncthreads();
     }
-    if (threadIdx.x == 0) sh_nlater = 0;                   // (read again only after the barriers of the first row end)
 
+    if (threadIdx.x == 0) sh_nlater = 0;
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
     const unsigned tid = threadIdx.x;
@@ -639,6 +686,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     rc_sum.c = c; rc_sum.K = K; rc_sum.nref_q = rc_sum.nref_p = 0.0f; rc_sum.C2_hi = 0.0f; rc_sum.neg_kappa = -1.0f;
     double Zq_prev = 1.0;                                  // target normaliser of the row in sweep 2
     double log2nu = 0.0;                                   // block ratio of the rows before the row being loaded
+    double log2P = 0.0;                                    // joint draft probability of their tokens
 
     // Iteration g overlaps three things slot by slot: sweep 2 of row g-1 (its Eq. (hik) sum, unless it
     // is the first row of its chain), the load of row g into the slot that sweep 2 just released, and
@@ -646,18 +694,27 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     // the whole row period and the memory pipeline never drains between rows.
     // The drafted token's two logits (the reference exponents of a row's first sweep) are fetched one row ahead, as
     // loaded: the wait for them then falls at the end of the previous iteration, where no other load is in flight,
-    // and not behind the first LDS fills of their own row, which it would drain.
-    auto token_logits = [&](int gg, uint32_t &zq, uint32_t &zp) {
+    // and not behind the first LDS fills of their own row, which it would drain.  The fetch brings the whole 16-byte
+    // vector the token lies in, one element per lane: lanes 0 .. PV-1 of every wave the target row's, lanes
+    // PV .. 2PV-1 the draft row's (the lanes above repeat them).  That vector's weights are summed apart from the
+    // sweep (sweep1_vec's `leave_out`), the token's own in float64.
+    const unsigned lane = tid & (kWave - 1u);
+    const bool lane_p = (lane / PV) & 1u;                  // this lane's element of the token vector is the draft row's
+    auto token_vector = [&](int gg, uint32_t &bits, int &tok_out) {
         const int gc = gg < nrows ? gg : nrows - 1;        // keeps every address in bounds
         const long long bk = chain_of(gc);
         const int r = first_row + gc % rpc;
         int tok = tokens[bk * L + r];
         tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-        zq = Elem<T>::bits(target + (bk * (L + 1) + r) * static_cast<long long>(V) + tok);
-        zp = Elem<T>::bits(draft + (bk * L + r) * static_cast<long long>(V) + tok);
+        tok_out = tok;
+        const long long at = static_cast<long long>(tok / PV) * PV + (lane % PV);      // < V: V is a multiple of PV
+        const T *row = lane_p ? draft + (bk * L + r) * static_cast<long long>(V)
+                              : target + (bk * (L + 1) + r) * static_cast<long long>(V);
+        bits = Elem<T>::bits(row + at);
     };
-    uint32_t zq_tok_next = 0, zp_tok_next = 0;
-    if (nrows > 0) token_logits(0, zq_tok_next, zp_tok_next);
+    uint32_t tokvec_next = 0;
+    int tok_next = 0;
+    if (nrows > 0) token_vector(0, tokvec_next, tok_next);
     for (int g = 0; g <= nrows; ++g) {
         const bool do_new = g < nrows;                     // a row is being loaded and gets its statistics
         const int g_new = do_new ? g : nrows - 1;          // keeps every address in bounds
@@ -681,14 +738,26 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         // Reference exponents of the new row: its token's logits (the drafted token was
         // sampled from this draft row, so no entry can exceed it by a factor near 2^127
         // unless the row is extremely peaked; that case is caught below).
-        const float zq_tok = Elem<T>::from_bits(zq_tok_next), zp_tok = Elem<T>::from_bits(zp_tok_next);
-        if (do_new) token_logits(g + 1, zq_tok_next, zp_tok_next);   // (the last row's logits again after the last row)
+        const int tok_new = __builtin_amdgcn_readfirstlane(tok_next);
+        const uint32_t tokvec = tokvec_next;
+        const float zq_tok = Elem<T>::from_bits(__builtin_amdgcn_readlane(tokvec, tok_new % PV));
+        const float zp_tok = Elem<T>::from_bits(__builtin_amdgcn_readlane(tokvec, PV + tok_new % PV));
+        if (do_new) token_vector(g + 1, tokvec_next, tok_next);      // (the last row's again after the last row)
         RowConsts rc_new;
         rc_new.c = c; rc_new.K = K; rc_new.C2_hi = 0.0f; rc_new.neg_kappa = -1.0f;
         rc_new.nref_q = -(zq_tok * c); rc_new.nref_p = -(zp_tok * c);
+        // weights of the token's neighbours in its vector (every wave computes the same two sums)
+        float nb_q, nb_p;
+        {
+            const float w = exp2_fast(fmaf(Elem<T>::from_bits(tokvec), c, lane_p ? rc_new.nref_p : rc_new.nref_q));
+            const bool nb = lane < 2u * PV && lane % PV != static_cast<unsigned>(tok_new % PV);
+            nb_q = wave_sum_f32(nb && !lane_p ? w : 0.0f);
+            nb_p = wave_sum_f32(nb && lane_p ? w : 0.0f);
+        }
 
         float Zq = 0.0f, Zp = 0.0f, acc = 0.0f;
-        StepCtx<T> cx{qnew, pnew, rc_sum, rc_new, tid, off_new, nvec, rem, n_on, do_new, do_sum};
+        StepCtx<T> cx{qnew, pnew, rc_sum, rc_new, tid, off_new, nvec, rem, n_on, do_new, do_sum,
+                      (tok_new / PV) / kChainThreads, tid == static_cast<unsigned>((tok_new / PV) % kChainThreads)};
         run_steps<T, KP, RS>(std::make_integer_sequence<int, NS + kLag>{}, cx, rq, rp, lds, Zq, Zp, acc);
         // vectors that do not fit on chip: read for the statistics now, once more for the sum; the
         // loads of the next slot are issued before the arithmetic of the current one
@@ -707,40 +776,55 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
                 U4 a1, b1, c1, d1;
                 fetch(j + 1, a1, b1, c1, d1);
                 if (j * kChainThreads < rem) {
-                    if (do_new) sweep1_vec<T>(a0, b0, rc_new, Zq, Zp);
+                    if (do_new) sweep1_vec<T>(a0, b0, rc_new, Zq, Zp, j == cx.tok_slot, cx.tok_mine);
                     if (do_sum) sweep2_vec<T, KP>(c0, d0, rc_sum, acc);
                 }
                 a0 = a1; b0 = b1; c0 = c1; d0 = d1;
             }
         }
 
-        asm volatile("" : "+v"(zq_tok_next), "+v"(zp_tok_next));   // the next row's token logits have arrived by here
+        asm volatile("" : "+v"(tokvec_next));              // the next row's token vector has arrived by here
         double Zq_tot = static_cast<double>(Zq), Zp_tot = static_cast<double>(Zp), s_tot = static_cast<double>(acc);
         block_sum3(Zq_tot, Zp_tot, s_tot, sh_d);
         Zq_tot = uniform_d(Zq_tot); Zp_tot = uniform_d(Zp_tot); s_tot = uniform_d(s_tot);
+        // The token's own weight is 2^(what the rounding of its reference exponent to float32 left over), within
+        // 1e-5 of one: three terms of the exponential series, in float64.  The sums so far hold everything else, so
+        // a row whose mass sits on its drafted token keeps the rest to float32 RELATIVE accuracy.
+        {
+            const double xq = fma(static_cast<double>(zq_tok), static_cast<double>(c), static_cast<double>(rc_new.nref_q)) *
+                              0.69314718055994530942;
+            const double xp = fma(static_cast<double>(zp_tok), static_cast<double>(c), static_cast<double>(rc_new.nref_p)) *
+                              0.69314718055994530942;
+            Zq_tot += static_cast<double>(nb_q) + (1.0 + xq + 0.5 * xq * xq);
+            Zp_tot += static_cast<double>(nb_p) + (1.0 + xp + 0.5 * xp * xp);
+        }
         if (do_sum && tid == 0) {
             const double s_val = s_tot / Zq_prev;
             s_out[bk_old * L + r_old] = s_val;
-            e_out[bk_old * L + r_old] = -1.0;
             // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term (rare:
-            // peaked rows, large block ratios).  The row has left the chip by now; it is noted down and read again
-            // after the row loop, when the registers are free for a proper streaming loop.  (A list that is full
-            // leaves the plain sum in force.)
+            // peaked rows, large block ratios).  The row has left the chip by now, and one workgroup reading it again
+            // alone would hold up the whole grid for the time of a row: it is marked, and k_chain_excess, launched
+            // behind this kernel, spreads the marked rows over the chip.
+            // (A list that is full leaves the plain sum in force.)
+            bool again = false;
             if constexpr (!PEND) {
-                const double *row = sh_sumrow[(g - 1) & 1];
-                if (excess_wanted(static_cast<float>(row[0]), static_cast<float>(s_val), K) && sh_nlater < kMaxLater) {
-                    LaterRow lr;
-                    lr.bk = bk_old; lr.r = r_old; lr.pad = 0; lr.log2nu = row[0]; lr.lse2_q = row[1]; lr.lse2_p = row[2];
-                    sh_later[sh_nlater] = lr;
+                const double *front = sh_sumrow[(g - 1) & 1];
+                if (excess_wanted(static_cast<float>(front[0]), static_cast<float>(s_val), K) && sh_nlater < kMaxLater &&
+                    excess_needed(front[0], front[1], s_val, K)) {
+                    again = true;
                     sh_nlater = sh_nlater + 1;
+                    later[static_cast<size_t>(blockIdx.x) * kLaterStride + sh_nlater] = static_cast<int32_t>(bk_old * L + r_old);
                 }
             }
+            e_out[bk_old * L + r_old] = again ? kExcessPending : -1.0;
         }
         if (do_new) {
             if (r_new == first_row) {                      // a new chain starts from the empty block ...
-                log2nu = 0.0;
-                if (first_row)                             // ... or from its token at the shared position 0
-                    log2nu = uniform_d(row0_from_parts<T>(row0, target, draft, tokens, bk_new, K, L, V, c, c_rel, stats));
+                log2nu = 0.0; log2P = 0.0;
+                if (first_row) {                           // ... or from its token at the shared position 0
+                    log2nu = uniform_d(row0_from_parts<T>(row0, target, draft, tokens, bk_new, K, L, V, c, c_rel, stats, log2P));
+                    log2P = uniform_d(log2P);
+                }
             }
             float ref_q = -rc_new.nref_q, ref_p = -rc_new.nref_p;
             // A sum far above 1 means that the entries that matter lie far above the token's logit: their
@@ -821,20 +905,98 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             const double dk = (static_cast<double>(rc_sum.C2_hi) - C2) * 0.693147180559945309417;
             rc_sum.neg_kappa = (dk > -0.25 && dk < 0.25) ? -static_cast<float>(1.0 + dk + 0.5 * dk * dk) : -1.0f;
             Zq_prev = uniform_d(Zq_tot);
-            if (tid == 0) { sh_sumrow[g & 1][0] = log2nu; sh_sumrow[g & 1][1] = lse2_q; sh_sumrow[g & 1][2] = lse2_p; }
+            if (tid == 0) { sh_sumrow[g & 1][0] = log2nu; sh_sumrow[g & 1][1] = log2P; }
             log2nu = uniform_d(log2nu + ((tok2_q - lse2_q + tok_adj) - (tok2_p - lse2_p)));
+            log2P = uniform_d(log2P + (tok2_p - lse2_p));
         }
     }
-    if constexpr (!PEND) {
-        __syncthreads();
-        const int nlater = sh_nlater;
-        for (int j = 0; j < nlater; ++j) {                 // uniform
-            const LaterRow lr = sh_later[j];
-            const ExcessConst ec = make_excess_const(lr.lse2_q, lr.lse2_p, lr.log2nu, K, c);
-            const double E = excess_row<T>(target + (lr.bk * (L + 1) + lr.r) * static_cast<long long>(V),
-                                           draft + (lr.bk * L + lr.r) * static_cast<long long>(V), nvec, ec, sh_d);
-            if (tid == 0) e_out[lr.bk * L + lr.r] = E;
+    if constexpr (!PEND)
+        if (tid == 0) later[static_cast<size_t>(blockIdx.x) * kLaterStride] = sh_nlater;   // (every workgroup, also when it is 0)
+}
+
+// E = nu^2 (s - g) of the rows k_chain handed over, straight from memory, in kPendParts parts per row which the
+// decision kernel adds up in part order.  Every workgroup reads the lengths of all `nlists` lists (nearly always all
+// 0: it leaves at once), numbers the listed rows in list order and takes the units blockIdx.x, blockIdx.x +
+// gridDim.x, ... of (row, part), part fastest.  Every wave fetches the statistics of the row's chain itself, one row
+// per lane (L <= 62).
+template <typename T>
+__global__ void __launch_bounds__(kExcessThreads)
+k_chain_excess(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
+               const RowStat *__restrict__ stats, const int32_t *__restrict__ later, int nlists,
+               double *__restrict__ e_part)
+{
+    constexpr int kPer = kMaxChainGrid / kExcessThreads;   // lists per thread
+    __shared__ double sh_d[kExcessThreads / kWave];
+    __shared__ int sh_before[kMaxChainGrid + 1];           // rows in the lists before list w; entry nlists: all of them
+    __shared__ int sh_wave[kExcessThreads / kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wid = tid / kWave;
+    int cnt[kPer], mine = 0;
+#pragma unroll
+    for (int a = 0; a < kPer; ++a) {
+        const int w = tid * kPer + a;
+        const int n = w < nlists ? later[static_cast<size_t>(w) * kLaterStride] : 0;
+        cnt[a] = n < 0 ? 0 : (n > kMaxLater ? kMaxLater : n);
+        mine += cnt[a];
+    }
+    if (__syncthreads_or(mine) == 0) return;               // no row anywhere
+    int incl = mine;                                       // inclusive scan over the wave, then over the waves
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    if (lane == kWave - 1) sh_wave[wid] = incl;
+    __syncthreads();
+    int before = incl - mine;
+    for (int v = 0; v < wid; ++v) before += sh_wave[v];
+#pragma unroll
+    for (int a = 0; a < kPer; ++a) {
+        sh_before[tid * kPer + a] = before;
+        before += cnt[a];
+    }
+    if (tid == kExcessThreads - 1) sh_before[kMaxChainGrid] = before;
+    __syncthreads();
+    const int nrows = sh_before[kMaxChainGrid];
+    constexpr int PV = Elem<T>::kPerVec;
+    constexpr int kAhead = 4;                              // vector pairs in flight per thread
+    const int nvec = V / PV;
+    const int per = (nvec + kPendParts - 1) / kPendParts;
+    for (int u = blockIdx.x; u < nrows * kPendParts; u += gridDim.x) {      // uniform
+        const int r = u / kPendParts, part = u % kPendParts;
+        int w = 0;                                         // the list that holds row r: the last one with sh_before[w] <= r
+        for (int step = kMaxChainGrid / 2; step >= 1; step >>= 1)
+            if (w + step < kMaxChainGrid && sh_before[w + step] <= r) w += step;
+        const long long pair = later[static_cast<size_t>(w) * kLaterStride + 1 + (r - sh_before[w])];
+        const long long bk = pair / L;
+        const int i = static_cast<int>(pair % L);
+        const int lo = part * per, hi = lo + per < nvec ? lo + per : nvec;
+        const RowStat st = stats[bk * L + (lane < L ? lane : L - 1)];
+        const double ratio = (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);   // log2 of the row's token ratio
+        double log2nu = 0.0;                               // added up as k_chain does: the same bits
+        for (int j = 0; j < i; ++j) log2nu += lane_d(ratio, j);
+        const ExcessConst ec = make_excess_const(lane_d(st.lse2_q, i), lane_d(st.lse2_p, i), log2nu, K, c);
+        const T *qrow = target + (bk * (L + 1) + i) * static_cast<long long>(V);
+        const T *prow = draft + pair * static_cast<long long>(V);
+        float acc = 0.0f;
+        for (int v0 = lo + tid; v0 < hi; v0 += kAhead * kExcessThreads) {
+            U4 q[kAhead], pp[kAhead];
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                const int v = v0 + a * kExcessThreads;
+                q[a] = load16_stream(qrow + static_cast<long long>(v < hi ? v : v0) * PV);
+                pp[a] = load16_stream(prow + static_cast<long long>(v < hi ? v : v0) * PV);
+            }
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                float zq[PV], zp[PV];
+                Elem<T>::unpack(q[a], zq);
+                Elem<T>::unpack(pp[a], zp);
+                if (v0 + a * kExcessThreads < hi) acc += excess_terms(zq, zp, ec);
+            }
         }
+        // (a part without vectors, where the row has fewer of them than parts, adds 0)
+        const double e_val = block_sum(static_cast<double>(acc), sh_d) * ec.scale;
+        if (tid == 0) e_part[pair * kPendParts + part] = e_val;
     }
 }
 
@@ -847,6 +1009,7 @@ int resident_workgroups()
     if (cached[dev] == 0) {
         int n = 0;
         cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+        if (cached[dev] > kMaxChainGrid) cached[dev] = kMaxChainGrid;      // (the workspace holds that many row lists)
     }
     return cached[dev];
 }
@@ -871,16 +1034,21 @@ hipError_t launch_kp(const Problem &p)
     Row0Part *row0 = reinterpret_cast<Row0Part *>(p.ws + p.lay.row0);
     if (first_row)
         hipLaunchKernelGGL((k_row0_parts<T>), dim3(kRow0Parts, static_cast<unsigned>(p.batch), 2), dim3(kRow0Threads), 0,
-                           p.stream, target, draft, p.K, p.L, p.V, p.c, row0);
+                           p.stream, target, draft, p.tokens, p.K, p.L, p.V, p.c, row0);
 #define SPECGBV_LAUNCH(RS)                                                                                  \
     hipLaunchKernelGGL((k_chain<T, KP, RS, PEND>), grid, dim3(kChainThreads), 0, p.stream, target, draft,  \
                        p.tokens, p.K, p.L, p.V, nchains, p.c, stats, s,                                    \
                        reinterpret_cast<double *>(p.ws + p.lay.excess),                                    \
-                       reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend, first_row, row0, p.c_rel)
+                       reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend, first_row, row0, p.c_rel,     \
+                       reinterpret_cast<int32_t *>(p.ws + p.lay.later))
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);
 #undef SPECGBV_LAUNCH
+    if (!PEND)
+        hipLaunchKernelGGL((k_chain_excess<T>), dim3(static_cast<unsigned>(cus)), dim3(kExcessThreads), 0, p.stream, target,
+                           draft, p.K, p.L, p.V, p.c, stats, reinterpret_cast<const int32_t *>(p.ws + p.lay.later),
+                           static_cast<int>(grid.x), reinterpret_cast<double *>(p.ws + p.lay.excess_part));
     return hipGetLastError();
 }
 
@@ -901,6 +1069,9 @@ hipError_t launch_typed(const Problem &p)
 }
 
 }  // namespace
+
+// Parts k_chain_excess leaves the cancellation-free sum of a marked row in.
+int chain_excess_parts(const Problem &) { return kPendParts; }
 
 bool chain_supported(const Problem &p)
 {

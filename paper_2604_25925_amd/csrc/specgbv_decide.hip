@@ -99,6 +99,7 @@ struct DecideIO {
     const double *s_part;       // s_parts > 1: the sums arrive as s_parts partial sums per row ([n_rows][kPendParts])
     double *s_store;            //              and the complete ones are stored here by the writing workgroup
     int s_parts;
+    int e_parts;                // > 0: an entry kExcessPending of e_arr stands for the sum of the row's first e_parts parts
     double *log_nu_out, *log_P_out, *h_out, *eta_out;
     int32_t *state_out;
     int32_t *accepted_len, *accepted_draft_idx, *out_tokens;
@@ -156,6 +157,10 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
             } else {
                 s = s_arr[base + k * L + i];
                 e = io.e_arr[base + k * L + i];
+                if (io.e_parts > 0 && e == kExcessPending) {    // (in part order: the same bits in every workgroup)
+                    e = 0.0;
+                    for (int q = 0; q < io.e_parts; ++q) e += io.e_part[(base + k * L + i) * kPendParts + q];
+                }
             }
         }
         l2nu[idx] = s;
@@ -901,6 +906,7 @@ hipError_t launch_final_typed(const Problem &p)
     io.s_part = reinterpret_cast<const double *>(p.ws + p.lay.pend_part);
     io.s_store = reinterpret_cast<double *>(p.ws + p.lay.s);
     io.s_parts = p.s_parts;
+    io.e_parts = p.e_parts;
     io.log_nu_out = reinterpret_cast<double *>(p.ws + p.lay.log_nu);
     io.log_P_out = reinterpret_cast<double *>(p.ws + p.lay.log_P);
     io.h_out = reinterpret_cast<double *>(p.ws + p.lay.h);

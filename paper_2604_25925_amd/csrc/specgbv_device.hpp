@@ -32,6 +32,8 @@ struct RowStat {
 //   q^(l+1)[x] = q^(l)[x] t_l[x]^K / N_l,   t_l[x] = max(1 - p[x] / (mu_l q^(l)[x]), 0),   q^(0) = q,
 // for the first count_l rows of every draft.  Per (level, prefix, draft, row), in base-2 logarithms:
 constexpr int kMaxPend = 16;     // levels applied on the fly at most
+constexpr double kExcessPending = -2.0;   // in the array of E = nu^2 (s - g): the row's sum is on its way, in parts (chain schedule)
+constexpr int kMaxDrafts = 64;   // K at most (one lane of a wave per draft where the drafts of a prefix are compared)
 struct PendRow {
     double log2mu;   // block ratio mu_l in front of this row (carried ratio continued along the drafted tokens with q^(l))
     double log2N;    // log2 of N_l = sum_x q^(l)[x] t_l[x]^K (0 when the level does not modify the row)
@@ -484,6 +486,29 @@ struct RunningSum {
         m2 = n2;
     }
 };
+
+// The drafted token is left out of a row's float32 sums: `here` says that the vector z holds it, as entry `elem`, and
+// its weight becomes 2^(-inf) = 0.  Its weight is added in float64 where the row's partial sums meet (with_token).
+// A row whose mass sits on its drafted token (probability 0.9999 and beyond: low temperatures) then keeps the mass of
+// all the OTHER entries to float32 relative accuracy, and 1 - P, 1 - Q and the factor's distance from one in
+// Eq. (hik) are made of exactly that; summed together with a weight near one it would be known to 6e-8 absolute.
+template <int N>
+__device__ __forceinline__ void leave_out(float (&z)[N], bool here, int elem)
+{
+#pragma unroll
+    for (int j = 0; j < N; ++j) z[j] = (here && j == elem) ? -__builtin_inff() : z[j];
+}
+
+// Z 2^M + 2^t as Z' 2^ref: a sum of weights relative to 2^M (M finite) and one more entry with scaled logit t
+// (t = -inf: a masked entry, weight 0).
+struct RefSum { double ref, Z; };
+__device__ __forceinline__ RefSum with_token(double M, double Z, double t)
+{
+    RefSum r;
+    r.ref = fmax(M, t);
+    r.Z = (Z > 0.0 ? Z * exp2(M - r.ref) : 0.0) + exp2(t - r.ref);
+    return r;
+}
 
 // Integral reference exponent of a group of entries whose largest logit is m (partial sums taken relative to
 // integral references rescale exactly).  A group without a finite entry (m = -3e38 or -inf: every entry

@@ -88,17 +88,22 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
     const T *row = is_draft ? draft + (bk * L + r) * static_cast<long long>(V)
                             : target + (bk * (L + 1) + r) * static_cast<long long>(V);
     constexpr int PV = Elem<T>::kPerVec;
-    RunningSum acc;
+    int tok = tokens[pair];
+    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    RunningSum acc;                               // the drafted token is left out (leave_out)
     if (VEC) {
         const int nvec = V / PV;
+        const int tok_vec = tok / PV, tok_elem = tok % PV;
         for (int i = threadIdx.x; i < nvec; i += kStatThreads) {
             float z[PV];
             Elem<T>::unpack(load16_stream(row + static_cast<long long>(i) * PV), z);
+            leave_out(z, i == tok_vec, tok_elem);
             acc.add(z, c);
         }
     } else {
         for (int x = threadIdx.x; x < V; x += kStatThreads) {
-            const float z[1] = {Elem<T>::scalar(row + x)};
+            float z[1] = {Elem<T>::scalar(row + x)};
+            leave_out(z, x == tok, 0);
             acc.add(z, c);
         }
     }
@@ -106,10 +111,10 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
     const double part = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));
     const double total = block_sum(acc.Z > 0.0f ? part : 0.0, sh_d);
     if (threadIdx.x == 0) {
-        const double lse2 = static_cast<double>(M) + log2(total);
-        int tok = tokens[pair];
-        tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-        const double tok2 = token_scaled(static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c), lse2, c_rel);
+        const double tok2_raw = static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c);
+        const RefSum all = with_token(static_cast<double>(M), total, tok2_raw);
+        const double lse2 = all.ref + log2(all.Z);
+        const double tok2 = token_scaled(tok2_raw, lse2, c_rel);
         if (is_draft) { stats[pair].lse2_p = lse2; stats[pair].tok2_p = tok2; }
         else { stats[pair].lse2_q = lse2; stats[pair].tok2_q = tok2; }
     }
@@ -126,8 +131,8 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
 // grid (row pairs * P, 2): block (pair * P + part, 0 / 1) reduces part `part` of the target / draft row of the pair
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kStatThreads)
-k_row_stats_parts(const T *__restrict__ target, const T *__restrict__ draft, int L, int V, float c, int P,
-                  Row0Part *__restrict__ parts)
+k_row_stats_parts(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int L,
+                  int V, float c, int P, Row0Part *__restrict__ parts)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ float sh_f[kStatThreads / kWave];
@@ -142,24 +147,29 @@ k_row_stats_parts(const T *__restrict__ target, const T *__restrict__ draft, int
     const int units = VEC ? V / PV : V;
     const int per = (units + P - 1) / P;
     const int lo = part * per, hi = lo + per < units ? lo + per : units;
-    RunningSum acc;
+    int tok = tokens[pair];
+    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    const int tok_unit = VEC ? tok / PV : tok, tok_elem = VEC ? tok % PV : 0;
+    RunningSum acc;                               // the drafted token is left out (leave_out)
     if (VEC) {
         int i = lo + static_cast<int>(threadIdx.x);
         for (; i + kStatThreads < hi; i += 2 * kStatThreads) {            // two loads in flight per thread
             const U4 a = load16_stream(row + static_cast<long long>(i) * PV);
             const U4 b2 = load16_stream(row + static_cast<long long>(i + kStatThreads) * PV);
             float z[PV];
-            Elem<T>::unpack(a, z); acc.add(z, c);
-            Elem<T>::unpack(b2, z); acc.add(z, c);
+            Elem<T>::unpack(a, z); leave_out(z, i == tok_unit, tok_elem); acc.add(z, c);
+            Elem<T>::unpack(b2, z); leave_out(z, i + kStatThreads == tok_unit, tok_elem); acc.add(z, c);
         }
         if (i < hi) {
             float z[PV];
             Elem<T>::unpack(load16_stream(row + static_cast<long long>(i) * PV), z);
+            leave_out(z, i == tok_unit, tok_elem);
             acc.add(z, c);
         }
     } else {
         for (int x = lo + static_cast<int>(threadIdx.x); x < hi; x += kStatThreads) {
-            const float z[1] = {Elem<T>::scalar(row + x)};
+            float z[1] = {Elem<T>::scalar(row + x)};
+            leave_out(z, x == tok, 0);
             acc.add(z, c);
         }
     }
@@ -167,9 +177,14 @@ k_row_stats_parts(const T *__restrict__ target, const T *__restrict__ draft, int
     const double mine = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));
     const double total = block_sum(acc.Z > 0.0f ? mine : 0.0, sh_d);
     if (threadIdx.x == 0) {
+        // the part that holds the drafted token adds its weight here, in float64
+        const bool mine_tok = tok_unit >= lo && tok_unit < hi;
+        const double tok2_raw = mine_tok ? static_cast<double>(Elem<T>::scalar(row + tok)) * static_cast<double>(c)
+                                         : -static_cast<double>(__builtin_inff());
+        const RefSum all = with_token(static_cast<double>(M), total, tok2_raw);
         Row0Part out;
-        out.ref = floor(static_cast<double>(M));
-        out.Z = total * exp2(static_cast<double>(M) - out.ref);
+        out.ref = floor(all.ref);
+        out.Z = all.Z * exp2(all.ref - out.ref);
         parts[(pair * 2 + (is_draft ? 1 : 0)) * kRowParts + part] = out;
     }
 }
@@ -557,11 +572,11 @@ hipError_t launch_typed(const Problem &p)
     if (stat_parts > 1) {
         const dim3 gs(static_cast<unsigned>(pairs * stat_parts), 2);
         if (vec)
-            hipLaunchKernelGGL((k_row_stats_parts<T, true>), gs, dim3(kStatThreads), 0, p.stream, target, draft, p.L, p.V,
-                               p.c, stat_parts, stat_part);
+            hipLaunchKernelGGL((k_row_stats_parts<T, true>), gs, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens,
+                               p.L, p.V, p.c, stat_parts, stat_part);
         else
-            hipLaunchKernelGGL((k_row_stats_parts<T, false>), gs, dim3(kStatThreads), 0, p.stream, target, draft, p.L, p.V,
-                               p.c, stat_parts, stat_part);
+            hipLaunchKernelGGL((k_row_stats_parts<T, false>), gs, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens,
+                               p.L, p.V, p.c, stat_parts, stat_part);
     } else {
         const dim3 g1(static_cast<unsigned>(pairs + p.pend_levels), 2);
         if (vec)
