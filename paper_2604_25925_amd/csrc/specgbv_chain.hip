@@ -275,9 +275,11 @@ __device__ __noinline__ bool excess_needed(double log2nu, double log2P, double s
 }
 
 // Rows a workgroup of k_chain hands to k_chain_excess: entry 0 of its list is their number, then their row indices.
-constexpr int kMaxLater = 63;
-constexpr int kLaterStride = kMaxLater + 1;
-static_assert(kLaterStride == 64, "the workspace holds 64 entries per list");
+// A list has room for every row the workgroup sums.
+inline int later_list_entries(long long nchains, long long grid, int L)
+{
+    return 1 + static_cast<int>((nchains + grid - 1) / grid) * (L > 1 ? L - 1 : 0);
+}
 
 constexpr int kLag = 6;    // slots between the load of a vector and its first use
 constexpr double kTokenRefLimit = 1073741824.0;   // 2^30: largest row sum accepted relative to the drafted token's weight
@@ -638,7 +640,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         int K, int L, int V, long long nchains, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
         double *__restrict__ e_out,
         int32_t *__restrict__ final_counter, ChainPend pend, int first_row, const Row0Part *__restrict__ row0, double c_rel,
-        int32_t *__restrict__ later)
+        int32_t *__restrict__ later, int later_stride)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
@@ -805,15 +807,14 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             // peaked rows, large block ratios).  The row has left the chip by now, and one workgroup reading it again
             // alone would hold up the whole grid for the time of a row: it is marked, and k_chain_excess, launched
             // behind this kernel, spreads the marked rows over the chip.
-            // (A list that is full leaves the plain sum in force.)
             bool again = false;
             if constexpr (!PEND) {
                 const double *front = sh_sumrow[(g - 1) & 1];
-                if (excess_wanted(static_cast<float>(front[0]), static_cast<float>(s_val), K) && sh_nlater < kMaxLater &&
+                if (excess_wanted(static_cast<float>(front[0]), static_cast<float>(s_val), K) && sh_nlater + 1 < later_stride &&
                     excess_needed(front[0], front[1], s_val, K)) {
                     again = true;
                     sh_nlater = sh_nlater + 1;
-                    later[static_cast<size_t>(blockIdx.x) * kLaterStride + sh_nlater] = static_cast<int32_t>(bk_old * L + r_old);
+                    later[static_cast<size_t>(blockIdx.x) * later_stride + sh_nlater] = static_cast<int32_t>(bk_old * L + r_old);
                 }
             }
             e_out[bk_old * L + r_old] = again ? kExcessPending : -1.0;
@@ -911,7 +912,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         }
     }
     if constexpr (!PEND)
-        if (tid == 0) later[static_cast<size_t>(blockIdx.x) * kLaterStride] = sh_nlater;   // (every workgroup, also when it is 0)
+        if (tid == 0) later[static_cast<size_t>(blockIdx.x) * later_stride] = sh_nlater;   // (every workgroup, also when it is 0)
 }
 
 // E = nu^2 (s - g) of the rows k_chain handed over, straight from memory, in kPendParts parts per row which the
@@ -922,7 +923,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
 template <typename T>
 __global__ void __launch_bounds__(kExcessThreads)
 k_chain_excess(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
-               const RowStat *__restrict__ stats, const int32_t *__restrict__ later, int nlists,
+               const RowStat *__restrict__ stats, const int32_t *__restrict__ later, int nlists, int later_stride,
                double *__restrict__ e_part)
 {
     constexpr int kPer = kMaxChainGrid / kExcessThreads;   // lists per thread
@@ -934,8 +935,8 @@ k_chain_excess(const T *__restrict__ target, const T *__restrict__ draft, int K,
 #pragma unroll
     for (int a = 0; a < kPer; ++a) {
         const int w = tid * kPer + a;
-        const int n = w < nlists ? later[static_cast<size_t>(w) * kLaterStride] : 0;
-        cnt[a] = n < 0 ? 0 : (n > kMaxLater ? kMaxLater : n);
+        const int n = w < nlists ? later[static_cast<size_t>(w) * later_stride] : 0;
+        cnt[a] = n < 0 ? 0 : (n > later_stride - 1 ? later_stride - 1 : n);
         mine += cnt[a];
     }
     if (__syncthreads_or(mine) == 0) return;               // no row anywhere
@@ -961,12 +962,12 @@ k_chain_excess(const T *__restrict__ target, const T *__restrict__ draft, int K,
     constexpr int kAhead = 4;                              // vector pairs in flight per thread
     const int nvec = V / PV;
     const int per = (nvec + kPendParts - 1) / kPendParts;
-    for (int u = blockIdx.x; u < nrows * kPendParts; u += gridDim.x) {      // uniform
-        const int r = u / kPendParts, part = u % kPendParts;
+    for (long long u = blockIdx.x; u < static_cast<long long>(nrows) * kPendParts; u += gridDim.x) {      // uniform
+        const int r = static_cast<int>(u / kPendParts), part = static_cast<int>(u % kPendParts);
         int w = 0;                                         // the list that holds row r: the last one with sh_before[w] <= r
         for (int step = kMaxChainGrid / 2; step >= 1; step >>= 1)
             if (w + step < kMaxChainGrid && sh_before[w + step] <= r) w += step;
-        const long long pair = later[static_cast<size_t>(w) * kLaterStride + 1 + (r - sh_before[w])];
+        const long long pair = later[static_cast<size_t>(w) * later_stride + 1 + (r - sh_before[w])];
         const long long bk = pair / L;
         const int i = static_cast<int>(pair % L);
         const int lo = part * per, hi = lo + per < nvec ? lo + per : nvec;
@@ -1022,6 +1023,7 @@ hipError_t launch_kp(const Problem &p)
     const long long nchains = static_cast<long long>(p.batch) * p.K;
     const long long cus = resident_workgroups();
     const dim3 grid(static_cast<unsigned>(nchains < cus ? nchains : cus));
+    const int stride = later_list_entries(nchains, grid.x, p.L);
     const T *target = static_cast<const T *>(p.target);
     const T *draft = static_cast<const T *>(p.draft);
     const int full_slots = (p.V / Elem<T>::kPerVec) / kChainThreads;
@@ -1040,7 +1042,7 @@ hipError_t launch_kp(const Problem &p)
                        p.tokens, p.K, p.L, p.V, nchains, p.c, stats, s,                                    \
                        reinterpret_cast<double *>(p.ws + p.lay.excess),                                    \
                        reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend, first_row, row0, p.c_rel,     \
-                       reinterpret_cast<int32_t *>(p.ws + p.lay.later))
+                       reinterpret_cast<int32_t *>(p.ws + p.lay.later), stride)
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);
@@ -1048,7 +1050,7 @@ hipError_t launch_kp(const Problem &p)
     if (!PEND)
         hipLaunchKernelGGL((k_chain_excess<T>), dim3(static_cast<unsigned>(cus)), dim3(kExcessThreads), 0, p.stream, target,
                            draft, p.K, p.L, p.V, p.c, stats, reinterpret_cast<const int32_t *>(p.ws + p.lay.later),
-                           static_cast<int>(grid.x), reinterpret_cast<double *>(p.ws + p.lay.excess_part));
+                           static_cast<int>(grid.x), stride, reinterpret_cast<double *>(p.ws + p.lay.excess_part));
     return hipGetLastError();
 }
 

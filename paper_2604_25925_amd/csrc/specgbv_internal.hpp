@@ -36,8 +36,8 @@ struct Workspace {
     size_t pend_cnt;   // int32  [B*K*L]  workgroups of a shared row that have stored their partial normaliser
     size_t stat_part;  // Row0Part [B*K*L][2][kRowParts]  partial row statistics (two-pass schedule, small batches)
     size_t row0;       // Row0Part [B][2][kRow0Parts]  partial statistics of the rows 0 a prefix's drafts share (chain schedule)
-    size_t later;      // int32 [kMaxChainGrid][64]  chain schedule: per workgroup, the number of rows whose Eq. (hik) sum is
-                       //             taken again without cancellation, then their row indices
+    size_t later;      // int32 [workgroups][1 + rows a workgroup sums]  chain schedule: per workgroup, the number of rows
+                       //             whose Eq. (hik) sum is taken again without cancellation, then their row indices
     size_t kseq_pos;   // int32 [2][B*L]  comparison verifier: drafts retained at each position, and the lowest of them
     size_t total;
     int nseg;

@@ -1,0 +1,93 @@
+"""Rows at the two ends where float32 sums are at their weakest, against the oracle (needs an MI355X: -m gpu).
+
+Near-certain tokens.  A drafted token of probability 1 - eps leaves 1 - P and 1 - Q in Eq. (hik) made of the mass
+of all the OTHER entries; a normaliser summed in float32 together with the token's weight (which is one) knows that
+mass to 6e-8 absolute, i.e. not at all for eps = 1e-6.  The kernels therefore leave the drafted token out of the
+float32 sums and add its weight in float64; these cases fail by factors of 10 - 1000 without that.  Every schedule
+that computes row statistics is covered: on-chip chains, the two-pass schedule, rows shared among workgroups
+(small batches) and the shared rows 0.
+
+Runaway block ratios.  A target far surer of the drafted tokens than the draft makes nu grow by orders of magnitude
+per position; s and g = (1 - 1/nu)^K then agree to many digits and Eq. (hik) needs nu^2 (s - g) summed term by term.
+On the chain schedule those rows go to a follow-up kernel: chains with every row handed over, and workgroups that
+hand over more rows than one chain has.
+"""
+import numpy as np
+import pytest
+
+from parity_util import check_case
+from specgbv_synth import Workload, f32_to_bf16_bits, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _set_probability(row, x, T, prob):
+    """Moves logit x of a float32 row so that softmax(row / T)[x] = prob."""
+    others = np.delete(row.astype(np.float64), x) / T
+    m = others.max()
+    lse = m + np.log(np.exp(others - m).sum())
+    row[x] = np.float32(T * (lse + np.log(prob / (1.0 - prob))))
+
+
+def _case(B, K, L, V, T, seed):
+    w = Workload("peaked", B, K, L, V, "f32", 2.5, 0.8, head=0, temperature=T)
+    return make_inputs(w, seed=seed)
+
+
+EPS = [(1e-4, 1e-4), (1e-5, 1e-3), (1e-3, 1e-6), (1e-6, 1e-6), (3e-5, 1e-5)]       # (1 - Q, 1 - P) of the drafted token
+
+
+@pytest.mark.parametrize("algo,dtype,V,B,shared", [
+    ("chain", "bf16", 32768, 3, False), ("chain", "f32", 14336, 3, False), ("chain", "bf16", 40960, 3, True),
+    ("split", "f32", 3001, 3, False), ("split", "bf16", 32768, 40, False), ("split", "f32", 16384, 1, False),
+    ("auto", "bf16", 32768, 2, True)])
+@pytest.mark.parametrize("T", [1.0, 0.4])
+def test_near_certain_drafted_tokens(algo, dtype, V, B, shared, T):
+    K, L = 4, 4
+    t, d, tok = _case(B, K, L, V, T, seed=31)
+    rng = np.random.default_rng(32)
+    for b in range(B):
+        eq, ep = EPS[b % len(EPS)]
+        # position 0: the rows 0 of a prefix's drafts are copies of one another, and stay so
+        x0 = int(tok[b, 0, 0])
+        _set_probability(t[b, 0, 0], x0, T, 1.0 - eq)
+        _set_probability(d[b, 0, 0], x0, T, 1.0 - ep)
+        for k in range(K):
+            t[b, k, 0], d[b, k, 0] = t[b, 0, 0], d[b, 0, 0]
+            tok[b, k, 0] = x0 if k != 2 else int(rng.integers(0, V))     # one draft starts with an unlikely token
+            for r in range(1, L):                                       # deeper positions: draft k keeps its tokens near-certain
+                if k % 2 == 0:
+                    _set_probability(t[b, k, r], int(tok[b, k, r]), T, 1.0 - eq * (r + 1))
+                    _set_probability(d[b, k, r], int(tok[b, k, r]), T, 1.0 - ep / (r + 1))
+    if dtype == "bf16":
+        t, d = f32_to_bf16_bits(t), f32_to_bf16_bits(d)
+    for off in (0, 1):
+        check_case(t, d, tok, T, 5, off, algo, "near-certain %s %s V=%d B=%d T=%g sh%d" % (algo, dtype, V, B, T, shared),
+                   shared_row0=shared)
+
+
+@pytest.mark.parametrize("dtype,V,B,K,L", [("bf16", 32768, 2, 4, 8), ("f32", 14336, 3, 3, 6), ("bf16", 28672, 90, 8, 4)])
+def test_block_ratio_runs_away_on_the_chain_schedule(dtype, V, B, K, L):
+    """q(token) = 0.9 against p(token) = 1e-3 at every position: nu gains a factor 900 per row and every sum of
+    Eq. (hik) from the second row on cancels against g.  B * K = 720 chains on 256 compute units: a workgroup then
+    hands over the rows of several chains."""
+    T = 1.0
+    t, d, tok = _case(B, K, L, V, T, seed=41)
+    for b in range(B):
+        for k in range(K):
+            if (b + k) % 3 == 2:
+                continue                                               # every third chain stays ordinary
+            for r in range(L):
+                x = int(tok[b, k, r])
+                _set_probability(t[b, k, r], x, T, 0.9)
+                _set_probability(d[b, k, r], x, T, 1.0e-3)
+    if dtype == "bf16":
+        t, d = f32_to_bf16_bits(t), f32_to_bf16_bits(d)
+    kw = {}
+    if B > 8:                                                          # the oracle takes a sample of the prefixes
+        kw["gpu_slice"] = list(range(0, B, 11))
+    rep, gpu, ora = check_case(t, d, tok, T, 9, 0, "chain", "runaway nu %s V=%d B=%d" % (dtype, V, B), **kw)
+    s, g_ = ora["s"][:, :, 1:], None
+    nu = np.exp(np.clip(ora["log_nu"][:, :, :L - 1], -700, 700))
+    g_ = np.where(nu > 1, (1 - 1 / np.maximum(nu, 1)) ** K, 0.0)
+    assert int(((nu > 1) & ((s - g_) * 16 < s)).sum()) >= s.size // 3, "the case no longer cancels"
