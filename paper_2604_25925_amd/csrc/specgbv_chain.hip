@@ -479,6 +479,17 @@ k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, const in
     const int nvec = V / PV;
     const int per = (nvec + kRow0Parts - 1) / kRow0Parts;
     const int lo = part * per, hi = lo + per < nvec ? lo + per : nvec;
+    // four loads in flight per thread; the first four are issued before the list of tokens is made
+    auto load4 = [&](int i, U4 (&v)[4]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int idx = i + j * kRow0Threads;
+            v[j] = load16_stream(row + static_cast<long long>(idx < hi ? idx : i) * PV);
+        }
+    };
+    U4 v[4];
+    int i = lo + static_cast<int>(threadIdx.x);
+    if (i < hi) load4(i, v);
     double tok2_mine = -static_cast<double>(__builtin_inff());     // first wave: scaled logit of the lane's token, if it is listed
     if (threadIdx.x < kWave) {
         const int j = threadIdx.x;
@@ -505,13 +516,7 @@ k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, const in
         }
     };
     RunningSum acc;
-    for (int i = lo + static_cast<int>(threadIdx.x); i < hi; i += 4 * kRow0Threads) {     // four loads in flight per thread
-        U4 v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int idx = i + j * kRow0Threads;
-            v[j] = load16_stream(row + static_cast<long long>(idx < hi ? idx : i) * PV);
-        }
+    while (i < hi) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (i + j * kRow0Threads < hi) {
@@ -521,6 +526,8 @@ k_row0_parts(const T *__restrict__ target, const T *__restrict__ draft, const in
                 acc.add(z, c);
             }
         }
+        i += 4 * kRow0Threads;
+        if (i < hi) load4(i, v);
     }
     const float M = block_max(acc.m2, sh_f);
     const double mine = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));

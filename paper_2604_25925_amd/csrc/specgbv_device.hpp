@@ -495,8 +495,28 @@ struct RunningSum {
 template <int N>
 __device__ __forceinline__ void leave_out(float (&z)[N], bool here, int elem)
 {
+    if (here) {
+        asm volatile("");                       // (keeps this a branch that all other waves skip)
 #pragma unroll
-    for (int j = 0; j < N; ++j) z[j] = (here && j == elem) ? -__builtin_inff() : z[j];
+        for (int j = 0; j < N; ++j) z[j] = j == elem ? -__builtin_inff() : z[j];
+    }
+}
+
+// The drafted token's index for leave_out, fetched by a vector load from an address the compiler cannot see is
+// uniform: it then queues with the row's loads.  (A scalar load is waited for where its result is first needed,
+// and everything derived from a loop-invariant index is needed before the loop: one memory latency in front of the
+// first row load, on kernels that consist of two or three such latencies when the batch is small.)
+__device__ __forceinline__ int token_index_queued(const int32_t *tokens, long long at)
+{
+    int zero = 0;
+    asm volatile("" : "+v"(zero));
+    return tokens[at + zero];
+}
+// ... and clamped to the vocabulary where it is used; opaque, so that the use stays behind the loads issued before it.
+__device__ __forceinline__ int token_index_used(int raw, int V)
+{
+    asm volatile("" : "+v"(raw));
+    return raw < 0 ? 0 : (raw >= V ? V - 1 : raw);
 }
 
 // Z 2^M + 2^t as Z' 2^ref: a sum of weights relative to 2^M (M finite) and one more entry with scaled logit t

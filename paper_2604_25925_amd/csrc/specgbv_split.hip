@@ -88,25 +88,26 @@ k_row_stats(const T *__restrict__ target, const T *__restrict__ draft,
     const T *row = is_draft ? draft + (bk * L + r) * static_cast<long long>(V)
                             : target + (bk * (L + 1) + r) * static_cast<long long>(V);
     constexpr int PV = Elem<T>::kPerVec;
-    int tok = tokens[pair];
-    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    const int tok_raw = token_index_queued(tokens, pair);
     RunningSum acc;                               // the drafted token is left out (leave_out)
     if (VEC) {
         const int nvec = V / PV;
-        const int tok_vec = tok / PV, tok_elem = tok % PV;
         for (int i = threadIdx.x; i < nvec; i += kStatThreads) {
+            const U4 v = load16_stream(row + static_cast<long long>(i) * PV);
+            const int tok = token_index_used(tok_raw, V);
             float z[PV];
-            Elem<T>::unpack(load16_stream(row + static_cast<long long>(i) * PV), z);
-            leave_out(z, i == tok_vec, tok_elem);
+            Elem<T>::unpack(v, z);
+            leave_out(z, i == tok / PV, tok % PV);
             acc.add(z, c);
         }
     } else {
         for (int x = threadIdx.x; x < V; x += kStatThreads) {
             float z[1] = {Elem<T>::scalar(row + x)};
-            leave_out(z, x == tok, 0);
+            leave_out(z, x == token_index_used(tok_raw, V), 0);
             acc.add(z, c);
         }
     }
+    const int tok = token_index_used(tok_raw, V);
     const float M = block_max(acc.m2, sh_f);
     const double part = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));
     const double total = block_sum(acc.Z > 0.0f ? part : 0.0, sh_d);
@@ -147,32 +148,35 @@ k_row_stats_parts(const T *__restrict__ target, const T *__restrict__ draft, con
     const int units = VEC ? V / PV : V;
     const int per = (units + P - 1) / P;
     const int lo = part * per, hi = lo + per < units ? lo + per : units;
-    int tok = tokens[pair];
-    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
-    const int tok_unit = VEC ? tok / PV : tok, tok_elem = VEC ? tok % PV : 0;
+    const int tok_raw = token_index_queued(tokens, pair);
     RunningSum acc;                               // the drafted token is left out (leave_out)
     if (VEC) {
         int i = lo + static_cast<int>(threadIdx.x);
         for (; i + kStatThreads < hi; i += 2 * kStatThreads) {            // two loads in flight per thread
             const U4 a = load16_stream(row + static_cast<long long>(i) * PV);
             const U4 b2 = load16_stream(row + static_cast<long long>(i + kStatThreads) * PV);
+            const int tk = token_index_used(tok_raw, V);
             float z[PV];
-            Elem<T>::unpack(a, z); leave_out(z, i == tok_unit, tok_elem); acc.add(z, c);
-            Elem<T>::unpack(b2, z); leave_out(z, i + kStatThreads == tok_unit, tok_elem); acc.add(z, c);
+            Elem<T>::unpack(a, z); leave_out(z, i == tk / PV, tk % PV); acc.add(z, c);
+            Elem<T>::unpack(b2, z); leave_out(z, i + kStatThreads == tk / PV, tk % PV); acc.add(z, c);
         }
         if (i < hi) {
+            const U4 a = load16_stream(row + static_cast<long long>(i) * PV);
+            const int tk = token_index_used(tok_raw, V);
             float z[PV];
-            Elem<T>::unpack(load16_stream(row + static_cast<long long>(i) * PV), z);
-            leave_out(z, i == tok_unit, tok_elem);
+            Elem<T>::unpack(a, z);
+            leave_out(z, i == tk / PV, tk % PV);
             acc.add(z, c);
         }
     } else {
         for (int x = lo + static_cast<int>(threadIdx.x); x < hi; x += kStatThreads) {
             float z[1] = {Elem<T>::scalar(row + x)};
-            leave_out(z, x == tok, 0);
+            leave_out(z, x == token_index_used(tok_raw, V), 0);
             acc.add(z, c);
         }
     }
+    const int tok = token_index_used(tok_raw, V);
+    const int tok_unit = VEC ? tok / PV : tok;
     const float M = block_max(acc.m2, sh_f);
     const double mine = static_cast<double>(acc.Z) * exp2(static_cast<double>(acc.m2) - static_cast<double>(M));
     const double total = block_sum(acc.Z > 0.0f ? mine : 0.0, sh_d);
