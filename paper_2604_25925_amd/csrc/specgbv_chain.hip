@@ -252,26 +252,11 @@ __device__ __noinline__ ExactStats exact_row_stats(const T *row, int nvec, float
 
 constexpr int kExcessThreads = 256;
 
-// Does the acceptance probability of a row whose s and g nearly cancel (excess_wanted) need the sum E at all?
-// With h = E / (E + D), D = (1 - Q) S2 / nu (the decision kernel's form of Eq. (hik) for a block ratio above one), a
-// relative error on E = nu (s - g) reaches h reduced by the factor 1 - h = D / (D + E): a block that is accepted
-// almost surely does not care how well s - g is known.  The test of excess_wanted, sharpened by that factor, which
-// is itself taken at the low end of what the plain s allows for s - g (1e-6 s below it; not above 0: needed).
-// (A function of its own, called by one thread for the few rows that pass the first test: its float64 registers
-// would otherwise be taken from the ones that hold the row pair.)
-__device__ __noinline__ bool excess_needed(double log2nu, double log2P, double s, int K)
+// excess_needed as a function of its own: called by one thread for the few rows that pass excess_wanted, its float64
+// registers would otherwise be taken from the ones that hold the row pair.
+__device__ __noinline__ bool excess_needed_call(double log2nu, double log2P, double s, int K)
 {
-    const double inv_nu = exp2_small(-log2nu), P = exp2_small(log2P);
-    const double t1 = 1.0 - inv_nu, A = 1.0 - P;
-    double g = 1.0;
-    for (int j = 0; j < K; ++j) g *= t1;
-    double U = 1.0, S2 = 0.0, pw = 1.0;
-    for (int j = 1; j <= K - 1; ++j) { S2 += U; pw *= t1; U = fma(A, U, pw); }
-    const double one_Q = fmax(1.0 - exp2_small(log2nu + log2P), 0.0);
-    const double D = inv_nu * one_Q * S2;
-    const double x = (s - g) - 1.0e-6 * s;
-    if (!(x > 0.0)) return true;
-    return x * 16.0 * (D + x / inv_nu) < s * D;
+    return excess_needed(log2nu, log2P, s, K);
 }
 
 // Rows a workgroup of k_chain hands to k_chain_excess: entry 0 of its list is their number, then their row indices.
@@ -818,7 +803,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             if constexpr (!PEND) {
                 const double *front = sh_sumrow[(g - 1) & 1];
                 if (excess_wanted(static_cast<float>(front[0]), static_cast<float>(s_val), K) && sh_nlater + 1 < later_stride &&
-                    excess_needed(front[0], front[1], s_val, K)) {
+                    excess_needed_call(front[0], front[1], s_val, K)) {
                     again = true;
                     sh_nlater = sh_nlater + 1;
                     later[static_cast<size_t>(blockIdx.x) * later_stride + sh_nlater] = static_cast<int32_t>(bk_old * L + r_old);

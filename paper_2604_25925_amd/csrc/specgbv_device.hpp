@@ -389,6 +389,28 @@ __device__ __forceinline__ bool excess_wanted(float l, float sf, int K)
     return (sf - g) * 16.0f < sf;
 }
 
+// Does the acceptance probability of a row whose s and g nearly cancel (excess_wanted) need the sum E at all?
+// With h = E / (E + D), D = (1 - Q) S2 / nu (the decision kernel's form of Eq. (hik) for a block ratio above one), a
+// relative error on E = nu (s - g) reaches h reduced by the factor 1 - h = D / (D + E): a block that is accepted
+// almost surely does not care how well s - g is known.  The test of excess_wanted, sharpened by that factor, which
+// is itself taken at the low end of what the plain s allows for s - g (1e-6 s below it; not above 0: needed).
+// log2P: log2 of the joint draft probability of the block's tokens.
+__device__ __forceinline__ bool excess_needed(double log2nu, double log2P, double s, int K)
+{
+    if (K == 1) return false;                   // S2 is empty: h = 1 whatever E is
+    const double inv_nu = exp2_small(-log2nu), P = exp2_small(log2P);
+    const double t1 = 1.0 - inv_nu, A = 1.0 - P;
+    double g = 1.0;
+    for (int j = 0; j < K; ++j) g *= t1;
+    double U = 1.0, S2 = 0.0, pw = 1.0;
+    for (int j = 1; j <= K - 1; ++j) { S2 += U; pw *= t1; U = fma(A, U, pw); }
+    const double one_Q = fmax(1.0 - exp2_small(log2nu + log2P), 0.0);
+    const double D = inv_nu * one_Q * S2;
+    const double x = (s - g) - 1.0e-6 * s;
+    if (!(x > 0.0)) return true;
+    return x * 16.0 * (D + x / inv_nu) < s * D;
+}
+
 // Entry l of a PendTable from the float64 constant C (same split as RatioConst).
 __device__ __forceinline__ void pend_table_set(PendTable &tab, int l, double C) {
     const RatioConst rc(C);

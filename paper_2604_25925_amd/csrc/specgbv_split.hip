@@ -301,6 +301,15 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
     if (threadIdx.x == 0) s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
 }
 
+// log2 of the joint draft probability of the tokens of rows 0 .. i-1 of the draft whose rows start at row0
+// (pending modifications change target rows only).
+__device__ __forceinline__ double draft_block_log2(const RowStat *stats, long long row0, int i)
+{
+    double l = 0.0;
+    for (int j = 0; j < i; ++j) l += stats[row0 + j].tok2_p - stats[row0 + j].lse2_p;
+    return l;
+}
+
 // grid rows * P as k_ot_sum_parts, launched after it: E = nu^2 (s - g) of the rows whose s and g nearly cancel, in the
 // same parts (-1 in every part marks a row without it).  Every workgroup adds up its row's partial sums and leaves at
 // once unless the row wants the sum (rare: peaked rows, large block ratios); the others sweep their part again.
@@ -331,7 +340,9 @@ k_excess_parts(const T *__restrict__ target, const T *__restrict__ draft, int K,
     double s_val = 0.0;
     for (int q = 0; q < P; ++q) s_val += s_part[pair * kPendParts + q];
     // (every thread has read the same values: uniform over the workgroup)
-    if (modified || !excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_val), K)) {
+    bool wanted = !modified && excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_val), K);
+    if (wanted) wanted = excess_needed(log2nu, draft_block_log2(stats, bk * L, i), s_val, K);
+    if (!wanted) {
         if (threadIdx.x == 0) e_part[pair * kPendParts + part] = -1.0;
         return;
     }
@@ -523,7 +534,8 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
     // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term: a second sweep
     // over the row pair (rare: peaked rows, large block ratios; rows under pending modifications keep the plain sum)
     double e_val = -1.0;
-    if (!(PEND && sh_tab.n > 0) && excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_val), K)) {   // uniform over the workgroup
+    if (!(PEND && sh_tab.n > 0) && excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_val), K) &&
+        excess_needed(log2nu, draft_block_log2(stats, bk * L, i), s_val, K)) {   // uniform over the workgroup
         const ExcessConst ec = make_excess_const(st.lse2_q, st.lse2_p, log2nu, K, c);
         float acc2 = 0.0f;
         for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
