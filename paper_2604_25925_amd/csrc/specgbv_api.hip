@@ -60,6 +60,9 @@ Workspace make_workspace(int batch, int K, int L, int V)
     w.pend_cnt = take(n * sizeof(int32_t));
     w.stat_part = take(n * 2 * kRowParts * sizeof(Row0Part));
     w.row0 = take(static_cast<size_t>(batch) * 2 * kRow0Parts * sizeof(Row0Part));
+    // (lists of g <= kMaxChainGrid workgroups, each 1 + ceil(chains / g) (L - 1) entries: at most this many in all)
+    w.later = take((static_cast<size_t>(kMaxChainGrid) +
+                    (static_cast<size_t>(batch) * K + kMaxChainGrid) * static_cast<size_t>(L > 1 ? L - 1 : 0)) * sizeof(int32_t));
     w.kseq_pos = take(static_cast<size_t>(batch) * L * 2 * sizeof(int32_t));
     w.total = off;
     return w;

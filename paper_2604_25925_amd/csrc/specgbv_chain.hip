@@ -250,11 +250,20 @@ __device__ __noinline__ ExactStats exact_row_stats(const T *row, int nvec, float
     return ExactStats{ref, a};
 }
 
+constexpr int kExcessThreads = 256;
+
 // excess_needed as a function of its own: called by one thread for the few rows that pass excess_wanted, its float64
 // registers would otherwise be taken from the ones that hold the row pair.
 __device__ __noinline__ bool excess_needed_call(double log2nu, double log2P, double s, int K)
 {
     return excess_needed(log2nu, log2P, s, K);
+}
+
+// Rows a workgroup of k_chain hands to k_chain_excess: entry 0 of its list is their number, then their row indices.
+// A list has room for every row the workgroup sums.
+inline int later_list_entries(long long nchains, long long grid, int L)
+{
+    return 1 + static_cast<int>((nchains + grid - 1) / grid) * (L > 1 ? L - 1 : 0);
 }
 
 constexpr int kLag = 6;    // slots between the load of a vector and its first use
@@ -623,13 +632,14 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         int K, int L, int V, long long nchains, float c, RowStat *__restrict__ stats, double *__restrict__ s_out,
         double *__restrict__ e_out,
         int32_t *__restrict__ final_counter, ChainPend pend, int first_row, const Row0Part *__restrict__ row0, double c_rel,
-        double *__restrict__ e_part)
+        int32_t *__restrict__ later, int later_stride)
 {
     __shared__ U4 lds_all[kLdsSlots * 2 * kChainThreads];
     __shared__ double sh_d[3 * kChainWaves];
     __shared__ double sh_sumrow[2][2];                     // log2 of the block ratio and of the drafts' joint probability in front
                                                            // of the row in sweep 2: written by thread 0 when the row's statistics
                                                            // are known, in the entry of the iteration's parity, read one iteration later
+    __shared__ int sh_nlater;                              // rows handed to k_chain_excess so far (thread 0 only)
     __shared__ PendTable sh_tab;                           // PEND only: levels that modify the current row
     __shared__ double sh_mu[kMaxPend];                     //            log2 block ratio of every level in front of the current row
     __shared__ int sh_cnt[kMaxPend];                       //            rows every level modifies (this prefix)
@@ -641,6 +651,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         __syncthreads();
     }
 
+    if (threadIdx.x == 0) sh_nlater = 0;
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
     const unsigned tid = threadIdx.x;
@@ -786,15 +797,16 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             s_out[bk_old * L + r_old] = s_val;
             // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term (rare:
             // peaked rows, large block ratios).  The row has left the chip by now, and one workgroup reading it again
-            // alone would hold up the whole grid for the time of a row: it is marked, its parts set to "not there yet",
-            // and the workgroups of the final-token kernel sum it together before they decide.
+            // alone would hold up the whole grid for the time of a row: it is marked, and k_chain_excess, launched
+            // behind this kernel, spreads the marked rows over the chip.
             bool again = false;
             if constexpr (!PEND) {
                 const double *front = sh_sumrow[(g - 1) & 1];
-                if (excess_wanted(static_cast<float>(front[0]), static_cast<float>(s_val), K) &&
+                if (excess_wanted(static_cast<float>(front[0]), static_cast<float>(s_val), K) && sh_nlater + 1 < later_stride &&
                     excess_needed_call(front[0], front[1], s_val, K)) {
                     again = true;
-                    for (int q = 0; q < kPendParts; ++q) e_part[(bk_old * L + r_old) * kPendParts + q] = -1.0;
+                    sh_nlater = sh_nlater + 1;
+                    later[static_cast<size_t>(blockIdx.x) * later_stride + sh_nlater] = static_cast<int32_t>(bk_old * L + r_old);
                 }
             }
             e_out[bk_old * L + r_old] = again ? kExcessPending : -1.0;
@@ -891,6 +903,94 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             log2P = uniform_d(log2P + (tok2_p - lse2_p));
         }
     }
+    if constexpr (!PEND)
+        if (tid == 0) later[static_cast<size_t>(blockIdx.x) * later_stride] = sh_nlater;   // (every workgroup, also when it is 0)
+}
+
+// E = nu^2 (s - g) of the rows k_chain handed over, straight from memory, in kPendParts parts per row which the
+// decision kernel adds up in part order.  Every workgroup reads the lengths of all `nlists` lists (nearly always all
+// 0: it leaves at once), numbers the listed rows in list order and takes the units blockIdx.x, blockIdx.x +
+// gridDim.x, ... of (row, part), part fastest.  Every wave fetches the statistics of the row's chain itself, one row
+// per lane (L <= 62).
+template <typename T>
+__global__ void __launch_bounds__(kExcessThreads)
+k_chain_excess(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
+               const RowStat *__restrict__ stats, const int32_t *__restrict__ later, int nlists, int later_stride,
+               double *__restrict__ e_part)
+{
+    constexpr int kPer = kMaxChainGrid / kExcessThreads;   // lists per thread
+    __shared__ double sh_d[kExcessThreads / kWave];
+    __shared__ int sh_before[kMaxChainGrid + 1];           // rows in the lists before list w; entry nlists: all of them
+    __shared__ int sh_wave[kExcessThreads / kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wid = tid / kWave;
+    int cnt[kPer], mine = 0;
+#pragma unroll
+    for (int a = 0; a < kPer; ++a) {
+        const int w = tid * kPer + a;
+        const int n = w < nlists ? later[static_cast<size_t>(w) * later_stride] : 0;
+        cnt[a] = n < 0 ? 0 : (n > later_stride - 1 ? later_stride - 1 : n);
+        mine += cnt[a];
+    }
+    if (__syncthreads_or(mine) == 0) return;               // no row anywhere
+    int incl = mine;                                       // inclusive scan over the wave, then over the waves
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+    }
+    if (lane == kWave - 1) sh_wave[wid] = incl;
+    __syncthreads();
+    int before = incl - mine;
+    for (int v = 0; v < wid; ++v) before += sh_wave[v];
+#pragma unroll
+    for (int a = 0; a < kPer; ++a) {
+        sh_before[tid * kPer + a] = before;
+        before += cnt[a];
+    }
+    if (tid == kExcessThreads - 1) sh_before[kMaxChainGrid] = before;
+    __syncthreads();
+    const int nrows = sh_before[kMaxChainGrid];
+    constexpr int PV = Elem<T>::kPerVec;
+    constexpr int kAhead = 4;                              // vector pairs in flight per thread
+    const int nvec = V / PV;
+    const int per = (nvec + kPendParts - 1) / kPendParts;
+    for (long long u = blockIdx.x; u < static_cast<long long>(nrows) * kPendParts; u += gridDim.x) {      // uniform
+        const int r = static_cast<int>(u / kPendParts), part = static_cast<int>(u % kPendParts);
+        int w = 0;                                         // the list that holds row r: the last one with sh_before[w] <= r
+        for (int step = kMaxChainGrid / 2; step >= 1; step >>= 1)
+            if (w + step < kMaxChainGrid && sh_before[w + step] <= r) w += step;
+        const long long pair = later[static_cast<size_t>(w) * later_stride + 1 + (r - sh_before[w])];
+        const long long bk = pair / L;
+        const int i = static_cast<int>(pair % L);
+        const int lo = part * per, hi = lo + per < nvec ? lo + per : nvec;
+        const RowStat st = stats[bk * L + (lane < L ? lane : L - 1)];
+        const double ratio = (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);   // log2 of the row's token ratio
+        double log2nu = 0.0;                               // added up as k_chain does: the same bits
+        for (int j = 0; j < i; ++j) log2nu += lane_d(ratio, j);
+        const ExcessConst ec = make_excess_const(lane_d(st.lse2_q, i), lane_d(st.lse2_p, i), log2nu, K, c);
+        const T *qrow = target + (bk * (L + 1) + i) * static_cast<long long>(V);
+        const T *prow = draft + pair * static_cast<long long>(V);
+        float acc = 0.0f;
+        for (int v0 = lo + tid; v0 < hi; v0 += kAhead * kExcessThreads) {
+            U4 q[kAhead], pp[kAhead];
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                const int v = v0 + a * kExcessThreads;
+                q[a] = load16_stream(qrow + static_cast<long long>(v < hi ? v : v0) * PV);
+                pp[a] = load16_stream(prow + static_cast<long long>(v < hi ? v : v0) * PV);
+            }
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                float zq[PV], zp[PV];
+                Elem<T>::unpack(q[a], zq);
+                Elem<T>::unpack(pp[a], zp);
+                if (v0 + a * kExcessThreads < hi) acc += excess_terms(zq, zp, ec);
+            }
+        }
+        // (a part without vectors, where the row has fewer of them than parts, adds 0)
+        const double e_val = block_sum(static_cast<double>(acc), sh_d) * ec.scale;
+        if (tid == 0) e_part[pair * kPendParts + part] = e_val;
+    }
 }
 
 // Workgroups that can be resident at once: one per compute unit (a workgroup takes 144 KiB of LDS).
@@ -902,6 +1002,7 @@ int resident_workgroups()
     if (cached[dev] == 0) {
         int n = 0;
         cached[dev] = (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : 256;
+        if (cached[dev] > kMaxChainGrid) cached[dev] = kMaxChainGrid;      // (the workspace holds that many row lists)
     }
     return cached[dev];
 }
@@ -914,6 +1015,7 @@ hipError_t launch_kp(const Problem &p)
     const long long nchains = static_cast<long long>(p.batch) * p.K;
     const long long cus = resident_workgroups();
     const dim3 grid(static_cast<unsigned>(nchains < cus ? nchains : cus));
+    const int stride = later_list_entries(nchains, grid.x, p.L);
     const T *target = static_cast<const T *>(p.target);
     const T *draft = static_cast<const T *>(p.draft);
     const int full_slots = (p.V / Elem<T>::kPerVec) / kChainThreads;
@@ -932,11 +1034,15 @@ hipError_t launch_kp(const Problem &p)
                        p.tokens, p.K, p.L, p.V, nchains, p.c, stats, s,                                    \
                        reinterpret_cast<double *>(p.ws + p.lay.excess),                                    \
                        reinterpret_cast<int32_t *>(p.ws + p.lay.counter), pend, first_row, row0, p.c_rel,     \
-                       reinterpret_cast<double *>(p.ws + p.lay.excess_part))
+                       reinterpret_cast<int32_t *>(p.ws + p.lay.later), stride)
     if (full_slots >= 23) SPECGBV_LAUNCH(23);
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);
 #undef SPECGBV_LAUNCH
+    if (!PEND)
+        hipLaunchKernelGGL((k_chain_excess<T>), dim3(static_cast<unsigned>(cus)), dim3(kExcessThreads), 0, p.stream, target,
+                           draft, p.K, p.L, p.V, p.c, stats, reinterpret_cast<const int32_t *>(p.ws + p.lay.later),
+                           static_cast<int>(grid.x), stride, reinterpret_cast<double *>(p.ws + p.lay.excess_part));
     return hipGetLastError();
 }
 
@@ -958,7 +1064,7 @@ hipError_t launch_typed(const Problem &p)
 
 }  // namespace
 
-// Parts the final-token kernel sums the cancellation-free sum of a marked row in.
+// Parts k_chain_excess leaves the cancellation-free sum of a marked row in.
 int chain_excess_parts(const Problem &) { return kPendParts; }
 
 bool chain_supported(const Problem &p)

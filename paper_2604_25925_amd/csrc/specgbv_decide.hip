@@ -99,9 +99,7 @@ struct DecideIO {
     const double *s_part;       // s_parts > 1: the sums arrive as s_parts partial sums per row ([n_rows][kPendParts])
     double *s_store;            //              and the complete ones are stored here by the writing workgroup
     int s_parts;
-    int e_parts;                // > 0 (chain schedule): an entry kExcessPending of e_arr marks a row whose E the workgroups of
-                                // its prefix still have to sum, in e_parts parts left in e_part (each -1 until it is there)
-    double *e_part_rw;          //   the same array, writable
+    int e_parts;                // > 0: an entry kExcessPending of e_arr stands for the sum of the row's first e_parts parts
     double *log_nu_out, *log_P_out, *h_out, *eta_out;
     int32_t *state_out;
     int32_t *accepted_len, *accepted_draft_idx, *out_tokens;
@@ -115,12 +113,9 @@ struct DecideIO {
 // *sel_out (shared memory) and is visible to every thread on return.  Only a workgroup with
 // write = true stores outputs and intermediates.  *u_final_out (shared memory) receives the uniform
 // of the final token (Philox slot K*L), drawn here so that the generator is instantiated once.
-// excess_hook(tq, tp, lq, lp, ex): called by all threads once the prefix's statistics are in LDS (and behind a
-// barrier); it may replace entries of ex and ends with a barrier if it does.
-template <typename Hook>
 __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, int L, uint64_t seed, uint64_t offset,
                                               bool write, double *lds, Selection *sel_out, double *u_final_out,
-                                              PendTable *tab_out, Hook excess_hook)
+                                              PendTable *tab_out)
 {
     const int32_t *__restrict__ tokens = io.tokens;
     const RowStat *__restrict__ stats = io.stats;
@@ -162,13 +157,16 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
             } else {
                 s = s_arr[base + k * L + i];
                 e = io.e_arr[base + k * L + i];
+                if (io.e_parts > 0 && e == kExcessPending) {    // (in part order: the same bits in every workgroup)
+                    e = 0.0;
+                    for (int q = 0; q < io.e_parts; ++q) e += io.e_part[(base + k * L + i) * kPendParts + q];
+                }
             }
         }
         l2nu[idx] = s;
         ex[idx] = e;
     }
     __syncthreads();
-    excess_hook(tq, tp, lq, lp, ex);
     for (int idx = tid; idx <= KL; idx += kDecideThreads) {
         const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
         if (idx == KL) { *u_final_out = e; continue; }
@@ -656,7 +654,6 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     __shared__ int sh_seg, sh_first[kSegThreads / kWave], sh_last[kSegThreads / kWave];
     __shared__ double sh_local_target, sh_total;
     __shared__ float sh_seg_m2;
-    __shared__ double sh_excess[kPendParts];
     const int b = blockIdx.y, tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wid = tid / kWave;
     int32_t *__restrict__ out_tokens = io.out_tokens;
@@ -669,79 +666,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
         decide_kseq<T>(target, draft, io, b, K, L, V, c, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
         K = 1;
     } else {
-        // Rows the chain kernel marked (block ratio above one, s and g nearly cancelling, and an acceptance
-        // probability that depends on their difference: rare) still lack their E = nu^2 (s - g).  The workgroups of the
-        // prefix sum it together, straight from memory: kPendParts parts per row, part q by workgroup q mod gridDim.x,
-        // left in the workspace with device-scope stores; every workgroup then needs all parts of the row (each runs
-        // the decision itself) and polls for the ones it has not summed.  The wait is bounded: a part that has not
-        // arrived after kExcessPolls looks (its workgroup has not been scheduled yet, say) is summed by the waiting
-        // workgroup itself -- the same bits, stored again -- so that no workgroup depends on another one's progress.
-        auto excess_hook = [&](const double *tq, const double *tp, const double *lq, const double *lp, double *ex) {
-            if (io.e_parts <= 0) return;                               // (uniform)
-            const int KL = K * L;
-            int marked = 0;
-            for (int idx = tid; idx < KL; idx += kSegThreads) marked |= ex[idx] == kExcessPending;
-            if (!__syncthreads_or(marked)) return;
-            constexpr int N = VEC ? Elem<T>::kPerVec : 1;
-            constexpr int kExcessPolls = 256;
-            const int units = VEC ? V / N : V;
-            const int per = (units + kPendParts - 1) / kPendParts;
-            for (int idx = 0; idx < KL; ++idx) {                       // uniform: every thread reads the same LDS entry
-                if (ex[idx] != kExcessPending) continue;
-                const int k = idx / L, i = idx % L + 1;                // (marks exist for i < L only)
-                const long long bk = static_cast<long long>(b) * K + k, pair = bk * L + i;
-                double log2nu = 0.0;                                   // added up as the chain kernel does
-                for (int j = 0; j < i; ++j) log2nu += tq[k * L + j] - tp[k * L + j];
-                const ExcessConst ec = make_excess_const(lq[k * L + i], lp[k * L + i], log2nu, K, c);
-                const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
-                const T *rp = draft + pair * static_cast<long long>(V);
-                double *parts = io.e_part_rw + pair * kPendParts;
-                auto sum_part = [&](int part) {                        // by the whole workgroup; the value in every thread
-                    const int lo = part * per, hi = lo + per < units ? lo + per : units;
-                    float acc = 0.0f;
-                    for_each_pair_range<T, VEC, kSegThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
-                        acc += excess_terms(zq, zp, ec);
-                    });
-                    const double v = block_sum(static_cast<double>(acc), sh_d) * ec.scale;
-                    if (tid == 0)
-                        __hip_atomic_store(reinterpret_cast<unsigned long long *>(parts + part),
-                                           static_cast<unsigned long long>(__double_as_longlong(v)), __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
-                    return v;
-                };
-                __syncthreads();                                       // (sh_excess of the previous row has been read)
-                for (int part = 0; part < kPendParts; ++part) {        // uniform
-                    const bool mine = part % static_cast<int>(gridDim.x) == static_cast<int>(blockIdx.x);
-                    const double v = mine ? sum_part(part) : -1.0;
-                    if (tid == 0) sh_excess[part] = v;
-                }
-                __syncthreads();
-                if (tid < kPendParts && sh_excess[tid] == -1.0) {      // (written by thread 0 itself, or by nobody yet)
-                    double v = -1.0;
-                    for (int look = 0; look < kExcessPolls && v == -1.0; ++look) {
-                        v = partial_load_d(parts + tid);
-                        if (v == -1.0) __builtin_amdgcn_s_sleep(32);
-                    }
-                    sh_excess[tid] = v;
-                }
-                __syncthreads();
-                for (int part = 0; part < kPendParts; ++part) {        // uniform; normally none is missing
-                    if (sh_excess[part] == -1.0) {
-                        const double v = sum_part(part);
-                        __syncthreads();
-                        if (tid == 0) sh_excess[part] = v;
-                        __syncthreads();
-                    }
-                }
-                if (tid == 0) {
-                    double e = 0.0;
-                    for (int part = 0; part < kPendParts; ++part) e += sh_excess[part];      // in part order
-                    ex[idx] = e;
-                }
-                __syncthreads();
-            }
-        };
-        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab, excess_hook);
+        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
     }
     const Selection sl = sh_sel;
     if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
@@ -982,7 +907,6 @@ hipError_t launch_final_typed(const Problem &p)
     io.s_store = reinterpret_cast<double *>(p.ws + p.lay.s);
     io.s_parts = p.s_parts;
     io.e_parts = p.e_parts;
-    io.e_part_rw = reinterpret_cast<double *>(p.ws + p.lay.excess_part);
     io.log_nu_out = reinterpret_cast<double *>(p.ws + p.lay.log_nu);
     io.log_P_out = reinterpret_cast<double *>(p.ws + p.lay.log_P);
     io.h_out = reinterpret_cast<double *>(p.ws + p.lay.h);

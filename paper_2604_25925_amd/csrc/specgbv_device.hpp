@@ -32,7 +32,7 @@ struct RowStat {
 //   q^(l+1)[x] = q^(l)[x] t_l[x]^K / N_l,   t_l[x] = max(1 - p[x] / (mu_l q^(l)[x]), 0),   q^(0) = q,
 // for the first count_l rows of every draft.  Per (level, prefix, draft, row), in base-2 logarithms:
 constexpr int kMaxPend = 16;     // levels applied on the fly at most
-constexpr double kExcessPending = -2.0;   // in the array of E = nu^2 (s - g): the row's sum is still to be taken, in parts (chain schedule)
+constexpr double kExcessPending = -2.0;   // in the array of E = nu^2 (s - g): the row's sum is on its way, in parts (chain schedule)
 constexpr int kMaxDrafts = 64;   // K at most (one lane of a wave per draft where the drafts of a prefix are compared)
 struct PendRow {
     double log2mu;   // block ratio mu_l in front of this row (carried ratio continued along the drafted tokens with q^(l))

@@ -14,7 +14,7 @@ struct Workspace {
     size_t stats;      // RowStat [B*K*L]
     size_t s;          // double  [B*K*L]   (position i = row i; position 0 unused)
     size_t excess;     // double  [B*K*L]   nu^2 (s - g) summed without cancellation where the sum kernels took it, else -1
-    size_t excess_part;// double  [B*K*L][kPendParts]  the same in parts (small batches; rows the chain kernel marks)
+    size_t excess_part;// double  [B*K*L][kPendParts]  the same in parts (small batches)
     size_t log_nu;     // double  [B*K*L]
     size_t log_P;      // double  [B*K*L]
     size_t h;          // double  [B*K*L]
@@ -36,11 +36,14 @@ struct Workspace {
     size_t pend_cnt;   // int32  [B*K*L]  workgroups of a shared row that have stored their partial normaliser
     size_t stat_part;  // Row0Part [B*K*L][2][kRowParts]  partial row statistics (two-pass schedule, small batches)
     size_t row0;       // Row0Part [B][2][kRow0Parts]  partial statistics of the rows 0 a prefix's drafts share (chain schedule)
+    size_t later;      // int32 [workgroups][1 + rows a workgroup sums]  chain schedule: per workgroup, the number of rows
+                       //             whose Eq. (hik) sum is taken again without cancellation, then their row indices
     size_t kseq_pos;   // int32 [2][B*L]  comparison verifier: drafts retained at each position, and the lowest of them
     size_t total;
     int nseg;
 };
 
+constexpr int kMaxChainGrid = 1024;            // workgroups of the chain kernel at most (one per compute unit)
 constexpr int kPendParts = 16;                 // workgroups a modified row's normaliser is shared among, at most
 constexpr int kRowParts = 16;                  // workgroups a row is shared among at most when the batch is small
 constexpr int kRow0Parts = 16;                 // slices a shared row 0 is reduced in
@@ -75,7 +78,7 @@ struct Problem {
     int32_t *state_count;          // [kMaxPend][batch]
     bool shared_row0;              // rows 0 of a prefix's drafts are copies of one another (caller's statement)
     int s_parts;                   // > 1: the sums of Eq. (hik) are left as this many partial sums per row (small batches)
-    int e_parts;                   // > 0 (chain schedule): rows marked kExcessPending get their E in this many parts, summed by the final-token kernel
+    int e_parts;                   // > 0 (chain schedule): rows marked kExcessPending have their E in this many parts
     int kseq_ndrafts;              // > 0: the comparison verifier (K-SEQ rule of Section 3.2) on the first kseq_ndrafts drafts
 };
 
@@ -95,7 +98,7 @@ bool chain_supported(const Problem &p);
 bool chain_preferred(const Problem &p);      // supported, and enough chains for it to beat the two-pass schedule
 bool chain_supports_pending(const Problem &p);   // supported, and the whole row pair fits on chip (pending modifications)
 hipError_t launch_chain_main(const Problem &p);
-int chain_excess_parts(const Problem &p);    // parts the cancellation-free sum of a marked row is taken in (final-token kernel)
+int chain_excess_parts(const Problem &p);    // parts k_chain_excess leaves the cancellation-free sum of a marked row in
 
 // Decision scan (Algorithm 1) and final-token kernels (Eq. (pres) / bonus token).
 hipError_t launch_decide_and_sample(const Problem &p);
