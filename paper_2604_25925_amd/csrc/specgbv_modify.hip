@@ -17,6 +17,11 @@
 //                 probability is 0): ln q_new for modified rows, ln q otherwise, and ln p.
 // An optional extra target row (the bonus row of the verification) is converted to
 // log-probabilities as well, so that the whole output can be verified at temperature 1.
+//
+// Rows of up to kRowSlots * 512 sixteen-byte vectors take a shorter route: k_mod_row keeps a row in the registers of
+// its workgroup between the statistics sweep and the store of its log-probabilities, so every row that no
+// modification touches (all draft rows, the target rows from the prefix's count on, the bonus row) is read once;
+// k_mod_norm and k_mod_write then run for the modified target rows only.
 #include "specgbv_internal.hpp"
 
 namespace specgbv {
@@ -98,6 +103,97 @@ k_mod_stats(const T *__restrict__ target, const T *__restrict__ draft, const int
     }
 }
 
+constexpr int kRowSlots = 40;          // vectors per thread k_mod_row keeps: rows up to 163840 bfloat16 / 81920 float32 entries
+
+// 8 (or 4) consecutive floats of an output row
+template <int N>
+__device__ __forceinline__ void store_vals(float *dst, const float (&v)[N])
+{
+    if (N % 4 == 0) {
+#pragma unroll
+        for (int j = 0; j < N; j += 4) *reinterpret_cast<float4 *>(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < N; ++j) dst[j] = v[j];
+    }
+}
+
+// k_mod_stats for rows of at most kRowSlots * kModThreads vectors, with the row kept in registers: the workgroup
+// then also writes the row's natural-log probabilities unless a modification is pending for it (target rows below
+// the prefix's count: k_mod_norm and k_mod_write do those).  grid.x = target rows followed by draft rows; all of a
+// thread's loads are issued before the first is used.
+template <typename T>
+__global__ void __launch_bounds__(kModThreads)
+k_mod_row(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int K,
+          int M, int bonus, int V, float c, long long n_trows, const int32_t *__restrict__ modify_count,
+          ModStat *__restrict__ tstat, ModStat *__restrict__ dstat, float *__restrict__ out_logq,
+          float *__restrict__ out_logp)
+{
+    constexpr float kLn2f = 0.693147180559945309417f;
+    __shared__ double sh_d[kModThreads / kWave];
+    __shared__ float sh_f[kModThreads / kWave];
+    const long long id = blockIdx.x;
+    const bool is_draft = id >= n_trows;
+    const long long row = is_draft ? id - n_trows : id;
+    const T *z_row = (is_draft ? draft : target) + row * static_cast<long long>(V);
+    const int rows_t = M + bonus;
+    const int r = static_cast<int>(row % (is_draft ? M : rows_t));
+    const long long bk = row / (is_draft ? M : rows_t);
+    constexpr int PV = Elem<T>::kPerVec;
+    const int nvec = V / PV;                               // host: nvec <= kRowSlots * kModThreads
+    const int tid = threadIdx.x;
+    U4 v[kRowSlots];
+#pragma unroll
+    for (int j = 0; j < kRowSlots; ++j) {
+        const int idx = j * kModThreads + tid;
+        if (j * kModThreads < nvec)                        // (uniform: slots the row does not reach issue nothing)
+            v[j] = load16_stream(z_row + static_cast<long long>(idx < nvec ? idx : nvec - 1) * PV);
+        else
+            v[j] = U4{0, 0, 0, 0};
+    }
+    RunningSum acc;
+#pragma unroll
+    for (int j = 0; j < kRowSlots; ++j) {
+        if (j * kModThreads + tid < nvec) {
+            float z[PV];
+            Elem<T>::unpack(v[j], z);
+            acc.add(z, c);
+        }
+    }
+    const float Mx = block_max(acc.m2, sh_f);
+    const double total = block_sum(static_cast<double>(acc.Z * exp2_fast(acc.m2 - Mx)), sh_d);
+    const double lse2 = static_cast<double>(Mx) + log2(total);
+    if (tid == 0) {
+        ModStat st;
+        st.lse2 = lse2;
+        st.tok2 = 0.0;
+        if (r < M) {                                       // the bonus row has no token
+            int tok = tokens[bk * M + r];
+            tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+            st.tok2 = static_cast<double>(Elem<T>::scalar(z_row + tok)) * static_cast<double>(c);
+        }
+        (is_draft ? dstat : tstat)[row] = st;
+    }
+    float *out = is_draft ? out_logp : out_logq;
+    if (!is_draft && r < M && r < modify_count[bk / K]) out = nullptr;     // a modification is pending for this row
+    if (!out) return;
+    out += row * static_cast<long long>(V);
+    // log2 prob[x] = fma(z, c, -h) - d with a float reference h and its float64 remainder d (as k_mod_write)
+    const float h = static_cast<float>(lse2);
+    const float dlt = static_cast<float>(lse2 - static_cast<double>(h));
+#pragma unroll
+    for (int j = 0; j < kRowSlots; ++j) {
+        const int idx = j * kModThreads + tid;
+        if (idx < nvec) {
+            float z[PV], a[PV];
+            Elem<T>::unpack(v[j], z);
+#pragma unroll
+            for (int e = 0; e < PV; ++e) a[e] = (fmaf(z[e], c, -h) - dlt) * kLn2f;
+            store_vals(out + static_cast<long long>(idx) * PV, a);
+        }
+    }
+}
+
 // log2 of the block ratio in front of row r of draft bk: the carried ratio times the token
 // ratios of rows 0..r-1 (original target probabilities).
 __device__ __forceinline__ double mod_log2nu(const ModStat *tstat, const ModStat *dstat, long long bk, int rows_t,
@@ -153,26 +249,14 @@ k_mod_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, int
     }
 }
 
-// 8 (or 4) consecutive floats of an output row
-template <int N>
-__device__ __forceinline__ void store_vals(float *dst, const float (&v)[N])
-{
-    if (N % 4 == 0) {
-#pragma unroll
-        for (int j = 0; j < N; j += 4) *reinterpret_cast<float4 *>(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
-    } else {
-#pragma unroll
-        for (int j = 0; j < N; ++j) dst[j] = v[j];
-    }
-}
-
-// grid.x = batch * K * (M + bonus) target rows
+// grid.x = batch * K * (M + bonus) target rows; plain_done: k_mod_row has written every row without a pending
+// modification and all of ln p, so those workgroups leave at once
 template <typename T, bool VEC>
 __global__ void __launch_bounds__(kModThreads)
 k_mod_write(const T *__restrict__ target, const T *__restrict__ draft, int K, int M, int bonus, int V, float c,
             const double *__restrict__ carry_log_nu, const int32_t *__restrict__ modify_count,
             const ModStat *__restrict__ tstat, const ModStat *__restrict__ dstat, const double *__restrict__ norm,
-            const int32_t *__restrict__ fb_in, float *__restrict__ out_logq, float *__restrict__ out_logp)
+            const int32_t *__restrict__ fb_in, float *__restrict__ out_logq, float *__restrict__ out_logp, int plain_done)
 {
     constexpr float kLn2f = 0.693147180559945309417f;
     const long long trow = blockIdx.x;
@@ -187,11 +271,12 @@ k_mod_write(const T *__restrict__ target, const T *__restrict__ draft, int K, in
     const float hq = static_cast<float>(sq.lse2), hp = static_cast<float>(sp.lse2);
     const float dq = static_cast<float>(sq.lse2 - static_cast<double>(hq));
     const float dp = static_cast<float>(sp.lse2 - static_cast<double>(hp));
+    if (plain_done && !(has_draft && r < modify_count[b])) return;     // (uniform over the workgroup)
     const bool modified = has_draft && r < modify_count[b] && fb_in[drow] == 0;
     const T *rq = target + trow * static_cast<long long>(V);
     const T *rp = has_draft ? draft + drow * static_cast<long long>(V) : rq;   // bonus row: no second stream
     float *oq = out_logq + trow * static_cast<long long>(V);
-    float *op = (out_logp && has_draft) ? out_logp + drow * static_cast<long long>(V) : nullptr;
+    float *op = (out_logp && has_draft && !plain_done) ? out_logp + drow * static_cast<long long>(V) : nullptr;
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
     if (modified) {
         // ln q_new = ln q + K ln t - ln W
@@ -239,14 +324,21 @@ hipError_t launch_modify_typed(const void *target_v, const void *draft_v, const 
     const long long bk = static_cast<long long>(batch) * K;
     const long long n_t = bk * (M + bonus), n_d = bk * M;
     const dim3 blk(kModThreads);
+    // rows short enough to stay in a workgroup's registers are read once unless a modification is pending for them
+    const bool rows_fit = vec && V / Elem<T>::kPerVec <= kRowSlots * kModThreads;
 #define SPECGBV_MOD_LAUNCH(VEC)                                                                                   \
     do {                                                                                                          \
-        hipLaunchKernelGGL((k_mod_stats<T, VEC>), dim3(static_cast<unsigned>(n_t + n_d)), blk, 0, stream, target,  \
-                           draft, tokens, M, bonus, V, c, n_t, tstat, dstat);                                     \
+        if (rows_fit)                                                                                             \
+            hipLaunchKernelGGL((k_mod_row<T>), dim3(static_cast<unsigned>(n_t + n_d)), blk, 0, stream, target,     \
+                               draft, tokens, K, M, bonus, V, c, n_t, count, tstat, dstat, out_logq, out_logp);   \
+        else                                                                                                      \
+            hipLaunchKernelGGL((k_mod_stats<T, VEC>), dim3(static_cast<unsigned>(n_t + n_d)), blk, 0, stream,      \
+                               target, draft, tokens, M, bonus, V, c, n_t, tstat, dstat);                         \
         hipLaunchKernelGGL((k_mod_norm<T, VEC>), dim3(static_cast<unsigned>(n_d)), blk, 0, stream, target, draft,  \
                            K, M, bonus, V, c, carry, count, tstat, dstat, norm, fb);                              \
         hipLaunchKernelGGL((k_mod_write<T, VEC>), dim3(static_cast<unsigned>(n_t)), blk, 0, stream, target, draft, \
-                           K, M, bonus, V, c, carry, count, tstat, dstat, norm, fb, out_logq, out_logp);          \
+                           K, M, bonus, V, c, carry, count, tstat, dstat, norm, fb, out_logq, out_logp,           \
+                           rows_fit ? 1 : 0);                                                                     \
     } while (0)
     if (vec) SPECGBV_MOD_LAUNCH(true);
     else SPECGBV_MOD_LAUNCH(false);
