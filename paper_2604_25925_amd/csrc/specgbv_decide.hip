@@ -100,6 +100,9 @@ struct DecideIO {
     double *s_store;            //              and the complete ones are stored here by the writing workgroup
     int s_parts;
     int e_parts;                // > 0: an entry kExcessPending of e_arr stands for the sum of the row's first e_parts parts
+    int e_coop;                 // != 0 (s_parts > 1, nothing pending): nobody has looked yet whether a row needs E; the
+                                // workgroups of the prefix find out and sum it together (e_part_rw: parts, each -1 until there)
+    double *e_part_rw;
     double *log_nu_out, *log_P_out, *h_out, *eta_out;
     int32_t *state_out;
     int32_t *accepted_len, *accepted_draft_idx, *out_tokens;
@@ -113,9 +116,13 @@ struct DecideIO {
 // *sel_out (shared memory) and is visible to every thread on return.  Only a workgroup with
 // write = true stores outputs and intermediates.  *u_final_out (shared memory) receives the uniform
 // of the final token (Philox slot K*L), drawn here so that the generator is instantiated once.
+// excess_hook(tq, tp, lq, lp, ex, s): called by all threads once the prefix's statistics are in LDS (and behind a
+// barrier); s[k * L + i - 1] is the Eq. (hik) sum of row i of draft k; it may replace entries of ex and ends with a
+// barrier if it does.
+template <typename Hook>
 __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, int L, uint64_t seed, uint64_t offset,
                                               bool write, double *lds, Selection *sel_out, double *u_final_out,
-                                              PendTable *tab_out)
+                                              PendTable *tab_out, Hook excess_hook)
 {
     const int32_t *__restrict__ tokens = io.tokens;
     const RowStat *__restrict__ stats = io.stats;
@@ -148,10 +155,10 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         double s = 0.0, e = -1.0;
         if (i < L) {
             if (io.s_parts > 1) {                           // in part order: the same bits in every workgroup
-                e = 0.0;
+                e = io.e_coop ? -1.0 : 0.0;
                 for (int q = 0; q < io.s_parts; ++q) {
                     s += io.s_part[(base + k * L + i) * kPendParts + q];
-                    e += io.e_part[(base + k * L + i) * kPendParts + q];
+                    if (!io.e_coop) e += io.e_part[(base + k * L + i) * kPendParts + q];
                 }
                 if (write) io.s_store[base + k * L + i] = s;
             } else {
@@ -167,6 +174,7 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         ex[idx] = e;
     }
     __syncthreads();
+    excess_hook(tq, tp, lq, lp, ex, l2nu);
     for (int idx = tid; idx <= KL; idx += kDecideThreads) {
         const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
         if (idx == KL) { *u_final_out = e; continue; }
@@ -654,6 +662,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
     __shared__ int sh_seg, sh_first[kSegThreads / kWave], sh_last[kSegThreads / kWave];
     __shared__ double sh_local_target, sh_total;
     __shared__ float sh_seg_m2;
+    __shared__ double sh_excess[kPendParts];
     const int b = blockIdx.y, tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wid = tid / kWave;
     int32_t *__restrict__ out_tokens = io.out_tokens;
@@ -666,7 +675,112 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
         decide_kseq<T>(target, draft, io, b, K, L, V, c, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
         K = 1;
     } else {
-        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
+        // Small batches (the sums of Eq. (hik) arrive in parts): whether a row's s and g cancel so far that its E =
+        // nu^2 (s - g) has to be summed term by term is known only here, where the parts meet.  Every workgroup of the
+        // prefix applies the kernels' two tests to every row (the same values, so the same rows), and for the rare
+        // row that fails them the workgroups sum E together, straight from memory: one part per workgroup (at most
+        // kPendParts), left in the workspace with a device-scope store; every workgroup needs all parts (each runs the
+        // decision itself) and polls for the ones it has not summed.  The wait is bounded: a part that has not
+        // arrived after kExcessPolls looks (its workgroup has not been scheduled yet, say) is summed by the waiting
+        // workgroup itself -- the same bits, stored again -- so no workgroup depends on another one's progress.
+        auto excess_hook = [&](const double *tq, const double *tp, const double *lq, const double *lp, double *ex,
+                               const double *s_row) {
+            if (!io.e_coop) return;                                    // (uniform)
+            const int KL = K * L;
+            int marked = 0;
+            for (int idx = tid; idx < KL; idx += kSegThreads) {
+                const int k = idx / L, i = idx % L + 1;
+                if (i >= L) continue;
+                double log2nu = 0.0, log2P = 0.0;
+                for (int j = 0; j < i; ++j) { log2nu += tq[k * L + j] - tp[k * L + j]; log2P += tp[k * L + j]; }
+                if (excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_row[idx]), K) &&
+                    excess_needed(log2nu, log2P, s_row[idx], K)) {
+                    ex[idx] = kExcessPending;
+                    marked = 1;
+                }
+            }
+            if (!__syncthreads_or(marked)) return;
+            constexpr int N = VEC ? Elem<T>::kPerVec : 1;
+            constexpr int kExcessPolls = 1024;
+            constexpr int kAhead = 4;                                  // vector pairs in flight per thread
+            const int nparts = static_cast<int>(gridDim.x) < kPendParts ? static_cast<int>(gridDim.x) : kPendParts;
+            const int units = VEC ? V / N : V;
+            const int per = (units + nparts - 1) / nparts;
+            for (int idx = 0; idx < KL; ++idx) {                       // uniform: every thread reads the same LDS entry
+                if (ex[idx] != kExcessPending) continue;
+                const int k = idx / L, i = idx % L + 1;
+                const long long bk = static_cast<long long>(b) * K + k, pair = bk * L + i;
+                double log2nu = 0.0;
+                for (int j = 0; j < i; ++j) log2nu += tq[k * L + j] - tp[k * L + j];
+                const ExcessConst ec = make_excess_const(lq[k * L + i], lp[k * L + i], log2nu, K, c);
+                const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
+                const T *rp = draft + pair * static_cast<long long>(V);
+                double *parts = io.e_part_rw + pair * kPendParts;
+                auto sum_part = [&](int part) {                        // by the whole workgroup; the value in every thread
+                    const int lo = part * per, hi = lo + per < units ? lo + per : units;
+                    float acc = 0.0f;
+                    if constexpr (VEC) {
+                        for (int v0 = lo + tid; v0 < hi; v0 += kAhead * kSegThreads) {
+                            U4 q4[kAhead], p4[kAhead];
+#pragma unroll
+                            for (int a = 0; a < kAhead; ++a) {
+                                const int v = v0 + a * kSegThreads;
+                                q4[a] = load16_stream(rq + static_cast<long long>(v < hi ? v : v0) * N);
+                                p4[a] = load16_stream(rp + static_cast<long long>(v < hi ? v : v0) * N);
+                            }
+#pragma unroll
+                            for (int a = 0; a < kAhead; ++a) {
+                                float zq[N], zp[N];
+                                Elem<T>::unpack(q4[a], zq);
+                                Elem<T>::unpack(p4[a], zp);
+                                if (v0 + a * kSegThreads < hi) acc += excess_terms(zq, zp, ec);
+                            }
+                        }
+                    } else {
+                        for_each_pair_range<T, VEC, kSegThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
+                            acc += excess_terms(zq, zp, ec);
+                        });
+                    }
+                    const double v = block_sum(static_cast<double>(acc), sh_d) * ec.scale;
+                    if (tid == 0)
+                        __hip_atomic_store(reinterpret_cast<unsigned long long *>(parts + part),
+                                           static_cast<unsigned long long>(__double_as_longlong(v)), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                    return v;
+                };
+                __syncthreads();                                       // (sh_excess of the previous row has been read)
+                {
+                    const int mine = static_cast<int>(blockIdx.x);     // (workgroups beyond kPendParts only wait)
+                    const double v = mine < nparts ? sum_part(mine) : -1.0;
+                    if (tid < kPendParts) sh_excess[tid] = tid == mine ? v : -1.0;
+                }
+                __syncthreads();
+                if (tid < nparts && sh_excess[tid] == -1.0) {
+                    double v = -1.0;
+                    for (int look = 0; look < kExcessPolls && v == -1.0; ++look) {
+                        v = partial_load_d(parts + tid);
+                        if (v == -1.0) __builtin_amdgcn_s_sleep(8);
+                    }
+                    sh_excess[tid] = v;
+                }
+                __syncthreads();
+                for (int part = 0; part < nparts; ++part) {            // uniform; normally none is missing
+                    if (sh_excess[part] == -1.0) {
+                        const double v = sum_part(part);
+                        __syncthreads();
+                        if (tid == 0) sh_excess[part] = v;
+                        __syncthreads();
+                    }
+                }
+                if (tid == 0) {
+                    double e = 0.0;
+                    for (int part = 0; part < nparts; ++part) e += sh_excess[part];          // in part order
+                    ex[idx] = e;
+                }
+                __syncthreads();
+            }
+        };
+        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab, excess_hook);
     }
     const Selection sl = sh_sel;
     if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
@@ -907,6 +1021,8 @@ hipError_t launch_final_typed(const Problem &p)
     io.s_store = reinterpret_cast<double *>(p.ws + p.lay.s);
     io.s_parts = p.s_parts;
     io.e_parts = p.e_parts;
+    io.e_coop = (p.s_parts > 1 && p.pend_levels == 0 && p.kseq_ndrafts == 0) ? 1 : 0;
+    io.e_part_rw = reinterpret_cast<double *>(p.ws + p.lay.excess_part);
     io.log_nu_out = reinterpret_cast<double *>(p.ws + p.lay.log_nu);
     io.log_P_out = reinterpret_cast<double *>(p.ws + p.lay.log_P);
     io.h_out = reinterpret_cast<double *>(p.ws + p.lay.h);

@@ -216,7 +216,7 @@ template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kStatThreads)
 k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int K, int L,
                int V, float c, int P, const Row0Part *__restrict__ stat_parts, int stat_P, RowStat *stats,
-               int32_t *__restrict__ final_counter, double *__restrict__ s_part,
+               int32_t *__restrict__ final_counter, double *__restrict__ s_part, double *__restrict__ e_part,
                const PendRow *__restrict__ pend, long long n_rows, int nlev, double c_rel)
 {
     __shared__ double sh_d[kStatThreads / kWave];
@@ -299,6 +299,9 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
     // (whether the row's s and g nearly cancel, so that Eq. (hik) needs nu^2 (s - g) summed term by term, only the sum
     // over all parts can tell: k_excess_parts looks at it once every part is in)
     if (threadIdx.x == 0) s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
+    // (without pending modifications the final-token kernel looks at the complete sums itself and takes E where a
+    // row needs it: its parts start as "not there yet")
+    if (!PEND && part == 0 && threadIdx.x < kPendParts) e_part[pair * kPendParts + threadIdx.x] = -1.0;
 }
 
 // log2 of the joint draft probability of the tokens of rows 0 .. i-1 of the draft whose rows start at row0
@@ -628,11 +631,12 @@ hipError_t launch_typed(const Problem &p)
 #define SPECGBV_OTP_LAUNCH(VEC, PEND)                                                                                 \
     do {                                                                                                              \
         hipLaunchKernelGGL((k_ot_sum_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, \
-                           p.K, p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part, pend, pairs, \
-                           p.pend_levels, p.c_rel);                                                                   \
-        hipLaunchKernelGGL((k_excess_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L, \
-                           p.V, p.c, p.s_parts, stats, pend_part, reinterpret_cast<double *>(p.ws + p.lay.excess_part),  \
-                           pend, pairs, p.pend_levels);                                                               \
+                           p.K, p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part,            \
+                           reinterpret_cast<double *>(p.ws + p.lay.excess_part), pend, pairs, p.pend_levels, p.c_rel);  \
+        if (PEND)                                                                                                     \
+            hipLaunchKernelGGL((k_excess_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.K,  \
+                               p.L, p.V, p.c, p.s_parts, stats, pend_part,                                            \
+                               reinterpret_cast<double *>(p.ws + p.lay.excess_part), pend, pairs, p.pend_levels);      \
     } while (0)
         if (p.pend_levels > 0) { if (vec) SPECGBV_OTP_LAUNCH(true, true); else SPECGBV_OTP_LAUNCH(false, true); }
         else { if (vec) SPECGBV_OTP_LAUNCH(true, false); else SPECGBV_OTP_LAUNCH(false, false); }

@@ -9,8 +9,9 @@ that computes row statistics is covered: on-chip chains, the two-pass schedule, 
 
 Runaway block ratios.  A target far surer of the drafted tokens than the draft makes nu grow by orders of magnitude
 per position; s and g = (1 - 1/nu)^K then agree to many digits and Eq. (hik) needs nu^2 (s - g) summed term by term.
-On the chain schedule those rows go to a follow-up kernel: chains with every row handed over, and workgroups that
-hand over more rows than one chain has.
+On the chain schedule those rows go to a follow-up kernel (chains with every row handed over, workgroups that hand
+over more rows than one chain has); on the two-pass schedule they get a second sweep, or, where a small batch
+leaves the sums in parts, the final-token kernel's workgroups sum them together.
 """
 import numpy as np
 import pytest
@@ -66,11 +67,16 @@ def test_near_certain_drafted_tokens(algo, dtype, V, B, shared, T):
                    shared_row0=shared)
 
 
-@pytest.mark.parametrize("dtype,V,B,K,L", [("bf16", 32768, 2, 4, 8), ("f32", 14336, 3, 3, 6), ("bf16", 28672, 90, 8, 4)])
-def test_block_ratio_runs_away_on_the_chain_schedule(dtype, V, B, K, L):
+@pytest.mark.parametrize("algo,dtype,V,B,K,L", [
+    ("chain", "bf16", 32768, 2, 4, 8), ("chain", "f32", 14336, 3, 3, 6), ("chain", "bf16", 28672, 90, 8, 4),
+    ("split", "bf16", 32768, 1, 4, 6), ("split", "f32", 16384, 2, 3, 5), ("split", "bf16", 131072, 1, 2, 4),
+    ("split", "f32", 3001, 1, 2, 4), ("split", "bf16", 32768, 40, 4, 4)])
+def test_block_ratio_runs_away(algo, dtype, V, B, K, L):
     """q(token) = 0.9 against p(token) = 1e-3 at every position: nu gains a factor 900 per row and every sum of
-    Eq. (hik) from the second row on cancels against g.  B * K = 720 chains on 256 compute units: a workgroup then
-    hands over the rows of several chains."""
+    Eq. (hik) from the second row on cancels against g.  On the chain schedule B * K = 720 chains on 256 compute
+    units make a workgroup hand over the rows of several chains; on the two-pass schedule the small batches leave
+    the sums in parts, and the final-token kernel's workgroups find the rows and sum E together (one, four and
+    sixteen workgroups per prefix at these vocabularies), while the batch of 40 takes the second sweep of k_ot_sum."""
     T = 1.0
     t, d, tok = _case(B, K, L, V, T, seed=41)
     for b in range(B):
@@ -86,7 +92,7 @@ def test_block_ratio_runs_away_on_the_chain_schedule(dtype, V, B, K, L):
     kw = {}
     if B > 8:                                                          # the oracle takes a sample of the prefixes
         kw["gpu_slice"] = list(range(0, B, 11))
-    rep, gpu, ora = check_case(t, d, tok, T, 9, 0, "chain", "runaway nu %s V=%d B=%d" % (dtype, V, B), **kw)
+    rep, gpu, ora = check_case(t, d, tok, T, 9, 0, algo, "runaway nu %s %s V=%d B=%d" % (algo, dtype, V, B), **kw)
     s, g_ = ora["s"][:, :, 1:], None
     nu = np.exp(np.clip(ora["log_nu"][:, :, :L - 1], -700, 700))
     g_ = np.where(nu > 1, (1 - 1 / np.maximum(nu, 1)) ** K, 0.0)
