@@ -14,7 +14,8 @@
 // pending level; a level's rows are shared among workgroups when it has few of them left).
 //
 // Small batches, where a workgroup per row would leave most of the chip idle, use k_row_stats_parts and
-// k_ot_sum_parts (and k_excess_parts for the rows that need the cancellation-free sum) instead: every row is cut into
+// k_ot_sum_parts (and, with pending modifications, k_excess_parts for the rows that need the cancellation-free sum;
+// without them the final-token kernel takes that sum itself) instead: every row is cut into
 // parts, combined in part order by the consumers.
 //
 // Any V and any alignment is accepted (rows whose byte length is not a multiple of 16
