@@ -99,6 +99,10 @@ size_t specgbv_workspace_bytes(int batch, int K, int L, int V, specgbv_dtype dty
  *
  * Errors are detected on the host before anything is launched; on error nothing is
  * written and specgbv_last_error() describes the cause.
+ *
+ * Environment (read at every call, meant for tests): SPECGBV_EXCESS_POLLS = how often a workgroup of the
+ * final-token kernel looks for a partial sum another workgroup of its prefix owes before it takes that sum
+ * itself (small batches; default 1024, 0 = never wait).  The results do not depend on it.
  */
 specgbv_status specgbv_verify(
     const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,

@@ -17,6 +17,8 @@
 //                  inverse-CDF search: the first token id whose running weight exceeds
 //                  u * total (segment by a workgroup-wide scan of the partial sums, entry by
 //                  a wave scan inside that segment).
+#include <cstdlib>
+
 #include "specgbv_internal.hpp"
 
 namespace specgbv {
@@ -103,6 +105,7 @@ struct DecideIO {
     int e_coop;                 // != 0 (s_parts > 1, nothing pending): nobody has looked yet whether a row needs E; the
                                 // workgroups of the prefix find out and sum it together (e_part_rw: parts, each -1 until there)
     double *e_part_rw;
+    int e_polls;                // looks a workgroup takes at a part another one sums before it sums the part itself
     double *log_nu_out, *log_P_out, *h_out, *eta_out;
     int32_t *state_out;
     int32_t *accepted_len, *accepted_draft_idx, *out_tokens;
@@ -681,7 +684,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
         // row that fails them the workgroups sum E together, straight from memory: one part per workgroup (at most
         // kPendParts), left in the workspace with a device-scope store; every workgroup needs all parts (each runs the
         // decision itself) and polls for the ones it has not summed.  The wait is bounded: a part that has not
-        // arrived after kExcessPolls looks (its workgroup has not been scheduled yet, say) is summed by the waiting
+        // arrived after io.e_polls looks (its workgroup has not been scheduled yet, say) is summed by the waiting
         // workgroup itself -- the same bits, stored again -- so no workgroup depends on another one's progress.
         auto excess_hook = [&](const double *tq, const double *tp, const double *lq, const double *lp, double *ex,
                                const double *s_row) {
@@ -701,7 +704,6 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
             }
             if (!__syncthreads_or(marked)) return;
             constexpr int N = VEC ? Elem<T>::kPerVec : 1;
-            constexpr int kExcessPolls = 1024;
             constexpr int kAhead = 4;                                  // vector pairs in flight per thread
             const int nparts = static_cast<int>(gridDim.x) < kPendParts ? static_cast<int>(gridDim.x) : kPendParts;
             const int units = VEC ? V / N : V;
@@ -757,7 +759,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
                 __syncthreads();
                 if (tid < nparts && sh_excess[tid] == -1.0) {
                     double v = -1.0;
-                    for (int look = 0; look < kExcessPolls && v == -1.0; ++look) {
+                    for (int look = 0; look < io.e_polls && v == -1.0; ++look) {
                         v = partial_load_d(parts + tid);
                         if (v == -1.0) __builtin_amdgcn_s_sleep(8);
                     }
@@ -1023,6 +1025,12 @@ hipError_t launch_final_typed(const Problem &p)
     io.e_parts = p.e_parts;
     io.e_coop = (p.s_parts > 1 && p.pend_levels == 0 && p.kseq_ndrafts == 0) ? 1 : 0;
     io.e_part_rw = reinterpret_cast<double *>(p.ws + p.lay.excess_part);
+    // (the environment variable lets a test take the fall-back of the bounded wait: 0 looks, every workgroup sums all parts)
+    io.e_polls = 1024;
+    if (const char *polls = std::getenv("SPECGBV_EXCESS_POLLS")) {
+        const long n = std::strtol(polls, nullptr, 10);
+        io.e_polls = n < 0 ? 0 : (n > 1048576 ? 1048576 : static_cast<int>(n));
+    }
     io.log_nu_out = reinterpret_cast<double *>(p.ws + p.lay.log_nu);
     io.log_P_out = reinterpret_cast<double *>(p.ws + p.lay.log_P);
     io.h_out = reinterpret_cast<double *>(p.ws + p.lay.h);

@@ -98,3 +98,12 @@ def test_block_ratio_runs_away(algo, dtype, V, B, K, L):
     nu = np.exp(np.clip(ora["log_nu"][:, :, :L - 1], -700, 700))
     g_ = np.where(nu > 1, (1 - 1 / np.maximum(nu, 1)) ** K, 0.0)
     assert int(((nu > 1) & ((s - g_) * 16 < s)).sum()) >= s.size // 3, "the case no longer cancels"
+
+
+def test_bounded_wait_falls_back_to_the_waiting_workgroups_own_sum(monkeypatch):
+    """With no look at all at the parts other workgroups sum (SPECGBV_EXCESS_POLLS=0) every workgroup of the
+    final-token kernel sums every part of a row that needs E itself: the path a workgroup takes when a part does not
+    arrive in time.  Same inputs as above, sixteen workgroups per prefix; the results do not change."""
+    monkeypatch.setenv("SPECGBV_EXCESS_POLLS", "0")
+    test_block_ratio_runs_away("split", "bf16", 131072, 1, 2, 4)
+    test_block_ratio_runs_away("split", "f32", 16384, 2, 3, 5)
