@@ -193,6 +193,7 @@ specgbv_status specgbv_verify_ex(
 
     p.s_parts = use_chain ? 1 : split_sum_parts(p);
     p.e_parts = (use_chain && !pending) ? chain_excess_parts(p) : 0;
+    p.e_coop = use_chain ? 0 : 1;
 
     hipError_t e;
     if (options && options->ev_main_start) {

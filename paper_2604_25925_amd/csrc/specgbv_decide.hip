@@ -97,12 +97,12 @@ struct DecideIO {
     int nlev;
     const double *s_arr;
     const double *e_arr;        // nu^2 (s - g) of Eq. (hik) where the sum kernels took it without cancellation, else negative
-    const double *e_part;       // s_parts > 1: the same in parts (every part negative: not taken)
+    const double *e_part;       // chain schedule: the parts of the rows marked kExcessPending
     const double *s_part;       // s_parts > 1: the sums arrive as s_parts partial sums per row ([n_rows][kPendParts])
     double *s_store;            //              and the complete ones are stored here by the writing workgroup
     int s_parts;
     int e_parts;                // > 0: an entry kExcessPending of e_arr stands for the sum of the row's first e_parts parts
-    int e_coop;                 // != 0 (s_parts > 1, nothing pending): nobody has looked yet whether a row needs E; the
+    int e_coop;                 // != 0 (two-pass schedule): nobody has looked yet whether a row needs E; the
                                 // workgroups of the prefix find out and sum it together (e_part_rw: parts, each -1 until there)
     double *e_part_rw;
     int e_polls;                // looks a workgroup takes at a part another one sums before it sums the part itself
@@ -158,11 +158,7 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         double s = 0.0, e = -1.0;
         if (i < L) {
             if (io.s_parts > 1) {                           // in part order: the same bits in every workgroup
-                e = io.e_coop ? -1.0 : 0.0;
-                for (int q = 0; q < io.s_parts; ++q) {
-                    s += io.s_part[(base + k * L + i) * kPendParts + q];
-                    if (!io.e_coop) e += io.e_part[(base + k * L + i) * kPendParts + q];
-                }
+                for (int q = 0; q < io.s_parts; ++q) s += io.s_part[(base + k * L + i) * kPendParts + q];
                 if (write) io.s_store[base + k * L + i] = s;
             } else {
                 s = s_arr[base + k * L + i];
@@ -678,8 +674,10 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
         decide_kseq<T>(target, draft, io, b, K, L, V, c, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab);
         K = 1;
     } else {
-        // Small batches (the sums of Eq. (hik) arrive in parts): whether a row's s and g cancel so far that its E =
-        // nu^2 (s - g) has to be summed term by term is known only here, where the parts meet.  Every workgroup of the
+        // Two-pass schedule: whether a row's s and g cancel so far that its E = nu^2 (s - g) has to be summed term by
+        // term is looked at here (with small batches the sums of Eq. (hik) arrive in parts and meet here; with larger
+        // ones the sum kernel's workgroup would have to take a second sweep alone).  tq holds the token probabilities
+        // under the pending modifications, if there are any, so nu is the one the decision uses.  Every workgroup of the
         // prefix applies the kernels' two tests to every row (the same values, so the same rows), and for the rare
         // row that fails them the workgroups sum E together, straight from memory: one part per workgroup (at most
         // kPendParts), left in the workspace with a device-scope store; every workgroup needs all parts (each runs the
@@ -698,8 +696,14 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
                 for (int j = 0; j < i; ++j) { log2nu += tq[k * L + j] - tp[k * L + j]; log2P += tp[k * L + j]; }
                 if (excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_row[idx]), K) &&
                     excess_needed(log2nu, log2P, s_row[idx], K)) {
-                    ex[idx] = kExcessPending;
-                    marked = 1;
+                    bool modified = false;                             // rows under pending modifications keep the plain sum
+                    if (io.pend)
+                        for (int l = 0; l < io.nlev; ++l)
+                            modified = modified || io.pend[static_cast<long long>(l) * io.n_rows + static_cast<long long>(b) * KL + idx + 1].flag != 0;
+                    if (!modified) {
+                        ex[idx] = kExcessPending;
+                        marked = 1;
+                    }
                 }
             }
             if (!__syncthreads_or(marked)) return;
@@ -1023,7 +1027,7 @@ hipError_t launch_final_typed(const Problem &p)
     io.s_store = reinterpret_cast<double *>(p.ws + p.lay.s);
     io.s_parts = p.s_parts;
     io.e_parts = p.e_parts;
-    io.e_coop = (p.s_parts > 1 && p.pend_levels == 0 && p.kseq_ndrafts == 0) ? 1 : 0;
+    io.e_coop = (p.e_coop != 0 && p.kseq_ndrafts == 0) ? 1 : 0;
     io.e_part_rw = reinterpret_cast<double *>(p.ws + p.lay.excess_part);
     // (the environment variable lets a test take the fall-back of the bounded wait: 0 looks, every workgroup sums all parts)
     io.e_polls = 1024;

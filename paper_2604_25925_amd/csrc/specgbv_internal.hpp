@@ -79,6 +79,7 @@ struct Problem {
     bool shared_row0;              // rows 0 of a prefix's drafts are copies of one another (caller's statement)
     int s_parts;                   // > 1: the sums of Eq. (hik) are left as this many partial sums per row (small batches)
     int e_parts;                   // > 0 (chain schedule): rows marked kExcessPending have their E in this many parts
+    int e_coop;                    // != 0 (two-pass schedule): the final-token kernel finds the rows that need E and sums it
     int kseq_ndrafts;              // > 0: the comparison verifier (K-SEQ rule of Section 3.2) on the first kseq_ndrafts drafts
 };
 

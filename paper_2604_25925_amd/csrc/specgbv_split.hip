@@ -14,8 +14,7 @@
 // pending level; a level's rows are shared among workgroups when it has few of them left).
 //
 // Small batches, where a workgroup per row would leave most of the chip idle, use k_row_stats_parts and
-// k_ot_sum_parts (and, with pending modifications, k_excess_parts for the rows that need the cancellation-free sum;
-// without them the final-token kernel takes that sum itself) instead: every row is cut into
+// k_ot_sum_parts instead: every row is cut into
 // parts, combined in part order by the consumers.
 //
 // Any V and any alignment is accepted (rows whose byte length is not a multiple of 16
@@ -298,71 +297,11 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
     }
     const double total = block_sum(static_cast<double>(acc), sh_d);
     // (whether the row's s and g nearly cancel, so that Eq. (hik) needs nu^2 (s - g) summed term by term, only the sum
-    // over all parts can tell: k_excess_parts looks at it once every part is in)
+    // over all parts can tell: the final-token kernel looks at it)
     if (threadIdx.x == 0) s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
-    // (without pending modifications the final-token kernel looks at the complete sums itself and takes E where a
-    // row needs it: its parts start as "not there yet")
-    if (!PEND && part == 0 && threadIdx.x < kPendParts) e_part[pair * kPendParts + threadIdx.x] = -1.0;
-}
-
-// log2 of the joint draft probability of the tokens of rows 0 .. i-1 of the draft whose rows start at row0
-// (pending modifications change target rows only).
-__device__ __forceinline__ double draft_block_log2(const RowStat *stats, long long row0, int i)
-{
-    double l = 0.0;
-    for (int j = 0; j < i; ++j) l += stats[row0 + j].tok2_p - stats[row0 + j].lse2_p;
-    return l;
-}
-
-// grid rows * P as k_ot_sum_parts, launched after it: E = nu^2 (s - g) of the rows whose s and g nearly cancel, in the
-// same parts (-1 in every part marks a row without it).  Every workgroup adds up its row's partial sums and leaves at
-// once unless the row wants the sum (rare: peaked rows, large block ratios); the others sweep their part again.
-template <typename T, bool VEC, bool PEND>
-__global__ void __launch_bounds__(kStatThreads)
-k_excess_parts(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c, int P,
-               const RowStat *__restrict__ stats, const double *__restrict__ s_part, double *__restrict__ e_part,
-               const PendRow *__restrict__ pend, long long n_rows, int nlev)
-{
-    __shared__ double sh_d[kStatThreads / kWave];
-    const long long idx = blockIdx.x / P;         // bk*(L-1) + (i-1)
-    const int part = static_cast<int>(blockIdx.x % P);
-    const int i = static_cast<int>(idx % (L - 1)) + 1;
-    const long long bk = idx / (L - 1);
-    const long long pair = bk * L + i;
-    const RowStat st = stats[pair];
-    double log2nu = 0.0;
-    bool modified = false;                        // rows under pending modifications keep the plain sum
-    if (PEND) {
-        log2nu = pend_block_ratio(stats, pend, n_rows, nlev, bk * L, i, sh_d);
-        for (int l = 0; l < nlev; ++l) modified = modified || pend[static_cast<long long>(l) * n_rows + pair].flag != 0;
-    } else {
-        for (int j = 0; j < i; ++j) {
-            const RowStat a = stats[bk * L + j];
-            log2nu += (a.tok2_q - a.lse2_q) - (a.tok2_p - a.lse2_p);
-        }
-    }
-    double s_val = 0.0;
-    for (int q = 0; q < P; ++q) s_val += s_part[pair * kPendParts + q];
-    // (every thread has read the same values: uniform over the workgroup)
-    bool wanted = !modified && excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_val), K);
-    if (wanted) wanted = excess_needed(log2nu, draft_block_log2(stats, bk * L, i), s_val, K);
-    if (!wanted) {
-        if (threadIdx.x == 0) e_part[pair * kPendParts + part] = -1.0;
-        return;
-    }
-    const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
-    const T *rp = draft + pair * static_cast<long long>(V);
-    constexpr int N = VEC ? Elem<T>::kPerVec : 1;
-    const int units = VEC ? V / N : V;
-    const int per = (units + P - 1) / P;
-    const int lo = part * per, hi = lo + per < units ? lo + per : units;
-    const ExcessConst ec = make_excess_const(st.lse2_q, st.lse2_p, log2nu, K, c);
-    float acc2 = 0.0f;
-    for_each_pair_range<T, VEC, kStatThreads>(rq, rp, lo, hi, [&](int, const float (&zq)[N], const float (&zp)[N]) {
-        acc2 += excess_terms(zq, zp, ec);
-    });
-    const double e_val = block_sum(static_cast<double>(acc2), sh_d) * ec.scale;
-    if (threadIdx.x == 0) e_part[pair * kPendParts + part] = e_val;
+    // (the final-token kernel looks at the complete sums itself and takes E where a row needs it: its parts start as
+    // "not there yet")
+    if (part == 0 && threadIdx.x < kPendParts) e_part[pair * kPendParts + threadIdx.x] = -1.0;
 }
 
 // One level of pending modification (the levels below it are done: their PendRow entries are read).
@@ -486,7 +425,7 @@ template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kStatThreads)
 k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
          const RowStat *__restrict__ stats, const PendRow *__restrict__ pend, long long n_rows, int nlev,
-         double *__restrict__ s_out, double *__restrict__ e_out)
+         double *__restrict__ s_out, double *__restrict__ e_out, double *__restrict__ e_part)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ PendTable sh_tab;
@@ -535,18 +474,11 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
     }
     const double total = block_sum(static_cast<double>(acc), sh_d);
     const double s_val = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
-    // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term: a second sweep
-    // over the row pair (rare: peaked rows, large block ratios; rows under pending modifications keep the plain sum)
-    double e_val = -1.0;
-    if (!(PEND && sh_tab.n > 0) && excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_val), K) &&
-        excess_needed(log2nu, draft_block_log2(stats, bk * L, i), s_val, K)) {   // uniform over the workgroup
-        const ExcessConst ec = make_excess_const(st.lse2_q, st.lse2_p, log2nu, K, c);
-        float acc2 = 0.0f;
-        for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
-            acc2 += excess_terms(zq, zp, ec);
-        });
-        e_val = block_sum(static_cast<double>(acc2), sh_d) * ec.scale;
-    }
+    // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term (rare: peaked
+    // rows, large block ratios): the final-token kernel finds those rows and its workgroups sum E together (the
+    // parts start as "not there yet")
+    const double e_val = -1.0;
+    if (threadIdx.x < kPendParts) e_part[(bk * L + i) * kPendParts + threadIdx.x] = -1.0;
     if (threadIdx.x == 0) { s_out[bk * L + i] = s_val; e_out[bk * L + i] = e_val; }
 }
 
@@ -634,10 +566,6 @@ hipError_t launch_typed(const Problem &p)
         hipLaunchKernelGGL((k_ot_sum_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, \
                            p.K, p.L, p.V, p.c, p.s_parts, stat_part, stat_parts, stats, counter, pend_part,            \
                            reinterpret_cast<double *>(p.ws + p.lay.excess_part), pend, pairs, p.pend_levels, p.c_rel);  \
-        if (PEND)                                                                                                     \
-            hipLaunchKernelGGL((k_excess_parts<T, VEC, PEND>), gq, dim3(kStatThreads), 0, p.stream, target, draft, p.K,  \
-                               p.L, p.V, p.c, p.s_parts, stats, pend_part,                                            \
-                               reinterpret_cast<double *>(p.ws + p.lay.excess_part), pend, pairs, p.pend_levels);      \
     } while (0)
         if (p.pend_levels > 0) { if (vec) SPECGBV_OTP_LAUNCH(true, true); else SPECGBV_OTP_LAUNCH(false, true); }
         else { if (vec) SPECGBV_OTP_LAUNCH(true, false); else SPECGBV_OTP_LAUNCH(false, false); }
@@ -647,7 +575,8 @@ hipError_t launch_typed(const Problem &p)
     const dim3 g2(static_cast<unsigned>(rows));
 #define SPECGBV_OT_LAUNCH(VEC, PEND)                                                                           \
     hipLaunchKernelGGL((k_ot_sum<T, VEC, PEND>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L, \
-                       p.V, p.c, stats, pend, pairs, p.pend_levels, s, reinterpret_cast<double *>(p.ws + p.lay.excess))
+                       p.V, p.c, stats, pend, pairs, p.pend_levels, s, reinterpret_cast<double *>(p.ws + p.lay.excess),        \
+                       reinterpret_cast<double *>(p.ws + p.lay.excess_part))
     if (p.pend_levels > 0) { if (vec) SPECGBV_OT_LAUNCH(true, true); else SPECGBV_OT_LAUNCH(false, true); }
     else { if (vec) SPECGBV_OT_LAUNCH(true, false); else SPECGBV_OT_LAUNCH(false, false); }
 #undef SPECGBV_OT_LAUNCH
