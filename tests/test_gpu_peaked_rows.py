@@ -70,14 +70,15 @@ def test_near_certain_drafted_tokens(algo, dtype, V, B, shared, T):
 @pytest.mark.parametrize("algo,dtype,V,B,K,L", [
     ("chain", "bf16", 32768, 2, 4, 8), ("chain", "f32", 14336, 3, 3, 6), ("chain", "bf16", 28672, 90, 8, 4),
     ("split", "bf16", 32768, 1, 4, 6), ("split", "f32", 16384, 2, 3, 5), ("split", "bf16", 131072, 1, 2, 4),
-    ("split", "f32", 3001, 1, 2, 4), ("split", "bf16", 262144, 1, 2, 3), ("split", "bf16", 32768, 40, 4, 4)])
+    ("split", "f32", 3001, 1, 2, 4), ("split", "bf16", 262144, 1, 2, 3), ("split", "bf16", 32768, 40, 4, 4),
+    ("split", "bf16", 131072, 192, 2, 3)])
 def test_block_ratio_runs_away(algo, dtype, V, B, K, L):
     """q(token) = 0.9 against p(token) = 1e-3 at every position: nu gains a factor 900 per row and every sum of
     Eq. (hik) from the second row on cancels against g.  On the chain schedule B * K = 720 chains on 256 compute
     units make a workgroup hand over the rows of several chains; on the two-pass schedule the small batches leave
     the sums in parts, and the final-token kernel's workgroups find the rows and sum E together (one, four, sixteen
-    and thirty-two workgroups per prefix at these vocabularies: the last sixteen only wait), while the batch of 40
-    takes the second sweep of k_ot_sum."""
+    and thirty-two workgroups per prefix at these vocabularies: the last sixteen only wait); so do the larger
+    batches, the last one with 192 x 16 final-token workgroups, more than the chip holds at once."""
     T = 1.0
     t, d, tok = _case(B, K, L, V, T, seed=41)
     for b in range(B):
