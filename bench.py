@@ -114,7 +114,7 @@ def bench_modify(a, w, sg, torch, tl, dl, tk, ws, out):
                    "mean_rows_modified": float(np.mean(counts)), "outputs": "logq [B,K,L+1,V] and logp [B,K,L,V], float32"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": committed_traffic("modify_" + w.name),
-                     "kernel": "k_mod_stats + k_mod_norm + k_mod_write",
+                     "kernel": "k_mod_row + k_mod_norm + k_mod_write",
                      "kernel_ms_avg": avg, "kernel_ms_min": ker[0],
                      "algorithmic_bytes_per_launch": read_b + write_b,
                      "algorithmic_read_bytes": read_b, "algorithmic_write_bytes": write_b},
@@ -482,7 +482,11 @@ def main() -> int:
                               "note": "untimed calls enqueued in one go before the warm-up calls, and again before the event-bracketed calls of the roofline figure, so that the shader clock is in its state under load"}},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": "vocabulary-streaming kernels (statistics + sums of Eq. (hik))",
+                     "kernel": "the vocabulary-streaming kernel(s) that compute the statistics and the sums of Eq. (hik) "
+                               "for every row: k_chain on the chain schedule (with k_row0_parts under --shared-row0), "
+                               "k_row_stats + k_ot_sum (or their _parts variants) on the two-pass schedule; the chain "
+                               "schedule's follow-up kernel for rows summed a second time (4 us when there is none) and "
+                               "the final-token kernel are outside the event bracket and inside ms_per_step",
                      "kernel_ms_avg": main_avg, "kernel_ms_min": main_ms[0],
                      "kernel_ms_median": main_ms[len(main_ms) // 2],
                      "kernel_ms_first5": [round(v, 4) for v in series[:5]],

@@ -190,7 +190,10 @@ typedef struct specgbv_options {
     int32_t pending_levels;    /* see pending_carry_log_nu                                  */
     void *ev_main_start;       /* hipEvent_t or NULL: recorded on the stream immediately    */
     void *ev_main_stop;        /*   before / after the vocabulary-streaming kernels that    */
-                               /*   compute the statistics and the sums of Eq. (hik)        */
+                               /*   compute the statistics and the sums of Eq. (hik) for    */
+                               /*   every row (the chain schedule's small follow-up kernel  */
+                               /*   for the rare rows whose sum is taken a second time and  */
+                               /*   the final-token kernel come after the stop event)       */
     /*
      * Pending distribution modifications (Algorithm 2) applied on the fly: both pointers NULL (none) or
      * both device pointers to pending_levels arrays of [batch] values, innermost level first

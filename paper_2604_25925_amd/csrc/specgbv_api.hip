@@ -206,6 +206,10 @@ specgbv_status specgbv_verify_ex(
         e = hipEventRecord(static_cast<hipEvent_t>(options->ev_main_stop), p.stream);
         if (e != hipSuccess) return fail(SPECGBV_EHIP, "hipEventRecord: %s", hipGetErrorString(e));
     }
+    if (use_chain) {
+        e = launch_chain_excess(p);
+        if (e != hipSuccess) return fail(SPECGBV_EHIP, "follow-up kernel launch: %s", hipGetErrorString(e));
+    }
     e = launch_decide_and_sample(p);
     if (e != hipSuccess) return fail(SPECGBV_EHIP, "decision/sampling kernel launch: %s", hipGetErrorString(e));
     return SPECGBV_OK;

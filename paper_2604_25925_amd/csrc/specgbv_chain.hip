@@ -1039,10 +1039,20 @@ hipError_t launch_kp(const Problem &p)
     else if (full_slots >= 15) SPECGBV_LAUNCH(15);
     else SPECGBV_LAUNCH(7);
 #undef SPECGBV_LAUNCH
-    if (!PEND)
-        hipLaunchKernelGGL((k_chain_excess<T>), dim3(static_cast<unsigned>(cus)), dim3(kExcessThreads), 0, p.stream, target,
-                           draft, p.K, p.L, p.V, p.c, stats, reinterpret_cast<const int32_t *>(p.ws + p.lay.later),
-                           static_cast<int>(grid.x), stride, reinterpret_cast<double *>(p.ws + p.lay.excess_part));
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_excess_typed(const Problem &p)
+{
+    const long long nchains = static_cast<long long>(p.batch) * p.K;
+    const long long cus = resident_workgroups();
+    const long long grid = nchains < cus ? nchains : cus;                  // k_chain's grid: one list per workgroup
+    hipLaunchKernelGGL((k_chain_excess<T>), dim3(static_cast<unsigned>(cus)), dim3(kExcessThreads), 0, p.stream,
+                       static_cast<const T *>(p.target), static_cast<const T *>(p.draft), p.K, p.L, p.V, p.c,
+                       reinterpret_cast<const RowStat *>(p.ws + p.lay.stats),
+                       reinterpret_cast<const int32_t *>(p.ws + p.lay.later), static_cast<int>(grid),
+                       later_list_entries(nchains, grid, p.L), reinterpret_cast<double *>(p.ws + p.lay.excess_part));
     return hipGetLastError();
 }
 
@@ -1095,6 +1105,12 @@ bool chain_preferred(const Problem &p)
 hipError_t launch_chain_main(const Problem &p)
 {
     return p.dtype == 1 ? launch_typed<uint16_t>(p) : launch_typed<float>(p);
+}
+
+hipError_t launch_chain_excess(const Problem &p)
+{
+    if (p.pend_levels > 0 || p.batch == 0) return hipSuccess;     // (rows under pending modifications keep the plain sum)
+    return p.dtype == 1 ? launch_excess_typed<uint16_t>(p) : launch_excess_typed<float>(p);
 }
 
 }  // namespace specgbv

@@ -99,6 +99,8 @@ bool chain_supported(const Problem &p);
 bool chain_preferred(const Problem &p);      // supported, and enough chains for it to beat the two-pass schedule
 bool chain_supports_pending(const Problem &p);   // supported, and the whole row pair fits on chip (pending modifications)
 hipError_t launch_chain_main(const Problem &p);
+// The chain schedule's follow-up kernel: E = nu^2 (s - g) of the rows k_chain handed over (usually none).
+hipError_t launch_chain_excess(const Problem &p);
 int chain_excess_parts(const Problem &p);    // parts k_chain_excess leaves the cancellation-free sum of a marked row in
 
 // Decision scan (Algorithm 1) and final-token kernels (Eq. (pres) / bonus token).
