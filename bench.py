@@ -494,6 +494,8 @@ def main() -> int:
                      "kernel_calls_above_1.05x_min": sum(1 for v in series if v > 1.05 * main_ms[0]),
                      "kernel_calls": len(series),
                      "traffic_source": traffic_source(ttag) if traffic is not None else None,
+                     # fetched + written bytes of the committed counter run over this run's kernel time
+                     "traffic_GBps": (traffic / (main_avg * 1e-3) / 1e9) if traffic is not None else None,
                      "algorithmic_bytes_per_launch": main_bytes},
     }
 
