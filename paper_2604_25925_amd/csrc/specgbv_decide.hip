@@ -119,13 +119,13 @@ struct DecideIO {
 // *sel_out (shared memory) and is visible to every thread on return.  Only a workgroup with
 // write = true stores outputs and intermediates.  *u_final_out (shared memory) receives the uniform
 // of the final token (Philox slot K*L), drawn here so that the generator is instantiated once.
-// excess_hook(tq, tp, lq, lp, ex, s): called by all threads once the prefix's statistics are in LDS (and behind a
-// barrier); s[k * L + i - 1] is the Eq. (hik) sum of row i of draft k; it may replace entries of ex and ends with a
-// barrier if it does.
+// excess_sums(tq, tp, lq, lp, ex): called by all threads (behind a barrier) when io.e_coop is set and some entry of
+// ex has been marked kExcessPending by the acceptance table's loop below; it replaces every marked entry by the
+// row's E = nu^2 (s - g) and ends with a barrier.
 template <typename Hook>
 __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, int L, uint64_t seed, uint64_t offset,
                                               bool write, double *lds, Selection *sel_out, double *u_final_out,
-                                              PendTable *tab_out, Hook excess_hook)
+                                              PendTable *tab_out, Hook excess_sums)
 {
     const int32_t *__restrict__ tokens = io.tokens;
     const RowStat *__restrict__ stats = io.stats;
@@ -173,10 +173,13 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         ex[idx] = e;
     }
     __syncthreads();
-    excess_hook(tq, tp, lq, lp, ex, l2nu);
-    for (int idx = tid; idx <= KL; idx += kDecideThreads) {
+    // One entry of the acceptance table.  With may_mark (two-pass schedule, first visit): a row whose s and g cancel
+    // so far that h needs E = nu^2 (s - g) summed term by term (the kernels' two tests; rows under pending
+    // modifications keep the plain sum) is marked instead and true is returned; its entry is made after the
+    // workgroups of the prefix have summed E together.
+    auto table_entry = [&](int idx, bool may_mark) -> bool {
         const double e = philox_uniform(seed, offset, static_cast<uint32_t>(b), static_cast<uint32_t>(idx));
-        if (idx == KL) { *u_final_out = e; continue; }
+        if (idx == KL) { *u_final_out = e; return false; }
         const int k = idx / L, i = idx % L + 1;
         const double s = l2nu[idx];                         // parked by this thread above
         double log2nu = 0.0, log2P = 0.0;
@@ -191,6 +194,14 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         const double g = g_K(inv_nu, K), cK = c_K(P, K);
         double hv;
         if (i < L && log2nu > 0.0) {
+            if (may_mark && excess_wanted(static_cast<float>(log2nu), static_cast<float>(s), K) &&
+                excess_needed(log2nu, log2P, s, K)) {
+                bool modified = false;
+                if (io.pend)
+                    for (int l = 0; l < io.nlev; ++l)
+                        modified = modified || io.pend[static_cast<long long>(l) * io.n_rows + base + idx + 1].flag != 0;
+                if (!modified) { ex[idx] = kExcessPending; return true; }
+            }
             // Block ratio above one: the denominator c_K(P) - nu (1 - s) equals [c_K(P) - c_K(1/nu)] + nu (s - g),
             // and c_K(P) - c_K(1/nu) = (1 - Q) S2 / nu with Q = nu P the block's joint target probability and
             // S2 = sum_{j=1}^{K-1} sum_{m<j} (1-P)^m (1 - 1/nu)^(j-1-m) (by the recurrence U_1 = 1,
@@ -221,6 +232,22 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         if (write) {
             io.log_nu_out[base + idx] = log_nu; io.log_P_out[base + idx] = log_P;
             io.h_out[base + idx] = hv; io.eta_out[base + idx] = e;
+        }
+        return false;
+    };
+    unsigned marked = 0u;                                   // bit n: the entry of this thread's n-th visit was marked
+    {
+        int n = 0;
+        for (int idx = tid; idx <= KL; idx += kDecideThreads, ++n)
+            if (table_entry(idx, io.e_coop != 0)) marked |= 1u << n;
+    }
+    if (io.e_coop) {                                        // (uniform)
+        static_assert((kMaxDrafts * 64 + kDecideThreads) / kDecideThreads <= 32, "one bit per visit (K <= 64, L < 64)");
+        if (__syncthreads_or(marked != 0u)) {
+            excess_sums(tq, tp, lq, lp, ex);
+            int n = 0;
+            for (int idx = tid; idx <= KL; idx += kDecideThreads, ++n)
+                if (marked >> n & 1u) table_entry(idx, false);
         }
     }
     for (int idx = tid; idx < K * K; idx += kDecideThreads) {
@@ -678,35 +705,15 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
         // term is looked at here (with small batches the sums of Eq. (hik) arrive in parts and meet here; with larger
         // ones the sum kernel's workgroup would have to take a second sweep alone).  tq holds the token probabilities
         // under the pending modifications, if there are any, so nu is the one the decision uses.  Every workgroup of the
-        // prefix applies the kernels' two tests to every row (the same values, so the same rows), and for the rare
-        // row that fails them the workgroups sum E together, straight from memory: one part per workgroup (at most
+        // prefix applies the kernels' two tests to every row while it makes the acceptance table (the same values, so
+        // the same rows), and for the rare row that fails them the workgroups sum E together, straight from memory (this
+        // function, called only then): one part per workgroup (at most
         // kPendParts), left in the workspace with a device-scope store; every workgroup needs all parts (each runs the
         // decision itself) and polls for the ones it has not summed.  The wait is bounded: a part that has not
         // arrived after io.e_polls looks (its workgroup has not been scheduled yet, say) is summed by the waiting
         // workgroup itself -- the same bits, stored again -- so no workgroup depends on another one's progress.
-        auto excess_hook = [&](const double *tq, const double *tp, const double *lq, const double *lp, double *ex,
-                               const double *s_row) {
-            if (!io.e_coop) return;                                    // (uniform)
+        auto excess_sums = [&](const double *tq, const double *tp, const double *lq, const double *lp, double *ex) {
             const int KL = K * L;
-            int marked = 0;
-            for (int idx = tid; idx < KL; idx += kSegThreads) {
-                const int k = idx / L, i = idx % L + 1;
-                if (i >= L) continue;
-                double log2nu = 0.0, log2P = 0.0;
-                for (int j = 0; j < i; ++j) { log2nu += tq[k * L + j] - tp[k * L + j]; log2P += tp[k * L + j]; }
-                if (excess_wanted(static_cast<float>(log2nu), static_cast<float>(s_row[idx]), K) &&
-                    excess_needed(log2nu, log2P, s_row[idx], K)) {
-                    bool modified = false;                             // rows under pending modifications keep the plain sum
-                    if (io.pend)
-                        for (int l = 0; l < io.nlev; ++l)
-                            modified = modified || io.pend[static_cast<long long>(l) * io.n_rows + static_cast<long long>(b) * KL + idx + 1].flag != 0;
-                    if (!modified) {
-                        ex[idx] = kExcessPending;
-                        marked = 1;
-                    }
-                }
-            }
-            if (!__syncthreads_or(marked)) return;
             constexpr int N = VEC ? Elem<T>::kPerVec : 1;
             constexpr int kAhead = 4;                                  // vector pairs in flight per thread
             const int nparts = static_cast<int>(gridDim.x) < kPendParts ? static_cast<int>(gridDim.x) : kPendParts;
@@ -786,7 +793,7 @@ k_final(const T *__restrict__ target, const T *__restrict__ draft, DecideIO io, 
                 __syncthreads();
             }
         };
-        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab, excess_hook);
+        decide_prefix(io, b, K, L, seed, offset, blockIdx.x == 0, lds_decide, &sh_sel, &sh_u, &sh_tab, excess_sums);
     }
     const Selection sl = sh_sel;
     if (blockIdx.x == 0 && tid == 0) fo.sel[b] = sl;
