@@ -259,6 +259,14 @@ __device__ __noinline__ bool excess_needed_call(double log2nu, double log2P, dou
     return excess_needed(log2nu, log2P, s, K);
 }
 
+// s with the drafted token's term exchanged for its float64 value (see token_term), likewise a function of its own:
+// s_tot the row's float32-summed terms and in_sweep the token's among them, both relative to the reference that the
+// normaliser 1 / inv_Zq is relative to.
+__device__ __noinline__ double token_term_call(double s_tot, float in_sweep, double inv_Zq, const TokenTerm *tt, int K)
+{
+    return (s_tot - static_cast<double>(in_sweep)) * inv_Zq + token_term(tt->log2q, tt->log2r, K);
+}
+
 // Rows a workgroup of k_chain hands to k_chain_excess: entry 0 of its list is their number, then their row indices.
 // A list has room for every row the workgroup sums.
 inline int later_list_entries(long long nchains, long long grid, int L)
@@ -640,6 +648,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
                                                            // of the row in sweep 2: written by thread 0 when the row's statistics
                                                            // are known, in the entry of the iteration's parity, read one iteration later
     __shared__ int sh_nlater;                              // rows handed to k_chain_excess so far (thread 0 only)
+    __shared__ TokenTerm sh_tokterm[2];                    // the drafted token of the row in sweep 2 (thread 0 only, by parity as above)
     __shared__ PendTable sh_tab;                           // PEND only: levels that modify the current row
     __shared__ double sh_mu[kMaxPend];                     //            log2 block ratio of every level in front of the current row
     __shared__ int sh_cnt[kMaxPend];                       //            rows every level modifies (this prefix)
@@ -793,7 +802,22 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             Zp_tot += static_cast<double>(nb_p) + (1.0 + xp + 0.5 * xp * xp);
         }
         if (do_sum && tid == 0) {
-            const double s_val = s_tot / Zq_prev;
+            const double inv_Zq = 1.0 / Zq_prev;
+            double s_val = s_tot * inv_Zq;
+            // The drafted token's own term once more in float64 where its p/(nu q) is near one: formed from a float32
+            // exponential, 1 - p/(nu q) is good to 6e-8 absolute only, and on a row whose mass sits on its drafted
+            // token, in front of a block ratio near one, that term is a good part of the whole sum.  The sweep's
+            // value of the term is taken out again (the same operations give the same bits).
+            {
+                const TokenTerm *tt = &sh_tokterm[(g - 1) & 1];
+                const float zq = tt->zq, zp = tt->zp;
+                const float u = fmaf(exp2_fast(fmaf(zp - zq, c, -rc_sum.C2_hi)), rc_sum.neg_kappa, 1.0f);
+                if (fabsf(u) < kTokenTermBelow) {
+                    float t1[1] = {__builtin_amdgcn_fmed3f(u, 0.0f, 1.0f)};
+                    pow_inplace<KP>(t1, K);
+                    s_val = token_term_call(s_tot, exp2_fast(fmaf(zq, c, rc_sum.nref_q)) * t1[0], inv_Zq, tt, K);
+                }
+            }
             s_out[bk_old * L + r_old] = s_val;
             // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term (rare:
             // peaked rows, large block ratios).  The row has left the chip by now, and one workgroup reading it again
@@ -893,12 +917,18 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             }
             // constants of this row's sweep 2 (next iteration)
             const double C2 = lse2_p - lse2_q + log2nu;
+            const double C2s = ratio_const(lse2_p, lse2_q, log2nu, c_rel);    // as the sweep takes it
             rc_sum.nref_q = -ref_q;
-            rc_sum.C2_hi = static_cast<float>(C2);
-            const double dk = (static_cast<double>(rc_sum.C2_hi) - C2) * 0.693147180559945309417;
+            rc_sum.C2_hi = static_cast<float>(C2s);
+            const double dk = (static_cast<double>(rc_sum.C2_hi) - C2s) * 0.693147180559945309417;
             rc_sum.neg_kappa = (dk > -0.25 && dk < 0.25) ? -static_cast<float>(1.0 + dk + 0.5 * dk * dk) : -1.0f;
             Zq_prev = uniform_d(Zq_tot);
-            if (tid == 0) { sh_sumrow[g & 1][0] = log2nu; sh_sumrow[g & 1][1] = log2P; }
+            if (tid == 0) {
+                sh_sumrow[g & 1][0] = log2nu; sh_sumrow[g & 1][1] = log2P;
+                TokenTerm tt;
+                tt.zq = zq_tok; tt.zp = zp_tok; tt.log2q = tok2_q - lse2_q; tt.log2r = (tok2_p - tok2_q) - C2;
+                sh_tokterm[g & 1] = tt;
+            }
             log2nu = uniform_d(log2nu + ((tok2_q - lse2_q + tok_adj) - (tok2_p - lse2_p)));
             log2P = uniform_d(log2P + (tok2_p - lse2_p));
         }

@@ -306,7 +306,7 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
         }
         Selection &sl = *sel_out;                // built in place (LDS): the level constants are indexed at run time
         sl.tau = tau;
-        sl.npend = 0; sl.pad = 0;
+        sl.npend = 0; sl.C2_adj = 0.0f;
         tab_out->n = 0;
         sl.target_row = (static_cast<long long>(b) * K + kf) * (L + 1) + tau;
         if (tau == L) {
@@ -315,6 +315,8 @@ __device__ __forceinline__ void decide_prefix(const DecideIO &io, int b, int K, 
             sl.draft_row = (static_cast<long long>(b) * K + kf) * L + tau;
             const double lse2_q = lq[kf * L + tau], lse2_p = lp[kf * L + tau];
             sl.C2 = lse2_p - lse2_q + (tau == 0 ? 0.0 : l2nu[kf * L + tau - 1]);
+            const double adj = tau == 0 ? 0.0 : -io.c_rel * l2nu[kf * L + tau - 1];
+            sl.C2_adj = adj - adj == 0.0 ? static_cast<float>(adj) : 0.0f;       // (an infinite block ratio stays what it is)
             sl.shift_q = rintf(static_cast<float>(lse2_q));         // integral: partial sums rescale exactly
             sl.lse2_q = lse2_q;
             sl.lse2_pq = lse2_p - lse2_q;
@@ -433,7 +435,7 @@ __device__ __forceinline__ void decide_kseq(const T *target, const T *draft, con
             }
         const int lead = __ffsll(static_cast<long long>(alive)) - 1;
         Selection &sl = *sel_out;
-        sl.tau = tau; sl.npend = 0; sl.pad = 0; tab_out->n = 0;
+        sl.tau = tau; sl.npend = 0; sl.C2_adj = 0.0f; tab_out->n = 0;
         sl.target_row = (static_cast<long long>(b) * K + lead) * (L + 1) + tau;
         if (tau == L) {
             sl.draft_row = -1; sl.C2 = 0.0; sl.shift_q = 0.0f; sl.lse2_q = 0.0; sl.lse2_pq = 0.0;
@@ -522,7 +524,7 @@ __device__ __forceinline__ float segment_weigh(const Selection &sl, const PendTa
         return m2;
     }
     const float m2 = sl.shift_q;
-    const RatioConst rc(sl.C2);
+    const RatioConst rc(sl.C2 + static_cast<double>(sl.C2_adj));
     if (PEND && tab.n > 0) {
         // modified row: plain weights q prod t_l^K, residual weights those times max(1 - p/(nu q'), 0)^K
         pending_weights(zq, zp, c, m2, tab, rc, K, wq, w);

@@ -59,7 +59,7 @@ struct Selection {
     float shift_q;          // reference exponent for target-row weights (unused for the bonus row)
     int tau;
     int npend;              // levels of pending modifications that modify the row (C2 and lse2_q then refer to the modified row)
-    int pad;
+    float C2_adj;           // added to C2 where it serves the sweep's ratio: minus c_rel log2 nu (see ratio_const)
     double lse2_pq;         // log2 Z_p - log2 Z_q of the unmodified row pair (0 for the bonus row)
     double Cl[kMaxPend];    // per such level: log2 of mu_l Z_p / Z_q minus the log2 N of the levels before it
 };
@@ -159,6 +159,18 @@ struct RatioConst {
         return __builtin_amdgcn_fmed3f(fmaf(r, neg_kappa, 1.0f), 0.0f, 1.0f);
     }
 };
+
+// C2 for the sweeps' ratio p[x] / (nu q[x]) = 2^(c (z_p - z_q) - C2), C2 = log2 Z_p - log2 Z_q + log2 nu, with the part
+// of the rounding of c that a constant can carry.  The float c differs from log2(e) / T by the relative amount
+// c_rel, which puts c_rel (c (z_p - z_q) - (E_p[c z] - E_q[c z])) into the exponent (the normalisers, summed with the
+// same c, move with it).  For the entries whose ratio is of order one - the only ones whose factor 1 - ratio is
+// sensitive - c (z_p - z_q) is C2 itself up to a few units, i.e. the error is c_rel (log2 nu + H_p - H_q) with the
+// two rows' entropies in bits: a block ratio of 2^-28 (a long block of improbable tokens) shifts every such ratio by
+// 1e-6, and the K-th power of a factor 0.2 by 1e-5.  The log2 nu part is taken out here; the entropies are not known.
+__device__ __forceinline__ double ratio_const(double lse2_p, double lse2_q, double log2nu, double c_rel)
+{
+    return (lse2_p - lse2_q) + log2nu * (1.0 - c_rel);
+}
 
 // 2^x in float64 (0 below x = -1000, infinity above x = 1000) by a degree-12 polynomial on [-1/2, 1/2] and an exponent shift
 // (relative error about 1e-15; far less code than the general library routine, which matters
@@ -550,6 +562,22 @@ __device__ __forceinline__ RefSum with_token(double M, double Z, double t)
     r.ref = fmax(M, t);
     r.Z = (Z > 0.0 ? Z * exp2(M - r.ref) : 0.0) + exp2(t - r.ref);
     return r;
+}
+
+// The drafted token's term q[x] max(1 - p[x]/(nu q[x]), 0)^K of its own row's Eq. (hik) sum, in float64 from the
+// row's statistics: log2q = log2 q[x], log2r = log2 of p[x]/(nu q[x]).  The sweeps form 1 - ratio per entry from a
+// float32 exponential, 6e-8 absolute at ratios near one; where the token's ratio is within kTokenTermBelow of one the
+// kernels replace the sweep's value of this one term (a row whose mass sits on its drafted token, behind a block
+// ratio near one, has little else in the sum; at K = 1 the sum is then off by 1e-5 - 1e-4 otherwise).
+constexpr float kTokenTermBelow = 0.0625f;
+struct TokenTerm {
+    float zq, zp;            // the token's two logits as the sweep sees them
+    double log2q, log2r;
+};
+__device__ __forceinline__ double token_term(double log2q, double log2r, int K)
+{
+    const double t = fmax(1.0 - exp2_small(log2r), 0.0);
+    return exp2_small(log2q) * powi_uniform(t, K);
 }
 
 // Integral reference exponent of a group of entries whose largest logit is m (partial sums taken relative to

@@ -207,6 +207,26 @@ __device__ __forceinline__ double lse2_from_parts(const Row0Part *pp, int P)
     return ref + log2(Z);
 }
 
+// The drafted token's term of a row's Eq. (hik) sum in float64 in place of the sweep's float32 value (see
+// token_term): called by one thread with the sum `total` (relative to 2^shift_q) of the entries [lo, hi) of the
+// row; returns total with the term exchanged if the token (*token) is among them, or total itself where the term
+// needs no second look (decided from the row's statistics: the token is not even fetched then).
+template <typename T>
+__device__ __forceinline__ double with_token_term(double total, const RowStat &st, double log2nu, const T *rq, const T *rp,
+                                                  const int32_t *token, int V, int lo, int hi, float c, float shift_q,
+                                                  const RatioConst &rc, int K)
+{
+    const double log2q = st.tok2_q - st.lse2_q, log2r = (st.tok2_p - st.lse2_p) - log2q - log2nu;
+    if (!(fabs(1.0 - exp2_small(log2r)) < static_cast<double>(kTokenTermBelow))) return total;
+    int tok = *token;
+    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    if (tok < lo || tok >= hi) return total;
+    const float zq[1] = {Elem<T>::scalar(rq + tok)}, zp[1] = {Elem<T>::scalar(rp + tok)};
+    float wq[1], w[1];
+    ot_weights(zq, zp, c, shift_q, rc, K, wq, w);            // the same operations as in the sweep: the same bits
+    return (total - static_cast<double>(w[0])) + token_term(log2q, log2r, K) * exp2_small(st.lse2_q - static_cast<double>(shift_q));
+}
+
 // grid rows * P, rows = batch * K * (L - 1): block row * P + part sums part `part` of the Eq. (hik) terms of row
 // pair i = 1 .. L-1 of a draft (PEND: against the row as the pending levels leave it, exactly as k_ot_sum does).
 // With stat_P > 1 the statistics of the draft's rows 0 .. i are still in parts
@@ -275,7 +295,7 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
     const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
     const T *rp = draft + pair * static_cast<long long>(V);
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
-    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu - sumN);
+    const RatioConst rc(ratio_const(st.lse2_p, st.lse2_q, log2nu, c_rel) - sumN);
     const int units = VEC ? V / N : V;
     const int per = (units + P - 1) / P;
     const int lo = part * per, hi = lo + per < units ? lo + per : units;
@@ -295,7 +315,9 @@ k_ot_sum_parts(const T *__restrict__ target, const T *__restrict__ draft, const 
             for (int j = 0; j < N; ++j) acc += w[j];
         });
     }
-    const double total = block_sum(static_cast<double>(acc), sh_d);
+    double total = block_sum(static_cast<double>(acc), sh_d);
+    if (threadIdx.x == 0 && !(PEND && sh_tab.n > 0))
+        total = with_token_term<T>(total, st, log2nu, rq, rp, tokens + pair, V, lo * N, hi * N, c, shift_q, rc, K);
     // (whether the row's s and g nearly cancel, so that Eq. (hik) needs nu^2 (s - g) summed term by term, only the sum
     // over all parts can tell: the final-token kernel looks at it)
     if (threadIdx.x == 0) s_part[pair * kPendParts + part] = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
@@ -423,9 +445,9 @@ k_pend_norm(const T *__restrict__ target, const T *__restrict__ draft, int K, in
 
 template <typename T, bool VEC, bool PEND>
 __global__ void __launch_bounds__(kStatThreads)
-k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L, int V, float c,
-         const RowStat *__restrict__ stats, const PendRow *__restrict__ pend, long long n_rows, int nlev,
-         double *__restrict__ s_out, double *__restrict__ e_out, double *__restrict__ e_part)
+k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, const int32_t *__restrict__ tokens, int K, int L, int V,
+         float c, const RowStat *__restrict__ stats, const PendRow *__restrict__ pend, long long n_rows, int nlev,
+         double *__restrict__ s_out, double *__restrict__ e_out, double *__restrict__ e_part, double c_rel)
 {
     __shared__ double sh_d[kStatThreads / kWave];
     __shared__ PendTable sh_tab;
@@ -455,7 +477,7 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
     const T *rq = target + (bk * (L + 1) + i) * static_cast<long long>(V);
     const T *rp = draft + (bk * L + i) * static_cast<long long>(V);
     constexpr int N = VEC ? Elem<T>::kPerVec : 1;
-    const RatioConst rc(st.lse2_p - st.lse2_q + log2nu - sumN);
+    const RatioConst rc(ratio_const(st.lse2_p, st.lse2_q, log2nu, c_rel) - sumN);
     float acc = 0.0f;
     if (PEND && sh_tab.n > 0) {                   // uniform over the workgroup
         for_each_pair<T, VEC, kStatThreads>(rq, rp, V, [&](int, const float (&zq)[N], const float (&zp)[N]) {
@@ -472,7 +494,9 @@ k_ot_sum(const T *__restrict__ target, const T *__restrict__ draft, int K, int L
             for (int j = 0; j < N; ++j) acc += w[j];
         });
     }
-    const double total = block_sum(static_cast<double>(acc), sh_d);
+    double total = block_sum(static_cast<double>(acc), sh_d);
+    if (threadIdx.x == 0 && !(PEND && sh_tab.n > 0))
+        total = with_token_term<T>(total, st, log2nu, rq, rp, tokens + (bk * L + i), V, 0, V, c, shift_q, rc, K);
     const double s_val = total * exp2(static_cast<double>(shift_q) - st.lse2_q - sumN);
     // where s and g = (1 - 1/nu)^K nearly cancel, Eq. (hik) needs nu^2 (s - g) summed term by term (rare: peaked
     // rows, large block ratios): the final-token kernel finds those rows and its workgroups sum E together (the
@@ -574,9 +598,9 @@ hipError_t launch_typed(const Problem &p)
     }
     const dim3 g2(static_cast<unsigned>(rows));
 #define SPECGBV_OT_LAUNCH(VEC, PEND)                                                                           \
-    hipLaunchKernelGGL((k_ot_sum<T, VEC, PEND>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.K, p.L, \
+    hipLaunchKernelGGL((k_ot_sum<T, VEC, PEND>), g2, dim3(kStatThreads), 0, p.stream, target, draft, p.tokens, p.K, p.L, \
                        p.V, p.c, stats, pend, pairs, p.pend_levels, s, reinterpret_cast<double *>(p.ws + p.lay.excess),        \
-                       reinterpret_cast<double *>(p.ws + p.lay.excess_part))
+                       reinterpret_cast<double *>(p.ws + p.lay.excess_part), p.c_rel)
     if (p.pend_levels > 0) { if (vec) SPECGBV_OT_LAUNCH(true, true); else SPECGBV_OT_LAUNCH(false, true); }
     else { if (vec) SPECGBV_OT_LAUNCH(true, false); else SPECGBV_OT_LAUNCH(false, false); }
 #undef SPECGBV_OT_LAUNCH
