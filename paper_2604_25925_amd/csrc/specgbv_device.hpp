@@ -387,10 +387,14 @@ __device__ __forceinline__ float excess_terms(const float (&zq)[N], const float 
     return acc;
 }
 
-// Do s and g agree so closely (block ratio above one) that nu (s - g) needs the sum E?  The plain sum s of a row
-// that a few entries dominate carries the float32 exponential's error of those entries unaveraged, 1e-7 for each
-// of its two exponentials and K times that through the power (3e-7 observed at K = 4 on a 526-entry row); below
-// (s - g) / s = 1/16 that is no longer safely under the 1e-5 the acceptance probability is held to.
+// Largest s / (s - g) at which the plain sum s still serves.  The sum of a row that a few entries dominate carries the
+// float32 error of those entries unaveraged: 1e-7 for each of its two exponentials and K times that, plus the
+// roundings of the multiplications, through the power (3e-7 observed at K = 4 on a 526-entry row, 1.3e-6 at K = 9 on
+// a row with 83 % of the sum in one entry).  Taken as 2e-7 + 1.3e-7 K relative, times this factor it stays at half the
+// 1e-5 the acceptance probability is held to: 15 at K = 1, 6.9 at K = 4, 4 at K = 8.
+__device__ __forceinline__ float cancel_factor(int K) { return fminf(16.0f, 38.5f / (1.54f + static_cast<float>(K))); }
+
+// Do s and g agree so closely (block ratio above one) that nu (s - g) needs the sum E?
 // (float32 throughout: the threshold need not be sharp, and float64 constants in a kernel whose registers hold a
 // whole row pair end up in scratch memory)
 __device__ __forceinline__ bool excess_wanted(float l, float sf, int K)
@@ -398,14 +402,15 @@ __device__ __forceinline__ bool excess_wanted(float l, float sf, int K)
     if (!(l > 0.0f)) return false;
     const float t1 = 1.0f - exp2_fast(-l);
     const float g = powi_uniform(t1, K);
-    return (sf - g) * 16.0f < sf;
+    return (sf - g) * cancel_factor(K) < sf;
 }
 
 // Does the acceptance probability of a row whose s and g nearly cancel (excess_wanted) need the sum E at all?
 // With h = E / (E + D), D = (1 - Q) S2 / nu (the decision kernel's form of Eq. (hik) for a block ratio above one), a
 // relative error on E = nu (s - g) reaches h reduced by the factor 1 - h = D / (D + E): a block that is accepted
 // almost surely does not care how well s - g is known.  The test of excess_wanted, sharpened by that factor, which
-// is itself taken at the low end of what the plain s allows for s - g (1e-6 s below it; not above 0: needed).
+// is itself taken at the low end of what the plain s allows for s - g (three times the sum's error below it, 1e-6 s at
+// K = 1; not above 0: needed).
 // log2P: log2 of the joint draft probability of the block's tokens.
 __device__ __forceinline__ bool excess_needed(double log2nu, double log2P, double s, int K)
 {
@@ -418,9 +423,10 @@ __device__ __forceinline__ bool excess_needed(double log2nu, double log2P, doubl
     for (int j = 1; j <= K - 1; ++j) { S2 += U; pw *= t1; U = fma(A, U, pw); }
     const double one_Q = fmax(1.0 - exp2_small(log2nu + log2P), 0.0);
     const double D = inv_nu * one_Q * S2;
-    const double x = (s - g) - 1.0e-6 * s;
+    const double f = static_cast<double>(cancel_factor(K));
+    const double x = (s - g) - (16.0e-6 / f) * s;
     if (!(x > 0.0)) return true;
-    return x * 16.0 * (D + x / inv_nu) < s * D;
+    return x * f * (D + x / inv_nu) < s * D;
 }
 
 // Entry l of a PendTable from the float64 constant C (same split as RatioConst).

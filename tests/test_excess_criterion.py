@@ -2,10 +2,10 @@
 the oracle's two forms of the acceptance probability.
 
 For a block ratio nu > 1 the kernels have s = sum_x q max(1 - p/(nu q), 0)^K from a float32 sweep (relative error up to
-3e-7 on rows that a few entries dominate) and g = (1 - 1/nu)^K; Eq. (hik) needs nu (s - g).  They take the sum
+2e-7 + 1.3e-7 K on rows that a few entries dominate) and g = (1 - 1/nu)^K; Eq. (hik) needs nu (s - g).  They take the sum
 again as E = nu^2 (s - g), term by term and without the difference, only where two tests say so (written out below as
 the kernels have them: `excess_wanted`, then `excess_needed`).  The property that makes the rule sound: wherever it
-says "the plain sum will do", the oracle's plain form of h evaluated at s (1 +- 3e-7) stays within the bar the
+says "the plain sum will do", the oracle's plain form of h evaluated at s (1 +- eps_s(K)) stays within the bar the
 acceptance probability is held to, 1e-5 |h| + 1e-9, of the oracle's cancellation-free form at the exact E.  Sweeps
 over nu, P, K and the size of s - g, including the corners (s - g far below the error of s, Q = nu P near one,
 K = 1).  No GPU involved: this pins the rule, the GPU parity tests pin its implementation."""
@@ -16,7 +16,14 @@ import pytest
 
 import oracle
 
-EPS_S = 3.0e-7          # relative error of the float32 sum (worst observed)
+def eps_s(K):
+    """Relative error allowed for on the float32 sum: 3e-7 observed at K = 4, 1.3e-6 at K = 9 on a row that one entry dominates."""
+    return 2.0e-7 + 1.3e-7 * K
+
+
+def cancel_factor(K):
+    """Largest s / (s - g) the plain sum serves up to: times eps_s(K) it is half the bar (float32 in the kernels)."""
+    return min(16.0, 38.5 / (1.54 + K))
 
 
 def plain_sum_suffices(log2nu, log2P, s, K):
@@ -26,7 +33,8 @@ def plain_sum_suffices(log2nu, log2P, s, K):
     inv_nu = 2.0 ** -log2nu
     t1 = 1.0 - inv_nu
     g = t1 ** K
-    if not (s - g) * 16.0 < s:                        # first test: the difference keeps four bits of s
+    f = cancel_factor(K)
+    if not (s - g) * f < s:                           # first test: the difference keeps enough bits of s
         return True
     if K == 1:
         return True                                   # h = 1 whatever E is
@@ -38,10 +46,10 @@ def plain_sum_suffices(log2nu, log2P, s, K):
         U = (1.0 - P) * U + pw
     one_Q = max(1.0 - 2.0 ** (log2nu + log2P), 0.0)
     D = inv_nu * one_Q * S2
-    x = (s - g) - 1.0e-6 * s                          # low end of what the plain s allows for s - g
+    x = (s - g) - (16.0e-6 / f) * s                   # low end of what the plain s allows for s - g
     if not x > 0.0:
         return False
-    return not x * 16.0 * (D + x / inv_nu) < s * D
+    return not x * f * (D + x / inv_nu) < s * D
 
 
 def _cases(seed, n):
@@ -71,7 +79,7 @@ def test_where_the_rule_keeps_the_plain_sum_the_plain_form_is_within_the_bar(see
         x = s - g                                                    # what float64 kept of it
         nu = 2.0 ** log2nu
         h_true = oracle.h_sub_excess(log2nu * ln2, log2P * ln2, nu * nu * x, K)
-        for d in (-EPS_S, EPS_S):
+        for d in (-eps_s(K), eps_s(K)):
             s_seen = s * (1.0 + d)
             if plain_sum_suffices(log2nu, log2P, s_seen, K):
                 kept += 1

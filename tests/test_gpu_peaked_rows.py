@@ -19,6 +19,12 @@ matter is about log2 nu: behind a block of improbable tokens (nu = 2^-40) a rati
 K-th power of the factor 0.2 by 3e-5 at K = 4.  The kernels take that part of the rounding into the ratio's constant.
 (With float32 logits the sweep's own rounding of z_p - z_q is of the same size; bf16 differences are exact.)
 
+A draft close to the target, many drafts.  With p nearly q every row has s barely above g once nu exceeds one
+(s = g when the two rows agree), at amplifications s/(s - g) of 4 - 16 that are ordinary rather than rare, and the
+K-th power passes K times the float32 error of the entries' factors on to s: a K = 9 row with 83 % of its sum in one
+entry is 1.3e-6 off, and at s/(s - g) = 6.7 the plain Eq. (hik) was 1.13 x over its bar.  The amplification up to which
+the plain sum serves therefore falls with K (cancel_factor).
+
 Runaway block ratios.  A target far surer of the drafted tokens than the draft makes nu grow by orders of magnitude
 per position; s and g = (1 - 1/nu)^K then agree to many digits and Eq. (hik) needs nu^2 (s - g) summed term by term.
 On the chain schedule those rows go to a follow-up kernel (chains with every row handed over, workgroups that hand
@@ -216,3 +222,25 @@ def test_tiny_block_ratios_at_a_temperature_whose_scale_rounds_badly(algo, dtype
     front = ora["log_nu"][:, :, 1:L - 1]                                # in front of rows 2 .. L-1
     s = ora["s"][:, :, 2:]
     assert (front < -14.0).all() and ((s > 1e-6) & (s < 1e-2)).mean() > 0.7, "the case no longer is what it claims"
+
+
+@pytest.mark.parametrize("algo,dtype,V,B,K,L,T", [
+    ("split", "f32", 29049, 5, 9, 9, 0.48), ("chain", "bf16", 32768, 4, 8, 8, 0.5), ("auto", "bf16", 16384, 2, 16, 6, 0.6),
+    ("chain", "f32", 14336, 6, 6, 8, 0.45)])
+def test_draft_close_to_the_target_with_many_drafts(algo, dtype, V, B, K, L, T):
+    w = Workload("aligned", B, K, L, V, "f32", 0.8, 0.1, head=0, temperature=T)
+    t, d, tok = make_inputs(w, seed=71)
+    for b in range(B):                                                  # a first token the target likes better: nu = 2.5 from row 1 on
+        x0 = int(tok[b, 0, 0])
+        _set_probability(t[b, 0, 0], x0, T, 0.5)
+        _set_probability(d[b, 0, 0], x0, T, 0.2)
+        for k in range(K):
+            t[b, k, 0], d[b, k, 0], tok[b, k, 0] = t[b, 0, 0], d[b, 0, 0], x0
+    if dtype == "bf16":
+        t, d = f32_to_bf16_bits(t), f32_to_bf16_bits(d)
+    rep, gpu, ora = check_case(t, d, tok, T, 11, 0, algo, "aligned %s %s V=%d B=%d K=%d T=%g" % (algo, dtype, V, B, K, T))
+    nu = np.exp(np.clip(ora["log_nu"][:, :, :L - 1], -700, 700))
+    s = ora["s"][:, :, 1:]
+    g = np.where(nu > 1, (1 - 1 / np.maximum(nu, 1)) ** K, 0.0)
+    amp = s / np.maximum(s - g, 1e-300)
+    assert int(((nu > 1) & (amp > 3) & (amp < 16)).sum()) >= 10, "the case no longer has rows between the two thresholds"
