@@ -647,8 +647,8 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
     __shared__ double sh_sumrow[2][2];                     // log2 of the block ratio and of the drafts' joint probability in front
                                                            // of the row in sweep 2: written by thread 0 when the row's statistics
                                                            // are known, in the entry of the iteration's parity, read one iteration later
-    __shared__ int sh_nlater;                              // rows handed to k_chain_excess so far (thread 0 only)
-    __shared__ TokenTerm sh_tokterm[2];                    // the drafted token of the row in sweep 2 (thread 0 only, by parity as above)
+    __shared__ int sh_nlater;                              // rows handed to k_chain_excess so far (the summing thread only)
+    __shared__ TokenTerm sh_tokterm[2];                    // the drafted token of the row in sweep 2 (written and read like sh_sumrow)
     __shared__ PendTable sh_tab;                           // PEND only: levels that modify the current row
     __shared__ double sh_mu[kMaxPend];                     //            log2 block ratio of every level in front of the current row
     __shared__ int sh_cnt[kMaxPend];                       //            rows every level modifies (this prefix)
@@ -660,7 +660,10 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         __syncthreads();
     }
 
-    if (threadIdx.x == 0) sh_nlater = 0;
+    // The thread that finishes a row's Eq. (hik) sum is the second wave's first: thread 0 stores the statistics of the
+    // row being loaded in the same iteration, and the two pieces of scalar work then run side by side.
+    constexpr unsigned kSumThread = kWave;
+    if (threadIdx.x == kSumThread) sh_nlater = 0;
     constexpr int PV = Elem<T>::kPerVec;
     constexpr int NS = RS + kLdsSlots;                     // slots kept on chip
     const unsigned tid = threadIdx.x;
@@ -801,7 +804,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
             Zq_tot += static_cast<double>(nb_q) + (1.0 + xq + 0.5 * xq * xq);
             Zp_tot += static_cast<double>(nb_p) + (1.0 + xp + 0.5 * xp * xp);
         }
-        if (do_sum && tid == 0) {
+        if (do_sum && tid == kSumThread) {
             const double inv_Zq = 1.0 / Zq_prev;
             double s_val = s_tot * inv_Zq;
             // The drafted token's own term once more in float64 where its p/(nu q) is near one: formed from a float32
@@ -934,7 +937,7 @@ k_chain(const T *__restrict__ target, const T *__restrict__ draft, const int32_t
         }
     }
     if constexpr (!PEND)
-        if (tid == 0) later[static_cast<size_t>(blockIdx.x) * later_stride] = sh_nlater;   // (every workgroup, also when it is 0)
+        if (tid == kSumThread) later[static_cast<size_t>(blockIdx.x) * later_stride] = sh_nlater;   // (every workgroup, also when it is 0)
 }
 
 // E = nu^2 (s - g) of the rows k_chain handed over, straight from memory, in kPendParts parts per row which the
@@ -993,22 +996,28 @@ k_chain_excess(const T *__restrict__ target, const T *__restrict__ draft, int K,
         const long long bk = pair / L;
         const int i = static_cast<int>(pair % L);
         const int lo = part * per, hi = lo + per < nvec ? lo + per : nvec;
+        const T *qrow = target + (bk * (L + 1) + i) * static_cast<long long>(V);
+        const T *prow = draft + pair * static_cast<long long>(V);
+        // the first vectors (nearly always all of the part's) are asked for before the row's constants are made: the
+        // statistics' latency and their float64 arithmetic pass while the vectors travel
+        U4 q[kAhead], pp[kAhead];
+        auto fetch = [&](int v0) {
+#pragma unroll
+            for (int a = 0; a < kAhead; ++a) {
+                const int v = v0 + a * kExcessThreads;
+                const long long at = static_cast<long long>(v < nvec ? v : nvec - 1) * PV;      // (stays inside the row)
+                q[a] = load16_stream(qrow + at);
+                pp[a] = load16_stream(prow + at);
+            }
+        };
         const RowStat st = stats[bk * L + (lane < L ? lane : L - 1)];
+        fetch(lo + tid);
         const double ratio = (st.tok2_q - st.lse2_q) - (st.tok2_p - st.lse2_p);   // log2 of the row's token ratio
         double log2nu = 0.0;                               // added up as k_chain does: the same bits
         for (int j = 0; j < i; ++j) log2nu += lane_d(ratio, j);
         const ExcessConst ec = make_excess_const(lane_d(st.lse2_q, i), lane_d(st.lse2_p, i), log2nu, K, c);
-        const T *qrow = target + (bk * (L + 1) + i) * static_cast<long long>(V);
-        const T *prow = draft + pair * static_cast<long long>(V);
         float acc = 0.0f;
         for (int v0 = lo + tid; v0 < hi; v0 += kAhead * kExcessThreads) {
-            U4 q[kAhead], pp[kAhead];
-#pragma unroll
-            for (int a = 0; a < kAhead; ++a) {
-                const int v = v0 + a * kExcessThreads;
-                q[a] = load16_stream(qrow + static_cast<long long>(v < hi ? v : v0) * PV);
-                pp[a] = load16_stream(prow + static_cast<long long>(v < hi ? v : v0) * PV);
-            }
 #pragma unroll
             for (int a = 0; a < kAhead; ++a) {
                 float zq[PV], zp[PV];
@@ -1016,6 +1025,7 @@ k_chain_excess(const T *__restrict__ target, const T *__restrict__ draft, int K,
                 Elem<T>::unpack(pp[a], zp);
                 if (v0 + a * kExcessThreads < hi) acc += excess_terms(zq, zp, ec);
             }
+            if (v0 + kAhead * kExcessThreads < hi) fetch(v0 + kAhead * kExcessThreads);
         }
         // (a part without vectors, where the row has fewer of them than parts, adds 0)
         const double e_val = block_sum(static_cast<double>(acc), sh_d) * ec.scale;
