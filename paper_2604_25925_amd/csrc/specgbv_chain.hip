@@ -1001,11 +1001,12 @@ k_chain_excess(const T *__restrict__ target, const T *__restrict__ draft, int K,
         // the first vectors (nearly always all of the part's) are asked for before the row's constants are made: the
         // statistics' latency and their float64 arithmetic pass while the vectors travel
         U4 q[kAhead], pp[kAhead];
+        const int last = hi > lo ? hi - 1 : nvec - 1;      // what a lane past the part's end reads again (inside the row)
         auto fetch = [&](int v0) {
 #pragma unroll
             for (int a = 0; a < kAhead; ++a) {
                 const int v = v0 + a * kExcessThreads;
-                const long long at = static_cast<long long>(v < nvec ? v : nvec - 1) * PV;      // (stays inside the row)
+                const long long at = static_cast<long long>(v < hi ? v : last) * PV;
                 q[a] = load16_stream(qrow + at);
                 pp[a] = load16_stream(prow + at);
             }
